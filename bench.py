@@ -1,0 +1,163 @@
+"""Benchmark of the chunked N-way reduce on one MI355X.
+
+One step = one hop_reduce call over the asynchronous-SGD workload (16 fp32
+objects of 64 MiB, the first 12 ready are reduced, 4 MiB chunks, tree degree
+4), inputs resident in HBM. Prints ONE JSON line with the metric, the
+roofline of the reduce kernel and the CPU oracle's rate on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B/s)
+
+
+def time_calls(fn, steps, warmup, torch):
+    """Average device time per call in ms, bracketed by events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def cpu_baseline(w, objs, order, torch, sample_elems):
+    """The oracle as it stands, single thread, on the first sample_elems elements of every object."""
+    import numpy as np
+
+    import oracle
+    import workloads
+    host = [workloads.to_numpy(o[:sample_elems]) for o in objs]
+    t0 = time.perf_counter()
+    rc, out, k_eff, _ = oracle.reduce(host, w.k, oracle.SUM, oracle.F32, w.chunk_bytes // 4, w.tree_degree, order, None)
+    dt = time.perf_counter() - t0
+    nbytes = (k_eff + 1) * sample_elems * 4
+    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d of %d elements of each object (%.0f MB counted), %.2f s" %
+                      (sample_elems, w.n_elems, nbytes / 1e6, dt)}, out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, help="which of the five workloads (default: 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-configs", action="store_true", help="also time the other workloads (extra JSON field)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one node's share of the reduce on ONE GPU; --gpus %d is not supported "
+              "(no collectives between GPUs exist in it)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2002_05814_amd as hop
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    hop.lib()                                   # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+
+    def run_workload(cfg, steps, warmup):
+        w = workloads.WORKLOADS[cfg]
+        objs = workloads.make_objects(w, device=dev)
+        order, fm = w.ready_order(), w.fail_mask()
+        n_out = max(1, w.n_dst)
+        # two destination sets, alternated, so that a call never finds its output lines in cache
+        dsts = [[torch.empty_like(objs[0]) for _ in range(n_out)] for _ in range(2)]
+        results = {}
+        for op in w.ops:
+            state = {"i": 0, "info": None, "rc": 0}
+
+            def step():
+                d = dsts[state["i"] & 1]
+                state["i"] += 1
+                if w.n_dst:
+                    state["rc"], state["info"] = hop.hop_allreduce(d, objs, w.k, op, w.dtype, w.chunk_bytes,
+                                                                   w.tree_degree, order, fm)
+                else:
+                    state["rc"], state["info"] = hop.hop_reduce(d[0], objs, w.k, op, w.dtype, w.chunk_bytes,
+                                                                w.tree_degree, order, fm)
+            ms, wall_ms = time_calls(step, steps, warmup, torch)
+            assert state["rc"] >= 0, hop.hop_strerror(state["rc"])
+            k_eff = state["info"]["k_eff"]
+            counted = (k_eff + 1) * w.object_bytes
+            if w.n_dst:
+                counted = (k_eff + w.n_dst) * w.object_bytes        # least traffic of reduce + broadcast
+            results[op] = {"ms": ms, "wall_ms": wall_ms, "gbs": counted / (ms * 1e-3) / 1e9, "bytes": counted,
+                           "info": state["info"], "status": state["rc"]}
+        return w, objs, order, dsts, results
+
+    w, objs, order, dsts, res = run_workload(args.workload, args.steps, args.warmup)
+    op = w.ops[0]
+    r = res[op]
+    out = {
+        "metric": "reduce input GB/s and % of MI355X HBM peak, N-way chunked reduce",
+        "value": round(r["gbs"], 2),
+        "unit": "GB/s",
+        "pct_of_hbm_peak": round(100.0 * r["gbs"] / HBM_PEAK_GBS, 2),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(r["ms"], 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {"f32": "f32", "bf16": "bf16 in, f32 accumulate", "i32": "int32"}[w.dtype],
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "k": w.k, "object_bytes": w.object_bytes,
+                   "chunk_bytes": w.chunk_bytes, "tree_degree": r["info"]["degree_used"], "op": op,
+                   "counted_bytes": r["bytes"], "launches_per_step": r["info"]["n_launches"],
+                   "host_ms_per_step": round(r["wall_ms"], 5)},
+        "roofline": {"bound": "hbm", "achieved": round(r["gbs"], 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(r["gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "hop::reduce_kernel", "per_unit": "(k_eff+1) x object_bytes per launch"},
+    }
+    if not args.no_cpu_baseline and w.dtype == "f32" and not w.n_dst:
+        sample = min(w.n_elems, 1 << 22)
+        base, want = cpu_baseline(w, objs, order, torch, sample)
+        got = workloads.to_numpy(dsts[(args.steps + args.warmup - 1) & 1][0][:sample])
+        base["matches_gpu_bits"] = bool(np.array_equal(got.view(np.uint32), want.view(np.uint32)))
+        out["cpu_baseline"] = base
+    else:
+        out["cpu_baseline"] = None
+    if args.all_configs:
+        extra = {}
+        del objs, dsts
+        torch.cuda.empty_cache()
+        for cfg in (1, 3, 4, 5):
+            wk, o2, _, d2, rs = run_workload(cfg, max(5, args.steps // 5), 2)
+            for opn, rr in rs.items():
+                extra["%s/%s" % (wk.name, opn)] = {"GB/s": round(rr["gbs"], 2), "ms": round(rr["ms"], 5),
+                                                  "frac_of_hbm_peak": round(rr["gbs"] / HBM_PEAK_GBS, 4),
+                                                  "counted_bytes": rr["bytes"], "status": rr["status"],
+                                                  "launches": rr["info"]["n_launches"]}
+            del o2, d2
+            torch.cuda.empty_cache()
+        out["all_configs"] = extra
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,226 @@
+/*
+ * hop.h -- C ABI of the MI355X chunked N-way reduce library.
+ *
+ * The library implements, on one GPU, the reduce path of Hoplite
+ * (arXiv 2002.05814): Reduce(target, num_objects, sources, op) of Table 1,
+ * scheduled by the dynamic d-ary tree of section 3.4.2, pipelined in chunks
+ * as in section 3.3, tolerant of failing participants as in section 3.5.2,
+ * plus the broadcast of section 3.4.1 and the reduce-then-broadcast allreduce
+ * of section 3.4.3.
+ *
+ * Conventions shared by every call
+ *   - "device pointer" = address in the memory of the current HIP device;
+ *     "host pointer"   = ordinary process memory.
+ *   - Objects are immutable (section 3.3): the library never writes a source
+ *     object and never frees caller memory. Destinations must not overlap any
+ *     source.
+ *   - Device buffers (sources, destinations) must be 16-byte aligned.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and return without waiting for the GPU, like the
+ *     paper's Reduce, which returns a future. Host arrays passed in are read
+ *     before the call returns and may be reused at once.
+ *   - Return value: a hop_status_t. Negative = error, nothing usable was
+ *     written. No C++ exception crosses this boundary.
+ *   - Thread safety: different sessions / calls may run on different host
+ *     threads; one session must be driven from one thread at a time.
+ */
+#ifndef HOP_H
+#define HOP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Reduce operations of Table 1 ("sum, min, max"). */
+typedef enum { HOP_SUM = 0, HOP_MIN = 1, HOP_MAX = 2 } hop_op_t;
+
+/* Element types. The paper reduces 32-bit floats (section 5.1); bf16 and
+ * int32 are additions. bf16 is widened exactly to binary32, combined in
+ * binary32 and rounded to nearest-even once when stored; int32 sum wraps
+ * modulo 2^32. */
+typedef enum { HOP_F32 = 0, HOP_BF16 = 1, HOP_I32 = 2 } hop_dtype_t;
+
+typedef enum {
+    HOP_OK = 0,
+    HOP_PARTIAL = 1,            /* fewer than k objects survived; all survivors were reduced */
+    HOP_ERR_INVALID = -1,       /* bad argument (see each call)                              */
+    HOP_ERR_ALIGN = -2,         /* a device buffer is not 16-byte aligned                    */
+    HOP_ERR_NO_SURVIVOR = -3,   /* no object survived: there is nothing to reduce            */
+    HOP_ERR_DEVICE = -4,        /* a HIP call failed                                         */
+    HOP_ERR_NOMEM = -5,         /* host or device allocation failed                          */
+    HOP_ERR_DEPTH = -6          /* the tree needs more partial results in flight than the
+                                   kernels hold in registers (see HOP_MAX_DEPTH)             */
+} hop_status_t;
+
+/* Most partial results that can be live at once while one element's tree
+ * expression is evaluated: 1 + the largest number of non-first-child
+ * ancestors of any tree node. A chain (d = 1) needs 1, a star 1, a binary
+ * tree on k nodes about log2(k). */
+#define HOP_MAX_DEPTH 16
+
+typedef struct {
+    int32_t k_eff;          /* objects folded into the result                         */
+    int32_t n_failed_seen;  /* failure notifications the scheduler acted on           */
+    int32_t n_replaced;     /* failed tree positions refilled by a waiting object     */
+    int32_t degree_used;    /* tree degree actually used (matters for tree_degree 0)  */
+    int64_t chunks_redone;  /* repair work: chunks relaunched after a failure, each
+                               counted once per source object read again             */
+    int32_t n_launches;     /* reduce kernels enqueued                                */
+    int32_t stack_depth;    /* partial results live at once (<= HOP_MAX_DEPTH)        */
+} hop_info_t;
+
+/*
+ * hop_reduce -- Reduce of Table 1 with the tree schedule of section 3.4.2
+ * and the failure handling of section 3.5.2, over objects already resident
+ * in device memory.
+ *
+ *   dst          device pointer, object_bytes bytes; receives the result.
+ *   objs         host array of n device pointers, each object_bytes bytes.
+ *   n            number of source objects (the paper's source list), >= 1.
+ *   object_bytes size of every object; a multiple of the element size; may
+ *                be 0 (nothing is launched).
+ *   ready_order  host array, a permutation of 0..n-1: the order in which the
+ *                objects become ready (arrive). NULL = 0,1,..,n-1.
+ *   k            num_objects: how many objects to reduce, 1 <= k <= n. The
+ *                first k arrivals take the k tree positions by generalised
+ *                in-order traversal (first child, node, other children).
+ *   op, dtype    see above.
+ *   chunk_bytes  pipelining block (section 3.3; the paper uses 4 MB): the unit
+ *                of readiness, scheduling, failure and repair. > 0 and a
+ *                multiple of 16.
+ *   tree_degree  d >= 1 (1 = chain, >= k-1 = star); 0 lets the library choose
+ *                among {1, 2, k} with the cost model of section 3.4.2 (Eq. 1).
+ *   fail_mask    host array of n entries or NULL (nobody fails).
+ *                fail_mask[i] < 0: object i is healthy. fail_mask[i] = c >= 0:
+ *                object i delivers exactly c chunks and then fails; c = 0 means
+ *                it never becomes ready; c >= number of chunks means it
+ *                completed, i.e. healthy. All participants stream their chunks
+ *                side by side, so a participant that fails after c chunks is
+ *                noticed when chunks 0..c-1 of the output have already been
+ *                produced with its data: those chunks are produced again
+ *                without it. The failed position goes to the next ready
+ *                object not yet in the tree, else stays empty.
+ *   stream       hipStream_t.
+ *   info         host pointer or NULL; filled before return.
+ *
+ * Result: for every element, the tree-ordered op over the objects finally in
+ * the tree = the first k ready objects that did not fail. HOP_PARTIAL when
+ * fewer than k survive (the paper would wait for reconstruction instead).
+ * Errors: HOP_ERR_INVALID for n < 1, k < 1, k > n, a non-permutation
+ * ready_order, bad op/dtype, object_bytes not a multiple of the element size,
+ * chunk_bytes 0 or not a multiple of 16, tree_degree < 0, NULL dst/objs;
+ * HOP_ERR_ALIGN; HOP_ERR_NO_SURVIVOR; HOP_ERR_DEPTH; HOP_ERR_DEVICE/NOMEM.
+ */
+int hop_reduce(void *dst, const void *const *objs, int n, size_t object_bytes,
+               const int32_t *ready_order, int k, hop_op_t op, hop_dtype_t dtype,
+               size_t chunk_bytes, int tree_degree, const int64_t *fail_mask,
+               void *stream, hop_info_t *info);
+
+/*
+ * hop_broadcast -- section 3.4.1: every receiver ends with a byte-identical
+ * copy of the object, moved chunk by chunk.
+ *   dsts   host array of n_dst device pointers (object_bytes each); n_dst >= 0.
+ *   src    device pointer, object_bytes bytes.
+ * The source is read once per chunk and written to every destination.
+ * Errors: HOP_ERR_INVALID (n_dst < 0, NULL table, chunk_bytes 0 or not a
+ * multiple of 16), HOP_ERR_ALIGN, HOP_ERR_DEVICE/NOMEM.
+ */
+int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_bytes,
+                  size_t chunk_bytes, void *stream);
+
+/*
+ * hop_allreduce -- section 3.4.3: Reduce followed by Broadcast, composed
+ * chunk by chunk (section 3.3): each finished result chunk goes to all n_dst
+ * destinations. Arguments as hop_reduce / hop_broadcast; n_dst >= 1. Every
+ * destination receives the same bits hop_reduce would have produced.
+ */
+int hop_allreduce(void *const *dsts, int n_dst, const void *const *objs, int n,
+                  size_t object_bytes, const int32_t *ready_order, int k, hop_op_t op,
+                  hop_dtype_t dtype, size_t chunk_bytes, int tree_degree,
+                  const int64_t *fail_mask, void *stream, hop_info_t *info);
+
+/*
+ * Event-level form of Reduce: the caller reports, as they happen, which
+ * chunks of which object have become ready and which participants failed;
+ * the scheduler assigns tree positions in arrival order (section 3.4.2),
+ * launches the reduce of every output chunk whose inputs are all present, and
+ * repairs after failures (section 3.5.2). hop_reduce is a replay of these
+ * calls.
+ */
+typedef struct hop_session hop_session_t;
+
+/* Opens a session. Arguments as hop_reduce. *s is set on HOP_OK. */
+int hop_session_begin(hop_session_t **s, void *dst, const void *const *objs, int n,
+                      size_t object_bytes, int k, hop_op_t op, hop_dtype_t dtype,
+                      size_t chunk_bytes, int tree_degree, void *stream);
+
+/* Object obj now has chunks 0..chunks_ready_total-1 ready (monotone; the first
+ * call for an object is its arrival and fixes its tree position or puts it
+ * among the waiting objects; 0 announces an object that has no data yet).
+ * Launches every output chunk that became complete. HOP_ERR_INVALID for an
+ * unknown object, a count that decreases or exceeds the number of chunks, or
+ * an object already reported failed. */
+int hop_session_ready(hop_session_t *s, int obj, int64_t chunks_ready_total);
+
+/* Participant obj failed. If all its chunks were already ready the object is
+ * complete and the call changes nothing. Otherwise it leaves the tree: output
+ * chunks already produced with its data are scheduled again, its position
+ * goes to the next waiting object (else stays empty). */
+int hop_session_fail(hop_session_t *s, int obj);
+
+/* Ends the session: participants that have not delivered every chunk are
+ * treated as failed, remaining work is enqueued, info (may be NULL) is
+ * filled, the session is freed. Returns HOP_OK / HOP_PARTIAL or an error
+ * (the session is freed in every case). */
+int hop_session_finish(hop_session_t *s, hop_info_t *info);
+
+/*
+ * Host-only view of the schedule, for inspection and tests: runs the same
+ * scheduler as hop_reduce on the same arguments but enqueues nothing on any
+ * device (no pointer is dereferenced; objects are named by index).
+ *
+ * Launch l re-computes output chunks [chunk_begin, chunk_end) by evaluating
+ * program entries [entry_begin, entry_end) for each element:
+ *   SET  : acc[level] = x            (x = the element of object `obj`)
+ *   else : acc[level] = acc[level] (op) x
+ *   then n_fold times: acc[level-1] = acc[level-1] (op) acc[level]; --level
+ * and storing acc[0]. Launches must be applied in order (a later launch may
+ * overwrite chunks of an earlier one: that is failure repair).
+ * Returns the status hop_reduce would return; *n_launches / *n_entries hold
+ * the counts needed (also when they exceed the capacities, in which case
+ * the arrays are filled up to capacity).
+ */
+typedef struct { int32_t obj; uint8_t level; uint8_t set; uint16_t n_fold; } hop_plan_entry_t;
+typedef struct { int64_t chunk_begin, chunk_end; int32_t entry_begin, entry_end; } hop_plan_launch_t;
+
+int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int k,
+                    hop_dtype_t dtype, size_t chunk_bytes, int tree_degree,
+                    const int64_t *fail_mask, hop_info_t *info,
+                    hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
+                    hop_plan_entry_t *entries, int entry_capacity, int *n_entries);
+
+/* node_of_slot[t] (k entries) = level-order index of the tree node that the
+ * t-th arrival takes in the complete d-ary tree on k nodes. */
+int hop_plan_slots(int k, int tree_degree, int32_t *node_of_slot);
+
+/* Degree the library would choose for tree_degree = 0: argmin over {1, 2, k}
+ * of T(d) of Eq. 1 (section 3.4.2) with per-level latency latency_s and
+ * bandwidth bytes_per_s; non-positive values select the library defaults. */
+int hop_pick_degree(int k, size_t object_bytes, double latency_s, double bytes_per_s);
+
+/* Bytes of device scratch one hop_reduce / hop_allreduce call of this shape
+ * takes from the library's cached workspace (programs, destination tables). */
+size_t hop_workspace_bytes(int n, int k, int n_dst);
+
+/* Frees the cached workspaces of the calling process (optional; for leak checks). */
+int hop_shutdown(void);
+
+const char *hop_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HOP_H */

@@ -1,0 +1,241 @@
+"""Python binding of libhop.so, the MI355X chunked N-way reduce library.
+
+Argument marshalling only: every function here turns tensors and lists into
+the pointers and sizes of the C ABI declared in include/hop.h and calls it.
+PyTorch provides device memory and streams, nothing else. There is no CPU
+fallback: if the library has not been built, importing its symbols fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch  # imported before libhop.so so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhop.so")
+
+HOP_SUM, HOP_MIN, HOP_MAX = 0, 1, 2
+HOP_F32, HOP_BF16, HOP_I32 = 0, 1, 2
+HOP_OK, HOP_PARTIAL = 0, 1
+HOP_ERR_INVALID, HOP_ERR_ALIGN, HOP_ERR_NO_SURVIVOR = -1, -2, -3
+HOP_ERR_DEVICE, HOP_ERR_NOMEM, HOP_ERR_DEPTH = -4, -5, -6
+HOP_MAX_DEPTH = 16
+
+OPS = {"sum": HOP_SUM, "min": HOP_MIN, "max": HOP_MAX}
+DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
+          torch.float32: HOP_F32, torch.bfloat16: HOP_BF16, torch.int32: HOP_I32}
+
+EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_session_begin", "hop_session_ready",
+           "hop_session_fail", "hop_session_finish", "hop_plan_reduce", "hop_plan_slots",
+           "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror"]
+
+
+class HopInfo(ctypes.Structure):
+    _fields_ = [("k_eff", ctypes.c_int32), ("n_failed_seen", ctypes.c_int32),
+                ("n_replaced", ctypes.c_int32), ("degree_used", ctypes.c_int32),
+                ("chunks_redone", ctypes.c_int64), ("n_launches", ctypes.c_int32),
+                ("stack_depth", ctypes.c_int32)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_}
+
+
+class PlanEntry(ctypes.Structure):
+    _fields_ = [("obj", ctypes.c_int32), ("level", ctypes.c_uint8), ("set", ctypes.c_uint8),
+                ("n_fold", ctypes.c_uint16)]
+
+
+class PlanLaunch(ctypes.Structure):
+    _fields_ = [("chunk_begin", ctypes.c_int64), ("chunk_end", ctypes.c_int64),
+                ("entry_begin", ctypes.c_int32), ("entry_end", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library. Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libhop.so is missing: build it with "
+                               "`python -m paper_2002_05814_amd.build` (hipcc, gfx950)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, vpp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
+        i32p, i64p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+        infop = ctypes.POINTER(HopInfo)
+        L.hop_reduce.argtypes = [vp, vpp, ctypes.c_int, ctypes.c_size_t, i32p, ctypes.c_int, ctypes.c_int,
+                                 ctypes.c_int, ctypes.c_size_t, ctypes.c_int, i64p, vp, infop]
+        L.hop_broadcast.argtypes = [vpp, ctypes.c_int, vp, ctypes.c_size_t, ctypes.c_size_t, vp]
+        L.hop_allreduce.argtypes = [vpp, ctypes.c_int, vpp, ctypes.c_int, ctypes.c_size_t, i32p, ctypes.c_int,
+                                    ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, i64p, vp, infop]
+        L.hop_session_begin.argtypes = [ctypes.POINTER(vp), vp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
+                                        ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, vp]
+        L.hop_session_ready.argtypes = [vp, ctypes.c_int, ctypes.c_int64]
+        L.hop_session_fail.argtypes = [vp, ctypes.c_int]
+        L.hop_session_finish.argtypes = [vp, infop]
+        L.hop_plan_reduce.argtypes = [ctypes.c_int, ctypes.c_size_t, i32p, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_size_t, ctypes.c_int, i64p, infop,
+                                      ctypes.POINTER(PlanLaunch), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                      ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        L.hop_plan_slots.argtypes = [ctypes.c_int, ctypes.c_int, i32p]
+        L.hop_pick_degree.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
+        L.hop_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        L.hop_workspace_bytes.restype = ctypes.c_size_t
+        L.hop_shutdown.argtypes = []
+        L.hop_strerror.argtypes = [ctypes.c_int]
+        L.hop_strerror.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name not in ("hop_workspace_bytes", "hop_strerror"):
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def hop_strerror(status: int) -> str:
+    return lib().hop_strerror(int(status)).decode()
+
+
+# ------------------------------------------------------------------ marshalling helpers
+
+def _ptr_table(items: Sequence) -> Tuple[ctypes.Array, int]:
+    """Host array of device pointers from tensors or raw integer addresses."""
+    ptrs = [int(t.data_ptr()) if isinstance(t, torch.Tensor) else int(t) for t in items]
+    return (ctypes.c_void_p * max(len(ptrs), 1))(*ptrs), len(ptrs)
+
+
+def _i32(a):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _i64(a):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=np.int64)
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def _bytes_of(t, object_bytes):
+    if object_bytes is not None:
+        return int(object_bytes)
+    return t.numel() * t.element_size()
+
+
+def _code(table, v):
+    return table[v] if v in table else int(v)
+
+
+# ------------------------------------------------------------------ the C ABI, same names
+
+def hop_reduce(dst, objs, k, op, dtype, chunk_bytes, tree_degree, ready_order=None, fail_mask=None,
+               stream=None, object_bytes=None):
+    """hop_reduce of include/hop.h. dst/objs: CUDA tensors (or raw addresses with object_bytes).
+
+    Returns (status, info dict).
+    """
+    tab, n = _ptr_table(objs)
+    _ro, ro = _i32(ready_order)
+    _fm, fm = _i64(fail_mask)
+    info = HopInfo()
+    dptr = ctypes.c_void_p(int(dst.data_ptr()) if isinstance(dst, torch.Tensor) else int(dst))
+    rc = lib().hop_reduce(dptr, tab, n, _bytes_of(objs[0] if n else dst, object_bytes), ro, int(k),
+                          _code(OPS, op), _code(DTYPES, dtype), int(chunk_bytes), int(tree_degree), fm,
+                          _stream(stream), ctypes.byref(info))
+    return rc, info.as_dict()
+
+
+def hop_broadcast(dsts, src, chunk_bytes, stream=None, object_bytes=None):
+    tab, n_dst = _ptr_table(dsts)
+    sptr = ctypes.c_void_p(int(src.data_ptr()) if isinstance(src, torch.Tensor) else int(src))
+    return lib().hop_broadcast(tab, n_dst, sptr, _bytes_of(src, object_bytes), int(chunk_bytes), _stream(stream))
+
+
+def hop_allreduce(dsts, objs, k, op, dtype, chunk_bytes, tree_degree, ready_order=None, fail_mask=None,
+                  stream=None, object_bytes=None):
+    dtab, n_dst = _ptr_table(dsts)
+    tab, n = _ptr_table(objs)
+    _ro, ro = _i32(ready_order)
+    _fm, fm = _i64(fail_mask)
+    info = HopInfo()
+    rc = lib().hop_allreduce(dtab, n_dst, tab, n, _bytes_of(objs[0] if n else dsts[0], object_bytes), ro, int(k),
+                             _code(OPS, op), _code(DTYPES, dtype), int(chunk_bytes), int(tree_degree), fm,
+                             _stream(stream), ctypes.byref(info))
+    return rc, info.as_dict()
+
+
+def hop_session_begin(dst, objs, k, op, dtype, chunk_bytes, tree_degree, stream=None, object_bytes=None):
+    """Returns (status, session handle)."""
+    tab, n = _ptr_table(objs)
+    h = ctypes.c_void_p()
+    dptr = ctypes.c_void_p(int(dst.data_ptr()) if isinstance(dst, torch.Tensor) else int(dst))
+    rc = lib().hop_session_begin(ctypes.byref(h), dptr, tab, n, _bytes_of(objs[0] if n else dst, object_bytes),
+                                 int(k), _code(OPS, op), _code(DTYPES, dtype), int(chunk_bytes),
+                                 int(tree_degree), _stream(stream))
+    return rc, h
+
+
+def hop_session_ready(session, obj, chunks_ready_total):
+    return lib().hop_session_ready(session, int(obj), int(chunks_ready_total))
+
+
+def hop_session_fail(session, obj):
+    return lib().hop_session_fail(session, int(obj))
+
+
+def hop_session_finish(session):
+    """Returns (status, info dict); the session handle is dead afterwards."""
+    info = HopInfo()
+    rc = lib().hop_session_finish(session, ctypes.byref(info))
+    return rc, info.as_dict()
+
+
+def hop_plan_reduce(n, object_bytes, k, dtype, chunk_bytes, tree_degree, ready_order=None, fail_mask=None):
+    """Host-only schedule: (status, info, launches, entries) with launches as
+    (chunk_begin, chunk_end, entry_begin, entry_end) and entries as (obj, level, set, n_fold)."""
+    _ro, ro = _i32(ready_order)
+    _fm, fm = _i64(fail_mask)
+    info = HopInfo()
+    nl, ne = ctypes.c_int(0), ctypes.c_int(0)
+    args = (int(n), int(object_bytes), ro, int(k), _code(DTYPES, dtype), int(chunk_bytes), int(tree_degree), fm)
+    rc = lib().hop_plan_reduce(*args, ctypes.byref(info), None, 0, ctypes.byref(nl), None, 0, ctypes.byref(ne))
+    if rc < 0:
+        return rc, info.as_dict(), [], []
+    L = (PlanLaunch * max(nl.value, 1))()
+    E = (PlanEntry * max(ne.value, 1))()
+    rc = lib().hop_plan_reduce(*args, ctypes.byref(info), L, nl.value, ctypes.byref(nl), E, ne.value,
+                               ctypes.byref(ne))
+    launches = [(L[i].chunk_begin, L[i].chunk_end, L[i].entry_begin, L[i].entry_end) for i in range(nl.value)]
+    entries = [(E[i].obj, E[i].level, E[i].set, E[i].n_fold) for i in range(ne.value)]
+    return rc, info.as_dict(), launches, entries
+
+
+def hop_plan_slots(k, tree_degree):
+    out = np.empty(max(k, 1), np.int32)
+    rc = lib().hop_plan_slots(int(k), int(tree_degree), out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    return rc, out
+
+
+def hop_pick_degree(k, object_bytes, latency_s=0.0, bytes_per_s=0.0):
+    return lib().hop_pick_degree(int(k), int(object_bytes), float(latency_s), float(bytes_per_s))
+
+
+def hop_workspace_bytes(n, k, n_dst=0):
+    return lib().hop_workspace_bytes(int(n), int(k), int(n_dst))
+
+
+def hop_shutdown():
+    return lib().hop_shutdown()

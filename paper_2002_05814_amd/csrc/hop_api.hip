@@ -1,0 +1,498 @@
+// C ABI of the reduce library (include/hop.h): argument checks, the GPU back
+// end that turns scheduler launches into kernel launches, the cached
+// workspace that carries accumulator programs and destination tables to the
+// device, and the recording back end behind hop_plan_reduce.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "hop_kernels.h"
+#include "hop_plan.hpp"
+
+namespace hop {
+
+// ----------------------------------------------------------------------------
+// workspace: pinned host staging + device memory, cached across calls
+// ----------------------------------------------------------------------------
+
+struct Block {
+    int device = -1;
+    char *host = nullptr;       // pinned
+    char *dev = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;    // last use on a stream
+    bool pending = false;
+};
+
+static std::mutex g_mu;
+static std::vector<Block *> g_free;
+static constexpr size_t kMinBlock = 256 * 1024;
+
+static Block *acquire_block(int device, size_t bytes)
+{
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        for (size_t i = 0; i < g_free.size(); ++i) {
+            Block *b = g_free[i];
+            if (b->device != device || b->cap < bytes) continue;
+            if (b->pending) {
+                if (hipEventQuery(b->ev) != hipSuccess) { (void)hipGetLastError(); continue; }
+                b->pending = false;
+            }
+            g_free.erase(g_free.begin() + i);
+            return b;
+        }
+    }
+    Block *b = new (std::nothrow) Block;
+    if (!b) return nullptr;
+    b->device = device;
+    b->cap = bytes < kMinBlock ? kMinBlock : ((bytes + kMinBlock - 1) / kMinBlock) * kMinBlock;
+    if (hipHostMalloc((void **)&b->host, b->cap, hipHostMallocDefault) != hipSuccess) { delete b; return nullptr; }
+    if (hipMalloc((void **)&b->dev, b->cap) != hipSuccess) { (void)hipHostFree(b->host); delete b; return nullptr; }
+    if (hipEventCreateWithFlags(&b->ev, hipEventDisableTiming) != hipSuccess) {
+        (void)hipFree(b->dev); (void)hipHostFree(b->host); delete b; return nullptr;
+    }
+    return b;
+}
+
+static void release_block(Block *b, hipStream_t stream)
+{
+    if (!b) return;
+    b->pending = (hipEventRecord(b->ev, stream) == hipSuccess);
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_free.push_back(b);
+}
+
+// Bump allocator over a list of blocks; everything staged is copied to the
+// device with one async copy per stage() call, ordered on the stream.
+class Workspace {
+public:
+    Workspace(int device, hipStream_t stream) : device_(device), stream_(stream) {}
+    ~Workspace() { for (Block *b : blocks_) release_block(b, stream_); }
+
+    // Copies `bytes` from src to device memory (16-byte aligned); returns the device address or null.
+    void *stage(const void *src, size_t bytes)
+    {
+        size_t need = (bytes + 255) & ~(size_t)255;
+        if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
+            Block *b = acquire_block(device_, need);
+            if (!b) return nullptr;
+            blocks_.push_back(b);
+            used_ = 0;
+        }
+        Block *b = blocks_.back();
+        std::memcpy(b->host + used_, src, bytes);
+        if (hipMemcpyAsync(b->dev + used_, b->host + used_, bytes, hipMemcpyHostToDevice, stream_) != hipSuccess)
+            return nullptr;
+        void *d = b->dev + used_;
+        used_ += need;
+        return d;
+    }
+
+private:
+    int device_;
+    hipStream_t stream_;
+    std::vector<Block *> blocks_;
+    size_t used_ = 0;
+};
+
+static int cu_count(int device)
+{
+    static std::mutex mu;
+    static std::vector<int> cache;
+    std::lock_guard<std::mutex> lk(mu);
+    if ((int)cache.size() <= device) cache.resize(device + 1, 0);
+    if (cache[device] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || v <= 0) v = 256;
+        cache[device] = v;
+    }
+    return cache[device];
+}
+
+// ----------------------------------------------------------------------------
+// back ends
+// ----------------------------------------------------------------------------
+
+struct Shape {
+    size_t object_bytes = 0, chunk_bytes = 0;
+    int64_t n_chunks = 1;
+    size_t begin(int64_t c) const { return (size_t)c * chunk_bytes; }
+    size_t end(int64_t c) const { size_t e = (size_t)c * chunk_bytes; return e < object_bytes ? e : object_bytes; }
+};
+
+class GpuBackend : public Backend {
+public:
+    GpuBackend(int device, hipStream_t stream, const void *const *objs, int n, std::vector<void *> dsts,
+               const Shape &shape, int op, int dtype)
+        : ws_(device, stream), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
+          op_(op), dtype_(dtype), n_cu_(cu_count(device)) {}
+
+    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) override
+    {
+        if (shape_.object_bytes == 0) return HOP_OK;
+        if (version != dev_version_) {
+            staging_.resize(prog.size());
+            depth_ = 1;
+            for (size_t i = 0; i < prog.size(); ++i) {
+                staging_[i].src = objs_[prog[i].obj];
+                staging_[i].ctl = (uint32_t)prog[i].level | ((uint32_t)prog[i].set << 8) | ((uint32_t)prog[i].n_fold << 16);
+                staging_[i].reserved = 0;
+                depth_ = std::max(depth_, (int)prog[i].level + 1);
+            }
+            dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
+            if (!dev_prog_) return HOP_ERR_NOMEM;
+            dev_version_ = version;
+        }
+        if (dsts_.size() > 1 && !dev_extra_) {
+            dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
+            if (!dev_extra_) return HOP_ERR_NOMEM;
+        }
+        const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
+        // the finished chunks go to the first destination; the broadcast copy then
+        // carries the same chunks to the others (reduce followed by broadcast, chunk by chunk)
+        hipError_t e = launch_reduce(stream_, dtype_, op_, depth_, dev_prog_, (int)prog.size(), dsts_[0],
+                                     nullptr, 0, b0, b1, n_cu_);
+        if (e == hipSuccess && dsts_.size() > 1)
+            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, n_cu_);
+        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+    }
+
+private:
+    Workspace ws_;
+    hipStream_t stream_;
+    std::vector<const void *> objs_;
+    std::vector<void *> dsts_;
+    Shape shape_;
+    int op_, dtype_, n_cu_;
+    std::vector<DevEntry> staging_;
+    const DevEntry *dev_prog_ = nullptr;
+    void *const *dev_extra_ = nullptr;
+    uint64_t dev_version_ = 0;
+    int depth_ = 1;
+};
+
+class RecordingBackend : public Backend {
+public:
+    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) override
+    {
+        if (version != version_) {
+            entry_begin_ = (int32_t)entries.size();
+            entries.insert(entries.end(), prog.begin(), prog.end());
+            version_ = version;
+        }
+        launches.push_back({c0, c1, entry_begin_, (int32_t)(entry_begin_ + prog.size())});
+        return HOP_OK;
+    }
+    std::vector<Entry> entries;
+    std::vector<hop_plan_launch_t> launches;
+
+private:
+    uint64_t version_ = 0;
+    int32_t entry_begin_ = 0;
+};
+
+// ----------------------------------------------------------------------------
+// argument checks shared by the entry points
+// ----------------------------------------------------------------------------
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+static int check_shape(int n, size_t object_bytes, int k, int op, int dtype, size_t chunk_bytes, int tree_degree,
+                       Shape *shape)
+{
+    if (n < 1 || k < 1 || k > n) return HOP_ERR_INVALID;
+    if (op < HOP_SUM || op > HOP_MAX || dtype < HOP_F32 || dtype > HOP_I32) return HOP_ERR_INVALID;
+    if (chunk_bytes == 0 || chunk_bytes % 16 != 0 || tree_degree < 0) return HOP_ERR_INVALID;
+    if (object_bytes % (size_t)elem_bytes(dtype) != 0) return HOP_ERR_INVALID;
+    shape->object_bytes = object_bytes;
+    shape->chunk_bytes = chunk_bytes;
+    shape->n_chunks = object_bytes ? (int64_t)((object_bytes + chunk_bytes - 1) / chunk_bytes) : 1;
+    return HOP_OK;
+}
+
+static int check_order(int n, const int32_t *ready_order)
+{
+    if (!ready_order) return HOP_OK;
+    std::vector<char> seen(n, 0);
+    for (int t = 0; t < n; ++t) {
+        int i = ready_order[t];
+        if (i < 0 || i >= n || seen[i]) return HOP_ERR_INVALID;
+        seen[i] = 1;
+    }
+    return HOP_OK;
+}
+
+static int check_buffers(const void *const *objs, int n, void *const *dsts, int n_dst, size_t object_bytes)
+{
+    if (!objs || !dsts || n_dst < 1) return HOP_ERR_INVALID;
+    for (int j = 0; j < n_dst; ++j) {
+        if (!dsts[j]) return HOP_ERR_INVALID;
+        if (!aligned16(dsts[j])) return HOP_ERR_ALIGN;
+    }
+    for (int i = 0; i < n; ++i) {
+        if (!objs[i]) return HOP_ERR_INVALID;
+        if (!aligned16(objs[i])) return HOP_ERR_ALIGN;
+        for (int j = 0; j < n_dst; ++j) {
+            const char *a = (const char *)objs[i], *b = (const char *)dsts[j];
+            if (object_bytes && a < b + object_bytes && b < a + object_bytes) return HOP_ERR_INVALID;   // result would overwrite a source
+        }
+    }
+    return HOP_OK;
+}
+
+static const double kDefaultLatency = 2e-6;     // seconds per tree level (kernel-launch scale)
+static const double kDefaultBandwidth = 5e12;   // bytes per second (HBM scale)
+
+static int pick_degree(int k, size_t object_bytes, double L, double B)
+{
+    if (k <= 2) return 1;
+    if (!(L > 0)) L = kDefaultLatency;
+    if (!(B > 0)) B = kDefaultBandwidth;
+    const int cand[3] = {1, 2, k};
+    int best = 1;
+    double best_t = tree_cost(k, 1, (double)object_bytes, L, B);
+    for (int i = 1; i < 3; ++i) {
+        double t = tree_cost(k, cand[i], (double)object_bytes, L, B);
+        if (t < best_t) { best_t = t; best = cand[i]; }
+    }
+    return best;
+}
+
+static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, int n, size_t object_bytes,
+                         const int32_t *ready_order, int k, int op, int dtype, size_t chunk_bytes,
+                         int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info)
+{
+    Shape shape;
+    int rc = check_shape(n, object_bytes, k, op, dtype, chunk_bytes, tree_degree, &shape);
+    if (rc < 0) return rc;
+    if ((rc = check_order(n, ready_order)) < 0) return rc;
+    if ((rc = check_buffers(objs, n, dsts, n_dst, object_bytes)) < 0) return rc;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
+    const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    try {
+        GpuBackend be(device, (hipStream_t)stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype);
+        Scheduler s(n, k, shape.n_chunks, d, &be);
+        return replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+}  // namespace hop
+
+// ----------------------------------------------------------------------------
+// C ABI
+// ----------------------------------------------------------------------------
+
+using namespace hop;
+
+struct hop_session {
+    std::unique_ptr<GpuBackend> be;
+    std::unique_ptr<Scheduler> sched;
+};
+
+extern "C" {
+
+int hop_reduce(void *dst, const void *const *objs, int n, size_t object_bytes, const int32_t *ready_order,
+               int k, hop_op_t op, hop_dtype_t dtype, size_t chunk_bytes, int tree_degree,
+               const int64_t *fail_mask, void *stream, hop_info_t *info)
+{
+    if (!dst) return HOP_ERR_INVALID;
+    void *dsts[1] = {dst};
+    return reduce_common(dsts, 1, objs, n, object_bytes, ready_order, k, (int)op, (int)dtype, chunk_bytes,
+                         tree_degree, fail_mask, stream, info);
+}
+
+int hop_allreduce(void *const *dsts, int n_dst, const void *const *objs, int n, size_t object_bytes,
+                  const int32_t *ready_order, int k, hop_op_t op, hop_dtype_t dtype, size_t chunk_bytes,
+                  int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info)
+{
+    if (!dsts || n_dst < 1) return HOP_ERR_INVALID;
+    for (int a = 0; a < n_dst; ++a)
+        for (int b = a + 1; b < n_dst; ++b)
+            if (dsts[a] == dsts[b]) return HOP_ERR_INVALID;
+    return reduce_common(dsts, n_dst, objs, n, object_bytes, ready_order, k, (int)op, (int)dtype, chunk_bytes,
+                         tree_degree, fail_mask, stream, info);
+}
+
+int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_bytes, size_t chunk_bytes,
+                  void *stream)
+{
+    if (n_dst < 0 || (n_dst > 0 && !dsts) || chunk_bytes == 0 || chunk_bytes % 16 != 0) return HOP_ERR_INVALID;
+    if (n_dst == 0 || object_bytes == 0) return HOP_OK;
+    if (!src) return HOP_ERR_INVALID;
+    if (!aligned16(src)) return HOP_ERR_ALIGN;
+    for (int j = 0; j < n_dst; ++j) {
+        if (!dsts[j]) return HOP_ERR_INVALID;
+        if (!aligned16(dsts[j])) return HOP_ERR_ALIGN;
+        const char *a = (const char *)src, *b = (const char *)dsts[j];
+        if (a < b + object_bytes && b < a + object_bytes) return HOP_ERR_INVALID;
+    }
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
+    try {
+        Workspace ws(device, (hipStream_t)stream);
+        void *const *table = (void *const *)ws.stage(dsts, (size_t)n_dst * sizeof(void *));
+        if (!table) return HOP_ERR_NOMEM;
+        // The whole source is present, so every chunk is ready at once: one launch covers them all.
+        hipError_t e = launch_copy((hipStream_t)stream, src, table, n_dst, 0, object_bytes, cu_count(device));
+        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_session_begin(hop_session_t **s, void *dst, const void *const *objs, int n, size_t object_bytes, int k,
+                      hop_op_t op, hop_dtype_t dtype, size_t chunk_bytes, int tree_degree, void *stream)
+{
+    if (!s || !dst) return HOP_ERR_INVALID;
+    *s = nullptr;
+    Shape shape;
+    int rc = check_shape(n, object_bytes, k, (int)op, (int)dtype, chunk_bytes, tree_degree, &shape);
+    if (rc < 0) return rc;
+    void *dsts[1] = {dst};
+    if ((rc = check_buffers(objs, n, dsts, 1, object_bytes)) < 0) return rc;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
+    const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    try {
+        std::unique_ptr<hop_session> h(new hop_session);
+        h->be.reset(new GpuBackend(device, (hipStream_t)stream, objs, n, std::vector<void *>(1, dst), shape,
+                                   (int)op, (int)dtype));
+        h->sched.reset(new Scheduler(n, k, shape.n_chunks, d, h->be.get()));
+        *s = h.release();
+        return HOP_OK;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_session_ready(hop_session_t *s, int obj, int64_t chunks_ready_total)
+{
+    if (!s) return HOP_ERR_INVALID;
+    try {
+        int rc = s->sched->on_ready(obj, chunks_ready_total);
+        return rc < 0 ? rc : s->sched->pump();
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_session_fail(hop_session_t *s, int obj)
+{
+    if (!s) return HOP_ERR_INVALID;
+    try {
+        int rc = s->sched->on_fail(obj);
+        return rc < 0 ? rc : s->sched->pump();
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_session_finish(hop_session_t *s, hop_info_t *info)
+{
+    if (!s) return HOP_ERR_INVALID;
+    int rc;
+    try {
+        rc = s->sched->finish(info);
+    } catch (const std::bad_alloc &) {
+        rc = HOP_ERR_NOMEM;
+    }
+    delete s;
+    return rc;
+}
+
+int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int k, hop_dtype_t dtype,
+                    size_t chunk_bytes, int tree_degree, const int64_t *fail_mask, hop_info_t *info,
+                    hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
+                    hop_plan_entry_t *entries, int entry_capacity, int *n_entries)
+{
+    Shape shape;
+    int rc = check_shape(n, object_bytes, k, HOP_SUM, (int)dtype, chunk_bytes, tree_degree, &shape);
+    if (rc < 0) return rc;
+    if ((rc = check_order(n, ready_order)) < 0) return rc;
+    const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    try {
+        RecordingBackend be;
+        Scheduler s(n, k, shape.n_chunks, d, &be);
+        rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
+        if (n_launches) *n_launches = (int)be.launches.size();
+        if (n_entries) *n_entries = (int)be.entries.size();
+        for (int i = 0; launches && i < launch_capacity && i < (int)be.launches.size(); ++i) launches[i] = be.launches[i];
+        for (int i = 0; entries && i < entry_capacity && i < (int)be.entries.size(); ++i) {
+            entries[i].obj = be.entries[i].obj;
+            entries[i].level = be.entries[i].level;
+            entries[i].set = be.entries[i].set;
+            entries[i].n_fold = be.entries[i].n_fold;
+        }
+        return rc;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_plan_slots(int k, int tree_degree, int32_t *node_of_slot)
+{
+    if (k < 1 || tree_degree < 1 || !node_of_slot) return HOP_ERR_INVALID;
+    try {
+        Tree t;
+        t.build(k, tree_degree);
+        std::memcpy(node_of_slot, t.node_of_slot.data(), sizeof(int32_t) * (size_t)k);
+        return HOP_OK;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_pick_degree(int k, size_t object_bytes, double latency_s, double bytes_per_s)
+{
+    if (k < 1) return HOP_ERR_INVALID;
+    return pick_degree(k, object_bytes, latency_s, bytes_per_s);
+}
+
+size_t hop_workspace_bytes(int n, int k, int n_dst)
+{
+    (void)n;
+    if (k < 0 || n_dst < 0) return 0;
+    size_t need = (size_t)k * sizeof(DevEntry) + (size_t)(n_dst > 1 ? n_dst - 1 : 0) * sizeof(void *) + 512;
+    return need < kMinBlock ? kMinBlock : ((need + kMinBlock - 1) / kMinBlock) * kMinBlock;
+}
+
+int hop_shutdown(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    int rc = HOP_OK;
+    for (Block *b : g_free) {
+        if (b->pending && hipEventSynchronize(b->ev) != hipSuccess) rc = HOP_ERR_DEVICE;
+        (void)hipEventDestroy(b->ev);
+        (void)hipFree(b->dev);
+        (void)hipHostFree(b->host);
+        delete b;
+    }
+    g_free.clear();
+    return rc;
+}
+
+const char *hop_strerror(int status)
+{
+    switch (status) {
+    case HOP_OK: return "ok";
+    case HOP_PARTIAL: return "fewer than k objects survived; all survivors were reduced";
+    case HOP_ERR_INVALID: return "invalid argument";
+    case HOP_ERR_ALIGN: return "device buffer not 16-byte aligned";
+    case HOP_ERR_NO_SURVIVOR: return "no object survived";
+    case HOP_ERR_DEVICE: return "HIP call failed";
+    case HOP_ERR_NOMEM: return "out of memory";
+    case HOP_ERR_DEPTH: return "reduce tree needs more live partial results than the kernels hold";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

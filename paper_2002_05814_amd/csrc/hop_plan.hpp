@@ -1,0 +1,325 @@
+// Host-side chunk scheduler of the MI355X reduce library: tree shape, slot
+// assignment by arrival, per-chunk readiness, failure repair, and the
+// translation of the tree into a flat accumulator program for the kernels.
+// No HIP in this file: it is driven either by the GPU back end (hop_api.hip)
+// or by a recording back end (hop_plan_reduce) that enqueues nothing.
+//
+// Paper passages: dynamic d-ary tree and in-order placement of arrivals,
+// subset reduce (section 3.4.2); chunk-granular pipelining (section 3.3);
+// removal and in-place replacement of a failed participant (section 3.5.2).
+#pragma once
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <deque>
+#include <set>
+#include <vector>
+
+#include "../../include/hop.h"
+
+namespace hop {
+
+// One step of the per-element accumulator program (same meaning as
+// hop_plan_entry_t): read the element of object `obj`, start or extend the
+// partial result at `level`, then fold `n_fold` finished partials downwards.
+struct Entry {
+    int32_t obj;
+    uint8_t level;
+    uint8_t set;
+    uint16_t n_fold;
+};
+
+// Complete d-ary tree on k nodes in level order; node_of_slot[t] is the node
+// that the t-th arrival takes (generalised in-order traversal, section 3.4.2).
+struct Tree {
+    int k = 0;
+    int64_t d = 1;
+    std::vector<int32_t> node_of_slot, slot_of_node;
+
+    int64_t child(int64_t j, int64_t c) const {
+        int64_t x = d * j + c;
+        return (x < k) ? x : -1;
+    }
+
+    void build(int k_, int64_t d_) {
+        k = k_;
+        d = d_;
+        node_of_slot.assign(k, -1);
+        slot_of_node.assign(k, -1);
+        // Explicit stack: (node, next child to descend into). A chain (d = 1)
+        // is k levels deep, so recursion is avoided.
+        struct Frame { int64_t node; int64_t next; bool visited; };
+        std::vector<Frame> st;
+        st.push_back({0, 1, false});
+        int t = 0;
+        while (!st.empty()) {
+            Frame &f = st.back();
+            if (f.next == 1) {                       // first child's subtree comes first
+                f.next = 2;
+                int64_t c1 = child(f.node, 1);
+                if (c1 >= 0) { st.push_back({c1, 1, false}); continue; }
+            }
+            if (!f.visited) {                        // then the node itself
+                f.visited = true;
+                node_of_slot[t] = (int32_t)f.node;
+                slot_of_node[f.node] = t;
+                ++t;
+            }
+            int64_t c = (f.next <= d) ? child(f.node, f.next) : -1;
+            if (c >= 0) {                            // then children 2..d, left to right
+                f.next++;
+                st.push_back({c, 1, false});
+                continue;
+            }
+            st.pop_back();
+        }
+    }
+};
+
+// Flattens the tree expression over the current occupants (-1 = empty
+// position, contributes nothing) into accumulator steps. A node combines,
+// left to right, [first child's partial, its own object, other children's
+// partials]; the first child's partial is built in the parent's own
+// accumulator, every later child in the next level and folded in when done.
+// Returns the number of accumulator levels used (0 if nobody is in the tree).
+inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant, std::vector<Entry> &out)
+{
+    out.clear();
+    int depth = 0;
+    if (tr.d == 1 || tr.k == 1) {
+        // chain: plain left fold in arrival order
+        for (int t = 0; t < tr.k; ++t) {
+            if (occupant[t] < 0) continue;
+            out.push_back({occupant[t], 0, (uint8_t)out.empty(), 0});
+        }
+        return out.empty() ? 0 : 1;
+    }
+    // d >= 2: height <= log2(k), recursion is shallow
+    struct R {
+        const Tree &tr; const std::vector<int32_t> &occ; std::vector<Entry> &out; int &depth;
+        bool emit(int64_t j, int level) {
+            bool started = false;
+            int64_t c1 = tr.child(j, 1);
+            if (c1 >= 0) started = emit(c1, level);
+            int32_t o = occ[tr.slot_of_node[j]];
+            if (o >= 0) {
+                out.push_back({o, (uint8_t)level, (uint8_t)!started, 0});
+                depth = std::max(depth, level + 1);
+                started = true;
+            }
+            for (int64_t c = 2; c <= tr.d; ++c) {
+                int64_t ch = tr.child(j, c);
+                if (ch < 0) break;
+                if (!started) {
+                    started = emit(ch, level);
+                } else if (level + 1 < 255 && emit(ch, level + 1)) {
+                    out.back().n_fold++;
+                }
+            }
+            return started;
+        }
+    } r{tr, occupant, out, depth};
+    r.emit(0, 0);
+    return depth;
+}
+
+// Where the scheduler sends work. launch() must make output chunks
+// [c0, c1) equal to the program's value; programs are identified by a
+// version that changes whenever the occupants change.
+struct Backend {
+    virtual ~Backend() {}
+    virtual int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) = 0;
+};
+
+class Scheduler {
+public:
+    Scheduler(int n, int k, int64_t n_chunks, int64_t degree, Backend *be)
+        : n_(n), k_(k), C_(n_chunks), be_(be),
+          ready_(n, 0), state_(n, UNSEEN), slot_of_obj_(n, -1), occupant_(k, -1)
+    {
+        tree_.build(k, degree);
+    }
+
+    // Object obj has chunks [0, c) ready. First call = arrival.
+    int on_ready(int obj, int64_t c)
+    {
+        if (obj < 0 || obj >= n_ || c < 0 || c > C_) return HOP_ERR_INVALID;
+        if (state_[obj] == FAILED || c < ready_[obj]) return HOP_ERR_INVALID;
+        if (state_[obj] == UNSEEN) {
+            state_[obj] = STREAMING;
+            if (!holes_.empty()) {
+                // a position emptied by a failure goes to the next ready object
+                int t = *holes_.begin();
+                holes_.erase(holes_.begin());
+                place(obj, t);
+                info_.n_replaced++;
+                invalidate();
+            } else if (next_free_ < k_) {
+                place(obj, next_free_++);
+            } else {
+                pool_.push_back(obj);
+            }
+        }
+        ready_[obj] = c;
+        if (c == C_) state_[obj] = COMPLETE;
+        return HOP_OK;
+    }
+
+    int on_fail(int obj)
+    {
+        if (obj < 0 || obj >= n_) return HOP_ERR_INVALID;
+        if (state_[obj] == FAILED || state_[obj] == COMPLETE) return HOP_OK;   // complete objects are immutable and stay valid
+        state_[obj] = FAILED;
+        info_.n_failed_seen++;
+        int t = slot_of_obj_[obj];
+        if (t < 0) return HOP_OK;            // was waiting (or never arrived): skipped when the pool is popped
+        slot_of_obj_[obj] = -1;
+        occupant_[t] = -1;
+        version_++;
+        invalidate();
+        while (!pool_.empty() && state_[pool_.front()] == FAILED) pool_.pop_front();
+        if (!pool_.empty()) {
+            int j = pool_.front();
+            pool_.pop_front();
+            place(j, t);
+            info_.n_replaced++;
+        } else {
+            holes_.insert(t);
+        }
+        return HOP_OK;
+    }
+
+    // Launch every output chunk whose inputs are all present.
+    int pump()
+    {
+        if (next_free_ < k_ && !closing_) return HOP_OK;     // tree still filling: later arrivals belong in front
+        int64_t frontier = C_;
+        int live = 0;
+        for (int t = 0; t < k_; ++t) {
+            int o = occupant_[t];
+            if (o < 0) continue;
+            live++;
+            frontier = std::min(frontier, ready_[o]);
+        }
+        if (live == 0 || frontier <= launched_) return HOP_OK;
+        if (compiled_version_ != version_) {
+            int depth = compile_program(tree_, occupant_, prog_);
+            compiled_version_ = version_;
+            info_.stack_depth = std::max(info_.stack_depth, depth);
+            if (depth > HOP_MAX_DEPTH) return HOP_ERR_DEPTH;
+        }
+        int64_t redo = std::max<int64_t>(0, std::min(frontier, redo_upto_) - launched_);
+        int rc = be_->launch(prog_, version_, launched_, frontier);
+        if (rc < 0) return rc;
+        info_.chunks_redone += redo * (int64_t)prog_.size();
+        info_.n_launches++;
+        launched_ = frontier;
+        return HOP_OK;
+    }
+
+    // No more events: incomplete participants count as failed, unfilled
+    // positions stay empty, the rest of the output is produced.
+    int finish(hop_info_t *info)
+    {
+        closing_ = true;
+        for (int obj : pool_)
+            if (state_[obj] == STREAMING) { state_[obj] = FAILED; info_.n_failed_seen++; }
+        for (int t = 0; t < k_; ++t) {
+            int o = occupant_[t];
+            if (o >= 0 && state_[o] == STREAMING) on_fail(o);
+            // a replacement pulled from the pool is complete (incomplete ones were just failed)
+        }
+        int rc = pump();
+        int live = 0;
+        for (int t = 0; t < k_; ++t) live += occupant_[t] >= 0;
+        info_.k_eff = live;
+        info_.degree_used = (int32_t)std::min<int64_t>(tree_.d, INT32_MAX);
+        if (info) *info = info_;
+        if (rc < 0) return rc;
+        if (live == 0) return HOP_ERR_NO_SURVIVOR;
+        return live < k_ ? HOP_PARTIAL : HOP_OK;
+    }
+
+    bool arrived(int obj) const { return state_[obj] != UNSEEN; }
+    bool alive(int obj) const { return state_[obj] == STREAMING || state_[obj] == COMPLETE; }
+    const Tree &tree() const { return tree_; }
+
+private:
+    enum State : uint8_t { UNSEEN, STREAMING, COMPLETE, FAILED };
+
+    void place(int obj, int t)
+    {
+        occupant_[t] = obj;
+        slot_of_obj_[obj] = t;
+        version_++;
+    }
+
+    // The occupants changed: everything produced so far contained the old set.
+    void invalidate()
+    {
+        redo_upto_ = std::max(redo_upto_, launched_);
+        launched_ = 0;
+    }
+
+    int n_, k_;
+    int64_t C_;
+    Backend *be_;
+    Tree tree_;
+    std::vector<int64_t> ready_;
+    std::vector<State> state_;
+    std::vector<int32_t> slot_of_obj_, occupant_;
+    std::deque<int32_t> pool_;           // arrived, not in the tree, in arrival order
+    std::set<int> holes_;                // positions emptied by a failure with nobody waiting
+    int next_free_ = 0;                  // positions [0, next_free_) have been handed out
+    bool closing_ = false;
+    int64_t launched_ = 0;               // output chunks [0, launched_) hold the current occupants' result
+    int64_t redo_upto_ = 0;              // chunks below this were produced at least once before
+    uint64_t version_ = 1, compiled_version_ = 0;
+    std::vector<Entry> prog_;
+    hop_info_t info_ = {};
+};
+
+// hop_reduce as a replay of session events: every object that ever becomes
+// ready announces itself in ready order; then all participants stream their
+// chunks side by side, so a participant with fail_mask c is found failed when
+// everyone has delivered c chunks, after the scheduler has used them.
+inline int replay_reduce(Scheduler &s, int n, int64_t C, const int32_t *ready_order,
+                         const int64_t *fail_mask, hop_info_t *info)
+{
+    std::vector<int> arrival;
+    std::vector<int64_t> limit(n, C);
+    std::vector<int64_t> steps;
+    for (int t = 0; t < n; ++t) {
+        int i = ready_order ? ready_order[t] : t;
+        if (fail_mask && fail_mask[i] >= 0 && fail_mask[i] < C) limit[i] = fail_mask[i];
+        if (limit[i] == 0) continue;                 // never becomes ready
+        arrival.push_back(i);
+        if (limit[i] < C) steps.push_back(limit[i]);
+    }
+    std::sort(steps.begin(), steps.end());
+    steps.erase(std::unique(steps.begin(), steps.end()), steps.end());
+    int rc;
+    for (int i : arrival)
+        if ((rc = s.on_ready(i, 0)) < 0) return rc;
+    for (int64_t step : steps) {
+        for (int i : arrival)
+            if (s.alive(i) && (rc = s.on_ready(i, std::min(step, limit[i]))) < 0) return rc;
+        if ((rc = s.pump()) < 0) return rc;
+        for (int i : arrival)
+            if (limit[i] == step && (rc = s.on_fail(i)) < 0) return rc;
+    }
+    for (int i : arrival)
+        if (s.alive(i) && (rc = s.on_ready(i, C)) < 0) return rc;
+    return s.finish(info);
+}
+
+// Eq. 1 of section 3.4.2: T(1) = n L + S/B, T(d) = L log_d n + d S/B. The
+// paper's runtime restricts the choice to d in {1, 2, n} (section 4).
+inline double tree_cost(int n, double d, double S, double L, double B)
+{
+    if (d <= 1.0) return n * L + S / B;
+    return L * (std::log((double)n) / std::log(d)) + d * S / B;
+}
+
+}  // namespace hop

@@ -1,0 +1,311 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bit-exact everywhere: integers always, floats because the library evaluates
+the same tree order as the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2002_05814_amd as hop
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+ORA_OP = {"sum": oracle.SUM, "min": oracle.MIN, "max": oracle.MAX}
+ORA_DT = {"f32": oracle.F32, "bf16": oracle.BF16, "i32": oracle.I32}
+ES = workloads.ELEM_BYTES
+
+
+def dev():
+    assert torch.cuda.is_available()
+    return torch.device("cuda:0")
+
+
+def bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def run_both(w, op, objs=None, order="w", fm="w", check_info=True):
+    """One workload through hop_reduce and through the oracle; asserts equality; returns info."""
+    objs = workloads.make_objects(w, device=dev()) if objs is None else objs
+    order = w.ready_order() if isinstance(order, str) else order
+    fm = w.fail_mask() if isinstance(fm, str) else fm
+    dst = torch.full_like(objs[0], 77)
+    print("case", w.name, w.dtype, op, "bytes", w.object_bytes, "chunk", w.chunk_bytes, "k", w.k, "d", w.tree_degree,
+          flush=True)
+    rc, info = hop.hop_reduce(dst, objs, w.k, op, w.dtype, w.chunk_bytes, w.tree_degree, order, fm)
+    torch.cuda.synchronize()
+    d = info["degree_used"] if w.tree_degree == 0 else w.tree_degree
+    orc, want, k_eff, n_rep = oracle.reduce([workloads.to_numpy(o) for o in objs], w.k, ORA_OP[op], ORA_DT[w.dtype],
+                                            max(1, w.chunk_bytes // ES[w.dtype]), d, order, fm)
+    assert rc == orc, (rc, orc)
+    if rc >= 0:
+        got = workloads.to_numpy(dst)
+        assert np.array_equal(bits(got), bits(want)), "mismatch at %s" % np.flatnonzero(bits(got) != bits(want))[:8]
+        if check_info:
+            assert info["k_eff"] == k_eff and info["n_replaced"] == n_rep
+    return rc, info
+
+
+# ------------------------------------------------------------------ the five workloads, oracle-sized
+
+def test_cfg1_full_size():
+    rc, info = run_both(workloads.WORKLOADS[1], "sum")
+    assert rc == hop.HOP_OK and info["n_launches"] == 1
+
+
+def test_cfg2_scaled_ragged():
+    # 1 MiB + 12 bytes per object: many tiles, a ragged last chunk and a sub-vector tail
+    w = workloads.WORKLOADS[2].scaled((1 << 20) + 12, 64 << 10)
+    rc, info = run_both(w, "sum")
+    assert rc == hop.HOP_OK and info["k_eff"] == 12
+
+
+def test_cfg3_scaled_allreduce():
+    w = workloads.WORKLOADS[3].scaled(256 << 10, 16 << 10)
+    objs = workloads.make_objects(w, device=dev())
+    dsts = [torch.full_like(objs[0], -5) for _ in range(w.n_dst)]
+    rc, info = hop.hop_allreduce(dsts, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and info["k_eff"] == 64
+    orc, outs, _, _ = oracle.allreduce([workloads.to_numpy(o) for o in objs], w.n_dst, w.k, oracle.SUM, oracle.I32,
+                                       w.chunk_bytes // 4, info["degree_used"], w.ready_order(), None)
+    for got, want in zip(dsts, outs):
+        assert np.array_equal(workloads.to_numpy(got), want)
+
+
+def test_cfg4_scaled_failure():
+    # 32 bf16 objects of 1 MiB + 6 bytes, 33 chunks; participant 7 fails after its 10th chunk
+    w = workloads.WORKLOADS[4].scaled((1 << 20) + 6, 32 << 10)
+    rc, info = run_both(w, "sum")
+    assert rc == hop.HOP_PARTIAL and info["k_eff"] == 31 and info["n_launches"] == 2
+    assert info["chunks_redone"] == 10 * 31
+
+
+@pytest.mark.parametrize("op", ["max", "sum"])
+def test_cfg5_full_size(op):
+    rc, info = run_both(workloads.WORKLOADS[5], op)
+    assert rc == hop.HOP_OK and info["k_eff"] == 1000 and info["stack_depth"] == 4
+
+
+# ------------------------------------------------------------------ all dtypes x ops x shapes, with failures
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i32"])
+@pytest.mark.parametrize("op", ["sum", "min", "max"])
+def test_random_shapes_and_failures(dtype, op):
+    rng = np.random.default_rng(hash((dtype, op)) % 2 ** 32)
+    base = workloads.WORKLOADS[{"f32": 2, "bf16": 4, "i32": 3}[dtype]]
+    for it in range(12):
+        n = int(rng.integers(1, 40))
+        k = int(rng.integers(1, n + 1))
+        d = int(rng.choice([1, 2, 3, 4, 8, 16, n + 3]))
+        chunk = 16 * int(rng.integers(1, 300))
+        n_elems = int(rng.integers(1, 40000))
+        nbytes = n_elems * ES[dtype]
+        C = -(-nbytes // chunk)
+        w = base.scaled(nbytes, chunk, n=n, k=k, tree_degree=d, order_seed=int(rng.integers(1 << 30)),
+                        data_seed=int(rng.integers(1 << 30)), fail={}, name="rand%d" % it)
+        fm = None
+        if it % 3:
+            fm = np.full(n, -1, np.int64)
+            bad = rng.random(n) < 0.3
+            fm[bad] = rng.integers(0, C + 2, size=int(bad.sum()))
+        run_both(w, op, fm=fm)
+
+
+def test_denormals_and_signed_zeros_are_preserved():
+    w = workloads.WORKLOADS[1].scaled(4096 * 4, 1024, n=4, k=4)
+    rng = np.random.default_rng(5)
+    vals = []
+    for i in range(4):
+        v = (rng.standard_normal(4096) * 1e-41).astype(np.float32)      # denormal range
+        v[::7] = 0.0
+        v[3::7] = -0.0
+        vals.append(v)
+    objs = [workloads.from_numpy(v, "f32", dev()) for v in vals]
+    for op in ("sum", "min", "max"):
+        run_both(w, op, objs=objs)
+
+
+def test_bf16_every_pattern_rounds_like_the_oracle():
+    # object 0 holds every finite bf16 pattern; the others add values that land on ties and near-ties
+    h = np.arange(1 << 16, dtype=np.uint16)
+    f = (h.astype(np.uint32) << 16).view(np.float32)
+    h = h[np.isfinite(f)]
+    E = h.size
+    w = workloads.WORKLOADS[4].scaled(E * 2, 4096, n=3, k=3, tree_degree=2, fail={})
+    for addend in (2.0 ** -8, 2.0 ** -9, 3 * 2.0 ** -9, 1.0, -2.0 ** -8, 1e-3, 255.0):
+        a = torch.full((E,), addend, dtype=torch.float32).to(torch.bfloat16)
+        b = torch.full((E,), addend * 2.0 ** -8, dtype=torch.float32).to(torch.bfloat16)
+        objs = [workloads.from_numpy(h, "bf16", dev()), a.to(dev()), b.to(dev())]
+        run_both(w, "sum", objs=objs, order=None, fm=None)
+
+
+# ------------------------------------------------------------------ edges and errors
+
+def test_tiny_and_empty_objects():
+    for dtype in ("f32", "bf16", "i32"):
+        for n_elems in (0, 1, 2, 3, 4, 5, 7, 8, 9):
+            w = workloads.WORKLOADS[1].scaled(n_elems * ES[dtype], 16, n=5, k=3, dtype=dtype,
+                                              dist={"f32": "uniform_pm1", "bf16": "normal_std1",
+                                                    "i32": "randint_pm2p20"}[dtype])
+            if n_elems == 0:
+                objs = [torch.zeros(4, dtype=workloads.TORCH_DTYPE[dtype], device=dev()) for _ in range(5)]
+                dst = torch.full_like(objs[0], 9)
+                rc, info = hop.hop_reduce(dst, objs, 3, "sum", dtype, 16, 2, None, None, object_bytes=0)
+                torch.cuda.synchronize()
+                assert rc == hop.HOP_OK and info["k_eff"] == 3
+                assert torch.all(dst == 9)                  # nothing written
+            else:
+                run_both(w, "sum", order=None)
+
+
+def test_k1_and_n1():
+    w = workloads.WORKLOADS[1].scaled(4000, 1024, n=1, k=1)
+    run_both(w, "sum", order=None)
+    w = workloads.WORKLOADS[1].scaled(4000, 1024, n=6, k=1)
+    run_both(w, "max", order=np.array([4, 2, 0, 1, 3, 5], np.int32))
+
+
+def test_errors():
+    d = dev()
+    objs = [torch.zeros(1024, device=d) for _ in range(4)]
+    dst = torch.zeros(1024, device=d)
+    R = hop.hop_reduce
+    assert R(dst, objs, 5, "sum", "f32", 1024, 2)[0] == hop.HOP_ERR_INVALID
+    assert R(dst, objs, 2, "sum", "f32", 100, 2)[0] == hop.HOP_ERR_INVALID
+    assert R(dst, objs, 2, "sum", "f32", 1024, 2, ready_order=[0, 0, 1, 2])[0] == hop.HOP_ERR_INVALID
+    assert R(dst, objs, 2, "sum", "f32", 1024, 2, fail_mask=[0, 0, 0, 0])[0] == hop.HOP_ERR_NO_SURVIVOR
+    assert R(objs[1], objs, 2, "sum", "f32", 1024, 2)[0] == hop.HOP_ERR_INVALID          # result over a source
+    mis = [objs[0], objs[1][1:], objs[2], objs[3]]
+    assert R(dst, mis, 2, "sum", "f32", 1024, 2, object_bytes=4000)[0] == hop.HOP_ERR_ALIGN
+    assert R(dst[1:], objs, 2, "sum", "f32", 1024, 2, object_bytes=4000)[0] == hop.HOP_ERR_ALIGN
+    assert hop.hop_broadcast([dst[1:]], objs[0], 1024, object_bytes=4000) == hop.HOP_ERR_ALIGN
+    assert hop.hop_broadcast([dst], dst, 1024) == hop.HOP_ERR_INVALID
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ broadcast
+
+def test_broadcast_paper_object_and_ragged_sizes():
+    d = dev()
+    src = torch.tensor([5, 1, 0], dtype=torch.int32, device=d)            # the array of figure 4
+    buf = [torch.zeros(4, dtype=torch.int32, device=d) for _ in range(3)]
+    assert hop.hop_broadcast(buf, src, 16, object_bytes=12) == hop.HOP_OK
+    torch.cuda.synchronize()
+    for b in buf:
+        assert b.tolist() == [5, 1, 0, 0]
+    rng = np.random.default_rng(2)
+    for nbytes in (1, 15, 16, 17, 4095, 1 << 20, (1 << 20) + 5):
+        blob = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+        s = torch.from_numpy(blob).to(d)
+        outs = [torch.zeros(nbytes + 3, dtype=torch.uint8, device=d) for _ in range(5)]
+        assert hop.hop_broadcast(outs, s, 4096, object_bytes=nbytes) == hop.HOP_OK
+        torch.cuda.synchronize()
+        want = oracle.broadcast(blob, 5)
+        for o, wv in zip(outs, want):
+            assert np.array_equal(o[:nbytes].cpu().numpy(), wv) and int(o[nbytes:].sum()) == 0
+    assert hop.hop_broadcast([], src, 16) == hop.HOP_OK
+
+
+# ------------------------------------------------------------------ event-level sessions
+
+def session_replay(objs, dst, k, op, dtype, chunk, d, order, fm, C, fine):
+    """Drives the session API with the same timeline hop_reduce replays, either in bulk
+    (per failure step) or chunk by chunk."""
+    rc, s = hop.hop_session_begin(dst, objs, k, op, dtype, chunk, d)
+    assert rc == hop.HOP_OK
+    n = len(objs)
+    limit = [C if (fm is None or fm[i] < 0 or fm[i] >= C) else int(fm[i]) for i in range(n)]
+    arrival = [int(i) for i in order if limit[i] > 0]
+    for i in arrival:
+        assert hop.hop_session_ready(s, i, 0) == hop.HOP_OK
+    alive = set(arrival)
+    steps = range(1, C + 1) if fine else sorted({limit[i] for i in arrival if limit[i] < C} | {C})
+    prev = 0
+    for step in steps:
+        for i in arrival:
+            if i in alive and min(step, limit[i]) > min(prev, limit[i]):
+                assert hop.hop_session_ready(s, i, min(step, limit[i])) == hop.HOP_OK
+        for i in arrival:
+            if i in alive and limit[i] == step and step < C:
+                assert hop.hop_session_fail(s, i) == hop.HOP_OK
+                alive.discard(i)
+        prev = step
+    return hop.hop_session_finish(s)
+
+
+@pytest.mark.parametrize("fine", [False, True])
+def test_session_events_match_oracle(fine):
+    rng = np.random.default_rng(31 + fine)
+    for it in range(10):
+        n = int(rng.integers(2, 20))
+        k = int(rng.integers(1, n + 1))
+        d = int(rng.choice([1, 2, 4, n]))
+        chunk, C = 1024, int(rng.integers(1, 9))
+        n_elems = (C - 1) * 256 + int(rng.integers(1, 257))
+        order = rng.permutation(n).astype(np.int32)
+        fm = np.full(n, -1, np.int64)
+        bad = rng.random(n) < 0.3
+        fm[bad] = rng.integers(0, C + 1, size=int(bad.sum()))
+        vals = [rng.standard_normal(n_elems).astype(np.float32) for _ in range(n)]
+        objs = [workloads.from_numpy(v, "f32", dev()) for v in vals]
+        dst = torch.zeros(n_elems, device=dev())
+        print("session case", it, n, k, d, C, fine, flush=True)
+        rc, info = session_replay(objs, dst, k, "sum", "f32", chunk, d, order, fm, C, fine)
+        torch.cuda.synchronize()
+        orc, want, k_eff, n_rep = oracle.reduce(vals, k, oracle.SUM, oracle.F32, 256, d, order, fm)
+        assert rc == orc
+        if rc >= 0:
+            assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+            assert info["k_eff"] == k_eff
+            if fine and not bad.any() and C > 1:
+                assert info["n_launches"] == C          # one launch per chunk as each becomes complete
+
+
+def test_session_late_arrival_fills_the_hole_and_unfinished_objects_count_as_failed():
+    d = dev()
+    rng = np.random.default_rng(3)
+    vals = [rng.standard_normal(1024).astype(np.float32) for _ in range(4)]
+    objs = [workloads.from_numpy(v, "f32", d) for v in vals]
+    dst = torch.zeros(1024, device=d)
+    rc, s = hop.hop_session_begin(dst, objs, 3, "sum", "f32", 1024, 2)          # 4 chunks
+    for i in (0, 1, 2):
+        assert hop.hop_session_ready(s, i, 2) == hop.HOP_OK
+    assert hop.hop_session_fail(s, 1) == hop.HOP_OK                              # nobody is waiting: position 1 is empty
+    assert hop.hop_session_ready(s, 1, 3) == hop.HOP_ERR_INVALID                 # a failed object cannot come back under the same id
+    assert hop.hop_session_ready(s, 3, 4) == hop.HOP_OK                          # late arrival takes position 1
+    assert hop.hop_session_ready(s, 0, 4) == hop.HOP_OK
+    assert hop.hop_session_ready(s, 0, 3) == hop.HOP_ERR_INVALID                 # counts never decrease
+    assert hop.hop_session_ready(s, 2, 4) == hop.HOP_OK
+    rc, info = hop.hop_session_finish(s)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and info["k_eff"] == 3 and info["n_replaced"] == 1
+    _, want, _, _ = oracle.reduce(vals, 3, oracle.SUM, oracle.F32, 256, 2, np.array([0, 3, 2, 1], np.int32), None)
+    assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+    # object 2 never finishes: at the end it counts as failed
+    rc, s = hop.hop_session_begin(dst, objs, 3, "sum", "f32", 1024, 2)
+    for i, c in ((0, 4), (1, 4), (2, 1)):
+        assert hop.hop_session_ready(s, i, c) == hop.HOP_OK
+    rc, info = hop.hop_session_finish(s)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_PARTIAL and info["k_eff"] == 2
+    fm = np.array([-1, -1, 1, 0], np.int64)
+    _, want, _, _ = oracle.reduce(vals, 3, oracle.SUM, oracle.F32, 256, 2, None, fm)
+    assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+
+
+def test_other_stream():
+    d = dev()
+    w = workloads.WORKLOADS[1]
+    objs = workloads.make_objects(w, device=d)
+    dst = torch.zeros_like(objs[0])
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    rc, info = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, None, None, stream=st)
+    st.synchronize()
+    _, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], w.k, oracle.SUM, oracle.F32,
+                                  w.chunk_bytes // 4, w.tree_degree, None, None)
+    assert rc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(want))

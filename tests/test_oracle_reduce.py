@@ -62,6 +62,20 @@ def test_node_combines_first_child_then_self_then_other_children():
     assert run(f32(1.0, 1.0, TWO24, 1.0), d=3)[0] == TWO24 + 4
 
 
+def test_min_max_keep_the_earlier_term_on_ties():
+    # the comparison forms keep the left operand unless the right one is strictly better, and a node
+    # combines [first child, itself, second child] left to right: with -0.0 and +0.0 (equal under
+    # comparison) the sign of the result names the term that came first
+    neg0, pos0 = np.float32(-0.0), np.float32(0.0)
+    for op in (MAX, MIN):
+        got = run([np.array([neg0]), np.array([pos0]), np.array([pos0])], op=op, d=2)
+        assert np.signbit(got[0])                  # first child (-0.0) came first
+        got = run([np.array([pos0]), np.array([neg0]), np.array([neg0])], op=op, d=2)
+        assert not np.signbit(got[0])
+        got = run([np.array([pos0]), np.array([neg0])], op=op, d=1)
+        assert not np.signbit(got[0])
+
+
 def test_ready_order_decides_position_not_object_index():
     objs = f32(1.0, TWO24, 1.0)          # object 1 is the big one
     # arrival order 0,2,1 -> (1+1)+2^24

@@ -1,0 +1,215 @@
+"""Host-side checks of the library (no GPU): it loads, exports its ABI, and its
+scheduler + accumulator programs reproduce the oracle when interpreted in numpy."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2002_05814_amd as hop
+import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+NP_OP = {
+    "sum": lambda a, b: a + b,
+    "min": lambda a, b: np.where(b < a, b, a),
+    "max": lambda a, b: np.where(b > a, b, a),
+}
+ORA_OP = {"sum": oracle.SUM, "min": oracle.MIN, "max": oracle.MAX}
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "hop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(hop_[a-z_]+)\s*\(", text))
+    assert declared == set(hop.EXPORTS), declared ^ set(hop.EXPORTS)
+    L = hop.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert hop.hop_strerror(0) == "ok" and "align" in hop.hop_strerror(hop.HOP_ERR_ALIGN)
+    assert hop.hop_workspace_bytes(16, 12, 0) >= 12 * 16
+
+
+def test_info_struct_layout_matches_header():
+    # int32 x4, int64, int32 x2 -> 32 bytes with natural alignment
+    assert ctypes.sizeof(hop.HopInfo) == 32
+    assert hop.HopInfo.chunks_redone.offset == 16
+    assert ctypes.sizeof(hop.PlanEntry) == 8 and ctypes.sizeof(hop.PlanLaunch) == 24
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 8, 16, 1 << 20])
+def test_slots_match_oracle(d):
+    for k in list(range(1, 70)) + [1000, 4097]:
+        rc, got = hop.hop_plan_slots(k, d)
+        want, _ = oracle.tree_slots(k, d)
+        assert rc == hop.HOP_OK and np.array_equal(got, want), (k, d)
+
+
+def interpret(objs, launches, entries, n_elems, chunk_elems, op):
+    """Apply the recorded launches in order, exactly as the header describes them."""
+    f = NP_OP[op]
+    dst = np.zeros(n_elems, objs[0].dtype)
+    for c0, c1, e0, e1 in launches:
+        seg = slice(c0 * chunk_elems, min(c1 * chunk_elems, n_elems))
+        acc = {}
+        for obj, level, is_set, n_fold in entries[e0:e1]:
+            x = objs[obj][seg]
+            acc[level] = x.copy() if is_set else f(acc[level], x).astype(x.dtype)
+            for _ in range(n_fold):
+                acc[level - 1] = f(acc[level - 1], acc[level]).astype(x.dtype)
+                del acc[level]
+                level -= 1
+        assert list(acc) == [0]
+        dst[seg] = acc[0]
+    return dst
+
+
+def random_case(rng, max_n=14, with_fail=True):
+    n = int(rng.integers(1, max_n + 1))
+    k = int(rng.integers(1, n + 1))
+    d = int(rng.choice([1, 2, 3, 4, 8, n + 5]))
+    chunk_elems = 4 * int(rng.integers(1, 5))
+    n_elems = int(rng.integers(1, 6 * chunk_elems))
+    C = -(-n_elems // chunk_elems)
+    order = rng.permutation(n).astype(np.int32)
+    fm = None
+    if with_fail and rng.random() < 0.7:
+        fm = np.full(n, -1, np.int64)
+        bad = rng.random(n) < 0.35
+        fm[bad] = rng.integers(0, C + 2, size=int(bad.sum()))
+    return n, k, d, chunk_elems, n_elems, order, fm
+
+
+@pytest.mark.parametrize("op", ["sum", "max", "min"])
+def test_interpreted_plan_equals_oracle_f32(op):
+    rng = np.random.default_rng({"sum": 1, "max": 2, "min": 3}[op])
+    for _ in range(300):
+        n, k, d, ce, E, order, fm = random_case(rng)
+        objs = [(rng.standard_normal(E) * 10.0 ** rng.integers(-3, 4)).astype(np.float32) for _ in range(n)]
+        rc, info, launches, entries = hop.hop_plan_reduce(n, E * 4, k, "f32", ce * 4, d, order, fm)
+        orc, want, k_eff, n_rep = oracle.reduce(objs, k, ORA_OP[op], oracle.F32, ce, d, order, fm)
+        assert rc == orc, (rc, orc)
+        if rc < 0:
+            assert rc == hop.HOP_ERR_NO_SURVIVOR
+            continue
+        assert info["k_eff"] == k_eff and info["n_replaced"] == n_rep and info["degree_used"] == d
+        got = interpret(objs, launches, entries, E, ce, op)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        # every object in the final program exactly once; k_eff of them
+        final = entries[launches[-1][2]:launches[-1][3]]
+        assert len(final) == k_eff and len({e[0] for e in final}) == k_eff
+        assert max(e[1] for e in final) + 1 <= info["stack_depth"] <= hop.HOP_MAX_DEPTH
+
+
+def test_interpreted_plan_equals_oracle_i32_wrapping():
+    rng = np.random.default_rng(4)
+    for _ in range(100):
+        n, k, d, ce, E, order, fm = random_case(rng)
+        objs = [rng.integers(-2 ** 31, 2 ** 31, size=E, dtype=np.int64).astype(np.int32) for _ in range(n)]
+        rc, info, launches, entries = hop.hop_plan_reduce(n, E * 4, k, "i32", ce * 4, d, order, fm)
+        orc, want, _, _ = oracle.reduce(objs, k, oracle.SUM, oracle.I32, ce, d, order, fm)
+        assert rc == orc
+        if rc < 0:
+            continue
+        with np.errstate(over="ignore"):
+            got = interpret([o.view(np.uint32) for o in objs], launches, entries, E, ce, "sum")
+        assert np.array_equal(got.view(np.int32), want)
+
+
+def test_failure_free_call_is_one_launch_over_all_chunks():
+    for cfg in (1, 2, 3, 5):
+        w = workloads.WORKLOADS[cfg]
+        rc, info, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
+                                                          w.tree_degree, w.ready_order(), w.fail_mask())
+        assert rc == hop.HOP_OK and info["k_eff"] == w.k and info["chunks_redone"] == 0
+        assert launches == [(0, w.n_chunks, 0, w.k)] and info["n_launches"] == 1
+        # only the first k arrivals are ever read
+        assert sorted(e[0] for e in entries) == sorted(w.ready_order()[:w.k].tolist())
+    # survey's stack depths: 3, 3, 4 for configs 1, 2, 5; config 3 picks a degree from {1, 2, k}
+    depths = {}
+    for cfg in (1, 2, 3, 5):
+        w = workloads.WORKLOADS[cfg]
+        _, info, _, _ = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
+                                            w.ready_order(), None)
+        depths[cfg] = (info["stack_depth"], info["degree_used"])
+    assert depths[1] == (3, 2) and depths[2] == (3, 4) and depths[5] == (4, 16)
+    assert depths[3][1] in (1, 2, 64)
+
+
+def test_mid_stream_failure_redoes_only_the_chunks_already_produced():
+    w = workloads.WORKLOADS[4]          # participant 7 fails after its 10th chunk of 32
+    rc, info, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
+                                                      w.tree_degree, w.ready_order(), w.fail_mask())
+    assert rc == hop.HOP_PARTIAL and info["k_eff"] == 31 and info["n_failed_seen"] == 1
+    assert info["n_replaced"] == 0 and info["stack_depth"] == 3
+    # chunks 0..9 were produced with all 32 participants, then everything is produced without #7
+    assert [(l[0], l[1]) for l in launches] == [(0, 10), (0, 32)]
+    first = entries[launches[0][2]:launches[0][3]]
+    second = entries[launches[1][2]:launches[1][3]]
+    assert len(first) == 32 and 7 in {e[0] for e in first}
+    assert len(second) == 31 and 7 not in {e[0] for e in second}
+    assert info["chunks_redone"] == 10 * 31 and info["n_launches"] == 2
+    # the survivors keep their relative order
+    assert [e[0] for e in second] == [e[0] for e in first if e[0] != 7]
+    # the failure time changes the repair work, never the final program
+    for c in (1, 5, 31):
+        fm = w.fail_mask().copy()
+        fm[7] = c
+        _, info_c, launches_c, entries_c = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
+                                                               w.tree_degree, w.ready_order(), fm)
+        assert [(l[0], l[1]) for l in launches_c] == [(0, c), (0, 32)]
+        assert entries_c[launches_c[1][2]:launches_c[1][3]] == second
+        assert info_c["chunks_redone"] == c * 31
+
+
+def test_replacement_from_waiting_objects():
+    # 6 of 10, second arrival fails after 3 chunks of 8: the 7th arrival takes its place
+    n, k, C = 10, 6, 8
+    fm = np.full(n, -1, np.int64)
+    fm[1] = 3
+    rc, info, launches, entries = hop.hop_plan_reduce(n, C * 64, k, "f32", 64, 2, None, fm)
+    assert rc == hop.HOP_OK and info["n_replaced"] == 1 and info["k_eff"] == 6
+    final = entries[launches[-1][2]:launches[-1][3]]
+    assert [e[0] for e in final] == [0, 6, 2, 3, 4, 5]
+    assert [(l[0], l[1]) for l in launches] == [(0, 3), (0, 8)]
+
+
+def test_pick_degree_is_argmin_of_eq1_over_1_2_n():
+    def T(n, d, S, L, B):
+        return n * L + S / B if d == 1 else L * math.log(n) / math.log(d) + d * S / B
+    rng = np.random.default_rng(8)
+    for _ in range(300):
+        n = int(rng.integers(3, 200))
+        S = int(10 ** rng.uniform(2, 10))
+        L = 10 ** rng.uniform(-7, -2)
+        B = 10 ** rng.uniform(8, 13)
+        got = hop.hop_pick_degree(n, S, L, B)
+        costs = {d: T(n, d, S, L, B) for d in (1, 2, n)}
+        assert got in costs and costs[got] <= min(costs.values()) * (1 + 1e-12)
+    # the qualitative rule of the paper's appendix B on its own testbed (10 Gbps, ~0.2 ms hops):
+    # small objects -> d = n, large objects -> d = 1
+    assert hop.hop_pick_degree(16, 1 << 10, 2e-4, 1.25e9) == 16
+    assert hop.hop_pick_degree(16, 1 << 30, 2e-4, 1.25e9) == 1
+
+
+def test_argument_errors_without_a_device():
+    P = hop.hop_plan_reduce
+    assert P(0, 64, 1, "f32", 16, 2)[0] == hop.HOP_ERR_INVALID
+    assert P(4, 64, 5, "f32", 16, 2)[0] == hop.HOP_ERR_INVALID
+    assert P(4, 64, 0, "f32", 16, 2)[0] == hop.HOP_ERR_INVALID
+    assert P(4, 64, 2, "f32", 0, 2)[0] == hop.HOP_ERR_INVALID
+    assert P(4, 64, 2, "f32", 24, 2)[0] == hop.HOP_ERR_INVALID          # chunk not a multiple of 16
+    assert P(4, 66, 2, "f32", 16, 2)[0] == hop.HOP_ERR_INVALID          # not a whole number of elements
+    assert P(4, 66, 2, "bf16", 16, 2)[0] == hop.HOP_OK
+    assert P(4, 64, 2, "f32", 16, -1)[0] == hop.HOP_ERR_INVALID
+    assert P(4, 64, 2, 7, 16, 2)[0] == hop.HOP_ERR_INVALID
+    assert P(4, 64, 2, "f32", 16, 2, ready_order=[0, 1, 1, 2])[0] == hop.HOP_ERR_INVALID
+    assert P(4, 64, 2, "f32", 16, 2, fail_mask=[0, 0, 0, 0])[0] == hop.HOP_ERR_NO_SURVIVOR
+    # a binary tree too deep for the register file of accumulators
+    rc, info, _, _ = P(1 << 17, 64, 1 << 17, "f32", 16, 2)
+    assert rc == hop.HOP_ERR_DEPTH
+    rc, info, _, _ = P(1 << 17, 64, 1 << 17, "f32", 16, 1)
+    assert rc == hop.HOP_OK and info["stack_depth"] == 1
