@@ -101,20 +101,6 @@ private:
     size_t used_ = 0;
 };
 
-static int cu_count(int device)
-{
-    static std::mutex mu;
-    static std::vector<int> cache;
-    std::lock_guard<std::mutex> lk(mu);
-    if ((int)cache.size() <= device) cache.resize(device + 1, 0);
-    if (cache[device] == 0) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || v <= 0) v = 256;
-        cache[device] = v;
-    }
-    return cache[device];
-}
-
 // ----------------------------------------------------------------------------
 // back ends
 // ----------------------------------------------------------------------------
@@ -131,7 +117,7 @@ public:
     GpuBackend(int device, hipStream_t stream, const void *const *objs, int n, std::vector<void *> dsts,
                const Shape &shape, int op, int dtype)
         : ws_(device, stream), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
-          op_(op), dtype_(dtype), n_cu_(cu_count(device)) {}
+          op_(op), dtype_(dtype) {}
 
     int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) override
     {
@@ -145,8 +131,11 @@ public:
                 staging_[i].reserved = 0;
                 depth_ = std::max(depth_, (int)prog[i].level + 1);
             }
-            dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
-            if (!dev_prog_) return HOP_ERR_NOMEM;
+            dev_prog_ = nullptr;
+            if ((int)staging_.size() > kInlineEntries) {      // short programs ride in the kernel arguments
+                dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
+                if (!dev_prog_) return HOP_ERR_NOMEM;
+            }
             dev_version_ = version;
         }
         if (dsts_.size() > 1 && !dev_extra_) {
@@ -154,12 +143,10 @@ public:
             if (!dev_extra_) return HOP_ERR_NOMEM;
         }
         const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
-        // the finished chunks go to the first destination; the broadcast copy then
-        // carries the same chunks to the others (reduce followed by broadcast, chunk by chunk)
-        hipError_t e = launch_reduce(stream_, dtype_, op_, depth_, dev_prog_, (int)prog.size(), dsts_[0],
-                                     nullptr, 0, b0, b1, n_cu_);
-        if (e == hipSuccess && dsts_.size() > 1)
-            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, n_cu_);
+        // Reduce followed by broadcast, composed at the finest grain: every reduced 16-byte
+        // vector goes from registers to all destinations, so the result is never read back.
+        hipError_t e = launch_reduce(stream_, dtype_, op_, depth_, staging_.data(), dev_prog_, (int)prog.size(),
+                                     dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1);
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     }
 
@@ -169,7 +156,7 @@ private:
     std::vector<const void *> objs_;
     std::vector<void *> dsts_;
     Shape shape_;
-    int op_, dtype_, n_cu_;
+    int op_, dtype_;
     std::vector<DevEntry> staging_;
     const DevEntry *dev_prog_ = nullptr;
     void *const *dev_extra_ = nullptr;
@@ -342,7 +329,7 @@ int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_b
         void *const *table = (void *const *)ws.stage(dsts, (size_t)n_dst * sizeof(void *));
         if (!table) return HOP_ERR_NOMEM;
         // The whole source is present, so every chunk is ready at once: one launch covers them all.
-        hipError_t e = launch_copy((hipStream_t)stream, src, table, n_dst, 0, object_bytes, cu_count(device));
+        hipError_t e = launch_copy((hipStream_t)stream, src, table, n_dst, 0, object_bytes);
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;

@@ -1,0 +1,290 @@
+// Device code of the gfx950 reduce and copy kernels (templates), shared by the
+// library's launchers. See hop_kernels.hip for what the kernels are for.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hop_kernels.h"
+
+namespace hop {
+
+// ----------------------------------------------------------------------------
+// element types
+// ----------------------------------------------------------------------------
+
+template <int DT> struct Traits;
+template <> struct Traits<HOP_F32>  { using acc_t = float;   static constexpr int W = 4; static constexpr int ES = 4; };
+template <> struct Traits<HOP_BF16> { using acc_t = float;   static constexpr int W = 8; static constexpr int ES = 2; };
+template <> struct Traits<HOP_I32>  { using acc_t = int32_t; static constexpr int W = 4; static constexpr int ES = 4; };
+
+__device__ __forceinline__ float bits_to_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t f32_to_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// binary32 -> bfloat16 bits, round to nearest, ties to even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = f32_to_bits(f);
+    uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    uint32_t nan = (u >> 16) | 0x0040u;
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? nan : rounded;
+}
+
+template <int OP> __device__ __forceinline__ float combine(float a, float b)
+{
+    if (OP == HOP_SUM) return a + b;
+    if (OP == HOP_MIN) return (b < a) ? b : a;
+    return (b > a) ? b : a;
+}
+template <int OP> __device__ __forceinline__ int32_t combine(int32_t a, int32_t b)
+{
+    if (OP == HOP_SUM) return (int32_t)((uint32_t)a + (uint32_t)b);   // wraps mod 2^32
+    if (OP == HOP_MIN) return (b < a) ? b : a;
+    return (b > a) ? b : a;
+}
+
+// 16 raw bytes <-> W accumulator-typed values
+template <int DT> __device__ __forceinline__ void decode(const uint4 &r, typename Traits<DT>::acc_t *x);
+template <> __device__ __forceinline__ void decode<HOP_F32>(const uint4 &r, float *x)
+{
+    x[0] = bits_to_f32(r.x); x[1] = bits_to_f32(r.y); x[2] = bits_to_f32(r.z); x[3] = bits_to_f32(r.w);
+}
+template <> __device__ __forceinline__ void decode<HOP_I32>(const uint4 &r, int32_t *x)
+{
+    x[0] = (int32_t)r.x; x[1] = (int32_t)r.y; x[2] = (int32_t)r.z; x[3] = (int32_t)r.w;
+}
+template <> __device__ __forceinline__ void decode<HOP_BF16>(const uint4 &r, float *x)
+{
+    // element 2i is the low half of word i (little endian); widening is exact
+    x[0] = bits_to_f32(r.x << 16); x[1] = bits_to_f32(r.x & 0xffff0000u);
+    x[2] = bits_to_f32(r.y << 16); x[3] = bits_to_f32(r.y & 0xffff0000u);
+    x[4] = bits_to_f32(r.z << 16); x[5] = bits_to_f32(r.z & 0xffff0000u);
+    x[6] = bits_to_f32(r.w << 16); x[7] = bits_to_f32(r.w & 0xffff0000u);
+}
+
+template <int DT> __device__ __forceinline__ uint4 encode(const typename Traits<DT>::acc_t *x);
+template <> __device__ __forceinline__ uint4 encode<HOP_F32>(const float *x)
+{
+    return make_uint4(f32_to_bits(x[0]), f32_to_bits(x[1]), f32_to_bits(x[2]), f32_to_bits(x[3]));
+}
+template <> __device__ __forceinline__ uint4 encode<HOP_I32>(const int32_t *x)
+{
+    return make_uint4((uint32_t)x[0], (uint32_t)x[1], (uint32_t)x[2], (uint32_t)x[3]);
+}
+template <> __device__ __forceinline__ uint4 encode<HOP_BF16>(const float *x)
+{
+    return make_uint4(f32_to_bf16_bits(x[0]) | (f32_to_bf16_bits(x[1]) << 16),
+                      f32_to_bf16_bits(x[2]) | (f32_to_bf16_bits(x[3]) << 16),
+                      f32_to_bf16_bits(x[4]) | (f32_to_bf16_bits(x[5]) << 16),
+                      f32_to_bf16_bits(x[6]) | (f32_to_bf16_bits(x[7]) << 16));
+}
+
+// one element (the ragged tail of an object whose size is not a multiple of 16 bytes)
+template <int DT> __device__ __forceinline__ typename Traits<DT>::acc_t load_elem(const void *p, size_t byte_off);
+template <> __device__ __forceinline__ float load_elem<HOP_F32>(const void *p, size_t o) { return *(const float *)((const char *)p + o); }
+template <> __device__ __forceinline__ int32_t load_elem<HOP_I32>(const void *p, size_t o) { return *(const int32_t *)((const char *)p + o); }
+template <> __device__ __forceinline__ float load_elem<HOP_BF16>(const void *p, size_t o)
+{
+    return bits_to_f32((uint32_t)(*(const uint16_t *)((const char *)p + o)) << 16);
+}
+template <int DT> __device__ __forceinline__ void store_elem(void *p, size_t byte_off, typename Traits<DT>::acc_t v);
+template <> __device__ __forceinline__ void store_elem<HOP_F32>(void *p, size_t o, float v) { *(float *)((char *)p + o) = v; }
+template <> __device__ __forceinline__ void store_elem<HOP_I32>(void *p, size_t o, int32_t v) { *(int32_t *)((char *)p + o) = v; }
+template <> __device__ __forceinline__ void store_elem<HOP_BF16>(void *p, size_t o, float v)
+{
+    *(uint16_t *)((char *)p + o) = (uint16_t)f32_to_bf16_bits(v);
+}
+
+// ----------------------------------------------------------------------------
+// the accumulator machine: D partial results of W values each, all in VGPRs.
+// Program steps are wave-uniform (scalar loads, scalar branches); every index
+// into acc[][] is a compile-time constant after unrolling.
+// ----------------------------------------------------------------------------
+
+template <int DT, int OP, int D, int W>
+struct Machine {
+    using A = typename Traits<DT>::acc_t;
+    A acc[D][W];
+
+    __device__ __forceinline__ void step(uint32_t ctl, const A (&x)[W])
+    {
+        uint32_t level = ctl & 0xffu;
+        const bool set = (ctl >> 8) & 1u;
+        uint32_t n_fold = ctl >> 16;
+#pragma unroll
+        for (int L = 0; L < D; ++L) {
+            if (level == (uint32_t)L) {
+                if (set) {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[L][w] = x[w];
+                } else {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[L][w] = combine<OP>(acc[L][w], x[w]);
+                }
+            }
+        }
+        while (n_fold) {
+#pragma unroll
+            for (int L = 1; L < D; ++L) {
+                if (level == (uint32_t)L) {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[L - 1][w] = combine<OP>(acc[L - 1][w], acc[L][w]);
+                }
+            }
+            --level;
+            --n_fold;
+        }
+    }
+};
+
+// All object traffic is streamed exactly once, so loads and stores carry the
+// non-temporal hint: lines are not kept in L2 / the memory-side cache, which
+// measurably raises sustained HBM bandwidth for this access pattern.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 ld16(const void *base, size_t byte_off)
+{
+    const u32x4 r = __builtin_nontemporal_load((const u32x4 *)((const char *)base + byte_off));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ void st16(void *base, size_t byte_off, const uint4 &v)
+{
+    const u32x4 r = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(r, (u32x4 *)((char *)base + byte_off));
+}
+
+// The program is read through the constant address space: it is never written
+// while a kernel runs, so its steps can be fetched with scalar loads and held
+// in SGPRs (a plain global pointer would make the compiler assume that the
+// result stores may change it, and fall back to per-lane loads).
+typedef const DevEntry __attribute__((address_space(4))) *prog_ptr;
+// Destination tables are read the same way.
+typedef void *const __attribute__((address_space(4))) *table_ptr;
+
+// One workgroup of THREADS lanes walks tiles of THREADS*VPT consecutive
+// 16-byte vectors (lane l owns vectors l, l+THREADS, ...: every load
+// instruction of a wave covers 1 KiB of consecutive addresses). For each tile
+// the program is run in groups of U steps: the U*VPT loads of a group are all
+// issued before the first of them is consumed, then the group's values are
+// folded in program order. D = accumulator levels held in registers.
+template <int DT, int OP, int D, int VPT, int U, int THREADS, class Prog>
+__device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog)
+{
+    using T = Traits<DT>;
+    using A = typename T::acc_t;
+    constexpr int W = T::W;
+    const table_ptr extra = (table_ptr)(uintptr_t)a.extra_dsts;
+    const int n = a.n_entries;
+    constexpr size_t kTile = (size_t)THREADS * VPT;
+    const size_t n_tiles = (a.n_vec + kTile - 1) / kTile;
+
+    for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        // lanes past the end of the range re-read the last vector (always inside the
+        // range) and skip the store, so control flow stays uniform across the wave
+        size_t off[VPT];
+        bool live[VPT];
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            const size_t v = tile * kTile + (size_t)j * THREADS + threadIdx.x;
+            live[j] = v < a.n_vec;
+            off[j] = a.byte_begin + (live[j] ? v : a.n_vec - 1) * 16;
+        }
+        Machine<DT, OP, D, VPT * W> m;
+        int t = 0;
+        for (; t + U <= n; t += U) {
+            uint4 raw[U][VPT];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const void *src = prog[t + u].src;
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) raw[u][j] = ld16(src, off[j]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                A x[VPT * W];
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
+                m.step(prog[t + u].ctl, x);
+            }
+        }
+        for (; t < n; ++t) {
+            const void *src = prog[t].src;
+            A x[VPT * W];
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {
+                const uint4 raw = ld16(src, off[j]);
+                decode<DT>(raw, &x[j * W]);
+            }
+            m.step(prog[t].ctl, x);
+        }
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            const uint4 out = encode<DT>(&m.acc[0][j * W]);
+            if (live[j]) {
+                st16(a.dst, off[j], out);
+                for (int e = 0; e < a.n_extra; ++e) st16(extra[e], off[j], out);
+            }
+        }
+    }
+
+    // ragged tail: fewer than 16 bytes at the very end of the object
+    if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail) {
+        const size_t off = a.byte_begin + a.n_vec * 16 + (size_t)threadIdx.x * T::ES;
+        Machine<DT, OP, D, 1> m;
+        for (int t = 0; t < n; ++t) {
+            A x[1] = {load_elem<DT>(prog[t].src, off)};
+            m.step(prog[t].ctl, x);
+        }
+        store_elem<DT>(a.dst, off, m.acc[0][0]);
+        for (int e = 0; e < a.n_extra; ++e) store_elem<DT>(extra[e], off, m.acc[0][0]);
+    }
+}
+
+// Program in device memory.
+template <int DT, int OP, int D, int VPT, int U, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
+{
+    reduce_body<DT, OP, D, VPT, U, THREADS>(a, (prog_ptr)(uintptr_t)a.prog);
+}
+
+// Program inside the kernel arguments.
+template <int DT, int OP, int D, int VPT, int U, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel_inline(ReduceArgsInline a)
+{
+    reduce_body<DT, OP, D, VPT, U, THREADS>(a.base, &a.steps[0]);
+}
+
+// One source, n_dst destinations: each 16-byte vector is read once and
+// written n_dst times. VPT vectors per lane are in flight together.
+template <int VPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
+{
+    constexpr size_t kTile = (size_t)THREADS * VPT;
+    const size_t n_tiles = (a.n_vec + kTile - 1) / kTile;
+    const table_ptr dsts = (table_ptr)(uintptr_t)a.dsts;
+    for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        uint4 x[VPT];
+        size_t off[VPT];
+        bool live[VPT];
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            const size_t v = tile * kTile + (size_t)j * THREADS + threadIdx.x;
+            live[j] = v < a.n_vec;
+            off[j] = a.byte_begin + (live[j] ? v : a.n_vec - 1) * 16;
+            x[j] = ld16(a.src, off[j]);
+        }
+        for (int d = 0; d < a.n_dst; ++d) {
+            void *dst = dsts[d];
+#pragma unroll
+            for (int j = 0; j < VPT; ++j)
+                if (live[j]) st16(dst, off[j], x[j]);
+        }
+    }
+    if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail_bytes) {
+        const size_t off = a.byte_begin + a.n_vec * 16 + threadIdx.x;
+        const unsigned char b = *((const unsigned char *)a.src + off);
+        for (int d = 0; d < a.n_dst; ++d) *((unsigned char *)dsts[d] + off) = b;
+    }
+}
+
+}  // namespace hop

@@ -20,8 +20,13 @@ struct DevEntry {
 };
 static_assert(sizeof(DevEntry) == 16, "program steps are 16 bytes");
 
+// Programs of at most this many steps travel inside the kernel arguments
+// (no separate host-to-device copy, steps read straight from the argument
+// segment); longer ones are staged in device memory.
+constexpr int kInlineEntries = 32;
+
 struct ReduceArgs {
-    const DevEntry *prog;      // device memory, n_entries steps
+    const DevEntry *prog;      // device memory, n_entries steps (unused by the inline variant)
     int n_entries;
     void *dst;                 // result
     void *const *extra_dsts;   // device table of n_extra further destinations (allreduce), or null
@@ -29,6 +34,11 @@ struct ReduceArgs {
     size_t byte_begin;         // first byte of the object range this launch covers
     size_t n_vec;              // full 16-byte vectors in the range
     int n_tail;                // elements after the last full vector (object end only)
+};
+
+struct ReduceArgsInline {
+    ReduceArgs base;
+    DevEntry steps[kInlineEntries];
 };
 
 struct CopyArgs {
@@ -40,21 +50,21 @@ struct CopyArgs {
     int n_tail_bytes;
 };
 
-// Workgroups per compute unit for the grid-stride loops.
-constexpr int kReduceBlocksPerCu = 8;
-constexpr int kCopyBlocksPerCu = 8;
-
 int elem_bytes(int dtype);
 
 // Reduce the byte range [byte_begin, byte_end) of the objects named by the
-// program into dst (and the extra destinations). depth = accumulator levels
-// the program uses (1..HOP_MAX_DEPTH). All pointers are device pointers.
-hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *prog,
-                         int n_entries, void *dst, void *const *extra_dsts, int n_extra,
-                         size_t byte_begin, size_t byte_end, int n_cu);
+// program into dst (and the n_extra further destinations of the device table
+// extra_dsts). depth = accumulator levels the program uses
+// (1..HOP_MAX_DEPTH). host_steps = the n_entries steps in host memory; when
+// there are more than kInlineEntries of them, dev_prog must hold the same
+// steps in device memory. Every other pointer is a device pointer.
+hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
+                         const DevEntry *dev_prog, int n_entries, void *dst, void *const *extra_dsts,
+                         int n_extra, size_t byte_begin, size_t byte_end);
 
-// Copy [byte_begin, byte_end) of src into the same range of every destination.
+// Copy [byte_begin, byte_end) of src into the same range of every destination
+// of the device table dsts.
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
-                       size_t byte_begin, size_t byte_end, int n_cu);
+                       size_t byte_begin, size_t byte_end);
 
 }  // namespace hop
