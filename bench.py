@@ -19,6 +19,18 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B/s)
 
+# HBM bytes moved by ONE reduce launch of workload 2, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE), each scaled by what the same counter read for the 256 MiB copy probe of this file
+# (profiles/reduce_kernel_cfg2_async_sgd.md). Valid only for the kernel launch shape named here: if the
+# library reports another one, the figure is withheld (null).
+MEASURED_TRAFFIC = {
+    "workload": "cfg2_async_sgd",
+    "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile "
+                     "per workgroup, nontemporal loads+stores, programs <= 32 steps in kernel arguments; "
+                     "copy: 64 lanes/workgroup, 4 vectors/lane, nontemporal",
+    "bytes": 872458034,
+}
+
 
 def time_calls(fn, steps, warmup, torch):
     """Average device time per call in ms, bracketed by events on the current stream."""
@@ -61,6 +73,9 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="which of the five workloads (default: 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true", help="also time the other workloads (extra JSON field)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run hop_broadcast of one 256 MiB object to one destination a few times: a copy of "
+                         "known size against which hardware byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one node's share of the reduce on ONE GPU; --gpus %d is not supported "
@@ -131,7 +146,10 @@ def main():
                    "counted_bytes": r["bytes"], "launches_per_step": r["info"]["n_launches"],
                    "host_ms_per_step": round(r["wall_ms"], 5)},
         "roofline": {"bound": "hbm", "achieved": round(r["gbs"], 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(r["gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
+                     "traffic": (MEASURED_TRAFFIC["bytes"]
+                                 if (w.name == MEASURED_TRAFFIC["workload"]
+                                     and hop.hop_kernel_config() == MEASURED_TRAFFIC["kernel_config"]) else None),
                      "kernel": "hop::reduce_kernel", "per_unit": "(k_eff+1) x object_bytes per launch"},
     }
     if not args.no_cpu_baseline and w.dtype == "f32" and not w.n_dst:
@@ -142,6 +160,17 @@ def main():
         out["cpu_baseline"] = base
     else:
         out["cpu_baseline"] = None
+    if args.copy_probe:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+        dstp = torch.empty_like(src)
+
+        def probe():
+            assert hop.hop_broadcast([dstp], src, 4 << 20) == hop.HOP_OK
+        ms, _ = time_calls(probe, 10, 2, torch)
+        out["copy_probe"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "ms": round(ms, 5),
+                             "GB/s_read_plus_write": round(2 * src.numel() * 4 / (ms * 1e-3) / 1e9, 2),
+                             "kernel": "hop::copy_kernel"}
+        del src, dstp
     if args.all_configs:
         extra = {}
         del objs, dsts

@@ -220,6 +220,11 @@ int hop_shutdown(void);
 
 const char *hop_strerror(int status);
 
+/* Static string naming the launch shape the kernels were built with (vectors
+ * per lane, unroll, workgroup size, cache policy). Measurements taken with
+ * hardware counters are only valid for the shape they were taken on. */
+const char *hop_kernel_config(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
 
 EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_session_begin", "hop_session_ready",
            "hop_session_fail", "hop_session_finish", "hop_plan_reduce", "hop_plan_slots",
-           "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror"]
+           "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
 
 
 class HopInfo(ctypes.Structure):
@@ -88,8 +88,10 @@ def lib() -> ctypes.CDLL:
         L.hop_shutdown.argtypes = []
         L.hop_strerror.argtypes = [ctypes.c_int]
         L.hop_strerror.restype = ctypes.c_char_p
+        L.hop_kernel_config.argtypes = []
+        L.hop_kernel_config.restype = ctypes.c_char_p
         for name in EXPORTS:
-            if name not in ("hop_workspace_bytes", "hop_strerror"):
+            if name not in ("hop_workspace_bytes", "hop_strerror", "hop_kernel_config"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -235,6 +237,10 @@ def hop_pick_degree(k, object_bytes, latency_s=0.0, bytes_per_s=0.0):
 
 def hop_workspace_bytes(n, k, n_dst=0):
     return lib().hop_workspace_bytes(int(n), int(k), int(n_dst))
+
+
+def hop_kernel_config() -> str:
+    return lib().hop_kernel_config().decode()
 
 
 def hop_shutdown():

@@ -467,6 +467,8 @@ int hop_shutdown(void)
     return rc;
 }
 
+const char *hop_kernel_config(void) { return kernel_config(); }
+
 const char *hop_strerror(int status)
 {
     switch (status) {

@@ -52,6 +52,9 @@ struct CopyArgs {
 
 int elem_bytes(int dtype);
 
+// Launch shape of the kernels, as text.
+const char *kernel_config();
+
 // Reduce the byte range [byte_begin, byte_end) of the objects named by the
 // program into dst (and the n_extra further destinations of the device table
 // extra_dsts). depth = accumulator levels the program uses

@@ -71,6 +71,13 @@ static unsigned grid_for(size_t n_vec, size_t tile_vecs)
 
 int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 
+const char *kernel_config()
+{
+    return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
+           "workgroup, nontemporal loads+stores, programs <= 32 steps in kernel arguments; "
+           "copy: 64 lanes/workgroup, 4 vectors/lane, nontemporal";
+}
+
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
                          const DevEntry *dev_prog, int n_entries, void *dst, void *const *extra_dsts,
                          int n_extra, size_t byte_begin, size_t byte_end)
