@@ -309,3 +309,96 @@ def test_other_stream():
     _, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], w.k, oracle.SUM, oracle.F32,
                                   w.chunk_bytes // 4, w.tree_degree, None, None)
     assert rc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+
+
+# ------------------------------------------------------------------ full-size workloads, sampled against the oracle
+
+def sampled_oracle_check(w, op, objs, dsts, rc, info, rng, per_chunk=64):
+    """The reduce is elementwise, so the oracle run on a gather of the same element positions from every
+    object must equal the gather of the GPU result. Positions: first and last elements of every chunk
+    plus random ones; per_chunk of them for each chunk so that the gathered objects keep the chunk count."""
+    C, E = w.n_chunks, w.n_elems
+    ce = w.chunk_bytes // ES[w.dtype]
+    idx = []
+    for c in range(C):
+        lo, hi = c * ce, min((c + 1) * ce, E)
+        pick = np.concatenate([[lo, lo + 1, hi - 2, hi - 1], rng.integers(lo, hi, size=per_chunk - 4)])
+        idx.append(np.sort(pick))
+    idx = torch.from_numpy(np.concatenate(idx)).to(dev())
+    small = [workloads.to_numpy(o[idx]) for o in objs]
+    d = info["degree_used"] if w.tree_degree == 0 else w.tree_degree
+    orc, want, k_eff, n_rep = oracle.reduce(small, w.k, ORA_OP[op], ORA_DT[w.dtype], per_chunk, d, w.ready_order(),
+                                            w.fail_mask())
+    assert rc == orc and info["k_eff"] == k_eff and info["n_replaced"] == n_rep
+    for dst in dsts:
+        got = workloads.to_numpy(dst[idx])
+        assert np.array_equal(bits(got), bits(want))
+    return small, want
+
+
+def test_cfg2_full_size_sampled():
+    w = workloads.WORKLOADS[2]
+    print("full size", w.name, flush=True)
+    objs = workloads.make_objects(w, device=dev())
+    dst = torch.zeros_like(objs[0])
+    rc, info = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and info["n_launches"] == 1 and info["k_eff"] == 12
+    small, want = sampled_oracle_check(w, "sum", objs, [dst], rc, info, np.random.default_rng(2))
+    # property that holds at any size: the four objects that were not among the first 12 ready were not read;
+    # a torch fp64 sum over the selected twelve agrees within the free-order tolerance on the WHOLE object
+    sel = w.ready_order()[:12]
+    ref = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
+    mag = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
+    for i in sel:
+        ref += objs[i].double()
+        mag += objs[i].double().abs()
+    tol = 1e-5 * np.log2(12)
+    err = (dst.double() - ref).abs()
+    assert bool((err <= tol * torch.maximum(ref.abs(), mag / 12)).all())
+
+
+def test_cfg3_full_size_allreduce_sampled():
+    w = workloads.WORKLOADS[3]
+    print("full size", w.name, flush=True)
+    objs = workloads.make_objects(w, device=dev())
+    dsts = [torch.zeros_like(objs[0]) for _ in range(w.n_dst)]
+    rc, info = hop.hop_allreduce(dsts, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and info["k_eff"] == 64
+    sampled_oracle_check(w, "sum", objs, dsts[:3] + dsts[-1:], rc, info, np.random.default_rng(3))
+    # integers are order-free: the whole result equals torch's sum, and all 64 destinations are identical
+    ref = torch.zeros_like(objs[0])
+    for o in objs:
+        ref += o
+    for d_ in dsts:
+        assert torch.equal(d_, ref)
+
+
+def test_cfg4_full_size_failure_sampled():
+    w = workloads.WORKLOADS[4]
+    print("full size", w.name, flush=True)
+    objs = workloads.make_objects(w, device=dev())
+    dst = torch.zeros_like(objs[0])
+    rc, info = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(),
+                              w.fail_mask())
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_PARTIAL and info["k_eff"] == 31 and info["n_launches"] == 2
+    assert info["chunks_redone"] == 10 * 31
+    sampled_oracle_check(w, "sum", objs, [dst], rc, info, np.random.default_rng(4))
+    # whole-object property: within the bf16 tolerance of the fp64 sum over the 31 survivors (object 7 excluded)
+    ref = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
+    for i in range(w.n):
+        if i != 7:
+            ref += objs[i].double()
+    err = (dst.double() - ref).abs()
+    assert bool((err <= 1e-2 * torch.maximum(ref.abs(), torch.tensor(1.0, device=dev(), dtype=torch.float64))).all())
+    del ref, err
+    # and independent of when the failure happened
+    dst2 = torch.zeros_like(dst)
+    fm = w.fail_mask().copy()
+    fm[7] = 31
+    rc2, info2 = hop.hop_reduce(dst2, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), fm)
+    torch.cuda.synchronize()
+    assert rc2 == hop.HOP_PARTIAL and info2["chunks_redone"] == 31 * 31
+    assert torch.equal(dst.view(torch.int16), dst2.view(torch.int16))
