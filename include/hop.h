@@ -202,6 +202,26 @@ int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int 
                     hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
                     hop_plan_entry_t *entries, int entry_capacity, int *n_entries);
 
+/*
+ * Host-only view of how a long program is cut for launches that cover few
+ * tiles (many small objects). Every run of at least min_run steps that works
+ * above level 0 (a non-first-child subtree hanging off the leftmost spine)
+ * becomes a sub-program of its own, levels shifted down by one, whose result
+ * is stored as a partial; in the program it came from it is replaced by one
+ * step with obj = -(1 + g) naming the partial of sub-program g. Programs of
+ * at least min_steps steps are cut, sub-programs included (recursively).
+ * sub_pass[g] is the pass in which sub-program g must run: it reads only
+ * objects and partials of earlier passes; the top program runs last.
+ * sub_begin receives n_subs + 1 offsets into sub_entries (capacity counts
+ * entries of sub_begin; sub_pass needs one less). Counts are always returned;
+ * arrays are filled up to capacity. Returns HOP_OK if anything was cut,
+ * HOP_PARTIAL if the program stays whole.
+ */
+int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int min_steps, int min_run,
+                   hop_plan_entry_t *top, int top_capacity, int *n_top,
+                   hop_plan_entry_t *sub_entries, int sub_capacity, int *n_sub_entries,
+                   int32_t *sub_begin, int32_t *sub_pass, int sub_table_capacity, int *n_subs, int *n_passes);
+
 /* node_of_slot[t] (k entries) = level-order index of the tree node that the
  * t-th arrival takes in the complete d-ary tree on k nodes. */
 int hop_plan_slots(int k, int tree_degree, int32_t *node_of_slot);

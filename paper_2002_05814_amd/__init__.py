@@ -29,7 +29,7 @@ DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
           torch.float32: HOP_F32, torch.bfloat16: HOP_BF16, torch.int32: HOP_I32}
 
 EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_session_begin", "hop_session_ready",
-           "hop_session_fail", "hop_session_finish", "hop_plan_reduce", "hop_plan_slots",
+           "hop_session_fail", "hop_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
            "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
 
 
@@ -81,6 +81,11 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_size_t, ctypes.c_int, i64p, infop,
                                       ctypes.POINTER(PlanLaunch), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        L.hop_plan_split.argtypes = [ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                     ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                     ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                     i32p, i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                     ctypes.POINTER(ctypes.c_int)]
         L.hop_plan_slots.argtypes = [ctypes.c_int, ctypes.c_int, i32p]
         L.hop_pick_degree.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
         L.hop_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
@@ -223,6 +228,25 @@ def hop_plan_reduce(n, object_bytes, k, dtype, chunk_bytes, tree_degree, ready_o
     launches = [(L[i].chunk_begin, L[i].chunk_end, L[i].entry_begin, L[i].entry_end) for i in range(nl.value)]
     entries = [(E[i].obj, E[i].level, E[i].set, E[i].n_fold) for i in range(ne.value)]
     return rc, info.as_dict(), launches, entries
+
+
+def hop_plan_split(entries, min_steps, min_run):
+    """(status, top entries, [(pass, sub-program entries), ...]) for a program of (obj, level, set, n_fold) tuples."""
+    n = len(entries)
+    E = (PlanEntry * max(n, 1))(*[PlanEntry(*e) for e in entries])
+    top = (PlanEntry * max(n, 1))()
+    sub = (PlanEntry * (2 * n + 1))()
+    begins = np.zeros(n + 2, np.int32)
+    passes = np.zeros(n + 2, np.int32)
+    nt, ns, nsub, npass = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    i32 = ctypes.POINTER(ctypes.c_int32)
+    rc = lib().hop_plan_split(E, n, int(min_steps), int(min_run), top, n, ctypes.byref(nt), sub, 2 * n + 1,
+                              ctypes.byref(ns), begins.ctypes.data_as(i32), passes.ctypes.data_as(i32), n + 2,
+                              ctypes.byref(nsub), ctypes.byref(npass))
+    as_t = lambda a, i: (a[i].obj, a[i].level, a[i].set, a[i].n_fold)
+    tops = [as_t(top, i) for i in range(nt.value)]
+    subs = [(int(passes[s]), [as_t(sub, i) for i in range(begins[s], begins[s + 1])]) for s in range(nsub.value)]
+    return rc, tops, subs
 
 
 def hop_plan_slots(k, tree_degree):

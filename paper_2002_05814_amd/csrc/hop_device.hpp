@@ -158,7 +158,7 @@ __device__ __forceinline__ void st16(void *base, size_t byte_off, const uint4 &v
 // in SGPRs (a plain global pointer would make the compiler assume that the
 // result stores may change it, and fall back to per-lane loads).
 typedef const DevEntry __attribute__((address_space(4))) *prog_ptr;
-// Destination tables are read the same way.
+// The broadcast's destination table is read the same way.
 typedef void *const __attribute__((address_space(4))) *table_ptr;
 
 // One workgroup of THREADS lanes walks tiles of THREADS*VPT consecutive
@@ -168,13 +168,11 @@ typedef void *const __attribute__((address_space(4))) *table_ptr;
 // issued before the first of them is consumed, then the group's values are
 // folded in program order. D = accumulator levels held in registers.
 template <int DT, int OP, int D, int VPT, int U, int THREADS, class Prog>
-__device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog)
+__device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog, const int n, void *const dst)
 {
     using T = Traits<DT>;
     using A = typename T::acc_t;
     constexpr int W = T::W;
-    const table_ptr extra = (table_ptr)(uintptr_t)a.extra_dsts;
-    const int n = a.n_entries;
     constexpr size_t kTile = (size_t)THREADS * VPT;
     const size_t n_tiles = (a.n_vec + kTile - 1) / kTile;
 
@@ -220,10 +218,7 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
             const uint4 out = encode<DT>(&m.acc[0][j * W]);
-            if (live[j]) {
-                st16(a.dst, off[j], out);
-                for (int e = 0; e < a.n_extra; ++e) st16(extra[e], off[j], out);
-            }
+            if (live[j]) st16(dst, off[j], out);
         }
     }
 
@@ -235,8 +230,7 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
             A x[1] = {load_elem<DT>(prog[t].src, off)};
             m.step(prog[t].ctl, x);
         }
-        store_elem<DT>(a.dst, off, m.acc[0][0]);
-        for (int e = 0; e < a.n_extra; ++e) store_elem<DT>(extra[e], off, m.acc[0][0]);
+        store_elem<DT>(dst, off, m.acc[0][0]);
     }
 }
 
@@ -244,14 +238,22 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
 template <int DT, int OP, int D, int VPT, int U, int THREADS>
 __global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
 {
-    reduce_body<DT, OP, D, VPT, U, THREADS>(a, (prog_ptr)(uintptr_t)a.prog);
+    const prog_ptr prog = (prog_ptr)(uintptr_t)a.prog;
+    if (a.subs) {
+        // several independent sub-programs in one launch: blockIdx.y picks one
+        typedef const SubLaunch __attribute__((address_space(4))) *sub_ptr;
+        const sub_ptr sub = (sub_ptr)(uintptr_t)a.subs + blockIdx.y;
+        reduce_body<DT, OP, D, VPT, U, THREADS>(a, prog + sub->entry_begin, (int)sub->n_entries, sub->dst);
+    } else {
+        reduce_body<DT, OP, D, VPT, U, THREADS>(a, prog, a.n_entries, a.dst);
+    }
 }
 
 // Program inside the kernel arguments.
 template <int DT, int OP, int D, int VPT, int U, int THREADS>
 __global__ __launch_bounds__(THREADS) void reduce_kernel_inline(ReduceArgsInline a)
 {
-    reduce_body<DT, OP, D, VPT, U, THREADS>(a.base, &a.steps[0]);
+    reduce_body<DT, OP, D, VPT, U, THREADS>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
 }
 
 // One source, n_dst destinations: each 16-byte vector is read once and

@@ -25,15 +25,23 @@ static_assert(sizeof(DevEntry) == 16, "program steps are 16 bytes");
 // segment); longer ones are staged in device memory.
 constexpr int kInlineEntries = 32;
 
+// One of several sub-programs evaluated by a single launch (grid dimension y):
+// steps [entry_begin, entry_begin + n_entries) of the launch's program, result to dst.
+struct SubLaunch {
+    uint32_t entry_begin;
+    uint32_t n_entries;
+    void *dst;
+};
+static_assert(sizeof(SubLaunch) == 16, "sub-launch descriptors are 16 bytes");
+
 struct ReduceArgs {
     const DevEntry *prog;      // device memory, n_entries steps (unused by the inline variant)
     int n_entries;
     void *dst;                 // result
-    void *const *extra_dsts;   // device table of n_extra further destinations (allreduce), or null
-    int n_extra;
     size_t byte_begin;         // first byte of the object range this launch covers
     size_t n_vec;              // full 16-byte vectors in the range
     int n_tail;                // elements after the last full vector (object end only)
+    const SubLaunch *subs;     // device table of gridDim.y sub-programs, or null (whole program -> dst)
 };
 
 struct ReduceArgsInline {
@@ -56,14 +64,19 @@ int elem_bytes(int dtype);
 const char *kernel_config();
 
 // Reduce the byte range [byte_begin, byte_end) of the objects named by the
-// program into dst (and the n_extra further destinations of the device table
-// extra_dsts). depth = accumulator levels the program uses
+// program into dst. depth = accumulator levels the program uses
 // (1..HOP_MAX_DEPTH). host_steps = the n_entries steps in host memory; when
 // there are more than kInlineEntries of them, dev_prog must hold the same
 // steps in device memory. Every other pointer is a device pointer.
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
-                         const DevEntry *dev_prog, int n_entries, void *dst, void *const *extra_dsts,
-                         int n_extra, size_t byte_begin, size_t byte_end);
+                         const DevEntry *dev_prog, int n_entries, void *dst, size_t byte_begin,
+                         size_t byte_end);
+
+// The same for n_subs independent sub-programs at once: dev_subs[s] names the steps
+// (inside dev_prog) and the destination of sub-program s; every sub-program covers the
+// same byte range and needs at most `depth` accumulator levels.
+hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
+                              const SubLaunch *dev_subs, int n_subs, size_t byte_begin, size_t byte_end);
 
 // Copy [byte_begin, byte_end) of src into the same range of every destination
 // of the device table dsts.

@@ -34,16 +34,26 @@ template <int DT, int D> struct VecPerLane {
     static constexpr int value = (D * W <= 32) ? 4 : (D * W <= 64) ? 2 : 1;
 };
 
+// Launches that cover few tiles (small objects, short chunk runs) cannot fill the
+// chip with 4 KiB tiles; they use 1 KiB tiles (one vector per lane) with 8 sources
+// in flight per lane instead, which shortens the dependent-load chain per wave.
+constexpr int kSmallUnroll = 8;
+constexpr size_t kSmallLaunchTiles = 2048;   // below this many 4 KiB tiles the small shape is used
+
 struct Launcher {
     void (*dev)(ReduceArgs);
     void (*inl)(ReduceArgsInline);
+    void (*dev_small)(ReduceArgs);
+    void (*inl_small)(ReduceArgsInline);
     int vpt;
 };
 
 template <int DT, int OP, int D> static Launcher make_launcher()
 {
     constexpr int V = VecPerLane<DT, D>::value;
-    return {reduce_kernel<DT, OP, D, V, kUnroll, kThreads>, reduce_kernel_inline<DT, OP, D, V, kUnroll, kThreads>, V};
+    return {reduce_kernel<DT, OP, D, V, kUnroll, kThreads>, reduce_kernel_inline<DT, OP, D, V, kUnroll, kThreads>,
+            reduce_kernel<DT, OP, D, 1, kSmallUnroll, kThreads>,
+            reduce_kernel_inline<DT, OP, D, 1, kSmallUnroll, kThreads>, V};
 }
 template <int DT, int OP> static Launcher pick_depth(int depth)
 {
@@ -74,43 +84,73 @@ int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-           "workgroup, nontemporal loads+stores, programs <= 32 steps in kernel arguments; "
-           "copy: 64 lanes/workgroup, 4 vectors/lane, nontemporal";
+           "workgroup (1 KiB tiles, unroll 8 below 2048 tiles), nontemporal loads+stores, programs <= 32 steps in "
+           "kernel arguments; "
+           "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal";
+}
+
+static Launcher pick(int dtype, int op, int depth)
+{
+    switch (dtype) {
+    case HOP_F32:  return pick_op<HOP_F32>(op, depth);
+    case HOP_BF16: return pick_op<HOP_BF16>(op, depth);
+    default:       return pick_op<HOP_I32>(op, depth);
+    }
+}
+
+static void fill_range(ReduceArgs &a, int dtype, size_t byte_begin, size_t byte_end)
+{
+    a.byte_begin = byte_begin;
+    a.n_vec = (byte_end - byte_begin) / 16;
+    a.n_tail = (int)(((byte_end - byte_begin) % 16) / elem_bytes(dtype));
 }
 
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
-                         const DevEntry *dev_prog, int n_entries, void *dst, void *const *extra_dsts,
-                         int n_extra, size_t byte_begin, size_t byte_end)
+                         const DevEntry *dev_prog, int n_entries, void *dst, size_t byte_begin,
+                         size_t byte_end)
 {
     if (byte_end <= byte_begin || n_entries <= 0) return hipSuccess;
-    Launcher l;
-    switch (dtype) {
-    case HOP_F32:  l = pick_op<HOP_F32>(op, depth); break;
-    case HOP_BF16: l = pick_op<HOP_BF16>(op, depth); break;
-    default:       l = pick_op<HOP_I32>(op, depth); break;
-    }
+    const Launcher l = pick(dtype, op, depth);
     ReduceArgsInline a;
     a.base.prog = dev_prog;
     a.base.n_entries = n_entries;
     a.base.dst = dst;
-    a.base.extra_dsts = extra_dsts;
-    a.base.n_extra = n_extra;
-    a.base.byte_begin = byte_begin;
-    a.base.n_vec = (byte_end - byte_begin) / 16;
-    a.base.n_tail = (int)(((byte_end - byte_begin) % 16) / elem_bytes(dtype));
-    const unsigned grid = grid_for(a.base.n_vec, (size_t)kThreads * l.vpt);
+    a.base.subs = nullptr;
+    fill_range(a.base, dtype, byte_begin, byte_end);
+    const bool small = grid_for(a.base.n_vec, (size_t)kThreads * l.vpt) < kSmallLaunchTiles;
+    const unsigned grid = grid_for(a.base.n_vec, (size_t)kThreads * (small ? 1 : l.vpt));
     if (n_entries <= kInlineEntries) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
         for (int i = n_entries; i < kInlineEntries; ++i) a.steps[i] = DevEntry{nullptr, 0, 0};
-        hipLaunchKernelGGL(l.inl, dim3(grid), dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL(small ? l.inl_small : l.inl, dim3(grid), dim3(kThreads), 0, stream, a);
     } else {
         if (!dev_prog) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(l.dev, dim3(grid), dim3(kThreads), 0, stream, a.base);
+        hipLaunchKernelGGL(small ? l.dev_small : l.dev, dim3(grid), dim3(kThreads), 0, stream, a.base);
     }
     return hipGetLastError();
 }
 
-constexpr int kCopyVpt = 4;
+hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
+                              const SubLaunch *dev_subs, int n_subs, size_t byte_begin, size_t byte_end)
+{
+    if (byte_end <= byte_begin || n_subs <= 0) return hipSuccess;
+    if (!dev_prog || !dev_subs || n_subs > 65535) return hipErrorInvalidValue;
+    const Launcher l = pick(dtype, op, depth);
+    ReduceArgs a;
+    a.prog = dev_prog;
+    a.n_entries = 0;
+    a.dst = nullptr;
+    a.subs = dev_subs;
+    fill_range(a, dtype, byte_begin, byte_end);
+    const unsigned grid = grid_for(a.n_vec, (size_t)kThreads);
+    hipLaunchKernelGGL(l.dev_small, dim3(grid, (unsigned)n_subs), dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+// The copy is write-bound; longer bursts per destination pay: 8 vectors per lane
+// (8 KiB per wave and destination) beat 1, 2 and 4 in sweeps with 63 destinations,
+// as did keeping all destinations in one workgroup rather than splitting them.
+constexpr int kCopyVpt = 8;
 
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
                        size_t byte_begin, size_t byte_end)

@@ -124,6 +124,113 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
     return depth;
 }
 
+// A program cut at its outermost level. Every maximal run of steps that works
+// above level 0 (from the step that starts a level-1 partial to the step whose
+// folds return to level 0) is an independent sub-expression: a non-first-child
+// subtree hanging off the leftmost spine of the tree. Runs of at least min_run
+// steps become sub-programs of their own (levels shifted down by one, the final
+// fold dropped); in the top program such a run is one step that combines the
+// sub-program's stored partial into level 0, which is the same arithmetic as the
+// fold it replaces. Shorter runs stay in the top program unchanged.
+struct SplitPlan {
+    std::vector<Entry> sub_entries;              // all sub-programs, concatenated
+    struct Range { int begin, end; };
+    std::vector<Range> subs;                     // sub-program s = sub_entries[begin, end)
+    std::vector<Entry> top;                      // obj >= 0: object; obj = -(1 + s): partial of sub-program s
+    int sub_depth = 0, top_depth = 0;
+};
+
+inline bool split_program(const std::vector<Entry> &prog, int min_run, SplitPlan &out)
+{
+    out = SplitPlan();
+    const int n = (int)prog.size();
+    int i = 0;
+    while (i < n) {
+        const Entry &e = prog[i];
+        if (e.level == 0) {
+            out.top.push_back(e);
+            out.top_depth = std::max(out.top_depth, 1);
+            ++i;
+            continue;
+        }
+        int j = i;                                // find the step that folds back to level 0
+        while (j < n && (int)prog[j].level - (int)prog[j].n_fold != 0) ++j;
+        if (j >= n || !(e.level == 1 && e.set)) return false;     // malformed program: do not split
+        const int len = j - i + 1;
+        if (len >= min_run) {
+            const int begin = (int)out.sub_entries.size();
+            for (int t = i; t <= j; ++t) {
+                Entry s = prog[t];
+                s.level = (uint8_t)(s.level - 1);
+                if (t == j) s.n_fold = (uint16_t)(s.n_fold - 1);
+                out.sub_depth = std::max(out.sub_depth, (int)s.level + 1);
+                out.sub_entries.push_back(s);
+            }
+            out.subs.push_back({begin, (int)out.sub_entries.size()});
+            out.top.push_back({-(int32_t)out.subs.size(), 0, 0, 0});
+        } else {
+            for (int t = i; t <= j; ++t) {
+                out.top.push_back(prog[t]);
+                out.top_depth = std::max(out.top_depth, (int)prog[t].level + 1);
+            }
+        }
+        i = j + 1;
+    }
+    return !out.subs.empty();
+}
+
+// The cut applied recursively: sub-programs that are still long are cut again,
+// so a deep tree becomes a few passes of many short independent programs. A
+// sub-program of height h reads only objects and partials of height < h; pass h
+// evaluates all sub-programs of height h side by side, the top program comes last.
+struct MultiPlan {
+    struct Sub { std::vector<Entry> steps; int height; int depth; };
+    std::vector<Sub> subs;                       // obj = -(1 + g) in any steps names the partial of subs[g]
+    std::vector<Entry> top;
+    int top_depth = 0;
+    int n_passes = 0;
+};
+
+inline int program_depth(const std::vector<Entry> &p)
+{
+    int d = 0;
+    for (const Entry &e : p) d = std::max(d, (int)e.level + 1);
+    return d;
+}
+
+// Returns the height of prog (0 = left whole) and its final steps in `out`.
+inline int split_recursive(const std::vector<Entry> &prog, size_t min_steps, int min_run, MultiPlan &mp,
+                           std::vector<Entry> &out)
+{
+    SplitPlan sp;
+    if (prog.size() < min_steps || !split_program(prog, min_run, sp)) {
+        out = prog;
+        return 0;
+    }
+    int height = 0;
+    std::vector<int> global_id(sp.subs.size());
+    for (size_t s = 0; s < sp.subs.size(); ++s) {
+        std::vector<Entry> steps(sp.sub_entries.begin() + sp.subs[s].begin, sp.sub_entries.begin() + sp.subs[s].end);
+        std::vector<Entry> final_steps;
+        const int h = split_recursive(steps, min_steps, min_run, mp, final_steps);
+        global_id[s] = (int)mp.subs.size();
+        mp.subs.push_back({final_steps, h, program_depth(final_steps)});
+        height = std::max(height, h + 1);
+    }
+    out = sp.top;
+    for (Entry &e : out)
+        if (e.obj < 0) e.obj = -(int32_t)(1 + global_id[-e.obj - 1]);
+    return height;
+}
+
+inline bool plan_passes(const std::vector<Entry> &prog, size_t min_steps, int min_run, MultiPlan &mp)
+{
+    mp = MultiPlan();
+    mp.n_passes = split_recursive(prog, min_steps, min_run, mp, mp.top);
+    mp.top_depth = program_depth(mp.top);
+    return mp.n_passes > 0;
+}
+
 // Where the scheduler sends work. launch() must make output chunks
 // [c0, c1) equal to the program's value; programs are identified by a
 // version that changes whenever the occupants change.

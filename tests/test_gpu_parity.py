@@ -115,6 +115,32 @@ def test_random_shapes_and_failures(dtype, op):
         run_both(w, op, fm=fm)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "i32", "bf16"])
+def test_many_small_objects_take_the_multi_pass_path(dtype):
+    # hundreds of inputs, few tiles: programs are cut into passes of independent subtrees (f32, i32);
+    # results must not change by a bit
+    rng = np.random.default_rng({"f32": 71, "i32": 72, "bf16": 73}[dtype])
+    base = workloads.WORKLOADS[{"f32": 5, "bf16": 4, "i32": 3}[dtype]]
+    dist = {"f32": "uniform_pm1", "bf16": "normal_std1", "i32": "randint_pm2p20"}[dtype]
+    for it in range(10):
+        n = int(rng.integers(64, 700))
+        k = int(rng.integers(64, n + 1))
+        d = int(rng.choice([2, 3, 4, 8, 16, 32]))
+        n_elems = int(rng.integers(1, 3000))
+        nbytes = n_elems * ES[dtype]
+        chunk = 16 * int(rng.integers(1, 200))
+        C = -(-nbytes // chunk)
+        w = base.scaled(nbytes, chunk, n=n, k=k, tree_degree=d, order_seed=int(rng.integers(1 << 30)),
+                        data_seed=int(rng.integers(1 << 30)), fail={}, name="small%d" % it, dist=dist, n_dst=0)
+        fm = None
+        if it % 2:
+            fm = np.full(n, -1, np.int64)
+            bad = rng.random(n) < 0.1
+            fm[bad] = rng.integers(0, C + 1, size=int(bad.sum()))
+        for op in ("sum", "max"):
+            run_both(w, op, fm=fm)
+
+
 def test_denormals_and_signed_zeros_are_preserved():
     w = workloads.WORKLOADS[1].scaled(4096 * 4, 1024, n=4, k=4)
     rng = np.random.default_rng(5)

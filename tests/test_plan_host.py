@@ -119,6 +119,76 @@ def test_interpreted_plan_equals_oracle_i32_wrapping():
         assert np.array_equal(got.view(np.int32), want)
 
 
+def run_entries(objs, entries, op, partials=()):
+    f = NP_OP[op]
+    acc = {}
+    for obj, level, is_set, n_fold in entries:
+        x = objs[obj] if obj >= 0 else partials[-obj - 1]
+        acc[level] = x.copy() if is_set else f(acc[level], x).astype(x.dtype)
+        for _ in range(n_fold):
+            acc[level - 1] = f(acc[level - 1], acc[level]).astype(x.dtype)
+            del acc[level]
+            level -= 1
+    assert list(acc) == [0]
+    return acc[0]
+
+
+def run_plan_passes(objs, tops, subs, op):
+    """Evaluate sub-programs pass by pass (each reads only partials of earlier passes), then the top."""
+    partials = [None] * len(subs)
+    for p in range(1 + max([ps for ps, _ in subs], default=-1)):
+        for g, (ps, steps) in enumerate(subs):
+            if ps == p:
+                for e in steps:
+                    assert e[0] >= 0 or (subs[-e[0] - 1][0] < p and partials[-e[0] - 1] is not None)
+                partials[g] = run_entries(objs, steps, op, partials)
+    return run_entries(objs, tops, op, partials)
+
+
+@pytest.mark.parametrize("min_steps,min_run", [(1, 1), (1, 2), (8, 4), (64, 4), (30, 9)])
+def test_split_program_keeps_the_bits(min_steps, min_run):
+    rng = np.random.default_rng(min_steps * 10 + min_run)
+    n_split = 0
+    for _ in range(120):
+        n = int(rng.integers(1, 200))
+        k = int(rng.integers(1, n + 1))
+        d = int(rng.choice([1, 2, 3, 4, 16, n + 1]))
+        E = 16
+        order = rng.permutation(n).astype(np.int32)
+        fm = None
+        if rng.random() < 0.5:
+            fm = np.full(n, -1, np.int64)
+            bad = rng.random(n) < 0.2
+            fm[bad] = rng.integers(0, 3, size=int(bad.sum()))
+        objs = [(rng.standard_normal(E) * 10.0 ** rng.integers(-3, 4)).astype(np.float32) for _ in range(n)]
+        rc, info, launches, entries = hop.hop_plan_reduce(n, E * 4, k, "f32", 32, d, order, fm)
+        if rc < 0:
+            continue
+        final = entries[launches[-1][2]:launches[-1][3]]
+        src, tops, subs = hop.hop_plan_split(final, min_steps, min_run)
+        whole = run_entries(objs, final, "sum")
+        if src == hop.HOP_PARTIAL:
+            assert subs == [] and tops == final
+            continue
+        n_split += 1
+        # every object still exactly once; every partial used exactly once
+        seen = [e[0] for e in tops if e[0] >= 0] + [e[0] for _, sp in subs for e in sp if e[0] >= 0]
+        assert sorted(seen) == sorted(e[0] for e in final)
+        refs = [-e[0] - 1 for e in tops if e[0] < 0] + [-e[0] - 1 for _, sp in subs for e in sp if e[0] < 0]
+        assert sorted(refs) == list(range(len(subs)))
+        got = run_plan_passes(objs, tops, subs, "sum")
+        assert np.array_equal(got.view(np.uint32), whole.view(np.uint32))
+    assert n_split > 10
+    # workload 5: 1000 steps in one program become three passes of short programs
+    w = workloads.WORKLOADS[5]
+    _, _, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
+                                                  w.ready_order(), None)
+    src, tops, subs = hop.hop_plan_split(entries, 64, 4)
+    assert src == hop.HOP_OK and len(tops) < 64 and max(len(sp) for _, sp in subs) < 64
+    assert {ps for ps, _ in subs} == {0, 1}
+    assert len(tops) + sum(len(sp) for _, sp in subs) - len(subs) == 1000
+
+
 def test_failure_free_call_is_one_launch_over_all_chunks():
     for cfg in (1, 2, 3, 5):
         w = workloads.WORKLOADS[cfg]
