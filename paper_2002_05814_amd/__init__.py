@@ -108,8 +108,27 @@ def hop_strerror(status: int) -> str:
 
 # ------------------------------------------------------------------ marshalling helpers
 
-def _ptr_table(items: Sequence) -> Tuple[ctypes.Array, int]:
+class PtrTable:
+    """A host array of device pointers built once from tensors (or raw addresses), for callers that
+    pass the same buffers again and again and do not want to re-marshal them on every call."""
+
+    def __init__(self, items: Sequence):
+        self.items = list(items)                     # keeps the tensors alive
+        self.array, self.n = _ptr_table(self.items)
+        self.object_bytes = (self.items[0].numel() * self.items[0].element_size()
+                             if self.n and isinstance(self.items[0], torch.Tensor) else None)
+
+    def __len__(self):
+        return self.n
+
+    def __getitem__(self, i):
+        return self.items[i]
+
+
+def _ptr_table(items) -> Tuple[ctypes.Array, int]:
     """Host array of device pointers from tensors or raw integer addresses."""
+    if isinstance(items, PtrTable):
+        return items.array, items.n
     ptrs = [int(t.data_ptr()) if isinstance(t, torch.Tensor) else int(t) for t in items]
     return (ctypes.c_void_p * max(len(ptrs), 1))(*ptrs), len(ptrs)
 

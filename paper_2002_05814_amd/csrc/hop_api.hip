@@ -137,22 +137,6 @@ public:
     int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) override
     {
         if (shape_.object_bytes == 0) return HOP_OK;
-        if (version != dev_version_) {
-            staging_.resize(prog.size());
-            depth_ = 1;
-            for (size_t i = 0; i < prog.size(); ++i) {
-                staging_[i].src = objs_[prog[i].obj];
-                staging_[i].ctl = (uint32_t)prog[i].level | ((uint32_t)prog[i].set << 8) | ((uint32_t)prog[i].n_fold << 16);
-                staging_[i].reserved = 0;
-                depth_ = std::max(depth_, (int)prog[i].level + 1);
-            }
-            dev_prog_ = nullptr;
-            if ((int)staging_.size() > kInlineEntries) {      // short programs ride in the kernel arguments
-                dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
-                if (!dev_prog_) return HOP_ERR_NOMEM;
-            }
-            dev_version_ = version;
-        }
         if (dsts_.size() > 1 && !dev_extra_) {
             dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
             if (!dev_extra_) return HOP_ERR_NOMEM;
@@ -166,6 +150,20 @@ public:
                 if (dsts_.size() > 1) ec = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1);
                 return ec == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
             }
+        }
+        if (version != dev_version_) {
+            staging_.resize(prog.size());
+            depth_ = 1;
+            for (size_t i = 0; i < prog.size(); ++i) {
+                staging_[i] = resolve(prog[i], nullptr, 0, 0);
+                depth_ = std::max(depth_, (int)prog[i].level + 1);
+            }
+            dev_prog_ = nullptr;
+            if ((int)staging_.size() > kInlineEntries) {      // short programs ride in the kernel arguments
+                dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
+                if (!dev_prog_) return HOP_ERR_NOMEM;
+            }
+            dev_version_ = version;
         }
         // Reduce followed by broadcast, chunk run by chunk run: the finished chunks land in the
         // first destination and the copy kernel carries them to the others while they are still
@@ -205,36 +203,46 @@ private:
         // Kernels address sources and results by the object's byte offset, so a partial that holds
         // only [b0, b1) is passed as base - b0. Passes run in stream order: pass h reads what
         // passes < h wrote.
+        // All passes' steps and sub-program tables, then the top program, travel in one copy.
+        struct PassInfo { size_t steps_at, subs_at; int n_subs, depth; };
+        std::vector<PassInfo> passes(mp.n_passes);
+        std::vector<DevEntry> blob;                     // SubLaunch and DevEntry are both 16 bytes
+        static_assert(sizeof(SubLaunch) == sizeof(DevEntry), "one staging array serves both");
         for (int pass = 0; pass < mp.n_passes; ++pass) {
-            std::vector<DevEntry> steps;
             std::vector<SubLaunch> subs;
-            int depth = 1;
+            PassInfo &pi = passes[pass];
+            pi.steps_at = blob.size();
+            pi.depth = 1;
             for (size_t g = 0; g < mp.subs.size(); ++g) {
                 const MultiPlan::Sub &sub = mp.subs[g];
                 if (sub.height != pass) continue;
                 SubLaunch sl;
-                sl.entry_begin = (uint32_t)steps.size();
+                sl.entry_begin = (uint32_t)(blob.size() - pi.steps_at);
                 sl.n_entries = (uint32_t)sub.steps.size();
                 sl.dst = (void *)((uintptr_t)partials + g * part_bytes - b0);
                 subs.push_back(sl);
-                for (const Entry &e : sub.steps) steps.push_back(resolve(e, partials, part_bytes, b0));
-                depth = std::max(depth, sub.depth);
+                for (const Entry &e : sub.steps) blob.push_back(resolve(e, partials, part_bytes, b0));
+                pi.depth = std::max(pi.depth, sub.depth);
             }
-            const DevEntry *dev_steps = (const DevEntry *)ws_.stage(steps.data(), steps.size() * sizeof(DevEntry));
-            const SubLaunch *dev_subs = (const SubLaunch *)ws_.stage(subs.data(), subs.size() * sizeof(SubLaunch));
-            if (!dev_steps || !dev_subs) return HOP_ERR_NOMEM;
-            if (launch_reduce_subs(stream_, dtype_, op_, depth, dev_steps, dev_subs, (int)subs.size(), b0, b1) != hipSuccess)
+            pi.subs_at = blob.size();
+            pi.n_subs = (int)subs.size();
+            for (const SubLaunch &sl : subs) {
+                DevEntry raw;
+                std::memcpy(&raw, &sl, sizeof raw);
+                blob.push_back(raw);
+            }
+        }
+        const size_t top_at = blob.size();
+        for (const Entry &e : mp.top) blob.push_back(resolve(e, partials, part_bytes, b0));
+        const DevEntry *dev = (const DevEntry *)ws_.stage(blob.data(), blob.size() * sizeof(DevEntry));
+        if (!dev) return HOP_ERR_NOMEM;
+        for (const PassInfo &pi : passes) {
+            if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.steps_at,
+                                   (const SubLaunch *)(dev + pi.subs_at), pi.n_subs, b0, b1) != hipSuccess)
                 return HOP_ERR_DEVICE;
         }
-        std::vector<DevEntry> top(mp.top.size());
-        for (size_t i = 0; i < top.size(); ++i) top[i] = resolve(mp.top[i], partials, part_bytes, b0);
-        const DevEntry *dev_top = nullptr;
-        if ((int)top.size() > kInlineEntries) {
-            dev_top = (const DevEntry *)ws_.stage(top.data(), top.size() * sizeof(DevEntry));
-            if (!dev_top) return HOP_ERR_NOMEM;
-        }
-        hipError_t e = launch_reduce(stream_, dtype_, op_, mp.top_depth, top.data(), dev_top, (int)top.size(),
-                                     dsts_[0], b0, b1);
+        hipError_t e = launch_reduce(stream_, dtype_, op_, mp.top_depth, blob.data() + top_at, dev + top_at,
+                                     (int)mp.top.size(), dsts_[0], b0, b1);
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     }
 

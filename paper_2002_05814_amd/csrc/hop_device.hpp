@@ -161,6 +161,29 @@ typedef const DevEntry __attribute__((address_space(4))) *prog_ptr;
 // The broadcast's destination table is read the same way.
 typedef void *const __attribute__((address_space(4))) *table_ptr;
 
+// G consecutive program steps: all G*VPT loads are issued before the first value
+// is consumed, then the values are folded in program order.
+template <int DT, int G, int VPT, class M, class Prog>
+__device__ __forceinline__ void run_group(M &m, const Prog prog, int t, const size_t (&off)[VPT])
+{
+    using A = typename Traits<DT>::acc_t;
+    constexpr int W = Traits<DT>::W;
+    uint4 raw[G][VPT];
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+        const void *src = prog[t + u].src;
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) raw[u][j] = ld16(src, off[j]);
+    }
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+        A x[VPT * W];
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
+        m.step(prog[t + u].ctl, x);
+    }
+}
+
 // One workgroup of THREADS lanes walks tiles of THREADS*VPT consecutive
 // 16-byte vectors (lane l owns vectors l, l+THREADS, ...: every load
 // instruction of a wave covers 1 KiB of consecutive addresses). For each tile
@@ -189,32 +212,12 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
         }
         Machine<DT, OP, D, VPT * W> m;
         int t = 0;
-        for (; t + U <= n; t += U) {
-            uint4 raw[U][VPT];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const void *src = prog[t + u].src;
-#pragma unroll
-                for (int j = 0; j < VPT; ++j) raw[u][j] = ld16(src, off[j]);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                A x[VPT * W];
-#pragma unroll
-                for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
-                m.step(prog[t + u].ctl, x);
-            }
-        }
-        for (; t < n; ++t) {
-            const void *src = prog[t].src;
-            A x[VPT * W];
-#pragma unroll
-            for (int j = 0; j < VPT; ++j) {
-                const uint4 raw = ld16(src, off[j]);
-                decode<DT>(raw, &x[j * W]);
-            }
-            m.step(prog[t].ctl, x);
-        }
+        for (; t + U <= n; t += U) run_group<DT, U, VPT>(m, prog, t, off);
+        // what is left is taken in halving groups so that it stays in flight together too
+        if (U > 8 && t + 8 <= n) { run_group<DT, 8, VPT>(m, prog, t, off); t += 8; }
+        if (U > 4 && t + 4 <= n) { run_group<DT, 4, VPT>(m, prog, t, off); t += 4; }
+        if (U > 2 && t + 2 <= n) { run_group<DT, 2, VPT>(m, prog, t, off); t += 2; }
+        if (U > 1 && t < n) { run_group<DT, 1, VPT>(m, prog, t, off); t += 1; }
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
             const uint4 out = encode<DT>(&m.acc[0][j * W]);

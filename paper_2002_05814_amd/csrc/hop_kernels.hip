@@ -35,9 +35,9 @@ template <int DT, int D> struct VecPerLane {
 };
 
 // Launches that cover few tiles (small objects, short chunk runs) cannot fill the
-// chip with 4 KiB tiles; they use 1 KiB tiles (one vector per lane) with 8 sources
+// chip with 4 KiB tiles; they use 1 KiB tiles (one vector per lane) with 16 sources
 // in flight per lane instead, which shortens the dependent-load chain per wave.
-constexpr int kSmallUnroll = 8;
+constexpr int kSmallUnroll = 16;
 constexpr size_t kSmallLaunchTiles = 2048;   // below this many 4 KiB tiles the small shape is used
 
 struct Launcher {
@@ -84,7 +84,7 @@ int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-           "workgroup (1 KiB tiles, unroll 8 below 2048 tiles), nontemporal loads+stores, programs <= 32 steps in "
+           "workgroup (1 KiB tiles, unroll 16 below 2048 tiles), nontemporal loads+stores, programs <= 32 steps in "
            "kernel arguments; "
            "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal";
 }
