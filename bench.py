@@ -95,8 +95,10 @@ def main():
     hop.lib()                                   # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
 
-    def run_workload(cfg, steps, warmup):
+    def run_workload(cfg, steps, warmup, no_fail=False):
         w = workloads.WORKLOADS[cfg]
+        if no_fail:
+            w = w.scaled(w.object_bytes, fail={}, name=w.name + "_without_failure")
         objs = workloads.make_objects(w, device=dev)
         order, fm = w.ready_order(), w.fail_mask()
         n_out = max(1, w.n_dst)
@@ -180,8 +182,8 @@ def main():
         extra = {}
         del objs, dsts
         torch.cuda.empty_cache()
-        for cfg in (1, 3, 4, 5):
-            wk, o2, _, d2, rs = run_workload(cfg, max(5, args.steps // 5), 2)
+        for cfg, no_fail in ((1, False), (3, False), (4, False), (4, True), (5, False)):
+            wk, o2, _, d2, rs = run_workload(cfg, max(5, args.steps // 5), 2, no_fail)
             for opn, rr in rs.items():
                 extra["%s/%s" % (wk.name, opn)] = {"GB/s": round(rr["gbs"], 2), "ms": round(rr["ms"], 5),
                                                   "frac_of_hbm_peak": round(rr["gbs"] / HBM_PEAK_GBS, 4),
