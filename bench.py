@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B
 MEASURED_TRAFFIC = {
     "workload": "cfg2_async_sgd",
     "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile "
-                     "per workgroup (1 KiB tiles, unroll 16 below 2048 tiles), nontemporal loads+stores, programs <= 32 "
+                     "per workgroup (1 KiB tiles, unroll 8 below 2048 tiles), nontemporal loads+stores, programs <= 32 "
                      "steps in kernel arguments; "
                      "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal",
     "bytes": 872458034,

@@ -171,6 +171,23 @@ int hop_session_ready(hop_session_t *s, int obj, int64_t chunks_ready_total);
  * goes to the next waiting object (else stays empty). */
 int hop_session_fail(hop_session_t *s, int obj);
 
+/* Scheduling policy. min_steps = 0 (default): an output chunk is produced by one
+ * launch once all its inputs are present (least traffic). min_steps = m >= 1:
+ * a chunk also advances whenever at least m further steps of its program have
+ * become runnable, its accumulators being saved in device scratch in between
+ * (4 bytes per element and live level), so that work overlaps the wait for
+ * late participants and little is left to do when the last one arrives
+ * (section 3.4.2: progress with a subset of the objects). Results are
+ * bit-identical in both modes. */
+int hop_session_set_eager(hop_session_t *s, int min_steps);
+
+/* Number of leading output chunks that are final in dst as far as the work
+ * enqueued so far goes (a later failure can take chunks back). This is what a
+ * downstream consumer on the same stream may read, e.g. a second session that
+ * takes dst as one of its sources (composed Reduce, section 3.4.2):
+ * hop_session_ready(next, obj, hop_session_chunks_final(s)). */
+int64_t hop_session_chunks_final(hop_session_t *s);
+
 /* Ends the session: participants that have not delivered every chunk are
  * treated as failed, remaining work is enqueued, info (may be NULL) is
  * filled, the session is freed. Returns HOP_OK / HOP_PARTIAL or an error
@@ -182,8 +199,9 @@ int hop_session_finish(hop_session_t *s, hop_info_t *info);
  * scheduler as hop_reduce on the same arguments but enqueues nothing on any
  * device (no pointer is dereferenced; objects are named by index).
  *
- * Launch l re-computes output chunks [chunk_begin, chunk_end) by evaluating
- * program entries [entry_begin, entry_end) for each element:
+ * Launch l works on output chunks [chunk_begin, chunk_end) by evaluating steps
+ * [step_begin, step_end) of the program entries[entry_begin, entry_end) for
+ * each element (hop_reduce always runs whole programs: step_begin = 0, final):
  *   SET  : acc[level] = x            (x = the element of object `obj`)
  *   else : acc[level] = acc[level] (op) x
  *   then n_fold times: acc[level-1] = acc[level-1] (op) acc[level]; --level
@@ -194,13 +212,29 @@ int hop_session_finish(hop_session_t *s, hop_info_t *info);
  * the arrays are filled up to capacity).
  */
 typedef struct { int32_t obj; uint8_t level; uint8_t set; uint16_t n_fold; } hop_plan_entry_t;
-typedef struct { int64_t chunk_begin, chunk_end; int32_t entry_begin, entry_end; } hop_plan_launch_t;
+typedef struct {
+    int64_t chunk_begin, chunk_end;   /* output chunks the launch works on                            */
+    int32_t entry_begin, entry_end;   /* the program in force: entries[entry_begin, entry_end)         */
+    int32_t step_begin, step_end;     /* steps of that program the launch runs (0 .. program length)   */
+    int32_t final;                    /* 1: stores the result; 0: saves live_after accumulator levels  */
+    int32_t live_before, live_after;  /* accumulator levels restored before / saved after the steps    */
+    int32_t reserved;
+} hop_plan_launch_t;
 
 int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int k,
                     hop_dtype_t dtype, size_t chunk_bytes, int tree_degree,
                     const int64_t *fail_mask, hop_info_t *info,
                     hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
                     hop_plan_entry_t *entries, int entry_capacity, int *n_entries);
+
+/* The same for the event-level form: a session that enqueues nothing. Drive it
+ * with hop_session_ready / _fail / _set_eager, then collect the record (and
+ * free the session) with hop_plan_session_finish. */
+int hop_plan_session_begin(hop_session_t **s, int n, size_t object_bytes, int k, hop_dtype_t dtype,
+                           size_t chunk_bytes, int tree_degree);
+int hop_plan_session_finish(hop_session_t *s, hop_info_t *info,
+                            hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
+                            hop_plan_entry_t *entries, int entry_capacity, int *n_entries);
 
 /*
  * Host-only view of how a long program is cut for launches that cover few

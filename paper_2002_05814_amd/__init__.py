@@ -29,7 +29,8 @@ DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
           torch.float32: HOP_F32, torch.bfloat16: HOP_BF16, torch.int32: HOP_I32}
 
 EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_session_begin", "hop_session_ready",
-           "hop_session_fail", "hop_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
+           "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_chunks_final",
+           "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
            "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
 
 
@@ -50,7 +51,10 @@ class PlanEntry(ctypes.Structure):
 
 class PlanLaunch(ctypes.Structure):
     _fields_ = [("chunk_begin", ctypes.c_int64), ("chunk_end", ctypes.c_int64),
-                ("entry_begin", ctypes.c_int32), ("entry_end", ctypes.c_int32)]
+                ("entry_begin", ctypes.c_int32), ("entry_end", ctypes.c_int32),
+                ("step_begin", ctypes.c_int32), ("step_end", ctypes.c_int32),
+                ("final", ctypes.c_int32), ("live_before", ctypes.c_int32), ("live_after", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 _lib = None
@@ -77,6 +81,14 @@ def lib() -> ctypes.CDLL:
         L.hop_session_ready.argtypes = [vp, ctypes.c_int, ctypes.c_int64]
         L.hop_session_fail.argtypes = [vp, ctypes.c_int]
         L.hop_session_finish.argtypes = [vp, infop]
+        L.hop_session_set_eager.argtypes = [vp, ctypes.c_int]
+        L.hop_session_chunks_final.argtypes = [vp]
+        L.hop_session_chunks_final.restype = ctypes.c_int64
+        L.hop_plan_session_begin.argtypes = [ctypes.POINTER(vp), ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_size_t, ctypes.c_int]
+        L.hop_plan_session_finish.argtypes = [vp, infop, ctypes.POINTER(PlanLaunch), ctypes.c_int,
+                                              ctypes.POINTER(ctypes.c_int), ctypes.POINTER(PlanEntry), ctypes.c_int,
+                                              ctypes.POINTER(ctypes.c_int)]
         L.hop_plan_reduce.argtypes = [ctypes.c_int, ctypes.c_size_t, i32p, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_size_t, ctypes.c_int, i64p, infop,
                                       ctypes.POINTER(PlanLaunch), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
@@ -96,7 +108,7 @@ def lib() -> ctypes.CDLL:
         L.hop_kernel_config.argtypes = []
         L.hop_kernel_config.restype = ctypes.c_char_p
         for name in EXPORTS:
-            if name not in ("hop_workspace_bytes", "hop_strerror", "hop_kernel_config"):
+            if name not in ("hop_workspace_bytes", "hop_strerror", "hop_kernel_config", "hop_session_chunks_final"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -222,6 +234,42 @@ def hop_session_fail(session, obj):
     return lib().hop_session_fail(session, int(obj))
 
 
+def hop_session_set_eager(session, min_steps):
+    return lib().hop_session_set_eager(session, int(min_steps))
+
+
+def hop_session_chunks_final(session):
+    return int(lib().hop_session_chunks_final(session))
+
+
+def hop_plan_session_begin(n, object_bytes, k, dtype, chunk_bytes, tree_degree):
+    """Host-only session (enqueues nothing). Returns (status, handle)."""
+    h = ctypes.c_void_p()
+    rc = lib().hop_plan_session_begin(ctypes.byref(h), int(n), int(object_bytes), int(k), _code(DTYPES, dtype),
+                                      int(chunk_bytes), int(tree_degree))
+    return rc, h
+
+
+def hop_plan_session_finish(session, capacity=1 << 16):
+    """Returns (status, info, launches, entries) like hop_plan_reduce; the handle is dead afterwards."""
+    info = HopInfo()
+    nl, ne = ctypes.c_int(0), ctypes.c_int(0)
+    L = (PlanLaunch * capacity)()
+    E = (PlanEntry * capacity)()
+    rc = lib().hop_plan_session_finish(session, ctypes.byref(info), L, capacity, ctypes.byref(nl), E, capacity,
+                                       ctypes.byref(ne))
+    return rc, info.as_dict(), _launch_tuples(L, min(nl.value, capacity)), _entry_tuples(E, min(ne.value, capacity))
+
+
+def _launch_tuples(L, n):
+    return [(L[i].chunk_begin, L[i].chunk_end, L[i].entry_begin, L[i].entry_end, L[i].step_begin, L[i].step_end,
+             L[i].final, L[i].live_before, L[i].live_after) for i in range(n)]
+
+
+def _entry_tuples(E, n):
+    return [(E[i].obj, E[i].level, E[i].set, E[i].n_fold) for i in range(n)]
+
+
 def hop_session_finish(session):
     """Returns (status, info dict); the session handle is dead afterwards."""
     info = HopInfo()
@@ -231,7 +279,8 @@ def hop_session_finish(session):
 
 def hop_plan_reduce(n, object_bytes, k, dtype, chunk_bytes, tree_degree, ready_order=None, fail_mask=None):
     """Host-only schedule: (status, info, launches, entries) with launches as
-    (chunk_begin, chunk_end, entry_begin, entry_end) and entries as (obj, level, set, n_fold)."""
+    (chunk_begin, chunk_end, entry_begin, entry_end, step_begin, step_end, final, live_before, live_after)
+    and entries as (obj, level, set, n_fold)."""
     _ro, ro = _i32(ready_order)
     _fm, fm = _i64(fail_mask)
     info = HopInfo()
@@ -244,9 +293,7 @@ def hop_plan_reduce(n, object_bytes, k, dtype, chunk_bytes, tree_degree, ready_o
     E = (PlanEntry * max(ne.value, 1))()
     rc = lib().hop_plan_reduce(*args, ctypes.byref(info), L, nl.value, ctypes.byref(nl), E, ne.value,
                                ctypes.byref(ne))
-    launches = [(L[i].chunk_begin, L[i].chunk_end, L[i].entry_begin, L[i].entry_end) for i in range(nl.value)]
-    entries = [(E[i].obj, E[i].level, E[i].set, E[i].n_fold) for i in range(ne.value)]
-    return rc, info.as_dict(), launches, entries
+    return rc, info.as_dict(), _launch_tuples(L, nl.value), _entry_tuples(E, ne.value)
 
 
 def hop_plan_split(entries, min_steps, min_run):

@@ -1,19 +1,25 @@
-"""Builds libhop.so (the C-ABI reduce library) for gfx950 with hipcc, in-tree."""
+"""Builds libhop.so (the C-ABI reduce library) for gfx950 with hipcc, in-tree.
+
+The reduce kernels are instantiated once per (element type, op) pair from
+csrc/hop_kernels_inst.hip; the translation units are compiled side by side and
+linked into one shared library.
+"""
 from __future__ import annotations
 
 import os
 import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhop.so")
-SOURCES = ["hop_api.hip", "hop_kernels.hip"]
 
 # -packed-fp32-ops is switched off for the device pass (the host pass does not know the
 # feature and says so: harmless).
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fno-fast-math", "-ffp-contract=off",
     "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
@@ -27,18 +33,40 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source into paper_2002_05814_amd/libhop.so (always rebuilds)."""
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
+def _units():
+    """(source, extra flags, object name) of every translation unit."""
+    units = [("hop_api.hip", [], "hop_api.o"), ("hop_kernels.hip", [], "hop_kernels.o")]
+    for dt in range(3):
+        for op in range(3):
+            units.append(("hop_kernels_inst.hip", ["-DHOP_INST_DT=%d" % dt, "-DHOP_INST_OP=%d" % op],
+                          "hop_inst_%d_%d.o" % (dt, op)))
+    return units
+
+
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    if verbose and res.stderr:
-        print(res.stderr)
-    os.replace(tmp, LIB)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
+
+
+def build(verbose: bool = False, jobs: int | None = None) -> str:
+    """Compile every HIP source into paper_2002_05814_amd/libhop.so (always rebuilds)."""
+    jobs = jobs or max(1, min(8, os.cpu_count() or 1))
+    cc = hipcc()
+    with tempfile.TemporaryDirectory(prefix="hop_build_") as tmpdir:
+        objs = []
+        cmds = []
+        for src, extra, obj in _units():
+            out = os.path.join(tmpdir, obj)
+            objs.append(out)
+            cmds.append([cc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", out])
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            list(pool.map(lambda c: _run(c, verbose), cmds))
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        _run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp], verbose)
+        os.replace(tmp, LIB)
     return LIB
 
 

@@ -130,13 +130,20 @@ struct Shape {
 class GpuBackend : public Backend {
 public:
     GpuBackend(int device, hipStream_t stream, const void *const *objs, int n, std::vector<void *> dsts,
-               const Shape &shape, int op, int dtype)
+               const Shape &shape, int op, int dtype, int k, int64_t degree)
         : ws_(device, stream), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
-          op_(op), dtype_(dtype) {}
+          op_(op), dtype_(dtype), k_(k), degree_(degree) {}
 
-    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) override
+    ~GpuBackend() override
+    {
+        if (spill_) (void)hipFreeAsync(spill_, stream_);      // stream-ordered: after the last segment kernel
+    }
+
+    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
+               int live_before, int live_after) override
     {
         if (shape_.object_bytes == 0) return HOP_OK;
+        if (t0 > 0 || !final) return launch_segment(prog, c0, c1, t0, t1, final, live_before, live_after);
         if (dsts_.size() > 1 && !dev_extra_) {
             dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
             if (!dev_extra_) return HOP_ERR_NOMEM;
@@ -177,6 +184,47 @@ public:
     }
 
 private:
+    // Steps [t0, t1) only: accumulators come from and/or go to the spill area, one array of 4-byte
+    // accumulators per level, each as long as the object has elements. It is allocated on the
+    // stream when the first partial segment is launched and freed on the stream with the session.
+    int launch_segment(const std::vector<Entry> &prog, int64_t c0, int64_t c1, int t0, int t1, bool final,
+                       int live_before, int live_after)
+    {
+        const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
+        if (!spill_) {
+            const size_t n_elems = shape_.object_bytes / (size_t)elem_bytes(dtype_);
+            level_stride_ = (n_elems * 4 + 255) & ~(size_t)255;
+            spill_levels_ = std::min(HOP_MAX_DEPTH, full_tree_depth(k_, degree_));
+            if (hipMallocAsync((void **)&spill_, level_stride_ * (size_t)spill_levels_, stream_) != hipSuccess) {
+                spill_ = nullptr;
+                return HOP_ERR_NOMEM;
+            }
+        }
+        int depth = 1;
+        std::vector<DevEntry> steps((size_t)(t1 - t0));
+        for (int t = t0; t < t1; ++t) {
+            steps[(size_t)(t - t0)] = resolve(prog[(size_t)t], nullptr, 0, 0);
+            depth = std::max(depth, (int)prog[(size_t)t].level + 1);
+        }
+        depth = std::max(depth, std::max(live_before, live_after));
+        if (depth > spill_levels_) return HOP_ERR_DEPTH;
+        const DevEntry *dev_steps = nullptr;           // t0 == t1: only move saved accumulators to the result
+        if (!steps.empty()) {
+            dev_steps = (const DevEntry *)ws_.stage(steps.data(), steps.size() * sizeof(DevEntry));
+            if (!dev_steps) return HOP_ERR_NOMEM;
+        }
+        hipError_t e = launch_reduce_segment(stream_, dtype_, op_, depth, dev_steps, t1 - t0, dsts_[0], spill_,
+                                             level_stride_, live_before, final ? 0 : live_after, b0, b1);
+        if (e == hipSuccess && final && dsts_.size() > 1) {
+            if (!dev_extra_) {
+                dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
+                if (!dev_extra_) return HOP_ERR_NOMEM;
+            }
+            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1);
+        }
+        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+    }
+
     // Many inputs but few output tiles (the many-small-objects case): one wave per tile would walk
     // the whole program alone, so the independent subtrees are evaluated side by side first.
     // Partials are stored in the accumulation type, which for bf16 is not the element type: bf16
@@ -261,24 +309,40 @@ private:
     std::vector<const void *> objs_;
     std::vector<void *> dsts_;
     Shape shape_;
-    int op_, dtype_;
+    int op_, dtype_, k_;
+    int64_t degree_;
     std::vector<DevEntry> staging_;
     const DevEntry *dev_prog_ = nullptr;
     void *const *dev_extra_ = nullptr;
     uint64_t dev_version_ = 0;
     int depth_ = 1;
+    char *spill_ = nullptr;
+    size_t level_stride_ = 0;
+    int spill_levels_ = 0;
 };
 
 class RecordingBackend : public Backend {
 public:
-    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) override
+    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
+               int live_before, int live_after) override
     {
         if (version != version_) {
             entry_begin_ = (int32_t)entries.size();
             entries.insert(entries.end(), prog.begin(), prog.end());
             version_ = version;
         }
-        launches.push_back({c0, c1, entry_begin_, (int32_t)(entry_begin_ + prog.size())});
+        hop_plan_launch_t l;
+        l.chunk_begin = c0;
+        l.chunk_end = c1;
+        l.entry_begin = entry_begin_;
+        l.entry_end = (int32_t)(entry_begin_ + prog.size());
+        l.step_begin = t0;
+        l.step_end = t1;
+        l.final = final ? 1 : 0;
+        l.live_before = live_before;
+        l.live_after = live_after;
+        l.reserved = 0;
+        launches.push_back(l);
         return HOP_OK;
     }
     std::vector<Entry> entries;
@@ -369,7 +433,8 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
     const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
     try {
-        GpuBackend be(device, (hipStream_t)stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype);
+        GpuBackend be(device, (hipStream_t)stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype,
+                      k, d);
         Scheduler s(n, k, shape.n_chunks, d, &be);
         return replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
     } catch (const std::bad_alloc &) {
@@ -386,9 +451,24 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
 using namespace hop;
 
 struct hop_session {
-    std::unique_ptr<GpuBackend> be;
+    std::unique_ptr<GpuBackend> be;             // sessions that enqueue work
+    std::unique_ptr<RecordingBackend> rec;      // host-only sessions (hop_plan_session_begin)
     std::unique_ptr<Scheduler> sched;
 };
+
+static void copy_record(const RecordingBackend &be, hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
+                        hop_plan_entry_t *entries, int entry_capacity, int *n_entries)
+{
+    if (n_launches) *n_launches = (int)be.launches.size();
+    if (n_entries) *n_entries = (int)be.entries.size();
+    for (int i = 0; launches && i < launch_capacity && i < (int)be.launches.size(); ++i) launches[i] = be.launches[i];
+    for (int i = 0; entries && i < entry_capacity && i < (int)be.entries.size(); ++i) {
+        entries[i].obj = be.entries[i].obj;
+        entries[i].level = be.entries[i].level;
+        entries[i].set = be.entries[i].set;
+        entries[i].n_fold = be.entries[i].n_fold;
+    }
+}
 
 extern "C" {
 
@@ -457,7 +537,7 @@ int hop_session_begin(hop_session_t **s, void *dst, const void *const *objs, int
     try {
         std::unique_ptr<hop_session> h(new hop_session);
         h->be.reset(new GpuBackend(device, (hipStream_t)stream, objs, n, std::vector<void *>(1, dst), shape,
-                                   (int)op, (int)dtype));
+                                   (int)op, (int)dtype, k, d));
         h->sched.reset(new Scheduler(n, k, shape.n_chunks, d, h->be.get()));
         *s = h.release();
         return HOP_OK;
@@ -501,6 +581,54 @@ int hop_session_finish(hop_session_t *s, hop_info_t *info)
     return rc;
 }
 
+int hop_session_set_eager(hop_session_t *s, int min_steps)
+{
+    if (!s || min_steps < 0) return HOP_ERR_INVALID;
+    s->sched->set_eager(min_steps);
+    return HOP_OK;
+}
+
+int64_t hop_session_chunks_final(hop_session_t *s)
+{
+    if (!s) return HOP_ERR_INVALID;
+    return s->sched->chunks_final();
+}
+
+int hop_plan_session_begin(hop_session_t **s, int n, size_t object_bytes, int k, hop_dtype_t dtype,
+                           size_t chunk_bytes, int tree_degree)
+{
+    if (!s) return HOP_ERR_INVALID;
+    *s = nullptr;
+    Shape shape;
+    int rc = check_shape(n, object_bytes, k, HOP_SUM, (int)dtype, chunk_bytes, tree_degree, &shape);
+    if (rc < 0) return rc;
+    const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    try {
+        std::unique_ptr<hop_session> h(new hop_session);
+        h->rec.reset(new RecordingBackend);
+        h->sched.reset(new Scheduler(n, k, shape.n_chunks, d, h->rec.get()));
+        *s = h.release();
+        return HOP_OK;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_plan_session_finish(hop_session_t *s, hop_info_t *info, hop_plan_launch_t *launches, int launch_capacity,
+                            int *n_launches, hop_plan_entry_t *entries, int entry_capacity, int *n_entries)
+{
+    if (!s || !s->rec) return HOP_ERR_INVALID;
+    int rc;
+    try {
+        rc = s->sched->finish(info);
+        copy_record(*s->rec, launches, launch_capacity, n_launches, entries, entry_capacity, n_entries);
+    } catch (const std::bad_alloc &) {
+        rc = HOP_ERR_NOMEM;
+    }
+    delete s;
+    return rc;
+}
+
 int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int k, hop_dtype_t dtype,
                     size_t chunk_bytes, int tree_degree, const int64_t *fail_mask, hop_info_t *info,
                     hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
@@ -515,15 +643,7 @@ int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int 
         RecordingBackend be;
         Scheduler s(n, k, shape.n_chunks, d, &be);
         rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
-        if (n_launches) *n_launches = (int)be.launches.size();
-        if (n_entries) *n_entries = (int)be.entries.size();
-        for (int i = 0; launches && i < launch_capacity && i < (int)be.launches.size(); ++i) launches[i] = be.launches[i];
-        for (int i = 0; entries && i < entry_capacity && i < (int)be.entries.size(); ++i) {
-            entries[i].obj = be.entries[i].obj;
-            entries[i].level = be.entries[i].level;
-            entries[i].set = be.entries[i].set;
-            entries[i].n_fold = be.entries[i].n_fold;
-        }
+        copy_record(be, launches, launch_capacity, n_launches, entries, entry_capacity, n_entries);
         return rc;
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;

@@ -153,6 +153,35 @@ __device__ __forceinline__ void st16(void *base, size_t byte_off, const uint4 &v
     __builtin_nontemporal_store(r, (u32x4 *)((char *)base + byte_off));
 }
 
+// Accumulator-typed values of one 16-byte source vector in the spill area: the
+// vector at object byte offset `off` holds W elements, whose W accumulators sit at
+// byte offset off / element size * 4 of a level's array (W * 4 bytes: 16 for
+// 32-bit elements, 32 for bf16).
+template <int DT> __device__ __forceinline__ void load_acc(const char *level_base, size_t off, typename Traits<DT>::acc_t *x)
+{
+    constexpr int W = Traits<DT>::W;
+    const size_t o = off / Traits<DT>::ES * 4;
+#pragma unroll
+    for (int q = 0; q < W / 4; ++q) {
+        const uint4 r = ld16(level_base, o + 16 * q);
+        x[4 * q + 0] = __builtin_bit_cast(typename Traits<DT>::acc_t, r.x);
+        x[4 * q + 1] = __builtin_bit_cast(typename Traits<DT>::acc_t, r.y);
+        x[4 * q + 2] = __builtin_bit_cast(typename Traits<DT>::acc_t, r.z);
+        x[4 * q + 3] = __builtin_bit_cast(typename Traits<DT>::acc_t, r.w);
+    }
+}
+template <int DT> __device__ __forceinline__ void store_acc(char *level_base, size_t off, const typename Traits<DT>::acc_t *x)
+{
+    constexpr int W = Traits<DT>::W;
+    const size_t o = off / Traits<DT>::ES * 4;
+#pragma unroll
+    for (int q = 0; q < W / 4; ++q) {
+        const uint4 r = make_uint4(__builtin_bit_cast(uint32_t, x[4 * q + 0]), __builtin_bit_cast(uint32_t, x[4 * q + 1]),
+                                   __builtin_bit_cast(uint32_t, x[4 * q + 2]), __builtin_bit_cast(uint32_t, x[4 * q + 3]));
+        st16(level_base, o + 16 * q, r);
+    }
+}
+
 // The program is read through the constant address space: it is never written
 // while a kernel runs, so its steps can be fetched with scalar loads and held
 // in SGPRs (a plain global pointer would make the compiler assume that the
@@ -190,7 +219,14 @@ __device__ __forceinline__ void run_group(M &m, const Prog prog, int t, const si
 // the program is run in groups of U steps: the U*VPT loads of a group are all
 // issued before the first of them is consumed, then the group's values are
 // folded in program order. D = accumulator levels held in registers.
-template <int DT, int OP, int D, int VPT, int U, int THREADS, class Prog>
+//
+// SEG: the launch runs only a segment of a program. Accumulator levels
+// [0, n_restore) are first read back from the spill area (where the previous
+// segment on these chunks left them); afterwards either levels [0, n_save) are
+// written to the spill area (more steps will follow) or, when n_save is 0, the
+// result is stored like in a whole-program launch. The spill area holds one
+// object-sized array of accumulator-typed values per level.
+template <int DT, int OP, int D, int VPT, int U, int THREADS, bool SEG = false, class Prog>
 __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog, const int n, void *const dst)
 {
     using T = Traits<DT>;
@@ -211,6 +247,15 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
             off[j] = a.byte_begin + (live[j] ? v : a.n_vec - 1) * 16;
         }
         Machine<DT, OP, D, VPT * W> m;
+        if (SEG) {
+#pragma unroll
+            for (int L = 0; L < D; ++L) {
+                if (L < a.n_restore) {
+#pragma unroll
+                    for (int j = 0; j < VPT; ++j) load_acc<DT>(a.spill + (size_t)L * a.level_stride, off[j], &m.acc[L][j * W]);
+                }
+            }
+        }
         int t = 0;
         for (; t + U <= n; t += U) run_group<DT, U, VPT>(m, prog, t, off);
         // what is left is taken in halving groups so that it stays in flight together too
@@ -218,10 +263,21 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
         if (U > 4 && t + 4 <= n) { run_group<DT, 4, VPT>(m, prog, t, off); t += 4; }
         if (U > 2 && t + 2 <= n) { run_group<DT, 2, VPT>(m, prog, t, off); t += 2; }
         if (U > 1 && t < n) { run_group<DT, 1, VPT>(m, prog, t, off); t += 1; }
+        if (SEG && a.n_save > 0) {
 #pragma unroll
-        for (int j = 0; j < VPT; ++j) {
-            const uint4 out = encode<DT>(&m.acc[0][j * W]);
-            if (live[j]) st16(dst, off[j], out);
+            for (int L = 0; L < D; ++L) {
+                if (L < a.n_save) {
+#pragma unroll
+                    for (int j = 0; j < VPT; ++j)
+                        if (live[j]) store_acc<DT>(a.spill + (size_t)L * a.level_stride, off[j], &m.acc[L][j * W]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {
+                const uint4 out = encode<DT>(&m.acc[0][j * W]);
+                if (live[j]) st16(dst, off[j], out);
+            }
         }
     }
 
@@ -229,11 +285,23 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
     if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail) {
         const size_t off = a.byte_begin + a.n_vec * 16 + (size_t)threadIdx.x * T::ES;
         Machine<DT, OP, D, 1> m;
+        const size_t acc_off = off / T::ES * sizeof(A);
+        if (SEG) {
+#pragma unroll
+            for (int L = 0; L < D; ++L)
+                if (L < a.n_restore) m.acc[L][0] = *(const A *)(a.spill + (size_t)L * a.level_stride + acc_off);
+        }
         for (int t = 0; t < n; ++t) {
             A x[1] = {load_elem<DT>(prog[t].src, off)};
             m.step(prog[t].ctl, x);
         }
-        store_elem<DT>(dst, off, m.acc[0][0]);
+        if (SEG && a.n_save > 0) {
+#pragma unroll
+            for (int L = 0; L < D; ++L)
+                if (L < a.n_save) *(A *)(a.spill + (size_t)L * a.level_stride + acc_off) = m.acc[L][0];
+        } else {
+            store_elem<DT>(dst, off, m.acc[0][0]);
+        }
     }
 }
 
@@ -250,6 +318,13 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
     } else {
         reduce_body<DT, OP, D, VPT, U, THREADS>(a, prog, a.n_entries, a.dst);
     }
+}
+
+// A segment of a program in device memory, with accumulators restored from and/or saved to the spill area.
+template <int DT, int OP, int D, int VPT, int U, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel_seg(ReduceArgs a)
+{
+    reduce_body<DT, OP, D, VPT, U, THREADS, true>(a, (prog_ptr)(uintptr_t)a.prog, a.n_entries, a.dst);
 }
 
 // Program inside the kernel arguments.

@@ -42,6 +42,11 @@ struct ReduceArgs {
     size_t n_vec;              // full 16-byte vectors in the range
     int n_tail;                // elements after the last full vector (object end only)
     const SubLaunch *subs;     // device table of gridDim.y sub-programs, or null (whole program -> dst)
+    // segment launches only (reduce_kernel_seg): where accumulators live between segments
+    char *spill;               // level L's array starts at spill + L * level_stride
+    size_t level_stride;
+    int n_restore;             // levels read back before the first step
+    int n_save;                // levels written after the last step; 0 = store the result to dst instead
 };
 
 struct ReduceArgsInline {
@@ -71,6 +76,14 @@ const char *kernel_config();
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
                          const DevEntry *dev_prog, int n_entries, void *dst, size_t byte_begin,
                          size_t byte_end);
+
+// Steps [0, n_entries) of dev_prog as one segment of a longer program: n_restore accumulator
+// levels are read back from the spill area first; then n_save levels are written to it, or, if
+// n_save is 0, the result goes to dst. The spill area holds, per level, one array of 4-byte
+// accumulators indexed like the object's elements; levels are level_stride bytes apart.
+hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
+                                 int n_entries, void *dst, char *spill, size_t level_stride, int n_restore,
+                                 int n_save, size_t byte_begin, size_t byte_end);
 
 // The same for n_subs independent sub-programs at once: dev_subs[s] names the steps
 // (inside dev_prog) and the destination of sub-program s; every sub-program covers the

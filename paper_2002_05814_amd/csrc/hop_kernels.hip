@@ -12,6 +12,7 @@
 
 #include "hop_device.hpp"
 #include "hop_kernels.h"
+#include "hop_launch_shape.h"
 
 namespace hop {
 
@@ -19,58 +20,7 @@ namespace hop {
 // launch helpers
 // ----------------------------------------------------------------------------
 
-// Launch shape, from sweeps on MI355X over the 64 MiB x 12, 256 MiB x 31 and
-// 16 MiB x 64 workloads: one wave per workgroup, each wave owning a tile of
-// 4 KiB per source (4 vectors per lane, all four loads of a source in flight
-// together), one tile per workgroup so that the dispatcher keeps every CU
-// supplied with fresh waves. Deeper accumulator stacks take fewer vectors per
-// lane to stay inside the register file.
-constexpr int kThreads = 64;
-constexpr int kUnroll = 1;
 constexpr size_t kMaxGrid = 1u << 22;
-
-template <int DT, int D> struct VecPerLane {
-    static constexpr int W = Traits<DT>::W;
-    static constexpr int value = (D * W <= 32) ? 4 : (D * W <= 64) ? 2 : 1;
-};
-
-// Launches that cover few tiles (small objects, short chunk runs) cannot fill the
-// chip with 4 KiB tiles; they use 1 KiB tiles (one vector per lane) with 16 sources
-// in flight per lane instead, which shortens the dependent-load chain per wave.
-constexpr int kSmallUnroll = 16;
-constexpr size_t kSmallLaunchTiles = 2048;   // below this many 4 KiB tiles the small shape is used
-
-struct Launcher {
-    void (*dev)(ReduceArgs);
-    void (*inl)(ReduceArgsInline);
-    void (*dev_small)(ReduceArgs);
-    void (*inl_small)(ReduceArgsInline);
-    int vpt;
-};
-
-template <int DT, int OP, int D> static Launcher make_launcher()
-{
-    constexpr int V = VecPerLane<DT, D>::value;
-    return {reduce_kernel<DT, OP, D, V, kUnroll, kThreads>, reduce_kernel_inline<DT, OP, D, V, kUnroll, kThreads>,
-            reduce_kernel<DT, OP, D, 1, kSmallUnroll, kThreads>,
-            reduce_kernel_inline<DT, OP, D, 1, kSmallUnroll, kThreads>, V};
-}
-template <int DT, int OP> static Launcher pick_depth(int depth)
-{
-    if (depth <= 1) return make_launcher<DT, OP, 1>();
-    if (depth <= 2) return make_launcher<DT, OP, 2>();
-    if (depth <= 4) return make_launcher<DT, OP, 4>();
-    if (depth <= 8) return make_launcher<DT, OP, 8>();
-    return make_launcher<DT, OP, 16>();
-}
-template <int DT> static Launcher pick_op(int op, int depth)
-{
-    switch (op) {
-    case HOP_SUM: return pick_depth<DT, HOP_SUM>(depth);
-    case HOP_MIN: return pick_depth<DT, HOP_MIN>(depth);
-    default:      return pick_depth<DT, HOP_MAX>(depth);
-    }
-}
 
 static unsigned grid_for(size_t n_vec, size_t tile_vecs)
 {
@@ -84,22 +34,26 @@ int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-           "workgroup (1 KiB tiles, unroll 16 below 2048 tiles), nontemporal loads+stores, programs <= 32 steps in "
+           "workgroup (1 KiB tiles, unroll 8 below 2048 tiles), nontemporal loads+stores, programs <= 32 steps in "
            "kernel arguments; "
            "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal";
 }
 
 static Launcher pick(int dtype, int op, int depth)
 {
-    switch (dtype) {
-    case HOP_F32:  return pick_op<HOP_F32>(op, depth);
-    case HOP_BF16: return pick_op<HOP_BF16>(op, depth);
-    default:       return pick_op<HOP_I32>(op, depth);
-    }
+    typedef Launcher (*fn)(int);
+    static const fn table[3][3] = {{launcher_0_0, launcher_0_1, launcher_0_2},
+                                   {launcher_1_0, launcher_1_1, launcher_1_2},
+                                   {launcher_2_0, launcher_2_1, launcher_2_2}};
+    return table[dtype][op](depth);
 }
 
 static void fill_range(ReduceArgs &a, int dtype, size_t byte_begin, size_t byte_end)
 {
+    a.spill = nullptr;
+    a.level_stride = 0;
+    a.n_restore = 0;
+    a.n_save = 0;
     a.byte_begin = byte_begin;
     a.n_vec = (byte_end - byte_begin) / 16;
     a.n_tail = (int)(((byte_end - byte_begin) % 16) / elem_bytes(dtype));
@@ -127,6 +81,30 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
         if (!dev_prog) return hipErrorInvalidValue;
         hipLaunchKernelGGL(small ? l.dev_small : l.dev, dim3(grid), dim3(kThreads), 0, stream, a.base);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
+                                 int n_entries, void *dst, char *spill, size_t level_stride, int n_restore,
+                                 int n_save, size_t byte_begin, size_t byte_end)
+{
+    if (byte_end <= byte_begin) return hipSuccess;
+    if ((n_entries > 0 && !dev_prog) || n_entries < 0 || (n_entries == 0 && n_restore < 1) || n_restore < 0 || n_save < 0 || n_restore > depth || n_save > depth ||
+        ((n_restore > 0 || n_save > 0) && !spill))
+        return hipErrorInvalidValue;
+    const Launcher l = pick(dtype, op, depth);
+    ReduceArgs a;
+    a.prog = dev_prog;
+    a.n_entries = n_entries;
+    a.dst = dst;
+    a.subs = nullptr;
+    fill_range(a, dtype, byte_begin, byte_end);
+    a.spill = spill;
+    a.level_stride = level_stride;
+    a.n_restore = n_restore;
+    a.n_save = n_save;
+    const unsigned grid = grid_for(a.n_vec, (size_t)kThreads * l.vpt);
+    hipLaunchKernelGGL(l.seg, dim3(grid), dim3(kThreads), 0, stream, a);
     return hipGetLastError();
 }
 

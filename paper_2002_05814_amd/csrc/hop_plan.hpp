@@ -78,7 +78,8 @@ struct Tree {
 };
 
 // Flattens the tree expression over the current occupants (-1 = empty
-// position, contributes nothing) into accumulator steps. A node combines,
+// position, contributes nothing; -2 = position not taken yet, shapes the
+// program like an object) into accumulator steps. A node combines,
 // left to right, [first child's partial, its own object, other children's
 // partials]; the first child's partial is built in the parent's own
 // accumulator, every later child in the next level and folded in when done.
@@ -90,7 +91,7 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
     if (tr.d == 1 || tr.k == 1) {
         // chain: plain left fold in arrival order
         for (int t = 0; t < tr.k; ++t) {
-            if (occupant[t] < 0) continue;
+            if (occupant[t] == -1) continue;
             out.push_back({occupant[t], 0, (uint8_t)out.empty(), 0});
         }
         return out.empty() ? 0 : 1;
@@ -103,7 +104,7 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
             int64_t c1 = tr.child(j, 1);
             if (c1 >= 0) started = emit(c1, level);
             int32_t o = occ[tr.slot_of_node[j]];
-            if (o >= 0) {
+            if (o != -1) {                    // an object, or a position still to be taken
                 out.push_back({o, (uint8_t)level, (uint8_t)!started, 0});
                 depth = std::max(depth, level + 1);
                 started = true;
@@ -231,13 +232,31 @@ inline bool plan_passes(const std::vector<Entry> &prog, size_t min_steps, int mi
     return mp.n_passes > 0;
 }
 
-// Where the scheduler sends work. launch() must make output chunks
-// [c0, c1) equal to the program's value; programs are identified by a
-// version that changes whenever the occupants change.
+// Accumulator levels a tree needs when every position is taken (holes only lower it).
+inline int full_tree_depth(int k, int64_t d)
+{
+    Tree tr;
+    tr.build(k, d);
+    std::vector<int32_t> occ(k, 0);
+    std::vector<Entry> prog;
+    return compile_program(tr, occ, prog);
+}
+
+// Where the scheduler sends work. launch() runs steps [t0, t1) of prog on output
+// chunks [c0, c1). If t0 > 0 the accumulators that the previous launch on those
+// chunks saved are restored first (live_before levels); if `final` the result
+// is stored, otherwise live_after accumulator levels are saved for the next
+// segment. Programs are identified by a version that changes whenever the
+// occupants change; steps below t0 are the same in the version that ran them.
 struct Backend {
     virtual ~Backend() {}
-    virtual int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1) = 0;
+    virtual int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1,
+                       bool final, int live_before, int live_after) = 0;
 };
+
+// Marker for a tree position that nobody has taken yet while arrivals are still
+// possible: it shapes the program like an object, but no step can run past it.
+constexpr int32_t kPending = -2;
 
 class Scheduler {
 public:
@@ -246,7 +265,14 @@ public:
           ready_(n, 0), state_(n, UNSEEN), slot_of_obj_(n, -1), occupant_(k, -1)
     {
         tree_.build(k, degree);
+        done_.push_back({C_, 0, 0, false});
     }
+
+    // 0 (default): a chunk is produced in one launch once all its inputs are present.
+    // m >= 1: a chunk also advances through the program whenever at least m further steps
+    // have become runnable, saving its accumulators in between (work overlaps the wait
+    // for late participants, at the price of extra traffic).
+    void set_eager(int min_steps) { eager_ = min_steps < 0 ? 0 : min_steps; }
 
     // Object obj has chunks [0, c) ready. First call = arrival.
     int on_ready(int obj, int64_t c)
@@ -261,7 +287,6 @@ public:
                 holes_.erase(holes_.begin());
                 place(obj, t);
                 info_.n_replaced++;
-                invalidate();
             } else if (next_free_ < k_) {
                 place(obj, next_free_++);
             } else {
@@ -284,7 +309,6 @@ public:
         slot_of_obj_[obj] = -1;
         occupant_[t] = -1;
         version_++;
-        invalidate();
         while (!pool_.empty() && state_[pool_.front()] == FAILED) pool_.pop_front();
         if (!pool_.empty()) {
             int j = pool_.front();
@@ -297,31 +321,73 @@ public:
         return HOP_OK;
     }
 
-    // Launch every output chunk whose inputs are all present.
+    // Launch whatever the readiness reported so far allows.
     int pump()
     {
-        if (next_free_ < k_ && !closing_) return HOP_OK;     // tree still filling: later arrivals belong in front
-        int64_t frontier = C_;
-        int live = 0;
-        for (int t = 0; t < k_; ++t) {
-            int o = occupant_[t];
-            if (o < 0) continue;
-            live++;
-            frontier = std::min(frontier, ready_[o]);
-        }
-        if (live == 0 || frontier <= launched_) return HOP_OK;
-        if (compiled_version_ != version_) {
-            int depth = compile_program(tree_, occupant_, prog_);
-            compiled_version_ = version_;
-            info_.stack_depth = std::max(info_.stack_depth, depth);
-            if (depth > HOP_MAX_DEPTH) return HOP_ERR_DEPTH;
-        }
-        int64_t redo = std::max<int64_t>(0, std::min(frontier, redo_upto_) - launched_);
-        int rc = be_->launch(prog_, version_, launched_, frontier);
+        int rc = recompile();
         if (rc < 0) return rc;
-        info_.chunks_redone += redo * (int64_t)prog_.size();
-        info_.n_launches++;
-        launched_ = frontier;
+        const int n_steps = (int)prog_.size();
+        if (n_steps == 0) return HOP_OK;
+        // How far can each chunk go? Steps run in order, so chunk c can run t steps iff the
+        // objects of steps 0..t-1 all have chunk c. With m[t] = min ready count over steps
+        // 0..t (non-increasing in t), chunks [m[t], m[t-1]) can run exactly t steps.
+        std::vector<Stair> target;
+        {
+            std::vector<int64_t> m(n_known_);
+            int64_t run = C_;
+            for (int t = 0; t < n_known_; ++t) {
+                run = std::min(run, ready_[prog_[t].obj]);
+                m[t] = run;
+            }
+            int64_t lo = 0;
+            for (int t = n_known_; t >= 0; --t) {
+                const int64_t hi = (t == 0) ? C_ : m[t - 1];
+                if (hi > lo) { target.push_back({hi, t, 0, false}); lo = hi; }
+            }
+        }
+        // Walk the two staircases together; every piece where progress is allowed is a launch.
+        struct Piece { int64_t c0, c1; int t0, t1; int64_t redo; };
+        std::vector<Piece> pieces;
+        std::vector<Stair> next;
+        size_t i = 0, j = 0;
+        int64_t c = 0;
+        while (c < C_) {
+            const int64_t end = std::min(done_[i].chunk_end, target[j].chunk_end);
+            const int t0 = done_[i].t;
+            int t1 = std::max(t0, target[j].t);
+            const bool complete = (t1 == n_steps);
+            if (t1 > t0 && !(complete || (eager_ > 0 && t1 - t0 >= eager_))) t1 = t0;
+            int redo = done_[i].redo;
+            bool stored = done_[i].stored;
+            // a launch if steps can run, or if every step has run but the result still sits in
+            // saved accumulators (the program got shorter after these chunks had run ahead)
+            if (t1 > t0 || (t0 == n_steps && !stored)) {
+                const int64_t again = std::max(0, std::min(t1, redo) - t0);
+                if (!pieces.empty() && pieces.back().c1 == c && pieces.back().t0 == t0 && pieces.back().t1 == t1) {
+                    pieces.back().c1 = end;
+                    pieces.back().redo += again * (end - c);
+                } else {
+                    pieces.push_back({c, end, t0, t1, again * (end - c)});
+                }
+                if (t1 >= redo) redo = 0;
+                stored = (t1 == n_steps);
+            }
+            if (!next.empty() && next.back().t == t1 && next.back().redo == redo && next.back().stored == stored)
+                next.back().chunk_end = end;
+            else
+                next.push_back({end, t1, redo, stored});
+            c = end;
+            if (done_[i].chunk_end == end) ++i;
+            if (target[j].chunk_end == end) ++j;
+        }
+        for (const Piece &p : pieces) {
+            const bool final = (p.t1 == n_steps);
+            rc = be_->launch(prog_, version_, p.c0, p.c1, p.t0, p.t1, final, live_levels(p.t0), final ? 0 : live_levels(p.t1));
+            if (rc < 0) return rc;
+            info_.n_launches++;
+            info_.chunks_redone += p.redo;
+        }
+        done_.swap(next);
         return HOP_OK;
     }
 
@@ -329,13 +395,16 @@ public:
     // positions stay empty, the rest of the output is produced.
     int finish(hop_info_t *info)
     {
-        closing_ = true;
         for (int obj : pool_)
             if (state_[obj] == STREAMING) { state_[obj] = FAILED; info_.n_failed_seen++; }
         for (int t = 0; t < k_; ++t) {
             int o = occupant_[t];
             if (o >= 0 && state_[o] == STREAMING) on_fail(o);
             // a replacement pulled from the pool is complete (incomplete ones were just failed)
+        }
+        if (!closing_) {
+            closing_ = true;
+            if (next_free_ < k_) version_++;        // positions nobody took are empty for good
         }
         int rc = pump();
         int live = 0;
@@ -348,12 +417,22 @@ public:
         return live < k_ ? HOP_PARTIAL : HOP_OK;
     }
 
+    // Output chunks [0, result) are final in the destination (as far as enqueued work goes).
+    int64_t chunks_final() const
+    {
+        if (prog_.empty() || compiled_version_ != version_) return 0;
+        return done_.front().stored ? done_.front().chunk_end : 0;
+    }
+
     bool arrived(int obj) const { return state_[obj] != UNSEEN; }
     bool alive(int obj) const { return state_[obj] == STREAMING || state_[obj] == COMPLETE; }
     const Tree &tree() const { return tree_; }
 
 private:
     enum State : uint8_t { UNSEEN, STREAMING, COMPLETE, FAILED };
+    // chunks [previous chunk_end, chunk_end) have run t steps of the program; redo > 0: they had
+    // run that many steps of an earlier program whose result was thrown away
+    struct Stair { int64_t chunk_end; int t; int redo; bool stored; };
 
     void place(int obj, int t)
     {
@@ -362,11 +441,52 @@ private:
         version_++;
     }
 
-    // The occupants changed: everything produced so far contained the old set.
-    void invalidate()
+    // accumulator levels alive between steps t-1 and t
+    int live_levels(int t) const
     {
-        redo_upto_ = std::max(redo_upto_, launched_);
-        launched_ = 0;
+        if (t <= 0) return 0;
+        return (int)prog_[t - 1].level - (int)prog_[t - 1].n_fold + 1;
+    }
+
+    // The occupants changed: rebuild the program. Chunks keep what they have computed as long
+    // as the steps they ran are unchanged (a common prefix of the old and the new program);
+    // chunks that ran past the first difference start over (section 3.5.2: every partial
+    // result that contains the failed object is cleared, the others are kept).
+    int recompile()
+    {
+        if (compiled_version_ == version_) return HOP_OK;
+        std::vector<int32_t> occ(occupant_);
+        if (!closing_)
+            for (int t = next_free_; t < k_; ++t) occ[t] = kPending;
+        std::vector<Entry> np;
+        const int depth = compile_program(tree_, occ, np);
+        info_.stack_depth = std::max(info_.stack_depth, depth);
+        if (depth > HOP_MAX_DEPTH) return HOP_ERR_DEPTH;
+        int keep = 0;
+        while (keep < (int)prog_.size() && keep < (int)np.size() && np[keep].obj != kPending &&
+               prog_[keep].obj == np[keep].obj && prog_[keep].level == np[keep].level &&
+               prog_[keep].set == np[keep].set && prog_[keep].n_fold == np[keep].n_fold)
+            ++keep;
+        // a chunk whose result was stored saved no accumulators: it cannot be continued either,
+        // unless nothing changed at all
+        const bool unchanged = keep == (int)prog_.size() && keep == (int)np.size();
+        std::vector<Stair> next;
+        for (Stair st : done_) {
+            if (st.t > keep || (st.stored && !unchanged)) {
+                st.redo = std::max(st.redo, st.t);
+                st.t = 0;
+                st.stored = false;
+            }
+            if (!next.empty() && next.back().t == st.t && next.back().redo == st.redo && next.back().stored == st.stored)
+                next.back().chunk_end = st.chunk_end;
+            else next.push_back(st);
+        }
+        done_.swap(next);
+        prog_.swap(np);
+        n_known_ = 0;
+        while (n_known_ < (int)prog_.size() && prog_[n_known_].obj != kPending) ++n_known_;
+        compiled_version_ = version_;
+        return HOP_OK;
     }
 
     int n_, k_;
@@ -380,10 +500,11 @@ private:
     std::set<int> holes_;                // positions emptied by a failure with nobody waiting
     int next_free_ = 0;                  // positions [0, next_free_) have been handed out
     bool closing_ = false;
-    int64_t launched_ = 0;               // output chunks [0, launched_) hold the current occupants' result
-    int64_t redo_upto_ = 0;              // chunks below this were produced at least once before
+    int eager_ = 0;
+    std::vector<Stair> done_;            // progress of every chunk through prog_
     uint64_t version_ = 1, compiled_version_ = 0;
     std::vector<Entry> prog_;
+    int n_known_ = 0;                    // steps before the first pending position
     hop_info_t info_ = {};
 };
 

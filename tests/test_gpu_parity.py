@@ -238,11 +238,12 @@ def test_broadcast_paper_object_and_ragged_sizes():
 
 # ------------------------------------------------------------------ event-level sessions
 
-def session_replay(objs, dst, k, op, dtype, chunk, d, order, fm, C, fine):
+def session_replay(objs, dst, k, op, dtype, chunk, d, order, fm, C, fine, eager=0):
     """Drives the session API with the same timeline hop_reduce replays, either in bulk
     (per failure step) or chunk by chunk."""
     rc, s = hop.hop_session_begin(dst, objs, k, op, dtype, chunk, d)
     assert rc == hop.HOP_OK
+    assert hop.hop_session_set_eager(s, eager) == hop.HOP_OK
     n = len(objs)
     limit = [C if (fm is None or fm[i] < 0 or fm[i] >= C) else int(fm[i]) for i in range(n)]
     arrival = [int(i) for i in order if limit[i] > 0]
@@ -289,6 +290,78 @@ def test_session_events_match_oracle(fine):
             assert info["k_eff"] == k_eff
             if fine and not bad.any() and C > 1:
                 assert info["n_launches"] == C          # one launch per chunk as each becomes complete
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i32"])
+def test_session_eager_segments_match_oracle(dtype):
+    # objects arrive whole, one after the other (object-by-object timeline), some failing part-way:
+    # with the eager policy every arrival is folded into saved accumulators at once; the bits must
+    # equal the fused evaluation's and the oracle's
+    rng = np.random.default_rng({"f32": 41, "bf16": 42, "i32": 43}[dtype])
+    base = workloads.WORKLOADS[{"f32": 2, "bf16": 4, "i32": 3}[dtype]]
+    es = ES[dtype]
+    for it in range(8):
+        n = int(rng.integers(2, 24))
+        k = int(rng.integers(1, n + 1))
+        d = int(rng.choice([1, 2, 3, 8]))
+        C = int(rng.integers(2, 7))
+        chunk = 16 * int(rng.integers(8, 300))
+        nbytes = (C - 1) * chunk + es * int(rng.integers(1, chunk // es + 1))
+        w = base.scaled(nbytes, chunk, n=n, k=k, tree_degree=d, order_seed=int(rng.integers(1 << 30)),
+                        data_seed=int(rng.integers(1 << 30)), fail={}, name="eager%d" % it, n_dst=0)
+        objs = workloads.make_objects(w, device=dev())
+        order = w.ready_order()
+        fm = np.full(n, -1, np.int64)
+        bad = rng.random(n) < 0.25
+        fm[bad] = rng.integers(1, C, size=int(bad.sum()))
+        eager = int(rng.integers(1, 4))
+        print("eager case", dtype, it, n, k, d, C, nbytes, eager, flush=True)
+        dst = torch.full_like(objs[0], 3)
+        rc, s = hop.hop_session_begin(dst, objs, k, "sum", dtype, chunk, d)
+        assert rc == hop.HOP_OK and hop.hop_session_set_eager(s, eager) == hop.HOP_OK
+        model_slots, pool, dead = [], [], set()
+        for i in order:                              # object-major: deliver, then (maybe) fail
+            i = int(i)
+            c = C if fm[i] < 0 else int(fm[i])
+            assert hop.hop_session_ready(s, i, c) == hop.HOP_OK
+            if len(model_slots) < k and None not in model_slots:
+                model_slots.append(i)
+            elif None in model_slots:
+                model_slots[model_slots.index(None)] = i
+            else:
+                pool.append(i)
+            if fm[i] >= 0:
+                assert hop.hop_session_fail(s, i) == hop.HOP_OK
+                dead.add(i)
+                if i in model_slots:
+                    pool = [p for p in pool if p not in dead]
+                    model_slots[model_slots.index(i)] = pool.pop(0) if pool else None
+                else:
+                    pool = [p for p in pool if p not in dead]
+        rc, info = hop.hop_session_finish(s)
+        torch.cuda.synchronize()
+        slots = model_slots + [None] * (k - len(model_slots))
+        live = [o for o in slots if o is not None]
+        if not live:
+            assert rc == hop.HOP_ERR_NO_SURVIVOR
+            continue
+        # the oracle's value for this placement: holes are objects that arrive and fail with nobody left
+        host = [workloads.to_numpy(o) for o in objs]
+        spare = [j for j in range(n) if j not in live]
+        o_order, o_fm = [], np.zeros(n, np.int64)
+        for o in slots:
+            if o is None:
+                o = spare.pop()
+                o_fm[o] = 1
+            else:
+                o_fm[o] = -1
+            o_order.append(o)
+        o_order += spare
+        orc, want, k_eff, _ = oracle.reduce(host, k, oracle.SUM, ORA_DT[dtype], chunk // es, d,
+                                            np.array(o_order, np.int32), o_fm)
+        assert rc == orc and info["k_eff"] == k_eff == len(live)
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+        assert info["n_launches"] >= 1
 
 
 def test_session_late_arrival_fills_the_hole_and_unfinished_objects_count_as_failed():

@@ -37,7 +37,7 @@ def test_info_struct_layout_matches_header():
     # int32 x4, int64, int32 x2 -> 32 bytes with natural alignment
     assert ctypes.sizeof(hop.HopInfo) == 32
     assert hop.HopInfo.chunks_redone.offset == 16
-    assert ctypes.sizeof(hop.PlanEntry) == 8 and ctypes.sizeof(hop.PlanLaunch) == 24
+    assert ctypes.sizeof(hop.PlanEntry) == 8 and ctypes.sizeof(hop.PlanLaunch) == 48
 
 
 @pytest.mark.parametrize("d", [1, 2, 3, 4, 8, 16, 1 << 20])
@@ -49,21 +49,33 @@ def test_slots_match_oracle(d):
 
 
 def interpret(objs, launches, entries, n_elems, chunk_elems, op):
-    """Apply the recorded launches in order, exactly as the header describes them."""
+    """Apply the recorded launches in order, exactly as the header describes them: steps
+    [step_begin, step_end) of the program in force, accumulators restored from / saved to a
+    per-level spill array between segments, the result stored by final launches."""
     f = NP_OP[op]
     dst = np.zeros(n_elems, objs[0].dtype)
-    for c0, c1, e0, e1 in launches:
+    spill = {}
+    for c0, c1, e0, e1, t0, t1, final, live_before, live_after in launches:
         seg = slice(c0 * chunk_elems, min(c1 * chunk_elems, n_elems))
-        acc = {}
-        for obj, level, is_set, n_fold in entries[e0:e1]:
+        prog = entries[e0:e1]
+        assert 0 <= t0 <= t1 <= len(prog) and (final == (t1 == len(prog))) and (t0 < t1 or final)
+        assert (live_before == 0) == (t0 == 0)
+        acc = {L: spill[L][seg].copy() for L in range(live_before)}
+        for obj, level, is_set, n_fold in prog[t0:t1]:
+            assert obj >= 0
             x = objs[obj][seg]
             acc[level] = x.copy() if is_set else f(acc[level], x).astype(x.dtype)
             for _ in range(n_fold):
                 acc[level - 1] = f(acc[level - 1], acc[level]).astype(x.dtype)
                 del acc[level]
                 level -= 1
-        assert list(acc) == [0]
-        dst[seg] = acc[0]
+        if final:
+            assert list(acc) == [0] and live_after == 0
+            dst[seg] = acc[0]
+        else:
+            assert sorted(acc) == list(range(live_after))
+            for L in range(live_after):
+                spill.setdefault(L, np.zeros(n_elems, objs[0].dtype))[seg] = acc[L]
     return dst
 
 
@@ -100,7 +112,7 @@ def test_interpreted_plan_equals_oracle_f32(op):
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
         # every object in the final program exactly once; k_eff of them
         final = entries[launches[-1][2]:launches[-1][3]]
-        assert len(final) == k_eff and len({e[0] for e in final}) == k_eff
+        assert launches[-1][6] == 1 and len(final) == k_eff and len({e[0] for e in final}) == k_eff
         assert max(e[1] for e in final) + 1 <= info["stack_depth"] <= hop.HOP_MAX_DEPTH
 
 
@@ -195,7 +207,7 @@ def test_failure_free_call_is_one_launch_over_all_chunks():
         rc, info, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
                                                           w.tree_degree, w.ready_order(), w.fail_mask())
         assert rc == hop.HOP_OK and info["k_eff"] == w.k and info["chunks_redone"] == 0
-        assert launches == [(0, w.n_chunks, 0, w.k)] and info["n_launches"] == 1
+        assert launches == [(0, w.n_chunks, 0, w.k, 0, w.k, 1, 0, 0)] and info["n_launches"] == 1
         # only the first k arrivals are ever read
         assert sorted(e[0] for e in entries) == sorted(w.ready_order()[:w.k].tolist())
     # survey's stack depths: 3, 3, 4 for configs 1, 2, 5; config 3 picks a degree from {1, 2, k}
@@ -283,3 +295,170 @@ def test_argument_errors_without_a_device():
     assert rc == hop.HOP_ERR_DEPTH
     rc, info, _, _ = P(1 << 17, 64, 1 << 17, "f32", 16, 1)
     assert rc == hop.HOP_OK and info["stack_depth"] == 1
+
+
+# ------------------------------------------------------------------ event-level sessions, eager segments
+
+class SlotModel:
+    """The placement rules of the header, written out independently: the t-th arrival takes position t
+    (or the lowest position emptied by a failure), later arrivals wait; a failed holder is replaced
+    by the first waiting object that is still alive, else its position stays empty."""
+
+    def __init__(self, n, k, C):
+        self.n, self.k, self.C = n, k, C
+        self.ready = {}
+        self.failed = set()
+        self.slots = []              # object or None (emptied)
+        self.pool = []
+
+    def on_ready(self, obj, c):
+        if obj not in self.ready:
+            empties = [t for t, o in enumerate(self.slots) if o is None]
+            if empties:
+                self.slots[empties[0]] = obj
+            elif len(self.slots) < self.k:
+                self.slots.append(obj)
+            else:
+                self.pool.append(obj)
+        self.ready[obj] = c
+
+    def on_fail(self, obj):
+        if obj in self.failed or self.ready.get(obj, 0) == self.C:
+            return
+        self.failed.add(obj)
+        if obj in self.slots:
+            t = self.slots.index(obj)
+            self.pool = [p for p in self.pool if p not in self.failed]
+            self.slots[t] = self.pool.pop(0) if self.pool else None
+
+    def finish(self):
+        for p in list(self.pool):
+            if self.ready[p] < self.C:
+                self.failed.add(p)
+        for t in range(len(self.slots)):
+            o = self.slots[t]
+            if o is not None and self.ready[o] < self.C:
+                self.on_fail(o)
+        return self.slots + [None] * (self.k - len(self.slots))
+
+
+def oracle_for_occupants(objs, slots, k, C, chunk_elems, d, op):
+    """The oracle's value for a given final placement (None = empty position)."""
+    n = len(objs)
+    used = [o for o in slots if o is not None]
+    spare = [i for i in range(n) if i not in used]
+    order, fm = [], np.zeros(n, np.int64)
+    for o in slots:
+        if o is None:
+            o = spare.pop()
+            fm[o] = 1            # arrives, then fails with nobody alive to replace it
+        else:
+            fm[o] = -1
+        order.append(o)
+    order += spare               # fail_mask 0: they never become ready
+    return oracle.reduce(objs, k, ORA_OP[op], oracle.F32, chunk_elems, d, np.array(order, np.int32), fm)
+
+
+@pytest.mark.parametrize("eager", [0, 1, 2, 5])
+def test_random_sessions_with_segments_equal_oracle(eager):
+    rng = np.random.default_rng(900 + eager)
+    n_segmented = 0
+    for it in range(150):
+        n = int(rng.integers(2, 12))
+        k = int(rng.integers(1, n + 1))
+        d = int(rng.choice([1, 2, 3, 4, n]))
+        C = int(rng.integers(2, 7))
+        ce = 4
+        E = (C - 1) * ce + int(rng.integers(1, ce + 1))
+        objs = [(rng.standard_normal(E) * 10.0 ** rng.integers(-2, 3)).astype(np.float32) for _ in range(n)]
+        rc, s = hop.hop_plan_session_begin(n, E * 4, k, "f32", ce * 4, d)
+        assert rc == hop.HOP_OK
+        assert hop.hop_session_set_eager(s, eager) == hop.HOP_OK
+        model = SlotModel(n, k, C)
+        # a random interleaving: objects arrive in random order and deliver chunks in random bursts;
+        # some fail mid-stream, some never finish
+        progress = {}
+        arrivals = list(rng.permutation(n))
+        n_never = int(rng.integers(0, 2))
+        never = set(arrivals[len(arrivals) - n_never:]) if n_never else set()
+        arrivals = [a for a in arrivals if a not in never]
+        doomed = {int(a): int(rng.integers(0, C)) for a in arrivals if rng.random() < 0.25}
+        stalls = {int(a) for a in arrivals if a not in doomed and rng.random() < 0.1}
+        active = []
+        while arrivals or active:
+            if arrivals and (not active or rng.random() < 0.4):
+                a = int(arrivals.pop(0))
+                active.append(a)
+                progress[a] = 0
+                assert hop.hop_session_ready(s, a, 0) == hop.HOP_OK
+                model.on_ready(a, 0)
+                continue
+            a = active[int(rng.integers(len(active)))]
+            if a in doomed and progress[a] >= doomed[a]:
+                assert hop.hop_session_fail(s, a) == hop.HOP_OK
+                model.on_fail(a)
+                active.remove(a)
+                continue
+            if a in stalls and progress[a] >= C - 1:
+                active.remove(a)              # never delivers its last chunk
+                continue
+            progress[a] = min(C, progress[a] + int(rng.integers(1, 3)))
+            assert hop.hop_session_ready(s, a, progress[a]) == hop.HOP_OK
+            model.on_ready(a, progress[a])
+            if progress[a] == C:
+                active.remove(a)
+        rc, info, launches, entries = hop.hop_plan_session_finish(s)
+        slots = model.finish()
+        live = [o for o in slots if o is not None]
+        if not live:
+            assert rc == hop.HOP_ERR_NO_SURVIVOR
+            continue
+        assert rc == (hop.HOP_OK if len(live) == k else hop.HOP_PARTIAL) and info["k_eff"] == len(live)
+        final_prog = entries[launches[-1][2]:launches[-1][3]]
+        assert [e[0] for e in final_prog] == live
+        got = interpret(objs, launches, entries, E, ce, "sum")
+        orc, want, k_eff, _ = oracle_for_occupants(objs, slots, k, C, ce, d, "sum")
+        assert orc == rc and k_eff == len(live)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        if eager == 0:
+            assert all(l[4] == 0 and l[6] == 1 for l in launches)       # whole programs only
+        n_segmented += any(l[6] == 0 for l in launches)
+    assert n_segmented > {0: -1, 1: 30, 2: 30, 5: 0}[eager] and (eager or n_segmented == 0)
+
+
+def test_eager_session_overlaps_the_wait_for_the_last_arrival():
+    # 8 objects of 4 chunks arrive whole, one after the other. Fused: nothing can run until the last
+    # one is there, then one launch runs all 8 steps. Eager: every arrival is folded in at once, so
+    # after the last arrival a single step is left.
+    n, C = 8, 4
+    for eager, want_last in ((0, (0, 8)), (1, (7, 8))):
+        rc, s = hop.hop_plan_session_begin(n, C * 64, n, "f32", 64, 2)
+        hop.hop_session_set_eager(s, eager)
+        for i in range(n):
+            assert hop.hop_session_ready(s, i, C) == hop.HOP_OK
+            assert hop.hop_session_chunks_final(s) == (C if i == n - 1 else 0)
+        rc, info, launches, entries = hop.hop_plan_session_finish(s)
+        assert rc == hop.HOP_OK
+        assert (launches[-1][4], launches[-1][5]) == want_last and launches[-1][6] == 1
+        assert info["n_launches"] == (1 if eager == 0 else n)
+        assert info["chunks_redone"] == 0
+
+
+def test_failure_keeps_partials_that_never_absorbed_the_failed_object():
+    # chain of 6, eager. Objects 0..3 deliver everything, object 4 delivers 2 of 4 chunks and fails,
+    # object 5 is healthy. Chunks 2,3 never ran past step 4 and keep their accumulators (steps 0..3);
+    # chunks 0,1 had absorbed object 4 and start over.
+    n, C = 6, 4
+    rc, s = hop.hop_plan_session_begin(n, C * 64, n, "f32", 64, 1)
+    hop.hop_session_set_eager(s, 1)
+    for i in range(4):
+        hop.hop_session_ready(s, i, C)
+    hop.hop_session_ready(s, 4, 2)
+    hop.hop_session_ready(s, 5, C)
+    assert hop.hop_session_fail(s, 4) == hop.HOP_OK
+    rc, info, launches, entries = hop.hop_plan_session_finish(s)
+    assert rc == hop.HOP_PARTIAL and info["k_eff"] == 5
+    after = [l for l in launches if entries[l[2]:l[3]] == [(0, 0, 1, 0), (1, 0, 0, 0), (2, 0, 0, 0), (3, 0, 0, 0), (5, 0, 0, 0)]]
+    # restarted chunks run all five steps, the others only the one that was missing
+    assert sorted((l[0], l[1], l[4], l[5]) for l in after) == [(0, 2, 0, 5), (2, 4, 4, 5)]
+    assert info["chunks_redone"] == 2 * 5
