@@ -66,6 +66,38 @@ def cpu_baseline(w, objs, order, torch, sample_elems):
                       (sample_elems, w.n_elems, nbytes / 1e6, dt)}, out
 
 
+def paced_arrivals(hop, torch, w, objs, order, dst, interval_us, reps=5):
+    """Objects become ready whole, one every interval_us (host clock), in the workload's ready order; only
+    the first k matter. Measured: host time from the last arrival to the completed result (stream
+    synchronised), median of reps, for the fused policy (one launch when everything is there) and the
+    eager one (every arrival folded into saved accumulators at once)."""
+    import statistics
+    table = hop.PtrTable(objs)
+    C = w.n_chunks
+    res = {"interval_us": interval_us, "k": w.k}
+    for name, eager in (("fused", 0), ("eager", 1)):
+        tails, launches = [], 0
+        for _ in range(reps + 1):
+            rc, s = hop.hop_session_begin(dst, table, w.k, w.ops[0], w.dtype, w.chunk_bytes, w.tree_degree)
+            assert rc == hop.HOP_OK, hop.hop_strerror(rc)
+            hop.hop_session_set_eager(s, eager)
+            torch.cuda.synchronize()
+            t_next = time.perf_counter()
+            for t in range(w.k):
+                while time.perf_counter() < t_next:
+                    pass
+                t_last = time.perf_counter()
+                assert hop.hop_session_ready(s, int(order[t]), C) == hop.HOP_OK
+                t_next += interval_us * 1e-6
+            rc, info = hop.hop_session_finish(s)
+            torch.cuda.synchronize()
+            tails.append((time.perf_counter() - t_last) * 1e6)
+            launches = info["n_launches"]
+            assert rc == hop.HOP_OK
+        res[name] = {"us_after_last_arrival": round(statistics.median(tails[1:]), 1), "launches": launches}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +106,10 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="which of the five workloads (default: 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true", help="also time the other workloads (extra JSON field)")
+    ap.add_argument("--paced-interval-us", type=float, default=None,
+                    help="also run the workload's objects through the event-level API, one whole object every "
+                         "INTERVAL microseconds, and report how long after the last arrival the result is complete, "
+                         "for the fused and the eager scheduling policy (the paper's asynchrony experiment)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run hop_broadcast of one 256 MiB object to one destination a few times: a copy of "
                          "known size against which hardware byte counters can be scaled")
@@ -178,6 +214,8 @@ def main():
                              "GB/s_read_plus_write": round(2 * src.numel() * 4 / (ms * 1e-3) / 1e9, 2),
                              "kernel": "hop::copy_kernel"}
         del src, dstp
+    if args.paced_interval_us is not None:
+        out["paced_arrivals"] = paced_arrivals(hop, torch, w, objs, order, dsts[0][0], args.paced_interval_us)
     if args.all_configs:
         extra = {}
         del objs, dsts

@@ -68,6 +68,66 @@ static void release_block(Block *b, hipStream_t stream)
     g_free.push_back(b);
 }
 
+// Large device-only scratch (saved accumulators of eager sessions), cached the same way: a
+// buffer goes back to the cache with an event and is handed out again once that event is done.
+struct DevBuf {
+    int device = -1;
+    char *ptr = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+static std::vector<DevBuf *> g_devbufs;
+static constexpr size_t kDevCacheLimit = (size_t)8 << 30;     // beyond this, idle buffers are freed
+
+static DevBuf *acquire_devbuf(int device, size_t bytes)
+{
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        DevBuf *best = nullptr;
+        size_t best_i = 0;
+        for (size_t i = 0; i < g_devbufs.size(); ++i) {
+            DevBuf *b = g_devbufs[i];
+            if (b->device != device || b->cap < bytes) continue;
+            if (b->pending) {
+                if (hipEventQuery(b->ev) != hipSuccess) { (void)hipGetLastError(); continue; }
+                b->pending = false;
+            }
+            if (!best || b->cap < best->cap) { best = b; best_i = i; }
+        }
+        if (best) {
+            g_devbufs.erase(g_devbufs.begin() + best_i);
+            return best;
+        }
+    }
+    DevBuf *b = new (std::nothrow) DevBuf;
+    if (!b) return nullptr;
+    b->device = device;
+    b->cap = bytes;
+    if (hipMalloc((void **)&b->ptr, bytes) != hipSuccess) { (void)hipGetLastError(); delete b; return nullptr; }
+    if (hipEventCreateWithFlags(&b->ev, hipEventDisableTiming) != hipSuccess) { (void)hipFree(b->ptr); delete b; return nullptr; }
+    return b;
+}
+
+static void release_devbuf(DevBuf *b, hipStream_t stream)
+{
+    if (!b) return;
+    b->pending = (hipEventRecord(b->ev, stream) == hipSuccess);
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_devbufs.push_back(b);
+    size_t total = 0;
+    for (DevBuf *x : g_devbufs) total += x->cap;
+    for (size_t i = 0; i < g_devbufs.size() && total > kDevCacheLimit;) {
+        DevBuf *x = g_devbufs[i];
+        if (x->pending && hipEventQuery(x->ev) != hipSuccess) { (void)hipGetLastError(); ++i; continue; }
+        total -= x->cap;
+        (void)hipEventDestroy(x->ev);
+        (void)hipFree(x->ptr);
+        delete x;
+        g_devbufs.erase(g_devbufs.begin() + i);
+    }
+}
+
 // Bump allocator over a list of blocks; everything staged is copied to the
 // device with one async copy per stage() call, ordered on the stream.
 class Workspace {
@@ -132,12 +192,9 @@ public:
     GpuBackend(int device, hipStream_t stream, const void *const *objs, int n, std::vector<void *> dsts,
                const Shape &shape, int op, int dtype, int k, int64_t degree)
         : ws_(device, stream), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
-          op_(op), dtype_(dtype), k_(k), degree_(degree) {}
+          op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device) {}
 
-    ~GpuBackend() override
-    {
-        if (spill_) (void)hipFreeAsync(spill_, stream_);      // stream-ordered: after the last segment kernel
-    }
+    ~GpuBackend() override { release_devbuf(spill_buf_, stream_); }
 
     int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
                int live_before, int live_after) override
@@ -185,8 +242,8 @@ public:
 
 private:
     // Steps [t0, t1) only: accumulators come from and/or go to the spill area, one array of 4-byte
-    // accumulators per level, each as long as the object has elements. It is allocated on the
-    // stream when the first partial segment is launched and freed on the stream with the session.
+    // accumulators per level, each as long as the object has elements. It is taken from the
+    // library's cache when the first partial segment is launched and returned with the session.
     int launch_segment(const std::vector<Entry> &prog, int64_t c0, int64_t c1, int t0, int t1, bool final,
                        int live_before, int live_after)
     {
@@ -195,10 +252,9 @@ private:
             const size_t n_elems = shape_.object_bytes / (size_t)elem_bytes(dtype_);
             level_stride_ = (n_elems * 4 + 255) & ~(size_t)255;
             spill_levels_ = std::min(HOP_MAX_DEPTH, full_tree_depth(k_, degree_));
-            if (hipMallocAsync((void **)&spill_, level_stride_ * (size_t)spill_levels_, stream_) != hipSuccess) {
-                spill_ = nullptr;
-                return HOP_ERR_NOMEM;
-            }
+            spill_buf_ = acquire_devbuf(device_, level_stride_ * (size_t)spill_levels_);
+            if (!spill_buf_) return HOP_ERR_NOMEM;
+            spill_ = spill_buf_->ptr;
         }
         int depth = 1;
         std::vector<DevEntry> steps((size_t)(t1 - t0));
@@ -316,6 +372,8 @@ private:
     void *const *dev_extra_ = nullptr;
     uint64_t dev_version_ = 0;
     int depth_ = 1;
+    int device_;
+    DevBuf *spill_buf_ = nullptr;
     char *spill_ = nullptr;
     size_t level_stride_ = 0;
     int spill_levels_ = 0;
@@ -726,6 +784,13 @@ int hop_shutdown(void)
         delete b;
     }
     g_free.clear();
+    for (DevBuf *b : g_devbufs) {
+        if (b->pending && hipEventSynchronize(b->ev) != hipSuccess) rc = HOP_ERR_DEVICE;
+        (void)hipEventDestroy(b->ev);
+        (void)hipFree(b->ptr);
+        delete b;
+    }
+    g_devbufs.clear();
     return rc;
 }
 

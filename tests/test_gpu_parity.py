@@ -396,6 +396,46 @@ def test_session_late_arrival_fills_the_hole_and_unfinished_objects_count_as_fai
     assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
 
 
+def test_composed_reduce_streams_one_result_into_the_next():
+    # paper section 3.4.2: the output of one Reduce is an input of another; as soon as leading chunks
+    # of the first result are final they are reported ready to the second session (same stream)
+    d = dev()
+    rng = np.random.default_rng(12)
+    C, ce = 5, 512
+    E = (C - 1) * ce + 100
+    a_vals = [rng.standard_normal(E).astype(np.float32) for _ in range(4)]
+    b_vals = [rng.standard_normal(E).astype(np.float32) for _ in range(2)]
+    a_objs = [workloads.from_numpy(v, "f32", d) for v in a_vals]
+    b_objs = [workloads.from_numpy(v, "f32", d) for v in b_vals]
+    mid = torch.zeros(E, device=d)
+    out = torch.zeros(E, device=d)
+    rc, sa = hop.hop_session_begin(mid, a_objs, 4, "sum", "f32", ce * 4, 2)
+    assert rc == hop.HOP_OK
+    rc, sb = hop.hop_session_begin(out, [b_objs[0], mid, b_objs[1]], 3, "sum", "f32", ce * 4, 2)
+    assert rc == hop.HOP_OK
+    assert hop.hop_session_ready(sb, 0, C) == hop.HOP_OK          # arrival order of the outer reduce: b0, mid, b1
+    assert hop.hop_session_ready(sb, 1, 0) == hop.HOP_OK
+    assert hop.hop_session_ready(sb, 2, C) == hop.HOP_OK
+    seen = 0
+    for c in range(1, C + 1):                                     # the inner participants stream chunk by chunk
+        for i in range(4):
+            assert hop.hop_session_ready(sa, i, c) == hop.HOP_OK
+        done = hop.hop_session_chunks_final(sa)
+        assert done == c
+        if done > seen:
+            assert hop.hop_session_ready(sb, 1, done) == hop.HOP_OK
+            assert hop.hop_session_chunks_final(sb) == done       # the outer result follows chunk by chunk
+            seen = done
+    rca, info_a = hop.hop_session_finish(sa)
+    rcb, info_b = hop.hop_session_finish(sb)
+    torch.cuda.synchronize()
+    assert rca == hop.HOP_OK and rcb == hop.HOP_OK and info_a["n_launches"] == C and info_b["n_launches"] == C
+    _, inner, _, _ = oracle.reduce(a_vals, 4, oracle.SUM, oracle.F32, ce, 2, None, None)
+    _, want, _, _ = oracle.reduce([b_vals[0], inner, b_vals[1]], 3, oracle.SUM, oracle.F32, ce, 2, None, None)
+    assert np.array_equal(bits(workloads.to_numpy(mid)), bits(inner))
+    assert np.array_equal(bits(workloads.to_numpy(out)), bits(want))
+
+
 def test_other_stream():
     d = dev()
     w = workloads.WORKLOADS[1]
