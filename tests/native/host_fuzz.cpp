@@ -1,0 +1,123 @@
+// Host-only stress of the chunk scheduler (hop_plan.hpp) under AddressSanitizer and
+// UBSan: random sessions (arrivals, chunk deliveries, failures, eager policies) against a
+// back end that checks every launch it is given. No GPU, no HIP.
+#include <cstdio>
+#include <cstdlib>
+#include <map>
+#include <random>
+#include <vector>
+
+#include "../../paper_2002_05814_amd/csrc/hop_plan.hpp"
+
+using namespace hop;
+
+struct CheckingBackend : Backend {
+    int64_t C = 0;
+    std::vector<int> steps_done;        // per chunk: steps whose accumulators are saved, or -1 if the result is stored
+    uint64_t last_version = 0;
+    long launches = 0;
+    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
+               int live_before, int live_after) override
+    {
+        if (!(0 <= c0 && c0 < c1 && c1 <= C)) { std::printf("bad chunk range\n"); std::abort(); }
+        if (!(0 <= t0 && t0 <= t1 && t1 <= (int)prog.size())) { std::printf("bad step range\n"); std::abort(); }
+        if (final != (t1 == (int)prog.size())) { std::printf("final flag\n"); std::abort(); }
+        if (t0 == t1 && !(final && t0 > 0)) { std::printf("empty launch\n"); std::abort(); }
+        if (version < last_version) { std::printf("version went back\n"); std::abort(); }
+        last_version = version;
+        for (int t = t0; t < t1; ++t)
+            if (prog[(size_t)t].obj < 0) { std::printf("step without an object\n"); std::abort(); }
+        // accumulator bookkeeping: what is restored must be what was saved
+        int level = t0 > 0 ? (int)prog[(size_t)t0 - 1].level - (int)prog[(size_t)t0 - 1].n_fold : -1;
+        if (live_before != level + 1) { std::printf("live_before\n"); std::abort(); }
+        for (int t = t0; t < t1; ++t) {
+            const Entry &e = prog[(size_t)t];
+            if (e.set ? (int)e.level != level + 1 : (int)e.level != level) { std::printf("level discipline\n"); std::abort(); }
+            level = (int)e.level - (int)e.n_fold;
+            if (level < 0) { std::printf("fold below zero\n"); std::abort(); }
+        }
+        if (final ? (level != 0 || live_after != 0) : live_after != level + 1) { std::printf("live_after\n"); std::abort(); }
+        for (int64_t c = c0; c < c1; ++c) {
+            const int have = steps_done[(size_t)c];
+            if (t0 == 0 ? false : have != t0) { std::printf("resume from %d but chunk has %d\n", t0, have); std::abort(); }
+            steps_done[(size_t)c] = final ? -1 : t1;
+        }
+        ++launches;
+        return HOP_OK;
+    }
+};
+
+int main(int argc, char **argv)
+{
+    const int rounds = argc > 1 ? std::atoi(argv[1]) : 3000;
+    std::mt19937_64 rng(12345);
+    auto rnd = [&](int lo, int hi) { return lo + (int)(rng() % (uint64_t)(hi - lo + 1)); };
+    long total_launches = 0;
+    for (int r = 0; r < rounds; ++r) {
+        const int n = rnd(1, 40), k = rnd(1, n);
+        const int degs[] = {1, 2, 3, 4, 8, 16, n + 1};
+        const int64_t d = degs[rnd(0, 6)];
+        const int64_t C = rnd(1, 9);
+        CheckingBackend be;
+        be.C = C;
+        be.steps_done.assign((size_t)C, 0);
+        Scheduler s(n, k, C, d, &be);
+        s.set_eager(rnd(0, 3));
+        std::vector<int> order((size_t)n);
+        for (int i = 0; i < n; ++i) order[(size_t)i] = i;
+        std::shuffle(order.begin(), order.end(), rng);
+        std::vector<int64_t> progress((size_t)n, -1);
+        std::vector<int> active;
+        size_t next = 0;
+        int guard = 0;
+        while ((next < order.size() || !active.empty()) && ++guard < 100000) {
+            if (next < order.size() && (active.empty() || rnd(0, 9) < 4)) {
+                const int a = order[next++];
+                if (rnd(0, 19) == 0) continue;                       // never shows up
+                progress[(size_t)a] = 0;
+                active.push_back(a);
+                if (s.on_ready(a, 0) != HOP_OK) std::abort();
+            } else {
+                const size_t pick = (size_t)rnd(0, (int)active.size() - 1);
+                const int a = active[pick];
+                const int what = rnd(0, 19);
+                if (what == 0) {                                     // fails
+                    if (s.on_fail(a) != HOP_OK) std::abort();
+                    active.erase(active.begin() + (long)pick);
+                } else if (what == 1) {                              // stalls for good
+                    active.erase(active.begin() + (long)pick);
+                } else {
+                    progress[(size_t)a] = std::min<int64_t>(C, progress[(size_t)a] + rnd(1, 3));
+                    if (s.on_ready(a, progress[(size_t)a]) != HOP_OK) std::abort();
+                    if (progress[(size_t)a] == C) active.erase(active.begin() + (long)pick);
+                }
+            }
+            if (s.pump() < 0) std::abort();
+            // invalid calls must be refused without damage
+            if (s.on_ready(-1, 0) != HOP_ERR_INVALID || s.on_ready(n, 0) != HOP_ERR_INVALID || s.on_fail(n) != HOP_ERR_INVALID)
+                std::abort();
+        }
+        hop_info_t info;
+        const int rc = s.finish(&info);
+        if (rc == HOP_OK || rc == HOP_PARTIAL) {
+            for (int64_t c = 0; c < C; ++c)
+                if (be.steps_done[(size_t)c] != -1) { std::printf("chunk %ld not stored (round %d)\n", (long)c, r); std::abort(); }
+            if (info.k_eff < 1 || info.k_eff > k || (rc == HOP_OK) != (info.k_eff == k)) std::abort();
+        } else if (rc != HOP_ERR_NO_SURVIVOR) {
+            std::printf("unexpected status %d\n", rc);
+            std::abort();
+        }
+        total_launches += be.launches;
+        // the program cutter on whatever tree this was
+        Tree tr;
+        tr.build(k, d);
+        std::vector<int32_t> occ((size_t)k);
+        for (int t = 0; t < k; ++t) occ[(size_t)t] = rnd(0, 9) ? t : -1;
+        std::vector<Entry> prog;
+        compile_program(tr, occ, prog);
+        MultiPlan mp;
+        plan_passes(prog, (size_t)rnd(1, 40), rnd(1, 6), mp);
+    }
+    std::printf("ok %d sessions, %ld launches\n", rounds, total_launches);
+    return 0;
+}
