@@ -132,6 +132,57 @@ int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_b
                   size_t chunk_bytes, void *stream);
 
 /*
+ * Receiver-driven broadcast, event by event (sections 3.4.1 and 3.5.1).
+ * hop_broadcast above is the case where all receivers are known at once; here
+ * receivers join one after the other and the library plays the object
+ * directory: a joining receiver is given ONE sender, an idle complete copy if
+ * there is one, else an idle partial copy (a receiver still receiving);
+ * a copy serves one receiver at a time and is listed again when its transfer
+ * ends, so the broadcast tree forms from the arrival order and data flows
+ * chunk by chunk through chains of partial copies. If a copy fails, the
+ * receiver it was serving asks again and resumes from the chunks it already
+ * has, never from a copy that (transitively) fetches from itself.
+ * Time is explicit: nothing moves until hop_bcast_step, which lets every
+ * transfer advance by at most max_chunks chunks (0 = as far as its sender
+ * has), senders before their receivers. On one GPU every "transfer" is a
+ * chunk-range copy between two device buffers on `stream`.
+ *
+ *   hop_bcast_begin        src = device pointer of the original copy, or NULL
+ *                          for a host-only session that only records copies.
+ *   hop_bcast_source_ready the original has chunks [0, c) (its Put may still be
+ *                          in progress); begins at 0.
+ *   hop_bcast_join         a receiver arrives with its device buffer dst
+ *                          (ignored in host-only sessions). Returns its copy id
+ *                          (>= 1; the original is copy 0) or a negative status;
+ *                          *sender (may be NULL) = the copy it was given, -1 if
+ *                          every copy is busy (it asks again at each step).
+ *   hop_bcast_fail         copy `copy` is lost.
+ *   hop_bcast_sender       the copy that `copy` currently fetches from, or -1.
+ *   hop_bcast_finish       steps until nothing moves any more, fills info and
+ *                          the log of copies (both may be NULL), frees the
+ *                          session. HOP_OK if every surviving receiver is
+ *                          complete, HOP_PARTIAL otherwise.
+ */
+typedef struct hop_bcast hop_bcast_t;
+typedef struct { int32_t from, to; int64_t chunk_begin, chunk_end; } hop_bcast_copy_t;
+typedef struct {
+    int32_t n_receivers;    /* receivers that joined                                   */
+    int32_t n_failed;       /* copies reported lost                                    */
+    int32_t n_resumed;      /* transfers taken up again from another sender            */
+    int32_t n_complete;     /* surviving receivers that hold the whole object          */
+    int64_t chunks_copied;  /* chunk transfers performed (no chunk is sent twice to the
+                               same receiver)                                          */
+} hop_bcast_info_t;
+
+int hop_bcast_begin(hop_bcast_t **b, const void *src, size_t object_bytes, size_t chunk_bytes, void *stream);
+int hop_bcast_source_ready(hop_bcast_t *b, int64_t chunks_ready_total);
+int hop_bcast_join(hop_bcast_t *b, void *dst, int *sender);
+int hop_bcast_fail(hop_bcast_t *b, int copy);
+int hop_bcast_step(hop_bcast_t *b, int64_t max_chunks);
+int hop_bcast_sender(hop_bcast_t *b, int copy);
+int hop_bcast_finish(hop_bcast_t *b, hop_bcast_info_t *info, hop_bcast_copy_t *log, int log_capacity, int *n_log);
+
+/*
  * hop_allreduce -- section 3.4.3: Reduce followed by Broadcast, composed
  * chunk by chunk (section 3.3): each finished result chunk goes to all n_dst
  * destinations. Arguments as hop_reduce / hop_broadcast; n_dst >= 1. Every

@@ -28,7 +28,8 @@ OPS = {"sum": HOP_SUM, "min": HOP_MIN, "max": HOP_MAX}
 DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
           torch.float32: HOP_F32, torch.bfloat16: HOP_BF16, torch.int32: HOP_I32}
 
-EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_session_begin", "hop_session_ready",
+EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_bcast_begin", "hop_bcast_source_ready",
+           "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready",
            "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_chunks_final",
            "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
            "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
@@ -39,6 +40,19 @@ class HopInfo(ctypes.Structure):
                 ("n_replaced", ctypes.c_int32), ("degree_used", ctypes.c_int32),
                 ("chunks_redone", ctypes.c_int64), ("n_launches", ctypes.c_int32),
                 ("stack_depth", ctypes.c_int32)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_}
+
+
+class BcastCopy(ctypes.Structure):
+    _fields_ = [("from_", ctypes.c_int32), ("to", ctypes.c_int32), ("chunk_begin", ctypes.c_int64),
+                ("chunk_end", ctypes.c_int64)]
+
+
+class BcastInfo(ctypes.Structure):
+    _fields_ = [("n_receivers", ctypes.c_int32), ("n_failed", ctypes.c_int32), ("n_resumed", ctypes.c_int32),
+                ("n_complete", ctypes.c_int32), ("chunks_copied", ctypes.c_int64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}
@@ -76,6 +90,14 @@ def lib() -> ctypes.CDLL:
         L.hop_broadcast.argtypes = [vpp, ctypes.c_int, vp, ctypes.c_size_t, ctypes.c_size_t, vp]
         L.hop_allreduce.argtypes = [vpp, ctypes.c_int, vpp, ctypes.c_int, ctypes.c_size_t, i32p, ctypes.c_int,
                                     ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, i64p, vp, infop]
+        L.hop_bcast_begin.argtypes = [ctypes.POINTER(vp), vp, ctypes.c_size_t, ctypes.c_size_t, vp]
+        L.hop_bcast_source_ready.argtypes = [vp, ctypes.c_int64]
+        L.hop_bcast_join.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int)]
+        L.hop_bcast_fail.argtypes = [vp, ctypes.c_int]
+        L.hop_bcast_step.argtypes = [vp, ctypes.c_int64]
+        L.hop_bcast_sender.argtypes = [vp, ctypes.c_int]
+        L.hop_bcast_finish.argtypes = [vp, ctypes.POINTER(BcastInfo), ctypes.POINTER(BcastCopy), ctypes.c_int,
+                                       ctypes.POINTER(ctypes.c_int)]
         L.hop_session_begin.argtypes = [ctypes.POINTER(vp), vp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
                                         ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, vp]
         L.hop_session_ready.argtypes = [vp, ctypes.c_int, ctypes.c_int64]
@@ -200,6 +222,51 @@ def hop_broadcast(dsts, src, chunk_bytes, stream=None, object_bytes=None):
     tab, n_dst = _ptr_table(dsts)
     sptr = ctypes.c_void_p(int(src.data_ptr()) if isinstance(src, torch.Tensor) else int(src))
     return lib().hop_broadcast(tab, n_dst, sptr, _bytes_of(src, object_bytes), int(chunk_bytes), _stream(stream))
+
+
+def hop_bcast_begin(src, object_bytes, chunk_bytes, stream=None):
+    """src: CUDA tensor / address, or None for a host-only session. Returns (status, handle)."""
+    h = ctypes.c_void_p()
+    if src is None:
+        rc = lib().hop_bcast_begin(ctypes.byref(h), None, int(object_bytes), int(chunk_bytes), None)
+    else:
+        sptr = ctypes.c_void_p(int(src.data_ptr()) if isinstance(src, torch.Tensor) else int(src))
+        rc = lib().hop_bcast_begin(ctypes.byref(h), sptr, int(object_bytes), int(chunk_bytes), _stream(stream))
+    return rc, h
+
+
+def hop_bcast_source_ready(b, chunks_ready_total):
+    return lib().hop_bcast_source_ready(b, int(chunks_ready_total))
+
+
+def hop_bcast_join(b, dst=None):
+    """Returns (copy id or negative status, sender)."""
+    sender = ctypes.c_int(-1)
+    dptr = None if dst is None else ctypes.c_void_p(int(dst.data_ptr()) if isinstance(dst, torch.Tensor) else int(dst))
+    rc = lib().hop_bcast_join(b, dptr, ctypes.byref(sender))
+    return rc, sender.value
+
+
+def hop_bcast_fail(b, copy):
+    return lib().hop_bcast_fail(b, int(copy))
+
+
+def hop_bcast_step(b, max_chunks=0):
+    return lib().hop_bcast_step(b, int(max_chunks))
+
+
+def hop_bcast_sender(b, copy):
+    return lib().hop_bcast_sender(b, int(copy))
+
+
+def hop_bcast_finish(b, capacity=1 << 14):
+    """Returns (status, info dict, [(from, to, chunk_begin, chunk_end), ...])."""
+    info = BcastInfo()
+    log = (BcastCopy * capacity)()
+    n = ctypes.c_int(0)
+    rc = lib().hop_bcast_finish(b, ctypes.byref(info), log, capacity, ctypes.byref(n))
+    m = min(n.value, capacity)
+    return rc, info.as_dict(), [(log[i].from_, log[i].to, log[i].chunk_begin, log[i].chunk_end) for i in range(m)]
 
 
 def hop_allreduce(dsts, objs, k, op, dtype, chunk_bytes, tree_degree, ready_order=None, fail_mask=None,

@@ -11,6 +11,7 @@
 #include <new>
 #include <vector>
 
+#include "hop_bcast.hpp"
 #include "hop_kernels.h"
 #include "hop_plan.hpp"
 
@@ -508,6 +509,43 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
 
 using namespace hop;
 
+// Broadcast back ends: enqueue 1-to-1 chunk-range copies, or only record them.
+class GpuBcastBackend : public BcastBackend {
+public:
+    GpuBcastBackend(hipStream_t stream, const Shape &shape) : stream_(stream), shape_(shape) {}
+    std::vector<void *> ptrs;                    // device address of every copy, by copy id
+    std::vector<hop_bcast_copy_t> log;
+    int copy(int from, int to, int64_t c0, int64_t c1) override
+    {
+        log.push_back({from, to, c0, c1});
+        hipError_t e = launch_copy(stream_, ptrs[(size_t)from], nullptr, 1, shape_.begin(c0), shape_.end(c1),
+                                   ptrs[(size_t)to]);
+        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+    }
+
+private:
+    hipStream_t stream_;
+    Shape shape_;
+};
+
+class RecordingBcastBackend : public BcastBackend {
+public:
+    std::vector<hop_bcast_copy_t> log;
+    int copy(int from, int to, int64_t c0, int64_t c1) override
+    {
+        log.push_back({from, to, c0, c1});
+        return HOP_OK;
+    }
+};
+
+struct hop_bcast {
+    std::unique_ptr<GpuBcastBackend> gpu;
+    std::unique_ptr<RecordingBcastBackend> rec;
+    std::unique_ptr<BcastScheduler> sched;
+    size_t object_bytes = 0;
+    std::vector<hop_bcast_copy_t> &log() { return gpu ? gpu->log : rec->log; }
+};
+
 struct hop_session {
     std::unique_ptr<GpuBackend> be;             // sessions that enqueue work
     std::unique_ptr<RecordingBackend> rec;      // host-only sessions (hop_plan_session_begin)
@@ -577,6 +615,108 @@ int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_b
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;
     }
+}
+
+int hop_bcast_begin(hop_bcast_t **b, const void *src, size_t object_bytes, size_t chunk_bytes, void *stream)
+{
+    if (!b || chunk_bytes == 0 || chunk_bytes % 16 != 0) return HOP_ERR_INVALID;
+    *b = nullptr;
+    if (src && !aligned16(src)) return HOP_ERR_ALIGN;
+    Shape shape;
+    shape.object_bytes = object_bytes;
+    shape.chunk_bytes = chunk_bytes;
+    shape.n_chunks = object_bytes ? (int64_t)((object_bytes + chunk_bytes - 1) / chunk_bytes) : 1;
+    try {
+        std::unique_ptr<hop_bcast> h(new hop_bcast);
+        h->object_bytes = object_bytes;
+        BcastBackend *be;
+        if (src) {
+            h->gpu.reset(new GpuBcastBackend((hipStream_t)stream, shape));
+            h->gpu->ptrs.push_back(const_cast<void *>(src));
+            be = h->gpu.get();
+        } else {
+            h->rec.reset(new RecordingBcastBackend);
+            be = h->rec.get();
+        }
+        h->sched.reset(new BcastScheduler(shape.n_chunks, be));
+        *b = h.release();
+        return HOP_OK;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_bcast_source_ready(hop_bcast_t *b, int64_t chunks_ready_total)
+{
+    if (!b) return HOP_ERR_INVALID;
+    return b->sched->source_ready(chunks_ready_total);
+}
+
+int hop_bcast_join(hop_bcast_t *b, void *dst, int *sender)
+{
+    if (!b) return HOP_ERR_INVALID;
+    try {
+        if (b->gpu) {
+            if (!dst) return HOP_ERR_INVALID;
+            if (!aligned16(dst)) return HOP_ERR_ALIGN;
+            for (void *p : b->gpu->ptrs) {
+                const char *x = (const char *)p, *y = (const char *)dst;
+                if (b->object_bytes && x < y + b->object_bytes && y < x + b->object_bytes) return HOP_ERR_INVALID;
+            }
+            b->gpu->ptrs.push_back(dst);
+        }
+        return b->sched->join(sender);
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_bcast_fail(hop_bcast_t *b, int copy)
+{
+    if (!b) return HOP_ERR_INVALID;
+    return b->sched->fail(copy);
+}
+
+int hop_bcast_step(hop_bcast_t *b, int64_t max_chunks)
+{
+    if (!b || max_chunks < 0) return HOP_ERR_INVALID;
+    try {
+        return b->sched->step(max_chunks);
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+int hop_bcast_sender(hop_bcast_t *b, int copy)
+{
+    if (!b || copy < 0 || copy >= b->sched->n_copies()) return HOP_ERR_INVALID;
+    return b->sched->sender_of(copy);
+}
+
+int hop_bcast_finish(hop_bcast_t *b, hop_bcast_info_t *info, hop_bcast_copy_t *log, int log_capacity, int *n_log)
+{
+    if (!b) return HOP_ERR_INVALID;
+    int rc;
+    try {
+        rc = b->sched->drain();
+        if (rc >= 0) rc = b->sched->all_complete() ? HOP_OK : HOP_PARTIAL;
+        if (info) {
+            info->n_receivers = b->sched->n_copies() - 1;
+            info->n_failed = b->sched->n_failed();
+            info->n_resumed = b->sched->n_resumed();
+            info->n_complete = 0;
+            for (int id = 1; id < b->sched->n_copies(); ++id)
+                info->n_complete += !b->sched->failed(id) && b->sched->complete(id);
+            info->chunks_copied = b->sched->chunks_copied();
+        }
+        std::vector<hop_bcast_copy_t> &l = b->log();
+        if (n_log) *n_log = (int)l.size();
+        for (int i = 0; log && i < log_capacity && i < (int)l.size(); ++i) log[i] = l[(size_t)i];
+    } catch (const std::bad_alloc &) {
+        rc = HOP_ERR_NOMEM;
+    }
+    delete b;
+    return rc;
 }
 
 int hop_session_begin(hop_session_t **s, void *dst, const void *const *objs, int n, size_t object_bytes, int k,

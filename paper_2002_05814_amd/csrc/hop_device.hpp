@@ -354,7 +354,7 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
             x[j] = ld16(a.src, off[j]);
         }
         for (int d = 0; d < a.n_dst; ++d) {
-            void *dst = dsts[d];
+            void *dst = a.dsts ? dsts[d] : a.dst0;
 #pragma unroll
             for (int j = 0; j < VPT; ++j)
                 if (live[j]) st16(dst, off[j], x[j]);
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
     if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail_bytes) {
         const size_t off = a.byte_begin + a.n_vec * 16 + threadIdx.x;
         const unsigned char b = *((const unsigned char *)a.src + off);
-        for (int d = 0; d < a.n_dst; ++d) *((unsigned char *)dsts[d] + off) = b;
+        for (int d = 0; d < a.n_dst; ++d) *((unsigned char *)(a.dsts ? dsts[d] : a.dst0) + off) = b;
     }
 }
 

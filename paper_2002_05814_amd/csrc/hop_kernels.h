@@ -56,7 +56,8 @@ struct ReduceArgsInline {
 
 struct CopyArgs {
     const void *src;
-    void *const *dsts;         // device table
+    void *dst0;                // the only destination when dsts is null
+    void *const *dsts;         // device table, or null
     int n_dst;
     size_t byte_begin;
     size_t n_vec;
@@ -92,8 +93,8 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
                               const SubLaunch *dev_subs, int n_subs, size_t byte_begin, size_t byte_end);
 
 // Copy [byte_begin, byte_end) of src into the same range of every destination
-// of the device table dsts.
+// of the device table dsts; with dsts == nullptr and n_dst == 1 into dst0.
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
-                       size_t byte_begin, size_t byte_end);
+                       size_t byte_begin, size_t byte_end, void *dst0 = nullptr);
 
 }  // namespace hop

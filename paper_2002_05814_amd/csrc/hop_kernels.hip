@@ -131,11 +131,13 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
 constexpr int kCopyVpt = 8;
 
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
-                       size_t byte_begin, size_t byte_end)
+                       size_t byte_begin, size_t byte_end, void *dst0)
 {
     if (byte_end <= byte_begin || n_dst <= 0) return hipSuccess;
+    if (!dsts && (n_dst != 1 || !dst0)) return hipErrorInvalidValue;
     CopyArgs a;
     a.src = src;
+    a.dst0 = dst0;
     a.dsts = dsts;
     a.n_dst = n_dst;
     a.byte_begin = byte_begin;

@@ -7,6 +7,7 @@
 #include <random>
 #include <vector>
 
+#include "../../paper_2002_05814_amd/csrc/hop_bcast.hpp"
 #include "../../paper_2002_05814_amd/csrc/hop_plan.hpp"
 
 using namespace hop;
@@ -46,6 +47,41 @@ struct CheckingBackend : Backend {
         return HOP_OK;
     }
 };
+
+struct CheckingBcast : BcastBackend {
+    int64_t C = 0;
+    std::map<int, int64_t> have;
+    int copy(int from, int to, int64_t c0, int64_t c1) override
+    {
+        if (from == to || to < 1 || c0 >= c1 || c1 > C) { std::printf("bad copy\n"); std::abort(); }
+        if (have[to] != c0) { std::printf("receiver %d has %ld, copy starts at %ld\n", to, (long)have[to], (long)c0); std::abort(); }
+        if (from != 0 && have[from] < c1) { std::printf("sender lacks the chunks\n"); std::abort(); }
+        have[to] = c1;
+        return HOP_OK;
+    }
+};
+
+static void fuzz_bcast(std::mt19937_64 &rng)
+{
+    auto rnd = [&](int lo, int hi) { return lo + (int)(rng() % (uint64_t)(hi - lo + 1)); };
+    CheckingBcast be;
+    be.C = rnd(1, 8);
+    BcastScheduler s(be.C, &be);
+    int64_t src = 0;
+    const int ops = rnd(1, 60);
+    for (int i = 0; i < ops; ++i) {
+        const int what = rnd(0, 9);
+        if (what < 3) { src = std::min<int64_t>(be.C, src + rnd(0, 2)); if (s.source_ready(src) != HOP_OK) std::abort(); }
+        else if (what < 6) { int sender; s.join(&sender); }
+        else if (what == 6 && s.n_copies() > 1) s.fail(rnd(1, s.n_copies() - 1));
+        else if (s.step(rnd(0, 2)) < 0) std::abort();
+        for (int a = 1; a < s.n_copies(); ++a)
+            for (int b2 = a + 1; b2 < s.n_copies(); ++b2)
+                if (s.sender_of(a) >= 0 && s.sender_of(a) == s.sender_of(b2)) { std::printf("two receivers on one sender\n"); std::abort(); }
+    }
+    s.source_ready(be.C);
+    if (s.drain() < 0 || !s.all_complete()) { std::printf("broadcast did not complete\n"); std::abort(); }
+}
 
 int main(int argc, char **argv)
 {
@@ -117,6 +153,7 @@ int main(int argc, char **argv)
         compile_program(tr, occ, prog);
         MultiPlan mp;
         plan_passes(prog, (size_t)rnd(1, 40), rnd(1, 6), mp);
+        fuzz_bcast(rng);
     }
     std::printf("ok %d sessions, %ld launches\n", rounds, total_launches);
     return 0;

@@ -236,6 +236,40 @@ def test_broadcast_paper_object_and_ragged_sizes():
     assert hop.hop_broadcast([], src, 16) == hop.HOP_OK
 
 
+def test_receiver_driven_broadcast_chains_and_survives_a_lost_copy():
+    d = dev()
+    rng = np.random.default_rng(21)
+    C, chunk = 7, 4096
+    nbytes = (C - 1) * chunk + 1000
+    blob = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+    src = torch.from_numpy(blob).to(d)
+    bufs = [torch.zeros(nbytes, dtype=torch.uint8, device=d) for _ in range(6)]
+    rc, b = hop.hop_bcast_begin(src, nbytes, chunk)
+    assert rc == hop.HOP_OK
+    assert hop.hop_bcast_source_ready(b, 3) == hop.HOP_OK              # the original is still being written
+    ids = []
+    for i in range(3):
+        rid, s = hop.hop_bcast_join(b, bufs[i])
+        ids.append(rid)
+        assert hop.hop_bcast_step(b, 1) == hop.HOP_OK
+    assert [hop.hop_bcast_sender(b, r) for r in ids] == [0, 1, 2]      # a chain through partial copies
+    assert hop.hop_bcast_fail(b, ids[1]) == hop.HOP_OK                 # the middle of the chain is lost
+    assert hop.hop_bcast_source_ready(b, C) == hop.HOP_OK
+    for i in range(3, 6):
+        rid, s = hop.hop_bcast_join(b, bufs[i])
+        ids.append(rid)
+        hop.hop_bcast_step(b, 2)
+    assert hop.hop_bcast_join(b, bufs[0])[0] == hop.HOP_ERR_INVALID    # a buffer cannot be two copies
+    rc, info, log = hop.hop_bcast_finish(b)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and info["n_complete"] == 5 and info["n_failed"] == 1 and info["n_resumed"] == 1
+    want = oracle.broadcast(blob, 1)[0]
+    for i, buf in enumerate(bufs):
+        if i != 1:
+            assert np.array_equal(buf.cpu().numpy(), want), i
+    assert info["chunks_copied"] == sum(c1 - c0 for _, _, c0, c1 in log)
+
+
 # ------------------------------------------------------------------ event-level sessions
 
 def session_replay(objs, dst, k, op, dtype, chunk, d, order, fm, C, fine, eager=0):
