@@ -575,3 +575,41 @@ def test_cfg4_full_size_failure_sampled():
     torch.cuda.synchronize()
     assert rc2 == hop.HOP_PARTIAL and info2["chunks_redone"] == 31 * 31
     assert torch.equal(dst.view(torch.int16), dst2.view(torch.int16))
+
+
+def test_two_host_threads_on_their_own_streams_and_shutdown():
+    import threading
+    d = dev()
+    w = workloads.WORKLOADS[2].scaled(1 << 20, 64 << 10)
+    objs = workloads.make_objects(w, device=d)
+    host = [workloads.to_numpy(o) for o in objs]
+    order = w.ready_order()
+    _, want, _, _ = oracle.reduce(host, w.k, oracle.SUM, oracle.F32, w.chunk_bytes // 4, w.tree_degree, order, None)
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(seed):
+        try:
+            st = torch.cuda.Stream()
+            dst = torch.zeros_like(objs[0])
+            for _ in range(50):
+                rc, info = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None,
+                                          stream=st)
+                assert rc == hop.HOP_OK
+            st.synchronize()
+            assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+        except Exception as e:            # noqa: BLE001 - reported to the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    assert hop.hop_shutdown() == hop.HOP_OK          # cached workspaces freed; the library keeps working after
+    dst = torch.zeros_like(objs[0])
+    rc, _ = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(want))

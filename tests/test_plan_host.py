@@ -462,3 +462,13 @@ def test_failure_keeps_partials_that_never_absorbed_the_failed_object():
     # restarted chunks run all five steps, the others only the one that was missing
     assert sorted((l[0], l[1], l[4], l[5]) for l in after) == [(0, 2, 0, 5), (2, 4, 4, 5)]
     assert info["chunks_redone"] == 2 * 5
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    # there is no CPU fallback: without the built library every entry point raises
+    monkeypatch.setattr(hop, "_lib", None)
+    monkeypatch.setattr(hop, "LIB_PATH", str(tmp_path / "libhop.so"))
+    with pytest.raises(RuntimeError, match="libhop.so is missing"):
+        hop.hop_plan_slots(4, 2)
+    with pytest.raises(RuntimeError):
+        hop.hop_reduce(0, [], 1, "sum", "f32", 16, 2, object_bytes=0)
