@@ -210,7 +210,7 @@ def test_failure_free_call_is_one_launch_over_all_chunks():
         assert launches == [(0, w.n_chunks, 0, w.k, 0, w.k, 1, 0, 0)] and info["n_launches"] == 1
         # only the first k arrivals are ever read
         assert sorted(e[0] for e in entries) == sorted(w.ready_order()[:w.k].tolist())
-    # survey's stack depths: 3, 3, 4 for configs 1, 2, 5; config 3 picks a degree from {1, 2, k}
+    # accumulator levels needed: 3, 3, 4 for workloads 1, 2, 5; workload 3 picks a degree from {1, 2, k}
     depths = {}
     for cfg in (1, 2, 3, 5):
         w = workloads.WORKLOADS[cfg]
