@@ -34,7 +34,7 @@ int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-           "workgroup (1 KiB tiles, unroll 8 below 2048 tiles), nontemporal loads+stores, programs <= 32 steps in "
+           "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768), nontemporal loads+stores, programs <= 32 steps in "
            "kernel arguments; "
            "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal";
 }
@@ -71,15 +71,20 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     a.base.dst = dst;
     a.base.subs = nullptr;
     fill_range(a.base, dtype, byte_begin, byte_end);
-    const bool small = grid_for(a.base.n_vec, (size_t)kThreads * l.vpt) < kSmallLaunchTiles;
-    const unsigned grid = grid_for(a.base.n_vec, (size_t)kThreads * (small ? 1 : l.vpt));
+    // shape by the amount of work, measured in 4 KiB tiles of the range
+    const size_t tiles4k = (a.base.n_vec + 255) / 256;
+    const int shape = tiles4k < kSmallLaunchTiles ? 0 : tiles4k < kMidLaunchTiles ? 1 : 2;
+    const int vpt = shape == 0 ? 1 : shape == 1 ? (l.vpt < kMidVecs ? l.vpt : kMidVecs) : l.vpt;
+    const unsigned grid = grid_for(a.base.n_vec, (size_t)kThreads * vpt);
     if (n_entries <= kInlineEntries) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
         for (int i = n_entries; i < kInlineEntries; ++i) a.steps[i] = DevEntry{nullptr, 0, 0};
-        hipLaunchKernelGGL(small ? l.inl_small : l.inl, dim3(grid), dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), 0,
+                           stream, a);
     } else {
         if (!dev_prog) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(small ? l.dev_small : l.dev, dim3(grid), dim3(kThreads), 0, stream, a.base);
+        hipLaunchKernelGGL(shape == 0 ? l.dev_small : shape == 1 ? l.dev_mid : l.dev, dim3(grid), dim3(kThreads), 0,
+                           stream, a.base);
     }
     return hipGetLastError();
 }

@@ -20,6 +20,8 @@ template <int DT, int OP, int D> static Launcher make_launcher()
     return {reduce_kernel<DT, OP, D, V, kUnroll, kThreads>, reduce_kernel_inline<DT, OP, D, V, kUnroll, kThreads>,
             reduce_kernel<DT, OP, D, 1, kSmallUnroll, kThreads>,
             reduce_kernel_inline<DT, OP, D, 1, kSmallUnroll, kThreads>,
+            reduce_kernel<DT, OP, D, (V < kMidVecs ? V : kMidVecs), kMidUnroll, kThreads>,
+            reduce_kernel_inline<DT, OP, D, (V < kMidVecs ? V : kMidVecs), kMidUnroll, kThreads>,
             reduce_kernel_seg<DT, OP, D, V, kUnroll, kThreads>, V};
 }
 
