@@ -27,7 +27,7 @@ MEASURED_TRAFFIC = {
     "workload": "cfg2_async_sgd",
     "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile "
                      "per workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768), "
-                     "nontemporal loads+stores, programs <= 32 steps in kernel arguments; "
+                     "nontemporal loads+stores, programs <= 128 steps in kernel arguments; "
                      "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal",
     "bytes": 872458034,
 }

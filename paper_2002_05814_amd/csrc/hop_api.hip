@@ -286,14 +286,15 @@ private:
     // the whole program alone, so the independent subtrees are evaluated side by side first.
     // Partials are stored in the accumulation type, which for bf16 is not the element type: bf16
     // keeps the plain path.
-    static constexpr size_t kSplitMinSteps = 64;        // shorter programs are not worth two launches
+    static constexpr size_t kSplitWantSteps = 128;      // shorter programs are not worth extra launches and a staging copy
+    static constexpr size_t kSplitMinSteps = 64;        // once cutting, (sub-)programs this long are cut again
     static constexpr size_t kSplitMaxBytes = 1u << 20;  // launches this large already fill the chip
     static constexpr int kSplitMinRun = 4;
     static constexpr size_t kSplitMaxScratch = 16u << 20;
 
     bool wants_split(size_t n_steps, size_t range_bytes) const
     {
-        return dtype_ != HOP_BF16 && n_steps >= kSplitMinSteps && range_bytes <= kSplitMaxBytes;
+        return dtype_ != HOP_BF16 && n_steps >= kSplitWantSteps && range_bytes <= kSplitMaxBytes;
     }
 
     int launch_split(const std::vector<Entry> &prog, size_t b0, size_t b1)

@@ -34,7 +34,7 @@ int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-           "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768), nontemporal loads+stores, programs <= 32 steps in "
+           "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768), nontemporal loads+stores, programs <= 128 steps in "
            "kernel arguments; "
            "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal";
 }
@@ -78,7 +78,6 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     const unsigned grid = grid_for(a.base.n_vec, (size_t)kThreads * vpt);
     if (n_entries <= kInlineEntries) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
-        for (int i = n_entries; i < kInlineEntries; ++i) a.steps[i] = DevEntry{nullptr, 0, 0};
         hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), 0,
                            stream, a);
     } else {
