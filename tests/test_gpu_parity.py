@@ -613,3 +613,49 @@ def test_two_host_threads_on_their_own_streams_and_shutdown():
     rc, _ = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
     torch.cuda.synchronize()
     assert rc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+
+
+def test_objects_larger_than_4_gib_use_64_bit_offsets():
+    d = dev()
+    n_elems = (1 << 30) + 1024 + 3                  # 4 GiB + 4 KiB + 12 bytes of int32: tail included
+    a = torch.arange(n_elems, dtype=torch.int32, device=d)
+    b = torch.full((n_elems,), 7, dtype=torch.int32, device=d)
+    b[-5:] = torch.tensor([1, 2, 3, 4, 5], dtype=torch.int32, device=d)
+    dst = torch.zeros(n_elems, dtype=torch.int32, device=d)
+    print("large object", n_elems * 4, flush=True)
+    rc, info = hop.hop_reduce(dst, [a, b], 2, "sum", "i32", 256 << 20, 1, None, None)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and info["n_launches"] == 1
+    assert torch.equal(dst, a + b)
+    # and a failure beyond the 4 GiB mark: chunks 0..16 (of 17) are produced twice
+    c = torch.ones(n_elems, dtype=torch.int32, device=d)
+    rc, info = hop.hop_reduce(dst, [a, b, c], 2, "max", "i32", 256 << 20, 2, None, [-1, 16, -1])
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and info["n_replaced"] == 1 and info["chunks_redone"] == 16 * 2
+    assert torch.equal(dst, torch.maximum(a, c))
+
+
+def test_reduce_can_be_captured_in_a_graph_and_replayed():
+    # short programs ride in the kernel arguments: a call is nothing but kernel launches on the
+    # caller's stream, so it can be recorded into a graph; every replay must see the current inputs
+    d = dev()
+    w = workloads.WORKLOADS[1]
+    objs = workloads.make_objects(w, device=d)
+    dst = torch.zeros_like(objs[0])
+    order = w.ready_order()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc, info = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
+    assert rc == hop.HOP_OK
+    rng = np.random.default_rng(5)
+    for rep in range(3):
+        for o in objs:                                # eager work between the replays
+            o.mul_(float(rng.uniform(0.5, 1.5)))
+        dst.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        _, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], w.k, oracle.SUM, oracle.F32,
+                                      w.chunk_bytes // 4, w.tree_degree, order, None)
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want)), rep

@@ -62,6 +62,28 @@ def test_node_combines_first_child_then_self_then_other_children():
     assert run(f32(1.0, 1.0, TWO24, 1.0), d=3)[0] == TWO24 + 4
 
 
+def test_parenthesisation_of_the_two_headline_trees():
+    # the grouping the definition gives for k = 8, d = 2 and k = 12, d = 4, written out by hand with
+    # numpy float32 adds (values with wildly different magnitudes so that every grouping differs)
+    rng = np.random.default_rng(33)
+    a = [(rng.standard_normal(64) * 10.0 ** rng.integers(-4, 5, size=64)).astype(np.float32) for _ in range(12)]
+    f = np.float32
+
+    def add(x, y):
+        return (x + y).astype(f)
+    # k = 8, d = 2: ((((a0+a1)+a2)+a3)+a4) + ((a5+a6)+a7)
+    want8 = add(add(add(add(add(a[0], a[1]), a[2]), a[3]), a[4]), add(add(a[5], a[6]), a[7]))
+    assert np.array_equal(run(a[:8], d=2), want8)
+    # k = 12, d = 4: L = (((a0+a1)+a2)+a3)+a4, M = ((a6+a7)+a8)+a9, result (((L+a5)+M)+a10)+a11
+    L = add(add(add(add(a[0], a[1]), a[2]), a[3]), a[4])
+    M = add(add(add(a[6], a[7]), a[8]), a[9])
+    want12 = add(add(add(add(L, a[5]), M), a[10]), a[11])
+    assert np.array_equal(run(a, d=4), want12)
+    # and they are not the plain left fold
+    fold = functools.reduce(add, a)
+    assert not np.array_equal(want12, fold)
+
+
 def test_min_max_keep_the_earlier_term_on_ties():
     # the comparison forms keep the left operand unless the right one is strictly better, and a node
     # combines [first child, itself, second child] left to right: with -0.0 and +0.0 (equal under
