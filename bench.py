@@ -163,8 +163,12 @@ def main():
             counted = (k_eff + 1) * w.object_bytes
             if w.n_dst:
                 counted = (k_eff + w.n_dst) * w.object_bytes        # least traffic of reduce + broadcast
+            # what the launches really moved (repairs included), from the scheduler's own account
+            moved = (state["info"]["chunk_steps"] + state["info"]["chunk_stores"]) * min(w.chunk_bytes, w.object_bytes)
+            if w.n_dst:
+                moved += w.n_dst * w.object_bytes       # copy kernel: 1 read + (n_dst - 1) writes
             results[op] = {"ms": ms, "wall_ms": wall_ms, "gbs": counted / (ms * 1e-3) / 1e9, "bytes": counted,
-                           "info": state["info"], "status": state["rc"]}
+                           "moved_gbs": moved / (ms * 1e-3) / 1e9, "info": state["info"], "status": state["rc"]}
         return w, objs, order, dsts, results
 
     w, objs, order, dsts, res = run_workload(args.workload, args.steps, args.warmup)
@@ -226,6 +230,7 @@ def main():
                 extra["%s/%s" % (wk.name, opn)] = {"GB/s": round(rr["gbs"], 2), "ms": round(rr["ms"], 5),
                                                   "frac_of_hbm_peak": round(rr["gbs"] / HBM_PEAK_GBS, 4),
                                                   "counted_bytes": rr["bytes"], "status": rr["status"],
+                                                  "GB/s_moved_incl_repair": round(rr["moved_gbs"], 2),
                                                   "launches": rr["info"]["n_launches"]}
             del o2, d2
             torch.cuda.empty_cache()

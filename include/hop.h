@@ -70,6 +70,10 @@ typedef struct {
                                counted once per source object read again             */
     int32_t n_launches;     /* reduce kernels enqueued                                */
     int32_t stack_depth;    /* partial results live at once (<= HOP_MAX_DEPTH)        */
+    int64_t chunk_steps;    /* work actually enqueued: sum over launches of chunks x
+                               program steps (= source chunks read), repairs included */
+    int64_t chunk_stores;   /* sum over launches of chunks whose result or accumulators
+                               were written                                           */
 } hop_info_t;
 
 /*

@@ -39,7 +39,7 @@ class HopInfo(ctypes.Structure):
     _fields_ = [("k_eff", ctypes.c_int32), ("n_failed_seen", ctypes.c_int32),
                 ("n_replaced", ctypes.c_int32), ("degree_used", ctypes.c_int32),
                 ("chunks_redone", ctypes.c_int64), ("n_launches", ctypes.c_int32),
-                ("stack_depth", ctypes.c_int32)]
+                ("stack_depth", ctypes.c_int32), ("chunk_steps", ctypes.c_int64), ("chunk_stores", ctypes.c_int64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}

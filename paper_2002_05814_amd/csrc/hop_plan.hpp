@@ -386,6 +386,8 @@ public:
             if (rc < 0) return rc;
             info_.n_launches++;
             info_.chunks_redone += p.redo;
+            info_.chunk_steps += (p.c1 - p.c0) * (int64_t)(p.t1 - p.t0);
+            info_.chunk_stores += (p.c1 - p.c0) * (int64_t)(final ? 1 : live_levels(p.t1));
         }
         done_.swap(next);
         return HOP_OK;

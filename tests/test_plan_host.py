@@ -34,8 +34,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_info_struct_layout_matches_header():
-    # int32 x4, int64, int32 x2 -> 32 bytes with natural alignment
-    assert ctypes.sizeof(hop.HopInfo) == 32
+    # int32 x4, int64, int32 x2, int64 x2 -> 48 bytes with natural alignment
+    assert ctypes.sizeof(hop.HopInfo) == 48
     assert hop.HopInfo.chunks_redone.offset == 16
     assert ctypes.sizeof(hop.PlanEntry) == 8 and ctypes.sizeof(hop.PlanLaunch) == 48
 
@@ -234,6 +234,7 @@ def test_mid_stream_failure_redoes_only_the_chunks_already_produced():
     assert len(first) == 32 and 7 in {e[0] for e in first}
     assert len(second) == 31 and 7 not in {e[0] for e in second}
     assert info["chunks_redone"] == 10 * 31 and info["n_launches"] == 2
+    assert info["chunk_steps"] == 10 * 32 + 32 * 31 and info["chunk_stores"] == 10 + 32
     # the survivors keep their relative order
     assert [e[0] for e in second] == [e[0] for e in first if e[0] != 7]
     # the failure time changes the repair work, never the final program
