@@ -4,6 +4,7 @@
 // device, and the recording back end behind hop_plan_reduce.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <memory>
@@ -34,29 +35,58 @@ static std::mutex g_mu;
 static std::vector<Block *> g_free;
 static constexpr size_t kMinBlock = 256 * 1024;
 
+// At most this many staging blocks exist per process; a caller that runs further ahead of the
+// GPU than that waits for the oldest block instead of allocating without bound.
+static constexpr int kMaxBlocks = 4;
+static int g_block_count = 0;
+
 static Block *acquire_block(int device, size_t bytes)
 {
+    Block *wait_for = nullptr;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         for (size_t i = 0; i < g_free.size(); ++i) {
             Block *b = g_free[i];
             if (b->device != device || b->cap < bytes) continue;
             if (b->pending) {
-                if (hipEventQuery(b->ev) != hipSuccess) { (void)hipGetLastError(); continue; }
+                if (hipEventQuery(b->ev) != hipSuccess) {
+                    (void)hipGetLastError();
+                    if (!wait_for) wait_for = b;          // g_free is in release order: the oldest one
+                    continue;
+                }
                 b->pending = false;
             }
             g_free.erase(g_free.begin() + i);
             return b;
         }
+        if (wait_for && g_block_count >= kMaxBlocks) {
+            g_free.erase(std::find(g_free.begin(), g_free.end(), wait_for));
+        } else {
+            wait_for = nullptr;
+            g_block_count++;
+        }
+    }
+    if (wait_for) {
+        if (hipEventSynchronize(wait_for->ev) != hipSuccess) (void)hipGetLastError();
+        wait_for->pending = false;
+        return wait_for;
     }
     Block *b = new (std::nothrow) Block;
-    if (!b) return nullptr;
-    b->device = device;
-    b->cap = bytes < kMinBlock ? kMinBlock : ((bytes + kMinBlock - 1) / kMinBlock) * kMinBlock;
-    if (hipHostMalloc((void **)&b->host, b->cap, hipHostMallocDefault) != hipSuccess) { delete b; return nullptr; }
-    if (hipMalloc((void **)&b->dev, b->cap) != hipSuccess) { (void)hipHostFree(b->host); delete b; return nullptr; }
-    if (hipEventCreateWithFlags(&b->ev, hipEventDisableTiming) != hipSuccess) {
-        (void)hipFree(b->dev); (void)hipHostFree(b->host); delete b; return nullptr;
+    bool ok = b != nullptr;
+    if (ok) {
+        b->device = device;
+        b->cap = bytes < kMinBlock ? kMinBlock : ((bytes + kMinBlock - 1) / kMinBlock) * kMinBlock;
+        ok = hipHostMalloc((void **)&b->host, b->cap, hipHostMallocDefault) == hipSuccess;
+        if (ok && hipMalloc((void **)&b->dev, b->cap) != hipSuccess) { (void)hipHostFree(b->host); ok = false; }
+        if (ok && hipEventCreateWithFlags(&b->ev, hipEventDisableTiming) != hipSuccess) {
+            (void)hipFree(b->dev); (void)hipHostFree(b->host); ok = false;
+        }
+    }
+    if (!ok) {
+        delete b;
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_block_count--;
+        return nullptr;
     }
     return b;
 }
@@ -83,23 +113,37 @@ static constexpr size_t kDevCacheLimit = (size_t)8 << 30;     // beyond this, id
 
 static DevBuf *acquire_devbuf(int device, size_t bytes)
 {
+    DevBuf *wait_for = nullptr;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         DevBuf *best = nullptr;
-        size_t best_i = 0;
-        for (size_t i = 0; i < g_devbufs.size(); ++i) {
-            DevBuf *b = g_devbufs[i];
+        int n_busy = 0;
+        for (DevBuf *b : g_devbufs) {
             if (b->device != device || b->cap < bytes) continue;
             if (b->pending) {
-                if (hipEventQuery(b->ev) != hipSuccess) { (void)hipGetLastError(); continue; }
+                if (hipEventQuery(b->ev) != hipSuccess) {
+                    (void)hipGetLastError();
+                    if (!wait_for) wait_for = b;          // release order: the oldest one
+                    ++n_busy;
+                    continue;
+                }
                 b->pending = false;
             }
-            if (!best || b->cap < best->cap) { best = b; best_i = i; }
+            if (!best || b->cap < best->cap) best = b;
         }
         if (best) {
-            g_devbufs.erase(g_devbufs.begin() + best_i);
+            g_devbufs.erase(std::find(g_devbufs.begin(), g_devbufs.end(), best));
             return best;
         }
+        // two buffers in flight are enough to overlap one session's tail with the next one's
+        // start; beyond that, wait for the oldest instead of growing
+        if (wait_for && n_busy >= 2) g_devbufs.erase(std::find(g_devbufs.begin(), g_devbufs.end(), wait_for));
+        else wait_for = nullptr;
+    }
+    if (wait_for) {
+        if (hipEventSynchronize(wait_for->ev) != hipSuccess) (void)hipGetLastError();
+        wait_for->pending = false;
+        return wait_for;
     }
     DevBuf *b = new (std::nothrow) DevBuf;
     if (!b) return nullptr;
@@ -923,6 +967,7 @@ int hop_shutdown(void)
         (void)hipFree(b->dev);
         (void)hipHostFree(b->host);
         delete b;
+        g_block_count--;
     }
     g_free.clear();
     for (DevBuf *b : g_devbufs) {
