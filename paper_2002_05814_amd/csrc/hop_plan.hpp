@@ -42,6 +42,9 @@ struct Tree {
         return (x < k) ? x : -1;
     }
 
+    // shape only: enough for compile_program, which walks the tree itself
+    void shape(int k_, int64_t d_) { k = k_; d = d_; }
+
     void build(int k_, int64_t d_) {
         k = k_;
         d = d_;
@@ -87,40 +90,44 @@ struct Tree {
 inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant, std::vector<Entry> &out)
 {
     out.clear();
+    out.reserve(occupant.size());
     int depth = 0;
-    if (tr.d == 1 || tr.k == 1) {
+    const int k = tr.k;
+    const int64_t d = tr.d;
+    if (d == 1 || k == 1) {
         // chain: plain left fold in arrival order
-        for (int t = 0; t < tr.k; ++t) {
+        for (int t = 0; t < k; ++t) {
             if (occupant[t] == -1) continue;
             out.push_back({occupant[t], 0, (uint8_t)out.empty(), 0});
         }
         return out.empty() ? 0 : 1;
     }
-    // d >= 2: height <= log2(k), recursion is shallow
+    // d >= 2: height <= log2(k), recursion is shallow. The walk is the in-order traversal
+    // itself, so the next position in arrival order is simply a running counter.
     struct R {
-        const Tree &tr; const std::vector<int32_t> &occ; std::vector<Entry> &out; int &depth;
+        const int k; const int64_t d; const int32_t *occ; std::vector<Entry> &out; int &depth; int slot;
         bool emit(int64_t j, int level) {
             bool started = false;
-            int64_t c1 = tr.child(j, 1);
-            if (c1 >= 0) started = emit(c1, level);
-            int32_t o = occ[tr.slot_of_node[j]];
+            const int64_t c1 = d * j + 1;
+            if (c1 < k) started = emit(c1, level);
+            const int32_t o = occ[slot++];
             if (o != -1) {                    // an object, or a position still to be taken
                 out.push_back({o, (uint8_t)level, (uint8_t)!started, 0});
-                depth = std::max(depth, level + 1);
+                if (level + 1 > depth) depth = level + 1;
                 started = true;
             }
-            for (int64_t c = 2; c <= tr.d; ++c) {
-                int64_t ch = tr.child(j, c);
-                if (ch < 0) break;
+            for (int64_t c = 2; c <= d; ++c) {
+                const int64_t ch = d * j + c;
+                if (ch >= k) break;
                 if (!started) {
                     started = emit(ch, level);
-                } else if (level + 1 < 255 && emit(ch, level + 1)) {
+                } else if (emit(ch, level + 1)) {     // d >= 2: at most log2(k) < 32 levels
                     out.back().n_fold++;
                 }
             }
             return started;
         }
-    } r{tr, occupant, out, depth};
+    } r{k, d, occupant.data(), out, depth, 0};
     r.emit(0, 0);
     return depth;
 }
@@ -145,6 +152,8 @@ inline bool split_program(const std::vector<Entry> &prog, int min_run, SplitPlan
 {
     out = SplitPlan();
     const int n = (int)prog.size();
+    out.sub_entries.reserve(prog.size());
+    out.top.reserve(prog.size() / 2 + 8);
     int i = 0;
     while (i < n) {
         const Entry &e = prog[i];
@@ -215,7 +224,8 @@ inline int split_recursive(const std::vector<Entry> &prog, size_t min_steps, int
         std::vector<Entry> final_steps;
         const int h = split_recursive(steps, min_steps, min_run, mp, final_steps);
         global_id[s] = (int)mp.subs.size();
-        mp.subs.push_back({final_steps, h, program_depth(final_steps)});
+        const int sub_depth = program_depth(final_steps);
+        mp.subs.push_back({std::move(final_steps), h, sub_depth});
         height = std::max(height, h + 1);
     }
     out = sp.top;
@@ -236,7 +246,7 @@ inline bool plan_passes(const std::vector<Entry> &prog, size_t min_steps, int mi
 inline int full_tree_depth(int k, int64_t d)
 {
     Tree tr;
-    tr.build(k, d);
+    tr.shape(k, d);
     std::vector<int32_t> occ(k, 0);
     std::vector<Entry> prog;
     return compile_program(tr, occ, prog);
@@ -264,7 +274,7 @@ public:
         : n_(n), k_(k), C_(n_chunks), be_(be),
           ready_(n, 0), state_(n, UNSEEN), slot_of_obj_(n, -1), occupant_(k, -1)
     {
-        tree_.build(k, degree);
+        tree_.shape(k, degree);
         done_.push_back({C_, 0, 0, false});
     }
 
@@ -273,6 +283,31 @@ public:
     // have become runnable, saving its accumulators in between (work overlaps the wait
     // for late participants, at the price of extra traffic).
     void set_eager(int min_steps) { eager_ = min_steps < 0 ? 0 : min_steps; }
+
+    // Bulk form of on_ready(obj, all chunks) for objects that arrive complete, in this order.
+    // Same effect as calling on_ready(objs[i], n_chunks) one by one.
+    int on_arrive_complete(const int *objs, int count)
+    {
+        for (int i = 0; i < count; ++i) {
+            const int obj = objs[i];
+            if (obj < 0 || obj >= n_) return HOP_ERR_INVALID;
+            if (state_[obj] != UNSEEN || !holes_.empty()) {      // not the plain case: take the general path
+                int rc = on_ready(obj, C_);
+                if (rc < 0) return rc;
+                continue;
+            }
+            state_[obj] = COMPLETE;
+            ready_[obj] = C_;
+            if (next_free_ < k_) {
+                occupant_[next_free_] = obj;
+                slot_of_obj_[obj] = next_free_++;
+                version_++;
+            } else {
+                pool_.push_back(obj);
+            }
+        }
+        return HOP_OK;
+    }
 
     // Object obj has chunks [0, c) ready. First call = arrival.
     int on_ready(int obj, int64_t c)
@@ -518,6 +553,7 @@ inline int replay_reduce(Scheduler &s, int n, int64_t C, const int32_t *ready_or
                          const int64_t *fail_mask, hop_info_t *info)
 {
     std::vector<int> arrival;
+    arrival.reserve(n);
     std::vector<int64_t> limit(n, C);
     std::vector<int64_t> steps;
     for (int t = 0; t < n; ++t) {
@@ -527,9 +563,14 @@ inline int replay_reduce(Scheduler &s, int n, int64_t C, const int32_t *ready_or
         arrival.push_back(i);
         if (limit[i] < C) steps.push_back(limit[i]);
     }
+    int rc;
+    if (steps.empty()) {
+        // nobody fails part-way: everyone announces itself and delivers everything, one launch
+        if ((rc = s.on_arrive_complete(arrival.data(), (int)arrival.size())) < 0) return rc;
+        return s.finish(info);
+    }
     std::sort(steps.begin(), steps.end());
     steps.erase(std::unique(steps.begin(), steps.end()), steps.end());
-    int rc;
     for (int i : arrival)
         if ((rc = s.on_ready(i, 0)) < 0) return rc;
     for (int64_t step : steps) {
