@@ -13,7 +13,7 @@
  *     "host pointer"   = ordinary process memory.
  *   - Objects are immutable (section 3.3): the library never writes a source
  *     object and never frees caller memory. Destinations must not overlap any
- *     source.
+ *     source nor each other.
  *   - Device buffers (sources, destinations) must be 16-byte aligned.
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and return without waiting for the GPU, like the
@@ -129,8 +129,9 @@ int hop_reduce(void *dst, const void *const *objs, int n, size_t object_bytes,
  *   dsts   host array of n_dst device pointers (object_bytes each); n_dst >= 0.
  *   src    device pointer, object_bytes bytes.
  * The source is read once per chunk and written to every destination.
- * Errors: HOP_ERR_INVALID (n_dst < 0, NULL table, chunk_bytes 0 or not a
- * multiple of 16), HOP_ERR_ALIGN, HOP_ERR_DEVICE/NOMEM.
+ * Errors: HOP_ERR_INVALID (n_dst < 0, NULL table or entry, chunk_bytes 0 or
+ * not a multiple of 16, destinations overlapping the source or each other),
+ * HOP_ERR_ALIGN, HOP_ERR_DEVICE/NOMEM.
  */
 int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_bytes,
                   size_t chunk_bytes, void *stream);

@@ -35,9 +35,11 @@ static std::mutex g_mu;
 static std::vector<Block *> g_free;
 static constexpr size_t kMinBlock = 256 * 1024;
 
-// At most this many staging blocks exist per process; a caller that runs further ahead of the
-// GPU than that waits for the oldest block instead of allocating without bound.
-static constexpr int kMaxBlocks = 4;
+// Once this many staging blocks exist, a caller that finds a large enough block still in use
+// by the GPU waits for the oldest such block instead of allocating another: a host that runs
+// ahead of the GPU is slowed down rather than growing the cache without bound. (Blocks held
+// by open sessions are not in the cache and are not waited for.)
+static constexpr int kMaxBlocks = 8;
 static int g_block_count = 0;
 
 static Block *acquire_block(int device, size_t bytes)
@@ -199,6 +201,17 @@ public:
         return d;
     }
 
+    // Makes sure the next `bytes` of stage()/scratch() requests come from one block.
+    bool reserve(size_t bytes)
+    {
+        if (!blocks_.empty() && used_ + bytes <= blocks_.back()->cap) return true;
+        Block *b = acquire_block(device_, bytes);
+        if (!b) return false;
+        blocks_.push_back(b);
+        used_ = 0;
+        return true;
+    }
+
     // Uninitialised device scratch (256-byte aligned), valid until the workspace is released.
     void *scratch(size_t bytes)
     {
@@ -347,8 +360,12 @@ private:
         if (!plan_passes(prog, kSplitMinSteps, kSplitMinRun, mp)) return HOP_PARTIAL;
         const size_t range = b1 - b0;
         const size_t part_bytes = (range + 255) & ~(size_t)255;
-        if (part_bytes * mp.subs.size() > kSplitMaxScratch || mp.subs.size() > 65535) return HOP_PARTIAL;
-        char *partials = (char *)ws_.scratch(part_bytes * mp.subs.size());
+        const size_t n_subs = mp.n_subs();
+        if (part_bytes * n_subs > kSplitMaxScratch || n_subs > 65535) return HOP_PARTIAL;
+        // partials, every step once, one table entry per sub-program: from one block
+        if (!ws_.reserve(part_bytes * n_subs + (prog.size() + 2 * n_subs) * sizeof(DevEntry) + 512))
+            return HOP_ERR_NOMEM;
+        char *partials = (char *)ws_.scratch(part_bytes * n_subs);
         if (!partials) return HOP_ERR_NOMEM;
         // Kernels address sources and results by the object's byte offset, so a partial that holds
         // only [b0, b1) is passed as base - b0. Passes run in stream order: pass h reads what
@@ -358,25 +375,28 @@ private:
         std::vector<PassInfo> passes(mp.n_passes);
         std::vector<DevEntry> blob;                     // SubLaunch and DevEntry are both 16 bytes
         static_assert(sizeof(SubLaunch) == sizeof(DevEntry), "one staging array serves both");
+        blob.reserve(mp.steps.size() + n_subs + mp.top.size());
         for (int pass = 0; pass < mp.n_passes; ++pass) {
-            std::vector<SubLaunch> subs;
             PassInfo &pi = passes[pass];
             pi.steps_at = blob.size();
             pi.depth = 1;
-            for (size_t g = 0; g < mp.subs.size(); ++g) {
-                const MultiPlan::Sub &sub = mp.subs[g];
-                if (sub.height != pass) continue;
-                SubLaunch sl;
-                sl.entry_begin = (uint32_t)(blob.size() - pi.steps_at);
-                sl.n_entries = (uint32_t)sub.steps.size();
-                sl.dst = (void *)((uintptr_t)partials + g * part_bytes - b0);
-                subs.push_back(sl);
-                for (const Entry &e : sub.steps) blob.push_back(resolve(e, partials, part_bytes, b0));
-                pi.depth = std::max(pi.depth, sub.depth);
+            pi.n_subs = 0;
+            for (size_t g = 0; g < n_subs; ++g) {
+                if (mp.height[g] != pass) continue;
+                for (int32_t t = mp.begin[g]; t < mp.begin[g + 1]; ++t)
+                    blob.push_back(resolve(mp.steps[(size_t)t], partials, part_bytes, b0));
+                pi.depth = std::max(pi.depth, (int)mp.depth[g]);
+                pi.n_subs++;
             }
             pi.subs_at = blob.size();
-            pi.n_subs = (int)subs.size();
-            for (const SubLaunch &sl : subs) {
+            uint32_t at = 0;
+            for (size_t g = 0; g < n_subs; ++g) {
+                if (mp.height[g] != pass) continue;
+                SubLaunch sl;
+                sl.entry_begin = at;
+                sl.n_entries = (uint32_t)(mp.begin[g + 1] - mp.begin[g]);
+                sl.dst = (void *)((uintptr_t)partials + g * part_bytes - b0);
+                at += sl.n_entries;
                 DevEntry raw;
                 std::memcpy(&raw, &sl, sizeof raw);
                 blob.push_back(raw);
@@ -506,6 +526,22 @@ static int check_buffers(const void *const *objs, int n, void *const *dsts, int 
     return HOP_OK;
 }
 
+// Destinations must not overlap each other (nor be the same buffer twice): sorted by address,
+// neighbours suffice.
+static int check_disjoint(void *const *dsts, int n_dst, size_t object_bytes)
+{
+    try {
+        std::vector<uintptr_t> at((size_t)n_dst);
+        for (int j = 0; j < n_dst; ++j) at[(size_t)j] = (uintptr_t)dsts[j];
+        std::sort(at.begin(), at.end());
+        for (size_t j = 1; j < at.size(); ++j)
+            if (at[j] == at[j - 1] || at[j] - at[j - 1] < object_bytes) return HOP_ERR_INVALID;
+        return HOP_OK;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
 static const double kDefaultLatency = 2e-6;     // seconds per tree level (kernel-launch scale)
 static const double kDefaultBandwidth = 5e12;   // bytes per second (HBM scale)
 
@@ -628,9 +664,8 @@ int hop_allreduce(void *const *dsts, int n_dst, const void *const *objs, int n, 
                   int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info)
 {
     if (!dsts || n_dst < 1) return HOP_ERR_INVALID;
-    for (int a = 0; a < n_dst; ++a)
-        for (int b = a + 1; b < n_dst; ++b)
-            if (dsts[a] == dsts[b]) return HOP_ERR_INVALID;
+    int rc = check_disjoint(dsts, n_dst, object_bytes);
+    if (rc < 0) return rc;
     return reduce_common(dsts, n_dst, objs, n, object_bytes, ready_order, k, (int)op, (int)dtype, chunk_bytes,
                          tree_degree, fail_mask, stream, info);
 }
@@ -647,6 +682,10 @@ int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_b
         if (!aligned16(dsts[j])) return HOP_ERR_ALIGN;
         const char *a = (const char *)src, *b = (const char *)dsts[j];
         if (a < b + object_bytes && b < a + object_bytes) return HOP_ERR_INVALID;
+    }
+    {
+        int rc = check_disjoint(dsts, n_dst, object_bytes);
+        if (rc < 0) return rc;
     }
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
@@ -904,16 +943,12 @@ int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int min_steps
         for (int i = 0; i < n_entries; ++i) prog[i] = {entries[i].obj, entries[i].level, entries[i].set, entries[i].n_fold};
         MultiPlan mp;
         const bool ok = plan_passes(prog, (size_t)min_steps, min_run, mp);
-        std::vector<Entry> flat;
-        std::vector<int32_t> begins;
-        for (const MultiPlan::Sub &sub : mp.subs) {
-            begins.push_back((int32_t)flat.size());
-            flat.insert(flat.end(), sub.steps.begin(), sub.steps.end());
-        }
-        begins.push_back((int32_t)flat.size());
+        const std::vector<Entry> &flat = mp.steps;
+        std::vector<int32_t> begins(mp.begin);
+        if (begins.empty()) begins.push_back(0);
         if (n_top) *n_top = (int)mp.top.size();
         if (n_sub_entries) *n_sub_entries = (int)flat.size();
-        if (n_subs) *n_subs = (int)mp.subs.size();
+        if (n_subs) *n_subs = (int)mp.n_subs();
         if (n_passes) *n_passes = mp.n_passes;
         auto put = [](hop_plan_entry_t *dst, int cap, const std::vector<Entry> &src) {
             for (int i = 0; dst && i < cap && i < (int)src.size(); ++i) {
@@ -923,7 +958,7 @@ int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int min_steps
         put(top, top_capacity, mp.top);
         put(sub_entries, sub_capacity, flat);
         for (int i = 0; sub_begin && i < sub_table_capacity && i < (int)begins.size(); ++i) sub_begin[i] = begins[i];
-        for (int i = 0; sub_pass && i < sub_table_capacity && i < (int)mp.subs.size(); ++i) sub_pass[i] = mp.subs[i].height;
+        for (int i = 0; sub_pass && i < sub_table_capacity && i < (int)mp.n_subs(); ++i) sub_pass[i] = mp.height[(size_t)i];
         return ok ? HOP_OK : HOP_PARTIAL;
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;

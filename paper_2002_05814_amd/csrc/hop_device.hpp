@@ -198,9 +198,11 @@ __device__ __forceinline__ void run_group(M &m, const Prog prog, int t, const si
     using A = typename Traits<DT>::acc_t;
     constexpr int W = Traits<DT>::W;
     uint4 raw[G][VPT];
+    uint32_t ctl[G];                  // fetched with the addresses, not one by one between the folds
 #pragma unroll
     for (int u = 0; u < G; ++u) {
         const void *src = prog[t + u].src;
+        ctl[u] = prog[t + u].ctl;
 #pragma unroll
         for (int j = 0; j < VPT; ++j) raw[u][j] = ld16(src, off[j]);
     }
@@ -209,7 +211,7 @@ __device__ __forceinline__ void run_group(M &m, const Prog prog, int t, const si
         A x[VPT * W];
 #pragma unroll
         for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
-        m.step(prog[t + u].ctl, x);
+        m.step(ctl[u], x);
     }
 }
 

@@ -90,8 +90,6 @@ struct Tree {
 inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant, std::vector<Entry> &out)
 {
     out.clear();
-    out.reserve(occupant.size());
-    int depth = 0;
     const int k = tr.k;
     const int64_t d = tr.d;
     if (d == 1 || k == 1) {
@@ -103,16 +101,26 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
         return out.empty() ? 0 : 1;
     }
     // d >= 2: height <= log2(k), recursion is shallow. The walk is the in-order traversal
-    // itself, so the next position in arrival order is simply a running counter.
-    struct R {
-        const int k; const int64_t d; const int32_t *occ; std::vector<Entry> &out; int &depth; int slot;
-        bool emit(int64_t j, int level) {
+    // itself, so the next position in arrival order is simply a running counter. Most nodes
+    // of a wide tree are leaves: they are emitted without a call.
+    out.resize((size_t)k);
+    struct Walk {
+        const int k; const int64_t d; const int32_t *occ; Entry *out; int n_out; int depth; int slot;
+        bool leaf(int level) {
+            const int32_t o = occ[slot++];
+            if (o == -1) return false;
+            out[n_out++] = Entry{o, (uint8_t)level, 1, 0};
+            if (level + 1 > depth) depth = level + 1;
+            return true;
+        }
+        bool is_leaf(int64_t j) const { return d * j + 1 >= k; }
+        bool node(int64_t j, int level) {
             bool started = false;
             const int64_t c1 = d * j + 1;
-            if (c1 < k) started = emit(c1, level);
+            if (c1 < k) started = is_leaf(c1) ? leaf(level) : node(c1, level);
             const int32_t o = occ[slot++];
             if (o != -1) {                    // an object, or a position still to be taken
-                out.push_back({o, (uint8_t)level, (uint8_t)!started, 0});
+                out[n_out++] = Entry{o, (uint8_t)level, (uint8_t)!started, 0};
                 if (level + 1 > depth) depth = level + 1;
                 started = true;
             }
@@ -120,85 +128,38 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
                 const int64_t ch = d * j + c;
                 if (ch >= k) break;
                 if (!started) {
-                    started = emit(ch, level);
-                } else if (emit(ch, level + 1)) {     // d >= 2: at most log2(k) < 32 levels
-                    out.back().n_fold++;
+                    started = is_leaf(ch) ? leaf(level) : node(ch, level);
+                } else if (is_leaf(ch) ? leaf(level + 1) : node(ch, level + 1)) {     // at most log2(k) < 32 levels
+                    out[n_out - 1].n_fold++;
                 }
             }
             return started;
         }
-    } r{k, d, occupant.data(), out, depth, 0};
-    r.emit(0, 0);
-    return depth;
+    } w{k, d, occupant.data(), out.data(), 0, 0, 0};
+    w.node(0, 0);
+    out.resize((size_t)w.n_out);
+    return w.depth;
 }
 
-// A program cut at its outermost level. Every maximal run of steps that works
-// above level 0 (from the step that starts a level-1 partial to the step whose
-// folds return to level 0) is an independent sub-expression: a non-first-child
-// subtree hanging off the leftmost spine of the tree. Runs of at least min_run
-// steps become sub-programs of their own (levels shifted down by one, the final
-// fold dropped); in the top program such a run is one step that combines the
-// sub-program's stored partial into level 0, which is the same arithmetic as the
-// fold it replaces. Shorter runs stay in the top program unchanged.
-struct SplitPlan {
-    std::vector<Entry> sub_entries;              // all sub-programs, concatenated
-    struct Range { int begin, end; };
-    std::vector<Range> subs;                     // sub-program s = sub_entries[begin, end)
-    std::vector<Entry> top;                      // obj >= 0: object; obj = -(1 + s): partial of sub-program s
-    int sub_depth = 0, top_depth = 0;
-};
-
-inline bool split_program(const std::vector<Entry> &prog, int min_run, SplitPlan &out)
-{
-    out = SplitPlan();
-    const int n = (int)prog.size();
-    out.sub_entries.reserve(prog.size());
-    out.top.reserve(prog.size() / 2 + 8);
-    int i = 0;
-    while (i < n) {
-        const Entry &e = prog[i];
-        if (e.level == 0) {
-            out.top.push_back(e);
-            out.top_depth = std::max(out.top_depth, 1);
-            ++i;
-            continue;
-        }
-        int j = i;                                // find the step that folds back to level 0
-        while (j < n && (int)prog[j].level - (int)prog[j].n_fold != 0) ++j;
-        if (j >= n || !(e.level == 1 && e.set)) return false;     // malformed program: do not split
-        const int len = j - i + 1;
-        if (len >= min_run) {
-            const int begin = (int)out.sub_entries.size();
-            for (int t = i; t <= j; ++t) {
-                Entry s = prog[t];
-                s.level = (uint8_t)(s.level - 1);
-                if (t == j) s.n_fold = (uint16_t)(s.n_fold - 1);
-                out.sub_depth = std::max(out.sub_depth, (int)s.level + 1);
-                out.sub_entries.push_back(s);
-            }
-            out.subs.push_back({begin, (int)out.sub_entries.size()});
-            out.top.push_back({-(int32_t)out.subs.size(), 0, 0, 0});
-        } else {
-            for (int t = i; t <= j; ++t) {
-                out.top.push_back(prog[t]);
-                out.top_depth = std::max(out.top_depth, (int)prog[t].level + 1);
-            }
-        }
-        i = j + 1;
-    }
-    return !out.subs.empty();
-}
-
-// The cut applied recursively: sub-programs that are still long are cut again,
-// so a deep tree becomes a few passes of many short independent programs. A
-// sub-program of height h reads only objects and partials of height < h; pass h
-// evaluates all sub-programs of height h side by side, the top program comes last.
+// A long program cut into short independent ones. Every `set` step above level 0
+// opens a run that ends at the step whose folds return below the run's level: a
+// non-first-child subtree of the tree, an independent sub-expression. A run of at
+// least min_run steps that lies directly in a program of at least min_steps steps
+// becomes a sub-program of its own: its steps with levels counted from the run's
+// level, its last fold dropped; in the program it came from, one step replaces it
+// that combines the sub-program's stored partial into the level below, which is
+// the same arithmetic as the dropped fold. Sub-programs are cut again by the same
+// rule, so a deep tree becomes a few passes of many short programs: a sub-program
+// of height h reads only objects and partials of height < h, pass h evaluates all
+// sub-programs of height h side by side, the top program comes last.
 struct MultiPlan {
-    struct Sub { std::vector<Entry> steps; int height; int depth; };
-    std::vector<Sub> subs;                       // obj = -(1 + g) in any steps names the partial of subs[g]
-    std::vector<Entry> top;
+    std::vector<Entry> steps;                    // all sub-programs: sub g = steps[begin[g], begin[g + 1])
+    std::vector<int32_t> begin;                  // n_subs() + 1 offsets
+    std::vector<int32_t> height, depth;          // per sub-program: pass it runs in, accumulator levels
+    std::vector<Entry> top;                      // obj >= 0: object; obj = -(1 + g): partial of sub-program g
     int top_depth = 0;
     int n_passes = 0;
+    size_t n_subs() const { return height.size(); }
 };
 
 inline int program_depth(const std::vector<Entry> &p)
@@ -208,38 +169,116 @@ inline int program_depth(const std::vector<Entry> &p)
     return d;
 }
 
-// Returns the height of prog (0 = left whole) and its final steps in `out`.
-inline int split_recursive(const std::vector<Entry> &prog, size_t min_steps, int min_run, MultiPlan &mp,
-                           std::vector<Entry> &out)
-{
-    SplitPlan sp;
-    if (prog.size() < min_steps || !split_program(prog, min_run, sp)) {
-        out = prog;
-        return 0;
-    }
-    int height = 0;
-    std::vector<int> global_id(sp.subs.size());
-    for (size_t s = 0; s < sp.subs.size(); ++s) {
-        std::vector<Entry> steps(sp.sub_entries.begin() + sp.subs[s].begin, sp.sub_entries.begin() + sp.subs[s].end);
-        std::vector<Entry> final_steps;
-        const int h = split_recursive(steps, min_steps, min_run, mp, final_steps);
-        global_id[s] = (int)mp.subs.size();
-        const int sub_depth = program_depth(final_steps);
-        mp.subs.push_back({std::move(final_steps), h, sub_depth});
-        height = std::max(height, h + 1);
-    }
-    out = sp.top;
-    for (Entry &e : out)
-        if (e.obj < 0) e.obj = -(int32_t)(1 + global_id[-e.obj - 1]);
-    return height;
-}
-
+// Returns false (top = prog, no sub-programs) if nothing was cut or the program is malformed.
 inline bool plan_passes(const std::vector<Entry> &prog, size_t min_steps, int min_run, MultiPlan &mp)
 {
     mp = MultiPlan();
-    mp.n_passes = split_recursive(prog, min_steps, min_run, mp, mp.top);
-    mp.top_depth = program_depth(mp.top);
-    return mp.n_passes > 0;
+    const int n = (int)prog.size();
+    auto whole = [&]() {
+        mp = MultiPlan();
+        mp.top = prog;
+        mp.top_depth = program_depth(prog);
+        return false;
+    };
+    if ((size_t)n < min_steps || n == 0) return whole();
+
+    // 1. where every run ends: at most one run is open per level at any time
+    std::vector<int32_t> run_end((size_t)n, -1);
+    {
+        int32_t open[256];
+        for (int l = 0; l < 256; ++l) open[l] = -1;
+        for (int i = 0; i < n; ++i) {
+            const Entry &e = prog[(size_t)i];
+            if (e.n_fold > e.level) return whole();
+            if (e.level >= 1) {
+                if (e.set) {
+                    if (open[e.level] >= 0) return whole();
+                    open[e.level] = i;
+                } else if (open[e.level] < 0) return whole();
+            }
+            for (int f = 0; f < (int)e.n_fold; ++f) {
+                const int l = (int)e.level - f;
+                if (open[l] < 0) return whole();
+                run_end[(size_t)open[l]] = i;
+                open[l] = -1;
+            }
+        }
+        for (int l = 0; l < 256; ++l)
+            if (open[l] >= 0) return whole();
+    }
+
+    // 2. which runs become sub-programs, and how many steps every program gets. The stack holds the
+    // programs the current step lies in; ids are handed out in order of appearance, so a
+    // sub-program's id is larger than that of the program it was cut from.
+    struct Open { int32_t id, base, end; bool cut; };        // base: level of the program's own accumulator
+    Open stack[257];
+    std::vector<int32_t> sub_at((size_t)n, -1), parent, count;
+    int n_top = 0;
+    {
+        int sp = 0;
+        stack[0] = {-1, 0, n - 1, true};
+        for (int i = 0; i < n; ++i) {
+            const Entry &e = prog[(size_t)i];
+            if (e.set && stack[sp].cut && (int)e.level == stack[sp].base + 1) {
+                const int len = run_end[(size_t)i] - i + 1;
+                if (len >= min_run) {
+                    const int32_t g = (int32_t)parent.size();
+                    sub_at[(size_t)i] = g;
+                    parent.push_back(stack[sp].id);
+                    count.push_back(0);
+                    (stack[sp].id < 0 ? n_top : count[(size_t)stack[sp].id])++;      // the step that reads the partial
+                    stack[++sp] = {g, (int32_t)e.level, run_end[(size_t)i], (size_t)len >= min_steps};
+                }
+            }
+            (stack[sp].id < 0 ? n_top : count[(size_t)stack[sp].id])++;
+            while (sp > 0 && stack[sp].end == i) --sp;
+        }
+    }
+    const size_t n_subs = parent.size();
+    if (n_subs == 0) return whole();
+
+    // 3. lay the sub-programs out one after the other and fill them
+    mp.begin.resize(n_subs + 1);
+    mp.begin[0] = 0;
+    for (size_t g = 0; g < n_subs; ++g) mp.begin[g + 1] = mp.begin[g] + count[g];
+    mp.steps.resize((size_t)mp.begin[n_subs]);
+    mp.top.resize((size_t)n_top);
+    mp.height.assign(n_subs, 0);
+    mp.depth.assign(n_subs, 1);
+    mp.top_depth = 1;
+    {
+        std::vector<int32_t> cursor(mp.begin.begin(), mp.begin.end() - 1);
+        int top_cursor = 0;
+        int sp = 0;
+        stack[0] = {-1, 0, n - 1, true};
+        auto put = [&](int32_t id, const Entry &e) {
+            if (id < 0) {
+                mp.top[(size_t)top_cursor++] = e;
+                mp.top_depth = std::max(mp.top_depth, (int)e.level + 1);
+            } else {
+                mp.steps[(size_t)cursor[(size_t)id]++] = e;
+                mp.depth[(size_t)id] = std::max(mp.depth[(size_t)id], (int32_t)e.level + 1);
+            }
+        };
+        for (int i = 0; i < n; ++i) {
+            const Entry &e = prog[(size_t)i];
+            const int32_t g = sub_at[(size_t)i];
+            if (g >= 0) {
+                put(stack[sp].id, Entry{-(1 + g), 0, 0, 0});
+                stack[sp + 1] = {g, (int32_t)e.level, run_end[(size_t)i], true};
+                ++sp;
+            }
+            // inside a program whose accumulator is level `base`, levels count from there and folds
+            // stop there (the fold out of the program is the reading step in its parent)
+            const int rel = (int)e.level - stack[sp].base;
+            put(stack[sp].id, Entry{e.obj, (uint8_t)rel, e.set, (uint16_t)std::min((int)e.n_fold, rel)});
+            while (sp > 0 && stack[sp].end == i) --sp;
+        }
+    }
+    for (size_t g = n_subs; g-- > 0;)
+        if (parent[g] >= 0) mp.height[(size_t)parent[g]] = std::max(mp.height[(size_t)parent[g]], mp.height[g] + 1);
+    for (size_t g = 0; g < n_subs; ++g) mp.n_passes = std::max(mp.n_passes, mp.height[g] + 1);
+    return true;
 }
 
 // Accumulator levels a tree needs when every position is taken (holes only lower it).

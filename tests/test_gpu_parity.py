@@ -210,6 +210,12 @@ def test_errors():
     assert R(dst[1:], objs, 2, "sum", "f32", 1024, 2, object_bytes=4000)[0] == hop.HOP_ERR_ALIGN
     assert hop.hop_broadcast([dst[1:]], objs[0], 1024, object_bytes=4000) == hop.HOP_ERR_ALIGN
     assert hop.hop_broadcast([dst], dst, 1024) == hop.HOP_ERR_INVALID
+    # destinations that overlap each other (the same buffer twice, or shifted by less than an object)
+    big = torch.zeros(2048, device=d)
+    assert hop.hop_broadcast([big[:1024], big[:1024]], objs[0], 1024) == hop.HOP_ERR_INVALID
+    assert hop.hop_broadcast([big[:1024], big[512:1536]], objs[0], 1024) == hop.HOP_ERR_INVALID
+    assert hop.hop_allreduce([big[512:1536], big[:1024]], objs, 2, "sum", "f32", 1024, 2)[0] == hop.HOP_ERR_INVALID
+    assert hop.hop_allreduce([big[:1024], big[1024:]], objs, 2, "sum", "f32", 1024, 2)[0] == hop.HOP_OK
     torch.cuda.synchronize()
 
 
