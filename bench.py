@@ -50,6 +50,29 @@ def time_calls(fn, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
+def time_calls_median(fn, steps, warmup, torch, batch=100):
+    """For launch-bound workloads: the timed calls are taken in batches and the median batch is
+    reported, so that a one-off stall of the runtime (tens of ms, a few times per process, at launch
+    counts that depend on nothing the library does) does not decide the figure."""
+    import statistics
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    dev_ms, wall_ms = [], []
+    for _ in range(max(1, steps // batch)):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(batch):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms.append((time.perf_counter() - t0) * 1e3 / batch)
+        dev_ms.append(e0.elapsed_time(e1) / batch)
+    return statistics.median(dev_ms), statistics.median(wall_ms)
+
+
 def cpu_baseline(w, objs, order, torch, sample_elems):
     """The oracle as it stands, single thread, on the first sample_elems elements of every object."""
     import numpy as np
@@ -101,8 +124,9 @@ def paced_arrivals(hop, torch, w, objs, order, dst, interval_us, reps=5):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed calls before the timed ones (the first few dozen calls of a process run at lower clocks)")
     ap.add_argument("--workload", type=int, default=2, help="which of the five workloads (default: 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true", help="also time the other workloads (extra JSON field)")
@@ -131,7 +155,7 @@ def main():
     hop.lib()                                   # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
 
-    def run_workload(cfg, steps, warmup, no_fail=False):
+    def run_workload(cfg, steps, warmup, no_fail=False, timer=time_calls):
         w = workloads.WORKLOADS[cfg]
         if no_fail:
             w = w.scaled(w.object_bytes, fail={}, name=w.name + "_without_failure")
@@ -166,7 +190,7 @@ def main():
                 else:
                     state["rc"], state["info"] = hop.hop_reduce(d[0], obj_table, w.k, op, w.dtype, w.chunk_bytes,
                                                                 w.tree_degree, order, fm)
-            ms, wall_ms = time_calls(step, steps, warmup, torch)
+            ms, wall_ms = timer(step, steps, warmup, torch)
             assert state["rc"] >= 0, hop.hop_strerror(state["rc"])
             k_eff = state["info"]["k_eff"]
             counted = (k_eff + 1) * w.object_bytes
@@ -234,12 +258,10 @@ def main():
         del objs, dsts
         torch.cuda.empty_cache()
         for cfg, no_fail in ((1, False), (3, False), (4, False), (4, True), (5, False)):
-            # The tiny workloads are launch-bound: a long warm-up keeps a one-off stall of the runtime
-            # (about 36 ms, once per process, around the 1500th kernel launch; never again in 30 000
-            # further calls) out of the timed calls.
+            # the tiny workloads are launch-bound: median over batches of 100 calls (see time_calls_median)
             tiny = cfg in (1, 5)
-            wk, o2, _, d2, rs = run_workload(cfg, args.steps * 4 if tiny else max(5, args.steps // 5),
-                                             2000 if tiny else 5, no_fail)
+            wk, o2, _, d2, rs = run_workload(cfg, 1000 if tiny else max(10, args.steps // 5),
+                                             300 if tiny else 20, no_fail, time_calls_median if tiny else time_calls)
             for opn, rr in rs.items():
                 extra["%s/%s" % (wk.name, opn)] = {"GB/s": round(rr["gbs"], 2), "ms": round(rr["ms"], 5),
                                                   "frac_of_hbm_peak": round(rr["gbs"] / HBM_PEAK_GBS, 4),

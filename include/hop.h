@@ -56,9 +56,11 @@ typedef enum {
 } hop_status_t;
 
 /* Most partial results that can be live at once while one element's tree
- * expression is evaluated: 1 + the largest number of non-first-child
- * ancestors of any tree node. A chain (d = 1) needs 1, a star 1, a binary
- * tree on k nodes about log2(k). */
+ * expression is evaluated. A child subtree that is not a first child and has
+ * more than one node is evaluated into a partial result of its own while its
+ * parent's partial waits; the depth is 1 + the deepest nesting of such
+ * subtrees. A chain (d = 1) and a star need 1, a complete binary tree on k
+ * nodes about log2(k) - 1. */
 #define HOP_MAX_DEPTH 16
 
 typedef struct {

@@ -34,7 +34,8 @@ int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-           "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768), nontemporal loads+stores, programs <= 128 steps in "
+           "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels with 4 vectors/lane: "
+           "8 waves per CU from 4096 tiles, and from 12288 tiles 1 KiB tiles, unroll 8, 11 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
            "kernel arguments; "
            "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal";
 }
@@ -73,16 +74,20 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     fill_range(a.base, dtype, byte_begin, byte_end);
     // shape by the amount of work, measured in 4 KiB tiles of the range
     const size_t tiles4k = (a.base.n_vec + 255) / 256;
-    const int shape = tiles4k < kSmallLaunchTiles ? 0 : tiles4k < kMidLaunchTiles ? 1 : 2;
+    const bool stream_shape = tiles4k >= kStreamLaunchTiles && l.vpt == 4 && depth <= kStreamMaxDepth;
+    const int shape = (tiles4k < kSmallLaunchTiles || stream_shape) ? 0 : tiles4k < kMidLaunchTiles ? 1 : 2;
     const int vpt = shape == 0 ? 1 : shape == 1 ? (l.vpt < kMidVecs ? l.vpt : kMidVecs) : l.vpt;
+    // LDS the kernels never touch: it only caps the number of resident waves per compute unit
+    const unsigned lds = stream_shape ? kStreamLdsBytes
+                         : (shape == 2 && vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
     const unsigned grid = grid_for(a.base.n_vec, (size_t)kThreads * vpt);
     if (n_entries <= kInlineEntries) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
-        hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), 0,
+        hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), lds,
                            stream, a);
     } else {
         if (!dev_prog) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(shape == 0 ? l.dev_small : shape == 1 ? l.dev_mid : l.dev, dim3(grid), dim3(kThreads), 0,
+        hipLaunchKernelGGL(shape == 0 ? l.dev_small : shape == 1 ? l.dev_mid : l.dev, dim3(grid), dim3(kThreads), lds,
                            stream, a.base);
     }
     return hipGetLastError();

@@ -26,6 +26,29 @@ constexpr size_t kSmallLaunchTiles = 768;    // below this many 4 KiB tiles the 
 constexpr int kMidVecs = 2;
 constexpr int kMidUnroll = 2;
 constexpr size_t kMidLaunchTiles = 2048;     // below this many 4 KiB tiles (and above the small limit)
+// Resident waves. Once the result store joins the read streams, the memory system runs best with
+// few waves in flight per compute unit, each with several loads outstanding; kernels that need few
+// registers otherwise fill a CU with 20+ waves and lose 5-10 points of bandwidth (a chain over
+// 12 x 64 MiB fp32: 72 % of the HBM peak uncapped, 79-84 % capped). The cap is an LDS allocation
+// per workgroup that the kernels never touch. It applies to the kernels that hold 4 vectors per
+// lane (shallow accumulator stacks); those with fewer (deep stacks, bf16 from depth 3) already hold
+// few waves through their register use, and capping them further only costs (measured).
+//  - from 48 MiB per object: the 1 KiB-tile kernel with 8 sources in flight at 11 waves per CU
+//    (12 x 64 MiB fp32, degree 4: 79 % -> 83-85 %; gains of 3..10 points in sweeps over chains,
+//    stars and trees of 4..64 inputs of 64..512 MiB, fp32, int32 and bf16);
+//  - from 16 MiB: 4 KiB tiles at 8 waves per CU (12 x 16 MiB fp32: 70 % -> 75 %; 32 inputs: 72 % ->
+//    83 %); below that a launch fits in one round of uncapped waves and a cap would split it in two.
+constexpr size_t kCapLaunchTiles = 4096;      // 4 KiB tiles; below: uncapped
+constexpr int kLargeWavesPerCU = 8;
+constexpr size_t kStreamLaunchTiles = 12288;  // from this many 4 KiB tiles: 1 KiB tiles, 8 sources in flight
+constexpr int kStreamMaxDepth = 8;
+constexpr int kStreamWavesPerCU = 11;
+constexpr unsigned kLdsBytesPerCU = 160 * 1024;
+constexpr unsigned kStreamLdsBytes = kLdsBytesPerCU / kStreamWavesPerCU / 256 * 256;   // per workgroup
+constexpr unsigned kLargeLdsBytes = kLdsBytesPerCU / kLargeWavesPerCU / 256 * 256;
+static_assert(kLdsBytesPerCU / kStreamLdsBytes == kStreamWavesPerCU, "cap must come out as intended");
+static_assert(kLdsBytesPerCU / kLargeLdsBytes == kLargeWavesPerCU, "cap must come out as intended");
+static_assert(kStreamLdsBytes <= 64 * 1024 && kLargeLdsBytes <= 64 * 1024, "needs no opt-in for large dynamic LDS");
 
 // W = accumulators per 16-byte vector (4 for 32-bit elements, 8 for bf16)
 // bf16 (W = 8) steps down one notch earlier than the 32-bit types: at equal accumulator count its

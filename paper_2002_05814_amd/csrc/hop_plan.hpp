@@ -85,7 +85,9 @@ struct Tree {
 // program like an object) into accumulator steps. A node combines,
 // left to right, [first child's partial, its own object, other children's
 // partials]; the first child's partial is built in the parent's own
-// accumulator, every later child in the next level and folded in when done.
+// accumulator, every later child that has children of its own in the next
+// level and folded in when done, a later child without children (one object)
+// is combined into the parent's accumulator at once.
 // Returns the number of accumulator levels used (0 if nobody is in the tree).
 inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant, std::vector<Entry> &out)
 {
@@ -129,7 +131,12 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
                 if (ch >= k) break;
                 if (!started) {
                     started = is_leaf(ch) ? leaf(level) : node(ch, level);
-                } else if (is_leaf(ch) ? leaf(level + 1) : node(ch, level + 1)) {     // at most log2(k) < 32 levels
+                } else if (is_leaf(ch)) {
+                    // a lone object joins its parent's partial directly: the same arithmetic as
+                    // starting a partial of its own in the next level and folding it at once
+                    const int32_t o = occ[slot++];
+                    if (o != -1) out[n_out++] = Entry{o, (uint8_t)level, 0, 0};
+                } else if (node(ch, level + 1)) {     // at most log2(k) < 32 levels
                     out[n_out - 1].n_fold++;
                 }
             }

@@ -87,7 +87,7 @@ def test_cfg4_scaled_failure():
 @pytest.mark.parametrize("op", ["max", "sum"])
 def test_cfg5_full_size(op):
     rc, info = run_both(workloads.WORKLOADS[5], op)
-    assert rc == hop.HOP_OK and info["k_eff"] == 1000 and info["stack_depth"] == 4
+    assert rc == hop.HOP_OK and info["k_eff"] == 1000 and info["stack_depth"] == 3
 
 
 # ------------------------------------------------------------------ all dtypes x ops x shapes, with failures

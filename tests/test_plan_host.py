@@ -210,14 +210,14 @@ def test_failure_free_call_is_one_launch_over_all_chunks():
         assert launches == [(0, w.n_chunks, 0, w.k, 0, w.k, 1, 0, 0)] and info["n_launches"] == 1
         # only the first k arrivals are ever read
         assert sorted(e[0] for e in entries) == sorted(w.ready_order()[:w.k].tolist())
-    # accumulator levels needed: 3, 3, 4 for workloads 1, 2, 5; workload 3 picks a degree from {1, 2, k}
+    # accumulator levels needed: 2, 2, 3 for workloads 1, 2, 5; workload 3 picks a degree from {1, 2, k}
     depths = {}
     for cfg in (1, 2, 3, 5):
         w = workloads.WORKLOADS[cfg]
         _, info, _, _ = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
                                             w.ready_order(), None)
         depths[cfg] = (info["stack_depth"], info["degree_used"])
-    assert depths[1] == (3, 2) and depths[2] == (3, 4) and depths[5] == (4, 16)
+    assert depths[1] == (2, 2) and depths[2] == (2, 4) and depths[5] == (3, 16)
     assert depths[3][1] in (1, 2, 64)
 
 
@@ -226,7 +226,7 @@ def test_mid_stream_failure_redoes_only_the_chunks_already_produced():
     rc, info, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
                                                       w.tree_degree, w.ready_order(), w.fail_mask())
     assert rc == hop.HOP_PARTIAL and info["k_eff"] == 31 and info["n_failed_seen"] == 1
-    assert info["n_replaced"] == 0 and info["stack_depth"] == 3
+    assert info["n_replaced"] == 0 and info["stack_depth"] == 2
     # chunks 0..9 were produced with all 32 participants, then everything is produced without #7
     assert [(l[0], l[1]) for l in launches] == [(0, 10), (0, 32)]
     first = entries[launches[0][2]:launches[0][3]]
@@ -293,6 +293,8 @@ def test_argument_errors_without_a_device():
     assert P(4, 64, 2, "f32", 16, 2, fail_mask=[0, 0, 0, 0])[0] == hop.HOP_ERR_NO_SURVIVOR
     # a binary tree too deep for the register file of accumulators
     rc, info, _, _ = P(1 << 17, 64, 1 << 17, "f32", 16, 2)
+    assert rc == hop.HOP_OK and info["stack_depth"] == hop.HOP_MAX_DEPTH
+    rc, info, _, _ = P(1 << 18, 64, 1 << 18, "f32", 16, 2)
     assert rc == hop.HOP_ERR_DEPTH
     rc, info, _, _ = P(1 << 17, 64, 1 << 17, "f32", 16, 1)
     assert rc == hop.HOP_OK and info["stack_depth"] == 1
