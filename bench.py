@@ -26,10 +26,11 @@ HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B
 MEASURED_TRAFFIC = {
     "workload": "cfg2_async_sgd",
     "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile "
-                     "per workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768), "
-                     "nontemporal loads+stores, programs <= 128 steps in kernel arguments; "
-                     "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal",
-    "bytes": 872428408,
+                     "per workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels"
+                     " with 4 vectors/lane: 8 waves per CU from 4096 tiles, and from 12288 tiles 1 KiB tiles, unroll "
+                     "8, 11 waves per CU; nontemporal loads+stores, programs <= 128 steps in kernel arguments; copy: "
+                     "64 lanes/workgroup, 8 vectors/lane, nontemporal",
+    "bytes": 872413018,
 }
 
 
