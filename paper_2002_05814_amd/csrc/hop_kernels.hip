@@ -37,7 +37,7 @@ const char *kernel_config()
            "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels with 4 vectors/lane: "
            "8 waves per CU from 4096 tiles, and from 12288 tiles 1 KiB tiles, unroll 8, 11 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
            "kernel arguments; "
-           "copy: 64 lanes/workgroup, 8 vectors/lane, nontemporal";
+           "copy: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal";
 }
 
 static Launcher pick(int dtype, int op, int depth)
@@ -138,6 +138,10 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
 // (8 KiB per wave and destination) beat 1, 2 and 4 in sweeps with 63 destinations,
 // as did keeping all destinations in one workgroup rather than splitting them.
 constexpr int kCopyVpt = 8;
+constexpr unsigned kCopyCapTiles = 5120;       // 8 KiB tiles: from 40 MiB per object
+constexpr int kCopyWavesPerCU = 10;
+constexpr unsigned kCopyLdsBytes = kLdsBytesPerCU / kCopyWavesPerCU / 256 * 256;
+static_assert(kLdsBytesPerCU / kCopyLdsBytes == kCopyWavesPerCU, "cap must come out as intended");
 
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
                        size_t byte_begin, size_t byte_end, void *dst0)
@@ -153,7 +157,10 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
     a.n_vec = (byte_end - byte_begin) / 16;
     a.n_tail_bytes = (int)((byte_end - byte_begin) % 16);
     const unsigned grid = grid_for(a.n_vec, (size_t)kThreads * kCopyVpt);
-    hipLaunchKernelGGL((copy_kernel<kCopyVpt, kThreads>), dim3(grid), dim3(kThreads), 0, stream, a);
+    // long copies, like long reduces, run faster with few resident waves (256 MiB one-to-one:
+    // 77 % -> 82 % of the HBM peak; 64 MiB to 8 destinations: 63 % -> 67 %; 16 MiB to 63: unchanged)
+    const unsigned lds = grid >= kCopyCapTiles ? kCopyLdsBytes : 0;
+    hipLaunchKernelGGL((copy_kernel<kCopyVpt, kThreads>), dim3(grid), dim3(kThreads), lds, stream, a);
     return hipGetLastError();
 }
 
