@@ -35,7 +35,7 @@ const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
            "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels with 4 vectors/lane: "
-           "8 waves per CU from 4096 tiles, and from 12288 tiles 1 KiB tiles, unroll 8, 11 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
+           "8 waves per CU from 4096 tiles, and from 12288 tiles (bf16 at depth 5..8: from 4096) 1 KiB tiles, unroll 8, 11 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
            "kernel arguments; "
            "copy: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal";
 }
@@ -74,7 +74,11 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     fill_range(a.base, dtype, byte_begin, byte_end);
     // shape by the amount of work, measured in 4 KiB tiles of the range
     const size_t tiles4k = (a.base.n_vec + 255) / 256;
-    const bool stream_shape = tiles4k >= kStreamLaunchTiles && l.vpt == 4 && depth <= kStreamMaxDepth;
+    // bf16 with 5..8 accumulator levels is bound by its unpacking arithmetic at 2 vectors per lane
+    // (64 inputs in a binary tree: 56 % of the HBM peak at any size); one vector per lane with 8
+    // sources in flight keeps it at 77-80 %
+    const bool deep_bf16 = dtype == HOP_BF16 && depth > 4 && depth <= kStreamMaxDepth && tiles4k >= kCapLaunchTiles;
+    const bool stream_shape = (tiles4k >= kStreamLaunchTiles && l.vpt == 4 && depth <= kStreamMaxDepth) || deep_bf16;
     const int shape = (tiles4k < kSmallLaunchTiles || stream_shape) ? 0 : tiles4k < kMidLaunchTiles ? 1 : 2;
     const int vpt = shape == 0 ? 1 : shape == 1 ? (l.vpt < kMidVecs ? l.vpt : kMidVecs) : l.vpt;
     // LDS the kernels never touch: it only caps the number of resident waves per compute unit

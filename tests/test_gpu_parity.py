@@ -515,6 +515,43 @@ def sampled_oracle_check(w, op, objs, dsts, rc, info, rng, per_chunk=64):
     return small, want
 
 
+# every launch shape of the reduce kernel, each at a size just inside its range, with one object a few
+# elements short of a tile so that the ragged end is exercised too: (dtype, n, k, degree, MiB, dist)
+LAUNCH_SHAPE_CASES = [
+    ("f32", 6, 5, 2, 2, "uniform_pm1"),            # 1 KiB tiles, 8 sources in flight (few tiles)
+    ("f32", 6, 5, 2, 6, "uniform_pm1"),            # 2 KiB tiles, 2 in flight
+    ("f32", 6, 5, 4, 12, "normal_std1"),           # 4 KiB tiles, uncapped
+    ("i32", 6, 6, 2, 20, "randint_pm2p20"),            # 4 KiB tiles, 8 waves per CU
+    ("f32", 5, 4, 1, 52, "normal_std1"),           # streaming shape: 1 KiB tiles, 11 waves per CU
+    ("bf16", 6, 6, 6, 50, "normal_std1"),          # streaming shape, bf16 at depth 1..2
+    ("bf16", 40, 40, 2, 17, "normal_std1"),        # bf16 binary tree (5 levels): 1 KiB tiles from 16 MiB
+    ("bf16", 12, 12, 4, 20, "normal_std1"),        # bf16 at depth 2 between 16 and 48 MiB: 4 KiB tiles capped
+    ("f32", 40, 40, 2, 49, "normal_std1"),         # fp32 binary tree (5 levels) in the streaming shape
+]
+
+
+@pytest.mark.parametrize("dtype,n,k,d,mib,dist", LAUNCH_SHAPE_CASES)
+def test_every_launch_shape_against_sampled_oracle(dtype, n, k, d, mib, dist):
+    nbytes = mib * (1 << 20) - 3 * 16 - ES[dtype]          # not a whole tile, not a whole vector
+    chunk = 1 << 20
+    w = workloads.Workload("shape_%s_%d" % (dtype, mib), n=n, dtype=dtype, object_bytes=nbytes, chunk_bytes=chunk,
+                           k=k, tree_degree=d, ops=("sum",), dist=dist, order_seed=1234 + mib, data_seed=99 + mib)
+    print("launch shape case", w.name, n, k, d, flush=True)
+    objs = workloads.make_objects(w, device=dev())
+    dst = torch.zeros_like(objs[0])
+    for op in ("sum", "max"):
+        rc, info = hop.hop_reduce(dst, objs, k, op, dtype, chunk, d, w.ready_order(), None)
+        torch.cuda.synchronize()
+        assert rc == hop.HOP_OK and info["n_launches"] == 1
+        rng = np.random.default_rng(mib)
+        sampled_oracle_check(w, op, objs, [dst], rc, info, rng, per_chunk=16)
+        # the very end of the object: the ragged vector and the elements before it
+        tail = slice(w.n_elems - 40, w.n_elems)
+        small = [workloads.to_numpy(o[tail]) for o in objs]
+        _, want, _, _ = oracle.reduce(small, k, ORA_OP[op], ORA_DT[dtype], 40, d, w.ready_order(), None)
+        assert np.array_equal(bits(workloads.to_numpy(dst[tail])), bits(want))
+
+
 def test_cfg2_full_size_sampled():
     w = workloads.WORKLOADS[2]
     print("full size", w.name, flush=True)
