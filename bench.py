@@ -136,6 +136,10 @@ def main():
                     help="also run the workload's objects through the event-level API, one whole object every "
                          "INTERVAL microseconds, and report how long after the last arrival the result is complete, "
                          "for the fused and the eager scheduling policy (the paper's asynchrony experiment)")
+    ap.add_argument("--degree-sweep", action="store_true",
+                    help="also time the workload with tree degrees 1, 2, 4, 8 and k (the ablation of the paper's "
+                         "appendix B, on one GPU: the degree fixes the association order and the accumulator depth, "
+                         "not the traffic)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run hop_broadcast of one 256 MiB object to one destination a few times: a copy of "
                          "known size against which hardware byte counters can be scaled")
@@ -253,6 +257,22 @@ def main():
                              "GB/s_read_plus_write": round(2 * src.numel() * 4 / (ms * 1e-3) / 1e9, 2),
                              "kernel": "hop::copy_kernel"}
         del src, dstp
+    if args.degree_sweep:
+        sweep = {}
+        table = hop.PtrTable(objs)
+        for deg in (1, 2, 4, 8, w.k):
+            st = {"i": 0, "info": None}
+
+            def step_deg():
+                st["i"] += 1
+                _, st["info"] = hop.hop_reduce(dsts[st["i"] & 1][0], table, w.k, op, w.dtype, w.chunk_bytes, deg, order,
+                                               None)
+            ms, _ = time_calls(step_deg, max(20, args.steps // 4), 10, torch)
+            nbytes = (st["info"]["k_eff"] + 1) * w.object_bytes        # reduce only, nobody fails
+            sweep["d=%d" % deg] = {"ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                   "levels": st["info"]["stack_depth"]}
+        sweep["picked_by_eq1"] = hop.hop_pick_degree(w.k, w.object_bytes, 0.0, 0.0)
+        out["degree_sweep"] = sweep
     if args.paced_interval_us is not None:
         out["paced_arrivals"] = paced_arrivals(hop, torch, w, objs, order, dsts[0][0], args.paced_interval_us)
     if args.all_configs:
