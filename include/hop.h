@@ -296,20 +296,21 @@ int hop_plan_session_finish(hop_session_t *s, hop_info_t *info,
 
 /*
  * Host-only view of how a long program is cut for launches that cover few
- * tiles (many small objects). Every run of at least min_run steps that works
- * above level 0 (a non-first-child subtree hanging off the leftmost spine)
- * becomes a sub-program of its own, levels shifted down by one, whose result
- * is stored as a partial; in the program it came from it is replaced by one
- * step with obj = -(1 + g) naming the partial of sub-program g. Programs of
- * at least min_steps steps are cut, sub-programs included (recursively).
- * sub_pass[g] is the pass in which sub-program g must run: it reads only
- * objects and partials of earlier passes; the top program runs last.
+ * tiles (many small objects). A run is a stretch of steps that starts a partial
+ * above level 0 and ends where it is folded away: a non-first-child subtree, an
+ * independent sub-expression. While the program has at least want_steps steps,
+ * every outermost run of min_run..max_run steps becomes a sub-program of its
+ * own (levels counted from the run's level); in the program it came from it is
+ * replaced by one step with obj = -(1 + g) naming the partial of sub-program g.
+ * What is left is cut again by the same rule until it is short or nothing
+ * more can be cut. sub_pass[g] is the pass in which sub-program g must run: it
+ * reads only objects and partials of earlier passes; the top program runs last.
  * sub_begin receives n_subs + 1 offsets into sub_entries (capacity counts
  * entries of sub_begin; sub_pass needs one less). Counts are always returned;
  * arrays are filled up to capacity. Returns HOP_OK if anything was cut,
  * HOP_PARTIAL if the program stays whole.
  */
-int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int min_steps, int min_run,
+int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int want_steps, int min_run, int max_run,
                    hop_plan_entry_t *top, int top_capacity, int *n_top,
                    hop_plan_entry_t *sub_entries, int sub_capacity, int *n_sub_entries,
                    int32_t *sub_begin, int32_t *sub_pass, int sub_table_capacity, int *n_subs, int *n_passes);

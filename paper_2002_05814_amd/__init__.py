@@ -115,7 +115,7 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_size_t, ctypes.c_int, i64p, infop,
                                       ctypes.POINTER(PlanLaunch), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
-        L.hop_plan_split.argtypes = [ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        L.hop_plan_split.argtypes = [ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
                                      ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
                                      i32p, i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int),
@@ -363,7 +363,7 @@ def hop_plan_reduce(n, object_bytes, k, dtype, chunk_bytes, tree_degree, ready_o
     return rc, info.as_dict(), _launch_tuples(L, nl.value), _entry_tuples(E, ne.value)
 
 
-def hop_plan_split(entries, min_steps, min_run):
+def hop_plan_split(entries, want_steps, min_run, max_run):
     """(status, top entries, [(pass, sub-program entries), ...]) for a program of (obj, level, set, n_fold) tuples."""
     n = len(entries)
     E = (PlanEntry * max(n, 1))(*[PlanEntry(*e) for e in entries])
@@ -373,7 +373,7 @@ def hop_plan_split(entries, min_steps, min_run):
     passes = np.zeros(n + 2, np.int32)
     nt, ns, nsub, npass = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
     i32 = ctypes.POINTER(ctypes.c_int32)
-    rc = lib().hop_plan_split(E, n, int(min_steps), int(min_run), top, n, ctypes.byref(nt), sub, 2 * n + 1,
+    rc = lib().hop_plan_split(E, n, int(want_steps), int(min_run), int(max_run), top, n, ctypes.byref(nt), sub, 2 * n + 1,
                               ctypes.byref(ns), begins.ctypes.data_as(i32), passes.ctypes.data_as(i32), n + 2,
                               ctypes.byref(nsub), ctypes.byref(npass))
     as_t = lambda a, i: (a[i].obj, a[i].level, a[i].set, a[i].n_fold)

@@ -25,6 +25,7 @@ namespace hop {
 struct Block {
     int device = -1;
     char *host = nullptr;       // pinned
+    char *host_dev = nullptr;   // the pinned memory as the device addresses it
     char *dev = nullptr;
     size_t cap = 0;
     hipEvent_t ev = nullptr;    // last use on a stream
@@ -79,6 +80,7 @@ static Block *acquire_block(int device, size_t bytes)
         b->device = device;
         b->cap = bytes < kMinBlock ? kMinBlock : ((bytes + kMinBlock - 1) / kMinBlock) * kMinBlock;
         ok = hipHostMalloc((void **)&b->host, b->cap, hipHostMallocDefault) == hipSuccess;
+        if (ok && hipHostGetDevicePointer((void **)&b->host_dev, b->host, 0) != hipSuccess) { (void)hipHostFree(b->host); ok = false; }
         if (ok && hipMalloc((void **)&b->dev, b->cap) != hipSuccess) { (void)hipHostFree(b->host); ok = false; }
         if (ok && hipEventCreateWithFlags(&b->ev, hipEventDisableTiming) != hipSuccess) {
             (void)hipFree(b->dev); (void)hipHostFree(b->host); ok = false;
@@ -197,6 +199,25 @@ public:
         if (hipMemcpyAsync(b->dev + used_, b->host + used_, bytes, hipMemcpyHostToDevice, stream_) != hipSuccess)
             return nullptr;
         void *d = b->dev + used_;
+        used_ += need;
+        return d;
+    }
+
+    // Copies `bytes` from src into pinned host memory and returns the address at which kernels
+    // read it in place (over the host link): for small tables read once by few workgroups this is
+    // cheaper than a copy engine transfer queued ahead of the kernel.
+    const void *stage_in_place(const void *src, size_t bytes)
+    {
+        size_t need = (bytes + 255) & ~(size_t)255;
+        if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
+            Block *b = acquire_block(device_, need);
+            if (!b) return nullptr;
+            blocks_.push_back(b);
+            used_ = 0;
+        }
+        Block *b = blocks_.back();
+        std::memcpy(b->host + used_, src, bytes);
+        const void *d = b->host_dev + used_;
         used_ += need;
         return d;
     }
@@ -343,8 +364,8 @@ private:
     // the whole program alone, so the independent subtrees are evaluated side by side first.
     // Partials are stored in the accumulation type, which for bf16 is not the element type: bf16
     // keeps the plain path.
-    static constexpr size_t kSplitWantSteps = 128;      // shorter programs are not worth extra launches and a staging copy
-    static constexpr size_t kSplitMinSteps = 64;        // once cutting, (sub-)programs this long are cut again
+    static constexpr size_t kSplitWantSteps = 128;      // shorter programs are not worth extra launches
+    static constexpr int kSplitMaxRun = 64;             // longest sub-program
     static constexpr size_t kSplitMaxBytes = 1u << 20;  // launches this large already fill the chip
     static constexpr int kSplitMinRun = 4;
     static constexpr size_t kSplitMaxScratch = 16u << 20;
@@ -357,7 +378,7 @@ private:
     int launch_split(const std::vector<Entry> &prog, size_t b0, size_t b1)
     {
         MultiPlan mp;
-        if (!plan_passes(prog, kSplitMinSteps, kSplitMinRun, mp)) return HOP_PARTIAL;
+        if (!plan_passes(prog, kSplitWantSteps, kSplitMinRun, kSplitMaxRun, mp)) return HOP_PARTIAL;
         const size_t range = b1 - b0;
         const size_t part_bytes = (range + 255) & ~(size_t)255;
         const size_t n_subs = mp.n_subs();
@@ -404,7 +425,7 @@ private:
         }
         const size_t top_at = blob.size();
         for (const Entry &e : mp.top) blob.push_back(resolve(e, partials, part_bytes, b0));
-        const DevEntry *dev = (const DevEntry *)ws_.stage(blob.data(), blob.size() * sizeof(DevEntry));
+        const DevEntry *dev = (const DevEntry *)ws_.stage_in_place(blob.data(), blob.size() * sizeof(DevEntry));
         if (!dev) return HOP_ERR_NOMEM;
         for (const PassInfo &pi : passes) {
             if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.steps_at,
@@ -932,17 +953,17 @@ int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int 
     }
 }
 
-int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int min_steps, int min_run,
+int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int want_steps, int min_run, int max_run,
                    hop_plan_entry_t *top, int top_capacity, int *n_top,
                    hop_plan_entry_t *sub_entries, int sub_capacity, int *n_sub_entries,
                    int32_t *sub_begin, int32_t *sub_pass, int sub_table_capacity, int *n_subs, int *n_passes)
 {
-    if (!entries || n_entries < 0 || min_run < 1 || min_steps < 0) return HOP_ERR_INVALID;
+    if (!entries || n_entries < 0 || min_run < 1 || max_run < min_run || want_steps < 0) return HOP_ERR_INVALID;
     try {
         std::vector<Entry> prog(n_entries);
         for (int i = 0; i < n_entries; ++i) prog[i] = {entries[i].obj, entries[i].level, entries[i].set, entries[i].n_fold};
         MultiPlan mp;
-        const bool ok = plan_passes(prog, (size_t)min_steps, min_run, mp);
+        const bool ok = plan_passes(prog, (size_t)want_steps, min_run, max_run, mp);
         const std::vector<Entry> &flat = mp.steps;
         std::vector<int32_t> begins(mp.begin);
         if (begins.empty()) begins.push_back(0);

@@ -150,15 +150,17 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
 
 // A long program cut into short independent ones. Every `set` step above level 0
 // opens a run that ends at the step whose folds return below the run's level: a
-// non-first-child subtree of the tree, an independent sub-expression. A run of at
-// least min_run steps that lies directly in a program of at least min_steps steps
-// becomes a sub-program of its own: its steps with levels counted from the run's
-// level, its last fold dropped; in the program it came from, one step replaces it
-// that combines the sub-program's stored partial into the level below, which is
-// the same arithmetic as the dropped fold. Sub-programs are cut again by the same
-// rule, so a deep tree becomes a few passes of many short programs: a sub-program
-// of height h reads only objects and partials of height < h, pass h evaluates all
-// sub-programs of height h side by side, the top program comes last.
+// non-first-child subtree of the tree, an independent sub-expression. Cutting
+// works bottom-up: every outermost run of min_run..max_run steps becomes a
+// sub-program of its own (its steps with levels counted from the run's level,
+// the fold out of the run dropped); in the program it came from, one step
+// replaces it that combines the sub-program's stored partial into the level
+// below - the same arithmetic as the dropped fold - and carries the folds that
+// went further down. If what is left still has want_steps steps or more, it is
+// cut again the same way (its runs now contain partials of the first cut), and
+// so on: a tree of any depth becomes a few passes of many short programs. Pass
+// h evaluates side by side all sub-programs cut in round h, which read only
+// objects and partials of earlier passes; the top program comes last.
 struct MultiPlan {
     std::vector<Entry> steps;                    // all sub-programs: sub g = steps[begin[g], begin[g + 1])
     std::vector<int32_t> begin;                  // n_subs() + 1 offsets
@@ -177,25 +179,28 @@ inline int program_depth(const std::vector<Entry> &p)
 }
 
 // Returns false (top = prog, no sub-programs) if nothing was cut or the program is malformed.
-inline bool plan_passes(const std::vector<Entry> &prog, size_t min_steps, int min_run, MultiPlan &mp)
+inline bool plan_passes(const std::vector<Entry> &prog, size_t want_steps, int min_run, int max_run, MultiPlan &mp)
 {
     mp = MultiPlan();
-    const int n = (int)prog.size();
     auto whole = [&]() {
         mp = MultiPlan();
         mp.top = prog;
         mp.top_depth = program_depth(prog);
         return false;
     };
-    if ((size_t)n < min_steps || n == 0) return whole();
-
-    // 1. where every run ends: at most one run is open per level at any time
-    std::vector<int32_t> run_end((size_t)n, -1);
-    {
+    if (min_run < 1) min_run = 1;
+    if (max_run < min_run) return whole();
+    std::vector<Entry> cur(prog), next;
+    std::vector<int32_t> run_end;
+    mp.begin.push_back(0);
+    for (int pass = 0; cur.size() >= want_steps && !cur.empty(); ++pass) {
+        const int n = (int)cur.size();
+        // where every run ends: at most one run is open per level at any time
+        run_end.assign((size_t)n, -1);
         int32_t open[256];
         for (int l = 0; l < 256; ++l) open[l] = -1;
         for (int i = 0; i < n; ++i) {
-            const Entry &e = prog[(size_t)i];
+            const Entry &e = cur[(size_t)i];
             if (e.n_fold > e.level) return whole();
             if (e.level >= 1) {
                 if (e.set) {
@@ -212,79 +217,43 @@ inline bool plan_passes(const std::vector<Entry> &prog, size_t min_steps, int mi
         }
         for (int l = 0; l < 256; ++l)
             if (open[l] >= 0) return whole();
-    }
-
-    // 2. which runs become sub-programs, and how many steps every program gets. The stack holds the
-    // programs the current step lies in; ids are handed out in order of appearance, so a
-    // sub-program's id is larger than that of the program it was cut from.
-    struct Open { int32_t id, base, end; bool cut; };        // base: level of the program's own accumulator
-    Open stack[257];
-    std::vector<int32_t> sub_at((size_t)n, -1), parent, count;
-    int n_top = 0;
-    {
-        int sp = 0;
-        stack[0] = {-1, 0, n - 1, true};
-        for (int i = 0; i < n; ++i) {
-            const Entry &e = prog[(size_t)i];
-            if (e.set && stack[sp].cut && (int)e.level == stack[sp].base + 1) {
-                const int len = run_end[(size_t)i] - i + 1;
-                if (len >= min_run) {
-                    const int32_t g = (int32_t)parent.size();
-                    sub_at[(size_t)i] = g;
-                    parent.push_back(stack[sp].id);
-                    count.push_back(0);
-                    (stack[sp].id < 0 ? n_top : count[(size_t)stack[sp].id])++;      // the step that reads the partial
-                    stack[++sp] = {g, (int32_t)e.level, run_end[(size_t)i], (size_t)len >= min_steps};
-                }
+        // outermost runs of suitable length leave; the rest stays, nested runs looked at in turn
+        next.clear();
+        next.reserve((size_t)n);
+        bool any = false;
+        for (int i = 0; i < n;) {
+            const Entry &e = cur[(size_t)i];
+            const int len = (e.set && e.level >= 1) ? run_end[(size_t)i] - i + 1 : 0;
+            if (len < min_run || len > max_run) {
+                next.push_back(e);
+                ++i;
+                continue;
             }
-            (stack[sp].id < 0 ? n_top : count[(size_t)stack[sp].id])++;
-            while (sp > 0 && stack[sp].end == i) --sp;
+            const int base = e.level, end = run_end[(size_t)i];
+            const int32_t g = (int32_t)mp.height.size();
+            int depth = 1;
+            for (int t = i; t <= end; ++t) {
+                const Entry &x = cur[(size_t)t];
+                const int rel = (int)x.level - base;
+                mp.steps.push_back(Entry{x.obj, (uint8_t)rel, x.set, (uint16_t)std::min((int)x.n_fold, rel)});
+                depth = std::max(depth, rel + 1);
+            }
+            const Entry &last = cur[(size_t)end];
+            const int beyond = (int)last.n_fold - ((int)last.level - base) - 1;      // folds below the run's parent level
+            next.push_back(Entry{-(1 + g), (uint8_t)(base - 1), 0, (uint16_t)beyond});
+            mp.begin.push_back((int32_t)mp.steps.size());
+            mp.height.push_back(pass);
+            mp.depth.push_back(depth);
+            mp.n_passes = pass + 1;
+            any = true;
+            i = end + 1;
         }
+        if (!any) break;
+        cur.swap(next);
     }
-    const size_t n_subs = parent.size();
-    if (n_subs == 0) return whole();
-
-    // 3. lay the sub-programs out one after the other and fill them
-    mp.begin.resize(n_subs + 1);
-    mp.begin[0] = 0;
-    for (size_t g = 0; g < n_subs; ++g) mp.begin[g + 1] = mp.begin[g] + count[g];
-    mp.steps.resize((size_t)mp.begin[n_subs]);
-    mp.top.resize((size_t)n_top);
-    mp.height.assign(n_subs, 0);
-    mp.depth.assign(n_subs, 1);
-    mp.top_depth = 1;
-    {
-        std::vector<int32_t> cursor(mp.begin.begin(), mp.begin.end() - 1);
-        int top_cursor = 0;
-        int sp = 0;
-        stack[0] = {-1, 0, n - 1, true};
-        auto put = [&](int32_t id, const Entry &e) {
-            if (id < 0) {
-                mp.top[(size_t)top_cursor++] = e;
-                mp.top_depth = std::max(mp.top_depth, (int)e.level + 1);
-            } else {
-                mp.steps[(size_t)cursor[(size_t)id]++] = e;
-                mp.depth[(size_t)id] = std::max(mp.depth[(size_t)id], (int32_t)e.level + 1);
-            }
-        };
-        for (int i = 0; i < n; ++i) {
-            const Entry &e = prog[(size_t)i];
-            const int32_t g = sub_at[(size_t)i];
-            if (g >= 0) {
-                put(stack[sp].id, Entry{-(1 + g), 0, 0, 0});
-                stack[sp + 1] = {g, (int32_t)e.level, run_end[(size_t)i], true};
-                ++sp;
-            }
-            // inside a program whose accumulator is level `base`, levels count from there and folds
-            // stop there (the fold out of the program is the reading step in its parent)
-            const int rel = (int)e.level - stack[sp].base;
-            put(stack[sp].id, Entry{e.obj, (uint8_t)rel, e.set, (uint16_t)std::min((int)e.n_fold, rel)});
-            while (sp > 0 && stack[sp].end == i) --sp;
-        }
-    }
-    for (size_t g = n_subs; g-- > 0;)
-        if (parent[g] >= 0) mp.height[(size_t)parent[g]] = std::max(mp.height[(size_t)parent[g]], mp.height[g] + 1);
-    for (size_t g = 0; g < n_subs; ++g) mp.n_passes = std::max(mp.n_passes, mp.height[g] + 1);
+    if (mp.height.empty()) return whole();
+    mp.top.swap(cur);
+    mp.top_depth = program_depth(mp.top);
     return true;
 }
 

@@ -152,7 +152,7 @@ int main(int argc, char **argv)
         std::vector<Entry> prog;
         compile_program(tr, occ, prog);
         MultiPlan mp;
-        plan_passes(prog, (size_t)rnd(1, 40), rnd(1, 6), mp);
+        { const int lo = rnd(1, 6); plan_passes(prog, (size_t)rnd(1, 40), lo, lo + rnd(0, 30), mp); }
         fuzz_bcast(rng);
     }
     std::printf("ok %d sessions, %ld launches\n", rounds, total_launches);

@@ -139,6 +139,11 @@ def test_many_small_objects_take_the_multi_pass_path(dtype):
             fm[bad] = rng.integers(0, C + 1, size=int(bad.sum()))
         for op in ("sum", "max"):
             run_both(w, op, fm=fm)
+    if dtype != "bf16":
+        # thousands of inputs in a binary tree: the program is cut in two rounds (two passes and the top)
+        w = base.scaled(256 * ES[dtype], 256 * ES[dtype], n=4000, k=3900, tree_degree=2, order_seed=77, data_seed=78,
+                        fail={}, name="small_deep", dist=dist, n_dst=0)
+        run_both(w, "sum")
 
 
 def test_denormals_and_signed_zeros_are_preserved():

@@ -157,9 +157,9 @@ def run_plan_passes(objs, tops, subs, op):
     return run_entries(objs, tops, op, partials)
 
 
-@pytest.mark.parametrize("min_steps,min_run", [(1, 1), (1, 2), (8, 4), (64, 4), (30, 9)])
-def test_split_program_keeps_the_bits(min_steps, min_run):
-    rng = np.random.default_rng(min_steps * 10 + min_run)
+@pytest.mark.parametrize("want_steps,min_run,max_run", [(1, 1, 1000), (1, 2, 5), (8, 4, 16), (64, 4, 64), (30, 9, 20), (2, 1, 3)])
+def test_split_program_keeps_the_bits(want_steps, min_run, max_run):
+    rng = np.random.default_rng(want_steps * 10 + min_run)
     n_split = 0
     for _ in range(120):
         n = int(rng.integers(1, 200))
@@ -177,7 +177,7 @@ def test_split_program_keeps_the_bits(min_steps, min_run):
         if rc < 0:
             continue
         final = entries[launches[-1][2]:launches[-1][3]]
-        src, tops, subs = hop.hop_plan_split(final, min_steps, min_run)
+        src, tops, subs = hop.hop_plan_split(final, want_steps, min_run, max_run)
         whole = run_entries(objs, final, "sum")
         if src == hop.HOP_PARTIAL:
             assert subs == [] and tops == final
@@ -190,15 +190,22 @@ def test_split_program_keeps_the_bits(min_steps, min_run):
         assert sorted(refs) == list(range(len(subs)))
         got = run_plan_passes(objs, tops, subs, "sum")
         assert np.array_equal(got.view(np.uint32), whole.view(np.uint32))
+        # sub-programs respect the length limits
+        assert all(min_run <= len(sp) <= max_run for _, sp in subs)
     assert n_split > 10
-    # workload 5: 1000 steps in one program become three passes of short programs
+    # workload 5: 1000 steps in one program become one pass of short programs and a short top program
     w = workloads.WORKLOADS[5]
     _, _, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
                                                   w.ready_order(), None)
-    src, tops, subs = hop.hop_plan_split(entries, 64, 4)
-    assert src == hop.HOP_OK and len(tops) < 64 and max(len(sp) for _, sp in subs) < 64
-    assert {ps for ps, _ in subs} == {0, 1}
+    src, tops, subs = hop.hop_plan_split(entries, 128, 4, 64)
+    assert src == hop.HOP_OK and len(tops) < 128 and max(len(sp) for _, sp in subs) <= 64
+    assert {ps for ps, _ in subs} == {0}
     assert len(tops) + sum(len(sp) for _, sp in subs) - len(subs) == 1000
+    # a binary tree on 4000 inputs needs a second round of cutting
+    _, _, _, e2 = hop.hop_plan_reduce(4000, 64, 4000, "f32", 64, 2, None, None)
+    src, tops, subs = hop.hop_plan_split(e2, 128, 4, 64)
+    assert src == hop.HOP_OK and len(tops) < 128 and {ps for ps, _ in subs} == {0, 1}
+    assert len(tops) + sum(len(sp) for _, sp in subs) - len(subs) == 4000
 
 
 def test_failure_free_call_is_one_launch_over_all_chunks():
