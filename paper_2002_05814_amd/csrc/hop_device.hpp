@@ -190,29 +190,64 @@ typedef const DevEntry __attribute__((address_space(4))) *prog_ptr;
 // The broadcast's destination table is read the same way.
 typedef void *const __attribute__((address_space(4))) *table_ptr;
 
+// The addresses and control words of G consecutive program steps, held in SGPRs.
+template <int G> struct StepGroup {
+    const void *src[G];
+    uint32_t ctl[G];
+};
+// Steps [t, t + G) of the program, indices clamped to the last step so that a look-ahead past the
+// end reads valid memory (its values are never used).
+template <int G, class Prog> __device__ __forceinline__ StepGroup<G> fetch_steps(const Prog prog, int t, int n)
+{
+    StepGroup<G> g;
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+        const int i = (t + u < n) ? t + u : n - 1;
+        g.src[u] = prog[i].src;
+        g.ctl[u] = prog[i].ctl;
+    }
+    return g;
+}
+
+// Keeps the scalar loads of a look-ahead where they are written (right behind the vector loads
+// they are meant to overlap with): an empty statement that formally reads the fetched words.
+// Without it the compiler sinks them to the end of the iteration, behind all the folds.
+template <int G> __device__ __forceinline__ void pin_here(const StepGroup<G> &g)
+{
+#pragma unroll
+    for (int u = 0; u < G; ++u) asm volatile("" : : "s"(g.src[u]), "s"(g.ctl[u]));
+}
+
 // G consecutive program steps: all G*VPT loads are issued before the first value
 // is consumed, then the values are folded in program order.
-template <int DT, int G, int VPT, class M, class Prog>
-__device__ __forceinline__ void run_group(M &m, const Prog prog, int t, const size_t (&off)[VPT])
+template <int DT, int G, int VPT, class M>
+__device__ __forceinline__ void issue_group(const StepGroup<G> &g, const size_t (&off)[VPT], uint4 (&raw)[G][VPT])
+{
+#pragma unroll
+    for (int u = 0; u < G; ++u)
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) raw[u][j] = ld16(g.src[u], off[j]);
+}
+template <int DT, int G, int VPT, class M>
+__device__ __forceinline__ void fold_group(M &m, const StepGroup<G> &g, const uint4 (&raw)[G][VPT])
 {
     using A = typename Traits<DT>::acc_t;
     constexpr int W = Traits<DT>::W;
-    uint4 raw[G][VPT];
-    uint32_t ctl[G];                  // fetched with the addresses, not one by one between the folds
-#pragma unroll
-    for (int u = 0; u < G; ++u) {
-        const void *src = prog[t + u].src;
-        ctl[u] = prog[t + u].ctl;
-#pragma unroll
-        for (int j = 0; j < VPT; ++j) raw[u][j] = ld16(src, off[j]);
-    }
 #pragma unroll
     for (int u = 0; u < G; ++u) {
         A x[VPT * W];
 #pragma unroll
         for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
-        m.step(ctl[u], x);
+        m.step(g.ctl[u], x);
     }
+}
+template <int DT, int G, int VPT, class M, class Prog>
+__device__ __forceinline__ void run_group(M &m, const Prog prog, int t, int n, const size_t (&off)[VPT])
+{
+    const StepGroup<G> g = fetch_steps<G>(prog, t, n);
+    uint4 raw[G][VPT];
+    issue_group<DT, G, VPT, M>(g, off, raw);
+    fold_group<DT, G, VPT, M>(m, g, raw);
 }
 
 // One workgroup of THREADS lanes walks tiles of THREADS*VPT consecutive
@@ -259,12 +294,24 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
             }
         }
         int t = 0;
-        for (; t + U <= n; t += U) run_group<DT, U, VPT>(m, prog, t, off);
+        if (n >= U) {
+            // the next group's addresses are fetched (scalar loads) while this group's data is in
+            // flight, so that their latency does not add to the data's
+            StepGroup<U> cur = fetch_steps<U>(prog, 0, n);
+            for (; t + U <= n; t += U) {
+                uint4 raw[U][VPT];
+                issue_group<DT, U, VPT, decltype(m)>(cur, off, raw);
+                const StepGroup<U> nxt = fetch_steps<U>(prog, t + U, n);
+                pin_here(nxt);
+                fold_group<DT, U, VPT>(m, cur, raw);
+                cur = nxt;
+            }
+        }
         // what is left is taken in halving groups so that it stays in flight together too
-        if (U > 8 && t + 8 <= n) { run_group<DT, 8, VPT>(m, prog, t, off); t += 8; }
-        if (U > 4 && t + 4 <= n) { run_group<DT, 4, VPT>(m, prog, t, off); t += 4; }
-        if (U > 2 && t + 2 <= n) { run_group<DT, 2, VPT>(m, prog, t, off); t += 2; }
-        if (U > 1 && t < n) { run_group<DT, 1, VPT>(m, prog, t, off); t += 1; }
+        if (U > 8 && t + 8 <= n) { run_group<DT, 8, VPT>(m, prog, t, n, off); t += 8; }
+        if (U > 4 && t + 4 <= n) { run_group<DT, 4, VPT>(m, prog, t, n, off); t += 4; }
+        if (U > 2 && t + 2 <= n) { run_group<DT, 2, VPT>(m, prog, t, n, off); t += 2; }
+        if (U > 1 && t < n) { run_group<DT, 1, VPT>(m, prog, t, n, off); t += 1; }
         if (SEG && a.n_save > 0) {
 #pragma unroll
             for (int L = 0; L < D; ++L) {
