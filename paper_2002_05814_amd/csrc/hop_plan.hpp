@@ -297,7 +297,11 @@ public:
     // m >= 1: a chunk also advances through the program whenever at least m further steps
     // have become runnable, saving its accumulators in between (work overlaps the wait
     // for late participants, at the price of extra traffic).
-    void set_eager(int min_steps) { eager_ = min_steps < 0 ? 0 : min_steps; }
+    void set_eager(int min_steps)
+    {
+        eager_ = min_steps < 0 ? 0 : min_steps;
+        dirty_ = true;
+    }
 
     // Bulk form of on_ready(obj, all chunks) for objects that arrive complete, in this order.
     // Same effect as calling on_ready(objs[i], n_chunks) one by one.
@@ -317,6 +321,7 @@ public:
                 occupant_[next_free_] = obj;
                 slot_of_obj_[obj] = next_free_++;
                 version_++;
+                dirty_ = true;
             } else {
                 pool_.push_back(obj);
             }
@@ -343,6 +348,7 @@ public:
                 pool_.push_back(obj);
             }
         }
+        if (c > ready_[obj] && slot_of_obj_[obj] >= 0) dirty_ = true;      // new chunks of a participant in the tree
         ready_[obj] = c;
         if (c == C_) state_[obj] = COMPLETE;
         return HOP_OK;
@@ -359,6 +365,7 @@ public:
         slot_of_obj_[obj] = -1;
         occupant_[t] = -1;
         version_++;
+        dirty_ = true;
         while (!pool_.empty() && state_[pool_.front()] == FAILED) pool_.pop_front();
         if (!pool_.empty()) {
             int j = pool_.front();
@@ -374,6 +381,12 @@ public:
     // Launch whatever the readiness reported so far allows.
     int pump()
     {
+        // Nothing that matters has happened since the last pump (e.g. an object beyond the first k
+        // reported more chunks), or - default policy - some position has not been taken yet, so no
+        // chunk can run the whole program: events stay cheap until there is something to launch.
+        if (!dirty_) return HOP_OK;
+        if (eager_ == 0 && !closing_ && next_free_ < k_) return HOP_OK;
+        dirty_ = false;
         int rc = recompile();
         if (rc < 0) return rc;
         const int n_steps = (int)prog_.size();
@@ -458,6 +471,7 @@ public:
             closing_ = true;
             if (next_free_ < k_) version_++;        // positions nobody took are empty for good
         }
+        dirty_ = true;
         int rc = pump();
         int live = 0;
         for (int t = 0; t < k_; ++t) live += occupant_[t] >= 0;
@@ -491,6 +505,7 @@ private:
         occupant_[t] = obj;
         slot_of_obj_[obj] = t;
         version_++;
+        dirty_ = true;
     }
 
     // accumulator levels alive between steps t-1 and t
@@ -552,6 +567,7 @@ private:
     std::set<int> holes_;                // positions emptied by a failure with nobody waiting
     int next_free_ = 0;                  // positions [0, next_free_) have been handed out
     bool closing_ = false;
+    bool dirty_ = false;                 // something changed that a pump could act on
     int eager_ = 0;
     std::vector<Stair> done_;            // progress of every chunk through prog_
     uint64_t version_ = 1, compiled_version_ = 0;

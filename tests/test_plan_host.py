@@ -482,3 +482,24 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
         hop.hop_plan_slots(4, 2)
     with pytest.raises(RuntimeError):
         hop.hop_reduce(0, [], 1, "sum", "f32", 16, 2, object_bytes=0)
+
+
+def test_events_before_anything_can_run_are_cheap_and_launch_nothing():
+    # 3000 whole objects arrive one by one (default policy): nothing can be launched before the last
+    # position is taken, one launch covers everything at the end, and the 3000 events together cost
+    # far less than 3000 recompilations of a 3000-step program would (a generous wall-clock bound)
+    import time
+    n = 3000
+    rc, s = hop.hop_plan_session_begin(n, 64, n, "f32", 64, 2)
+    assert rc == hop.HOP_OK
+    t0 = time.perf_counter()
+    for i in range(n):
+        assert hop.hop_session_ready(s, i, 1) == hop.HOP_OK
+        if i in (0, 1, n // 2, n - 2):
+            assert hop.hop_session_chunks_final(s) == 0
+    dt = time.perf_counter() - t0
+    assert hop.hop_session_chunks_final(s) == 1
+    # objects beyond the tree do not stir anything either
+    rc, info, launches, entries = hop.hop_plan_session_finish(s)
+    assert rc == hop.HOP_OK and info["n_launches"] == 1 and len(entries) == n
+    assert dt < 0.5, dt
