@@ -683,11 +683,13 @@ def test_objects_larger_than_4_gib_use_64_bit_offsets():
     assert torch.equal(dst, torch.maximum(a, c))
 
 
-def test_reduce_can_be_captured_in_a_graph_and_replayed():
+@pytest.mark.parametrize("object_mib", [1, 49])
+def test_reduce_can_be_captured_in_a_graph_and_replayed(object_mib):
     # short programs ride in the kernel arguments: a call is nothing but kernel launches on the
-    # caller's stream, so it can be recorded into a graph; every replay must see the current inputs
+    # caller's stream, so it can be recorded into a graph; every replay must see the current inputs.
+    # 49 MiB objects take the launch shape that caps resident waves with a dynamic LDS allocation.
     d = dev()
-    w = workloads.WORKLOADS[1]
+    w = workloads.WORKLOADS[1].scaled(object_mib << 20)
     objs = workloads.make_objects(w, device=d)
     dst = torch.zeros_like(objs[0])
     order = w.ready_order()
