@@ -223,6 +223,17 @@ int hop_session_begin(hop_session_t **s, void *dst, const void *const *objs, int
  * an object already reported failed. */
 int hop_session_ready(hop_session_t *s, int obj, int64_t chunks_ready_total);
 
+/* The same notification for data that is still being produced on the GPU: the
+ * chunks are ready once `event` (a hipEvent_t recorded on the producer's
+ * stream, passed as void*; NULL = ready now) has completed. The session's
+ * stream is made to wait for the event before any work enqueued from now on,
+ * so no host synchronisation is needed between a producer (a copy landing a
+ * chunk, a kernel computing an object, another session's output) and the
+ * reduce: the event plays the part of the paper's readiness notification
+ * (section 3.3). The event may be re-recorded or destroyed after the call
+ * returns. Host-only sessions ignore it. */
+int hop_session_ready_after(hop_session_t *s, int obj, int64_t chunks_ready_total, void *event);
+
 /* Participant obj failed. If all its chunks were already ready the object is
  * complete and the call changes nothing. Otherwise it leaves the tree: output
  * chunks already produced with its data are scheduled again, its position

@@ -29,7 +29,7 @@ DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
           torch.float32: HOP_F32, torch.bfloat16: HOP_BF16, torch.int32: HOP_I32}
 
 EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_bcast_begin", "hop_bcast_source_ready",
-           "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready",
+           "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready", "hop_session_ready_after",
            "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_chunks_final",
            "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
            "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
@@ -101,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.hop_session_begin.argtypes = [ctypes.POINTER(vp), vp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
                                         ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, vp]
         L.hop_session_ready.argtypes = [vp, ctypes.c_int, ctypes.c_int64]
+        L.hop_session_ready_after.argtypes = [vp, ctypes.c_int, ctypes.c_int64, vp]
         L.hop_session_fail.argtypes = [vp, ctypes.c_int]
         L.hop_session_finish.argtypes = [vp, infop]
         L.hop_session_set_eager.argtypes = [vp, ctypes.c_int]
@@ -295,6 +296,14 @@ def hop_session_begin(dst, objs, k, op, dtype, chunk_bytes, tree_degree, stream=
 
 def hop_session_ready(session, obj, chunks_ready_total):
     return lib().hop_session_ready(session, int(obj), int(chunks_ready_total))
+
+
+def hop_session_ready_after(session, obj, chunks_ready_total, event=None):
+    """event: a recorded torch.cuda.Event (or a raw hipEvent_t address) after which the chunks are valid."""
+    ev = None
+    if event is not None:
+        ev = ctypes.c_void_p(int(event.cuda_event) if isinstance(event, torch.cuda.Event) else int(event))
+    return lib().hop_session_ready_after(session, int(obj), int(chunks_ready_total), ev)
 
 
 def hop_session_fail(session, obj):

@@ -275,6 +275,9 @@ public:
 
     ~GpuBackend() override { release_devbuf(spill_buf_, stream_); }
 
+    // everything enqueued on the session's stream from now on runs after `ev` has completed
+    bool wait_for(hipEvent_t ev) { return hipStreamWaitEvent(stream_, ev, 0) == hipSuccess; }
+
     int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
                int live_before, int live_after) override
     {
@@ -858,6 +861,14 @@ int hop_session_ready(hop_session_t *s, int obj, int64_t chunks_ready_total)
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;
     }
+}
+
+int hop_session_ready_after(hop_session_t *s, int obj, int64_t chunks_ready_total, void *event)
+{
+    if (!s) return HOP_ERR_INVALID;
+    // the wait is enqueued at once, ahead of whatever this or a later notification launches
+    if (event && s->be && !s->be->wait_for((hipEvent_t)event)) return HOP_ERR_DEVICE;
+    return hop_session_ready(s, obj, chunks_ready_total);
 }
 
 int hop_session_fail(hop_session_t *s, int obj)

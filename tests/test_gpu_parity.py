@@ -481,6 +481,43 @@ def test_composed_reduce_streams_one_result_into_the_next():
     assert np.array_equal(bits(workloads.to_numpy(out)), bits(want))
 
 
+def test_readiness_by_event_needs_no_host_synchronisation():
+    # The producers run on another stream: each one first idles for a while, then writes its object
+    # chunk by chunk and records an event per chunk. The session is told "ready after this event";
+    # nobody waits on the host between producing and reducing. Had the session's stream not waited
+    # for the events it would have read the zeros the objects held before.
+    d = dev()
+    rng = np.random.default_rng(21)
+    C, ce, n = 4, 4096, 5
+    E = C * ce
+    vals = [rng.standard_normal(E).astype(np.float32) for _ in range(n)]
+    staged = [workloads.from_numpy(v, "f32", d) for v in vals]
+    objs = [torch.zeros(E, device=d) for _ in range(n)]
+    dst = torch.zeros(E, device=d)
+    producer, consumer = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    rc, s = hop.hop_session_begin(dst, objs, n, "sum", "f32", ce * 4, 2, stream=consumer.cuda_stream)
+    assert rc == hop.HOP_OK
+    order = [3, 0, 4, 1, 2]
+    events = []
+    for c in range(C):
+        for i in order:
+            with torch.cuda.stream(producer):
+                torch.cuda._sleep(20_000_000)                     # a few milliseconds of nothing
+                objs[i][c * ce:(c + 1) * ce].copy_(staged[i][c * ce:(c + 1) * ce])
+                ev = torch.cuda.Event()
+                ev.record(producer)
+            events.append(ev)
+            assert hop.hop_session_ready_after(s, i, c + 1, ev) == hop.HOP_OK
+    rc, info = hop.hop_session_finish(s)
+    assert rc == hop.HOP_OK and info["n_launches"] == C
+    # the host ran ahead: the producers (some 0.2 s of idling) cannot be through yet
+    assert not producer.query()
+    torch.cuda.synchronize()
+    _, want, _, _ = oracle.reduce(vals, n, oracle.SUM, oracle.F32, ce, 2, np.array(order, np.int32), None)
+    assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+
+
 def test_other_stream():
     d = dev()
     w = workloads.WORKLOADS[1]
