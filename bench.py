@@ -99,18 +99,20 @@ def cpu_baseline(w, objs, order, torch, sample_elems, min_seconds=10.0):
 def paced_arrivals(hop, torch, w, objs, order, dst, interval_us, reps=5):
     """Objects become ready whole, one every interval_us (host clock), in the workload's ready order; only
     the first k matter. Measured: host time from the last arrival to the completed result (stream
-    synchronised), median of reps, for the fused policy (one launch when everything is there) and the
-    eager one (every arrival folded into saved accumulators at once)."""
+    synchronised), median of reps, for the fused policy (one launch when everything is there), the
+    eager one (every arrival folded into saved accumulators at once) and the adaptive one (eager, but only
+    while the stream has nothing left to do)."""
     import statistics
     table = hop.PtrTable(objs)
     C = w.n_chunks
     res = {"interval_us": interval_us, "k": w.k}
-    for name, eager in (("fused", 0), ("eager", 1)):
+    for name, eager in (("fused", 0), ("eager", 1), ("adaptive", 1)):
         tails, launches = [], 0
         for _ in range(reps + 1):
             rc, s = hop.hop_session_begin(dst, table, w.k, w.ops[0], w.dtype, w.chunk_bytes, w.tree_degree)
             assert rc == hop.HOP_OK, hop.hop_strerror(rc)
             hop.hop_session_set_eager(s, eager)
+            hop.hop_session_set_adaptive(s, name == "adaptive")
             torch.cuda.synchronize()
             t_next = time.perf_counter()
             for t in range(w.k):

@@ -250,6 +250,15 @@ int hop_session_fail(hop_session_t *s, int obj);
  * bit-identical in both modes. */
 int hop_session_set_eager(hop_session_t *s, int min_steps);
 
+/* Refinement of the eager policy (min_steps >= 1): a chunk advances part of
+ * the way only if the stream has already executed everything this session
+ * enqueued before. Participants that arrive faster than the GPU works are then
+ * folded together into fewer, longer launches (in the limit the default
+ * policy's single launch); participants that arrive with gaps are worked off
+ * in the gaps. The number of launches then depends on timing; the result does
+ * not. Host-only sessions count as always idle. */
+int hop_session_set_adaptive(hop_session_t *s, int on);
+
 /* Number of leading output chunks that are final in dst as far as the work
  * enqueued so far goes (a later failure can take chunks back). This is what a
  * downstream consumer on the same stream may read, e.g. a second session that

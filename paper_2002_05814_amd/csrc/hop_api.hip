@@ -273,13 +273,41 @@ public:
         : ws_(device, stream), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
           op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device) {}
 
-    ~GpuBackend() override { release_devbuf(spill_buf_, stream_); }
+    ~GpuBackend() override
+    {
+        release_devbuf(spill_buf_, stream_);
+        if (busy_ev_) (void)hipEventDestroy(busy_ev_);
+    }
+
+    // Adaptive sessions ask whether the stream has worked off what this session launched: an event
+    // is recorded behind every launch from now on.
+    void track_idle() { track_idle_ = true; }
+    bool idle() override
+    {
+        if (!busy_recorded_) return true;
+        if (hipEventQuery(busy_ev_) == hipSuccess) return true;
+        (void)hipGetLastError();
+        return false;
+    }
 
     // everything enqueued on the session's stream from now on runs after `ev` has completed
     bool wait_for(hipEvent_t ev) { return hipStreamWaitEvent(stream_, ev, 0) == hipSuccess; }
 
     int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
                int live_before, int live_after) override
+    {
+        const int rc = launch_work(prog, version, c0, c1, t0, t1, final, live_before, live_after);
+        if (rc >= 0 && track_idle_) {
+            if (!busy_ev_ && hipEventCreateWithFlags(&busy_ev_, hipEventDisableTiming) != hipSuccess) return HOP_ERR_DEVICE;
+            if (hipEventRecord(busy_ev_, stream_) != hipSuccess) return HOP_ERR_DEVICE;
+            busy_recorded_ = true;
+        }
+        return rc;
+    }
+
+private:
+    int launch_work(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
+                    int live_before, int live_after)
     {
         if (shape_.object_bytes == 0) return HOP_OK;
         if (t0 > 0 || !final) return launch_segment(prog, c0, c1, t0, t1, final, live_before, live_after);
@@ -467,6 +495,8 @@ private:
     char *spill_ = nullptr;
     size_t level_stride_ = 0;
     int spill_levels_ = 0;
+    hipEvent_t busy_ev_ = nullptr;
+    bool busy_recorded_ = false, track_idle_ = false;
 };
 
 class RecordingBackend : public Backend {
@@ -899,6 +929,14 @@ int hop_session_set_eager(hop_session_t *s, int min_steps)
 {
     if (!s || min_steps < 0) return HOP_ERR_INVALID;
     s->sched->set_eager(min_steps);
+    return HOP_OK;
+}
+
+int hop_session_set_adaptive(hop_session_t *s, int on)
+{
+    if (!s) return HOP_ERR_INVALID;
+    s->sched->set_adaptive(on != 0);
+    if (on && s->be) s->be->track_idle();
     return HOP_OK;
 }
 

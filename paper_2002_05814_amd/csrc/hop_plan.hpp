@@ -275,6 +275,9 @@ inline int full_tree_depth(int k, int64_t d)
 // occupants change; steps below t0 are the same in the version that ran them.
 struct Backend {
     virtual ~Backend() {}
+    // Has everything launched so far been executed? Asked only by the adaptive policy, which
+    // advances chunks part of the way only while the device would otherwise sit idle.
+    virtual bool idle() { return true; }
     virtual int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1,
                        bool final, int live_before, int live_after) = 0;
 };
@@ -302,6 +305,11 @@ public:
         eager_ = min_steps < 0 ? 0 : min_steps;
         dirty_ = true;
     }
+    // With the eager policy: advance chunks part of the way only when the back end reports that
+    // all earlier work has been executed. Arrivals that come in faster than the device works are
+    // then folded together into fewer, longer launches (in the limit: the default policy's single
+    // launch), arrivals with gaps between them are worked off in the gaps.
+    void set_adaptive(bool on) { adaptive_ = on; }
 
     // Bulk form of on_ready(obj, all chunks) for objects that arrive complete, in this order.
     // Same effect as calling on_ready(objs[i], n_chunks) one by one.
@@ -409,6 +417,8 @@ public:
             }
         }
         // Walk the two staircases together; every piece where progress is allowed is a launch.
+        const bool may_partial = eager_ > 0 && (!adaptive_ || be_->idle());
+        bool held_back = false;
         struct Piece { int64_t c0, c1; int t0, t1; int64_t redo; };
         std::vector<Piece> pieces;
         std::vector<Stair> next;
@@ -419,7 +429,10 @@ public:
             const int t0 = done_[i].t;
             int t1 = std::max(t0, target[j].t);
             const bool complete = (t1 == n_steps);
-            if (t1 > t0 && !(complete || (eager_ > 0 && t1 - t0 >= eager_))) t1 = t0;
+            if (t1 > t0 && !(complete || (may_partial && t1 - t0 >= eager_))) {
+                held_back |= eager_ > 0 && !may_partial && t1 - t0 >= eager_;
+                t1 = t0;
+            }
             int redo = done_[i].redo;
             bool stored = done_[i].stored;
             // a launch if steps can run, or if every step has run but the result still sits in
@@ -453,6 +466,7 @@ public:
             info_.chunk_stores += (p.c1 - p.c0) * (int64_t)(final ? 1 : live_levels(p.t1));
         }
         done_.swap(next);
+        if (held_back) dirty_ = true;        // try again at the next event
         return HOP_OK;
     }
 
@@ -569,6 +583,7 @@ private:
     bool closing_ = false;
     bool dirty_ = false;                 // something changed that a pump could act on
     int eager_ = 0;
+    bool adaptive_ = false;
     std::vector<Stair> done_;            // progress of every chunk through prog_
     uint64_t version_ = 1, compiled_version_ = 0;
     std::vector<Entry> prog_;

@@ -14,6 +14,8 @@ using namespace hop;
 
 struct CheckingBackend : Backend {
     int64_t C = 0;
+    std::mt19937_64 *rng = nullptr;      // when set: the device is "busy" at random
+    bool idle() override { return !rng || ((*rng)() & 1u); }
     std::vector<int> steps_done;        // per chunk: steps whose accumulators are saved, or -1 if the result is stored
     uint64_t last_version = 0;
     long launches = 0;
@@ -99,6 +101,7 @@ int main(int argc, char **argv)
         be.steps_done.assign((size_t)C, 0);
         Scheduler s(n, k, C, d, &be);
         s.set_eager(rnd(0, 3));
+        if (rnd(0, 2) == 0) { be.rng = &rng; s.set_adaptive(true); }
         std::vector<int> order((size_t)n);
         for (int i = 0; i < n; ++i) order[(size_t)i] = i;
         std::shuffle(order.begin(), order.end(), rng);

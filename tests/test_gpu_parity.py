@@ -481,6 +481,45 @@ def test_composed_reduce_streams_one_result_into_the_next():
     assert np.array_equal(bits(workloads.to_numpy(out)), bits(want))
 
 
+def test_adaptive_policy_changes_the_launches_not_the_bits():
+    # eager, but partial progress only while the stream is idle: however the launches fall (it depends
+    # on timing), the result is the oracle's, bit for bit; with failures and a late replacement
+    d = dev()
+    rng = np.random.default_rng(33)
+    for dtype in ("f32", "bf16", "i32"):
+        C, ce, n, k = 6, 8192, 9, 7
+        E = C * ce - 5
+        w = workloads.WORKLOADS[1].scaled(E * ES[dtype], ce * ES[dtype], n=n, k=k, dtype=dtype, tree_degree=3,
+                                          dist={"f32": "uniform_pm1", "bf16": "normal_std1", "i32": "randint_pm2p20"}[dtype],
+                                          order_seed=int(rng.integers(1 << 30)), data_seed=int(rng.integers(1 << 30)))
+        objs = workloads.make_objects(w, device=d)
+        order = w.ready_order()
+        dst = torch.zeros_like(objs[0])
+        rc, s = hop.hop_session_begin(dst, objs, k, "sum", dtype, w.chunk_bytes, 3)
+        assert rc == hop.HOP_OK
+        assert hop.hop_session_set_eager(s, 1) == hop.HOP_OK and hop.hop_session_set_adaptive(s, 1) == hop.HOP_OK
+        failing = int(order[2])
+        fm = np.full(n, -1, np.int64)
+        fm[failing] = 2
+        for c in range(1, C + 1):
+            for i in order:
+                i = int(i)
+                if i == failing and c > 2:
+                    continue
+                assert hop.hop_session_ready(s, i, c) == hop.HOP_OK
+                if c % 2 == 0:
+                    torch.cuda.synchronize()                     # sometimes the stream is idle, sometimes not
+            if c == 2:
+                assert hop.hop_session_fail(s, failing) == hop.HOP_OK
+        rc, info = hop.hop_session_finish(s)
+        torch.cuda.synchronize()
+        # the oracle on the final occupants: everybody announced itself at chunk 1, the failing one left after 2
+        orc, want, k_eff, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], k, oracle.SUM, ORA_DT[dtype], ce, 3,
+                                            order, fm)
+        assert rc == orc and info["k_eff"] == k_eff
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+
+
 def test_readiness_by_event_needs_no_host_synchronisation():
     # The producers run on another stream: each one first idles for a while, then writes its object
     # chunk by chunk and records an event per chunk. The session is told "ready after this event";
