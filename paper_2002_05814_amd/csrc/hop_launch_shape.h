@@ -6,12 +6,14 @@
 
 namespace hop {
 
-// Launch shape, from sweeps on MI355X over the 64 MiB x 12, 256 MiB x 31 and
-// 16 MiB x 64 workloads: one wave per workgroup, each wave owning a tile of
-// 4 KiB per source (4 vectors per lane, all four loads of a source in flight
-// together), one tile per workgroup so that the dispatcher keeps every CU
-// supplied with fresh waves. Deeper accumulator stacks take fewer vectors per
-// lane to stay inside the register file.
+// Basic shape, from sweeps on MI355X over the 64 MiB x 12, 256 MiB x 31 and
+// 16 MiB x 64 workloads: one wave per workgroup, one tile per workgroup (the
+// dispatcher keeps the CUs supplied with fresh waves; persistent grids and
+// larger workgroups were slower), each wave owning a tile of up to 4 KiB per
+// source (4 vectors per lane, the four loads of a source in flight together).
+// Deeper accumulator stacks take fewer vectors per lane to stay inside the
+// register file. The size of the launch then decides tile size, loads in flight
+// and how many waves may be resident (below).
 constexpr int kThreads = 64;
 constexpr int kUnroll = 1;
 
