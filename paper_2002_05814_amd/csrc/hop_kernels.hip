@@ -35,7 +35,7 @@ const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
            "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels with 4 vectors/lane: "
-           "8 waves per CU from 4096 tiles, and from 12288 tiles (bf16 at depth 5..8: from 4096) 1 KiB tiles, unroll 8, 11 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
+           "8 waves per CU from 4096 tiles, and from 12288 tiles (bf16 at depth 5..8: from 4096) 1 KiB tiles, unroll 8, 10 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
            "kernel arguments; "
            "copy: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal";
 }

@@ -35,7 +35,8 @@ constexpr size_t kMidLaunchTiles = 2048;     // below this many 4 KiB tiles (and
 // per workgroup that the kernels never touch. It applies to the kernels that hold 4 vectors per
 // lane (shallow accumulator stacks); those with fewer (deep stacks, bf16 from depth 3) already hold
 // few waves through their register use, and capping them further only costs (measured).
-//  - from 48 MiB per object: the 1 KiB-tile kernel with 8 sources in flight at 11 waves per CU
+//  - from 48 MiB per object: the 1 KiB-tile kernel with 8 sources in flight at 10 waves per CU (9 measured a little faster still on the
+//    two large workloads, 7 much slower: 10 keeps a margin)
 //    (12 x 64 MiB fp32, degree 4: 79 % -> 83-85 %; gains of 3..10 points in sweeps over chains,
 //    stars and trees of 4..64 inputs of 64..512 MiB, fp32, int32 and bf16);
 //  - from 16 MiB: 4 KiB tiles at 8 waves per CU (12 x 16 MiB fp32: 70 % -> 75 %; 32 inputs: 72 % ->
@@ -44,7 +45,7 @@ constexpr size_t kCapLaunchTiles = 4096;      // 4 KiB tiles; below: uncapped
 constexpr int kLargeWavesPerCU = 8;
 constexpr size_t kStreamLaunchTiles = 12288;  // from this many 4 KiB tiles: 1 KiB tiles, 8 sources in flight
 constexpr int kStreamMaxDepth = 8;
-constexpr int kStreamWavesPerCU = 11;
+constexpr int kStreamWavesPerCU = 10;
 constexpr unsigned kLdsBytesPerCU = 160 * 1024;
 constexpr unsigned kStreamLdsBytes = kLdsBytesPerCU / kStreamWavesPerCU / 256 * 256;   // per workgroup
 constexpr unsigned kLargeLdsBytes = kLdsBytesPerCU / kLargeWavesPerCU / 256 * 256;
