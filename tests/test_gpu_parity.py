@@ -146,6 +146,37 @@ def test_many_small_objects_take_the_multi_pass_path(dtype):
         run_both(w, "sum")
 
 
+def test_infinities_and_nans_come_out_as_in_the_oracle():
+    # at most one NaN meets any element position (which of two NaN payloads an addition keeps is not
+    # fixed by the C the oracle is written in): inf - inf, inf + finite, a quiet NaN with a payload, a
+    # signalling NaN that meets a number, a signalling NaN that meets only zeros, NaNs in min and max
+    d = dev()
+    E = 64
+    vals = [np.zeros(E, np.float32) for _ in range(4)]
+    qnan = np.array([0x7fc01234], np.uint32).view(np.float32)[0]
+    snan = np.array([0x7f801234], np.uint32).view(np.float32)[0]
+    vals[0][0], vals[1][0] = np.inf, -np.inf
+    vals[0][1], vals[2][1] = np.inf, 1.0
+    vals[1][2], vals[2][2] = qnan, 2.0
+    vals[3][3], vals[0][3] = snan, 1.0
+    vals[2][5] = snan
+    vals[3][6], vals[1][6] = -np.inf, -np.inf
+    objs = [workloads.from_numpy(x, "f32", d) for x in vals]
+    for op in ("sum", "max", "min"):
+        for deg in (1, 2, 4):
+            dst = torch.zeros(E, device=d)
+            rc, info = hop.hop_reduce(dst, objs, 4, op, "f32", 256, deg, None, None)
+            torch.cuda.synchronize()
+            orc, want, _, _ = oracle.reduce(vals, 4, ORA_OP[op], oracle.F32, 64, deg, None, None)
+            assert rc == orc == hop.HOP_OK
+            assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want)), (op, deg)
+    # a reduce of one object is a copy, signalling NaNs included
+    dst = torch.zeros(E, device=d)
+    rc, _ = hop.hop_reduce(dst, objs[3:4], 1, "sum", "f32", 256, 2, None, None)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(vals[3]))
+
+
 def test_denormals_and_signed_zeros_are_preserved():
     w = workloads.WORKLOADS[1].scaled(4096 * 4, 1024, n=4, k=4)
     rng = np.random.default_rng(5)
