@@ -416,4 +416,40 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
     }
 }
 
+// One source, several destinations, the source read through the caches: a workgroup copies
+// one tile to one destination and ends. The tiles of a launch are grouped into spans; within
+// a span the workgroups go destination by destination, tile index fastest. Consecutive
+// workgroups then store consecutive tiles of one destination (a stream of short-lived waves,
+// which is what the memory system writes fastest), and a span's source tiles are read again
+// for every destination from the L2 of the XCD that read them first: workgroups are dealt to
+// the XCDs in turn and a span holds a multiple of 8 tiles, so a tile meets the same XCD for
+// every destination, and a span is sized to leave each XCD's share well inside its L2.
+template <int VPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void fanout_kernel(CopyArgs a)
+{
+    constexpr size_t kTile = (size_t)THREADS * VPT;
+    const table_ptr dsts = (table_ptr)(uintptr_t)a.dsts;
+    const unsigned per_span = a.span_tiles * (unsigned)a.n_dst;
+    const unsigned span = blockIdx.x / per_span, r = blockIdx.x - span * per_span;
+    const unsigned first = span * a.span_tiles;
+    const unsigned rest = a.n_tiles - first;
+    const unsigned ts = rest < a.span_tiles ? rest : a.span_tiles;      // tiles in this span
+    const unsigned d = r / ts, tile = first + (r - d * ts);
+    void *dst = dsts[d];
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const size_t v = tile * kTile + (size_t)j * THREADS + threadIdx.x;
+        if (v < a.n_vec) {
+            const size_t off = a.byte_begin + v * 16;
+            const u32x4 x = *(const u32x4 *)((const char *)a.src + off);
+            __builtin_nontemporal_store(x, (u32x4 *)((char *)dst + off));
+        }
+    }
+    if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail_bytes) {
+        const size_t off = a.byte_begin + a.n_vec * 16 + threadIdx.x;
+        const unsigned char b = *((const unsigned char *)a.src + off);
+        for (int e = 0; e < a.n_dst; ++e) *((unsigned char *)dsts[e] + off) = b;
+    }
+}
+
 }  // namespace hop

@@ -64,6 +64,8 @@ struct CopyArgs {
     size_t byte_begin;
     size_t n_vec;
     int n_tail_bytes;
+    unsigned n_tiles;          // fan-out kernel only: tiles in this launch
+    unsigned span_tiles;       // fan-out kernel only: tiles per span
 };
 
 int elem_bytes(int dtype);

@@ -37,7 +37,9 @@ const char *kernel_config()
            "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels with 4 vectors/lane: "
            "8 waves per CU from 4096 tiles, and from 12288 tiles (bf16 at depth 5..8: from 4096) 1 KiB tiles, unroll 8, 10 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
            "kernel arguments; "
-           "copy: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal";
+           "copy to one destination: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal; "
+           "to several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 tiles, "
+           "cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations)";
 }
 
 static Launcher pick(int dtype, int op, int depth)
@@ -138,14 +140,31 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
     return hipGetLastError();
 }
 
-// The copy is write-bound; longer bursts per destination pay: 8 vectors per lane
-// (8 KiB per wave and destination) beat 1, 2 and 4 in sweeps with 63 destinations,
-// as did keeping all destinations in one workgroup rather than splitting them.
+// One destination: every vector is read once (non-temporal) and stored once, 8 vectors per
+// lane in flight. Several destinations: the fan-out kernel, one 4 KiB tile and one destination
+// per workgroup, the source served from L2 after its first read, 12 resident waves per CU (10
+// and 12 measured alike, 6 and no limit 12-15 % slower). Measured on MI355X with the source not
+// in any cache beforehand, 16 / 64 / 256 MiB to 63 destinations: 151 / 592 / 2460 us against
+// 187 / 768 / 3170 us for a kernel that reads a tile once and stores it to every destination in
+// turn; to 8 destinations: 22 / 82 / 401 us against 25 / 114 / 481 us. Spans of 32 MiB (4 MiB
+// per XCD, the whole L2) were 40 % slower than spans of 16 MiB. A source of 128 MiB or more
+// going to fewer than 8 destinations is read from HBM for a large part of the run, which wants
+// more waves in flight: no limit there (256 MiB to 2: 140 us against 152 us).
 constexpr int kCopyVpt = 8;
 constexpr unsigned kCopyCapTiles = 5120;       // 8 KiB tiles: from 40 MiB per object
 constexpr int kCopyWavesPerCU = 10;
 constexpr unsigned kCopyLdsBytes = kLdsBytesPerCU / kCopyWavesPerCU / 256 * 256;
 static_assert(kLdsBytesPerCU / kCopyLdsBytes == kCopyWavesPerCU, "cap must come out as intended");
+constexpr int kFanoutVpt = 4;
+constexpr unsigned kFanoutSpanTiles = 4096;    // 4 KiB tiles: 16 MiB of the source, 2 MiB per XCD
+constexpr unsigned kFanoutMaxBlocks = 1u << 30;
+constexpr int kFanoutMaxDst = (int)(kFanoutMaxBlocks / kFanoutSpanTiles);
+constexpr int kFanoutWavesPerCU = 12;
+constexpr unsigned kFanoutLdsBytes = kLdsBytesPerCU / kFanoutWavesPerCU / 256 * 256;
+static_assert(kLdsBytesPerCU / kFanoutLdsBytes == kFanoutWavesPerCU, "cap must come out as intended");
+constexpr int kFanoutFewDst = 8;
+constexpr size_t kFanoutLongBytes = (size_t)128 << 20;
+static_assert(kFanoutSpanTiles % 8 == 0, "a tile must meet the same XCD for every destination");
 
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
                        size_t byte_begin, size_t byte_end, void *dst0)
@@ -160,9 +179,36 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
     a.byte_begin = byte_begin;
     a.n_vec = (byte_end - byte_begin) / 16;
     a.n_tail_bytes = (int)((byte_end - byte_begin) % 16);
+    a.n_tiles = 0;
+    a.span_tiles = 0;
+    if (n_dst >= 2 && n_dst <= kFanoutMaxDst) {
+        // whole spans per launch, as many as keep the grid below kFanoutMaxBlocks (one launch
+        // unless the copy is enormous); the bytes beyond the last whole vector go with the last
+        constexpr size_t kTileVecs = (size_t)kThreads * kFanoutVpt;
+        const size_t tiles = (a.n_vec + kTileVecs - 1) / kTileVecs;
+        const size_t spans_per_launch = kFanoutMaxBlocks / ((size_t)kFanoutSpanTiles * (size_t)n_dst);
+        const size_t tiles_per_launch = spans_per_launch * kFanoutSpanTiles;
+        a.span_tiles = kFanoutSpanTiles;
+        const unsigned lds = (n_dst < kFanoutFewDst && byte_end - byte_begin >= kFanoutLongBytes) ? 0 : kFanoutLdsBytes;
+        size_t done = 0;
+        do {
+            const size_t now = tiles - done < tiles_per_launch ? tiles - done : tiles_per_launch;
+            const bool last = done + now == tiles;
+            CopyArgs part = a;
+            part.byte_begin = byte_begin + done * kTileVecs * 16;
+            part.n_vec = last ? a.n_vec - done * kTileVecs : now * kTileVecs;
+            part.n_tail_bytes = last ? a.n_tail_bytes : 0;
+            part.n_tiles = (unsigned)now;
+            const size_t grid = (now < 1 ? 1 : now) * (size_t)n_dst;     // one workgroup at least, for the tail bytes
+            if (now == 0) part.n_tiles = 1;                              // its only tile is empty: n_vec == 0
+            hipLaunchKernelGGL((fanout_kernel<kFanoutVpt, kThreads>), dim3((unsigned)grid), dim3(kThreads), lds, stream, part);
+            done += now;
+        } while (done < tiles);
+        return hipGetLastError();
+    }
     const unsigned grid = grid_for(a.n_vec, (size_t)kThreads * kCopyVpt);
     // long copies, like long reduces, run faster with few resident waves (256 MiB one-to-one:
-    // 77 % -> 82 % of the HBM peak; 64 MiB to 8 destinations: 63 % -> 67 %; 16 MiB to 63: unchanged)
+    // 77 % -> 82 % of the HBM peak)
     const unsigned lds = grid >= kCopyCapTiles ? kCopyLdsBytes : 0;
     hipLaunchKernelGGL((copy_kernel<kCopyVpt, kThreads>), dim3(grid), dim3(kThreads), lds, stream, a);
     return hipGetLastError();

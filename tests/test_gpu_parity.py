@@ -278,6 +278,22 @@ def test_broadcast_paper_object_and_ragged_sizes():
     assert hop.hop_broadcast([], src, 16) == hop.HOP_OK
 
 
+def test_broadcast_over_several_spans_with_a_ragged_end():
+    # the copy to several destinations walks the source in 16 MiB spans, destination by destination:
+    # sizes around one, two and three spans, a last tile that is not full, bytes beyond the last vector
+    d = dev()
+    rng = np.random.default_rng(77)
+    span = 16 << 20
+    for nbytes, n_dst in ((span, 2), (span + 16, 3), (2 * span - 4096 + 48 + 7, 9), (3 * span + 5, 2), (span - 3, 1)):
+        blob = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+        s = torch.from_numpy(blob).to(d)
+        outs = [torch.zeros(nbytes + 16, dtype=torch.uint8, device=d) for _ in range(n_dst)]
+        assert hop.hop_broadcast(outs, s, 1 << 20, object_bytes=nbytes) == hop.HOP_OK
+        torch.cuda.synchronize()
+        for o in outs:
+            assert torch.equal(o[:nbytes], s) and int(o[nbytes:].sum()) == 0, (nbytes, n_dst)
+
+
 def test_receiver_driven_broadcast_chains_and_survives_a_lost_copy():
     d = dev()
     rng = np.random.default_rng(21)
