@@ -25,15 +25,15 @@ HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B
 # library reports another one, the figure is withheld (null).
 MEASURED_TRAFFIC = {
     "workload": "cfg2_async_sgd",
-    "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-                     "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels with 4 "
-                     "vectors/lane: 8 waves per CU from 4096 tiles, and from 12288 tiles (bf16 at depth 5..8: from 4096) 1"
-                     " KiB tiles, unroll 8, 10 waves per CU; nontemporal loads+stores, programs <= 128 steps in kernel "
-                     "arguments; copy to one destination: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 "
-                     "tiles, nontemporal; to several: one 4 KiB tile and one destination per workgroup, destination-major "
-                     "within spans of 4096 tiles, cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 "
-                     "MiB to < 8 destinations)",
-    "bytes": 872401295,
+    "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB "
+                     "tiles: 1 KiB tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart;"
+                     " from 2048: 1 KiB pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU "
+                     "from 4096 tiles; bf16 at depth 5..8 from 4096 tiles: 1 KiB tiles, unroll 8, 10 waves per CU; "
+                     "nontemporal loads+stores, programs <= 128 steps in kernel arguments; copy to one destination: 64 "
+                     "lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal; to several: one 4 KiB"
+                     " tile and one destination per workgroup, destination-major within spans of 4096 tiles, cached loads,"
+                     " nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations)",
+    "bytes": 872350290,
 }
 
 

@@ -270,16 +270,29 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
     using A = typename T::acc_t;
     constexpr int W = T::W;
     constexpr size_t kTile = (size_t)THREADS * VPT;
-    const size_t n_tiles = (a.n_vec + kTile - 1) / kTile;
+    // Which vectors a workgroup owns. Contiguous: VPT * THREADS consecutive vectors. Strided
+    // (piece_stride_log2 = s >= 0): the range is cut into pieces of THREADS vectors and into groups
+    // of VPT << s pieces; workgroup r of a group owns pieces r, r + 2^s, r + 2 * 2^s, ... of it. A
+    // wave's loads in flight then lie 2^s pieces apart instead of side by side, and consecutive
+    // workgroups still cover consecutive pieces.
+    const int sl = a.piece_stride_log2;
+    const size_t n_tiles = sl < 0 ? (a.n_vec + kTile - 1) / kTile : ((a.n_vec + (kTile << sl) - 1) / (kTile << sl)) << sl;
 
     for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         // lanes past the end of the range re-read the last vector (always inside the
         // range) and skip the store, so control flow stays uniform across the wave
         size_t off[VPT];
         bool live[VPT];
+        size_t first = tile * kTile, step = THREADS;     // vector index of piece 0, distance between pieces
+        if (sl >= 0) {
+            const size_t r = tile & (((size_t)1 << sl) - 1);
+            first = (((tile >> sl) * VPT) << sl) * THREADS + r * THREADS;
+            step = (size_t)THREADS << sl;
+            if (first >= a.n_vec) continue;               // a workgroup of the last group with nothing to do
+        }
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
-            const size_t v = tile * kTile + (size_t)j * THREADS + threadIdx.x;
+            const size_t v = first + (size_t)j * step + threadIdx.x;
             live[j] = v < a.n_vec;
             off[j] = a.byte_begin + (live[j] ? v : a.n_vec - 1) * 16;
         }

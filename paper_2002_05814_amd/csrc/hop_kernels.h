@@ -43,6 +43,8 @@ struct ReduceArgs {
     size_t n_vec;              // full 16-byte vectors in the range
     int n_tail;                // elements after the last full vector (object end only)
     const SubLaunch *subs;     // device table of gridDim.y sub-programs, or null (whole program -> dst)
+    int piece_stride_log2;     // < 0: a workgroup's vectors are contiguous; s >= 0: its VPT pieces of one vector
+                               // per lane lie 2^s pieces apart (see reduce_body)
     // segment launches only (reduce_kernel_seg): where accumulators live between segments
     char *spill;               // level L's array starts at spill + L * level_stride
     size_t level_stride;

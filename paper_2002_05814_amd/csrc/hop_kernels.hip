@@ -33,10 +33,11 @@ int elem_bytes(int dtype) { return dtype == HOP_BF16 ? 2 : 4; }
 
 const char *kernel_config()
 {
-    return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1, one 4 KiB tile per "
-           "workgroup (2 KiB tiles, unroll 2 below 2048 tiles; 1 KiB tiles, unroll 8 below 768); kernels with 4 vectors/lane: "
-           "8 waves per CU from 4096 tiles, and from 12288 tiles (bf16 at depth 5..8: from 4096) 1 KiB tiles, unroll 8, 10 waves per CU; nontemporal loads+stores, programs <= 128 steps in "
-           "kernel arguments; "
+    return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB tiles: 1 KiB "
+           "tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart; from 2048: 1 KiB "
+           "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 4096 tiles; bf16 at "
+           "depth 5..8 from 4096 tiles: 1 KiB tiles, unroll 8, 10 waves per CU; nontemporal loads+stores, programs <= "
+           "128 steps in kernel arguments; "
            "copy to one destination: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal; "
            "to several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 tiles, "
            "cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations)";
@@ -60,6 +61,7 @@ static void fill_range(ReduceArgs &a, int dtype, size_t byte_begin, size_t byte_
     a.byte_begin = byte_begin;
     a.n_vec = (byte_end - byte_begin) / 16;
     a.n_tail = (int)(((byte_end - byte_begin) % 16) / elem_bytes(dtype));
+    a.piece_stride_log2 = -1;
 }
 
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
@@ -80,13 +82,16 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     // (64 inputs in a binary tree: 56 % of the HBM peak at any size); one vector per lane with 8
     // sources in flight keeps it at 77-80 %
     const bool deep_bf16 = dtype == HOP_BF16 && depth > 4 && depth <= kStreamMaxDepth && tiles4k >= kCapLaunchTiles;
-    const bool stream_shape = (tiles4k >= kStreamLaunchTiles && l.vpt == 4 && depth <= kStreamMaxDepth) || deep_bf16;
-    const int shape = (tiles4k < kSmallLaunchTiles || stream_shape) ? 0 : tiles4k < kMidLaunchTiles ? 1 : 2;
+    const int shape = (tiles4k < kSmallLaunchTiles || deep_bf16) ? 0 : tiles4k < kMidLaunchTiles ? 1 : 2;
     const int vpt = shape == 0 ? 1 : shape == 1 ? (l.vpt < kMidVecs ? l.vpt : kMidVecs) : l.vpt;
     // LDS the kernels never touch: it only caps the number of resident waves per compute unit
-    const unsigned lds = stream_shape ? kStreamLdsBytes
+    const unsigned lds = deep_bf16 ? kStreamLdsBytes
                          : (shape == 2 && vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
-    const unsigned grid = grid_for(a.base.n_vec, (size_t)kThreads * vpt);
+    const int stride_log2 = vpt < 2 ? -1 : shape == 2 ? kPieceStrideLog2 : shape == 1 ? kMidPieceStrideLog2 : -1;
+    a.base.piece_stride_log2 = stride_log2;
+    // strided: whole groups of (vpt << stride) pieces, one workgroup per 2^stride-th of a group
+    const unsigned grid = stride_log2 < 0 ? grid_for(a.base.n_vec, (size_t)kThreads * vpt)
+                                          : grid_for(a.base.n_vec, ((size_t)kThreads * vpt) << stride_log2) << stride_log2;
     if (n_entries <= kInlineEntries) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
         hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), lds,

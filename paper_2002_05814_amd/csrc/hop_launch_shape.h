@@ -9,11 +9,11 @@ namespace hop {
 // Basic shape, from sweeps on MI355X over the 64 MiB x 12, 256 MiB x 31 and
 // 16 MiB x 64 workloads: one wave per workgroup, one tile per workgroup (the
 // dispatcher keeps the CUs supplied with fresh waves; persistent grids and
-// larger workgroups were slower), each wave owning a tile of up to 4 KiB per
-// source (4 vectors per lane, the four loads of a source in flight together).
+// larger workgroups were slower), each wave owning up to 4 KiB per source
+// (4 vectors per lane, the four loads of a source in flight together).
 // Deeper accumulator stacks take fewer vectors per lane to stay inside the
-// register file. The size of the launch then decides tile size, loads in flight
-// and how many waves may be resident (below).
+// register file. The size of the launch then decides tile size, loads in flight,
+// where a wave's vectors lie and how many waves may be resident (below).
 constexpr int kThreads = 64;
 constexpr int kUnroll = 1;
 
@@ -22,28 +22,36 @@ constexpr int kUnroll = 1;
 // in flight per lane instead, which shortens the dependent-load chain per wave.
 constexpr int kSmallUnroll = 8;
 constexpr size_t kSmallLaunchTiles = 768;    // below this many 4 KiB tiles the small shape is used
-// In between, 2 KiB tiles with two sources in flight: finer work granularity than the large
+// In between, 2 KiB per wave with two sources in flight: finer work granularity than the large
 // shape (whose few thousand long-lived waves quantise badly at these sizes), fewer
 // dependent rounds than the small one. From sweeps over 0.25..24 MiB objects.
 constexpr int kMidVecs = 2;
 constexpr int kMidUnroll = 2;
 constexpr size_t kMidLaunchTiles = 2048;     // below this many 4 KiB tiles (and above the small limit)
+// Where a wave's vectors lie. The loads a wave has in flight together should not sit side by side:
+// with its 4 vectors per lane in four 1 KiB pieces 64 KiB apart (instead of one contiguous 4 KiB) the
+// same kernel moves 31 x 256 MiB at 88 % of the HBM peak instead of 78 %, 12 x 64 MiB at 85 % instead
+// of 79 %, 4 x 128 MiB at 82 % instead of 78 %; 16 KiB apart measures about the same, 4 KiB and
+// 256 KiB apart clearly less. Consecutive workgroups still cover consecutive pieces, so the chip as a
+// whole streams through every source front to back. The 2 KiB shape gains 3-5 points with its two
+// pieces 16 KiB apart. The alternative of keeping several sources in flight at the same offset
+// (1 KiB tiles, 8 sources) depends on how the sources lie relative to each other: 70 % to 83 % for
+// 31 x 256 MiB as the distance between consecutive objects varies by a few KiB; pieces of one source
+// at a time do not (85-86 % for every placement tried).
+constexpr int kMidPieceStrideLog2 = 4;        // 2 KiB per wave: the two pieces lie 16 KiB apart
+constexpr int kPieceStrideLog2 = 6;           // up to 4 KiB per wave: the pieces lie 64 KiB apart
 // Resident waves. Once the result store joins the read streams, the memory system runs best with
-// few waves in flight per compute unit, each with several loads outstanding; kernels that need few
-// registers otherwise fill a CU with 20+ waves and lose 5-10 points of bandwidth (a chain over
-// 12 x 64 MiB fp32: 72 % of the HBM peak uncapped, 79-84 % capped). The cap is an LDS allocation
-// per workgroup that the kernels never touch. It applies to the kernels that hold 4 vectors per
-// lane (shallow accumulator stacks); those with fewer (deep stacks, bf16 from depth 3) already hold
-// few waves through their register use, and capping them further only costs (measured).
-//  - from 48 MiB per object: the 1 KiB-tile kernel with 8 sources in flight at 10 waves per CU (9 measured a little faster still on the
-//    two large workloads, 7 much slower: 10 keeps a margin)
-//    (12 x 64 MiB fp32, degree 4: 79 % -> 83-85 %; gains of 3..10 points in sweeps over chains,
-//    stars and trees of 4..64 inputs of 64..512 MiB, fp32, int32 and bf16);
-//  - from 16 MiB: 4 KiB tiles at 8 waves per CU (12 x 16 MiB fp32: 70 % -> 75 %; 32 inputs: 72 % ->
-//    83 %); below that a launch fits in one round of uncapped waves and a cap would split it in two.
+// few waves in flight per compute unit; kernels that need few registers otherwise fill a CU with
+// 20+ waves and lose 5-10 points of bandwidth. The cap is an LDS allocation per workgroup that the
+// kernels never touch. It applies to the kernels that hold 4 vectors per lane (shallow accumulator
+// stacks), from 16 MiB per object: 8 waves per CU (7 is a little faster for some shapes and much slower
+// for others, 10 and 12 lose 2-3 points); those with fewer vectors already hold few waves through
+// their register use, and capping them further only costs (measured). Below 16 MiB a launch fits in
+// one round of uncapped waves and a cap would split it in two.
 constexpr size_t kCapLaunchTiles = 4096;      // 4 KiB tiles; below: uncapped
 constexpr int kLargeWavesPerCU = 8;
-constexpr size_t kStreamLaunchTiles = 12288;  // from this many 4 KiB tiles: 1 KiB tiles, 8 sources in flight
+// bf16 with 5..8 accumulator levels (1 vector per lane at best in the 4 KiB shape) runs 1 KiB tiles
+// with 8 sources in flight at 10 waves per CU instead.
 constexpr int kStreamMaxDepth = 8;
 constexpr int kStreamWavesPerCU = 10;
 constexpr unsigned kLdsBytesPerCU = 160 * 1024;

@@ -644,30 +644,40 @@ def sampled_oracle_check(w, op, objs, dsts, rc, info, rng, per_chunk=64):
 
 
 # every launch shape of the reduce kernel, each at a size just inside its range, with one object a few
-# elements short of a tile so that the ragged end is exercised too: (dtype, n, k, degree, MiB, dist)
+# elements short of a tile so that the ragged end is exercised too: (dtype, n, k, degree, bytes short of or
+# beyond a whole number of MiB, MiB, dist). From 3 MiB a workgroup's pieces lie 16 or 64 KiB apart, in
+# groups of 32 or 256 KiB: "a few KiB beyond" leaves a last group in which most workgroups own nothing.
+SHORT = -3 * 16                                    # not a whole tile, not a whole vector (minus one element below)
+BEYOND = 5 * 1024 + 3 * 16                         # a last group with five whole pieces and a ragged sixth
 LAUNCH_SHAPE_CASES = [
-    ("f32", 6, 5, 2, 2, "uniform_pm1"),            # 1 KiB tiles, 8 sources in flight (few tiles)
-    ("f32", 6, 5, 2, 6, "uniform_pm1"),            # 2 KiB tiles, 2 in flight
-    ("f32", 6, 5, 4, 12, "normal_std1"),           # 4 KiB tiles, uncapped
-    ("i32", 6, 6, 2, 20, "randint_pm2p20"),            # 4 KiB tiles, 8 waves per CU
-    ("f32", 5, 4, 1, 52, "normal_std1"),           # streaming shape: 1 KiB tiles, 11 waves per CU
-    ("bf16", 6, 6, 6, 50, "normal_std1"),          # streaming shape, bf16 at depth 1..2
-    ("bf16", 40, 40, 2, 17, "normal_std1"),        # bf16 binary tree (5 levels): 1 KiB tiles from 16 MiB
-    ("bf16", 12, 12, 4, 20, "normal_std1"),        # bf16 at depth 2 between 16 and 48 MiB: 4 KiB tiles capped
-    ("f32", 40, 40, 2, 49, "normal_std1"),         # fp32 binary tree (5 levels) in the streaming shape
+    ("f32", 6, 5, 2, SHORT, 2, "uniform_pm1"),       # 1 KiB tiles, 8 sources in flight (few tiles)
+    ("f32", 6, 5, 2, SHORT, 6, "uniform_pm1"),       # 2 KiB tiles, 2 in flight, pieces 16 KiB apart
+    ("f32", 6, 5, 2, BEYOND, 5, "uniform_pm1"),      # the same, a few KiB into the last group
+    ("f32", 6, 5, 4, SHORT, 12, "normal_std1"),      # four pieces 64 KiB apart, uncapped
+    ("f32", 6, 5, 4, BEYOND, 9, "normal_std1"),      # the same, a few KiB into the last group
+    ("i32", 6, 6, 2, SHORT, 20, "randint_pm2p20"),   # four pieces 64 KiB apart, 8 waves per CU
+    ("i32", 6, 6, 2, BEYOND, 17, "randint_pm2p20"),  # the same, a few KiB into the last group
+    ("f32", 5, 4, 1, SHORT, 52, "normal_std1"),      # a chain over 52 MiB objects
+    ("bf16", 6, 6, 6, SHORT, 50, "normal_std1"),     # bf16 at depth 1..2, four pieces
+    ("bf16", 40, 40, 2, SHORT, 17, "normal_std1"),   # bf16 binary tree (5 levels): 1 KiB tiles, 8 in flight, from 16 MiB
+    ("bf16", 12, 12, 4, SHORT, 20, "normal_std1"),   # bf16 at depth 2
+    ("bf16", 16, 16, 2, BEYOND, 9, "normal_std1"),   # bf16 at depth 3..4: two pieces per workgroup, 64 KiB apart
+    ("f32", 40, 40, 2, SHORT, 49, "normal_std1"),    # fp32 binary tree (5 levels)
 ]
 
 
-@pytest.mark.parametrize("dtype,n,k,d,mib,dist", LAUNCH_SHAPE_CASES)
-def test_every_launch_shape_against_sampled_oracle(dtype, n, k, d, mib, dist):
-    nbytes = mib * (1 << 20) - 3 * 16 - ES[dtype]          # not a whole tile, not a whole vector
+@pytest.mark.parametrize("dtype,n,k,d,delta,mib,dist", LAUNCH_SHAPE_CASES)
+def test_every_launch_shape_against_sampled_oracle(dtype, n, k, d, delta, mib, dist):
+    nbytes = mib * (1 << 20) + delta - ES[dtype]
     chunk = 1 << 20
     w = workloads.Workload("shape_%s_%d" % (dtype, mib), n=n, dtype=dtype, object_bytes=nbytes, chunk_bytes=chunk,
                            k=k, tree_degree=d, ops=("sum",), dist=dist, order_seed=1234 + mib, data_seed=99 + mib)
-    print("launch shape case", w.name, n, k, d, flush=True)
+    print("launch shape case", w.name, n, k, d, nbytes, flush=True)
     objs = workloads.make_objects(w, device=dev())
     dst = torch.zeros_like(objs[0])
+    sel = [objs[i] for i in w.ready_order()[:k]]
     for op in ("sum", "max"):
+        dst.fill_(7)                                  # a piece no workgroup wrote would keep this
         rc, info = hop.hop_reduce(dst, objs, k, op, dtype, chunk, d, w.ready_order(), None)
         torch.cuda.synchronize()
         assert rc == hop.HOP_OK and info["n_launches"] == 1
@@ -678,6 +688,26 @@ def test_every_launch_shape_against_sampled_oracle(dtype, n, k, d, mib, dist):
         small = [workloads.to_numpy(o[tail]) for o in objs]
         _, want, _, _ = oracle.reduce(small, k, ORA_OP[op], ORA_DT[dtype], 40, d, w.ready_order(), None)
         assert np.array_equal(bits(workloads.to_numpy(dst[tail])), bits(want))
+        # every element, by properties that hold in any order: max is exact; an integer sum is exact; a float
+        # sum lies within the free-order tolerance of the fp64 sum
+        if op == "max":
+            ref = sel[0].clone()
+            for o in sel[1:]:
+                ref = torch.maximum(ref, o)
+            assert torch.equal(dst, ref)
+        elif dtype == "i32":
+            ref = torch.zeros_like(sel[0])
+            for o in sel:
+                ref += o
+            assert torch.equal(dst, ref)
+        else:
+            ref = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
+            mag = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
+            for o in sel:
+                ref += o.double()
+                mag += o.double().abs()
+            tol = 1e-5 * np.log2(k) if dtype == "f32" else 1e-2
+            assert bool(((dst.double() - ref).abs() <= tol * torch.maximum(ref.abs(), mag / k)).all())
 
 
 def test_cfg2_full_size_sampled():
