@@ -396,21 +396,30 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel_inline(ReduceArgsInline
     reduce_body<DT, OP, D, VPT, U, THREADS>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
 }
 
-// One source, n_dst destinations: each 16-byte vector is read once and
+// One source, n_dst destinations: each 16-byte vector is read once (non-temporal) and
 // written n_dst times. VPT vectors per lane are in flight together.
 template <int VPT, int THREADS>
 __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
 {
     constexpr size_t kTile = (size_t)THREADS * VPT;
-    const size_t n_tiles = (a.n_vec + kTile - 1) / kTile;
+    // the vectors of a workgroup: contiguous, or VPT pieces 2^s pieces apart (as in reduce_body)
+    const int sl = a.piece_stride_log2;
+    const size_t n_tiles = sl < 0 ? (a.n_vec + kTile - 1) / kTile : ((a.n_vec + (kTile << sl) - 1) / (kTile << sl)) << sl;
     const table_ptr dsts = (table_ptr)(uintptr_t)a.dsts;
     for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         uint4 x[VPT];
         size_t off[VPT];
         bool live[VPT];
+        size_t first = tile * kTile, step = THREADS;
+        if (sl >= 0) {
+            const size_t r = tile & (((size_t)1 << sl) - 1);
+            first = (((tile >> sl) * VPT) << sl) * THREADS + r * THREADS;
+            step = (size_t)THREADS << sl;
+            if (first >= a.n_vec) continue;
+        }
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
-            const size_t v = tile * kTile + (size_t)j * THREADS + threadIdx.x;
+            const size_t v = first + (size_t)j * step + threadIdx.x;
             live[j] = v < a.n_vec;
             off[j] = a.byte_begin + (live[j] ? v : a.n_vec - 1) * 16;
             x[j] = ld16(a.src, off[j]);

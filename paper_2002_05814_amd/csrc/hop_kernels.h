@@ -66,6 +66,7 @@ struct CopyArgs {
     size_t byte_begin;
     size_t n_vec;
     int n_tail_bytes;
+    int piece_stride_log2;     // copy kernel only: < 0 contiguous vectors per workgroup, else pieces 2^s apart
     unsigned n_tiles;          // fan-out kernel only: tiles in this launch
     unsigned span_tiles;       // fan-out kernel only: tiles per span
 };

@@ -38,7 +38,8 @@ const char *kernel_config()
            "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 4096 tiles; bf16 at "
            "depth 5..8 from 4096 tiles: 1 KiB tiles, unroll 8, 10 waves per CU; nontemporal loads+stores, programs <= "
            "128 steps in kernel arguments; "
-           "copy to one destination: 64 lanes/workgroup, 8 vectors/lane, 10 waves per CU from 5120 tiles, nontemporal; "
+           "copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from 5120 8-KiB tiles 4 vectors/lane in "
+           "1 KiB pieces 64 KiB apart, 10 waves per CU; nontemporal; "
            "to several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 tiles, "
            "cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations)";
 }
@@ -123,8 +124,14 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
     a.level_stride = level_stride;
     a.n_restore = n_restore;
     a.n_save = n_save;
-    const unsigned grid = grid_for(a.n_vec, (size_t)kThreads * l.vpt);
-    hipLaunchKernelGGL(l.seg, dim3(grid), dim3(kThreads), 0, stream, a);
+    // long ranges as in launch_reduce: pieces 64 KiB apart, and few resident waves for the 4-vector kernels
+    const size_t tiles4k = (a.n_vec + 255) / 256;
+    const bool strided = l.vpt >= 2 && tiles4k >= kMidLaunchTiles;
+    a.piece_stride_log2 = strided ? kPieceStrideLog2 : -1;
+    const unsigned lds = (l.vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
+    const unsigned grid = !strided ? grid_for(a.n_vec, (size_t)kThreads * l.vpt)
+                                   : grid_for(a.n_vec, ((size_t)kThreads * l.vpt) << kPieceStrideLog2) << kPieceStrideLog2;
+    hipLaunchKernelGGL(l.seg, dim3(grid), dim3(kThreads), lds, stream, a);
     return hipGetLastError();
 }
 
@@ -145,8 +152,10 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
     return hipGetLastError();
 }
 
-// One destination: every vector is read once (non-temporal) and stored once, 8 vectors per
-// lane in flight. Several destinations: the fan-out kernel, one 4 KiB tile and one destination
+// One destination: every vector is read once (non-temporal) and stored once; 8 contiguous
+// vectors per lane in flight, and from 40 MiB 4 vectors per lane in 1 KiB pieces 64 KiB apart
+// at 10 waves per CU (256 MiB: 6.47 -> 6.73 TB/s read + write, 64 MiB: 5.94 -> 6.14; at 16 MiB
+// the contiguous uncapped kernel is the fastest). Several destinations: the fan-out kernel, one 4 KiB tile and one destination
 // per workgroup, the source served from L2 after its first read, 12 resident waves per CU (10
 // and 12 measured alike, 6 and no limit 12-15 % slower). Measured on MI355X with the source not
 // in any cache beforehand, 16 / 64 / 256 MiB to 63 destinations: 151 / 592 / 2460 us against
@@ -156,6 +165,7 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
 // going to fewer than 8 destinations is read from HBM for a large part of the run, which wants
 // more waves in flight: no limit there (256 MiB to 2: 140 us against 152 us).
 constexpr int kCopyVpt = 8;
+constexpr int kLongCopyVpt = 4;
 constexpr unsigned kCopyCapTiles = 5120;       // 8 KiB tiles: from 40 MiB per object
 constexpr int kCopyWavesPerCU = 10;
 constexpr unsigned kCopyLdsBytes = kLdsBytesPerCU / kCopyWavesPerCU / 256 * 256;
@@ -186,6 +196,7 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
     a.n_tail_bytes = (int)((byte_end - byte_begin) % 16);
     a.n_tiles = 0;
     a.span_tiles = 0;
+    a.piece_stride_log2 = -1;
     if (n_dst >= 2 && n_dst <= kFanoutMaxDst) {
         // whole spans per launch, as many as keep the grid below kFanoutMaxBlocks (one launch
         // unless the copy is enormous); the bytes beyond the last whole vector go with the last
@@ -212,10 +223,15 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
         return hipGetLastError();
     }
     const unsigned grid = grid_for(a.n_vec, (size_t)kThreads * kCopyVpt);
-    // long copies, like long reduces, run faster with few resident waves (256 MiB one-to-one:
-    // 77 % -> 82 % of the HBM peak)
-    const unsigned lds = grid >= kCopyCapTiles ? kCopyLdsBytes : 0;
-    hipLaunchKernelGGL((copy_kernel<kCopyVpt, kThreads>), dim3(grid), dim3(kThreads), lds, stream, a);
+    if (grid >= kCopyCapTiles) {
+        // long copies, like long reduces, run faster with few resident waves and with a wave's
+        // vectors apart (256 MiB one-to-one: 77 % -> 84 % of the HBM peak)
+        a.piece_stride_log2 = kPieceStrideLog2;
+        const unsigned g = grid_for(a.n_vec, ((size_t)kThreads * kLongCopyVpt) << kPieceStrideLog2) << kPieceStrideLog2;
+        hipLaunchKernelGGL((copy_kernel<kLongCopyVpt, kThreads>), dim3(g), dim3(kThreads), kCopyLdsBytes, stream, a);
+    } else {
+        hipLaunchKernelGGL((copy_kernel<kCopyVpt, kThreads>), dim3(grid), dim3(kThreads), 0, stream, a);
+    }
     return hipGetLastError();
 }
 

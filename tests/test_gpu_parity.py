@@ -284,7 +284,8 @@ def test_broadcast_over_several_spans_with_a_ragged_end():
     d = dev()
     rng = np.random.default_rng(77)
     span = 16 << 20
-    for nbytes, n_dst in ((span, 2), (span + 16, 3), (2 * span - 4096 + 48 + 7, 9), (3 * span + 5, 2), (span - 3, 1)):
+    for nbytes, n_dst in ((span, 2), (span + 16, 3), (2 * span - 4096 + 48 + 7, 9), (3 * span + 5, 2), (span - 3, 1),
+                          ((41 << 20) + 5 * 1024 + 21, 1)):        # long one-to-one copy: pieces 64 KiB apart, a ragged last group
         blob = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
         s = torch.from_numpy(blob).to(d)
         outs = [torch.zeros(nbytes + 16, dtype=torch.uint8, device=d) for _ in range(n_dst)]
