@@ -332,6 +332,7 @@ private:
                 staging_[i] = resolve(prog[i], nullptr, 0, 0);
                 depth_ = std::max(depth_, (int)prog[i].level + 1);
             }
+            mark_runs(staging_.data(), staging_.size());
             dev_prog_ = nullptr;
             if ((int)staging_.size() > kInlineEntries) {      // short programs ride in the kernel arguments
                 dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
@@ -435,8 +436,10 @@ private:
             pi.n_subs = 0;
             for (size_t g = 0; g < n_subs; ++g) {
                 if (mp.height[g] != pass) continue;
+                const size_t sub_at = blob.size();
                 for (int32_t t = mp.begin[g]; t < mp.begin[g + 1]; ++t)
                     blob.push_back(resolve(mp.steps[(size_t)t], partials, part_bytes, b0));
+                mark_runs(blob.data() + sub_at, blob.size() - sub_at);
                 pi.depth = std::max(pi.depth, (int)mp.depth[g]);
                 pi.n_subs++;
             }
@@ -456,6 +459,7 @@ private:
         }
         const size_t top_at = blob.size();
         for (const Entry &e : mp.top) blob.push_back(resolve(e, partials, part_bytes, b0));
+        mark_runs(blob.data() + top_at, blob.size() - top_at);
         const DevEntry *dev = (const DevEntry *)ws_.stage_in_place(blob.data(), blob.size() * sizeof(DevEntry));
         if (!dev) return HOP_ERR_NOMEM;
         for (const PassInfo &pi : passes) {

@@ -135,6 +135,23 @@ struct Machine {
             --n_fold;
         }
     }
+
+    // G values, one after the other, into the accumulator of one level
+    template <int G, class Get> __device__ __forceinline__ void run(uint32_t level, Get get)
+    {
+#pragma unroll
+        for (int L = 0; L < D; ++L) {
+            if (level == (uint32_t)L) {
+#pragma unroll
+                for (int u = 0; u < G; ++u) {
+                    A x[W];
+                    get(u, x);
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[L][w] = combine<OP>(acc[L][w], x[w]);
+                }
+            }
+        }
+    }
 };
 
 // All object traffic is streamed exactly once, so loads and stores carry the
@@ -233,6 +250,14 @@ __device__ __forceinline__ void fold_group(M &m, const StepGroup<G> &g, const ui
 {
     using A = typename Traits<DT>::acc_t;
     constexpr int W = Traits<DT>::W;
+    if (G == kRunSteps && (g.ctl[0] & kRunBit)) {
+        // a run of plain combines into one level: one dispatch for the whole group
+        m.template run<G>(g.ctl[0] & 0xffu, [&](int u, A *x) {
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
+        });
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < G; ++u) {
         A x[VPT * W];

@@ -36,8 +36,8 @@ const char *kernel_config()
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB tiles: 1 KiB "
            "tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart; from 2048: 1 KiB "
            "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 4096 tiles; bf16 at "
-           "depth 5..8 from 4096 tiles: 1 KiB tiles, unroll 8, 10 waves per CU; nontemporal loads+stores, programs <= "
-           "128 steps in kernel arguments; "
+           "depth 5..8 from 4096 tiles: 1 KiB tiles, unroll 8, 10 waves per CU; groups of 8 plain steps marked by the host; "
+           "nontemporal loads+stores, programs <= 128 steps in kernel arguments; "
            "copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from 5120 8-KiB tiles 4 vectors/lane in "
            "1 KiB pieces 64 KiB apart, 10 waves per CU; nontemporal; "
            "to several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 tiles, "

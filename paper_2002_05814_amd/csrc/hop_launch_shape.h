@@ -21,6 +21,7 @@ constexpr int kUnroll = 1;
 // chip with 4 KiB tiles; they use 1 KiB tiles (one vector per lane) with 8 sources
 // in flight per lane instead, which shortens the dependent-load chain per wave.
 constexpr int kSmallUnroll = 8;
+static_assert(kSmallUnroll == kRunSteps, "runs are marked for the group size of the small shape");
 constexpr size_t kSmallLaunchTiles = 768;    // below this many 4 KiB tiles the small shape is used
 // In between, 2 KiB per wave with two sources in flight: finer work granularity than the large
 // shape (whose few thousand long-lived waves quantise badly at these sizes), fewer
