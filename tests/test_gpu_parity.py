@@ -95,7 +95,7 @@ def test_cfg5_full_size(op):
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "i32"])
 @pytest.mark.parametrize("op", ["sum", "min", "max"])
 def test_random_shapes_and_failures(dtype, op):
-    rng = np.random.default_rng(hash((dtype, op)) % 2 ** 32)
+    rng = np.random.default_rng(1000 + 10 * ["f32", "bf16", "i32"].index(dtype) + ["sum", "min", "max"].index(op))
     base = workloads.WORKLOADS[{"f32": 2, "bf16": 4, "i32": 3}[dtype]]
     for it in range(12):
         n = int(rng.integers(1, 40))
@@ -113,6 +113,22 @@ def test_random_shapes_and_failures(dtype, op):
             bad = rng.random(n) < 0.3
             fm[bad] = rng.integers(0, C + 2, size=int(bad.sum()))
         run_both(w, op, fm=fm)
+
+
+@pytest.mark.parametrize("d", [1, 2, 16, 64])
+def test_every_input_count_up_to_forty(d):
+    # chains, binary trees, wide trees and stars over 1..40 inputs: the kernel takes the steps in groups of
+    # eight, and groups that consist of plain combines into one level in one go; every count puts the group
+    # boundaries elsewhere in the program
+    base = workloads.WORKLOADS[2]
+    for n in range(1, 41):
+        w = base.scaled(200 * 4 + 4, 512, n=n, k=n, tree_degree=d, order_seed=500 + n, data_seed=600 + n, fail={},
+                        name="count%d" % n)
+        run_both(w, "sum")
+    w = workloads.WORKLOADS[4].scaled(200 * 2 + 2, 512, n=37, k=35, tree_degree=d, order_seed=5, data_seed=6, fail={},
+                                      name="count_bf16")
+    run_both(w, "sum")
+    run_both(w, "min")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "i32", "bf16"])
