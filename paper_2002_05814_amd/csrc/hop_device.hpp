@@ -275,12 +275,13 @@ __device__ __forceinline__ void run_group(M &m, const Prog prog, int t, int n, c
     fold_group<DT, G, VPT, M>(m, g, raw);
 }
 
-// One workgroup of THREADS lanes walks tiles of THREADS*VPT consecutive
-// 16-byte vectors (lane l owns vectors l, l+THREADS, ...: every load
-// instruction of a wave covers 1 KiB of consecutive addresses). For each tile
-// the program is run in groups of U steps: the U*VPT loads of a group are all
-// issued before the first of them is consumed, then the group's values are
-// folded in program order. D = accumulator levels held in registers.
+// One workgroup of THREADS lanes walks tiles of THREADS*VPT 16-byte vectors:
+// VPT pieces of THREADS consecutive vectors (every load instruction of a wave
+// covers 1 KiB of consecutive addresses), the pieces side by side or a fixed
+// distance apart (piece_stride_log2, below). For each tile the program is run
+// in groups of U steps: the U*VPT loads of a group are all issued before the
+// first of them is consumed, then the group's values are folded in program
+// order. D = accumulator levels held in registers.
 //
 // SEG: the launch runs only a segment of a program. Accumulator levels
 // [0, n_restore) are first read back from the spill area (where the previous
