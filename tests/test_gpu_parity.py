@@ -584,6 +584,36 @@ def test_adaptive_policy_changes_the_launches_not_the_bits():
         assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
 
 
+@pytest.mark.parametrize("dtype,mib", [("f32", 9), ("bf16", 17), ("i32", 33)])
+def test_eager_segments_over_long_ranges(dtype, mib):
+    # whole objects arrive one at a time and every arrival is folded into the saved accumulators at once: the
+    # segment launches span the whole object, long enough for the layout with pieces 64 KiB apart (and, from
+    # 16 MiB, the cap on resident waves). Same bits as the one-launch reduce and as the oracle on samples.
+    d = dev()
+    nbytes = mib * (1 << 20) + 5 * 1024 + 3 * 16 - ES[dtype]
+    chunk = 3 << 20
+    n, k, deg = 7, 6, 2
+    w = workloads.Workload("eager_long_%s" % dtype, n=n, dtype=dtype, object_bytes=nbytes, chunk_bytes=chunk, k=k,
+                           tree_degree=deg, ops=("sum",), order_seed=4242 + mib, data_seed=4343 + mib,
+                           dist={"f32": "normal_std1", "bf16": "normal_std1", "i32": "randint_pm2p20"}[dtype])
+    objs = workloads.make_objects(w, device=d)
+    order = w.ready_order()
+    fused = torch.zeros_like(objs[0])
+    rc, info = hop.hop_reduce(fused, objs, k, "sum", dtype, chunk, deg, order, None)
+    assert rc == hop.HOP_OK
+    dst = torch.full_like(objs[0], 3)
+    rc, s = hop.hop_session_begin(dst, objs, k, "sum", dtype, chunk, deg)
+    assert rc == hop.HOP_OK and hop.hop_session_set_eager(s, 1) == hop.HOP_OK
+    for i in order:
+        assert hop.hop_session_ready(s, int(i), w.n_chunks) == hop.HOP_OK
+    rc, sinfo = hop.hop_session_finish(s)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK and sinfo["n_launches"] >= k - 1
+    assert torch.equal(dst.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       fused.view(torch.int16 if dtype == "bf16" else torch.int32))
+    sampled_oracle_check(w, "sum", objs, [dst], rc, sinfo, np.random.default_rng(mib), per_chunk=16)
+
+
 def test_readiness_by_event_needs_no_host_synchronisation():
     # The producers run on another stream: each one first idles for a while, then writes its object
     # chunk by chunk and records an event per chunk. The session is told "ready after this event";
