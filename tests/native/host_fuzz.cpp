@@ -5,10 +5,12 @@
 #include <cstdlib>
 #include <map>
 #include <random>
+#include <string>
 #include <vector>
 
 #include "../../paper_2002_05814_amd/csrc/hop_bcast.hpp"
 #include "../../paper_2002_05814_amd/csrc/hop_plan.hpp"
+#include "../../paper_2002_05814_amd/csrc/hop_program.h"
 
 using namespace hop;
 
@@ -85,6 +87,52 @@ static void fuzz_bcast(std::mt19937_64 &rng)
     if (s.drain() < 0 || !s.all_complete()) { std::printf("broadcast did not complete\n"); std::abort(); }
 }
 
+// The marking of step groups (hop_program.h): a marked group must be eight plain combines into one
+// level and start a multiple of eight steps from the program's start, every such group must be
+// marked, and a walk that takes marked groups in one go (as the small-tile kernel does) must build
+// the same expression, parenthesis for parenthesis, as the walk that looks at every control word.
+static std::string walk(const std::vector<DevEntry> &p, bool use_marks)
+{
+    std::vector<std::string> acc(HOP_MAX_DEPTH + 1);
+    auto term = [&](size_t t) { return "x" + std::to_string((size_t)(uintptr_t)p[t].src); };
+    auto one = [&](size_t t) {
+        uint32_t level = p[t].ctl & 0xffu, n_fold = p[t].ctl >> 16;
+        const bool set = (p[t].ctl >> 8) & 1u;
+        acc[level] = set ? term(t) : "(" + acc[level] + "+" + term(t) + ")";
+        for (; n_fold; --n_fold, --level) acc[level - 1] = "(" + acc[level - 1] + "+" + acc[level] + ")";
+    };
+    size_t t = 0;
+    for (; t + kRunSteps <= p.size(); t += kRunSteps) {
+        if (use_marks && (p[t].ctl & kRunBit)) {
+            const uint32_t level = p[t].ctl & 0xffu;
+            for (int u = 0; u < kRunSteps; ++u) acc[level] = "(" + acc[level] + "+" + term(t + (size_t)u) + ")";
+        } else {
+            for (int u = 0; u < kRunSteps; ++u) one(t + (size_t)u);
+        }
+    }
+    for (; t < p.size(); ++t) one(t);
+    return acc[0];
+}
+static void check_marks(const std::vector<Entry> &prog)
+{
+    std::vector<DevEntry> p(prog.size());
+    for (size_t t = 0; t < prog.size(); ++t) {
+        p[t].src = (const void *)(uintptr_t)(t + 1);
+        p[t].ctl = (uint32_t)prog[t].level | ((uint32_t)prog[t].set << 8) | ((uint32_t)prog[t].n_fold << 16);
+        p[t].reserved = 0;
+    }
+    const std::string plain = walk(p, false);
+    mark_runs(p.data(), p.size());
+    for (size_t t = 0; t < p.size(); ++t) {
+        bool all_plain = t % kRunSteps == 0 && t + kRunSteps <= p.size();
+        for (int u = 0; all_plain && u < kRunSteps; ++u)
+            all_plain = prog[t + (size_t)u].set == 0 && prog[t + (size_t)u].n_fold == 0 && prog[t + (size_t)u].level == prog[t].level;
+        if (((p[t].ctl & kRunBit) != 0) != all_plain) { std::printf("run mark wrong at step %zu\n", t); std::abort(); }
+        if ((p[t].ctl & ~kRunBit) != ((uint32_t)prog[t].level | ((uint32_t)prog[t].set << 8) | ((uint32_t)prog[t].n_fold << 16))) std::abort();
+    }
+    if (walk(p, true) != plain) { std::printf("marked walk builds another expression\n"); std::abort(); }
+}
+
 int main(int argc, char **argv)
 {
     const int rounds = argc > 1 ? std::atoi(argv[1]) : 3000;
@@ -154,6 +202,7 @@ int main(int argc, char **argv)
         for (int t = 0; t < k; ++t) occ[(size_t)t] = rnd(0, 9) ? t : -1;
         std::vector<Entry> prog;
         compile_program(tr, occ, prog);
+        check_marks(prog);
         MultiPlan mp;
         { const int lo = rnd(1, 6); plan_passes(prog, (size_t)rnd(1, 40), lo, lo + rnd(0, 30), mp); }
         fuzz_bcast(rng);
