@@ -45,7 +45,7 @@ static int g_block_count = 0;
 
 static Block *acquire_block(int device, size_t bytes)
 {
-    Block *wait_for = nullptr;
+    Block *wait_for = nullptr, *too_small = nullptr;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         for (size_t i = 0; i < g_free.size(); ++i) {
@@ -62,12 +62,31 @@ static Block *acquire_block(int device, size_t bytes)
             g_free.erase(g_free.begin() + i);
             return b;
         }
-        if (wait_for && g_block_count >= kMaxBlocks) {
+        if (g_block_count >= kMaxBlocks) {
+            // at the limit: an idle block that is too small makes room for one of the right size
+            // (otherwise callers of the larger size would queue for the few blocks that fit them)
+            for (size_t i = 0; i < g_free.size() && !too_small; ++i) {
+                Block *b = g_free[i];
+                if (b->device != device || b->cap >= bytes) continue;
+                if (b->pending && hipEventQuery(b->ev) != hipSuccess) { (void)hipGetLastError(); continue; }
+                too_small = b;
+                g_free.erase(g_free.begin() + i);
+            }
+        }
+        if (too_small) {
+            wait_for = nullptr;                           // its place in the count goes to the new block
+        } else if (wait_for && g_block_count >= kMaxBlocks) {
             g_free.erase(std::find(g_free.begin(), g_free.end(), wait_for));
         } else {
             wait_for = nullptr;
             g_block_count++;
         }
+    }
+    if (too_small) {
+        (void)hipEventDestroy(too_small->ev);
+        (void)hipFree(too_small->dev);
+        (void)hipHostFree(too_small->host);
+        delete too_small;
     }
     if (wait_for) {
         if (hipEventSynchronize(wait_for->ev) != hipSuccess) (void)hipGetLastError();
@@ -397,7 +416,7 @@ private:
     // Partials are stored in the accumulation type, which for bf16 is not the element type: bf16
     // keeps the plain path.
     static constexpr size_t kSplitWantSteps = 128;      // shorter programs are not worth extra launches
-    static constexpr int kSplitMaxRun = 64;             // longest sub-program
+    static constexpr int kSplitMaxRun = kMaxSubSteps;   // longest sub-program: a record fits the lanes of a wave
     static constexpr size_t kSplitMaxBytes = 1u << 20;  // launches this large already fill the chip
     static constexpr int kSplitMinRun = 4;
     static constexpr size_t kSplitMaxScratch = 16u << 20;
@@ -415,46 +434,46 @@ private:
         const size_t part_bytes = (range + 255) & ~(size_t)255;
         const size_t n_subs = mp.n_subs();
         if (part_bytes * n_subs > kSplitMaxScratch || n_subs > 65535) return HOP_PARTIAL;
-        // partials, every step once, one table entry per sub-program: from one block
-        if (!ws_.reserve(part_bytes * n_subs + (prog.size() + 2 * n_subs) * sizeof(DevEntry) + 512))
-            return HOP_ERR_NOMEM;
+        // partials, then every sub-program as a record of equal length per pass: from one block
+        struct PassInfo { size_t records_at; int sub_entries, n_subs, depth; };
+        std::vector<PassInfo> passes(mp.n_passes, PassInfo{0, 2, 0, 1});
+        for (size_t g = 0; g < n_subs; ++g) {
+            PassInfo &pi = passes[(size_t)mp.height[g]];
+            pi.sub_entries = std::max(pi.sub_entries, (int)(mp.begin[g + 1] - mp.begin[g]) + 1);
+            pi.depth = std::max(pi.depth, (int)mp.depth[g]);
+            pi.n_subs++;
+        }
+        size_t n_blob = mp.top.size();
+        for (const PassInfo &pi : passes) {
+            if (pi.sub_entries > kMaxSubSteps + 1) return HOP_PARTIAL;
+            n_blob += (size_t)pi.sub_entries * (size_t)pi.n_subs;
+        }
+        if (!ws_.reserve(part_bytes * n_subs + n_blob * sizeof(DevEntry) + 512)) return HOP_ERR_NOMEM;
         char *partials = (char *)ws_.scratch(part_bytes * n_subs);
         if (!partials) return HOP_ERR_NOMEM;
         // Kernels address sources and results by the object's byte offset, so a partial that holds
         // only [b0, b1) is passed as base - b0. Passes run in stream order: pass h reads what
         // passes < h wrote.
-        // All passes' steps and sub-program tables, then the top program, travel in one copy.
-        struct PassInfo { size_t steps_at, subs_at; int n_subs, depth; };
-        std::vector<PassInfo> passes(mp.n_passes);
-        std::vector<DevEntry> blob;                     // SubLaunch and DevEntry are both 16 bytes
-        static_assert(sizeof(SubLaunch) == sizeof(DevEntry), "one staging array serves both");
-        blob.reserve(mp.steps.size() + n_subs + mp.top.size());
+        // All passes' records, then the top program, travel in one copy.
+        std::vector<DevEntry> blob;
+        blob.reserve(n_blob);
         for (int pass = 0; pass < mp.n_passes; ++pass) {
-            PassInfo &pi = passes[pass];
-            pi.steps_at = blob.size();
-            pi.depth = 1;
-            pi.n_subs = 0;
+            PassInfo &pi = passes[(size_t)pass];
+            pi.records_at = blob.size();
             for (size_t g = 0; g < n_subs; ++g) {
                 if (mp.height[g] != pass) continue;
-                const size_t sub_at = blob.size();
+                const size_t rec_at = blob.size();
+                SubHeader h;
+                h.dst = (void *)((uintptr_t)partials + g * part_bytes - b0);
+                h.n_entries = (uint32_t)(mp.begin[g + 1] - mp.begin[g]);
+                h.reserved = 0;
+                DevEntry raw;
+                std::memcpy(&raw, &h, sizeof raw);
+                blob.push_back(raw);
                 for (int32_t t = mp.begin[g]; t < mp.begin[g + 1]; ++t)
                     blob.push_back(resolve(mp.steps[(size_t)t], partials, part_bytes, b0));
-                mark_runs(blob.data() + sub_at, blob.size() - sub_at);
-                pi.depth = std::max(pi.depth, (int)mp.depth[g]);
-                pi.n_subs++;
-            }
-            pi.subs_at = blob.size();
-            uint32_t at = 0;
-            for (size_t g = 0; g < n_subs; ++g) {
-                if (mp.height[g] != pass) continue;
-                SubLaunch sl;
-                sl.entry_begin = at;
-                sl.n_entries = (uint32_t)(mp.begin[g + 1] - mp.begin[g]);
-                sl.dst = (void *)((uintptr_t)partials + g * part_bytes - b0);
-                at += sl.n_entries;
-                DevEntry raw;
-                std::memcpy(&raw, &sl, sizeof raw);
-                blob.push_back(raw);
+                mark_runs(blob.data() + rec_at + 1, blob.size() - rec_at - 1);
+                blob.resize(rec_at + (size_t)pi.sub_entries, DevEntry{nullptr, 0, 0});
             }
         }
         const size_t top_at = blob.size();
@@ -463,8 +482,8 @@ private:
         const DevEntry *dev = (const DevEntry *)ws_.stage_in_place(blob.data(), blob.size() * sizeof(DevEntry));
         if (!dev) return HOP_ERR_NOMEM;
         for (const PassInfo &pi : passes) {
-            if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.steps_at,
-                                   (const SubLaunch *)(dev + pi.subs_at), pi.n_subs, b0, b1) != hipSuccess)
+            if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.records_at, pi.sub_entries, pi.n_subs, b0,
+                                   b1) != hipSuccess)
                 return HOP_ERR_DEVICE;
         }
         hipError_t e = launch_reduce(stream_, dtype_, op_, mp.top_depth, blob.data() + top_at, dev + top_at,

@@ -207,6 +207,26 @@ typedef const DevEntry __attribute__((address_space(4))) *prog_ptr;
 // The broadcast's destination table is read the same way.
 typedef void *const __attribute__((address_space(4))) *table_ptr;
 
+// A sub-program record held by the lanes of a wave: lane 0 has the SubHeader, lane 1 + t step t
+// (the 16 bytes of a DevEntry as x = address low, y = address high, z = ctl). Reading a step is
+// three lane reads with a wave-uniform lane number, so the values land in SGPRs like those of a
+// scalar load.
+struct LaneStep {
+    const void *src;
+    uint32_t ctl;
+};
+struct LaneProg {
+    uint4 mine;
+    __device__ __forceinline__ static uint32_t from(uint32_t v, int lane) { return (uint32_t)__builtin_amdgcn_readlane((int)v, lane); }
+    __device__ __forceinline__ LaneStep operator[](int t) const
+    {
+        const uint64_t p = ((uint64_t)from(mine.y, t + 1) << 32) | from(mine.x, t + 1);
+        return {(const void *)(uintptr_t)p, from(mine.z, t + 1)};
+    }
+    __device__ __forceinline__ int n_entries() const { return (int)from(mine.z, 0); }
+    __device__ __forceinline__ void *dst() const { return (void *)(uintptr_t)(((uint64_t)from(mine.y, 0) << 32) | from(mine.x, 0)); }
+};
+
 // The addresses and control words of G consecutive program steps, held in SGPRs.
 template <int G> struct StepGroup {
     const void *src[G];
@@ -397,14 +417,16 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
 template <int DT, int OP, int D, int VPT, int U, int THREADS>
 __global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
 {
-    const prog_ptr prog = (prog_ptr)(uintptr_t)a.prog;
-    if (a.subs) {
-        // several independent sub-programs in one launch: blockIdx.y picks one
-        typedef const SubLaunch __attribute__((address_space(4))) *sub_ptr;
-        const sub_ptr sub = (sub_ptr)(uintptr_t)a.subs + blockIdx.y;
-        reduce_body<DT, OP, D, VPT, U, THREADS>(a, prog + sub->entry_begin, (int)sub->n_entries, sub->dst);
+    if (a.sub_entries > 0) {
+        // several independent sub-programs in one launch: blockIdx.y picks a record, lane i fetches
+        // its entry i (lanes past the record's end re-read its last entry), and the steps are then
+        // taken from the lanes
+        const int lane = (int)threadIdx.x < a.sub_entries ? (int)threadIdx.x : a.sub_entries - 1;
+        const uint4 *rec = (const uint4 *)a.prog + (size_t)blockIdx.y * (size_t)a.sub_entries;
+        const LaneProg lp{rec[lane]};
+        reduce_body<DT, OP, D, VPT, U, THREADS>(a, lp, lp.n_entries(), lp.dst());
     } else {
-        reduce_body<DT, OP, D, VPT, U, THREADS>(a, prog, a.n_entries, a.dst);
+        reduce_body<DT, OP, D, VPT, U, THREADS>(a, (prog_ptr)(uintptr_t)a.prog, a.n_entries, a.dst);
     }
 }
 

@@ -17,14 +17,19 @@ namespace hop {
 // path); longer ones are staged in device memory.
 constexpr int kInlineEntries = 128;
 
-// One of several sub-programs evaluated by a single launch (grid dimension y):
-// steps [entry_begin, entry_begin + n_entries) of the launch's program, result to dst.
-struct SubLaunch {
-    uint32_t entry_begin;
-    uint32_t n_entries;
-    void *dst;
+// Several independent sub-programs evaluated by a single launch (grid dimension y): the launch's
+// program memory holds gridDim.y records of sub_entries entries each, a SubHeader and then the
+// sub-program's steps (at most kMaxSubSteps, the rest of the record is padding). A workgroup
+// fetches its whole record with one vector load, lane i entry i, and takes the steps from
+// the lanes afterwards: one trip to the program's memory instead of one per group of steps, which
+// matters because these programs are read in place from pinned host memory.
+struct SubHeader {
+    void *dst;                 // where the sub-program's result goes
+    uint32_t n_entries;        // its number of steps
+    uint32_t reserved;
 };
-static_assert(sizeof(SubLaunch) == 16, "sub-launch descriptors are 16 bytes");
+static_assert(sizeof(SubHeader) == sizeof(DevEntry), "a header takes one entry");
+constexpr int kMaxSubSteps = 63;   // header + steps fit the 64 lanes of a wave
 
 struct ReduceArgs {
     const DevEntry *prog;      // device memory, n_entries steps (unused by the inline variant)
@@ -33,7 +38,7 @@ struct ReduceArgs {
     size_t byte_begin;         // first byte of the object range this launch covers
     size_t n_vec;              // full 16-byte vectors in the range
     int n_tail;                // elements after the last full vector (object end only)
-    const SubLaunch *subs;     // device table of gridDim.y sub-programs, or null (whole program -> dst)
+    int sub_entries;           // > 0: prog holds gridDim.y sub-program records of this many entries (see SubHeader)
     int piece_stride_log2;     // < 0: a workgroup's vectors are contiguous; s >= 0: its VPT pieces of one vector
                                // per lane lie 2^s pieces apart (see reduce_body)
     // segment launches only (reduce_kernel_seg): where accumulators live between segments
@@ -84,11 +89,11 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
                                  int n_entries, void *dst, char *spill, size_t level_stride, int n_restore,
                                  int n_save, size_t byte_begin, size_t byte_end);
 
-// The same for n_subs independent sub-programs at once: dev_subs[s] names the steps
-// (inside dev_prog) and the destination of sub-program s; every sub-program covers the
-// same byte range and needs at most `depth` accumulator levels.
-hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
-                              const SubLaunch *dev_subs, int n_subs, size_t byte_begin, size_t byte_end);
+// The same for n_subs independent sub-programs at once: dev_records holds n_subs records of
+// sub_entries entries (SubHeader, steps, padding; 2 <= sub_entries <= kMaxSubSteps + 1); every
+// sub-program covers the same byte range and needs at most `depth` accumulator levels.
+hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
+                              int sub_entries, int n_subs, size_t byte_begin, size_t byte_end);
 
 // Copy [byte_begin, byte_end) of src into the same range of every destination
 // of the device table dsts; with dsts == nullptr and n_dst == 1 into dst0.

@@ -75,7 +75,7 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     a.base.prog = dev_prog;
     a.base.n_entries = n_entries;
     a.base.dst = dst;
-    a.base.subs = nullptr;
+    a.base.sub_entries = 0;
     fill_range(a.base, dtype, byte_begin, byte_end);
     // shape by the amount of work, measured in 4 KiB tiles of the range
     const size_t tiles4k = (a.base.n_vec + 255) / 256;
@@ -118,7 +118,7 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
     a.prog = dev_prog;
     a.n_entries = n_entries;
     a.dst = dst;
-    a.subs = nullptr;
+    a.sub_entries = 0;
     fill_range(a, dtype, byte_begin, byte_end);
     a.spill = spill;
     a.level_stride = level_stride;
@@ -135,18 +135,19 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
     return hipGetLastError();
 }
 
-hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
-                              const SubLaunch *dev_subs, int n_subs, size_t byte_begin, size_t byte_end)
+hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
+                              int sub_entries, int n_subs, size_t byte_begin, size_t byte_end)
 {
     if (byte_end <= byte_begin || n_subs <= 0) return hipSuccess;
-    if (!dev_prog || !dev_subs || n_subs > 65535) return hipErrorInvalidValue;
+    if (!dev_records || n_subs > 65535 || sub_entries < 2 || sub_entries > kMaxSubSteps + 1) return hipErrorInvalidValue;
+    static_assert(kMaxSubSteps + 1 <= kThreads, "one lane per entry of a record");
     const Launcher l = pick(dtype, op, depth);
     ReduceArgs a;
-    a.prog = dev_prog;
+    a.prog = dev_records;
     a.n_entries = 0;
     a.dst = nullptr;
-    a.subs = dev_subs;
     fill_range(a, dtype, byte_begin, byte_end);
+    a.sub_entries = sub_entries;
     const unsigned grid = grid_for(a.n_vec, (size_t)kThreads);
     hipLaunchKernelGGL(l.dev_small, dim3(grid, (unsigned)n_subs), dim3(kThreads), 0, stream, a);
     return hipGetLastError();
