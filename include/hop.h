@@ -345,7 +345,11 @@ int hop_plan_slots(int k, int tree_degree, int32_t *node_of_slot);
 int hop_pick_degree(int k, size_t object_bytes, double latency_s, double bytes_per_s);
 
 /* Bytes of device scratch one hop_reduce / hop_allreduce call of this shape
- * takes from the library's cached workspace (programs, destination tables). */
+ * takes from the library's cached workspace (programs, destination tables).
+ * A call over 128 or more inputs of at most 1 MiB each (fp32, int32) is cut
+ * into sub-programs and takes, beyond this figure, one object-sized partial
+ * result per sub-program plus their programs, at most 16 MiB + 1 MiB in all;
+ * a cut that would need more is not made. */
 size_t hop_workspace_bytes(int n, int k, int n_dst);
 
 /* Frees the cached workspaces of the calling process (optional; for leak checks). */
