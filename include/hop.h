@@ -130,7 +130,9 @@ int hop_reduce(void *dst, const void *const *objs, int n, size_t object_bytes,
  * copy of the object, moved chunk by chunk.
  *   dsts   host array of n_dst device pointers (object_bytes each); n_dst >= 0.
  *   src    device pointer, object_bytes bytes.
- * The source is read once per chunk and written to every destination.
+ * The source is fetched from device memory once and written to every
+ * destination (with several destinations it is re-read per destination from
+ * the on-chip caches).
  * Errors: HOP_ERR_INVALID (n_dst < 0, NULL table or entry, chunk_bytes 0 or
  * not a multiple of 16, destinations overlapping the source or each other),
  * HOP_ERR_ALIGN, HOP_ERR_DEVICE/NOMEM.
