@@ -311,6 +311,35 @@ def test_broadcast_over_several_spans_with_a_ragged_end():
             assert torch.equal(o[:nbytes], s) and int(o[nbytes:].sum()) == 0, (nbytes, n_dst)
 
 
+def test_copies_see_what_was_written_just_before():
+    # the copy to several destinations reads its source through the caches, and reads it again per
+    # destination: a source rewritten between two calls (by the reduce kernel, by another library) must come
+    # out new, in every destination, every time
+    d = dev()
+    E = (4 << 20) + 1024 + 12
+    dsts = [torch.zeros(E, dtype=torch.int32, device=d) for _ in range(5)]
+    objs = [torch.zeros(E, dtype=torch.int32, device=d) for _ in range(8)]
+    g = torch.Generator(device=d)
+    g.manual_seed(99)
+    for rnd in range(4):
+        for o in objs:
+            o.random_(-1000, 1000, generator=g)
+        rc, _ = hop.hop_allreduce(dsts, objs, 8, "sum", "i32", 1 << 20, 2, None, None)
+        assert rc == hop.HOP_OK
+        want = torch.zeros_like(objs[0])
+        for o in objs:
+            want += o
+        for t in dsts:
+            assert torch.equal(t, want), rnd
+    src = torch.zeros(E, dtype=torch.int32, device=d)
+    outs = [torch.zeros(E, dtype=torch.int32, device=d) for _ in range(6)]
+    for rnd in range(4):
+        src.random_(-1000, 1000, generator=g)
+        assert hop.hop_broadcast(outs, src, 1 << 20) == hop.HOP_OK
+        for t in outs:
+            assert torch.equal(t, src), rnd
+
+
 def test_receiver_driven_broadcast_chains_and_survives_a_lost_copy():
     d = dev()
     rng = np.random.default_rng(21)
