@@ -290,7 +290,10 @@ public:
     GpuBackend(int device, hipStream_t stream, const void *const *objs, int n, std::vector<void *> dsts,
                const Shape &shape, int op, int dtype, int k, int64_t degree)
         : ws_(device, stream), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
-          op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device) {}
+          op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device)
+    {
+        if (dsts_.size() > 1) extra_residue_ = common_residue(dsts_.data() + 1, (int)dsts_.size() - 1);
+    }
 
     ~GpuBackend() override
     {
@@ -340,7 +343,7 @@ private:
             if (rc != HOP_PARTIAL) {                // HOP_PARTIAL here = "not splittable, use the plain path"
                 if (rc < 0) return rc;
                 hipError_t ec = hipSuccess;
-                if (dsts_.size() > 1) ec = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1);
+                if (dsts_.size() > 1) ec = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
                 return ec == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
             }
         }
@@ -366,7 +369,7 @@ private:
         hipError_t e = launch_reduce(stream_, dtype_, op_, depth_, staging_.data(), dev_prog_, (int)prog.size(),
                                      dsts_[0], b0, b1);
         if (e == hipSuccess && dsts_.size() > 1)
-            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1);
+            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     }
 
@@ -406,7 +409,7 @@ private:
                 dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
                 if (!dev_extra_) return HOP_ERR_NOMEM;
             }
-            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1);
+            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
         }
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     }
@@ -511,6 +514,7 @@ private:
     std::vector<DevEntry> staging_;
     const DevEntry *dev_prog_ = nullptr;
     void *const *dev_extra_ = nullptr;
+    unsigned extra_residue_ = 0;                // address modulo 128 shared by (most of) the other destinations
     uint64_t dev_version_ = 0;
     int depth_ = 1;
     int device_;
@@ -771,7 +775,7 @@ int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_b
         void *const *table = (void *const *)ws.stage(dsts, (size_t)n_dst * sizeof(void *));
         if (!table) return HOP_ERR_NOMEM;
         // The whole source is present, so every chunk is ready at once: one launch covers them all.
-        hipError_t e = launch_copy((hipStream_t)stream, src, table, n_dst, 0, object_bytes);
+        hipError_t e = launch_copy((hipStream_t)stream, src, table, n_dst, 0, object_bytes, nullptr, common_residue(dsts, n_dst));
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;

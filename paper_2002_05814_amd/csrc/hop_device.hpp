@@ -322,11 +322,15 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
     // wave's loads in flight then lie 2^s pieces apart instead of side by side, and consecutive
     // workgroups still cover consecutive pieces.
     const int sl = a.piece_stride_log2;
-    const size_t n_tiles = sl < 0 ? (a.n_vec + kTile - 1) / kTile : ((a.n_vec + (kTile << sl) - 1) / (kTile << sl)) << sl;
+    // The grid of vectors starts lead vectors before the range (the host picks lead so that it starts
+    // where the sources are 128-byte aligned: a wave's 1 KiB load then covers 8 whole lines instead of
+    // parts of 9, which is worth 10 points of bandwidth for sources that are only 16-byte aligned).
+    const size_t lead = (size_t)a.lead_vecs, n_all = a.n_vec + lead;
+    const size_t n_tiles = sl < 0 ? (n_all + kTile - 1) / kTile : ((n_all + (kTile << sl) - 1) / (kTile << sl)) << sl;
 
     for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        // lanes past the end of the range re-read the last vector (always inside the
-        // range) and skip the store, so control flow stays uniform across the wave
+        // lanes in front of the range or past its end re-read its first or last vector (always
+        // inside the range) and skip the store, so control flow stays uniform across the wave
         size_t off[VPT];
         bool live[VPT];
         size_t first = tile * kTile, step = THREADS;     // vector index of piece 0, distance between pieces
@@ -334,13 +338,13 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
             const size_t r = tile & (((size_t)1 << sl) - 1);
             first = (((tile >> sl) * VPT) << sl) * THREADS + r * THREADS;
             step = (size_t)THREADS << sl;
-            if (first >= a.n_vec) continue;               // a workgroup of the last group with nothing to do
+            if (first >= n_all) continue;                 // a workgroup of the last group with nothing to do
         }
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
             const size_t v = first + (size_t)j * step + threadIdx.x;
-            live[j] = v < a.n_vec;
-            off[j] = a.byte_begin + (live[j] ? v : a.n_vec - 1) * 16;
+            live[j] = v >= lead && v < n_all;
+            off[j] = a.byte_begin + ((live[j] ? v : v < lead ? lead : n_all - 1) - lead) * 16;
         }
         Machine<DT, OP, D, VPT * W> m;
         if (SEG) {
@@ -452,7 +456,11 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
     constexpr size_t kTile = (size_t)THREADS * VPT;
     // the vectors of a workgroup: contiguous, or VPT pieces 2^s pieces apart (as in reduce_body)
     const int sl = a.piece_stride_log2;
-    const size_t n_tiles = sl < 0 ? (a.n_vec + kTile - 1) / kTile : ((a.n_vec + (kTile << sl) - 1) / (kTile << sl)) << sl;
+    // the grid of vectors starts lead vectors before the range, at a 128-byte boundary of the
+    // destination: stores of whole lines (a destination that is only 16-byte aligned otherwise
+    // costs a tenth of the bandwidth here and a third in the fan-out kernel)
+    const size_t lead = (size_t)a.lead_vecs, n_all = a.n_vec + lead;
+    const size_t n_tiles = sl < 0 ? (n_all + kTile - 1) / kTile : ((n_all + (kTile << sl) - 1) / (kTile << sl)) << sl;
     const table_ptr dsts = (table_ptr)(uintptr_t)a.dsts;
     for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         uint4 x[VPT];
@@ -463,13 +471,13 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
             const size_t r = tile & (((size_t)1 << sl) - 1);
             first = (((tile >> sl) * VPT) << sl) * THREADS + r * THREADS;
             step = (size_t)THREADS << sl;
-            if (first >= a.n_vec) continue;
+            if (first >= n_all) continue;
         }
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
             const size_t v = first + (size_t)j * step + threadIdx.x;
-            live[j] = v < a.n_vec;
-            off[j] = a.byte_begin + (live[j] ? v : a.n_vec - 1) * 16;
+            live[j] = v >= lead && v < n_all;
+            off[j] = a.byte_begin + ((live[j] ? v : v < lead ? lead : n_all - 1) - lead) * 16;
             x[j] = ld16(a.src, off[j]);
         }
         for (int d = 0; d < a.n_dst; ++d) {
@@ -506,11 +514,12 @@ __global__ __launch_bounds__(THREADS) void fanout_kernel(CopyArgs a)
     const unsigned ts = rest < a.span_tiles ? rest : a.span_tiles;      // tiles in this span
     const unsigned d = r / ts, tile = first + (r - d * ts);
     void *dst = dsts[d];
+    const size_t lead = (size_t)a.lead_vecs, n_all = a.n_vec + lead;    // as in copy_kernel
 #pragma unroll
     for (int j = 0; j < VPT; ++j) {
         const size_t v = tile * kTile + (size_t)j * THREADS + threadIdx.x;
-        if (v < a.n_vec) {
-            const size_t off = a.byte_begin + v * 16;
+        if (v >= lead && v < n_all) {
+            const size_t off = a.byte_begin + (v - lead) * 16;
             const u32x4 x = *(const u32x4 *)((const char *)a.src + off);
             __builtin_nontemporal_store(x, (u32x4 *)((char *)dst + off));
         }

@@ -39,6 +39,8 @@ struct ReduceArgs {
     size_t n_vec;              // full 16-byte vectors in the range
     int n_tail;                // elements after the last full vector (object end only)
     int sub_entries;           // > 0: prog holds gridDim.y sub-program records of this many entries (see SubHeader)
+    int lead_vecs;             // the workgroups' grid of vectors starts this many vectors before byte_begin, where
+                               // the sources are 128-byte aligned; the vectors in front of the range are skipped
     int piece_stride_log2;     // < 0: a workgroup's vectors are contiguous; s >= 0: its VPT pieces of one vector
                                // per lane lie 2^s pieces apart (see reduce_body)
     // segment launches only (reduce_kernel_seg): where accumulators live between segments
@@ -63,6 +65,8 @@ struct CopyArgs {
     size_t n_vec;
     int n_tail_bytes;
     int piece_stride_log2;     // copy kernel only: < 0 contiguous vectors per workgroup, else pieces 2^s apart
+    int lead_vecs;             // the grid of vectors starts this many vectors before byte_begin, where the
+                               // destinations are 128-byte aligned; vectors in front of the range are skipped
     unsigned n_tiles;          // fan-out kernel only: tiles in this launch
     unsigned span_tiles;       // fan-out kernel only: tiles per span
 };
@@ -97,7 +101,20 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
 
 // Copy [byte_begin, byte_end) of src into the same range of every destination
 // of the device table dsts; with dsts == nullptr and n_dst == 1 into dst0.
+// dst_residue: address modulo 128 of the table's destinations (of most of them, if they
+// differ; see common_residue), used to start the stores at whole lines; dst0's own otherwise.
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
-                       size_t byte_begin, size_t byte_end, void *dst0 = nullptr);
+                       size_t byte_begin, size_t byte_end, void *dst0 = nullptr, unsigned dst_residue = 0);
+
+// The address modulo 128 that most of n (16-byte aligned) host-visible pointers share.
+inline unsigned common_residue(void *const *p, int n)
+{
+    int count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < n; ++i) count[((uintptr_t)p[i] >> 4) & 7]++;
+    int best = 0;
+    for (int r = 1; r < 8; ++r)
+        if (count[r] > count[best]) best = r;
+    return (unsigned)best * 16;
+}
 
 }  // namespace hop

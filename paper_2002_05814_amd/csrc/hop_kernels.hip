@@ -37,7 +37,8 @@ const char *kernel_config()
            "tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart; from 2048: 1 KiB "
            "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 4096 tiles; bf16 at "
            "depth 5..8 from 4096 tiles: 1 KiB tiles, unroll 8, 10 waves per CU; groups of 8 plain steps marked by the host; "
-           "nontemporal loads+stores, programs <= 128 steps in kernel arguments; "
+           "nontemporal loads+stores, programs <= 128 steps in kernel arguments; vector grids start at a 128-byte boundary of "
+           "the sources (reduce) or destinations (copies); "
            "copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from 5120 8-KiB tiles 4 vectors/lane in "
            "1 KiB pieces 64 KiB apart, 10 waves per CU; nontemporal; "
            "to several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 tiles, "
@@ -63,6 +64,19 @@ static void fill_range(ReduceArgs &a, int dtype, size_t byte_begin, size_t byte_
     a.n_vec = (byte_end - byte_begin) / 16;
     a.n_tail = (int)(((byte_end - byte_begin) % 16) / elem_bytes(dtype));
     a.piece_stride_log2 = -1;
+    a.lead_vecs = 0;
+}
+
+// Vectors between the last 128-byte boundary of the sources and the start of the range: the residue
+// most of the program's sources share (objects from one allocator usually share it).
+static int lead_vectors(const DevEntry *host_steps, int n_entries, size_t byte_begin)
+{
+    int count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < n_entries; ++i) count[(((uintptr_t)host_steps[i].src + byte_begin) >> 4) & 7]++;
+    int best = 0;
+    for (int r = 1; r < 8; ++r)
+        if (count[r] > count[best]) best = r;
+    return best;
 }
 
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
@@ -77,6 +91,7 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     a.base.dst = dst;
     a.base.sub_entries = 0;
     fill_range(a.base, dtype, byte_begin, byte_end);
+    if (host_steps && a.base.n_vec > 0) a.base.lead_vecs = lead_vectors(host_steps, n_entries, byte_begin);
     // shape by the amount of work, measured in 4 KiB tiles of the range
     const size_t tiles4k = (a.base.n_vec + 255) / 256;
     // bf16 with 5..8 accumulator levels is bound by its unpacking arithmetic at 2 vectors per lane
@@ -91,8 +106,9 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     const int stride_log2 = vpt < 2 ? -1 : shape == 2 ? kPieceStrideLog2 : shape == 1 ? kMidPieceStrideLog2 : -1;
     a.base.piece_stride_log2 = stride_log2;
     // strided: whole groups of (vpt << stride) pieces, one workgroup per 2^stride-th of a group
-    const unsigned grid = stride_log2 < 0 ? grid_for(a.base.n_vec, (size_t)kThreads * vpt)
-                                          : grid_for(a.base.n_vec, ((size_t)kThreads * vpt) << stride_log2) << stride_log2;
+    const size_t n_all = a.base.n_vec + (size_t)a.base.lead_vecs;
+    const unsigned grid = stride_log2 < 0 ? grid_for(n_all, (size_t)kThreads * vpt)
+                                          : grid_for(n_all, ((size_t)kThreads * vpt) << stride_log2) << stride_log2;
     if (n_entries <= kInlineEntries) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
         hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), lds,
@@ -183,8 +199,9 @@ constexpr size_t kFanoutLongBytes = (size_t)128 << 20;
 static_assert(kFanoutSpanTiles % 8 == 0, "a tile must meet the same XCD for every destination");
 
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
-                       size_t byte_begin, size_t byte_end, void *dst0)
+                       size_t byte_begin, size_t byte_end, void *dst0, unsigned dst_residue)
 {
+    if (dst0) dst_residue = (unsigned)((uintptr_t)dst0 & 127);
     if (byte_end <= byte_begin || n_dst <= 0) return hipSuccess;
     if (!dsts && (n_dst != 1 || !dst0)) return hipErrorInvalidValue;
     CopyArgs a;
@@ -198,13 +215,17 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
     a.n_tiles = 0;
     a.span_tiles = 0;
     a.piece_stride_log2 = -1;
+    // where the destinations (most of them) are 128-byte aligned; the table is in device memory, so
+    // the caller passes the residue it saw when it built the table
+    a.lead_vecs = a.n_vec > 0 ? (int)((((uintptr_t)dst_residue + byte_begin) >> 4) & 7) : 0;
     if (n_dst >= 2 && n_dst <= kFanoutMaxDst) {
         // whole spans per launch, as many as keep the grid below kFanoutMaxBlocks (one launch
         // unless the copy is enormous); the bytes beyond the last whole vector go with the last
         constexpr size_t kTileVecs = (size_t)kThreads * kFanoutVpt;
-        const size_t tiles = (a.n_vec + kTileVecs - 1) / kTileVecs;
         const size_t spans_per_launch = kFanoutMaxBlocks / ((size_t)kFanoutSpanTiles * (size_t)n_dst);
         const size_t tiles_per_launch = spans_per_launch * kFanoutSpanTiles;
+        if ((a.n_vec + 8 + kTileVecs - 1) / kTileVecs > tiles_per_launch) a.lead_vecs = 0;    // several launches: plain grid
+        const size_t tiles = (a.n_vec + (size_t)a.lead_vecs + kTileVecs - 1) / kTileVecs;
         a.span_tiles = kFanoutSpanTiles;
         const unsigned lds = (n_dst < kFanoutFewDst && byte_end - byte_begin >= kFanoutLongBytes) ? 0 : kFanoutLdsBytes;
         size_t done = 0;
@@ -213,7 +234,7 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
             const bool last = done + now == tiles;
             CopyArgs part = a;
             part.byte_begin = byte_begin + done * kTileVecs * 16;
-            part.n_vec = last ? a.n_vec - done * kTileVecs : now * kTileVecs;
+            part.n_vec = last ? a.n_vec + (size_t)a.lead_vecs - done * kTileVecs - (size_t)part.lead_vecs : now * kTileVecs;
             part.n_tail_bytes = last ? a.n_tail_bytes : 0;
             part.n_tiles = (unsigned)now;
             const size_t grid = (now < 1 ? 1 : now) * (size_t)n_dst;     // one workgroup at least, for the tail bytes
@@ -223,12 +244,13 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
         } while (done < tiles);
         return hipGetLastError();
     }
-    const unsigned grid = grid_for(a.n_vec, (size_t)kThreads * kCopyVpt);
+    const size_t n_all = a.n_vec + (size_t)a.lead_vecs;
+    const unsigned grid = grid_for(n_all, (size_t)kThreads * kCopyVpt);
     if (grid >= kCopyCapTiles) {
         // long copies, like long reduces, run faster with few resident waves and with a wave's
         // vectors apart (256 MiB one-to-one: 77 % -> 84 % of the HBM peak)
         a.piece_stride_log2 = kPieceStrideLog2;
-        const unsigned g = grid_for(a.n_vec, ((size_t)kThreads * kLongCopyVpt) << kPieceStrideLog2) << kPieceStrideLog2;
+        const unsigned g = grid_for(n_all, ((size_t)kThreads * kLongCopyVpt) << kPieceStrideLog2) << kPieceStrideLog2;
         hipLaunchKernelGGL((copy_kernel<kLongCopyVpt, kThreads>), dim3(g), dim3(kThreads), kCopyLdsBytes, stream, a);
     } else {
         hipLaunchKernelGGL((copy_kernel<kCopyVpt, kThreads>), dim3(grid), dim3(kThreads), 0, stream, a);

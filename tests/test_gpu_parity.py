@@ -311,6 +311,27 @@ def test_broadcast_over_several_spans_with_a_ragged_end():
             assert torch.equal(o[:nbytes], s) and int(o[nbytes:].sum()) == 0, (nbytes, n_dst)
 
 
+@pytest.mark.parametrize("nbytes,n_dst", [((41 << 20) + 5 * 1024 + 21, 1), ((17 << 20) + 333, 3), (70001, 4), (100, 2), (9, 3)])
+def test_broadcast_to_destinations_that_are_only_16_byte_aligned(nbytes, n_dst):
+    # destinations 16..112 bytes past a 128-byte boundary (the copy kernels start their stores at a boundary
+    # of most destinations and skip what lies in front), the source 32 bytes past one
+    d = dev()
+    rng = np.random.default_rng(nbytes)
+    slot = (nbytes + 1023) // 1024 * 1024 + 1024
+    pool = torch.zeros((n_dst + 1) * slot, dtype=torch.uint8, device=d)
+    assert pool.data_ptr() % 128 == 0
+    src = pool[32:32 + nbytes]
+    src.copy_(torch.from_numpy(rng.integers(1, 256, size=nbytes, dtype=np.uint8)).to(d))
+    res = [16, 16, 80, 112][:n_dst]
+    outs = [pool[(j + 1) * slot + res[j]:(j + 1) * slot + res[j] + nbytes] for j in range(n_dst)]
+    assert hop.hop_broadcast(outs, src, 1 << 20, object_bytes=nbytes) == hop.HOP_OK
+    torch.cuda.synchronize()
+    for j, o in enumerate(outs):
+        assert torch.equal(o, src), j
+        lo = (j + 1) * slot
+        assert int(pool[lo:lo + res[j]].sum()) == 0 and int(pool[lo + res[j] + nbytes:lo + slot].sum()) == 0, j
+
+
 def test_copies_see_what_was_written_just_before():
     # the copy to several destinations reads its source through the caches, and reads it again per
     # destination: a source rewritten between two calls (by the reduce kernel, by another library) must come
@@ -784,6 +805,65 @@ def test_every_launch_shape_against_sampled_oracle(dtype, n, k, d, delta, mib, d
                 mag += o.double().abs()
             tol = 1e-5 * np.log2(k) if dtype == "f32" else 1e-2
             assert bool(((dst.double() - ref).abs() <= tol * torch.maximum(ref.abs(), mag / k)).all())
+
+
+@pytest.mark.parametrize("dtype,mib,residues", [("f32", 2, (16,)), ("f32", 6, (16,)), ("f32", 12, (80,)), ("i32", 20, (112,)),
+                                                ("bf16", 20, (16,)), ("f32", 9, (0, 16, 32, 48, 64, 80, 96, 112))])
+def test_sources_that_are_only_16_byte_aligned(dtype, mib, residues):
+    # objects carved from one buffer so that they start 16..112 bytes past a 128-byte boundary (all alike, or
+    # every object differently), the result 48 bytes past one: the kernels start their grid of vectors at a
+    # boundary of the sources and skip what lies in front of the range
+    d = dev()
+    n, k, deg = 6, 5, 2
+    nbytes = mib * (1 << 20) + 5 * 1024 + 3 * 16 - ES[dtype]
+    chunk = 1 << 20
+    w = workloads.Workload("unaligned_%s_%d" % (dtype, mib), n=n, dtype=dtype, object_bytes=nbytes, chunk_bytes=chunk,
+                           k=k, tree_degree=deg, ops=("sum",), order_seed=77 + mib, data_seed=88 + mib,
+                           dist={"f32": "normal_std1", "bf16": "normal_std1", "i32": "randint_pm2p20"}[dtype])
+    aligned = workloads.make_objects(w, device=d)
+    E, es = w.n_elems, ES[dtype]
+    slot = (nbytes + 1023) // 1024 * 1024 + 1024
+    pool = torch.zeros((n + 1) * slot // es, dtype=aligned[0].dtype, device=d)
+    assert pool.data_ptr() % 128 == 0
+    objs = []
+    for i, a in enumerate(aligned):
+        at = (i * slot + residues[i % len(residues)]) // es
+        pool[at:at + E].copy_(a)
+        objs.append(pool[at:at + E])
+        assert objs[-1].data_ptr() % 128 == residues[i % len(residues)]
+    at = (n * slot + 48) // es
+    dst = pool[at:at + E]
+    sel = [objs[i] for i in w.ready_order()[:k]]
+    for op in ("sum", "max"):
+        dst.fill_(7)
+        rc, info = hop.hop_reduce(dst, objs, k, op, dtype, chunk, deg, w.ready_order(), None)
+        torch.cuda.synchronize()
+        assert rc == hop.HOP_OK
+        sampled_oracle_check(w, op, objs, [dst], rc, info, np.random.default_rng(mib), per_chunk=16)
+        head = slice(0, 40)
+        _, want, _, _ = oracle.reduce([workloads.to_numpy(o[head]) for o in objs], k, ORA_OP[op], ORA_DT[dtype], 40, deg,
+                                      w.ready_order(), None)
+        assert np.array_equal(bits(workloads.to_numpy(dst[head])), bits(want))
+        if op == "max":
+            ref = sel[0].clone()
+            for o in sel[1:]:
+                ref = torch.maximum(ref, o)
+            assert torch.equal(dst, ref)
+        elif dtype == "i32":
+            ref = torch.zeros_like(sel[0])
+            for o in sel:
+                ref += o
+            assert torch.equal(dst, ref)
+        else:
+            ref = torch.zeros(E, dtype=torch.float64, device=d)
+            mag = torch.zeros(E, dtype=torch.float64, device=d)
+            for o in sel:
+                ref += o.double()
+                mag += o.double().abs()
+            tol = 1e-5 * np.log2(k) if dtype == "f32" else 1e-2
+            assert bool(((dst.double() - ref).abs() <= tol * torch.maximum(ref.abs(), mag / k)).all())
+    # nothing outside the result was written: the bytes around it are still zero
+    assert int(pool[at - 12:at].abs().sum()) == 0 and int(pool[at + E:at + E + 12].abs().sum()) == 0
 
 
 def test_cfg2_full_size_sampled():
