@@ -191,6 +191,25 @@ def test_infinities_and_nans_come_out_as_in_the_oracle():
     rc, _ = hop.hop_reduce(dst, objs[3:4], 1, "sum", "f32", 256, 2, None, None)
     torch.cuda.synchronize()
     assert rc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(vals[3]))
+    # bf16: the same cases as 16-bit patterns, plus sums that overflow to infinity and a sum whose fp32
+    # value rounds up into the next bf16 binade at the one final rounding
+    b = [np.zeros(E, np.uint16) for _ in range(4)]
+    b[0][0], b[1][0] = 0x7f80, 0xff80                      # inf + -inf
+    b[0][1], b[2][1] = 0x7f80, 0x3f80                      # inf + 1
+    b[1][2], b[2][2] = 0x7fc1, 0x4000                      # quiet NaN with a payload + 2
+    b[3][3], b[0][3] = 0x7f81, 0x3f80                      # signalling NaN + 1
+    b[2][5] = 0x7f81                                       # signalling NaN + zeros
+    b[0][6], b[1][6], b[2][6] = 0x7f7f, 0x7f7f, 0x7f7f     # three times the largest finite value
+    b[0][7], b[1][7] = 0x3fff, 0x3b80                      # 1.9921875 + 2^-8: a tie at bf16 precision
+    bobjs = [workloads.from_numpy(x, "bf16", d) for x in b]
+    for op in ("sum", "max", "min"):
+        for deg in (1, 2, 4):
+            dst = torch.zeros(E, dtype=torch.bfloat16, device=d)
+            rc, info = hop.hop_reduce(dst, bobjs, 4, op, "bf16", 128, deg, None, None)
+            torch.cuda.synchronize()
+            orc, want, _, _ = oracle.reduce(b, 4, ORA_OP[op], oracle.BF16, 64, deg, None, None)
+            assert rc == orc == hop.HOP_OK
+            assert np.array_equal(workloads.to_numpy(dst), want), (op, deg)
 
 
 def test_denormals_and_signed_zeros_are_preserved():
