@@ -5,8 +5,8 @@
 // The reduce is the elementwise ReduceOp of the paper's Table 1 applied in the
 // order fixed by the reduce tree of section 3.4.2; the copy is the data
 // movement of the broadcast of section 3.4.1. Both are pure streaming work:
-// every input byte is read once with 128-bit loads, nothing is staged through
-// LDS and no matrix unit is involved.
+// every input byte comes from HBM once, with 128-bit loads, nothing is staged
+// through LDS and no matrix unit is involved.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
