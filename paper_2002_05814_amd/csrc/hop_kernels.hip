@@ -36,7 +36,7 @@ const char *kernel_config()
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB tiles: 1 KiB "
            "tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart; from 2048: 1 KiB "
            "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 4096 tiles; bf16 at "
-           "depth 5..8 from 4096 tiles: 1 KiB tiles, unroll 8, 10 waves per CU; groups of 8 plain steps marked by the host; "
+           "depth 5..8 from 768 tiles: 2 vectors/lane, unroll 2 (pieces 64 KiB apart from 2048 tiles); groups of 8 plain steps marked by the host; "
            "nontemporal loads+stores, programs <= 128 steps in kernel arguments; vector grids start at a 128-byte boundary of "
            "the sources (reduce) or destinations (copies); "
            "copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from 5120 8-KiB tiles 4 vectors/lane in "
@@ -94,16 +94,17 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     if (host_steps && a.base.n_vec > 0) a.base.lead_vecs = lead_vectors(host_steps, n_entries, byte_begin);
     // shape by the amount of work, measured in 4 KiB tiles of the range
     const size_t tiles4k = (a.base.n_vec + 255) / 256;
-    // bf16 with 5..8 accumulator levels is bound by its unpacking arithmetic at 2 vectors per lane
-    // (64 inputs in a binary tree: 56 % of the HBM peak at any size); one vector per lane with 8
-    // sources in flight keeps it at 77-80 %
-    const bool deep_bf16 = dtype == HOP_BF16 && depth > 4 && depth <= kStreamMaxDepth && tiles4k >= kCapLaunchTiles;
-    const int shape = (tiles4k < kSmallLaunchTiles || deep_bf16) ? 0 : tiles4k < kMidLaunchTiles ? 1 : 2;
+    // bf16 with 5..8 accumulator levels (2 vectors per lane) needs more loads in flight than one
+    // source at a time gives it: two sources in flight, the pieces 64 KiB apart, no cap (64 inputs of
+    // 32 MiB in a binary tree: 81 % of the HBM peak, against 59-63 % for one source at a time and
+    // 70-79 %, depending on how the objects lie, for 1 KiB tiles with 8 sources in flight)
+    const bool deep_bf16 = dtype == HOP_BF16 && depth > 4 && depth <= kDeepBf16MaxDepth;
+    const int shape = tiles4k < kSmallLaunchTiles ? 0 : (tiles4k < kMidLaunchTiles || deep_bf16) ? 1 : 2;
     const int vpt = shape == 0 ? 1 : shape == 1 ? (l.vpt < kMidVecs ? l.vpt : kMidVecs) : l.vpt;
     // LDS the kernels never touch: it only caps the number of resident waves per compute unit
-    const unsigned lds = deep_bf16 ? kStreamLdsBytes
-                         : (shape == 2 && vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
-    const int stride_log2 = vpt < 2 ? -1 : shape == 2 ? kPieceStrideLog2 : shape == 1 ? kMidPieceStrideLog2 : -1;
+    const unsigned lds = (shape == 2 && vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
+    const int stride_log2 = vpt < 2 ? -1 : (shape == 2 || tiles4k >= kMidLaunchTiles) ? kPieceStrideLog2
+                            : shape == 1 ? kMidPieceStrideLog2 : -1;
     a.base.piece_stride_log2 = stride_log2;
     // strided: whole groups of (vpt << stride) pieces, one workgroup per 2^stride-th of a group
     const size_t n_all = a.base.n_vec + (size_t)a.base.lead_vecs;

@@ -51,16 +51,12 @@ constexpr int kPieceStrideLog2 = 6;           // up to 4 KiB per wave: the piece
 // one round of uncapped waves and a cap would split it in two.
 constexpr size_t kCapLaunchTiles = 4096;      // 4 KiB tiles; below: uncapped
 constexpr int kLargeWavesPerCU = 8;
-// bf16 with 5..8 accumulator levels (1 vector per lane at best in the 4 KiB shape) runs 1 KiB tiles
-// with 8 sources in flight at 10 waves per CU instead.
-constexpr int kStreamMaxDepth = 8;
-constexpr int kStreamWavesPerCU = 10;
+// bf16 with 5..8 accumulator levels keeps the 2 KiB shape (two sources in flight) at every size.
+constexpr int kDeepBf16MaxDepth = 8;
 constexpr unsigned kLdsBytesPerCU = 160 * 1024;
-constexpr unsigned kStreamLdsBytes = kLdsBytesPerCU / kStreamWavesPerCU / 256 * 256;   // per workgroup
-constexpr unsigned kLargeLdsBytes = kLdsBytesPerCU / kLargeWavesPerCU / 256 * 256;
-static_assert(kLdsBytesPerCU / kStreamLdsBytes == kStreamWavesPerCU, "cap must come out as intended");
+constexpr unsigned kLargeLdsBytes = kLdsBytesPerCU / kLargeWavesPerCU / 256 * 256;      // per workgroup
 static_assert(kLdsBytesPerCU / kLargeLdsBytes == kLargeWavesPerCU, "cap must come out as intended");
-static_assert(kStreamLdsBytes <= 64 * 1024 && kLargeLdsBytes <= 64 * 1024, "needs no opt-in for large dynamic LDS");
+static_assert(kLargeLdsBytes <= 64 * 1024, "needs no opt-in for large dynamic LDS");
 
 // W = accumulators per 16-byte vector (4 for 32-bit elements, 8 for bf16)
 // bf16 (W = 8) steps down one notch earlier than the 32-bit types: at equal accumulator count its

@@ -775,7 +775,8 @@ LAUNCH_SHAPE_CASES = [
     ("i32", 6, 6, 2, BEYOND, 17, "randint_pm2p20"),  # the same, a few KiB into the last group
     ("f32", 5, 4, 1, SHORT, 52, "normal_std1"),      # a chain over 52 MiB objects
     ("bf16", 6, 6, 6, SHORT, 50, "normal_std1"),     # bf16 at depth 1..2, four pieces
-    ("bf16", 40, 40, 2, SHORT, 17, "normal_std1"),   # bf16 binary tree (5 levels): 1 KiB tiles, 8 in flight, from 16 MiB
+    ("bf16", 40, 40, 2, SHORT, 17, "normal_std1"),   # bf16 binary tree (5 levels): two pieces, two sources in flight
+    ("bf16", 40, 40, 2, BEYOND, 5, "normal_std1"),   # the same below 8 MiB: pieces 16 KiB apart
     ("bf16", 12, 12, 4, SHORT, 20, "normal_std1"),   # bf16 at depth 2
     ("bf16", 16, 16, 2, BEYOND, 9, "normal_std1"),   # bf16 at depth 3..4: two pieces per workgroup, 64 KiB apart
     ("f32", 40, 40, 2, SHORT, 49, "normal_std1"),    # fp32 binary tree (5 levels)
