@@ -35,7 +35,7 @@ const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB tiles: 1 KiB "
            "tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart; from 2048: 1 KiB "
-           "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 4096 tiles; bf16 at "
+           "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 5120 tiles; bf16 at "
            "depth 5..8 from 768 tiles: 2 vectors/lane, unroll 2 (pieces 64 KiB apart from 2048 tiles); groups of 8 plain steps marked by the host; "
            "nontemporal loads+stores, programs <= 128 steps in kernel arguments; vector grids start at a 128-byte boundary of "
            "the sources (reduce) or destinations (copies); "

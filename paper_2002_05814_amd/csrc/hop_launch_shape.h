@@ -45,11 +45,12 @@ constexpr int kPieceStrideLog2 = 6;           // up to 4 KiB per wave: the piece
 // few waves in flight per compute unit; kernels that need few registers otherwise fill a CU with
 // 20+ waves and lose 5-10 points of bandwidth. The cap is an LDS allocation per workgroup that the
 // kernels never touch. It applies to the kernels that hold 4 vectors per lane (shallow accumulator
-// stacks), from 16 MiB per object: 8 waves per CU (7 is a little faster for some shapes and much slower
+// stacks), from 20 MiB per object: 8 waves per CU (7 is a little faster for some shapes and much slower
 // for others, 10 and 12 lose 2-3 points); those with fewer vectors already hold few waves through
-// their register use, and capping them further only costs (measured). Below 16 MiB a launch fits in
-// one round of uncapped waves and a cap would split it in two.
-constexpr size_t kCapLaunchTiles = 4096;      // 4 KiB tiles; below: uncapped
+// their register use, and capping them further only costs (measured). Up to 16 MiB a launch fits in
+// one round of uncapped waves and a cap would split it in two (12 inputs of 18 MiB: 77 % uncapped,
+// 74 % capped; of 22 MiB: 78 % and 82 %).
+constexpr size_t kCapLaunchTiles = 5120;      // 4 KiB tiles; below: uncapped
 constexpr int kLargeWavesPerCU = 8;
 // bf16 with 5..8 accumulator levels keeps the 2 KiB shape (two sources in flight) at every size.
 constexpr int kDeepBf16MaxDepth = 8;

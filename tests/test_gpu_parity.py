@@ -657,7 +657,7 @@ def test_adaptive_policy_changes_the_launches_not_the_bits():
 def test_eager_segments_over_long_ranges(dtype, mib):
     # whole objects arrive one at a time and every arrival is folded into the saved accumulators at once: the
     # segment launches span the whole object, long enough for the layout with pieces 64 KiB apart (and, from
-    # 16 MiB, the cap on resident waves). Same bits as the one-launch reduce and as the oracle on samples.
+    # 20 MiB, the cap on resident waves). Same bits as the one-launch reduce and as the oracle on samples.
     d = dev()
     nbytes = mib * (1 << 20) + 5 * 1024 + 3 * 16 - ES[dtype]
     chunk = 3 << 20
@@ -771,8 +771,8 @@ LAUNCH_SHAPE_CASES = [
     ("f32", 6, 5, 2, BEYOND, 5, "uniform_pm1"),      # the same, a few KiB into the last group
     ("f32", 6, 5, 4, SHORT, 12, "normal_std1"),      # four pieces 64 KiB apart, uncapped
     ("f32", 6, 5, 4, BEYOND, 9, "normal_std1"),      # the same, a few KiB into the last group
-    ("i32", 6, 6, 2, SHORT, 20, "randint_pm2p20"),   # four pieces 64 KiB apart, 8 waves per CU
-    ("i32", 6, 6, 2, BEYOND, 17, "randint_pm2p20"),  # the same, a few KiB into the last group
+    ("i32", 6, 6, 2, SHORT, 22, "randint_pm2p20"),   # four pieces 64 KiB apart, 8 waves per CU
+    ("i32", 6, 6, 2, BEYOND, 21, "randint_pm2p20"),  # the same, a few KiB into the last group
     ("f32", 5, 4, 1, SHORT, 52, "normal_std1"),      # a chain over 52 MiB objects
     ("bf16", 6, 6, 6, SHORT, 50, "normal_std1"),     # bf16 at depth 1..2, four pieces
     ("bf16", 40, 40, 2, SHORT, 17, "normal_std1"),   # bf16 binary tree (5 levels): two pieces, two sources in flight
