@@ -403,7 +403,8 @@ private:
             if (!dev_steps) return HOP_ERR_NOMEM;
         }
         hipError_t e = launch_reduce_segment(stream_, dtype_, op_, depth, dev_steps, t1 - t0, dsts_[0], spill_,
-                                             level_stride_, live_before, final ? 0 : live_after, b0, b1);
+                                             level_stride_, live_before, final ? 0 : live_after, b0, b1,
+                                             steps.empty() ? 0 : lead_vectors(steps.data(), (int)steps.size(), b0));
         if (e == hipSuccess && final && dsts_.size() > 1) {
             if (!dev_extra_) {
                 dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));

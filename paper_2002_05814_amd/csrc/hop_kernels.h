@@ -91,7 +91,7 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
 // accumulators indexed like the object's elements; levels are level_stride bytes apart.
 hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
                                  int n_entries, void *dst, char *spill, size_t level_stride, int n_restore,
-                                 int n_save, size_t byte_begin, size_t byte_end);
+                                 int n_save, size_t byte_begin, size_t byte_end, int lead_vecs = 0);
 
 // The same for n_subs independent sub-programs at once: dev_records holds n_subs records of
 // sub_entries entries (SubHeader, steps, padding; 2 <= sub_entries <= kMaxSubSteps + 1); every

@@ -67,18 +67,6 @@ static void fill_range(ReduceArgs &a, int dtype, size_t byte_begin, size_t byte_
     a.lead_vecs = 0;
 }
 
-// Vectors between the last 128-byte boundary of the sources and the start of the range: the residue
-// most of the program's sources share (objects from one allocator usually share it).
-static int lead_vectors(const DevEntry *host_steps, int n_entries, size_t byte_begin)
-{
-    int count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int i = 0; i < n_entries; ++i) count[(((uintptr_t)host_steps[i].src + byte_begin) >> 4) & 7]++;
-    int best = 0;
-    for (int r = 1; r < 8; ++r)
-        if (count[r] > count[best]) best = r;
-    return best;
-}
-
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
                          const DevEntry *dev_prog, int n_entries, void *dst, size_t byte_begin,
                          size_t byte_end)
@@ -124,7 +112,7 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
 
 hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
                                  int n_entries, void *dst, char *spill, size_t level_stride, int n_restore,
-                                 int n_save, size_t byte_begin, size_t byte_end)
+                                 int n_save, size_t byte_begin, size_t byte_end, int lead_vecs)
 {
     if (byte_end <= byte_begin) return hipSuccess;
     if ((n_entries > 0 && !dev_prog) || n_entries < 0 || (n_entries == 0 && n_restore < 1) || n_restore < 0 || n_save < 0 || n_restore > depth || n_save > depth ||
@@ -141,13 +129,15 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
     a.level_stride = level_stride;
     a.n_restore = n_restore;
     a.n_save = n_save;
+    if (a.n_vec > 0 && lead_vecs > 0 && lead_vecs < 8) a.lead_vecs = lead_vecs;
     // long ranges as in launch_reduce: pieces 64 KiB apart, and few resident waves for the 4-vector kernels
     const size_t tiles4k = (a.n_vec + 255) / 256;
     const bool strided = l.vpt >= 2 && tiles4k >= kMidLaunchTiles;
     a.piece_stride_log2 = strided ? kPieceStrideLog2 : -1;
     const unsigned lds = (l.vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
-    const unsigned grid = !strided ? grid_for(a.n_vec, (size_t)kThreads * l.vpt)
-                                   : grid_for(a.n_vec, ((size_t)kThreads * l.vpt) << kPieceStrideLog2) << kPieceStrideLog2;
+    const size_t n_all = a.n_vec + (size_t)a.lead_vecs;
+    const unsigned grid = !strided ? grid_for(n_all, (size_t)kThreads * l.vpt)
+                                   : grid_for(n_all, ((size_t)kThreads * l.vpt) << kPieceStrideLog2) << kPieceStrideLog2;
     hipLaunchKernelGGL(l.seg, dim3(grid), dim3(kThreads), lds, stream, a);
     return hipGetLastError();
 }

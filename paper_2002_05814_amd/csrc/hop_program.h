@@ -35,4 +35,17 @@ inline void mark_runs(DevEntry *steps, size_t n)
     }
 }
 
+// Vectors between the last 128-byte boundary of the sources and the start of the range: the residue
+// most of the program's sources share (objects from one allocator usually share it). The kernels
+// start their grid of vectors that many vectors before the range.
+inline int lead_vectors(const DevEntry *host_steps, int n_entries, size_t byte_begin)
+{
+    int count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < n_entries; ++i) count[(((uintptr_t)host_steps[i].src + byte_begin) >> 4) & 7]++;
+    int best = 0;
+    for (int r = 1; r < 8; ++r)
+        if (count[r] > count[best]) best = r;
+    return best;
+}
+
 }  // namespace hop

@@ -882,6 +882,18 @@ def test_sources_that_are_only_16_byte_aligned(dtype, mib, residues):
                 mag += o.double().abs()
             tol = 1e-5 * np.log2(k) if dtype == "f32" else 1e-2
             assert bool(((dst.double() - ref).abs() <= tol * torch.maximum(ref.abs(), mag / k)).all())
+    if mib in (9, 12):
+        # the same objects through eager segments (every arrival folded into saved accumulators at once)
+        rc, _ = hop.hop_reduce(dst, objs, k, "sum", dtype, chunk, deg, w.ready_order(), None)
+        fused = dst.clone()
+        dst.fill_(3)
+        rc, ses = hop.hop_session_begin(dst, objs, k, "sum", dtype, chunk, deg)
+        assert rc == hop.HOP_OK and hop.hop_session_set_eager(ses, 1) == hop.HOP_OK
+        for i in w.ready_order():
+            assert hop.hop_session_ready(ses, int(i), w.n_chunks) == hop.HOP_OK
+        rc, _ = hop.hop_session_finish(ses)
+        torch.cuda.synchronize()
+        assert rc == hop.HOP_OK and torch.equal(dst.view(torch.int32), fused.view(torch.int32))
     # nothing outside the result was written: the bytes around it are still zero
     assert int(pool[at - 12:at].abs().sum()) == 0 and int(pool[at + E:at + E + 12].abs().sum()) == 0
 
