@@ -27,16 +27,17 @@ MEASURED_TRAFFIC = {
     "workload": "cfg2_async_sgd",
     "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB "
                      "tiles: 1 KiB tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart;"
-                     " from 2048: 1 KiB pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU "
-                     "from 5120 tiles; bf16 at depth 5..8 from 768 tiles: 2 vectors/lane, unroll 2 (pieces 64 KiB apart "
-                     "from 2048 tiles); groups of 8 plain steps marked by the host; nontemporal loads+stores, programs <= "
-                     "128 steps in kernel arguments; vector grids start at a 128-byte boundary of the sources (reduce) or "
+                     " from 2048: 1 KiB pieces 64 KiB apart, one per vector (the 2 KiB shape instead if the rounds of "
+                     "resident waves would be less than 80 % full); kernels with 4 vectors/lane: 8 waves per CU from 5120 "
+                     "tiles; bf16 at depth 5..8 from 768 tiles: 2 vectors/lane, unroll 2 (pieces 64 KiB apart from 2048 "
+                     "tiles); groups of 8 plain steps marked by the host; nontemporal loads+stores, programs <= 128 steps "
+                     "in kernel arguments; vector grids start at a 128-byte boundary of the sources (reduce) or "
                      "destinations (copies); copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from "
                      "5120 8-KiB tiles 4 vectors/lane in 1 KiB pieces 64 KiB apart, 10 waves per CU; nontemporal; to "
                      "several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 "
                      "tiles, cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 "
                      "destinations)",
-    "bytes": 872312200,
+    "bytes": 872313828,
 }
 
 

@@ -10,6 +10,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 #include "hop_device.hpp"
 #include "hop_kernels.h"
 #include "hop_launch_shape.h"
@@ -35,7 +39,8 @@ const char *kernel_config()
 {
     return "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB tiles: 1 KiB "
            "tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart; from 2048: 1 KiB "
-           "pieces 64 KiB apart, one per vector; kernels with 4 vectors/lane: 8 waves per CU from 5120 tiles; bf16 at "
+           "pieces 64 KiB apart, one per vector (the 2 KiB shape instead if the rounds of resident waves would be less "
+           "than 80 % full); kernels with 4 vectors/lane: 8 waves per CU from 5120 tiles; bf16 at "
            "depth 5..8 from 768 tiles: 2 vectors/lane, unroll 2 (pieces 64 KiB apart from 2048 tiles); groups of 8 plain steps marked by the host; "
            "nontemporal loads+stores, programs <= 128 steps in kernel arguments; vector grids start at a 128-byte boundary of "
            "the sources (reduce) or destinations (copies); "
@@ -67,6 +72,27 @@ static void fill_range(ReduceArgs &a, int dtype, size_t byte_begin, size_t byte_
     a.lead_vecs = 0;
 }
 
+// Workgroups of one wave that the whole device holds at once for a kernel launched without dynamic
+// LDS (by its register use), asked of the runtime once per kernel; 0 if it cannot be told.
+static size_t chip_slots(const void *kernel)
+{
+    static std::mutex mu;
+    static std::vector<std::pair<const void *, size_t>> known;
+    std::lock_guard<std::mutex> lk(mu);
+    for (const auto &k : known)
+        if (k.first == kernel) return k.second;
+    size_t slots = 0;
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) == hipSuccess &&
+        hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && per_cu > 0 && cus > 0)
+        slots = (size_t)per_cu * (size_t)cus;
+    else
+        (void)hipGetLastError();
+    known.emplace_back(kernel, slots);
+    return slots;
+}
+
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
                          const DevEntry *dev_prog, int n_entries, void *dst, size_t byte_begin,
                          size_t byte_end)
@@ -87,18 +113,34 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     // 32 MiB in a binary tree: 81 % of the HBM peak, against 59-63 % for one source at a time and
     // 70-79 %, depending on how the objects lie, for 1 KiB tiles with 8 sources in flight)
     const bool deep_bf16 = dtype == HOP_BF16 && depth > 4 && depth <= kDeepBf16MaxDepth;
-    const int shape = tiles4k < kSmallLaunchTiles ? 0 : (tiles4k < kMidLaunchTiles || deep_bf16) ? 1 : 2;
-    const int vpt = shape == 0 ? 1 : shape == 1 ? (l.vpt < kMidVecs ? l.vpt : kMidVecs) : l.vpt;
+    int shape = tiles4k < kSmallLaunchTiles ? 0 : (tiles4k < kMidLaunchTiles || deep_bf16) ? 1 : 2;
+    const bool inl = n_entries <= kInlineEntries;
+    const size_t n_all = a.base.n_vec + (size_t)a.base.lead_vecs;
+    // strided: whole groups of (vpt << stride) pieces, one workgroup per 2^stride-th of a group
+    auto grid_of = [&](int vpt, int stride_log2) {
+        return stride_log2 < 0 ? grid_for(n_all, (size_t)kThreads * vpt)
+                               : grid_for(n_all, ((size_t)kThreads * vpt) << stride_log2) << stride_log2;
+    };
     // LDS the kernels never touch: it only caps the number of resident waves per compute unit
-    const unsigned lds = (shape == 2 && vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
+    const unsigned lds = (shape == 2 && l.vpt == 4 && tiles4k >= kCapLaunchTiles) ? kLargeLdsBytes : 0;
+    if (shape == 2 && lds == 0 && l.vpt >= 2) {
+        // One wave per workgroup and equal work per wave: a launch that needs 1.25 rounds of resident
+        // waves takes as long as one that needs 2 (200 inputs of 10 MiB, fp32: 67 % of the HBM peak
+        // where 8 MiB and 14 MiB reach 85 %). If the last round of the large shape would be poorly
+        // filled, the 2 KiB shape with its shorter waves takes the launch (81 % in that example).
+        const size_t slots = chip_slots(inl ? (const void *)l.inl : (const void *)l.dev);
+        const size_t wgs = grid_of(l.vpt, kPieceStrideLog2);
+        if (slots > 0 && wgs > slots) {
+            const size_t rounds = (wgs + slots - 1) / slots;
+            if ((double)wgs < kMinRoundFill * (double)(rounds * slots)) shape = 1;
+        }
+    }
+    const int vpt = shape == 0 ? 1 : shape == 1 ? (l.vpt < kMidVecs ? l.vpt : kMidVecs) : l.vpt;
     const int stride_log2 = vpt < 2 ? -1 : (shape == 2 || tiles4k >= kMidLaunchTiles) ? kPieceStrideLog2
                             : shape == 1 ? kMidPieceStrideLog2 : -1;
     a.base.piece_stride_log2 = stride_log2;
-    // strided: whole groups of (vpt << stride) pieces, one workgroup per 2^stride-th of a group
-    const size_t n_all = a.base.n_vec + (size_t)a.base.lead_vecs;
-    const unsigned grid = stride_log2 < 0 ? grid_for(n_all, (size_t)kThreads * vpt)
-                                          : grid_for(n_all, ((size_t)kThreads * vpt) << stride_log2) << stride_log2;
-    if (n_entries <= kInlineEntries) {
+    const unsigned grid = grid_of(vpt, stride_log2);
+    if (inl) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
         hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), lds,
                            stream, a);

@@ -50,6 +50,7 @@ constexpr int kPieceStrideLog2 = 6;           // up to 4 KiB per wave: the piece
 // their register use, and capping them further only costs (measured). Up to 16 MiB a launch fits in
 // one round of uncapped waves and a cap would split it in two (12 inputs of 18 MiB: 77 % uncapped,
 // 74 % capped; of 22 MiB: 78 % and 82 %).
+constexpr double kMinRoundFill = 0.80;        // uncapped large launches: least fill of the rounds of resident waves
 constexpr size_t kCapLaunchTiles = 5120;      // 4 KiB tiles; below: uncapped
 constexpr int kLargeWavesPerCU = 8;
 // bf16 with 5..8 accumulator levels keeps the 2 KiB shape (two sources in flight) at every size.
