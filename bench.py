@@ -136,6 +136,43 @@ def paced_arrivals(hop, torch, w, objs, order, dst, interval_us, reps=5):
     return res
 
 
+def streamed_chunks(hop, torch, w, objs, order, dst, interval_us, reps=5):
+    """All k objects stream side by side: every interval_us (host clock) each of them has one more chunk.
+    Measured: host time from the last notification to the completed result, and the launches it took, with
+    the default policy (a launch per chunk run as soon as all k have it): the pipelining of section 3.3."""
+    import statistics
+    table = hop.PtrTable(objs)
+    C = w.n_chunks
+    first_k = [int(order[t]) for t in range(w.k)]
+    res = {"interval_us": interval_us, "k": w.k, "chunks": C}
+    for name in ("fused",):
+        tails, totals, launches = [], [], 0
+        for _ in range(reps + 1):
+            rc, s = hop.hop_session_begin(dst, table, w.k, w.ops[0], w.dtype, w.chunk_bytes, w.tree_degree)
+            assert rc == hop.HOP_OK, hop.hop_strerror(rc)
+            for i in first_k:
+                assert hop.hop_session_ready(s, i, 0) == hop.HOP_OK
+            torch.cuda.synchronize()
+            t_begin = t_next = time.perf_counter()
+            for c in range(1, C + 1):
+                while time.perf_counter() < t_next:
+                    pass
+                for i in first_k:
+                    assert hop.hop_session_ready(s, i, c) == hop.HOP_OK
+                t_last = time.perf_counter()
+                t_next += interval_us * 1e-6
+            rc, info = hop.hop_session_finish(s)
+            torch.cuda.synchronize()
+            t_end = time.perf_counter()
+            tails.append((t_end - t_last) * 1e6)
+            totals.append((t_end - t_begin) * 1e6)
+            launches = info["n_launches"]
+            assert rc == hop.HOP_OK
+        res[name] = {"us_after_last_chunk": round(statistics.median(tails[1:]), 1),
+                     "us_first_chunk_to_result": round(statistics.median(totals[1:]), 1), "launches": launches}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,6 +182,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="which of the five workloads (default: 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true", help="also time the other workloads (extra JSON field)")
+    ap.add_argument("--streamed-interval-us", type=float, default=None,
+                    help="also: all k objects stream chunk by chunk, one more chunk each per interval")
     ap.add_argument("--paced-interval-us", type=float, default=None,
                     help="also run the workload's objects through the event-level API, one whole object every "
                          "INTERVAL microseconds, and report how long after the last arrival the result is complete, "
@@ -286,6 +325,8 @@ def main():
                                    "levels": st["info"]["stack_depth"]}
         sweep["picked_by_eq1"] = hop.hop_pick_degree(w.k, w.object_bytes, 0.0, 0.0)
         out["degree_sweep"] = sweep
+    if args.streamed_interval_us is not None:
+        out["streamed_chunks"] = streamed_chunks(hop, torch, w, objs, order, dsts[0][0], args.streamed_interval_us)
     if args.paced_interval_us is not None:
         out["paced_arrivals"] = paced_arrivals(hop, torch, w, objs, order, dsts[0][0], args.paced_interval_us)
     if args.all_configs:
