@@ -51,8 +51,10 @@ typedef enum {
     HOP_ERR_NO_SURVIVOR = -3,   /* no object survived: there is nothing to reduce            */
     HOP_ERR_DEVICE = -4,        /* a HIP call failed                                         */
     HOP_ERR_NOMEM = -5,         /* host or device allocation failed                          */
-    HOP_ERR_DEPTH = -6          /* the tree needs more partial results in flight than the
+    HOP_ERR_DEPTH = -6,         /* the tree needs more partial results in flight than the
                                    kernels hold in registers (see HOP_MAX_DEPTH)             */
+    HOP_ERR_TOO_LARGE = -7      /* hop_reduce_noalloc only: the call needs more device
+                                   scratch than the library's static array holds            */
 } hop_status_t;
 
 /* Most partial results that can be live at once while one element's tree
@@ -124,6 +126,37 @@ int hop_reduce(void *dst, const void *const *objs, int n, size_t object_bytes,
                const int32_t *ready_order, int k, hop_op_t op, hop_dtype_t dtype,
                size_t chunk_bytes, int tree_degree, const int64_t *fail_mask,
                void *stream, hop_info_t *info);
+
+/*
+ * hop_reduce_noalloc -- hop_reduce for callers that cannot allocate device
+ * memory: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc. Same arguments, same result bits, same status codes as
+ * hop_reduce, but the call allocates and frees nothing on the device and
+ * calls no allocating library routine: whatever device scratch the kernels
+ * need (programs of more than 128 steps; the partial results and
+ * sub-programs of a reduce over many small objects) lives in one static
+ * device array of hop_noalloc_scratch_bytes() bytes (8 MiB) that every GPU
+ * the library runs on holds until the process ends, and programs and tables
+ * reach it through kernel arguments instead of a staging buffer.
+ *   - A call whose program alone does not fit (about 500 000 inputs) returns
+ *     HOP_ERR_TOO_LARGE and enqueues nothing. A many-small-objects call
+ *     whose partial results do not fit is evaluated by one program instead
+ *     (slower, same bits).
+ *   - All calls on one GPU share that GPU's array, which keeps the last
+ *     call's contents; nothing in it has to start at zero (every partial
+ *     result is written before it is read). Calls on the same stream are
+ *     ordered by the stream. Calls that overlap on one GPU (different
+ *     streams, or host threads on different streams) race on the array:
+ *     the caller must serialise them.
+ *   - hop_reduce's repair of a mid-stream failure works as in hop_reduce.
+ */
+int hop_reduce_noalloc(void *dst, const void *const *objs, int n, size_t object_bytes,
+                       const int32_t *ready_order, int k, hop_op_t op, hop_dtype_t dtype,
+                       size_t chunk_bytes, int tree_degree, const int64_t *fail_mask,
+                       void *stream, hop_info_t *info);
+
+/* Size in bytes of the static device array behind hop_reduce_noalloc. */
+size_t hop_noalloc_scratch_bytes(void);
 
 /*
  * hop_broadcast -- section 3.4.1: every receiver ends with a byte-identical

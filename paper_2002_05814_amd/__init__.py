@@ -21,14 +21,14 @@ HOP_SUM, HOP_MIN, HOP_MAX = 0, 1, 2
 HOP_F32, HOP_BF16, HOP_I32 = 0, 1, 2
 HOP_OK, HOP_PARTIAL = 0, 1
 HOP_ERR_INVALID, HOP_ERR_ALIGN, HOP_ERR_NO_SURVIVOR = -1, -2, -3
-HOP_ERR_DEVICE, HOP_ERR_NOMEM, HOP_ERR_DEPTH = -4, -5, -6
+HOP_ERR_DEVICE, HOP_ERR_NOMEM, HOP_ERR_DEPTH, HOP_ERR_TOO_LARGE = -4, -5, -6, -7
 HOP_MAX_DEPTH = 16
 
 OPS = {"sum": HOP_SUM, "min": HOP_MIN, "max": HOP_MAX}
 DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
           torch.float32: HOP_F32, torch.bfloat16: HOP_BF16, torch.int32: HOP_I32}
 
-EXPORTS = ["hop_reduce", "hop_broadcast", "hop_allreduce", "hop_bcast_begin", "hop_bcast_source_ready",
+EXPORTS = ["hop_reduce", "hop_reduce_noalloc", "hop_noalloc_scratch_bytes", "hop_broadcast", "hop_allreduce", "hop_bcast_begin", "hop_bcast_source_ready",
            "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready", "hop_session_ready_after",
            "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_set_adaptive", "hop_session_chunks_final",
            "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
@@ -87,6 +87,9 @@ def lib() -> ctypes.CDLL:
         infop = ctypes.POINTER(HopInfo)
         L.hop_reduce.argtypes = [vp, vpp, ctypes.c_int, ctypes.c_size_t, i32p, ctypes.c_int, ctypes.c_int,
                                  ctypes.c_int, ctypes.c_size_t, ctypes.c_int, i64p, vp, infop]
+        L.hop_reduce_noalloc.argtypes = L.hop_reduce.argtypes
+        L.hop_noalloc_scratch_bytes.argtypes = []
+        L.hop_noalloc_scratch_bytes.restype = ctypes.c_size_t
         L.hop_broadcast.argtypes = [vpp, ctypes.c_int, vp, ctypes.c_size_t, ctypes.c_size_t, vp]
         L.hop_allreduce.argtypes = [vpp, ctypes.c_int, vpp, ctypes.c_int, ctypes.c_size_t, i32p, ctypes.c_int,
                                     ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, i64p, vp, infop]
@@ -132,7 +135,7 @@ def lib() -> ctypes.CDLL:
         L.hop_kernel_config.argtypes = []
         L.hop_kernel_config.restype = ctypes.c_char_p
         for name in EXPORTS:
-            if name not in ("hop_workspace_bytes", "hop_strerror", "hop_kernel_config", "hop_session_chunks_final"):
+            if name not in ("hop_workspace_bytes", "hop_noalloc_scratch_bytes", "hop_strerror", "hop_kernel_config", "hop_session_chunks_final"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -218,6 +221,24 @@ def hop_reduce(dst, objs, k, op, dtype, chunk_bytes, tree_degree, ready_order=No
                           _code(OPS, op), _code(DTYPES, dtype), int(chunk_bytes), int(tree_degree), fm,
                           _stream(stream), ctypes.byref(info))
     return rc, info.as_dict()
+
+
+def hop_reduce_noalloc(dst, objs, k, op, dtype, chunk_bytes, tree_degree, ready_order=None, fail_mask=None,
+                       stream=None, object_bytes=None):
+    """hop_reduce_noalloc of include/hop.h: hop_reduce with the library's static device scratch."""
+    tab, n = _ptr_table(objs)
+    _ro, ro = _i32(ready_order)
+    _fm, fm = _i64(fail_mask)
+    info = HopInfo()
+    dptr = ctypes.c_void_p(int(dst.data_ptr()) if isinstance(dst, torch.Tensor) else int(dst))
+    rc = lib().hop_reduce_noalloc(dptr, tab, n, _bytes_of(objs[0] if n else dst, object_bytes), ro, int(k),
+                                  _code(OPS, op), _code(DTYPES, dtype), int(chunk_bytes), int(tree_degree), fm,
+                                  _stream(stream), ctypes.byref(info))
+    return rc, info.as_dict()
+
+
+def hop_noalloc_scratch_bytes() -> int:
+    return int(lib().hop_noalloc_scratch_bytes())
 
 
 def hop_broadcast(dsts, src, chunk_bytes, stream=None, object_bytes=None):

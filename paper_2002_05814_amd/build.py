@@ -6,6 +6,7 @@ linked into one shared library.
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import shutil
 import subprocess
@@ -51,16 +52,40 @@ def _run(cmd, verbose):
         raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
 
 
-def build(verbose: bool = False, jobs: int | None = None) -> str:
-    """Compile every HIP source into paper_2002_05814_amd/libhop.so (always rebuilds)."""
+def _sources_digest(src: str, extra) -> str:
+    """Hash of a translation unit's inputs: its source, every header beside it, the public header, the flags."""
+    h = hashlib.sha256()
+    names = [os.path.join(CSRC, src)] + sorted(
+        os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".h", ".hpp")))
+    names.append(os.path.join(os.path.dirname(HERE), "include", "hop.h"))
+    for name in names:
+        with open(name, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join([*HIPCC_FLAGS, *extra]).encode())
+    return h.hexdigest()[:20]
+
+
+def build(verbose: bool = False, jobs: int | None = None, object_cache: str | None = None) -> str:
+    """Compile every HIP source into paper_2002_05814_amd/libhop.so.
+
+    Without object_cache everything is compiled afresh. With it (a directory), objects whose inputs are
+    unchanged since an earlier build are taken from there: for edit-compile loops during development.
+    """
     jobs = jobs or max(1, min(8, os.cpu_count() or 1))
     cc = hipcc()
     with tempfile.TemporaryDirectory(prefix="hop_build_") as tmpdir:
         objs = []
         cmds = []
         for src, extra, obj in _units():
-            out = os.path.join(tmpdir, obj)
-            objs.append(out)
+            if object_cache:
+                os.makedirs(object_cache, exist_ok=True)
+                out = os.path.join(object_cache, "%s.%s.o" % (obj[:-2], _sources_digest(src, extra)))
+                objs.append(out)
+                if os.path.exists(out):
+                    continue
+            else:
+                out = os.path.join(tmpdir, obj)
+                objs.append(out)
             cmds.append([cc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", out])
         with ThreadPoolExecutor(max_workers=jobs) as pool:
             list(pool.map(lambda c: _run(c, verbose), cmds))
@@ -71,4 +96,6 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    cache = os.path.join(os.path.dirname(HERE), "_build") if "--incremental" in sys.argv[1:] else None
+    print(build(verbose="--quiet" not in sys.argv[1:], object_cache=cache))

@@ -196,17 +196,103 @@ static void release_devbuf(DevBuf *b, hipStream_t stream)
     }
 }
 
+// ----------------------------------------------------------------------------
+// scratch for callers that cannot allocate (hop_reduce_noalloc)
+// ----------------------------------------------------------------------------
+
+// One array per GPU the library runs on, held until the process ends. Host code never uses the
+// array's name as an address: static_scratch() asks the runtime where the current device keeps
+// its copy, once per device, and everything else (kernel arguments, the bump allocator below)
+// works with that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxStaticDevices = 64;
+static char *g_scratch_ptr[kMaxStaticDevices];
+
+static int static_scratch(int device, char **ptr)
+{
+    if (device < 0 || device >= kMaxStaticDevices) return HOP_ERR_DEVICE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {     // the current device's copy
+            (void)hipGetLastError();
+            return HOP_ERR_DEVICE;
+        }
+        g_scratch_ptr[device] = (char *)p;
+    }
+    *ptr = g_scratch_ptr[device];
+    return HOP_OK;
+}
+
+// Carries up to kPokeVectors * 16 bytes from the kernel arguments to device memory: how programs
+// and tables reach the static scratch without a staging buffer.
+constexpr int kPokeVectors = 240;
+struct PokeArgs {
+    uint4 *dst;
+    int n;
+    int pad;
+    uint4 data[kPokeVectors];
+};
+static_assert(sizeof(PokeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+
+__global__ __launch_bounds__(256) void poke_kernel(PokeArgs a)
+{
+    const int i = (int)threadIdx.x;
+    if (i < a.n) a.dst[i] = a.data[i];
+}
+
+static bool poke(hipStream_t stream, void *dst, const void *src, size_t bytes)
+{
+    const char *from = (const char *)src;
+    char *to = (char *)dst;
+    while (bytes > 0) {
+        PokeArgs a;
+        const size_t now = bytes < sizeof a.data ? bytes : sizeof a.data;
+        a.dst = (uint4 *)to;
+        a.n = (int)((now + 15) / 16);
+        a.pad = 0;
+        std::memset(&a.data[(size_t)a.n - 1], 0, sizeof(uint4));        // the last vector may be partly filled
+        std::memcpy(a.data, from, now);
+        hipLaunchKernelGGL(poke_kernel, dim3(1), dim3(256), 0, stream, a);
+        if (hipGetLastError() != hipSuccess) return false;
+        from += now;
+        to += now;
+        bytes -= now;
+    }
+    return true;
+}
+
 // Bump allocator over a list of blocks; everything staged is copied to the
 // device with one async copy per stage() call, ordered on the stream.
+//
+// Static mode (static_base given): every request is served from one caller-given stretch of
+// device memory, nothing is allocated, and staged data travels through kernel arguments. A
+// request that does not fit fails, and error() then says HOP_ERR_TOO_LARGE.
 class Workspace {
 public:
-    Workspace(int device, hipStream_t stream) : device_(device), stream_(stream) {}
+    Workspace(int device, hipStream_t stream, char *static_base = nullptr, size_t static_cap = 0)
+        : device_(device), stream_(stream), static_base_(static_base), static_cap_(static_base ? static_cap : 0) {}
+    Workspace(const Workspace &) = delete;
+    Workspace &operator=(const Workspace &) = delete;
     ~Workspace() { for (Block *b : blocks_) release_block(b, stream_); }
+
+    bool is_static() const { return static_base_ != nullptr; }
+    // why the last request failed
+    int error() const { return too_large_ ? HOP_ERR_TOO_LARGE : HOP_ERR_NOMEM; }
+    // bytes a request of any kind may still take in static mode
+    size_t static_left() const { return static_cap_ - used_; }
 
     // Copies `bytes` from src to device memory (16-byte aligned); returns the device address or null.
     void *stage(const void *src, size_t bytes)
     {
         size_t need = (bytes + 255) & ~(size_t)255;
+        if (is_static()) {
+            void *d = scratch(bytes);
+            if (d && !poke(stream_, d, src, bytes)) return nullptr;
+            return d;
+        }
         if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
             Block *b = acquire_block(device_, need);
             if (!b) return nullptr;
@@ -228,6 +314,7 @@ public:
     const void *stage_in_place(const void *src, size_t bytes)
     {
         size_t need = (bytes + 255) & ~(size_t)255;
+        if (is_static()) return stage(src, bytes);        // no pinned memory here: a copy on the device
         if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
             Block *b = acquire_block(device_, need);
             if (!b) return nullptr;
@@ -244,6 +331,10 @@ public:
     // Makes sure the next `bytes` of stage()/scratch() requests come from one block.
     bool reserve(size_t bytes)
     {
+        if (is_static()) {
+            too_large_ = used_ + bytes > static_cap_;
+            return !too_large_;
+        }
         if (!blocks_.empty() && used_ + bytes <= blocks_.back()->cap) return true;
         Block *b = acquire_block(device_, bytes);
         if (!b) return false;
@@ -256,6 +347,12 @@ public:
     void *scratch(size_t bytes)
     {
         size_t need = (bytes + 255) & ~(size_t)255;
+        if (is_static()) {
+            if (need > static_cap_ - used_) { too_large_ = true; return nullptr; }
+            void *d = static_base_ + used_;
+            used_ += need;
+            return d;
+        }
         if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
             Block *b = acquire_block(device_, need);
             if (!b) return nullptr;
@@ -272,6 +369,9 @@ private:
     hipStream_t stream_;
     std::vector<Block *> blocks_;
     size_t used_ = 0;
+    char *static_base_ = nullptr;
+    size_t static_cap_ = 0;
+    bool too_large_ = false;
 };
 
 // ----------------------------------------------------------------------------
@@ -287,9 +387,12 @@ struct Shape {
 
 class GpuBackend : public Backend {
 public:
+    // static_base != nullptr: all device scratch comes from [static_base, static_base + static_cap) and
+    // nothing is allocated (the back end of hop_reduce_noalloc)
     GpuBackend(int device, hipStream_t stream, const void *const *objs, int n, std::vector<void *> dsts,
-               const Shape &shape, int op, int dtype, int k, int64_t degree)
-        : ws_(device, stream), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
+               const Shape &shape, int op, int dtype, int k, int64_t degree, char *static_base = nullptr,
+               size_t static_cap = 0)
+        : ws_(device, stream, static_base, static_cap), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
           op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device)
     {
         if (dsts_.size() > 1) extra_residue_ = common_residue(dsts_.data() + 1, (int)dsts_.size() - 1);
@@ -335,7 +438,7 @@ private:
         if (t0 > 0 || !final) return launch_segment(prog, c0, c1, t0, t1, final, live_before, live_after);
         if (dsts_.size() > 1 && !dev_extra_) {
             dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
-            if (!dev_extra_) return HOP_ERR_NOMEM;
+            if (!dev_extra_) return ws_.error();
         }
         const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
         if (wants_split(prog.size(), b1 - b0)) {
@@ -358,7 +461,7 @@ private:
             dev_prog_ = nullptr;
             if ((int)staging_.size() > kInlineEntries) {      // short programs ride in the kernel arguments
                 dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
-                if (!dev_prog_) return HOP_ERR_NOMEM;
+                if (!dev_prog_) return ws_.error();
             }
             dev_version_ = version;
         }
@@ -382,6 +485,7 @@ private:
     {
         const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
         if (!spill_) {
+            if (ws_.is_static()) return HOP_ERR_TOO_LARGE;        // saved accumulators are object-sized: never from the static scratch
             const size_t n_elems = shape_.object_bytes / (size_t)elem_bytes(dtype_);
             level_stride_ = (n_elems * 4 + 255) & ~(size_t)255;
             spill_levels_ = std::min(HOP_MAX_DEPTH, full_tree_depth(k_, degree_));
@@ -400,7 +504,7 @@ private:
         const DevEntry *dev_steps = nullptr;           // t0 == t1: only move saved accumulators to the result
         if (!steps.empty()) {
             dev_steps = (const DevEntry *)ws_.stage(steps.data(), steps.size() * sizeof(DevEntry));
-            if (!dev_steps) return HOP_ERR_NOMEM;
+            if (!dev_steps) return ws_.error();
         }
         hipError_t e = launch_reduce_segment(stream_, dtype_, op_, depth, dev_steps, t1 - t0, dsts_[0], spill_,
                                              level_stride_, live_before, final ? 0 : live_after, b0, b1,
@@ -408,7 +512,7 @@ private:
         if (e == hipSuccess && final && dsts_.size() > 1) {
             if (!dev_extra_) {
                 dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
-                if (!dev_extra_) return HOP_ERR_NOMEM;
+                if (!dev_extra_) return ws_.error();
             }
             e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
         }
@@ -452,9 +556,13 @@ private:
             if (pi.sub_entries > kMaxSubSteps + 1) return HOP_PARTIAL;
             n_blob += (size_t)pi.sub_entries * (size_t)pi.n_subs;
         }
-        if (!ws_.reserve(part_bytes * n_subs + n_blob * sizeof(DevEntry) + 512)) return HOP_ERR_NOMEM;
+        const size_t need = part_bytes * n_subs + n_blob * sizeof(DevEntry) + 512;
+        // without the right to allocate, a cut that does not fit beside the whole program (which the
+        // plain path then has to stage) is not made
+        if (ws_.is_static() && need + prog.size() * sizeof(DevEntry) + 256 > ws_.static_left()) return HOP_PARTIAL;
+        if (!ws_.reserve(need)) return ws_.error();
         char *partials = (char *)ws_.scratch(part_bytes * n_subs);
-        if (!partials) return HOP_ERR_NOMEM;
+        if (!partials) return ws_.error();
         // Kernels address sources and results by the object's byte offset, so a partial that holds
         // only [b0, b1) is passed as base - b0. Passes run in stream order: pass h reads what
         // passes < h wrote.
@@ -484,7 +592,7 @@ private:
         for (const Entry &e : mp.top) blob.push_back(resolve(e, partials, part_bytes, b0));
         mark_runs(blob.data() + top_at, blob.size() - top_at);
         const DevEntry *dev = (const DevEntry *)ws_.stage_in_place(blob.data(), blob.size() * sizeof(DevEntry));
-        if (!dev) return HOP_ERR_NOMEM;
+        if (!dev) return ws_.error();
         for (const PassInfo &pi : passes) {
             if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.records_at, pi.sub_entries, pi.n_subs, b0,
                                    b1) != hipSuccess)
@@ -644,7 +752,8 @@ static int pick_degree(int k, size_t object_bytes, double L, double B)
 
 static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, int n, size_t object_bytes,
                          const int32_t *ready_order, int k, int op, int dtype, size_t chunk_bytes,
-                         int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info)
+                         int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info,
+                         bool no_alloc = false)
 {
     Shape shape;
     int rc = check_shape(n, object_bytes, k, op, dtype, chunk_bytes, tree_degree, &shape);
@@ -654,9 +763,11 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
     const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    char *static_base = nullptr;
+    if (no_alloc && (rc = static_scratch(device, &static_base)) < 0) return rc;
     try {
         GpuBackend be(device, (hipStream_t)stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype,
-                      k, d);
+                      k, d, static_base, kStaticScratchBytes);
         Scheduler s(n, k, shape.n_chunks, d, &be);
         return replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
     } catch (const std::bad_alloc &) {
@@ -740,6 +851,18 @@ int hop_reduce(void *dst, const void *const *objs, int n, size_t object_bytes, c
     return reduce_common(dsts, 1, objs, n, object_bytes, ready_order, k, (int)op, (int)dtype, chunk_bytes,
                          tree_degree, fail_mask, stream, info);
 }
+
+int hop_reduce_noalloc(void *dst, const void *const *objs, int n, size_t object_bytes, const int32_t *ready_order,
+                       int k, hop_op_t op, hop_dtype_t dtype, size_t chunk_bytes, int tree_degree,
+                       const int64_t *fail_mask, void *stream, hop_info_t *info)
+{
+    if (!dst) return HOP_ERR_INVALID;
+    void *dsts[1] = {dst};
+    return reduce_common(dsts, 1, objs, n, object_bytes, ready_order, k, (int)op, (int)dtype, chunk_bytes,
+                         tree_degree, fail_mask, stream, info, true);
+}
+
+size_t hop_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int hop_allreduce(void *const *dsts, int n_dst, const void *const *objs, int n, size_t object_bytes,
                   const int32_t *ready_order, int k, hop_op_t op, hop_dtype_t dtype, size_t chunk_bytes,
@@ -1126,6 +1249,7 @@ const char *hop_strerror(int status)
     case HOP_ERR_DEVICE: return "HIP call failed";
     case HOP_ERR_NOMEM: return "out of memory";
     case HOP_ERR_DEPTH: return "reduce tree needs more live partial results than the kernels hold";
+    case HOP_ERR_TOO_LARGE: return "the call needs more device scratch than the static array of the no-allocation entry point holds";
     default: return "unknown status";
     }
 }
