@@ -78,6 +78,9 @@ typedef struct {
                                program steps (= source chunks read), repairs included */
     int64_t chunk_stores;   /* sum over launches of chunks whose result or accumulators
                                were written                                           */
+    int64_t partial_loads;  /* sum over launches of chunks x kept partial results read
+                               (4 bytes per element each), see hop_session_set_retention */
+    int64_t partial_stores; /* sum over launches of chunks x partial results kept      */
 } hop_info_t;
 
 /*
@@ -109,8 +112,10 @@ typedef struct {
  *                side by side, so a participant that fails after c chunks is
  *                noticed when chunks 0..c-1 of the output have already been
  *                produced with its data: those chunks are produced again
- *                without it. The failed position goes to the next ready
- *                object not yet in the tree, else stays empty.
+ *                without it, from the kept partial results of the subtrees it
+ *                was not in where there are any (see
+ *                hop_session_set_retention). The failed position goes to the
+ *                next ready object not yet in the tree, else stays empty.
  *   stream       hipStream_t.
  *   info         host pointer or NULL; filled before return.
  *
@@ -294,6 +299,25 @@ int hop_session_set_eager(hop_session_t *s, int min_steps);
  * not. Host-only sessions count as always idle. */
 int hop_session_set_adaptive(hop_session_t *s, int on);
 
+/* Keeping partial results for the repair of failures (section 3.5.2: when a
+ * participant fails, the partial results that do not contain its object are
+ * kept and only its ancestors in the tree start over). on != 0 (default): a
+ * launch that produces output chunks while some participant in the tree is
+ * still streaming - and so can still fail - also stores, in device scratch of
+ * the library (4 bytes per element and subtree), the partial result of every
+ * subtree below the root that has more than one node; after a failure (or a
+ * late arrival into an empty position) the chunks already produced are
+ * repaired by a launch that reads the kept partials of the untouched subtrees
+ * and re-reads only the objects of the subtree that changed and those
+ * directly below the root. Launches made when nobody can fail any more (every
+ * launch of a call whose participants all complete) keep nothing and cost
+ * nothing extra. Nothing is kept either for launches over at most 1 MiB per
+ * object, for chains and stars (no subtrees), for more than 16 subtrees, when
+ * the kept arrays would exceed a quarter of what the launch reads or 16 GiB,
+ * or in hop_reduce_noalloc. on = 0: never keep; a repair reads every object
+ * of the chunk again. Results are bit-identical either way. */
+int hop_session_set_retention(hop_session_t *s, int on);
+
 /* Number of leading output chunks that are final in dst as far as the work
  * enqueued so far goes (a later failure can take chunks back). This is what a
  * downstream consumer on the same stream may read, e.g. a second session that
@@ -320,11 +344,25 @@ int hop_session_finish(hop_session_t *s, hop_info_t *info);
  *   then n_fold times: acc[level-1] = acc[level-1] (op) acc[level]; --level
  * and storing acc[0]. Launches must be applied in order (a later launch may
  * overwrite chunks of an earlier one: that is failure repair).
+ * Kept partial results (hop_session_set_retention): there are up to 16 arrays
+ * kept[q] of accumulator-typed values, indexed like the object's elements. A
+ * step with obj = -(1 + q) takes x from kept[q] instead of an object. A step
+ * with save = q >= 0 stops its folds when they have come down to save_level,
+ * stores kept[q] = acc[save_level] for the launch's chunks, and then performs
+ * the remaining folds.
  * Returns the status hop_reduce would return; *n_launches / *n_entries hold
  * the counts needed (also when they exceed the capacities, in which case
  * the arrays are filled up to capacity).
  */
-typedef struct { int32_t obj; uint8_t level; uint8_t set; uint16_t n_fold; } hop_plan_entry_t;
+typedef struct {
+    int32_t obj;            /* >= 0: object; -(1 + q): kept partial result q (see below)            */
+    uint8_t level;
+    uint8_t set;
+    uint16_t n_fold;
+    int16_t save;           /* -1, or q: this step also stores kept partial q (see below)          */
+    uint8_t save_level;
+    uint8_t reserved;
+} hop_plan_entry_t;
 typedef struct {
     int64_t chunk_begin, chunk_end;   /* output chunks the launch works on                            */
     int32_t entry_begin, entry_end;   /* the program in force: entries[entry_begin, entry_end)         */

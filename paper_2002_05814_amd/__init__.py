@@ -30,7 +30,7 @@ DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
 
 EXPORTS = ["hop_reduce", "hop_reduce_noalloc", "hop_noalloc_scratch_bytes", "hop_broadcast", "hop_allreduce", "hop_bcast_begin", "hop_bcast_source_ready",
            "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready", "hop_session_ready_after",
-           "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_set_adaptive", "hop_session_chunks_final",
+           "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_set_adaptive", "hop_session_set_retention", "hop_session_chunks_final",
            "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
            "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
 
@@ -39,7 +39,8 @@ class HopInfo(ctypes.Structure):
     _fields_ = [("k_eff", ctypes.c_int32), ("n_failed_seen", ctypes.c_int32),
                 ("n_replaced", ctypes.c_int32), ("degree_used", ctypes.c_int32),
                 ("chunks_redone", ctypes.c_int64), ("n_launches", ctypes.c_int32),
-                ("stack_depth", ctypes.c_int32), ("chunk_steps", ctypes.c_int64), ("chunk_stores", ctypes.c_int64)]
+                ("stack_depth", ctypes.c_int32), ("chunk_steps", ctypes.c_int64), ("chunk_stores", ctypes.c_int64),
+                ("partial_loads", ctypes.c_int64), ("partial_stores", ctypes.c_int64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}
@@ -60,7 +61,11 @@ class BcastInfo(ctypes.Structure):
 
 class PlanEntry(ctypes.Structure):
     _fields_ = [("obj", ctypes.c_int32), ("level", ctypes.c_uint8), ("set", ctypes.c_uint8),
-                ("n_fold", ctypes.c_uint16)]
+                ("n_fold", ctypes.c_uint16), ("save", ctypes.c_int16), ("save_level", ctypes.c_uint8),
+                ("reserved", ctypes.c_uint8)]
+
+    def __init__(self, obj=0, level=0, set=0, n_fold=0, save=-1, save_level=0):
+        super().__init__(obj, level, set, n_fold, save, save_level, 0)
 
 
 class PlanLaunch(ctypes.Structure):
@@ -109,6 +114,7 @@ def lib() -> ctypes.CDLL:
         L.hop_session_finish.argtypes = [vp, infop]
         L.hop_session_set_eager.argtypes = [vp, ctypes.c_int]
         L.hop_session_set_adaptive.argtypes = [vp, ctypes.c_int]
+        L.hop_session_set_retention.argtypes = [vp, ctypes.c_int]
         L.hop_session_chunks_final.argtypes = [vp]
         L.hop_session_chunks_final.restype = ctypes.c_int64
         L.hop_plan_session_begin.argtypes = [ctypes.POINTER(vp), ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
@@ -336,6 +342,10 @@ def hop_session_set_adaptive(session, on):
     return lib().hop_session_set_adaptive(session, int(bool(on)))
 
 
+def hop_session_set_retention(session, on):
+    return lib().hop_session_set_retention(session, int(bool(on)))
+
+
 def hop_session_set_eager(session, min_steps):
     return lib().hop_session_set_eager(session, int(min_steps))
 
@@ -369,7 +379,10 @@ def _launch_tuples(L, n):
 
 
 def _entry_tuples(E, n):
-    return [(E[i].obj, E[i].level, E[i].set, E[i].n_fold) for i in range(n)]
+    """(obj, level, set, n_fold) per step; a step that stores a kept partial result carries two more
+    fields, (..., save, save_level). obj = -(1 + q) reads kept partial q."""
+    return [(E[i].obj, E[i].level, E[i].set, E[i].n_fold) if E[i].save < 0 else
+            (E[i].obj, E[i].level, E[i].set, E[i].n_fold, E[i].save, E[i].save_level) for i in range(n)]
 
 
 def hop_session_finish(session):

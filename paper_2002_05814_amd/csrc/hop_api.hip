@@ -401,6 +401,7 @@ public:
     ~GpuBackend() override
     {
         release_devbuf(spill_buf_, stream_);
+        release_devbuf(kept_buf_, stream_);
         if (busy_ev_) (void)hipEventDestroy(busy_ev_);
     }
 
@@ -417,6 +418,23 @@ public:
 
     // everything enqueued on the session's stream from now on runs after `ev` has completed
     bool wait_for(hipEvent_t ev) { return hipStreamWaitEvent(stream_, ev, 0) == hipSuccess; }
+
+    // Memory for the partial results kept for failure repair: one array of 4-byte accumulators per
+    // partial, each as long as the object has elements, from the library's cache of device buffers.
+    // Refused without the right to allocate, and beyond kMaxKeptBytes.
+    bool keep_partials(int n_partials) override
+    {
+        if (kept_) return true;
+        if (ws_.is_static() || n_partials < 1 || shape_.object_bytes == 0) return false;
+        const size_t n_elems = shape_.object_bytes / (size_t)elem_bytes(dtype_);
+        kept_stride_ = (n_elems * 4 + 255) & ~(size_t)255;
+        if (kept_stride_ > kMaxKeptBytes / (size_t)n_partials) return false;
+        kept_buf_ = acquire_devbuf(device_, kept_stride_ * (size_t)n_partials);
+        if (!kept_buf_) return false;
+        kept_ = kept_buf_->ptr;
+        n_kept_ = n_partials;
+        return true;
+    }
 
     int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
                int live_before, int live_after) override
@@ -436,6 +454,8 @@ private:
     {
         if (shape_.object_bytes == 0) return HOP_OK;
         if (t0 > 0 || !final) return launch_segment(prog, c0, c1, t0, t1, final, live_before, live_after);
+        for (const Entry &e : prog)
+            if (e.obj < 0 || e.save >= 0) return launch_kept(prog, version, c0, c1);
         if (dsts_.size() > 1 && !dev_extra_) {
             dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
             if (!dev_extra_) return ws_.error();
@@ -510,6 +530,47 @@ private:
                                              level_stride_, live_before, final ? 0 : live_after, b0, b1,
                                              steps.empty() ? 0 : lead_vectors(steps.data(), (int)steps.size(), b0));
         if (e == hipSuccess && final && dsts_.size() > 1) {
+            if (!dev_extra_) {
+                dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
+                if (!dev_extra_) return ws_.error();
+            }
+            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
+        }
+        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+    }
+
+    // A whole program some of whose steps read a kept partial result (obj = -(1 + q)) or store one
+    // (save = q): the repair of a failure and the launches that prepare for one.
+    static constexpr size_t kMaxKeptBytes = (size_t)16 << 30;
+
+    int launch_kept(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1)
+    {
+        if (!kept_) return HOP_ERR_NOMEM;               // keep_partials was not asked, or said no
+        const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
+        if (version != kept_version_) {
+            kept_steps_.resize(prog.size());
+            kept_depth_ = 1;
+            for (size_t i = 0; i < prog.size(); ++i) {
+                const Entry &e = prog[i];
+                if (e.obj < 0 && -e.obj - 1 >= n_kept_) return HOP_ERR_INVALID;
+                if (e.save >= n_kept_ || e.save_level > e.level) return HOP_ERR_INVALID;
+                DevEntry d;
+                d.src = e.obj >= 0 ? objs_[e.obj] : (const void *)(kept_ + (size_t)(-e.obj - 1) * kept_stride_);
+                d.ctl = (uint32_t)e.level | ((uint32_t)e.set << 8) | ((uint32_t)e.n_fold << 16) | (e.obj < 0 ? kPartialBit : 0u);
+                d.aux = e.save >= 0 ? ((uint32_t)e.save + 1u) | ((uint32_t)e.save_level << 16) : 0u;
+                kept_steps_[i] = d;
+                kept_depth_ = std::max(kept_depth_, (int)e.level + 1);
+            }
+            kept_dev_ = nullptr;
+            if ((int)kept_steps_.size() > kInlineEntries) {       // short programs ride in the kernel arguments
+                kept_dev_ = (const DevEntry *)ws_.stage(kept_steps_.data(), kept_steps_.size() * sizeof(DevEntry));
+                if (!kept_dev_) return ws_.error();
+            }
+            kept_version_ = version;
+        }
+        hipError_t e = launch_reduce_kept(stream_, dtype_, op_, kept_depth_, kept_steps_.data(), kept_dev_, (int)prog.size(),
+                                          dsts_[0], kept_, kept_stride_, b0, b1);
+        if (e == hipSuccess && dsts_.size() > 1) {
             if (!dev_extra_) {
                 dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
                 if (!dev_extra_) return ws_.error();
@@ -609,7 +670,7 @@ private:
         d.src = e.obj >= 0 ? objs_[e.obj]
                            : (const void *)((uintptr_t)partials + (size_t)(-e.obj - 1) * part_bytes - b0);
         d.ctl = (uint32_t)e.level | ((uint32_t)e.set << 8) | ((uint32_t)e.n_fold << 16);
-        d.reserved = 0;
+        d.aux = 0;
         return d;
     }
 
@@ -633,6 +694,14 @@ private:
     int spill_levels_ = 0;
     hipEvent_t busy_ev_ = nullptr;
     bool busy_recorded_ = false, track_idle_ = false;
+    DevBuf *kept_buf_ = nullptr;                // partial results kept for failure repair
+    char *kept_ = nullptr;
+    size_t kept_stride_ = 0;
+    int n_kept_ = 0;
+    std::vector<DevEntry> kept_steps_;
+    const DevEntry *kept_dev_ = nullptr;
+    uint64_t kept_version_ = 0;
+    int kept_depth_ = 1;
 };
 
 class RecordingBackend : public Backend {
@@ -750,6 +819,16 @@ static int pick_degree(int k, size_t object_bytes, double L, double B)
     return best;
 }
 
+// Launches over more than this many bytes per object keep partial results while a participant
+// can still fail (smaller ones would not repay a second launch and the extra arrays; it is
+// also the size up to which a long program may be cut into sub-programs instead).
+static constexpr size_t kRetainAboveBytes = 1u << 20;
+
+static void default_retention(Scheduler &s, const Shape &shape, int dtype)
+{
+    s.set_retention(true, (int64_t)(kRetainAboveBytes / shape.chunk_bytes) + 1, elem_bytes(dtype));
+}
+
 static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, int n, size_t object_bytes,
                          const int32_t *ready_order, int k, int op, int dtype, size_t chunk_bytes,
                          int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info,
@@ -769,6 +848,7 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
         GpuBackend be(device, (hipStream_t)stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype,
                       k, d, static_base, kStaticScratchBytes);
         Scheduler s(n, k, shape.n_chunks, d, &be);
+        default_retention(s, shape, dtype);
         return replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;
@@ -824,6 +904,8 @@ struct hop_session {
     std::unique_ptr<GpuBackend> be;             // sessions that enqueue work
     std::unique_ptr<RecordingBackend> rec;      // host-only sessions (hop_plan_session_begin)
     std::unique_ptr<Scheduler> sched;
+    size_t chunk_bytes = 16;
+    int dtype = HOP_F32;
 };
 
 static void copy_record(const RecordingBackend &be, hop_plan_launch_t *launches, int launch_capacity, int *n_launches,
@@ -837,8 +919,12 @@ static void copy_record(const RecordingBackend &be, hop_plan_launch_t *launches,
         entries[i].level = be.entries[i].level;
         entries[i].set = be.entries[i].set;
         entries[i].n_fold = be.entries[i].n_fold;
+        entries[i].save = be.entries[i].save;
+        entries[i].save_level = be.entries[i].save_level;
+        entries[i].reserved = 0;
     }
 }
+
 
 extern "C" {
 
@@ -1026,6 +1112,9 @@ int hop_session_begin(hop_session_t **s, void *dst, const void *const *objs, int
         h->be.reset(new GpuBackend(device, (hipStream_t)stream, objs, n, std::vector<void *>(1, dst), shape,
                                    (int)op, (int)dtype, k, d));
         h->sched.reset(new Scheduler(n, k, shape.n_chunks, d, h->be.get()));
+        default_retention(*h->sched, shape, (int)dtype);
+        h->chunk_bytes = chunk_bytes;
+        h->dtype = (int)dtype;
         *s = h.release();
         return HOP_OK;
     } catch (const std::bad_alloc &) {
@@ -1083,6 +1172,13 @@ int hop_session_set_eager(hop_session_t *s, int min_steps)
     return HOP_OK;
 }
 
+int hop_session_set_retention(hop_session_t *s, int on)
+{
+    if (!s) return HOP_ERR_INVALID;
+    s->sched->set_retention(on != 0, (int64_t)(kRetainAboveBytes / s->chunk_bytes) + 1, elem_bytes(s->dtype));
+    return HOP_OK;
+}
+
 int hop_session_set_adaptive(hop_session_t *s, int on)
 {
     if (!s) return HOP_ERR_INVALID;
@@ -1110,6 +1206,9 @@ int hop_plan_session_begin(hop_session_t **s, int n, size_t object_bytes, int k,
         std::unique_ptr<hop_session> h(new hop_session);
         h->rec.reset(new RecordingBackend);
         h->sched.reset(new Scheduler(n, k, shape.n_chunks, d, h->rec.get()));
+        default_retention(*h->sched, shape, (int)dtype);
+        h->chunk_bytes = chunk_bytes;
+        h->dtype = (int)dtype;
         *s = h.release();
         return HOP_OK;
     } catch (const std::bad_alloc &) {
@@ -1145,6 +1244,7 @@ int hop_plan_reduce(int n, size_t object_bytes, const int32_t *ready_order, int 
     try {
         RecordingBackend be;
         Scheduler s(n, k, shape.n_chunks, d, &be);
+        default_retention(s, shape, (int)dtype);
         rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
         copy_record(be, launches, launch_capacity, n_launches, entries, entry_capacity, n_entries);
         return rc;

@@ -143,6 +143,39 @@ struct Machine {
         }
     }
 
+    // The two halves of step(), for kernels that do something between a step's folds.
+    __device__ __forceinline__ void combine_at(uint32_t level, bool set, const A (&x)[W])
+    {
+#pragma unroll
+        for (int L = 0; L < D; ++L) {
+            if (level == (uint32_t)L) {
+                if (set) {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[L][w] = x[w];
+                } else {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[L][w] = combine<OP>(acc[L][w], x[w]);
+                }
+            }
+        }
+    }
+    // acc[level - 1] (op)= acc[level], count times, level by level downwards; returns the level reached
+    __device__ __forceinline__ uint32_t fold_down(uint32_t level, uint32_t count)
+    {
+        while (count) {
+#pragma unroll
+            for (int L = 1; L < D; ++L) {
+                if (level == (uint32_t)L) {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[L - 1][w] = combine<OP>(acc[L - 1][w], acc[L][w]);
+                }
+            }
+            --level;
+            --count;
+        }
+        return level;
+    }
+
     // G values, one after the other, into the accumulator of one level
     template <int G, class Get> __device__ __forceinline__ void run(uint32_t level, Get get)
     {
@@ -422,6 +455,136 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
             store_elem<DT>(dst, off, m.acc[0][0]);
         }
     }
+}
+
+// The reduce that keeps and reuses partial results (failure repair, section 3.5.2: the partial
+// results that do not contain the failed object survive). Same tiling as reduce_body, one step
+// at a time. A step whose control word carries kPartialBit reads a kept partial instead of an
+// object; a step with a save mark stores, once its folds have come down to the marked level,
+// that level's accumulator as a kept partial (array q of the kept area, a.spill + q *
+// a.level_stride: accumulator-typed values indexed like the object's elements, so the W
+// accumulators of a source vector lie side by side; laying a bf16 vector's two halves out in two
+// planes, which makes every store instruction cover consecutive addresses, measured 10 % slower:
+// twice as many write streams) and then finishes its folds. The next step's address and control
+// words are fetched while this step's data is in flight.
+template <int DT, int OP, int D, int VPT, int THREADS, class Prog>
+__device__ __forceinline__ void reduce_body_kept(const ReduceArgs &a, const Prog prog, const int n, void *const dst)
+{
+    using T = Traits<DT>;
+    using A = typename T::acc_t;
+    constexpr int W = T::W;
+    constexpr size_t kTile = (size_t)THREADS * VPT;
+    const int sl = a.piece_stride_log2;
+    const size_t lead = (size_t)a.lead_vecs, n_all = a.n_vec + lead;
+    const size_t n_tiles = sl < 0 ? (n_all + kTile - 1) / kTile : ((n_all + (kTile << sl) - 1) / (kTile << sl)) << sl;
+
+    for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        size_t off[VPT];
+        bool live[VPT];
+        size_t first = tile * kTile, step = THREADS;
+        if (sl >= 0) {
+            const size_t r = tile & (((size_t)1 << sl) - 1);
+            first = (((tile >> sl) * VPT) << sl) * THREADS + r * THREADS;
+            step = (size_t)THREADS << sl;
+            if (first >= n_all) continue;
+        }
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            const size_t v = first + (size_t)j * step + threadIdx.x;
+            live[j] = v >= lead && v < n_all;
+            off[j] = a.byte_begin + ((live[j] ? v : v < lead ? lead : n_all - 1) - lead) * 16;
+        }
+        Machine<DT, OP, D, VPT * W> m;
+        const void *src = prog[0].src;
+        uint32_t ctl = prog[0].ctl, aux = prog[0].aux;
+        for (int t = 0; t < n; ++t) {
+            A x[VPT * W];
+            uint4 raw[VPT];
+            const bool partial = (ctl & kPartialBit) != 0;
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) load_acc<DT>((const char *)src, off[j], &x[j * W]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) raw[j] = ld16(src, off[j]);
+            }
+            // look ahead (clamped to the last step, whose words are then simply read twice)
+            const int nx = t + 1 < n ? t + 1 : n - 1;
+            const void *src_n = prog[nx].src;
+            const uint32_t ctl_n = prog[nx].ctl, aux_n = prog[nx].aux;
+            asm volatile("" : : "s"(src_n), "s"(ctl_n), "s"(aux_n));
+            if (!partial) {
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) decode<DT>(raw[j], &x[j * W]);
+            }
+            uint32_t level = ctl & 0xffu, n_fold = ctl >> 16;
+            m.combine_at(level, (ctl >> 8) & 1u, x);
+            if (aux) {
+                const uint32_t keep_level = aux >> 16;
+                const uint32_t inner = level - keep_level;          // folds that stay inside the kept subtree
+                level = m.fold_down(level, inner);
+                n_fold -= inner;
+                char *base = a.spill + (size_t)((aux & 0xffffu) - 1) * a.level_stride;
+#pragma unroll
+                for (int L = 0; L < D; ++L) {
+                    if (keep_level == (uint32_t)L) {
+#pragma unroll
+                        for (int j = 0; j < VPT; ++j)
+                            if (live[j]) store_acc<DT>(base, off[j], &m.acc[L][j * W]);
+                    }
+                }
+            }
+            m.fold_down(level, n_fold);
+            src = src_n;
+            ctl = ctl_n;
+            aux = aux_n;
+        }
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            const uint4 out = encode<DT>(&m.acc[0][j * W]);
+            if (live[j]) st16(dst, off[j], out);
+        }
+    }
+
+    // ragged tail: fewer than 16 bytes at the very end of the object
+    if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail) {
+        const size_t off = a.byte_begin + a.n_vec * 16 + (size_t)threadIdx.x * T::ES;
+        const size_t acc_off = off / T::ES * sizeof(A);
+        Machine<DT, OP, D, 1> m;
+        for (int t = 0; t < n; ++t) {
+            const uint32_t ctl = prog[t].ctl, aux = prog[t].aux;
+            A x[1];
+            if (ctl & kPartialBit) x[0] = *(const A *)((const char *)prog[t].src + acc_off);
+            else x[0] = load_elem<DT>(prog[t].src, off);
+            uint32_t level = ctl & 0xffu, n_fold = ctl >> 16;
+            m.combine_at(level, (ctl >> 8) & 1u, x);
+            if (aux) {
+                const uint32_t keep_level = aux >> 16;
+                const uint32_t inner = level - keep_level;
+                level = m.fold_down(level, inner);
+                n_fold -= inner;
+                char *base = a.spill + (size_t)((aux & 0xffffu) - 1) * a.level_stride;
+#pragma unroll
+                for (int L = 0; L < D; ++L)
+                    if (keep_level == (uint32_t)L) *(A *)(base + acc_off) = m.acc[L][0];
+            }
+            m.fold_down(level, n_fold);
+        }
+        store_elem<DT>(dst, off, m.acc[0][0]);
+    }
+}
+
+// Program in device memory, steps that keep or read partial results (reduce_body_kept).
+template <int DT, int OP, int D, int VPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel_kept(ReduceArgs a)
+{
+    reduce_body_kept<DT, OP, D, VPT, THREADS>(a, (prog_ptr)(uintptr_t)a.prog, a.n_entries, a.dst);
+}
+// The same with the program inside the kernel arguments.
+template <int DT, int OP, int D, int VPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel_kept_inline(ReduceArgsInline a)
+{
+    reduce_body_kept<DT, OP, D, VPT, THREADS>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
 }
 
 // Program in device memory.

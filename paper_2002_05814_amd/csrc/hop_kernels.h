@@ -93,6 +93,14 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
                                  int n_entries, void *dst, char *spill, size_t level_stride, int n_restore,
                                  int n_save, size_t byte_begin, size_t byte_end, int lead_vecs = 0);
 
+// A whole program (n_entries steps in device memory) some of whose steps read kept partial results
+// (kPartialBit) or store one (aux): `kept` is the area of the kept partials, one array of 4-byte
+// accumulators per partial, indexed like the object's elements, level_stride bytes apart.
+// host_steps = the steps in host memory; with more than kInlineEntries of them dev_prog must hold them too.
+hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
+                              const DevEntry *dev_prog, int n_entries, void *dst, char *kept, size_t level_stride,
+                              size_t byte_begin, size_t byte_end);
+
 // The same for n_subs independent sub-programs at once: dev_records holds n_subs records of
 // sub_entries entries (SubHeader, steps, padding; 2 <= sub_entries <= kMaxSubSteps + 1); every
 // sub-program covers the same byte range and needs at most `depth` accumulator levels.

@@ -184,6 +184,46 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
     return hipGetLastError();
 }
 
+// Resident waves per compute unit for the launches that keep or reuse partial results (4 vectors per
+// lane, two steps' loads in flight per wave).
+constexpr int kKeptWavesPerCU = 8;
+constexpr unsigned kKeptLdsBytes = kLdsBytesPerCU / kKeptWavesPerCU / 256 * 256;
+
+hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
+                              const DevEntry *dev_prog, int n_entries, void *dst, char *kept, size_t level_stride,
+                              size_t byte_begin, size_t byte_end)
+{
+    if (byte_end <= byte_begin || n_entries <= 0) return hipSuccess;
+    if (!host_steps || !kept) return hipErrorInvalidValue;
+    const Launcher l = pick(dtype, op, depth);
+    ReduceArgsInline a;
+    a.base.prog = dev_prog;
+    a.base.n_entries = n_entries;
+    a.base.dst = dst;
+    a.base.sub_entries = 0;
+    fill_range(a.base, dtype, byte_begin, byte_end);
+    a.base.spill = kept;
+    a.base.level_stride = level_stride;
+    if (a.base.n_vec > 0) a.base.lead_vecs = lead_vectors(host_steps, n_entries, byte_begin);
+    // shaped like the long whole-program launches: pieces 64 KiB apart, few resident waves for the
+    // kernels that hold 4 vectors per lane
+    const size_t tiles4k = (a.base.n_vec + 255) / 256;
+    const bool strided = l.vpt >= 2 && tiles4k >= kMidLaunchTiles;
+    a.base.piece_stride_log2 = strided ? kPieceStrideLog2 : -1;
+    const unsigned lds = (l.vpt == 4 && tiles4k >= kCapLaunchTiles) ? kKeptLdsBytes : 0;
+    const size_t n_all = a.base.n_vec + (size_t)a.base.lead_vecs;
+    const unsigned grid = !strided ? grid_for(n_all, (size_t)kThreads * l.vpt)
+                                   : grid_for(n_all, ((size_t)kThreads * l.vpt) << kPieceStrideLog2) << kPieceStrideLog2;
+    if (n_entries <= kInlineEntries) {
+        for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
+        hipLaunchKernelGGL(l.kept_inl, dim3(grid), dim3(kThreads), lds, stream, a);
+    } else {
+        if (!dev_prog) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(l.kept, dim3(grid), dim3(kThreads), lds, stream, a.base);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
                               int sub_entries, int n_subs, size_t byte_begin, size_t byte_end)
 {

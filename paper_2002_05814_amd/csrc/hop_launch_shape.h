@@ -76,6 +76,8 @@ struct Launcher {
     void (*dev_mid)(ReduceArgs);
     void (*inl_mid)(ReduceArgsInline);
     void (*seg)(ReduceArgs);
+    void (*kept)(ReduceArgs);
+    void (*kept_inl)(ReduceArgsInline);
     int vpt;
 };
 

@@ -23,11 +23,20 @@ namespace hop {
 // One step of the per-element accumulator program (same meaning as
 // hop_plan_entry_t): read the element of object `obj`, start or extend the
 // partial result at `level`, then fold `n_fold` finished partials downwards.
+//
+// Two extensions serve the repair of failures (section 3.5.2: partial results that do not
+// contain the failed object are kept). obj = -(1 + q) reads kept partial q, an array of
+// accumulator-typed values, instead of an object. save = q >= 0: once the step's value is combined
+// and the folds have come down to save_level, acc[save_level] is also stored as kept partial q;
+// the remaining folds follow.
 struct Entry {
     int32_t obj;
     uint8_t level;
     uint8_t set;
     uint16_t n_fold;
+    int16_t save = -1;
+    uint8_t save_level = 0;
+    uint8_t reserved = 0;
 };
 
 // Complete d-ary tree on k nodes in level order; node_of_slot[t] is the node
@@ -89,9 +98,12 @@ struct Tree {
 // level and folded in when done, a later child without children (one object)
 // is combined into the parent's accumulator at once.
 // Returns the number of accumulator levels used (0 if nobody is in the tree).
-inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant, std::vector<Entry> &out)
+// slot_of_step (may be null) receives, per step, the tree position (arrival rank) whose occupant it reads.
+inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant, std::vector<Entry> &out,
+                           std::vector<int32_t> *slot_of_step = nullptr)
 {
     out.clear();
+    if (slot_of_step) slot_of_step->clear();
     const int k = tr.k;
     const int64_t d = tr.d;
     if (d == 1 || k == 1) {
@@ -99,6 +111,7 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
         for (int t = 0; t < k; ++t) {
             if (occupant[t] == -1) continue;
             out.push_back({occupant[t], 0, (uint8_t)out.empty(), 0});
+            if (slot_of_step) slot_of_step->push_back(t);
         }
         return out.empty() ? 0 : 1;
     }
@@ -106,12 +119,17 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
     // itself, so the next position in arrival order is simply a running counter. Most nodes
     // of a wide tree are leaves: they are emitted without a call.
     out.resize((size_t)k);
+    if (slot_of_step) slot_of_step->resize((size_t)k);
     struct Walk {
-        const int k; const int64_t d; const int32_t *occ; Entry *out; int n_out; int depth; int slot;
+        const int k; const int64_t d; const int32_t *occ; Entry *out; int n_out; int depth; int slot; int32_t *slots;
+        void emit(const Entry &e) {
+            if (slots) slots[n_out] = slot - 1;          // the position just read
+            out[n_out++] = e;
+        }
         bool leaf(int level) {
             const int32_t o = occ[slot++];
             if (o == -1) return false;
-            out[n_out++] = Entry{o, (uint8_t)level, 1, 0};
+            emit(Entry{o, (uint8_t)level, 1, 0});
             if (level + 1 > depth) depth = level + 1;
             return true;
         }
@@ -122,7 +140,7 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
             if (c1 < k) started = is_leaf(c1) ? leaf(level) : node(c1, level);
             const int32_t o = occ[slot++];
             if (o != -1) {                    // an object, or a position still to be taken
-                out[n_out++] = Entry{o, (uint8_t)level, (uint8_t)!started, 0};
+                emit(Entry{o, (uint8_t)level, (uint8_t)!started, 0});
                 if (level + 1 > depth) depth = level + 1;
                 started = true;
             }
@@ -135,16 +153,17 @@ inline int compile_program(const Tree &tr, const std::vector<int32_t> &occupant,
                     // a lone object joins its parent's partial directly: the same arithmetic as
                     // starting a partial of its own in the next level and folding it at once
                     const int32_t o = occ[slot++];
-                    if (o != -1) out[n_out++] = Entry{o, (uint8_t)level, 0, 0};
+                    if (o != -1) emit(Entry{o, (uint8_t)level, 0, 0});
                 } else if (node(ch, level + 1)) {     // at most log2(k) < 32 levels
                     out[n_out - 1].n_fold++;
                 }
             }
             return started;
         }
-    } w{k, d, occupant.data(), out.data(), 0, 0, 0};
+    } w{k, d, occupant.data(), out.data(), 0, 0, 0, slot_of_step ? slot_of_step->data() : nullptr};
     w.node(0, 0);
     out.resize((size_t)w.n_out);
+    if (slot_of_step) slot_of_step->resize((size_t)w.n_out);
     return w.depth;
 }
 
@@ -278,6 +297,10 @@ struct Backend {
     // Has everything launched so far been executed? Asked only by the adaptive policy, which
     // advances chunks part of the way only while the device would otherwise sit idle.
     virtual bool idle() { return true; }
+    // May launches keep up to n_partials partial results (one accumulator-typed array of object length
+    // each) beside the result? Asked once, before the first launch that would; a back end without
+    // the memory says no and failures are then repaired by producing the chunks again from scratch.
+    virtual bool keep_partials(int n_partials) { (void)n_partials; return true; }
     virtual int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1,
                        bool final, int live_before, int live_after) = 0;
 };
@@ -294,6 +317,27 @@ public:
     {
         tree_.shape(k, degree);
         done_.push_back({C_, 0, 0, false});
+        kept_.push_back({C_, 0});
+        gens_.emplace_back();
+        find_runs();
+    }
+
+    // Retention of partial results across failures (section 3.5.2: when a participant fails, only
+    // the partial results that contain its object are cleared). A launch that produces chunks
+    // while some participant in the tree is still streaming - and so can still fail - also stores,
+    // per element, the partial result of every subtree below the root (in the accumulation type,
+    // exactly the value the root's fold consumes). If a participant then fails, the chunks already
+    // produced are repaired by a launch that reads the kept partials of the untouched subtrees and
+    // re-reads only the objects of the subtree that changed and those directly below the root.
+    // Launches made when nobody can fail any more (every bulk call) keep nothing and cost nothing.
+    //   on          false: never keep anything (failures redo the produced chunks whole)
+    //   min_chunks  launches over fewer chunks keep nothing (too small to be worth a second array)
+    //   elem_bytes  size of a source element (a kept value takes 4 bytes)
+    void set_retention(bool on, int64_t min_chunks, int elem_bytes)
+    {
+        retain_ = on;
+        retain_min_chunks_ = min_chunks < 1 ? 1 : min_chunks;
+        elem_bytes_ = elem_bytes;
     }
 
     // 0 (default): a chunk is produced in one launch once all its inputs are present.
@@ -326,10 +370,7 @@ public:
             state_[obj] = COMPLETE;
             ready_[obj] = C_;
             if (next_free_ < k_) {
-                occupant_[next_free_] = obj;
-                slot_of_obj_[obj] = next_free_++;
-                version_++;
-                dirty_ = true;
+                place(obj, next_free_++);
             } else {
                 pool_.push_back(obj);
             }
@@ -372,6 +413,7 @@ public:
         if (t < 0) return HOP_OK;            // was waiting (or never arrived): skipped when the pool is popped
         slot_of_obj_[obj] = -1;
         occupant_[t] = -1;
+        touch_run(t);
         version_++;
         dirty_ = true;
         while (!pool_.empty() && state_[pool_.front()] == FAILED) pool_.pop_front();
@@ -419,13 +461,21 @@ public:
         // Walk the two staircases together; every piece where progress is allowed is a launch.
         const bool may_partial = eager_ > 0 && (!adaptive_ || be_->idle());
         bool held_back = false;
-        struct Piece { int64_t c0, c1; int t0, t1; int64_t redo; };
+        // act: what a whole-program launch does with the kept partials of its chunks (see run_actions);
+        // empty for launches that have nothing to do with them
+        struct Piece { int64_t c0, c1; int t0, t1; int64_t redo, redo_chunks; uint32_t gen; std::vector<int8_t> act; };
         std::vector<Piece> pieces;
         std::vector<Stair> next;
-        size_t i = 0, j = 0;
+        // runs may be kept or reused only by whole-program launches; everything known about the tree
+        const bool retention = retain_ && !keep_refused_ && !runs_.empty() && n_known_ == n_steps;
+        const bool exposed = retention && any_streaming();
+        std::vector<std::vector<int8_t>> act_of_gen(retention ? gens_.size() : 0);
+        std::vector<char> act_known(act_of_gen.size(), 0);
+        size_t i = 0, j = 0, m = 0;
         int64_t c = 0;
         while (c < C_) {
-            const int64_t end = std::min(done_[i].chunk_end, target[j].chunk_end);
+            int64_t end = std::min(done_[i].chunk_end, target[j].chunk_end);
+            if (retention) end = std::min(end, kept_[m].chunk_end);
             const int t0 = done_[i].t;
             int t1 = std::max(t0, target[j].t);
             const bool complete = (t1 == n_steps);
@@ -439,13 +489,28 @@ public:
             // saved accumulators (the program got shorter after these chunks had run ahead)
             if (t1 > t0 || (t0 == n_steps && !stored)) {
                 const int64_t again = std::max(0, std::min(t1, redo) - t0);
-                if (!pieces.empty() && pieces.back().c1 == c && pieces.back().t0 == t0 && pieces.back().t1 == t1) {
+                std::vector<int8_t> act;
+                uint32_t gen = 0;
+                if (retention && t0 == 0 && t1 == n_steps) {
+                    gen = kept_[m].gen;
+                    if (!act_known[gen]) {
+                        act_of_gen[gen] = run_actions(gen, exposed);
+                        act_known[gen] = 1;
+                    }
+                    act = act_of_gen[gen];
+                    bool any = false;
+                    for (int8_t a : act) any |= a != RUN_PLAIN;
+                    if (!any) act.clear();
+                }
+                if (!pieces.empty() && pieces.back().c1 == c && pieces.back().t0 == t0 && pieces.back().t1 == t1 &&
+                    pieces.back().act == act && (act.empty() || pieces.back().gen == gen)) {
                     pieces.back().c1 = end;
                     pieces.back().redo += again * (end - c);
+                    pieces.back().redo_chunks += again > 0 ? end - c : 0;
                 } else {
-                    pieces.push_back({c, end, t0, t1, again * (end - c)});
+                    pieces.push_back({c, end, t0, t1, again * (end - c), again > 0 ? end - c : 0, gen, act});
                 }
-                if (t1 >= redo) redo = 0;
+                if (t1 >= redo || t1 == n_steps) redo = 0;      // (the new program may be shorter than the one redone)
                 stored = (t1 == n_steps);
             }
             if (!next.empty() && next.back().t == t1 && next.back().redo == redo && next.back().stored == stored)
@@ -455,9 +520,52 @@ public:
             c = end;
             if (done_[i].chunk_end == end) ++i;
             if (target[j].chunk_end == end) ++j;
+            if (retention && kept_[m].chunk_end == end) ++m;
         }
-        for (const Piece &p : pieces) {
+        for (Piece &p : pieces) {
             const bool final = (p.t1 == n_steps);
+            // launches too short to be worth a kept array store nothing (they may still read)
+            if (!p.act.empty() && p.c1 - p.c0 < retain_min_chunks_) {
+                bool any = false;
+                for (int8_t &a : p.act) {
+                    if (a == RUN_SAVE) a = RUN_PLAIN;
+                    any |= a != RUN_PLAIN;
+                }
+                if (!any) p.act.clear();
+            }
+            if (!p.act.empty() && !keep_asked_) {
+                keep_asked_ = true;
+                keep_refused_ = !be_->keep_partials((int)runs_.size());
+            }
+            if (!p.act.empty() && !keep_refused_) {
+                std::vector<Entry> rp;
+                int n_reuse = 0, n_save = 0;
+                retained_program(p.act, rp, &n_reuse, &n_save);
+                rc = be_->launch(rp, (uint64_t(1) << 63) | ++aux_version_, p.c0, p.c1, 0, (int)rp.size(), true, 0, 0);
+                if (rc < 0) return rc;
+                const int64_t chunks = p.c1 - p.c0, n_obj = (int64_t)rp.size() - n_reuse;
+                info_.n_launches++;
+                info_.chunks_redone += n_reuse > 0 ? p.redo_chunks * n_obj : p.redo;
+                info_.chunk_steps += chunks * n_obj;
+                info_.chunk_stores += chunks;
+                info_.partial_loads += chunks * n_reuse;
+                info_.partial_stores += chunks * n_save;
+                // what these chunks hold now: the partials just stored, and the older ones still valid
+                std::vector<uint32_t> now(runs_.size(), 0);
+                const std::vector<uint32_t> had = gens_[p.gen];
+                bool any = false;
+                for (size_t r = 0; r < runs_.size(); ++r) {
+                    now[r] = p.act[r] == RUN_SAVE ? run_ver_[r] : (had[r] == run_ver_[r] ? had[r] : 0);
+                    any |= now[r] != 0;
+                }
+                uint32_t g = 0;
+                if (any) {
+                    for (g = 1; g < gens_.size() && gens_[g] != now; ++g) {}
+                    if (g == gens_.size()) gens_.push_back(now);
+                }
+                assign_kept(p.c0, p.c1, g);
+                continue;
+            }
             rc = be_->launch(prog_, version_, p.c0, p.c1, p.t0, p.t1, final, live_levels(p.t0), final ? 0 : live_levels(p.t1));
             if (rc < 0) return rc;
             info_.n_launches++;
@@ -507,6 +615,8 @@ public:
     bool arrived(int obj) const { return state_[obj] != UNSEEN; }
     bool alive(int obj) const { return state_[obj] == STREAMING || state_[obj] == COMPLETE; }
     const Tree &tree() const { return tree_; }
+    // who holds each tree position now (-1 = empty)
+    const std::vector<int32_t> &occupants() const { return occupant_; }
 
 private:
     enum State : uint8_t { UNSEEN, STREAMING, COMPLETE, FAILED };
@@ -518,8 +628,134 @@ private:
     {
         occupant_[t] = obj;
         slot_of_obj_[obj] = t;
+        touch_run(t);
         version_++;
         dirty_ = true;
+    }
+
+    // ---- kept partial results -------------------------------------------------------------
+
+    // The subtrees below the root with more than one node, as ranges of tree positions (in-order
+    // numbering makes a subtree a contiguous range of arrivals): the first child's subtree, then the
+    // root, then the other children's subtrees, then the root's childless children.
+    void find_runs()
+    {
+        const int64_t d = tree_.d;
+        if (d < 2 || k_ < 3) return;
+        auto subtree_size = [&](int64_t j) {
+            int64_t size = 0, first = j, last = j;
+            while (first < k_) {
+                size += std::min<int64_t>(last, k_ - 1) - first + 1;
+                if (first > (INT64_MAX - 1) / d) break;
+                first = d * first + 1;
+                last = (last > (INT64_MAX - d) / d) ? INT64_MAX : d * last + d;
+            }
+            return size;
+        };
+        int64_t slot = 0;
+        for (int64_t c = 1; c <= d && c < k_; ++c) {
+            const int64_t size = subtree_size(c);
+            if (size >= 2) {
+                if ((int)runs_.size() == kMaxKept) { runs_.clear(); return; }      // too many arrays to keep: keep none
+                runs_.push_back({(int)slot, (int)(slot + size)});
+            }
+            slot += size;
+            if (c == 1) ++slot;             // the root itself comes right after its first child's subtree
+        }
+        run_of_slot_.assign((size_t)k_, -1);
+        for (size_t r = 0; r < runs_.size(); ++r)
+            for (int t = runs_[r].slot_begin; t < runs_[r].slot_end; ++t) run_of_slot_[(size_t)t] = (int16_t)r;
+        run_ver_.assign(runs_.size(), 1);
+        gens_[0].assign(runs_.size(), 0);
+    }
+
+    void touch_run(int t)
+    {
+        if (run_of_slot_.empty()) return;
+        const int r = run_of_slot_[(size_t)t];
+        if (r >= 0) run_ver_[(size_t)r]++;
+    }
+
+    bool any_streaming() const
+    {
+        for (int t = 0; t < k_; ++t)
+            if (occupant_[t] >= 0 && state_[occupant_[t]] == STREAMING) return true;
+        return false;
+    }
+
+    // What a whole-program launch over chunks whose kept partials are generation `gen` does with
+    // every run: 0 nothing, 1 read its kept partial instead of its objects, 2 store its partial.
+    enum : int8_t { RUN_PLAIN = 0, RUN_REUSE = 1, RUN_SAVE = 2 };
+    std::vector<int8_t> run_actions(uint32_t gen, bool may_save) const
+    {
+        std::vector<int8_t> act(runs_.size(), RUN_PLAIN);
+        if (runs_.empty() || !retain_ || keep_refused_) return act;
+        const std::vector<uint32_t> &have = gens_[gen];
+        int n_save = 0;
+        for (size_t r = 0; r < runs_.size(); ++r) {
+            const int len = run_steps_[r].second - run_steps_[r].first;
+            // worth it only if the kept value (4 bytes) is smaller than what it stands for
+            if (len < 1 || len * elem_bytes_ <= 4 || !prog_[(size_t)run_steps_[r].first].set) continue;
+            if (have[r] != 0 && have[r] == run_ver_[r]) { act[r] = RUN_REUSE; continue; }
+            if (may_save) { act[r] = RUN_SAVE; ++n_save; }
+        }
+        // keeping must stay a side cost: at most a quarter of what the launch reads anyway
+        if ((int64_t)n_save * 4 * 4 > (int64_t)prog_.size() * elem_bytes_)
+            for (int8_t &a : act) if (a == RUN_SAVE) a = RUN_PLAIN;
+        return act;
+    }
+
+    // prog_ with the runs treated as act says
+    void retained_program(const std::vector<int8_t> &act, std::vector<Entry> &out, int *n_reuse, int *n_save) const
+    {
+        out.clear();
+        out.reserve(prog_.size());
+        *n_reuse = *n_save = 0;
+        size_t r = 0;
+        for (int i = 0; i < (int)prog_.size();) {
+            while (r < runs_.size() && run_steps_[r].second <= i) ++r;
+            if (r < runs_.size() && run_steps_[r].first == i && run_steps_[r].second > i && act[r] != RUN_PLAIN) {
+                const int i0 = run_steps_[r].first, i1 = run_steps_[r].second;
+                const Entry &first = prog_[(size_t)i0], &last = prog_[(size_t)i1 - 1];
+                const int internal = (int)last.level - (int)first.level;       // folds of the last step that stay inside the run
+                if (act[r] == RUN_REUSE) {
+                    // the partial starts the run's accumulator; the folds that carried the run's value
+                    // further down follow as before
+                    Entry e{-(1 + (int32_t)r), first.level, 1, (uint16_t)((int)last.n_fold - internal)};
+                    out.push_back(e);
+                    ++*n_reuse;
+                } else {
+                    for (int t = i0; t < i1; ++t) out.push_back(prog_[(size_t)t]);
+                    out.back().save = (int16_t)r;
+                    out.back().save_level = first.level;
+                    ++*n_save;
+                }
+                i = i1;
+                continue;
+            }
+            out.push_back(prog_[(size_t)i]);
+            ++i;
+        }
+    }
+
+    void assign_kept(int64_t c0, int64_t c1, uint32_t gen)
+    {
+        std::vector<Kept> next;
+        int64_t begin = 0;
+        auto put = [&](int64_t end, uint32_t g) {
+            if (end <= begin) return;
+            if (!next.empty() && next.back().gen == g) next.back().chunk_end = end;
+            else next.push_back({end, g});
+            begin = end;
+        };
+        for (const Kept &kp : kept_) {
+            const int64_t lo = begin, hi = kp.chunk_end;
+            if (hi <= c0 || lo >= c1) { put(hi, kp.gen); continue; }
+            if (lo < c0) put(c0, kp.gen);
+            put(std::min(hi, c1), gen);
+            if (hi > c1) put(hi, kp.gen);
+        }
+        kept_.swap(next);
     }
 
     // accumulator levels alive between steps t-1 and t
@@ -540,7 +776,7 @@ private:
         if (!closing_)
             for (int t = next_free_; t < k_; ++t) occ[t] = kPending;
         std::vector<Entry> np;
-        const int depth = compile_program(tree_, occ, np);
+        const int depth = compile_program(tree_, occ, np, runs_.empty() ? nullptr : &slot_of_step_);
         info_.stack_depth = std::max(info_.stack_depth, depth);
         if (depth > HOP_MAX_DEPTH) return HOP_ERR_DEPTH;
         int keep = 0;
@@ -564,6 +800,14 @@ private:
         }
         done_.swap(next);
         prog_.swap(np);
+        // where every run's steps are (positions inside a run are consecutive steps; empty ones emit nothing)
+        run_steps_.assign(runs_.size(), std::make_pair(0, 0));
+        for (size_t r = 0, i = 0; r < runs_.size(); ++r) {
+            while (i < slot_of_step_.size() && slot_of_step_[i] < runs_[r].slot_begin) ++i;
+            run_steps_[r].first = (int)i;
+            while (i < slot_of_step_.size() && slot_of_step_[i] < runs_[r].slot_end) ++i;
+            run_steps_[r].second = (int)i;
+        }
         n_known_ = 0;
         while (n_known_ < (int)prog_.size() && prog_[n_known_].obj != kPending) ++n_known_;
         compiled_version_ = version_;
@@ -584,6 +828,20 @@ private:
     bool dirty_ = false;                 // something changed that a pump could act on
     int eager_ = 0;
     bool adaptive_ = false;
+    struct Run { int slot_begin, slot_end; };
+    struct Kept { int64_t chunk_end; uint32_t gen; };
+    static constexpr int kMaxKept = 16;
+    std::vector<Run> runs_;                          // subtrees below the root, as ranges of positions
+    std::vector<int16_t> run_of_slot_;
+    std::vector<uint32_t> run_ver_;                  // changes whenever an occupant inside the run changes
+    std::vector<std::pair<int, int>> run_steps_;     // the run's steps in prog_: [first, second)
+    std::vector<Kept> kept_;                         // chunks [previous end, chunk_end) hold the partials of generation gen
+    std::vector<std::vector<uint32_t>> gens_;        // per generation and run: run_ver_ when its partial was stored, 0 = none
+    bool retain_ = true, keep_asked_ = false, keep_refused_ = false;
+    int64_t retain_min_chunks_ = 1;
+    int elem_bytes_ = 4;
+    std::vector<int32_t> slot_of_step_;
+    uint64_t aux_version_ = 0;                       // names the programs built by retained_program
     std::vector<Stair> done_;            // progress of every chunk through prog_
     uint64_t version_ = 1, compiled_version_ = 0;
     std::vector<Entry> prog_;

@@ -9,11 +9,14 @@ namespace hop {
 
 // One accumulator-program step as the kernel reads it (16 bytes, so that a
 // step is one scalar 128-bit load): the source object's base address and
-// ctl = level | set << 8 | run << 9 | n_fold << 16 (run: see kRunBit).
+// ctl = level | set << 8 | run << 9 | partial << 10 | n_fold << 16 (run: see kRunBit;
+// partial: see kPartialBit). aux is read only by the kernels that keep or reuse partial
+// results: 0, or (1 + q) | save_level << 16 = once the folds of this step have come down to
+// save_level, acc[save_level] is also stored as kept partial q.
 struct DevEntry {
     const void *src;
     uint32_t ctl;
-    uint32_t reserved;
+    uint32_t aux;
 };
 static_assert(sizeof(DevEntry) == 16, "program steps are 16 bytes");
 
@@ -24,6 +27,9 @@ static_assert(sizeof(DevEntry) == 16, "program steps are 16 bytes");
 // which is most of the per-step instruction count for programs over many small objects (a node
 // with 16 leaf children is a run of 16 such steps). Kernels with other group sizes ignore the bit.
 constexpr uint32_t kRunBit = 1u << 9;
+// Bit 10 of ctl: src is not an object but an array of accumulator-typed values, one per element
+// (4 bytes each whatever the element type): a kept partial result.
+constexpr uint32_t kPartialBit = 1u << 10;
 constexpr int kRunSteps = 8;
 inline void mark_runs(DevEntry *steps, size_t n)
 {

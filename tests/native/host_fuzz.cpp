@@ -14,13 +14,56 @@
 
 using namespace hop;
 
+// Evaluates every launch symbolically, chunk by chunk: accumulators, saved accumulators and kept
+// partial results are expressions written out as strings, so that at the end every chunk's stored
+// result can be compared, parenthesis for parenthesis, with the expression of the final tree.
+static std::string sym_eval(const std::vector<Entry> &prog, int t0, int t1, std::vector<std::string> acc,
+                            const std::vector<std::string> *kept_of_chunk, std::vector<std::string> *kept_out,
+                            std::vector<std::string> *acc_out)
+{
+    acc.resize(HOP_MAX_DEPTH + 1);
+    for (int t = t0; t < t1; ++t) {
+        const Entry &e = prog[(size_t)t];
+        std::string x;
+        if (e.obj >= 0) x = "o" + std::to_string(e.obj);
+        else {
+            const size_t q = (size_t)(-e.obj - 1);
+            if (!kept_of_chunk || q >= kept_of_chunk->size() || (*kept_of_chunk)[q].empty()) { std::printf("reads a partial that was never kept\n"); std::abort(); }
+            x = (*kept_of_chunk)[q];
+        }
+        int level = e.level, n_fold = e.n_fold;
+        acc[(size_t)level] = e.set ? x : "(" + acc[(size_t)level] + "+" + x + ")";
+        auto fold = [&]() { acc[(size_t)level - 1] = "(" + acc[(size_t)level - 1] + "+" + acc[(size_t)level] + ")"; acc[(size_t)level].clear(); --level; --n_fold; };
+        if (e.save >= 0) {
+            if (e.save_level > e.level || (int)e.level - (int)e.save_level > n_fold) { std::printf("save level\n"); std::abort(); }
+            while (level > (int)e.save_level) fold();
+            if (!kept_out || (size_t)e.save >= kept_out->size()) { std::printf("keeps where nothing can be kept\n"); std::abort(); }
+            (*kept_out)[(size_t)e.save] = acc[(size_t)level];
+        }
+        while (n_fold > 0) fold();
+    }
+    if (acc_out) *acc_out = acc;
+    return acc[0];
+}
+
 struct CheckingBackend : Backend {
     int64_t C = 0;
     std::mt19937_64 *rng = nullptr;      // when set: the device is "busy" at random
     bool idle() override { return !rng || ((*rng)() & 1u); }
+    bool refuse_keeping = false;
+    int n_partials = 0;
+    bool keep_partials(int n) override
+    {
+        if (n < 1 || n > 16) { std::printf("asks to keep %d partials\n", n); std::abort(); }
+        n_partials = n;
+        return !refuse_keeping;
+    }
     std::vector<int> steps_done;        // per chunk: steps whose accumulators are saved, or -1 if the result is stored
+    std::vector<std::vector<std::string>> saved;      // per chunk: accumulators saved by the last segment
+    std::vector<std::vector<std::string>> kept;       // per chunk: kept partial results
+    std::vector<std::string> result;                  // per chunk: what was stored
     uint64_t last_version = 0;
-    long launches = 0;
+    long launches = 0, kept_reads = 0, kept_writes = 0;
     int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
                int live_before, int live_after) override
     {
@@ -28,10 +71,17 @@ struct CheckingBackend : Backend {
         if (!(0 <= t0 && t0 <= t1 && t1 <= (int)prog.size())) { std::printf("bad step range\n"); std::abort(); }
         if (final != (t1 == (int)prog.size())) { std::printf("final flag\n"); std::abort(); }
         if (t0 == t1 && !(final && t0 > 0)) { std::printf("empty launch\n"); std::abort(); }
-        if (version < last_version) { std::printf("version went back\n"); std::abort(); }
-        last_version = version;
-        for (int t = t0; t < t1; ++t)
-            if (prog[(size_t)t].obj < 0) { std::printf("step without an object\n"); std::abort(); }
+        const bool aux = (version >> 63) != 0;       // a program built for keeping / reusing partials
+        if (!aux) {
+            if (version < last_version) { std::printf("version went back\n"); std::abort(); }
+            last_version = version;
+        }
+        for (int t = t0; t < t1; ++t) {
+            const Entry &e = prog[(size_t)t];
+            if ((e.obj < 0 || e.save >= 0) && !(aux && t0 == 0 && final && n_partials > 0 && !refuse_keeping)) { std::printf("partial in a plain launch\n"); std::abort(); }
+            kept_reads += e.obj < 0;
+            kept_writes += e.save >= 0;
+        }
         // accumulator bookkeeping: what is restored must be what was saved
         int level = t0 > 0 ? (int)prog[(size_t)t0 - 1].level - (int)prog[(size_t)t0 - 1].n_fold : -1;
         if (live_before != level + 1) { std::printf("live_before\n"); std::abort(); }
@@ -46,6 +96,12 @@ struct CheckingBackend : Backend {
             const int have = steps_done[(size_t)c];
             if (t0 == 0 ? false : have != t0) { std::printf("resume from %d but chunk has %d\n", t0, have); std::abort(); }
             steps_done[(size_t)c] = final ? -1 : t1;
+            std::vector<std::string> acc(t0 > 0 ? saved[(size_t)c] : std::vector<std::string>()), after;
+            kept[(size_t)c].resize(16);
+            const std::vector<std::string> before(kept[(size_t)c]);
+            const std::string r = sym_eval(prog, t0, t1, acc, &before, &kept[(size_t)c], &after);
+            if (final) result[(size_t)c] = r;
+            else saved[(size_t)c] = after;
         }
         ++launches;
         return HOP_OK;
@@ -119,7 +175,7 @@ static void check_marks(const std::vector<Entry> &prog)
     for (size_t t = 0; t < prog.size(); ++t) {
         p[t].src = (const void *)(uintptr_t)(t + 1);
         p[t].ctl = (uint32_t)prog[t].level | ((uint32_t)prog[t].set << 8) | ((uint32_t)prog[t].n_fold << 16);
-        p[t].reserved = 0;
+        p[t].aux = 0;
     }
     const std::string plain = walk(p, false);
     mark_runs(p.data(), p.size());
@@ -138,7 +194,7 @@ int main(int argc, char **argv)
     const int rounds = argc > 1 ? std::atoi(argv[1]) : 3000;
     std::mt19937_64 rng(12345);
     auto rnd = [&](int lo, int hi) { return lo + (int)(rng() % (uint64_t)(hi - lo + 1)); };
-    long total_launches = 0;
+    long total_launches = 0, total_kept_reads = 0, total_kept_writes = 0;
     for (int r = 0; r < rounds; ++r) {
         const int n = rnd(1, 40), k = rnd(1, n);
         const int degs[] = {1, 2, 3, 4, 8, 16, n + 1};
@@ -147,8 +203,13 @@ int main(int argc, char **argv)
         CheckingBackend be;
         be.C = C;
         be.steps_done.assign((size_t)C, 0);
+        be.saved.assign((size_t)C, {});
+        be.kept.assign((size_t)C, {});
+        be.result.assign((size_t)C, "");
+        be.refuse_keeping = rnd(0, 9) == 0;
         Scheduler s(n, k, C, d, &be);
-        s.set_eager(rnd(0, 3));
+        s.set_retention(rnd(0, 4) != 0, rnd(1, 3), rnd(0, 1) ? 4 : 2);
+        s.set_eager(rnd(0, 3) ? 0 : rnd(1, 3));
         if (rnd(0, 2) == 0) { be.rng = &rng; s.set_adaptive(true); }
         std::vector<int> order((size_t)n);
         for (int i = 0; i < n; ++i) order[(size_t)i] = i;
@@ -190,6 +251,20 @@ int main(int argc, char **argv)
             for (int64_t c = 0; c < C; ++c)
                 if (be.steps_done[(size_t)c] != -1) { std::printf("chunk %ld not stored (round %d)\n", (long)c, r); std::abort(); }
             if (info.k_eff < 1 || info.k_eff > k || (rc == HOP_OK) != (info.k_eff == k)) std::abort();
+            // every chunk holds the expression of the final tree, whatever was kept and reused on the way
+            Tree ft;
+            ft.shape(k, d);
+            std::vector<Entry> fp;
+            compile_program(ft, s.occupants(), fp);
+            const std::string want = sym_eval(fp, 0, (int)fp.size(), {}, nullptr, nullptr, nullptr);
+            for (int64_t c = 0; c < C; ++c)
+                if (be.result[(size_t)c] != want) {
+                    std::printf("round %d chunk %ld holds %s, the tree says %s\n", r, (long)c, be.result[(size_t)c].c_str(), want.c_str());
+                    std::abort();
+                }
+            if (info.partial_loads < 0 || (info.partial_loads > 0) != (be.kept_reads > 0) || (info.partial_stores > 0) != (be.kept_writes > 0)) std::abort();
+            total_kept_reads += be.kept_reads;
+            total_kept_writes += be.kept_writes;
         } else if (rc != HOP_ERR_NO_SURVIVOR) {
             std::printf("unexpected status %d\n", rc);
             std::abort();
@@ -207,6 +282,7 @@ int main(int argc, char **argv)
         { const int lo = rnd(1, 6); plan_passes(prog, (size_t)rnd(1, 40), lo, lo + rnd(0, 30), mp); }
         fuzz_bcast(rng);
     }
-    std::printf("ok %d sessions, %ld launches\n", rounds, total_launches);
+    if (rounds >= 1000 && (total_kept_reads < 50 || total_kept_writes < 200)) { std::printf("keeping was hardly exercised: %ld reads, %ld writes\n", total_kept_reads, total_kept_writes); return 1; }
+    std::printf("ok %d sessions, %ld launches, %ld partials kept, %ld reused\n", rounds, total_launches, total_kept_writes, total_kept_reads);
     return 0;
 }

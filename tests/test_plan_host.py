@@ -34,10 +34,10 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_info_struct_layout_matches_header():
-    # int32 x4, int64, int32 x2, int64 x2 -> 48 bytes with natural alignment
-    assert ctypes.sizeof(hop.HopInfo) == 48
-    assert hop.HopInfo.chunks_redone.offset == 16
-    assert ctypes.sizeof(hop.PlanEntry) == 8 and ctypes.sizeof(hop.PlanLaunch) == 48
+    # int32 x4, int64, int32 x2, int64 x4 -> 64 bytes with natural alignment
+    assert ctypes.sizeof(hop.HopInfo) == 64
+    assert hop.HopInfo.chunks_redone.offset == 16 and hop.HopInfo.partial_stores.offset == 56
+    assert ctypes.sizeof(hop.PlanEntry) == 12 and ctypes.sizeof(hop.PlanLaunch) == 48
 
 
 @pytest.mark.parametrize("d", [1, 2, 3, 4, 8, 16, 1 << 20])
@@ -55,20 +55,43 @@ def interpret(objs, launches, entries, n_elems, chunk_elems, op):
     f = NP_OP[op]
     dst = np.zeros(n_elems, objs[0].dtype)
     spill = {}
+    kept = {}                # q -> array of kept partial results; NaN / a marker where nothing was kept
     for c0, c1, e0, e1, t0, t1, final, live_before, live_after in launches:
         seg = slice(c0 * chunk_elems, min(c1 * chunk_elems, n_elems))
         prog = entries[e0:e1]
         assert 0 <= t0 <= t1 <= len(prog) and (final == (t1 == len(prog))) and (t0 < t1 or final)
         assert (live_before == 0) == (t0 == 0)
         acc = {L: spill[L][seg].copy() for L in range(live_before)}
-        for obj, level, is_set, n_fold in prog[t0:t1]:
-            assert obj >= 0
-            x = objs[obj][seg]
+        stored_now = {}
+        for e in prog[t0:t1]:
+            obj, level, is_set, n_fold = e[:4]
+            if obj >= 0:
+                x = objs[obj][seg]
+            else:
+                # a kept partial result: it must have been stored for every one of these chunks by an
+                # earlier launch (never by this one)
+                assert t0 == 0 and final
+                have, x = kept[-obj - 1]
+                assert have[c0:c1].all(), "reads a partial that was never kept"
+                x = x[seg]
             acc[level] = x.copy() if is_set else f(acc[level], x).astype(x.dtype)
+            if len(e) > 4:
+                q, save_level = e[4], e[5]
+                assert t0 == 0 and final and save_level <= level and level - save_level <= n_fold
+                while level > save_level:
+                    acc[level - 1] = f(acc[level - 1], acc[level]).astype(x.dtype)
+                    del acc[level]
+                    level -= 1
+                    n_fold -= 1
+                stored_now[q] = acc[level].copy()
             for _ in range(n_fold):
                 acc[level - 1] = f(acc[level - 1], acc[level]).astype(x.dtype)
                 del acc[level]
                 level -= 1
+        for q, val in stored_now.items():
+            have, arr = kept.setdefault(q, (np.zeros(max(c1, 1) + 10 ** 6, bool), np.zeros(n_elems, objs[0].dtype)))
+            have[c0:c1] = True
+            arr[seg] = val
         if final:
             assert list(acc) == [0] and live_after == 0
             dst[seg] = acc[0]
@@ -95,13 +118,24 @@ def random_case(rng, max_n=14, with_fail=True):
     return n, k, d, chunk_elems, n_elems, order, fm
 
 
+# The schedule is in units of chunks, so the same plan can be made for objects 2^18 times as large
+# (chunks of megabytes instead of bytes) and still be interpreted on the small arrays: that is how the
+# tests here reach the policies that depend on the size of a launch (partial results are kept only by
+# launches over more than 1 MiB per object).
+BIG = 1 << 18
+
+
 @pytest.mark.parametrize("op", ["sum", "max", "min"])
-def test_interpreted_plan_equals_oracle_f32(op):
-    rng = np.random.default_rng({"sum": 1, "max": 2, "min": 3}[op])
+@pytest.mark.parametrize("scale", [1, BIG])
+def test_interpreted_plan_equals_oracle_f32(op, scale):
+    rng = np.random.default_rng({"sum": 1, "max": 2, "min": 3}[op] + (scale > 1) * 10)
+    n_kept = n_reused = 0
     for _ in range(300):
-        n, k, d, ce, E, order, fm = random_case(rng)
+        n, k, d, ce, E, order, fm = random_case(rng, max_n=14 if scale == 1 else 30)
         objs = [(rng.standard_normal(E) * 10.0 ** rng.integers(-3, 4)).astype(np.float32) for _ in range(n)]
-        rc, info, launches, entries = hop.hop_plan_reduce(n, E * 4, k, "f32", ce * 4, d, order, fm)
+        rc, info, launches, entries = hop.hop_plan_reduce(n, E * 4 * scale, k, "f32", ce * 4 * scale, d, order, fm)
+        n_kept += info["partial_stores"] > 0
+        n_reused += info["partial_loads"] > 0
         orc, want, k_eff, n_rep = oracle.reduce(objs, k, ORA_OP[op], oracle.F32, ce, d, order, fm)
         assert rc == orc, (rc, orc)
         if rc < 0:
@@ -112,8 +146,11 @@ def test_interpreted_plan_equals_oracle_f32(op):
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
         # every object in the final program exactly once; k_eff of them
         final = entries[launches[-1][2]:launches[-1][3]]
-        assert launches[-1][6] == 1 and len(final) == k_eff and len({e[0] for e in final}) == k_eff
-        assert max(e[1] for e in final) + 1 <= info["stack_depth"] <= hop.HOP_MAX_DEPTH
+        assert launches[-1][6] == 1 and max(e[1] for e in final) + 1 <= info["stack_depth"] <= hop.HOP_MAX_DEPTH
+        if not any(e[0] < 0 for e in final):
+            assert len(final) == k_eff and len({e[0] for e in final}) == k_eff
+    # small launches never keep anything; large ones with mid-stream failures do, and reuse it
+    assert (n_kept, n_reused) == (0, 0) if scale == 1 else (n_kept > 20 and n_reused > 10), (n_kept, n_reused)
 
 
 def test_interpreted_plan_equals_oracle_i32_wrapping():
@@ -121,7 +158,8 @@ def test_interpreted_plan_equals_oracle_i32_wrapping():
     for _ in range(100):
         n, k, d, ce, E, order, fm = random_case(rng)
         objs = [rng.integers(-2 ** 31, 2 ** 31, size=E, dtype=np.int64).astype(np.int32) for _ in range(n)]
-        rc, info, launches, entries = hop.hop_plan_reduce(n, E * 4, k, "i32", ce * 4, d, order, fm)
+        scale = BIG if _ % 2 else 1
+        rc, info, launches, entries = hop.hop_plan_reduce(n, E * 4 * scale, k, "i32", ce * 4 * scale, d, order, fm)
         orc, want, _, _ = oracle.reduce(objs, k, oracle.SUM, oracle.I32, ce, d, order, fm)
         assert rc == orc
         if rc < 0:
@@ -228,31 +266,54 @@ def test_failure_free_call_is_one_launch_over_all_chunks():
     assert depths[3][1] in (1, 2, 64)
 
 
-def test_mid_stream_failure_redoes_only_the_chunks_already_produced():
+def test_mid_stream_failure_repairs_from_kept_subtree_partials():
     w = workloads.WORKLOADS[4]          # participant 7 fails after its 10th chunk of 32
     rc, info, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
                                                       w.tree_degree, w.ready_order(), w.fail_mask())
     assert rc == hop.HOP_PARTIAL and info["k_eff"] == 31 and info["n_failed_seen"] == 1
     assert info["n_replaced"] == 0 and info["stack_depth"] == 2
-    # chunks 0..9 were produced with all 32 participants, then everything is produced without #7
-    assert [(l[0], l[1]) for l in launches] == [(0, 10), (0, 32)]
-    first = entries[launches[0][2]:launches[0][3]]
-    second = entries[launches[1][2]:launches[1][3]]
+    # chunks 0..9 are produced with all 32 participants while any of them can still fail: the launch
+    # also keeps the partial results of the three subtrees below the root (9, 9 and 8 arrivals). #7 is
+    # the 29th arrival, a childless child of the root: the repair of chunks 0..9 reads the three kept
+    # partials, the root's own object and its four remaining childless children; chunks 10..31 are
+    # produced from the 31 survivors.
+    assert [(l[0], l[1]) for l in launches] == [(0, 10), (0, 10), (10, 32)]
+    first, repair, rest = (entries[l[2]:l[3]] for l in launches)
     assert len(first) == 32 and 7 in {e[0] for e in first}
-    assert len(second) == 31 and 7 not in {e[0] for e in second}
-    assert info["chunks_redone"] == 10 * 31 and info["n_launches"] == 2
-    assert info["chunk_steps"] == 10 * 32 + 32 * 31 and info["chunk_stores"] == 10 + 32
+    assert [e[4] for e in first if len(e) > 4] == [0, 1, 2] and [first.index(e) for e in first if len(e) > 4] == [8, 18, 26]
+    assert [e[0] for e in repair if e[0] < 0] == [-1, -2, -3] and len(repair) == 3 + 1 + 4
+    assert 7 not in {e[0] for e in repair} and all(len(e) == 4 for e in repair + rest)
+    assert len(rest) == 31 and 7 not in {e[0] for e in rest}
+    assert info["n_launches"] == 3 and info["chunks_redone"] == 10 * 5
+    assert info["chunk_steps"] == 10 * 32 + 10 * 5 + 22 * 31 and info["chunk_stores"] == 10 + 10 + 22
+    assert info["partial_stores"] == 10 * 3 and info["partial_loads"] == 10 * 3
     # the survivors keep their relative order
-    assert [e[0] for e in second] == [e[0] for e in first if e[0] != 7]
+    assert [e[0] for e in rest] == [e[0] for e in first if e[0] != 7]
     # the failure time changes the repair work, never the final program
     for c in (1, 5, 31):
         fm = w.fail_mask().copy()
         fm[7] = c
         _, info_c, launches_c, entries_c = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
                                                                w.tree_degree, w.ready_order(), fm)
-        assert [(l[0], l[1]) for l in launches_c] == [(0, c), (0, 32)]
-        assert entries_c[launches_c[1][2]:launches_c[1][3]] == second
-        assert info_c["chunks_redone"] == c * 31
+        assert [(l[0], l[1]) for l in launches_c] == [(0, c), (0, c), (c, 32)]
+        assert entries_c[launches_c[2][2]:launches_c[2][3]] == rest
+        assert info_c["chunks_redone"] == c * 5
+    # a participant inside a subtree: that subtree is read again, the other two come from their partials
+    order = w.ready_order()
+    inside = int(order[12])                  # 13th arrival: in the second subtree (arrivals 11..19)
+    fm = np.full(w.n, -1, np.int64)
+    fm[inside] = 4
+    _, info_i, launches_i, entries_i = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes,
+                                                           w.tree_degree, order, fm)
+    repair_i = entries_i[launches_i[1][2]:launches_i[1][3]]
+    assert [e[0] for e in repair_i if e[0] < 0] == [-1, -3] and len(repair_i) == 2 + 1 + 8 + 5
+    assert info_i["chunks_redone"] == 4 * 14
+    # small launches (at most 1 MiB per object) keep nothing: the chunks are produced again whole
+    ws = w.scaled((1 << 20) + 6, 32 << 10)
+    _, info_s, launches_s, _ = hop.hop_plan_reduce(ws.n, ws.object_bytes, ws.k, ws.dtype, ws.chunk_bytes,
+                                                   ws.tree_degree, ws.ready_order(), ws.fail_mask())
+    assert [(l[0], l[1]) for l in launches_s] == [(0, 10), (0, 33)] and info_s["partial_stores"] == 0
+    assert info_s["chunks_redone"] == 10 * 31
 
 
 def test_replacement_from_waiting_objects():
@@ -369,21 +430,23 @@ def oracle_for_occupants(objs, slots, k, C, chunk_elems, d, op):
     return oracle.reduce(objs, k, ORA_OP[op], oracle.F32, chunk_elems, d, np.array(order, np.int32), fm)
 
 
-@pytest.mark.parametrize("eager", [0, 1, 2, 5])
-def test_random_sessions_with_segments_equal_oracle(eager):
-    rng = np.random.default_rng(900 + eager)
-    n_segmented = 0
+@pytest.mark.parametrize("eager,scale", [(0, 1), (1, 1), (2, 1), (5, 1), (0, BIG), (2, BIG)])
+def test_random_sessions_with_segments_equal_oracle(eager, scale):
+    rng = np.random.default_rng(900 + eager + (scale > 1))
+    n_segmented = n_kept = n_reused = 0
     for it in range(150):
-        n = int(rng.integers(2, 12))
+        n = int(rng.integers(2, 12 if scale == 1 else 30))
         k = int(rng.integers(1, n + 1))
         d = int(rng.choice([1, 2, 3, 4, n]))
         C = int(rng.integers(2, 7))
         ce = 4
         E = (C - 1) * ce + int(rng.integers(1, ce + 1))
         objs = [(rng.standard_normal(E) * 10.0 ** rng.integers(-2, 3)).astype(np.float32) for _ in range(n)]
-        rc, s = hop.hop_plan_session_begin(n, E * 4, k, "f32", ce * 4, d)
+        rc, s = hop.hop_plan_session_begin(n, E * 4 * scale, k, "f32", ce * 4 * scale, d)
         assert rc == hop.HOP_OK
         assert hop.hop_session_set_eager(s, eager) == hop.HOP_OK
+        keeping = it % 5 != 0
+        assert hop.hop_session_set_retention(s, keeping) == hop.HOP_OK
         model = SlotModel(n, k, C)
         # a random interleaving: objects arrive in random order and deliver chunks in random bursts;
         # some fail mid-stream, some never finish
@@ -425,7 +488,11 @@ def test_random_sessions_with_segments_equal_oracle(eager):
             continue
         assert rc == (hop.HOP_OK if len(live) == k else hop.HOP_PARTIAL) and info["k_eff"] == len(live)
         final_prog = entries[launches[-1][2]:launches[-1][3]]
-        assert [e[0] for e in final_prog] == live
+        if not any(e[0] < 0 for e in final_prog):
+            assert [e[0] for e in final_prog] == live
+        assert keeping or info["partial_stores"] == 0
+        n_kept += info["partial_stores"] > 0
+        n_reused += info["partial_loads"] > 0
         got = interpret(objs, launches, entries, E, ce, "sum")
         orc, want, k_eff, _ = oracle_for_occupants(objs, slots, k, C, ce, d, "sum")
         assert orc == rc and k_eff == len(live)
@@ -434,6 +501,7 @@ def test_random_sessions_with_segments_equal_oracle(eager):
             assert all(l[4] == 0 and l[6] == 1 for l in launches)       # whole programs only
         n_segmented += any(l[6] == 0 for l in launches)
     assert n_segmented > {0: -1, 1: 30, 2: 30, 5: 0}[eager] and (eager or n_segmented == 0)
+    assert (n_kept, n_reused) == (0, 0) if scale == 1 else (n_kept > 10 and n_reused > 3), (n_kept, n_reused)
 
 
 def test_eager_session_overlaps_the_wait_for_the_last_arrival():
