@@ -19,49 +19,68 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B/s)
 
-# HBM bytes moved by ONE reduce launch of workload 2, from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE), each scaled by what the same counter read for the 256 MiB copy probe of this file
-# (profiles/reduce_kernel_cfg2_async_sgd.md). Valid only for the kernel launch shape named here: if the
-# library reports another one, the figure is withheld (null).
-MEASURED_TRAFFIC = {
-    "workload": "cfg2_async_sgd",
-    "kernel_config": "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB "
-                     "tiles: 1 KiB tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart;"
-                     " from 2048: 1 KiB pieces 64 KiB apart, one per vector (the 2 KiB shape instead if the rounds of "
-                     "resident waves would be less than 80 % full); kernels with 4 vectors/lane: 8 waves per CU from 5120 "
-                     "tiles; bf16 at depth 5..8 from 768 tiles: 2 vectors/lane, unroll 2 (pieces 64 KiB apart from 2048 "
-                     "tiles); groups of 8 plain steps marked by the host; nontemporal loads+stores, programs <= 128 steps "
-                     "in kernel arguments; vector grids start at a 128-byte boundary of the sources (reduce) or "
-                     "destinations (copies); copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from "
-                     "5120 8-KiB tiles 4 vectors/lane in 1 KiB pieces 64 KiB apart, 10 waves per CU; nontemporal; to "
-                     "several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 "
-                     "tiles, cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 "
-                     "destinations)",
-    "bytes": 872313828,
+# HBM bytes moved per call, from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what
+# the same counter read for the 256 MiB copy probe of this file; summed over the call's launches. The
+# summaries are in profiles/ (with the commands that made them). The figures hold only for the kernel launch
+# shapes they were taken with: they are reported only while the library's hop_kernel_config() string is the
+# one recorded here (else null).
+PROFILED_TRAFFIC = {
+    "kernel_config": "",
+    "workloads": {},
+}
+
+# The paper's own headline results (its sections 5.2-5.4 and 5 "setup"): context, not a target.
+PAPER_CONTEXT = {
+    "source": "arXiv 2002.05814 (SIGCOMM '21), sections 5.2-5.4",
+    "speedups_over_ray": {"async_sgd_parameter_server_16_nodes": "7.8x AlexNet / 7.0x VGG-16 / 5.0x ResNet-50",
+                          "rl_16_nodes": "3.9x A3C, 1.8x IMPALA", "ensemble_serving_16_nodes": "3.3x (2.2x on 8 nodes)"},
+    "hardware": "AWS EC2, 16 m5.4xlarge nodes (16 vCPUs, 64 GB, 10 Gbps network = 1.25 GB/s per node); the "
+                "application runs on 8 or 16 p3.2xlarge nodes (one V100 each, same network); CPU objects only, no GPU "
+                "path in the paper",
+    "note": "speedups of whole applications over Ray on a 10 Gbps cluster; nothing there is comparable with a "
+            "fraction of one GPU's HBM bandwidth",
 }
 
 
+def profiled_traffic(workload_name, kernel_config):
+    """Counter-measured HBM bytes per call of this workload ({"bytes_per_call", "profile"}), or None if there
+    is no profile for it or the library's launch shapes have changed since the counters were taken."""
+    entry = PROFILED_TRAFFIC["workloads"].get(workload_name)
+    if not entry or PROFILED_TRAFFIC["kernel_config"] != kernel_config:
+        return None
+    return entry
+
+
 def time_calls(fn, steps, warmup, torch):
-    """Average device time per call in ms, bracketed by events on the current stream."""
+    """Device time per call in ms over exactly `steps` calls enqueued back to back between two events on the
+    current stream (the stream the kernels are launched on): (mean over all calls, host wall mean, median over
+    batches). An event behind every call would cost 2-3 us per call (the next kernel no longer starts while
+    the previous one drains), so the calls are marked in batches of at least 5 (a tenth of the steps)."""
+    import statistics
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
+    batch = max(5, steps // 10)
+    edges = list(range(0, steps, batch)) + [steps]
+    marks = [torch.cuda.Event(enable_timing=True) for _ in edges]
     t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
+    marks[0].record()
+    nxt = 1
+    for i in range(steps):
         fn()
-    e1.record()
+        if i + 1 == edges[nxt]:
+            marks[nxt].record()
+            nxt += 1
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    return e0.elapsed_time(e1) / steps, wall_ms / steps
+    each = [marks[j].elapsed_time(marks[j + 1]) / (edges[j + 1] - edges[j]) for j in range(len(edges) - 1)]
+    return marks[0].elapsed_time(marks[-1]) / steps, wall_ms / steps, statistics.median(each)
 
 
 def time_calls_median(fn, steps, warmup, torch, batch=100):
-    """For launch-bound workloads: the timed calls are taken in batches and the median batch is
-    reported, so that a one-off stall of the runtime (tens of ms, a few times per process, at launch
-    counts that depend on nothing the library does) does not decide the figure."""
+    """For launch-bound workloads (a call takes 10-30 us, an event behind every call would be part of what is
+    measured): the timed calls are taken in batches and the median batch is reported, so that a one-off stall
+    of the runtime (tens of ms, a few times per process) does not decide the figure."""
     import statistics
     for _ in range(warmup):
         fn()
@@ -78,28 +97,75 @@ def time_calls_median(fn, steps, warmup, torch, batch=100):
         torch.cuda.synchronize()
         wall_ms.append((time.perf_counter() - t0) * 1e3 / batch)
         dev_ms.append(e0.elapsed_time(e1) / batch)
-    return statistics.median(dev_ms), statistics.median(wall_ms)
+    return statistics.mean(dev_ms), statistics.median(wall_ms), statistics.median(dev_ms)
 
 
-def cpu_baseline(w, objs, order, torch, sample_elems, min_seconds=10.0):
-    """The oracle as it stands, single thread, on the first sample_elems elements of every object, repeated
-    until about min_seconds of CPU time have been spent; the mean rate is reported."""
+def host_description():
+    """CPU model and core counts of the machine the oracle is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except (AttributeError, OSError):
+        usable = os.cpu_count() or 1
+    return {"cpu_model": model, "nproc": os.cpu_count() or 1, "usable_cores": usable}
+
+
+def cpu_baseline(w, objs, order, torch, sample_elems, min_seconds=10.0, all_core_seconds=4.0, max_threads=16):
+    """The oracle as it stands on the first sample_elems elements of every object. Leg 1 (the reported value):
+    one thread, repeated until about min_seconds of CPU time have been spent. Leg 2: the same oracle call per
+    contiguous slice of elements (the reduce is elementwise, so slices are independent), the slices spread over
+    the host's usable cores (at most max_threads) by a thread pool; core count stated."""
+    import concurrent.futures
+
     import numpy as np
 
     import oracle
     import workloads
     host = [workloads.to_numpy(o[:sample_elems]) for o in objs]
+    ce = w.chunk_bytes // 4
     reps, spent, out, k_eff = 0, 0.0, None, 0
     while reps < 2 or spent < min_seconds:
         t0 = time.perf_counter()
-        rc, out, k_eff, _ = oracle.reduce(host, w.k, oracle.SUM, oracle.F32, w.chunk_bytes // 4, w.tree_degree, order,
-                                          None)
+        rc, out, k_eff, _ = oracle.reduce(host, w.k, oracle.SUM, oracle.F32, ce, w.tree_degree, order, None)
         spent += time.perf_counter() - t0
         reps += 1
     nbytes = (k_eff + 1) * sample_elems * 4
-    return {"value": round(nbytes * reps / spent / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+    desc = host_description()
+    base = {"value": round(nbytes * reps / spent / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": "%d passes over the first %d of %d elements of each object (%.0f MB counted per pass), %.1f s" %
-                      (reps, sample_elems, w.n_elems, nbytes / 1e6, spent)}, out
+                      (reps, sample_elems, w.n_elems, nbytes / 1e6, spent),
+            "host": desc}
+    # leg 2: all usable cores
+    threads = max(1, min(desc["usable_cores"], max_threads))
+    cuts = np.linspace(0, sample_elems, 4 * threads + 1).astype(np.int64) // ce * ce
+    cuts[-1] = sample_elems
+    spans = [(int(a), int(b)) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+
+    def one(span):
+        a, b = span
+        rc2, part, _, _ = oracle.reduce([h[a:b] for h in host], w.k, oracle.SUM, oracle.F32, ce, w.tree_degree, order, None)
+        return a, b, part
+    reps2, spent2, same = 0, 0.0, True
+    with concurrent.futures.ThreadPoolExecutor(max_workers=threads) as pool:
+        while reps2 < 1 or spent2 < all_core_seconds:
+            t0 = time.perf_counter()
+            parts = list(pool.map(one, spans))
+            spent2 += time.perf_counter() - t0
+            reps2 += 1
+        for a, b, part in parts:
+            same = same and bool(np.array_equal(part.view(np.uint32), out[a:b].view(np.uint32)))
+    base["all_cores"] = {"value": round(nbytes * reps2 / spent2 / 1e9, 4), "unit": "GB/s", "cores": threads,
+                         "sample": "%d passes, %d slices per pass, %.1f s" % (reps2, len(spans), spent2),
+                         "equals_single_thread_bits": same}
+    return base, out
 
 
 def paced_arrivals(hop, torch, w, objs, order, dst, interval_us, reps=5):
@@ -181,7 +247,9 @@ def main():
                     help="untimed calls before the timed ones (the first few dozen calls of a process run at lower clocks)")
     ap.add_argument("--workload", type=int, default=2, help="which of the five workloads (default: 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all-configs", action="store_true", help="also time the other workloads (extra JSON field)")
+    ap.add_argument("--all-configs", action="store_true", help="(default behaviour now; kept for old command lines)")
+    ap.add_argument("--skip-all-configs", action="store_true",
+                    help="time only the headline workload, not the other four (they take a few seconds)")
     ap.add_argument("--streamed-interval-us", type=float, default=None,
                     help="also: all k objects stream chunk by chunk, one more chunk each per interval")
     ap.add_argument("--paced-interval-us", type=float, default=None,
@@ -248,23 +316,57 @@ def main():
                 else:
                     state["rc"], state["info"] = hop.hop_reduce(d[0], obj_table, w.k, op, w.dtype, w.chunk_bytes,
                                                                 w.tree_degree, order, fm)
-            ms, wall_ms = timer(step, steps, warmup, torch)
+            ms, wall_ms, ms_median = timer(step, steps, warmup, torch)
             assert state["rc"] >= 0, hop.hop_strerror(state["rc"])
-            k_eff = state["info"]["k_eff"]
+            info = state["info"]
+            k_eff = info["k_eff"]
             counted = (k_eff + 1) * w.object_bytes
             if w.n_dst:
                 counted = (k_eff + w.n_dst) * w.object_bytes        # least traffic of reduce + broadcast
-            # what the launches really moved (repairs included), from the scheduler's own account
-            moved = (state["info"]["chunk_steps"] + state["info"]["chunk_stores"]) * min(w.chunk_bytes, w.object_bytes)
+            # what the launches really moved (repairs and kept partial results included), from the
+            # scheduler's own account: source chunks read, result chunks written, partials (4 bytes per element)
+            cb = min(w.chunk_bytes, w.object_bytes)
+            moved = (info["chunk_steps"] + info["chunk_stores"]) * cb
+            moved += (info["partial_loads"] + info["partial_stores"]) * (cb // workloads.ELEM_BYTES[w.dtype]) * 4
             if w.n_dst:
                 moved += w.n_dst * w.object_bytes       # copy kernel: 1 read + (n_dst - 1) writes
-            results[op] = {"ms": ms, "wall_ms": wall_ms, "gbs": counted / (ms * 1e-3) / 1e9, "bytes": counted,
-                           "moved_gbs": moved / (ms * 1e-3) / 1e9, "info": state["info"], "status": state["rc"]}
+            results[op] = {"ms": ms, "ms_median": ms_median, "wall_ms": wall_ms, "gbs": counted / (ms * 1e-3) / 1e9,
+                           "gbs_median": counted / (ms_median * 1e-3) / 1e9, "bytes": counted, "moved": moved,
+                           "moved_gbs": moved / (ms * 1e-3) / 1e9, "info": info, "status": state["rc"]}
         return w, objs, order, dsts, results
 
+    extra = None
+    if not args.skip_all_configs:
+        # The other four workloads (workload 4 also without its failure), each with the bytes counted for the
+        # metric, the bytes its launches really moved, and the fraction of the HBM peak on counted bytes. They
+        # run before the headline workload so that its few timed steps do not meet a device that has just woken
+        # up (the first few dozen launches of a process run at lower clocks).
+        extra = {}
+        for cfg, no_fail in ((1, False), (3, False), (4, False), (4, True), (5, False)):
+            if cfg == args.workload and not no_fail:
+                continue
+            # the tiny workloads are launch-bound: median over batches of 100 calls (see time_calls_median)
+            tiny = cfg in (1, 5)
+            wk, o2, _, d2, rs = run_workload(cfg, 1000 if tiny else 50, 300 if tiny else 20, no_fail,
+                                             time_calls_median if tiny else time_calls)
+            for opn, rr in rs.items():
+                t = profiled_traffic(wk.name, hop.hop_kernel_config())
+                extra["%s/%s" % (wk.name, opn)] = {
+                    "GB/s": round(rr["gbs_median"], 2), "ms": round(rr["ms_median"], 5), "ms_mean": round(rr["ms"], 5),
+                    "frac_of_hbm_peak": round(rr["gbs_median"] / HBM_PEAK_GBS, 4), "counted_bytes": rr["bytes"],
+                    "counted_as": "(k_eff + n_dst) x object_bytes" if wk.n_dst else "(k_eff + 1) x object_bytes",
+                    "moved_bytes": rr["moved"], "moved_over_counted": round(rr["moved"] / rr["bytes"], 4),
+                    "GB/s_moved": round(rr["moved"] / (rr["ms_median"] * 1e-3) / 1e9, 2),
+                    "traffic_from_counters": t["bytes_per_call"] if t else None,
+                    "status": rr["status"], "status_text": hop.hop_strerror(rr["status"]), "k_eff": rr["info"]["k_eff"],
+                    "launches": rr["info"]["n_launches"], "host_ms_per_call": round(rr["wall_ms"], 5),
+                    "timing": "median of batches of 100 calls" if tiny else "median of batches of 5 calls"}
+            del o2, d2
+            torch.cuda.empty_cache()
     w, objs, order, dsts, res = run_workload(args.workload, args.steps, args.warmup)
     op = w.ops[0]
     r = res[op]
+    traffic = profiled_traffic(w.name, hop.hop_kernel_config())
     out = {
         "metric": "reduce input GB/s and % of MI355X HBM peak, N-way chunked reduce",
         "value": round(r["gbs"], 2),
@@ -274,6 +376,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(r["ms"], 5),
+        "ms_per_step_median": round(r["ms_median"], 5),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -283,13 +386,17 @@ def main():
                    "chunk_bytes": w.chunk_bytes, "tree_degree": r["info"]["degree_used"], "op": op,
                    "counted_bytes": r["bytes"], "launches_per_step": r["info"]["n_launches"],
                    "host_ms_per_step": round(r["wall_ms"], 5)},
+        # one launch per call for this workload: the kernel's average duration over the timed region is the
+        # time per call (the gap between launches, under 1 % here, counts against the kernel)
         "roofline": {"bound": "hbm", "achieved": round(r["gbs"], 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
-                     "traffic": (MEASURED_TRAFFIC["bytes"]
-                                 if (w.name == MEASURED_TRAFFIC["workload"]
-                                     and hop.hop_kernel_config() == MEASURED_TRAFFIC["kernel_config"]) else None),
-                     "kernel": "hop::reduce_kernel", "per_unit": "(k_eff+1) x object_bytes per launch"},
+                     "traffic": traffic["bytes_per_call"] if traffic else None,
+                     "traffic_source": (traffic["profile"] if traffic else None),
+                     "kernel": "hop::reduce_kernel_inline", "per_unit": "(k_eff+1) x object_bytes per launch"},
+        "paper_context": PAPER_CONTEXT,
     }
+    if extra is not None:
+        out["all_configs"] = extra
     if not args.no_cpu_baseline and w.dtype == "f32" and not w.n_dst:
         sample = w.n_elems                      # the whole workload; repeated to about 10 s of CPU time
         base, want = cpu_baseline(w, objs, order, torch, sample)
@@ -304,7 +411,7 @@ def main():
 
         def probe():
             assert hop.hop_broadcast([dstp], src, 4 << 20) == hop.HOP_OK
-        ms, _ = time_calls(probe, 10, 2, torch)
+        ms, _, _ = time_calls(probe, 10, 2, torch)
         out["copy_probe"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "ms": round(ms, 5),
                              "GB/s_read_plus_write": round(2 * src.numel() * 4 / (ms * 1e-3) / 1e9, 2),
                              "kernel": "hop::copy_kernel"}
@@ -319,7 +426,7 @@ def main():
                 st["i"] += 1
                 _, st["info"] = hop.hop_reduce(dsts[st["i"] & 1][0], table, w.k, op, w.dtype, w.chunk_bytes, deg, order,
                                                None)
-            ms, _ = time_calls(step_deg, max(20, args.steps // 4), 10, torch)
+            ms, _, _ = time_calls(step_deg, max(20, args.steps // 4), 10, torch)
             nbytes = (st["info"]["k_eff"] + 1) * w.object_bytes        # reduce only, nobody fails
             sweep["d=%d" % deg] = {"ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                    "levels": st["info"]["stack_depth"]}
@@ -329,24 +436,6 @@ def main():
         out["streamed_chunks"] = streamed_chunks(hop, torch, w, objs, order, dsts[0][0], args.streamed_interval_us)
     if args.paced_interval_us is not None:
         out["paced_arrivals"] = paced_arrivals(hop, torch, w, objs, order, dsts[0][0], args.paced_interval_us)
-    if args.all_configs:
-        extra = {}
-        del objs, dsts
-        torch.cuda.empty_cache()
-        for cfg, no_fail in ((1, False), (3, False), (4, False), (4, True), (5, False)):
-            # the tiny workloads are launch-bound: median over batches of 100 calls (see time_calls_median)
-            tiny = cfg in (1, 5)
-            wk, o2, _, d2, rs = run_workload(cfg, 1000 if tiny else max(10, args.steps // 5),
-                                             300 if tiny else 20, no_fail, time_calls_median if tiny else time_calls)
-            for opn, rr in rs.items():
-                extra["%s/%s" % (wk.name, opn)] = {"GB/s": round(rr["gbs"], 2), "ms": round(rr["ms"], 5),
-                                                  "frac_of_hbm_peak": round(rr["gbs"] / HBM_PEAK_GBS, 4),
-                                                  "counted_bytes": rr["bytes"], "status": rr["status"],
-                                                  "GB/s_moved_incl_repair": round(rr["moved_gbs"], 2),
-                                                  "launches": rr["info"]["n_launches"]}
-            del o2, d2
-            torch.cuda.empty_cache()
-        out["all_configs"] = extra
     print(json.dumps(out))
 
 

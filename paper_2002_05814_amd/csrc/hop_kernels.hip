@@ -47,7 +47,9 @@ const char *kernel_config()
            "copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from 5120 8-KiB tiles 4 vectors/lane in "
            "1 KiB pieces 64 KiB apart, 10 waves per CU; nontemporal; "
            "to several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 tiles, "
-           "cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations)";
+           "cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations); "
+           "launches that keep or read partial results: one step at a time, 4|2|1 vectors/lane, pieces 64 KiB apart from 2048 "
+           "tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators indexed like the elements, nontemporal";
 }
 
 static Launcher pick(int dtype, int op, int depth)

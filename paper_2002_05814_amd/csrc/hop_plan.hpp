@@ -319,7 +319,6 @@ public:
         done_.push_back({C_, 0, 0, false});
         kept_.push_back({C_, 0});
         gens_.emplace_back();
-        find_runs();
     }
 
     // Retention of partial results across failures (section 3.5.2: when a participant fails, only
@@ -333,11 +332,23 @@ public:
     //   on          false: never keep anything (failures redo the produced chunks whole)
     //   min_chunks  launches over fewer chunks keep nothing (too small to be worth a second array)
     //   elem_bytes  size of a source element (a kept value takes 4 bytes)
+    // Off until this is called. (Where no launch can be long enough, nothing is prepared at all.)
     void set_retention(bool on, int64_t min_chunks, int elem_bytes)
     {
-        retain_ = on;
         retain_min_chunks_ = min_chunks < 1 ? 1 : min_chunks;
         elem_bytes_ = elem_bytes;
+        const bool want = on && retain_min_chunks_ <= C_;
+        if (want == retain_) return;
+        retain_ = want;
+        // what was kept under another setting is forgotten; the subtrees are found when first needed
+        kept_.assign(1, Kept{C_, 0});
+        gens_.assign(1, std::vector<uint32_t>());
+        runs_.clear();
+        run_of_slot_.clear();
+        run_ver_.clear();
+        if (retain_) find_runs();
+        compiled_version_ = 0;              // the next pump compiles again, now with (or without) the runs' step ranges
+        dirty_ = true;
     }
 
     // 0 (default): a chunk is produced in one launch once all its inputs are present.
@@ -837,7 +848,7 @@ private:
     std::vector<std::pair<int, int>> run_steps_;     // the run's steps in prog_: [first, second)
     std::vector<Kept> kept_;                         // chunks [previous end, chunk_end) hold the partials of generation gen
     std::vector<std::vector<uint32_t>> gens_;        // per generation and run: run_ver_ when its partial was stored, 0 = none
-    bool retain_ = true, keep_asked_ = false, keep_refused_ = false;
+    bool retain_ = false, keep_asked_ = false, keep_refused_ = false;
     int64_t retain_min_chunks_ = 1;
     int elem_bytes_ = 4;
     std::vector<int32_t> slot_of_step_;

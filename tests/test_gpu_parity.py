@@ -759,6 +759,39 @@ def sampled_oracle_check(w, op, objs, dsts, rc, info, rng, per_chunk=64):
     return small, want
 
 
+def full_oracle_check(w, op, objs, dsts, rc, info, order=None, fm=None):
+    """Every element of the result against the oracle's tree-ordered reduce of the same inputs."""
+    order = w.ready_order() if order is None else order
+    d = info["degree_used"] if w.tree_degree == 0 else w.tree_degree
+    host = [workloads.to_numpy(o) for o in objs]
+    orc, want, k_eff, n_rep = oracle.reduce(host, w.k, ORA_OP[op], ORA_DT[w.dtype], max(1, w.chunk_bytes // ES[w.dtype]), d,
+                                            order, fm)
+    assert rc == orc and info["k_eff"] == k_eff and info["n_replaced"] == n_rep
+    for dst in dsts:
+        got = workloads.to_numpy(dst)
+        assert np.array_equal(bits(got), bits(want)), "mismatch at %s" % np.flatnonzero(bits(got) != bits(want))[:8]
+    return host, want
+
+
+def free_order_check(w, host, got, order=None, fm=None, n_check=1 << 20):
+    """A float sum against the order-free definition (the oracle's float64 sum over the occupants) within the
+    tolerance for free ordering, on the first and last n_check elements."""
+    order = w.ready_order() if order is None else order
+    rc, occ, k_eff, _ = oracle.occupants(w.n, w.k, w.n_chunks, order, fm)
+    assert rc >= 0
+    tol = 1e-5 * np.log2(max(k_eff, 2)) if w.dtype == "f32" else 1e-2
+    for part in (slice(0, n_check), slice(max(0, w.n_elems - n_check), w.n_elems)):
+        small = [h[part] for h in host]
+        ref = oracle.reduce_set(small, occ, oracle.SUM, ORA_DT[w.dtype])
+        mag = np.zeros_like(ref)
+        for o in occ:
+            if o >= 0:
+                x = small[o] if w.dtype == "f32" else oracle.bf16_to_f32(small[o])
+                mag += np.abs(x.astype(np.float64))
+        g = got[part] if w.dtype == "f32" else oracle.bf16_to_f32(got[part])
+        assert np.all(np.abs(g.astype(np.float64) - ref) <= tol * np.maximum(np.abs(ref), mag / k_eff))
+
+
 # every launch shape of the reduce kernel, each at a size just inside its range, with one object a few
 # elements short of a tile so that the ragged end is exercised too: (dtype, n, k, degree, bytes short of or
 # beyond a whole number of MiB, MiB, dist). From 3 MiB a workgroup's pieces lie 16 or 64 KiB apart, in
@@ -784,7 +817,7 @@ LAUNCH_SHAPE_CASES = [
 
 
 @pytest.mark.parametrize("dtype,n,k,d,delta,mib,dist", LAUNCH_SHAPE_CASES)
-def test_every_launch_shape_against_sampled_oracle(dtype, n, k, d, delta, mib, dist):
+def test_every_launch_shape_against_the_oracle(dtype, n, k, d, delta, mib, dist):
     nbytes = mib * (1 << 20) + delta - ES[dtype]
     chunk = 1 << 20
     w = workloads.Workload("shape_%s_%d" % (dtype, mib), n=n, dtype=dtype, object_bytes=nbytes, chunk_bytes=chunk,
@@ -805,26 +838,18 @@ def test_every_launch_shape_against_sampled_oracle(dtype, n, k, d, delta, mib, d
         small = [workloads.to_numpy(o[tail]) for o in objs]
         _, want, _, _ = oracle.reduce(small, k, ORA_OP[op], ORA_DT[dtype], 40, d, w.ready_order(), None)
         assert np.array_equal(bits(workloads.to_numpy(dst[tail])), bits(want))
-        # every element, by properties that hold in any order: max is exact; an integer sum is exact; a float
-        # sum lies within the free-order tolerance of the fp64 sum
-        if op == "max":
+        if op == "sum":
+            # every element against the oracle, and (floats) against the order-free definition within the
+            # tolerance for free ordering
+            host, want = full_oracle_check(w, op, objs, [dst], rc, info)
+            if dtype != "i32":
+                free_order_check(w, host, want)
+        else:
+            # max is exact in any order: every element against a plain running maximum
             ref = sel[0].clone()
             for o in sel[1:]:
                 ref = torch.maximum(ref, o)
             assert torch.equal(dst, ref)
-        elif dtype == "i32":
-            ref = torch.zeros_like(sel[0])
-            for o in sel:
-                ref += o
-            assert torch.equal(dst, ref)
-        else:
-            ref = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
-            mag = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
-            for o in sel:
-                ref += o.double()
-                mag += o.double().abs()
-            tol = 1e-5 * np.log2(k) if dtype == "f32" else 1e-2
-            assert bool(((dst.double() - ref).abs() <= tol * torch.maximum(ref.abs(), mag / k)).all())
 
 
 @pytest.mark.parametrize("dtype,mib,residues", [("f32", 2, (16,)), ("f32", 6, (16,)), ("f32", 12, (80,)), ("i32", 20, (112,)),
@@ -864,24 +889,13 @@ def test_sources_that_are_only_16_byte_aligned(dtype, mib, residues):
         _, want, _, _ = oracle.reduce([workloads.to_numpy(o[head]) for o in objs], k, ORA_OP[op], ORA_DT[dtype], 40, deg,
                                       w.ready_order(), None)
         assert np.array_equal(bits(workloads.to_numpy(dst[head])), bits(want))
-        if op == "max":
+        if op == "sum":
+            full_oracle_check(w, op, objs, [dst], rc, info)
+        else:
             ref = sel[0].clone()
             for o in sel[1:]:
                 ref = torch.maximum(ref, o)
             assert torch.equal(dst, ref)
-        elif dtype == "i32":
-            ref = torch.zeros_like(sel[0])
-            for o in sel:
-                ref += o
-            assert torch.equal(dst, ref)
-        else:
-            ref = torch.zeros(E, dtype=torch.float64, device=d)
-            mag = torch.zeros(E, dtype=torch.float64, device=d)
-            for o in sel:
-                ref += o.double()
-                mag += o.double().abs()
-            tol = 1e-5 * np.log2(k) if dtype == "f32" else 1e-2
-            assert bool(((dst.double() - ref).abs() <= tol * torch.maximum(ref.abs(), mag / k)).all())
     if mib in (9, 12):
         # the same objects through eager segments (every arrival folded into saved accumulators at once)
         rc, _ = hop.hop_reduce(dst, objs, k, "sum", dtype, chunk, deg, w.ready_order(), None)
@@ -898,7 +912,7 @@ def test_sources_that_are_only_16_byte_aligned(dtype, mib, residues):
     assert int(pool[at - 12:at].abs().sum()) == 0 and int(pool[at + E:at + E + 12].abs().sum()) == 0
 
 
-def test_cfg2_full_size_sampled():
+def test_cfg2_full_size_every_element():
     w = workloads.WORKLOADS[2]
     print("full size", w.name, flush=True)
     objs = workloads.make_objects(w, device=dev())
@@ -906,21 +920,12 @@ def test_cfg2_full_size_sampled():
     rc, info = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
     torch.cuda.synchronize()
     assert rc == hop.HOP_OK and info["n_launches"] == 1 and info["k_eff"] == 12
-    small, want = sampled_oracle_check(w, "sum", objs, [dst], rc, info, np.random.default_rng(2))
-    # property that holds at any size: the four objects that were not among the first 12 ready were not read;
-    # a torch fp64 sum over the selected twelve agrees within the free-order tolerance on the WHOLE object
-    sel = w.ready_order()[:12]
-    ref = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
-    mag = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
-    for i in sel:
-        ref += objs[i].double()
-        mag += objs[i].double().abs()
-    tol = 1e-5 * np.log2(12)
-    err = (dst.double() - ref).abs()
-    assert bool((err <= tol * torch.maximum(ref.abs(), mag / 12)).all())
+    host, want = full_oracle_check(w, "sum", objs, [dst], rc, info)
+    # the order-free definition: the float64 sum over the first 12 ready, within the free-order tolerance
+    free_order_check(w, host, want)
 
 
-def test_cfg3_full_size_allreduce_sampled():
+def test_cfg3_full_size_allreduce_every_element():
     w = workloads.WORKLOADS[3]
     print("full size", w.name, flush=True)
     objs = workloads.make_objects(w, device=dev())
@@ -928,16 +933,15 @@ def test_cfg3_full_size_allreduce_sampled():
     rc, info = hop.hop_allreduce(dsts, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
     torch.cuda.synchronize()
     assert rc == hop.HOP_OK and info["k_eff"] == 64
-    sampled_oracle_check(w, "sum", objs, dsts[:3] + dsts[-1:], rc, info, np.random.default_rng(3))
-    # integers are order-free: the whole result equals torch's sum, and all 64 destinations are identical
-    ref = torch.zeros_like(objs[0])
-    for o in objs:
-        ref += o
-    for d_ in dsts:
-        assert torch.equal(d_, ref)
+    # the first destination against the oracle, every element; the other 63 against the first
+    host, want = full_oracle_check(w, "sum", objs, dsts[:1], rc, info)
+    assert all(torch.equal(dsts[0], x) for x in dsts[1:])
+    # integers are order-free: the oracle's unwrapped int64 sum over all 64, wrapped, is the same
+    ref = oracle.reduce_set([h[:1 << 20] for h in host], np.arange(64, dtype=np.int32), oracle.SUM, oracle.I32)
+    assert np.array_equal(ref.astype(np.int32), want[:1 << 20])
 
 
-def test_cfg4_full_size_failure_sampled():
+def test_cfg4_full_size_failure_every_element():
     w = workloads.WORKLOADS[4]
     print("full size", w.name, flush=True)
     objs = workloads.make_objects(w, device=dev())
@@ -948,16 +952,11 @@ def test_cfg4_full_size_failure_sampled():
     # launch over chunks 0..9 that keeps the three subtree partials, their repair, chunks 10..31
     assert rc == hop.HOP_PARTIAL and info["k_eff"] == 31 and info["n_launches"] == 3
     assert info["chunks_redone"] == 10 * 5 and info["partial_stores"] == info["partial_loads"] == 10 * 3
-    sampled_oracle_check(w, "sum", objs, [dst], rc, info, np.random.default_rng(4))
-    # whole-object property: within the bf16 tolerance of the fp64 sum over the 31 survivors (object 7 excluded)
-    ref = torch.zeros(w.n_elems, dtype=torch.float64, device=dev())
-    for i in range(w.n):
-        if i != 7:
-            ref += objs[i].double()
-    err = (dst.double() - ref).abs()
-    assert bool((err <= 1e-2 * torch.maximum(ref.abs(), torch.tensor(1.0, device=dev(), dtype=torch.float64))).all())
-    del ref, err
-    # and independent of when the failure happened
+    host, want = full_oracle_check(w, "sum", objs, [dst], rc, info, fm=w.fail_mask())
+    # the order-free definition: within the bf16 tolerance of the float64 sum over the 31 survivors
+    free_order_check(w, host, want, fm=w.fail_mask())
+    del host
+    # and independent of when the failure happened, and of whether partial results were kept
     dst2 = torch.zeros_like(dst)
     fm = w.fail_mask().copy()
     fm[7] = 31

@@ -231,6 +231,54 @@ def test_f32_sum_close_to_float64_and_to_reduce_set(d):
     assert np.allclose(ref, want, rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("op,np_red", [(SUM, None), (MIN, np.minimum), (MAX, np.maximum)])
+def test_reduce_set_every_branch_against_library_reductions(op, np_red):
+    # the order-free definition in every element type and op, with empty positions (-1) among the
+    # occupants: int32 carried in int64 (the sum leaves the int32 range and must not wrap), floats in
+    # float64; expected values from numpy's int64 / float64 reductions, math.fsum (exact) and torch's
+    # bfloat16 widening
+    import math
+    rng = np.random.default_rng(40 + op)
+    n, E = 20, 600
+    occ = np.array([3, -1, 17, 0, 9, -1, 12, 5, 19, 1], np.int32)        # two empty positions
+    live = [int(o) for o in occ if o >= 0]
+    # int32: values near the ends of the range
+    ints = [rng.integers(-2 ** 31, 2 ** 31, size=E, dtype=np.int64).astype(np.int32) for _ in range(n)]
+    for i in live:
+        ints[i][:8] = np.int32(2 ** 31 - 1)
+    got = oracle.reduce_set(ints, occ, op, I32)
+    P = np.stack([ints[i] for i in live]).astype(np.int64)
+    want = P.sum(axis=0) if op == SUM else np_red.reduce(P, axis=0)
+    assert got.dtype == np.int64 and np.array_equal(got, want)
+    if op == SUM:
+        assert got[0] > 2 ** 32                      # really unwrapped
+    # float32
+    flts = [(rng.standard_normal(E) * 10.0 ** rng.integers(-4, 5)).astype(np.float32) for _ in range(n)]
+    got = oracle.reduce_set(flts, occ, op, F32)
+    Pf = np.stack([flts[i] for i in live]).astype(np.float64)
+    if op == SUM:
+        exact = np.array([math.fsum(Pf[:, e]) for e in range(E)])
+        assert np.all(np.abs(got - exact) <= 1e-15 * np.abs(Pf).sum(axis=0) * len(live))
+    else:
+        assert np.array_equal(got, np_red.reduce(Pf, axis=0))
+    # bfloat16 (bit patterns), widened by torch
+    halves = [rng.integers(0, 1 << 16, size=E, dtype=np.uint32).astype(np.uint16) for _ in range(n)]
+    for h in halves:
+        h[(h & 0x7F80) == 0x7F80] = 0x3F80          # no infinities or NaNs among the inputs
+    wide = [torch.from_numpy(h.view(np.int16).copy()).view(torch.bfloat16).double().numpy() for h in halves]
+    got = oracle.reduce_set(halves, occ, op, BF16)
+    Pb = np.stack([wide[i] for i in live])
+    if op == SUM:
+        exact = np.array([math.fsum(Pb[:, e]) for e in range(E)])
+        assert np.all(np.abs(got - exact) <= 1e-15 * np.abs(Pb).sum(axis=0) * len(live))
+    else:
+        assert np.array_equal(got, np_red.reduce(Pb, axis=0))
+    # a single occupant comes back unchanged, whatever the op
+    one = np.array([-1, 7, -1], np.int32)
+    assert np.array_equal(oracle.reduce_set(flts, one, op, F32), flts[7].astype(np.float64))
+    assert np.array_equal(oracle.reduce_set(ints, one, op, I32), ints[7].astype(np.int64))
+
+
 # ------------------------------------------------------------ bfloat16
 
 def test_bf16_conversion_matches_torch_exhaustively():
