@@ -279,6 +279,14 @@ public:
     ~Workspace() { for (Block *b : blocks_) release_block(b, stream_); }
 
     bool is_static() const { return static_base_ != nullptr; }
+    // Hands the blocks over to the caller (who releases them later): what was staged stays valid.
+    std::vector<Block *> detach()
+    {
+        std::vector<Block *> out;
+        out.swap(blocks_);
+        used_ = 0;
+        return out;
+    }
     // why the last request failed
     int error() const { return too_large_ ? HOP_ERR_TOO_LARGE : HOP_ERR_NOMEM; }
     // bytes a request of any kind may still take in static mode
@@ -403,6 +411,15 @@ public:
         release_devbuf(spill_buf_, stream_);
         release_devbuf(kept_buf_, stream_);
         if (busy_ev_) (void)hipEventDestroy(busy_ev_);
+    }
+
+    // the staged programs and scratch this back end's launches refer to, for a caller that will replay them
+    std::vector<Block *> detach_blocks()
+    {
+        dev_prog_ = nullptr;
+        dev_extra_ = nullptr;
+        dev_version_ = 0;
+        return ws_.detach();
     }
 
     // Adaptive sessions ask whether the stream has worked off what this session launched: an event
@@ -829,6 +846,63 @@ static void default_retention(Scheduler &s, const Shape &shape, int dtype)
     s.set_retention(true, (int64_t)(kRetainAboveBytes / shape.chunk_bytes) + 1, elem_bytes(dtype));
 }
 
+// ----------------------------------------------------------------------------
+// repeated calls
+// ----------------------------------------------------------------------------
+
+// A failure-free hop_reduce over small inputs is bound by the host: checking, planning, cutting the
+// program and building its records take longer than the kernels run. A caller that repeats such a
+// call with the same objects, order and shape (a serving loop) gets the launches of the first call
+// again: they are recorded once, together with the staged programs and the scratch they refer to,
+// and enqueued again with the new destination. Bounded: at most kMaxCachedCalls recordings, the least
+// recently used one makes room; hop_shutdown frees them all.
+struct CachedCall {
+    int device = 0, n = 0, k = 0, op = 0, dtype = 0;
+    size_t object_bytes = 0, chunk_bytes = 0;
+    int64_t degree = 0;
+    bool identity_order = true;
+    std::vector<int32_t> order;
+    std::vector<const void *> objs;
+    std::vector<RecordedLaunch> launches;
+    std::vector<Block *> blocks;
+    hop_info_t info = {};
+    int status = HOP_OK;
+    hipStream_t last_stream = nullptr;
+    hipEvent_t ev = nullptr;
+    bool in_use = false;
+    uint64_t stamp = 0;
+};
+static std::vector<CachedCall *> g_calls;
+static uint64_t g_call_stamp = 0;
+static constexpr size_t kMaxCachedCalls = 128;          // a serving loop may rotate through many sets of buffers
+static constexpr size_t kMaxCachedInputBytes = (size_t)64 << 20;      // larger calls are bound by the kernels
+
+static void free_cached_call(CachedCall *c)
+{
+    for (Block *b : c->blocks) release_block(b, c->last_stream);
+    if (c->ev) (void)hipEventDestroy(c->ev);
+    delete c;
+}
+
+static bool same_call(const CachedCall &c, int device, const void *const *objs, int n, size_t object_bytes,
+                      const int32_t *ready_order, int k, int op, int dtype, size_t chunk_bytes, int64_t degree)
+{
+    if (c.device != device || c.n != n || c.k != k || c.op != op || c.dtype != dtype || c.object_bytes != object_bytes ||
+        c.chunk_bytes != chunk_bytes || c.degree != degree || c.identity_order != (ready_order == nullptr))
+        return false;
+    // the objects first: recordings of the same shape over other buffers differ in the first pointer
+    if (std::memcmp(c.objs.data(), objs, sizeof(void *) * (size_t)n) != 0) return false;
+    return !ready_order || std::memcmp(c.order.data(), ready_order, sizeof(int32_t) * (size_t)n) == 0;
+}
+
+static bool nobody_fails(const int64_t *fail_mask, int n, int64_t n_chunks)
+{
+    if (!fail_mask) return true;
+    for (int i = 0; i < n; ++i)
+        if (fail_mask[i] >= 0 && fail_mask[i] < n_chunks) return false;
+    return true;
+}
+
 static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, int n, size_t object_bytes,
                          const int32_t *ready_order, int k, int op, int dtype, size_t chunk_bytes,
                          int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info,
@@ -837,11 +911,57 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
     Shape shape;
     int rc = check_shape(n, object_bytes, k, op, dtype, chunk_bytes, tree_degree, &shape);
     if (rc < 0) return rc;
-    if ((rc = check_order(n, ready_order)) < 0) return rc;
-    if ((rc = check_buffers(objs, n, dsts, n_dst, object_bytes)) < 0) return rc;
+    if (!objs || !dsts) return HOP_ERR_INVALID;
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
     const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    bool cacheable = n_dst == 1 && !no_alloc && object_bytes > 0 && object_bytes <= kMaxCachedInputBytes / (size_t)k &&
+                     nobody_fails(fail_mask, n, shape.n_chunks);
+    if (cacheable) {
+        // a stream that is being captured into a graph takes the plain path: a recording's hand-over between
+        // streams uses an event from outside the capture
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing((hipStream_t)stream, &cap) != hipSuccess) { (void)hipGetLastError(); cacheable = false; }
+        else if (cap != hipStreamCaptureStatusNone) cacheable = false;
+    }
+    if (cacheable) {
+        CachedCall *hit = nullptr;
+        {
+            std::lock_guard<std::mutex> lk(g_mu);
+            for (CachedCall *c : g_calls)
+                if (!c->in_use && same_call(*c, device, objs, n, object_bytes, ready_order, k, op, dtype, chunk_bytes, d)) {
+                    hit = c;
+                    c->in_use = true;
+                    c->stamp = ++g_call_stamp;
+                    break;
+                }
+        }
+        if (hit) {
+            // the objects and the order were checked when the call was recorded; the destination is new
+            rc = check_buffers(objs, n, dsts, n_dst, object_bytes);
+            if (rc >= 0 && hit->last_stream != (hipStream_t)stream) {
+                // the recording's scratch is shared by its uses: a use on another stream follows the last one
+                if (!hit->ev && hipEventCreateWithFlags(&hit->ev, hipEventDisableTiming) != hipSuccess) rc = HOP_ERR_DEVICE;
+                if (rc >= 0 && hipEventRecord(hit->ev, hit->last_stream) == hipSuccess) {
+                    if (hipStreamWaitEvent((hipStream_t)stream, hit->ev, 0) != hipSuccess) rc = HOP_ERR_DEVICE;
+                } else {
+                    (void)hipGetLastError();        // the stream of the last use is gone: its work is done
+                }
+            }
+            for (size_t i = 0; rc >= 0 && i < hit->launches.size(); ++i)
+                if (replay_launch(hit->launches[i], (hipStream_t)stream, dsts[0]) != hipSuccess) rc = HOP_ERR_DEVICE;
+            if (rc >= 0) {
+                hit->last_stream = (hipStream_t)stream;
+                if (info) *info = hit->info;
+                rc = hit->status;
+            }
+            std::lock_guard<std::mutex> lk(g_mu);
+            hit->in_use = false;
+            return rc;
+        }
+    }
+    if ((rc = check_order(n, ready_order)) < 0) return rc;
+    if ((rc = check_buffers(objs, n, dsts, n_dst, object_bytes)) < 0) return rc;
     char *static_base = nullptr;
     if (no_alloc && (rc = static_scratch(device, &static_base)) < 0) return rc;
     try {
@@ -849,8 +969,44 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
                       k, d, static_base, kStaticScratchBytes);
         Scheduler s(n, k, shape.n_chunks, d, &be);
         default_retention(s, shape, dtype);
-        return replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, info);
+        LaunchRecorder rec;
+        hop_info_t my_info = {};
+        if (cacheable) set_launch_recorder(&rec);
+        rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, &my_info);
+        set_launch_recorder(nullptr);
+        if (info) *info = my_info;
+        if (cacheable && rc >= 0 && !rec.unusable && !rec.launches.empty()) {
+            CachedCall *c = new CachedCall;
+            c->device = device; c->n = n; c->k = k; c->op = op; c->dtype = dtype;
+            c->object_bytes = object_bytes; c->chunk_bytes = chunk_bytes; c->degree = d;
+            c->identity_order = ready_order == nullptr;
+            if (ready_order) c->order.assign(ready_order, ready_order + n);
+            c->objs.assign(objs, objs + n);
+            c->launches.swap(rec.launches);
+            c->blocks = be.detach_blocks();
+            c->info = my_info;
+            c->status = rc;
+            c->last_stream = (hipStream_t)stream;
+            CachedCall *victim = nullptr;
+            {
+                std::lock_guard<std::mutex> lk(g_mu);
+                c->stamp = ++g_call_stamp;
+                g_calls.push_back(c);
+                if (g_calls.size() > kMaxCachedCalls) {
+                    size_t at = g_calls.size();
+                    for (size_t i = 0; i < g_calls.size(); ++i)
+                        if (!g_calls[i]->in_use && g_calls[i] != c && (at == g_calls.size() || g_calls[i]->stamp < g_calls[at]->stamp)) at = i;
+                    if (at < g_calls.size()) {
+                        victim = g_calls[at];
+                        g_calls.erase(g_calls.begin() + (long)at);
+                    }
+                }
+            }
+            if (victim) free_cached_call(victim);
+        }
+        return rc;
     } catch (const std::bad_alloc &) {
+        set_launch_recorder(nullptr);
         return HOP_ERR_NOMEM;
     }
 }
@@ -1315,6 +1471,15 @@ size_t hop_workspace_bytes(int n, int k, int n_dst)
 
 int hop_shutdown(void)
 {
+    {
+        // recorded calls first: their blocks go back to the cache that is emptied below
+        std::vector<CachedCall *> calls;
+        {
+            std::lock_guard<std::mutex> lk(g_mu);
+            calls.swap(g_calls);
+        }
+        for (CachedCall *c : calls) free_cached_call(c);
+    }
     std::lock_guard<std::mutex> lk(g_mu);
     int rc = HOP_OK;
     for (Block *b : g_free) {

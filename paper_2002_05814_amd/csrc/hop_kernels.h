@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/hop.h"
 #include "hop_program.h"
 
@@ -72,6 +74,24 @@ struct CopyArgs {
 };
 
 int elem_bytes(int dtype);
+
+// Recording of kernel launches, for calls that will be repeated with the same arguments: while a
+// recorder is installed on the calling thread, every whole-program reduce launch (launch_reduce,
+// launch_reduce_subs) is also written down - kernel, grid, LDS, the argument block - and can be
+// enqueued again later with replay_launch, with another result buffer if the launch wrote the
+// caller's result. Launches of any other kind mark the recording unusable.
+struct RecordedLaunch {
+    const void *kernel;
+    unsigned grid_x, grid_y, lds;
+    bool writes_result;                 // the argument block's ReduceArgs::dst is the caller's destination
+    std::vector<unsigned char> args;
+};
+struct LaunchRecorder {
+    std::vector<RecordedLaunch> launches;
+    bool unusable = false;
+};
+void set_launch_recorder(LaunchRecorder *r);          // per host thread; nullptr = none
+hipError_t replay_launch(const RecordedLaunch &l, hipStream_t stream, void *dst);
 
 // Launch shape of the kernels, as text.
 const char *kernel_config();

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstring>
 #include <mutex>
 #include <utility>
 #include <vector>
@@ -50,6 +51,45 @@ const char *kernel_config()
            "cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations); "
            "launches that keep or read partial results: one step at a time, 4|2|1 vectors/lane, pieces 64 KiB apart from 2048 "
            "tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators indexed like the elements, nontemporal";
+}
+
+static thread_local LaunchRecorder *tl_recorder = nullptr;
+
+void set_launch_recorder(LaunchRecorder *r) { tl_recorder = r; }
+
+static void not_recordable()
+{
+    if (tl_recorder) tl_recorder->unusable = true;
+}
+
+// Launch of a reduce kernel whose only parameter is its argument block (ReduceArgs first in it).
+template <class Args>
+static hipError_t enqueue(void (*kernel)(Args), dim3 grid, unsigned lds, hipStream_t stream, const Args &a, bool writes_result)
+{
+    if (tl_recorder) {
+        RecordedLaunch r;
+        r.kernel = (const void *)kernel;
+        r.grid_x = grid.x;
+        r.grid_y = grid.y;
+        r.lds = lds;
+        r.writes_result = writes_result;
+        r.args.assign((const unsigned char *)&a, (const unsigned char *)&a + sizeof a);
+        tl_recorder->launches.push_back(std::move(r));
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t replay_launch(const RecordedLaunch &l, hipStream_t stream, void *dst)
+{
+    // the argument block is copied so that the result pointer can be replaced (and because another
+    // thread may replay the same recording)
+    alignas(16) unsigned char block[sizeof(ReduceArgsInline)];
+    if (l.args.size() > sizeof block) return hipErrorInvalidValue;
+    std::memcpy(block, l.args.data(), l.args.size());
+    if (l.writes_result) ((ReduceArgs *)block)->dst = dst;
+    void *params[1] = {block};
+    return hipLaunchKernel(l.kernel, dim3(l.grid_x, l.grid_y), dim3(kThreads), params, l.lds, stream);
 }
 
 static Launcher pick(int dtype, int op, int depth)
@@ -144,14 +184,11 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     const unsigned grid = grid_of(vpt, stride_log2);
     if (inl) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
-        hipLaunchKernelGGL(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), dim3(kThreads), lds,
-                           stream, a);
-    } else {
-        if (!dev_prog) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(shape == 0 ? l.dev_small : shape == 1 ? l.dev_mid : l.dev, dim3(grid), dim3(kThreads), lds,
-                           stream, a.base);
+        for (int i = n_entries; i < kInlineEntries; ++i) a.steps[i] = DevEntry{nullptr, 0, 0};
+        return enqueue(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), lds, stream, a, true);
     }
-    return hipGetLastError();
+    if (!dev_prog) return hipErrorInvalidValue;
+    return enqueue(shape == 0 ? l.dev_small : shape == 1 ? l.dev_mid : l.dev, dim3(grid), lds, stream, a.base, true);
 }
 
 hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
@@ -182,6 +219,7 @@ hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int dept
     const size_t n_all = a.n_vec + (size_t)a.lead_vecs;
     const unsigned grid = !strided ? grid_for(n_all, (size_t)kThreads * l.vpt)
                                    : grid_for(n_all, ((size_t)kThreads * l.vpt) << kPieceStrideLog2) << kPieceStrideLog2;
+    not_recordable();
     hipLaunchKernelGGL(l.seg, dim3(grid), dim3(kThreads), lds, stream, a);
     return hipGetLastError();
 }
@@ -216,6 +254,7 @@ hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, 
     const size_t n_all = a.base.n_vec + (size_t)a.base.lead_vecs;
     const unsigned grid = !strided ? grid_for(n_all, (size_t)kThreads * l.vpt)
                                    : grid_for(n_all, ((size_t)kThreads * l.vpt) << kPieceStrideLog2) << kPieceStrideLog2;
+    not_recordable();
     if (n_entries <= kInlineEntries) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
         hipLaunchKernelGGL(l.kept_inl, dim3(grid), dim3(kThreads), lds, stream, a);
@@ -240,8 +279,7 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
     fill_range(a, dtype, byte_begin, byte_end);
     a.sub_entries = sub_entries;
     const unsigned grid = grid_for(a.n_vec, (size_t)kThreads);
-    hipLaunchKernelGGL(l.dev_small, dim3(grid, (unsigned)n_subs), dim3(kThreads), 0, stream, a);
-    return hipGetLastError();
+    return enqueue(l.dev_small, dim3(grid, (unsigned)n_subs), 0, stream, a, false);
 }
 
 // One destination: every vector is read once (non-temporal) and stored once; 8 contiguous
@@ -276,6 +314,7 @@ static_assert(kFanoutSpanTiles % 8 == 0, "a tile must meet the same XCD for ever
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
                        size_t byte_begin, size_t byte_end, void *dst0, unsigned dst_residue)
 {
+    not_recordable();
     if (dst0) dst_residue = (unsigned)((uintptr_t)dst0 & 127);
     if (byte_end <= byte_begin || n_dst <= 0) return hipSuccess;
     if (!dsts && (n_dst != 1 || !dst0)) return hipErrorInvalidValue;

@@ -1075,6 +1075,51 @@ def test_late_arrival_into_a_hole_reuses_the_kept_partials():
     assert orc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
 
 
+def test_repeated_small_calls_replay_their_recorded_launches_correctly():
+    # a failure-free call over small inputs is recorded the first time and replayed afterwards; every
+    # replay must land in the destination of that call and see the objects' current contents, and
+    # anything that changes the schedule (order, k, degree, another object) must not hit the recording
+    d = dev()
+    w = workloads.WORKLOADS[5]
+    objs = workloads.make_objects(w, device=d)
+    order = w.ready_order()
+
+    def check(objs_now, order_now, k, deg, stream=None):
+        dst = torch.full_like(objs_now[0], -3)
+        rc, info = hop.hop_reduce(dst, objs_now, k, "sum", w.dtype, w.chunk_bytes, deg, order_now, None, stream=stream)
+        if stream is not None:
+            stream.synchronize()
+        torch.cuda.synchronize()
+        orc, want, k_eff, _ = oracle.reduce([workloads.to_numpy(o) for o in objs_now], k, oracle.SUM, oracle.F32,
+                                            w.chunk_bytes // 4, deg, order_now, None)
+        assert rc == orc == hop.HOP_OK and info["k_eff"] == k_eff
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+        return info
+    first = check(objs, order, w.k, w.tree_degree)
+    for rep in range(3):                               # replays: new destination each time, contents changed in place
+        objs[int(order[rep])].mul_(1.5)
+        assert check(objs, order, w.k, w.tree_degree) == first
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    check(objs, order, w.k, w.tree_degree, stream=st)            # another stream shares the recording's scratch
+    check(objs, order, w.k, w.tree_degree)
+    order2 = order.copy()
+    order2[[0, 1]] = order2[[1, 0]]
+    check(objs, order2, w.k, w.tree_degree)                      # another arrival order: another schedule
+    check(objs, order, w.k - 1, w.tree_degree)
+    check(objs, order, w.k, 4)
+    swapped = list(objs)
+    swapped[3], swapped[4] = swapped[4], swapped[3]
+    check(swapped, order, w.k, w.tree_degree)
+    # more distinct calls than recordings are kept: the oldest ones make room and are simply planned again
+    for i in range(140):
+        check(objs[:200 + i], np.arange(200 + i, dtype=np.int32), 150 + i, 8)
+    check(objs, order, w.k, w.tree_degree)
+    assert hop.hop_shutdown() == hop.HOP_OK                      # frees the recordings too
+    check(objs, order, w.k, w.tree_degree)
+    check(objs, order, w.k, w.tree_degree)
+
+
 def test_two_host_threads_on_their_own_streams_and_shutdown():
     import threading
     d = dev()
