@@ -79,8 +79,7 @@ def time_calls(fn, steps, warmup, torch):
 
 def time_calls_median(fn, steps, warmup, torch, batch=100):
     """For launch-bound workloads (a call takes 10-30 us, an event behind every call would be part of what is
-    measured): the timed calls are taken in batches and the median batch is reported, so that a one-off stall
-    of the runtime (tens of ms, a few times per process) does not decide the figure."""
+    measured): the timed calls are taken in batches of 100; mean and median over the batches are reported."""
     import statistics
     for _ in range(warmup):
         fn()
@@ -280,9 +279,16 @@ def main():
         sys.exit(1)
     hop.lib()                                   # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
+    # CPython's full garbage collection walks every tracked object of the process (170 000 after importing
+    # torch: 30-40 ms), and the per-call objects of the binding trigger one every few thousand calls, in the
+    # middle of whatever loop is being timed. What exists now is long-lived: it is moved out of the
+    # collector's sight, as a serving process would do after start-up.
+    import gc
+    gc.collect()
+    gc.freeze()
 
     def run_workload(cfg, steps, warmup, no_fail=False, timer=time_calls):
-        w = workloads.WORKLOADS[cfg]
+        w = workloads.WORKLOADS[cfg] if cfg in workloads.WORKLOADS else workloads.EXTRA_WORKLOADS[cfg]
         if no_fail:
             w = w.scaled(w.object_bytes, fail={}, name=w.name + "_without_failure")
         objs = workloads.make_objects(w, device=dev)
@@ -419,7 +425,7 @@ def main():
     if args.degree_sweep:
         sweep = {}
         table = hop.PtrTable(objs)
-        for deg in (1, 2, 4, 8, w.k):
+        for deg in sorted({1, 2, 4, 8, w.k}):
             st = {"i": 0, "info": None}
 
             def step_deg():
@@ -430,6 +436,8 @@ def main():
             nbytes = (st["info"]["k_eff"] + 1) * w.object_bytes        # reduce only, nobody fails
             sweep["d=%d" % deg] = {"ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                    "levels": st["info"]["stack_depth"]}
+        rc_cal, lat, bw = hop.hop_calibrate()
+        sweep["calibrated"] = {"status": rc_cal, "latency_us": round(lat * 1e6, 3), "GB/s": round(bw / 1e9, 1)}
         sweep["picked_by_eq1"] = hop.hop_pick_degree(w.k, w.object_bytes, 0.0, 0.0)
         out["degree_sweep"] = sweep
     if args.streamed_interval_us is not None:

@@ -413,9 +413,32 @@ int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int want_step
 int hop_plan_slots(int k, int tree_degree, int32_t *node_of_slot);
 
 /* Degree the library would choose for tree_degree = 0: argmin over {1, 2, k}
- * of T(d) of Eq. 1 (section 3.4.2) with per-level latency latency_s and
- * bandwidth bytes_per_s; non-positive values select the library defaults. */
+ * (the candidates of the paper's runtime, section 4) of T(d) of Eq. 1
+ * (section 3.4.2) with per-level latency latency_s and bandwidth
+ * bytes_per_s. Candidates within 2 % of the best predicted time count as
+ * equal; among equals the tree that needs the fewest accumulator levels wins
+ * (a chain and a star need one), then the smaller degree. Non-positive
+ * values select the constants measured by the last hop_calibrate of this
+ * process, or, if there was none, typical MI355X figures (3 us, 6.5 TB/s). */
 int hop_pick_degree(int k, size_t object_bytes, double latency_s, double bytes_per_s);
+
+/* Measures the two constants of Eq. 1 on the current device, as section 4 of
+ * the paper does on its cluster: latency_s = what one more dependent launch of
+ * the smallest reduce costs (the price of a tree level that is a launch of its
+ * own), bytes_per_s = the rate at which the reduce kernel streams objects in
+ * (four 64 MiB objects). Takes under a millisecond of GPU time on a stream of
+ * its own, allocates 320 MiB of device memory and frees it again, waits for the
+ * result. The values are kept per device and used by every later
+ * tree_degree = 0 call there; the first such call on a device calibrates by
+ * itself (and so blocks once) unless its stream is being captured into a
+ * graph. Either pointer may be NULL. On one GPU the degree changes neither the
+ * bytes moved nor the number of launches of the default policy, only the
+ * association order and the number of accumulator levels, so the choice
+ * matters little for speed (measured: under 1 % for fp32 and int32); for floats
+ * it decides the result's bits, which therefore can differ between devices
+ * and library versions when tree_degree is 0. Pass an explicit degree where
+ * bit-reproducibility matters. */
+int hop_calibrate(double *latency_s, double *bytes_per_s);
 
 /* Bytes of device scratch one hop_reduce / hop_allreduce call of this shape
  * takes from the library's cached workspace (programs, destination tables).

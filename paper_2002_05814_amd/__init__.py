@@ -32,7 +32,7 @@ EXPORTS = ["hop_reduce", "hop_reduce_noalloc", "hop_noalloc_scratch_bytes", "hop
            "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready", "hop_session_ready_after",
            "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_set_adaptive", "hop_session_set_retention", "hop_session_chunks_final",
            "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
-           "hop_pick_degree", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
+           "hop_pick_degree", "hop_calibrate", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
 
 
 class HopInfo(ctypes.Structure):
@@ -133,6 +133,7 @@ def lib() -> ctypes.CDLL:
                                      ctypes.POINTER(ctypes.c_int)]
         L.hop_plan_slots.argtypes = [ctypes.c_int, ctypes.c_int, i32p]
         L.hop_pick_degree.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
+        L.hop_calibrate.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.hop_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.hop_workspace_bytes.restype = ctypes.c_size_t
         L.hop_shutdown.argtypes = []
@@ -438,6 +439,13 @@ def hop_plan_slots(k, tree_degree):
 
 def hop_pick_degree(k, object_bytes, latency_s=0.0, bytes_per_s=0.0):
     return lib().hop_pick_degree(int(k), int(object_bytes), float(latency_s), float(bytes_per_s))
+
+
+def hop_calibrate():
+    """Measures Eq. 1's constants on the current device. Returns (status, latency_s, bytes_per_s)."""
+    lat, bw = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = lib().hop_calibrate(ctypes.byref(lat), ctypes.byref(bw))
+    return rc, lat.value, bw.value
 
 
 def hop_workspace_bytes(n, k, n_dst=0):

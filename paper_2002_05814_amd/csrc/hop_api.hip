@@ -818,22 +818,132 @@ static int check_disjoint(void *const *dsts, int n_dst, size_t object_bytes)
     }
 }
 
-static const double kDefaultLatency = 2e-6;     // seconds per tree level (kernel-launch scale)
-static const double kDefaultBandwidth = 5e12;   // bytes per second (HBM scale)
+// The two constants of the cost model of section 3.4.2 (Eq. 1): L, the latency one more tree level
+// costs, and B, the bandwidth at which a node takes in an object. The paper's runtime measures both
+// (section 4); here calibrate() measures them on the device (what one more dependent launch costs,
+// and the rate at which the reduce kernel streams objects in) and keeps them per device. Until a
+// device has been calibrated the figures below stand in (typical MI355X values), so that the
+// host-only planning calls, which never touch a device, have something to work with.
+static const double kDefaultLatency = 3e-6;     // seconds
+static const double kDefaultBandwidth = 6.5e12; // bytes per second
+constexpr int kMaxCalibratedDevices = 64;
+static double g_latency[kMaxCalibratedDevices], g_bandwidth[kMaxCalibratedDevices];     // 0 = not measured
+static int g_calibrated_last = -1;              // the device calibrated last: what host-only planning uses
 
+static void model_constants(int device, double *L, double *B)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (device < 0) device = g_calibrated_last;
+    const bool have = device >= 0 && device < kMaxCalibratedDevices && g_latency[device] > 0;
+    *L = have ? g_latency[device] : kDefaultLatency;
+    *B = have ? g_bandwidth[device] : kDefaultBandwidth;
+}
+
+// argmin of Eq. 1 over the paper's candidates {1, 2, k} (section 4). Candidates whose predicted
+// time lies within 2 % of the best count as equal; among equals the tree with the fewest
+// accumulator levels wins (the reduce kernels hold fewer vectors per lane the more levels a tree
+// needs), then the smaller degree.
 static int pick_degree(int k, size_t object_bytes, double L, double B)
 {
     if (k <= 2) return 1;
-    if (!(L > 0)) L = kDefaultLatency;
-    if (!(B > 0)) B = kDefaultBandwidth;
-    const int cand[3] = {1, 2, k};
-    int best = 1;
-    double best_t = tree_cost(k, 1, (double)object_bytes, L, B);
-    for (int i = 1; i < 3; ++i) {
-        double t = tree_cost(k, cand[i], (double)object_bytes, L, B);
-        if (t < best_t) { best_t = t; best = cand[i]; }
+    if (!(L > 0) || !(B > 0)) {
+        double l0, b0;
+        model_constants(-1, &l0, &b0);
+        if (!(L > 0)) L = l0;
+        if (!(B > 0)) B = b0;
     }
-    return best;
+    const int cand[3] = {1, 2, k};
+    double t[3], best_t = 0;
+    for (int i = 0; i < 3; ++i) {
+        t[i] = tree_cost(k, cand[i], (double)object_bytes, L, B);
+        if (i == 0 || t[i] < best_t) best_t = t[i];
+    }
+    int best = -1, best_depth = 0;
+    for (int i = 0; i < 3; ++i) {
+        if (t[i] > best_t * 1.02) continue;
+        const int depth = cand[i] == 2 ? full_tree_depth(k, 2) : 1;       // a chain and a star need one level
+        if (best < 0 || depth < best_depth) { best = i; best_depth = depth; }
+    }
+    return cand[best];
+}
+
+// Measures L and B on the current device (a few hundred microseconds of GPU time, 320 MiB of scratch
+// allocated and freed again) and keeps them for the tree_degree = 0 calls on that device.
+static int calibrate(double *latency_s, double *bytes_per_s)
+{
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device >= kMaxCalibratedDevices) return HOP_ERR_DEVICE;
+    constexpr size_t kBytes = (size_t)64 << 20;
+    constexpr int kSources = 4, kTiny = 32;
+    char *buf = nullptr;
+    hipStream_t stream = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = HOP_OK;
+    double L = 0, B = 0;
+    if (hipMalloc((void **)&buf, kBytes * (kSources + 1)) != hipSuccess) { (void)hipGetLastError(); return HOP_ERR_NOMEM; }
+    if (hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) != hipSuccess || hipEventCreate(&e0) != hipSuccess ||
+        hipEventCreate(&e1) != hipSuccess)
+        rc = HOP_ERR_DEVICE;
+    if (rc == HOP_OK && hipMemsetAsync(buf, 0, kBytes * (kSources + 1), stream) != hipSuccess) rc = HOP_ERR_DEVICE;
+    if (rc == HOP_OK) {
+        DevEntry steps[kSources];
+        for (int i = 0; i < kSources; ++i) steps[i] = DevEntry{buf + (size_t)(i + 1) * kBytes, i == 0 ? (1u << 8) : 0u, 0};
+        float ms = 0;
+        // L: dependent launches of the smallest reduce (one vector), back to back
+        for (int pass = 0; pass < 2 && rc == HOP_OK; ++pass) {
+            if (hipEventRecord(e0, stream) != hipSuccess) rc = HOP_ERR_DEVICE;
+            for (int i = 0; i < kTiny && rc == HOP_OK; ++i)
+                if (launch_reduce(stream, HOP_F32, HOP_SUM, 1, steps, nullptr, kSources, buf, 0, 16) != hipSuccess) rc = HOP_ERR_DEVICE;
+            if (rc == HOP_OK && (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                                 hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+                rc = HOP_ERR_DEVICE;
+            L = (double)ms * 1e-3 / kTiny;              // the second pass counts (the first loads the kernel)
+        }
+        // B: the reduce kernel over four 64 MiB objects, the fastest of three launches
+        for (int pass = 0; pass < 4 && rc == HOP_OK; ++pass) {
+            if (hipEventRecord(e0, stream) != hipSuccess ||
+                launch_reduce(stream, HOP_F32, HOP_SUM, 1, steps, nullptr, kSources, buf, 0, kBytes) != hipSuccess ||
+                hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+                rc = HOP_ERR_DEVICE;
+            else if (pass > 0 && ms > 0) B = std::max(B, (double)kBytes * (kSources + 1) / ((double)ms * 1e-3));
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (stream) { (void)hipStreamSynchronize(stream); (void)hipStreamDestroy(stream); }
+    (void)hipFree(buf);
+    if (rc != HOP_OK) { (void)hipGetLastError(); return rc; }
+    if (!(L > 0) || !(B > 0)) return HOP_ERR_DEVICE;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_latency[device] = L;
+        g_bandwidth[device] = B;
+        g_calibrated_last = device;
+    }
+    if (latency_s) *latency_s = L;
+    if (bytes_per_s) *bytes_per_s = B;
+    return HOP_OK;
+}
+
+// The degree for tree_degree = 0 on the current device: Eq. 1 with that device's measured constants,
+// which are taken on the first such call unless the stream is being captured (then, and if the
+// measurement fails, with what is there).
+static int auto_degree(int device, int k, size_t object_bytes, hipStream_t stream)
+{
+    bool have;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        have = device >= 0 && device < kMaxCalibratedDevices && g_latency[device] > 0;
+    }
+    if (!have && k > 2) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) (void)calibrate(nullptr, nullptr);
+        else (void)hipGetLastError();
+    }
+    double L, B;
+    model_constants(device, &L, &B);
+    return pick_degree(k, object_bytes, L, B);
 }
 
 // Launches over more than this many bytes per object keep partial results while a participant
@@ -914,7 +1024,7 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
     if (!objs || !dsts) return HOP_ERR_INVALID;
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
-    const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    const int64_t d = tree_degree > 0 ? tree_degree : auto_degree(device, k, object_bytes, (hipStream_t)stream);
     bool cacheable = n_dst == 1 && !no_alloc && object_bytes > 0 && object_bytes <= kMaxCachedInputBytes / (size_t)k &&
                      nobody_fails(fail_mask, n, shape.n_chunks);
     if (cacheable) {
@@ -1262,7 +1372,7 @@ int hop_session_begin(hop_session_t **s, void *dst, const void *const *objs, int
     if ((rc = check_buffers(objs, n, dsts, 1, object_bytes)) < 0) return rc;
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
-    const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+    const int64_t d = tree_degree > 0 ? tree_degree : auto_degree(device, k, object_bytes, (hipStream_t)stream);
     try {
         std::unique_ptr<hop_session> h(new hop_session);
         h->be.reset(new GpuBackend(device, (hipStream_t)stream, objs, n, std::vector<void *>(1, dst), shape,
@@ -1459,6 +1569,15 @@ int hop_pick_degree(int k, size_t object_bytes, double latency_s, double bytes_p
 {
     if (k < 1) return HOP_ERR_INVALID;
     return pick_degree(k, object_bytes, latency_s, bytes_per_s);
+}
+
+int hop_calibrate(double *latency_s, double *bytes_per_s)
+{
+    try {
+        return calibrate(latency_s, bytes_per_s);
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
 }
 
 size_t hop_workspace_bytes(int n, int k, int n_dst)

@@ -684,10 +684,12 @@ def test_eager_segments_over_long_ranges(dtype, mib):
 
 
 def test_readiness_by_event_needs_no_host_synchronisation():
-    # The producers run on another stream: each one first idles for a while, then writes its object
-    # chunk by chunk and records an event per chunk. The session is told "ready after this event";
-    # nobody waits on the host between producing and reducing. Had the session's stream not waited
-    # for the events it would have read the zeros the objects held before.
+    # The producers run on another stream: before each chunk of each object the producer stream is kept
+    # busy with real work (passes over a 256 MiB buffer), then the chunk is written and an event recorded.
+    # The session is told "ready after this event"; nobody waits on the host between producing and
+    # reducing, and the session's stream has nothing else to wait for. Had it not waited for the events, it
+    # would have read the zeros the objects held before. (A correct library can never fail this test,
+    # however the host and the device are scheduled: only the result is checked, no timing.)
     d = dev()
     rng = np.random.default_rng(21)
     C, ce, n = 4, 4096, 5
@@ -696,6 +698,7 @@ def test_readiness_by_event_needs_no_host_synchronisation():
     staged = [workloads.from_numpy(v, "f32", d) for v in vals]
     objs = [torch.zeros(E, device=d) for _ in range(n)]
     dst = torch.zeros(E, device=d)
+    ballast = torch.zeros(64 << 20, device=d)
     producer, consumer = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
     rc, s = hop.hop_session_begin(dst, objs, n, "sum", "f32", ce * 4, 2, stream=consumer.cuda_stream)
@@ -705,7 +708,8 @@ def test_readiness_by_event_needs_no_host_synchronisation():
     for c in range(C):
         for i in order:
             with torch.cuda.stream(producer):
-                torch.cuda._sleep(20_000_000)                     # a few milliseconds of nothing
+                for _ in range(4):
+                    ballast.add_(1.0)                             # about half a millisecond of work in front of the data
                 objs[i][c * ce:(c + 1) * ce].copy_(staged[i][c * ce:(c + 1) * ce])
                 ev = torch.cuda.Event()
                 ev.record(producer)
@@ -713,11 +717,12 @@ def test_readiness_by_event_needs_no_host_synchronisation():
             assert hop.hop_session_ready_after(s, i, c + 1, ev) == hop.HOP_OK
     rc, info = hop.hop_session_finish(s)
     assert rc == hop.HOP_OK and info["n_launches"] == C
-    # the host ran ahead: the producers (some 0.2 s of idling) cannot be through yet
-    assert not producer.query()
+    consumer.synchronize()                    # the consumer alone: if it had not waited for the producer, this returns early
+    got = workloads.to_numpy(dst)
     torch.cuda.synchronize()
     _, want, _, _ = oracle.reduce(vals, n, oracle.SUM, oracle.F32, ce, 2, np.array(order, np.int32), None)
-    assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+    assert np.array_equal(bits(got), bits(want))
+    assert float(ballast[0]) == 4.0 * C * n
 
 
 def test_other_stream():
@@ -1073,6 +1078,19 @@ def test_late_arrival_into_a_hole_reuses_the_kept_partials():
     orc, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], 8, oracle.SUM, oracle.F32, w.chunk_bytes // 4, 2,
                                     order, fm)
     assert orc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+
+
+def test_calibration_feeds_the_automatic_degree():
+    rc, lat, bw = hop.hop_calibrate()
+    assert rc == hop.HOP_OK
+    # a dependent launch costs microseconds, the reduce streams at terabytes per second (MI355X peak: 8)
+    assert 2e-7 < lat < 1e-4 and 1e12 < bw < 8e12, (lat, bw)
+    for k, nbytes in ((64, 16 << 20), (12, 64 << 20), (1000, 4096), (5, 1 << 20)):
+        assert hop.hop_pick_degree(k, nbytes) == hop.hop_pick_degree(k, nbytes, lat, bw)
+    # tree_degree 0 uses it, and the result is the oracle's for the degree reported
+    w = workloads.WORKLOADS[3].scaled(256 << 10, 16 << 10, n_dst=0)
+    rc, info = run_both(w, "sum")
+    assert rc == hop.HOP_OK and info["degree_used"] == hop.hop_pick_degree(w.k, w.object_bytes, lat, bw)
 
 
 def test_repeated_small_calls_replay_their_recorded_launches_correctly():

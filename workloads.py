@@ -92,6 +92,15 @@ WORKLOADS: Dict[int, Workload] = {
 }
 
 
+# Not one of the five: a deep bf16 tree for the degree ablation (64 inputs of 32 MiB; a binary tree over
+# them needs 5 accumulator levels, a chain or a star one).
+EXTRA_WORKLOADS: Dict[int, Workload] = {
+    6: Workload("sweep_bf16_64x32MiB", n=64, dtype="bf16", object_bytes=32 * MiB, chunk_bytes=2 * MiB,
+                k=64, tree_degree=0, ops=("sum",), dist="normal_std1", order_seed=58140006,
+                data_seed=SEED_BASE + 6),
+}
+
+
 def _fill(w: Workload, n_elems: int, gen: torch.Generator, device) -> torch.Tensor:
     """One object's values, drawn from the workload's recipe."""
     if w.dist == "uniform_pm1":
