@@ -440,13 +440,29 @@ int hop_pick_degree(int k, size_t object_bytes, double latency_s, double bytes_p
  * bit-reproducibility matters. */
 int hop_calibrate(double *latency_s, double *bytes_per_s);
 
-/* Bytes of device scratch one hop_reduce / hop_allreduce call of this shape
- * takes from the library's cached workspace (programs, destination tables).
- * A call over 128 or more inputs of at most 1 MiB each (fp32, int32) is cut
- * into sub-programs and takes, beyond this figure, one object-sized partial
- * result per sub-program plus their programs, at most 16 MiB + 1 MiB in all;
- * a cut that would need more is not made. */
-size_t hop_workspace_bytes(int n, int k, int n_dst);
+/* Upper bound, in bytes, of the device memory the library takes from its
+ * cached workspaces for ONE hop_reduce / hop_allreduce call or one session of
+ * this shape (arguments as hop_reduce; n_dst = destinations, 1 for a plain
+ * reduce; tree_degree 0 = the degree the library would pick now). Counted:
+ *   - the staged program (16 bytes per step when there are more than 128) and
+ *     the table of the other n_dst - 1 destinations, in blocks of 256 KiB (the
+ *     same number of bytes of pinned host memory goes with them);
+ *   - for a call over 128 or more inputs of at most 1 MiB each (fp32, int32):
+ *     the partial results and records of its sub-programs (at most 16 MiB; a
+ *     cut that would need more is not made);
+ *   - HOP_WS_EAGER (sessions with hop_session_set_eager(s, m >= 1)): the saved
+ *     accumulators, 4 bytes per element and accumulator level of the tree;
+ *   - HOP_WS_FAILURES (participants may fail mid-stream; objects above 1 MiB):
+ *     the kept partial results, 4 bytes per element and subtree below the
+ *     root (hop_session_set_retention).
+ * The memory is allocated on first use, cached by the library (idle buffers
+ * above 8 GiB in total are freed) and freed by hop_shutdown; calls that find
+ * nothing cached allocate, and so can block. Returns 0 for invalid arguments.
+ * hop_reduce_noalloc takes none of this: see hop_noalloc_scratch_bytes. */
+#define HOP_WS_EAGER 1
+#define HOP_WS_FAILURES 2
+size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes, int tree_degree,
+                           hop_dtype_t dtype, int n_dst, int policy);
 
 /* Frees the cached workspaces of the calling process (optional; for leak checks). */
 int hop_shutdown(void);

@@ -134,7 +134,8 @@ def lib() -> ctypes.CDLL:
         L.hop_plan_slots.argtypes = [ctypes.c_int, ctypes.c_int, i32p]
         L.hop_pick_degree.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
         L.hop_calibrate.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
-        L.hop_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        L.hop_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
+                                          ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.hop_workspace_bytes.restype = ctypes.c_size_t
         L.hop_shutdown.argtypes = []
         L.hop_strerror.argtypes = [ctypes.c_int]
@@ -448,8 +449,12 @@ def hop_calibrate():
     return rc, lat.value, bw.value
 
 
-def hop_workspace_bytes(n, k, n_dst=0):
-    return lib().hop_workspace_bytes(int(n), int(k), int(n_dst))
+HOP_WS_EAGER, HOP_WS_FAILURES = 1, 2
+
+
+def hop_workspace_bytes(n, k, object_bytes, chunk_bytes, tree_degree, dtype, n_dst=1, policy=0):
+    return lib().hop_workspace_bytes(int(n), int(k), int(object_bytes), int(chunk_bytes), int(tree_degree),
+                                     _code(DTYPES, dtype), int(n_dst), int(policy))
 
 
 def hop_kernel_config() -> str:

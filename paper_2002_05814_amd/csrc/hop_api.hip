@@ -443,8 +443,9 @@ public:
     {
         if (kept_) return true;
         if (ws_.is_static() || n_partials < 1 || shape_.object_bytes == 0) return false;
-        const size_t n_elems = shape_.object_bytes / (size_t)elem_bytes(dtype_);
-        kept_stride_ = (n_elems * 4 + 255) & ~(size_t)255;
+        // 4 bytes per element, in blocks for 64 source vectors each (see kept_offset in the device code)
+        const size_t n_blocks = ((shape_.object_bytes + 15) / 16 + 63) / 64;
+        kept_stride_ = n_blocks * 1024 * (size_t)(4 / elem_bytes(dtype_));
         if (kept_stride_ > kMaxKeptBytes / (size_t)n_partials) return false;
         kept_buf_ = acquire_devbuf(device_, kept_stride_ * (size_t)n_partials);
         if (!kept_buf_) return false;
@@ -1580,12 +1581,51 @@ int hop_calibrate(double *latency_s, double *bytes_per_s)
     }
 }
 
-size_t hop_workspace_bytes(int n, int k, int n_dst)
+size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes, int tree_degree, hop_dtype_t dtype,
+                           int n_dst, int policy)
 {
-    (void)n;
-    if (k < 0 || n_dst < 0) return 0;
-    size_t need = (size_t)k * sizeof(DevEntry) + (size_t)(n_dst > 1 ? n_dst - 1 : 0) * sizeof(void *) + 512;
-    return need < kMinBlock ? kMinBlock : ((need + kMinBlock - 1) / kMinBlock) * kMinBlock;
+    Shape shape;
+    if (n_dst < 0 || check_shape(n, object_bytes, k, HOP_SUM, (int)dtype, chunk_bytes, tree_degree, &shape) < 0) return 0;
+    try {
+        const int64_t d = tree_degree > 0 ? tree_degree : pick_degree(k, object_bytes, 0, 0);
+        auto blocks = [](size_t bytes) { return bytes == 0 ? (size_t)0 : ((bytes + kMinBlock - 1) / kMinBlock) * kMinBlock; };
+        auto round256 = [](size_t bytes) { return (bytes + 255) & ~(size_t)255; };
+        const size_t n_elems = object_bytes / (size_t)elem_bytes((int)dtype);
+        // staged program (longer than the kernel arguments hold) and destination table
+        size_t staged = 0;
+        if (k > kInlineEntries) staged += round256((size_t)k * sizeof(DevEntry));
+        if (n_dst > 1) staged += round256((size_t)(n_dst - 1) * sizeof(void *));
+        size_t total = blocks(staged);
+        // the cut into sub-programs of a call over many small objects: their partial results and records
+        if (dtype != HOP_BF16 && (size_t)k >= 128 && object_bytes > 0 && object_bytes <= ((size_t)1 << 20)) {
+            Tree tr;
+            tr.shape(k, d);
+            std::vector<int32_t> occ((size_t)k, 0);
+            std::vector<Entry> prog;
+            compile_program(tr, occ, prog);
+            MultiPlan mp;
+            if (plan_passes(prog, 128, 4, kMaxSubSteps, mp)) {
+                const size_t partials = round256(object_bytes) * mp.n_subs();
+                if (partials <= ((size_t)16 << 20))
+                    total = std::max(total, blocks(partials + (mp.steps.size() + mp.n_subs() * 2 + mp.top.size()) * sizeof(DevEntry) + 512));
+            }
+        }
+        const size_t level_stride = round256(n_elems * 4);
+        if (policy & HOP_WS_EAGER) {
+            // saved accumulators: one array of 4-byte values per level the tree can need, plus one staged program
+            // segment per launch (at most k steps each, one 256 KiB block at a time)
+            total += level_stride * (size_t)std::min(HOP_MAX_DEPTH, std::max(1, full_tree_depth(k, d)));
+            total += blocks(round256((size_t)k * sizeof(DevEntry)));
+        }
+        if ((policy & HOP_WS_FAILURES) && object_bytes > kRetainAboveBytes) {
+            const size_t runs = subtrees_below_root(k, d, kMaxKept).size();
+            const size_t kept_stride = (((object_bytes + 15) / 16 + 63) / 64) * 1024 * (size_t)(4 / elem_bytes((int)dtype));
+            if (runs > 0 && kept_stride <= ((size_t)16 << 30) / runs) total += kept_stride * runs;
+        }
+        return total;
+    } catch (const std::bad_alloc &) {
+        return 0;
+    }
 }
 
 int hop_shutdown(void)

@@ -457,16 +457,56 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
     }
 }
 
+// Layout of a kept partial result: one accumulator-typed value (4 bytes) per element of the
+// object. The accumulators of 64 consecutive source vectors (the vectors the lanes of a wave hold)
+// form a block of Q * 1 KiB, Q = W / 4: first the accumulators 0..3 of all 64 vectors, then 4..7 of
+// all 64 (bf16: Q = 2; for 32-bit elements the layout is simply that of the object). Every store
+// and load instruction of a wave then covers 1 KiB of consecutive addresses and a partial is one
+// sequential stream. With a vector's W accumulators side by side instead, each instruction would
+// touch every other 16 bytes of 2 KiB (measured: 10 % more bytes written to memory than stored);
+// with the two halves in two planes an object's length apart, twice as many write streams (10 %
+// slower).
+template <int DT> __device__ __forceinline__ size_t kept_offset(size_t off, int q)
+{
+    constexpr size_t Q = Traits<DT>::W / 4;
+    const size_t v = off >> 4;                   // index of the 16-byte source vector
+    return ((v >> 6) * Q + (size_t)q) * 1024 + (v & 63) * 16;
+}
+template <int DT> __device__ __forceinline__ void load_kept(const char *base, size_t off, typename Traits<DT>::acc_t *x)
+{
+    using A = typename Traits<DT>::acc_t;
+#pragma unroll
+    for (int q = 0; q < Traits<DT>::W / 4; ++q) {
+        const uint4 r = ld16(base, kept_offset<DT>(off, q));
+        x[4 * q + 0] = __builtin_bit_cast(A, r.x);
+        x[4 * q + 1] = __builtin_bit_cast(A, r.y);
+        x[4 * q + 2] = __builtin_bit_cast(A, r.z);
+        x[4 * q + 3] = __builtin_bit_cast(A, r.w);
+    }
+}
+template <int DT> __device__ __forceinline__ void store_kept(char *base, size_t off, const typename Traits<DT>::acc_t *x)
+{
+#pragma unroll
+    for (int q = 0; q < Traits<DT>::W / 4; ++q) {
+        const uint4 r = make_uint4(__builtin_bit_cast(uint32_t, x[4 * q + 0]), __builtin_bit_cast(uint32_t, x[4 * q + 1]),
+                                   __builtin_bit_cast(uint32_t, x[4 * q + 2]), __builtin_bit_cast(uint32_t, x[4 * q + 3]));
+        st16(base, kept_offset<DT>(off, q), r);
+    }
+}
+// where the accumulator of the single element at object byte offset off lives
+template <int DT> __device__ __forceinline__ size_t kept_elem_offset(size_t off)
+{
+    const size_t i = (off & 15) / Traits<DT>::ES;           // element within its vector
+    return kept_offset<DT>(off & ~(size_t)15, (int)(i >> 2)) + (i & 3) * 4;
+}
+
 // The reduce that keeps and reuses partial results (failure repair, section 3.5.2: the partial
 // results that do not contain the failed object survive). Same tiling as reduce_body, one step
 // at a time. A step whose control word carries kPartialBit reads a kept partial instead of an
 // object; a step with a save mark stores, once its folds have come down to the marked level,
 // that level's accumulator as a kept partial (array q of the kept area, a.spill + q *
-// a.level_stride: accumulator-typed values indexed like the object's elements, so the W
-// accumulators of a source vector lie side by side; laying a bf16 vector's two halves out in two
-// planes, which makes every store instruction cover consecutive addresses, measured 10 % slower:
-// twice as many write streams) and then finishes its folds. The next step's address and control
-// words are fetched while this step's data is in flight.
+// a.level_stride, laid out as kept_offset says) and then finishes its folds. The next step's
+// address and control words are fetched while this step's data is in flight.
 template <int DT, int OP, int D, int VPT, int THREADS, class Prog>
 __device__ __forceinline__ void reduce_body_kept(const ReduceArgs &a, const Prog prog, const int n, void *const dst)
 {
@@ -503,7 +543,7 @@ __device__ __forceinline__ void reduce_body_kept(const ReduceArgs &a, const Prog
             const bool partial = (ctl & kPartialBit) != 0;
             if (partial) {
 #pragma unroll
-                for (int j = 0; j < VPT; ++j) load_acc<DT>((const char *)src, off[j], &x[j * W]);
+                for (int j = 0; j < VPT; ++j) load_kept<DT>((const char *)src, off[j], &x[j * W]);
             } else {
 #pragma unroll
                 for (int j = 0; j < VPT; ++j) raw[j] = ld16(src, off[j]);
@@ -530,7 +570,7 @@ __device__ __forceinline__ void reduce_body_kept(const ReduceArgs &a, const Prog
                     if (keep_level == (uint32_t)L) {
 #pragma unroll
                         for (int j = 0; j < VPT; ++j)
-                            if (live[j]) store_acc<DT>(base, off[j], &m.acc[L][j * W]);
+                            if (live[j]) store_kept<DT>(base, off[j], &m.acc[L][j * W]);
                     }
                 }
             }
@@ -549,7 +589,7 @@ __device__ __forceinline__ void reduce_body_kept(const ReduceArgs &a, const Prog
     // ragged tail: fewer than 16 bytes at the very end of the object
     if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail) {
         const size_t off = a.byte_begin + a.n_vec * 16 + (size_t)threadIdx.x * T::ES;
-        const size_t acc_off = off / T::ES * sizeof(A);
+        const size_t acc_off = kept_elem_offset<DT>(off);
         Machine<DT, OP, D, 1> m;
         for (int t = 0; t < n; ++t) {
             const uint32_t ctl = prog[t].ctl, aux = prog[t].aux;

@@ -286,6 +286,39 @@ inline int full_tree_depth(int k, int64_t d)
     return compile_program(tr, occ, prog);
 }
 
+// The subtrees below the root that have more than one node, as ranges [slot_begin, slot_end) of
+// tree positions (in-order numbering makes a subtree a contiguous range of arrivals): the first
+// child's subtree, then the root, then the other children's subtrees, then the root's childless
+// children. These are the partial results kept for failure repair (section 3.5.2). More than
+// max_runs of them: none (too many arrays to keep).
+struct SlotRun { int slot_begin, slot_end; };
+inline std::vector<SlotRun> subtrees_below_root(int k, int64_t d, int max_runs)
+{
+    std::vector<SlotRun> runs;
+    if (d < 2 || k < 3) return runs;
+    auto subtree_size = [&](int64_t j) {
+        int64_t size = 0, first = j, last = j;
+        while (first < k) {
+            size += std::min<int64_t>(last, k - 1) - first + 1;
+            if (first > (INT64_MAX - 1) / d) break;
+            first = d * first + 1;
+            last = (last > (INT64_MAX - d) / d) ? INT64_MAX : d * last + d;
+        }
+        return size;
+    };
+    int64_t slot = 0;
+    for (int64_t c = 1; c <= d && c < k; ++c) {
+        const int64_t size = subtree_size(c);
+        if (size >= 2) {
+            if ((int)runs.size() == max_runs) { runs.clear(); return runs; }
+            runs.push_back({(int)slot, (int)(slot + size)});
+        }
+        slot += size;
+        if (c == 1) ++slot;             // the root itself comes right after its first child's subtree
+    }
+    return runs;
+}
+
 // Where the scheduler sends work. launch() runs steps [t0, t1) of prog on output
 // chunks [c0, c1). If t0 > 0 the accumulators that the previous launch on those
 // chunks saved are restored first (live_before levels); if `final` the result
@@ -308,6 +341,8 @@ struct Backend {
 // Marker for a tree position that nobody has taken yet while arrivals are still
 // possible: it shapes the program like an object, but no step can run past it.
 constexpr int32_t kPending = -2;
+
+constexpr int kMaxKept = 16;        // most partial results kept per chunk
 
 class Scheduler {
 public:
@@ -646,33 +681,10 @@ private:
 
     // ---- kept partial results -------------------------------------------------------------
 
-    // The subtrees below the root with more than one node, as ranges of tree positions (in-order
-    // numbering makes a subtree a contiguous range of arrivals): the first child's subtree, then the
-    // root, then the other children's subtrees, then the root's childless children.
     void find_runs()
     {
-        const int64_t d = tree_.d;
-        if (d < 2 || k_ < 3) return;
-        auto subtree_size = [&](int64_t j) {
-            int64_t size = 0, first = j, last = j;
-            while (first < k_) {
-                size += std::min<int64_t>(last, k_ - 1) - first + 1;
-                if (first > (INT64_MAX - 1) / d) break;
-                first = d * first + 1;
-                last = (last > (INT64_MAX - d) / d) ? INT64_MAX : d * last + d;
-            }
-            return size;
-        };
-        int64_t slot = 0;
-        for (int64_t c = 1; c <= d && c < k_; ++c) {
-            const int64_t size = subtree_size(c);
-            if (size >= 2) {
-                if ((int)runs_.size() == kMaxKept) { runs_.clear(); return; }      // too many arrays to keep: keep none
-                runs_.push_back({(int)slot, (int)(slot + size)});
-            }
-            slot += size;
-            if (c == 1) ++slot;             // the root itself comes right after its first child's subtree
-        }
+        runs_ = subtrees_below_root(k_, tree_.d, kMaxKept);
+        if (runs_.empty()) return;
         run_of_slot_.assign((size_t)k_, -1);
         for (size_t r = 0; r < runs_.size(); ++r)
             for (int t = runs_[r].slot_begin; t < runs_[r].slot_end; ++t) run_of_slot_[(size_t)t] = (int16_t)r;
@@ -839,10 +851,8 @@ private:
     bool dirty_ = false;                 // something changed that a pump could act on
     int eager_ = 0;
     bool adaptive_ = false;
-    struct Run { int slot_begin, slot_end; };
     struct Kept { int64_t chunk_end; uint32_t gen; };
-    static constexpr int kMaxKept = 16;
-    std::vector<Run> runs_;                          // subtrees below the root, as ranges of positions
+    std::vector<SlotRun> runs_;                          // subtrees below the root, as ranges of positions
     std::vector<int16_t> run_of_slot_;
     std::vector<uint32_t> run_ver_;                  // changes whenever an occupant inside the run changes
     std::vector<std::pair<int, int>> run_steps_;     // the run's steps in prog_: [first, second)

@@ -30,7 +30,29 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert getattr(L, name) is not None
     assert hop.hop_strerror(0) == "ok" and "align" in hop.hop_strerror(hop.HOP_ERR_ALIGN)
-    assert hop.hop_workspace_bytes(16, 12, 0) >= 12 * 16
+
+
+def test_workspace_bytes_counts_every_kind_of_scratch():
+    W = hop.hop_workspace_bytes
+    MiB = 1 << 20
+    # workload 2: program in the kernel arguments, one destination: nothing from the workspace
+    assert W(16, 12, 64 * MiB, 4 * MiB, 4, "f32") == 0
+    # workload 3: the table of the other 63 destinations: one 256 KiB block
+    assert W(64, 64, 16 * MiB, MiB, 2, "i32", n_dst=64) == 256 << 10
+    # a program of 200 steps over large objects is staged
+    assert W(200, 200, 2 * MiB, MiB, 4, "f32") == 256 << 10
+    # workload 5: 56 sub-programs with one 4 KiB partial result each, and their records
+    w5 = W(1024, 1000, 4096, 4096, 16, "f32")
+    assert 56 * 4096 < w5 <= 512 << 10
+    # workload 4 with failures possible: three kept partial results of 4 bytes per element
+    assert W(32, 32, 256 * MiB, 8 * MiB, 8, "bf16", policy=hop.HOP_WS_FAILURES) == 3 * 512 * MiB
+    assert W(32, 32, 256 * MiB, 8 * MiB, 1, "bf16", policy=hop.HOP_WS_FAILURES) == 0           # a chain has no subtrees
+    assert W(32, 32, MiB, 64 << 10, 8, "bf16", policy=hop.HOP_WS_FAILURES) == 0                 # too small to keep anything
+    # eager sessions: one array of saved accumulators per level (2 for this tree) and a block of staged segments
+    assert W(16, 12, 64 * MiB, 4 * MiB, 4, "f32", policy=hop.HOP_WS_EAGER) == 2 * 64 * MiB + (256 << 10)
+    assert W(64, 64, 32 * MiB, MiB, 2, "bf16", policy=hop.HOP_WS_EAGER) == 5 * 64 * MiB + (256 << 10)
+    # invalid shapes
+    assert W(4, 5, 64, 16, 2, "f32") == 0 and W(4, 2, 64, 24, 2, "f32") == 0
 
 
 def test_info_struct_layout_matches_header():
