@@ -99,6 +99,78 @@ def time_calls_median(fn, steps, warmup, torch, batch=100):
     return statistics.mean(dev_ms), statistics.median(wall_ms), statistics.median(dev_ms)
 
 
+# A caller written in C: the same hop_reduce call in a plain loop, to separate the library's host cost per
+# call from the Python binding's. Compiled with gcc when bench.py runs (nothing of the method is in it).
+C_LOOP_SOURCE = r"""
+#include <stddef.h>
+#include <stdint.h>
+#include <time.h>
+typedef int (*reduce_fn)(void *, const void *const *, int, size_t, const int32_t *, int, int, int, size_t, int,
+                         const int64_t *, void *, void *);
+double c_loop(reduce_fn f, int repeats, void *const *dsts, int n_dsts, const void *const *const *obj_sets, int n_sets,
+              int n, size_t object_bytes, const int32_t *order, int k, int op, int dtype, size_t chunk_bytes, int degree,
+              void *stream, int *status)
+{
+    struct timespec t0, t1;
+    clock_gettime(CLOCK_MONOTONIC, &t0);
+    for (int i = 0; i < repeats; ++i) {
+        int rc = f(dsts[i % n_dsts], obj_sets[i % n_sets], n, object_bytes, order, k, op, dtype, chunk_bytes, degree, 0,
+                   stream, 0);
+        if (rc < 0) { *status = rc; break; }
+    }
+    clock_gettime(CLOCK_MONOTONIC, &t1);
+    return (t1.tv_sec - t0.tv_sec) + 1e-9 * (t1.tv_nsec - t0.tv_nsec);
+}
+"""
+
+
+def c_loop_host_time(hop, torch, w, obj_tables, dsts, order, op, repeats=3000):
+    """Host seconds per hop_reduce call from a C loop (the stream is synchronised before and after; the
+    loop itself only enqueues), and the device-inclusive time per call of the same loop. None without gcc."""
+    import ctypes
+    import shutil
+    import subprocess
+    import tempfile
+    if shutil.which("gcc") is None:
+        return None
+    with tempfile.TemporaryDirectory(prefix="hop_cloop_") as tmp:
+        src, lib = os.path.join(tmp, "cloop.c"), os.path.join(tmp, "cloop.so")
+        with open(src, "w") as f:
+            f.write(C_LOOP_SOURCE)
+        subprocess.run(["gcc", "-O2", "-shared", "-fPIC", src, "-o", lib], check=True)
+        L = ctypes.CDLL(lib)
+        L.c_loop.restype = ctypes.c_double
+        n_sets = len(obj_tables)
+        sets = (ctypes.c_void_p * n_sets)(*[ctypes.cast(t.array, ctypes.c_void_p) for t in obj_tables])
+        dptr = (ctypes.c_void_p * len(dsts))(*[int(d.data_ptr()) for d in dsts])
+        oarr = order.astype("int32")
+        status = ctypes.c_int(0)
+        fn = ctypes.cast(hop.lib().hop_reduce, ctypes.c_void_p)
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        args = (fn, repeats, dptr, len(dsts), sets, n_sets, w.n, ctypes.c_size_t(w.object_bytes),
+                oarr.ctypes.data_as(ctypes.c_void_p), w.k, hop.OPS[op], hop.DTYPES[w.dtype], ctypes.c_size_t(w.chunk_bytes),
+                w.tree_degree, stream, ctypes.byref(status))
+        L.c_loop.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                             ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                             ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.c_loop(*args)                                   # warm-up (and records the calls)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        L.c_loop(*args)
+        torch.cuda.synchronize()
+        total_s = time.perf_counter() - t0
+        # the host's share: a burst short enough for the launch queue to take it without pushing back
+        burst = 200
+        short = list(args)
+        short[1] = burst
+        host_s = min(L.c_loop(*short) + 0.0 * (torch.cuda.synchronize() or 0) for _ in range(5))
+        torch.cuda.synchronize()
+        if status.value < 0:
+            return None
+        return {"host_us_per_call": round(host_s / burst * 1e6, 3), "us_per_call_with_device": round(total_s / repeats * 1e6, 3),
+                "calls": repeats, "host_burst": burst}
+
+
 def host_description():
     """CPU model and core counts of the machine the oracle is timed on."""
     model = "unknown"
@@ -210,11 +282,14 @@ def streamed_chunks(hop, torch, w, objs, order, dst, interval_us, reps=5):
     C = w.n_chunks
     first_k = [int(order[t]) for t in range(w.k)]
     res = {"interval_us": interval_us, "k": w.k, "chunks": C}
-    for name in ("fused",):
+    # while the chunks stream in every participant can still fail, so by default each launch also keeps the
+    # partial results of the subtrees below the root (failure repair); "fused_no_keeping" switches that off
+    for name in ("fused", "fused_no_keeping"):
         tails, totals, launches = [], [], 0
         for _ in range(reps + 1):
             rc, s = hop.hop_session_begin(dst, table, w.k, w.ops[0], w.dtype, w.chunk_bytes, w.tree_degree)
             assert rc == hop.HOP_OK, hop.hop_strerror(rc)
+            hop.hop_session_set_retention(s, name == "fused")
             for i in first_k:
                 assert hop.hop_session_ready(s, i, 0) == hop.HOP_OK
             torch.cuda.synchronize()
@@ -234,7 +309,8 @@ def streamed_chunks(hop, torch, w, objs, order, dst, interval_us, reps=5):
             launches = info["n_launches"]
             assert rc == hop.HOP_OK
         res[name] = {"us_after_last_chunk": round(statistics.median(tails[1:]), 1),
-                     "us_first_chunk_to_result": round(statistics.median(totals[1:]), 1), "launches": launches}
+                     "us_first_chunk_to_result": round(statistics.median(totals[1:]), 1), "launches": launches,
+                     "partials_kept_per_chunk": info["partial_stores"] // max(1, C)}
     return res
 
 
@@ -311,6 +387,8 @@ def main():
         for op in w.ops:
             state = {"i": 0, "info": None, "rc": 0}
 
+            stream = torch.cuda.current_stream().cuda_stream        # looked up once, as a caller in a loop would
+
             def step():
                 d = dsts[state["i"] & 1]
                 obj_table = obj_tables[state["i"] % n_sets]
@@ -318,10 +396,10 @@ def main():
                 if w.n_dst:
                     state["rc"], state["info"] = hop.hop_allreduce(dst_tables[(state["i"] - 1) & 1], obj_table, w.k,
                                                                    op, w.dtype, w.chunk_bytes, w.tree_degree,
-                                                                   order, fm)
+                                                                   order, fm, stream=stream)
                 else:
                     state["rc"], state["info"] = hop.hop_reduce(d[0], obj_table, w.k, op, w.dtype, w.chunk_bytes,
-                                                                w.tree_degree, order, fm)
+                                                                w.tree_degree, order, fm, stream=stream)
             ms, wall_ms, ms_median = timer(step, steps, warmup, torch)
             assert state["rc"] >= 0, hop.hop_strerror(state["rc"])
             info = state["info"]
@@ -339,6 +417,9 @@ def main():
             results[op] = {"ms": ms, "ms_median": ms_median, "wall_ms": wall_ms, "gbs": counted / (ms * 1e-3) / 1e9,
                            "gbs_median": counted / (ms_median * 1e-3) / 1e9, "bytes": counted, "moved": moved,
                            "moved_gbs": moved / (ms * 1e-3) / 1e9, "info": info, "status": state["rc"]}
+            if n_sets > 1 and not w.n_dst:
+                # launch-bound: what a caller written in C pays per call
+                results[op]["c_loop"] = c_loop_host_time(hop, torch, w, obj_tables, [d[0] for d in dsts], order, op)
         return w, objs, order, dsts, results
 
     extra = None
@@ -366,6 +447,7 @@ def main():
                     "traffic_from_counters": t["bytes_per_call"] if t else None,
                     "status": rr["status"], "status_text": hop.hop_strerror(rr["status"]), "k_eff": rr["info"]["k_eff"],
                     "launches": rr["info"]["n_launches"], "host_ms_per_call": round(rr["wall_ms"], 5),
+                    "c_caller": rr.get("c_loop"),
                     "timing": "median of batches of 100 calls" if tiny else "median of batches of 5 calls"}
             del o2, d2
             torch.cuda.empty_cache()

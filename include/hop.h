@@ -311,8 +311,9 @@ int hop_session_set_adaptive(hop_session_t *s, int on);
  * and re-reads only the objects of the subtree that changed and those
  * directly below the root. Launches made when nobody can fail any more (every
  * launch of a call whose participants all complete) keep nothing and cost
- * nothing extra. Nothing is kept either for launches over at most 1 MiB per
- * object, for chains and stars (no subtrees), for more than 16 subtrees, when
+ * nothing extra; launches that keep partials move 10-20 % more bytes and take
+ * about as much longer. Nothing is kept either for launches over less than
+ * 8 MiB per object, for chains and stars (no subtrees), for more than 16 subtrees, when
  * the kept arrays would exceed a quarter of what the launch reads or 16 GiB,
  * or in hop_reduce_noalloc. on = 0: never keep; a repair reads every object
  * of the chunk again. Results are bit-identical either way. */
@@ -452,7 +453,7 @@ int hop_calibrate(double *latency_s, double *bytes_per_s);
  *     cut that would need more is not made);
  *   - HOP_WS_EAGER (sessions with hop_session_set_eager(s, m >= 1)): the saved
  *     accumulators, 4 bytes per element and accumulator level of the tree;
- *   - HOP_WS_FAILURES (participants may fail mid-stream; objects above 1 MiB):
+ *   - HOP_WS_FAILURES (participants may fail mid-stream; objects of 8 MiB or more):
  *     the kept partial results, 4 bytes per element and subtree below the
  *     root (hop_session_set_retention).
  * The memory is allocated on first use, cached by the library (idle buffers

@@ -43,7 +43,10 @@ class HopInfo(ctypes.Structure):
                 ("partial_loads", ctypes.c_int64), ("partial_stores", ctypes.c_int64)]
 
     def as_dict(self):
-        return {f: getattr(self, f) for f, _ in self._fields_}
+        return {"k_eff": self.k_eff, "n_failed_seen": self.n_failed_seen, "n_replaced": self.n_replaced,
+                "degree_used": self.degree_used, "chunks_redone": self.chunks_redone, "n_launches": self.n_launches,
+                "stack_depth": self.stack_depth, "chunk_steps": self.chunk_steps, "chunk_stores": self.chunk_stores,
+                "partial_loads": self.partial_loads, "partial_stores": self.partial_stores}
 
 
 class BcastCopy(ctypes.Structure):
@@ -180,11 +183,23 @@ def _ptr_table(items) -> Tuple[ctypes.Array, int]:
     return (ctypes.c_void_p * max(len(ptrs), 1))(*ptrs), len(ptrs)
 
 
+_I32P = ctypes.POINTER(ctypes.c_int32)
+_i32_recent = {}        # id(array) -> (array, pointer): callers repeat calls with the same order array
+
+
 def _i32(a):
     if a is None:
         return None, None
+    hit = _i32_recent.get(id(a))
+    if hit is not None and hit[0] is a:
+        return hit
     arr = np.ascontiguousarray(a, dtype=np.int32)
-    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    out = (arr, arr.ctypes.data_as(_I32P))
+    if arr is a:                       # the pointer is into the caller's own array: later contents are seen too
+        if len(_i32_recent) >= 16:
+            _i32_recent.clear()
+        _i32_recent[id(a)] = out
+    return out
 
 
 def _i64(a):
@@ -208,6 +223,15 @@ def _bytes_of(t, object_bytes):
     return t.numel() * t.element_size()
 
 
+def _table_bytes(objs, n, fallback, object_bytes):
+    """Size of one object: given, or known to the pointer table, or taken from the first tensor."""
+    if object_bytes is not None:
+        return int(object_bytes)
+    if isinstance(objs, PtrTable) and objs.object_bytes is not None:
+        return objs.object_bytes
+    return _bytes_of(objs[0] if n else fallback, None)
+
+
 def _code(table, v):
     return table[v] if v in table else int(v)
 
@@ -225,7 +249,7 @@ def hop_reduce(dst, objs, k, op, dtype, chunk_bytes, tree_degree, ready_order=No
     _fm, fm = _i64(fail_mask)
     info = HopInfo()
     dptr = ctypes.c_void_p(int(dst.data_ptr()) if isinstance(dst, torch.Tensor) else int(dst))
-    rc = lib().hop_reduce(dptr, tab, n, _bytes_of(objs[0] if n else dst, object_bytes), ro, int(k),
+    rc = lib().hop_reduce(dptr, tab, n, _table_bytes(objs, n, dst, object_bytes), ro, int(k),
                           _code(OPS, op), _code(DTYPES, dtype), int(chunk_bytes), int(tree_degree), fm,
                           _stream(stream), ctypes.byref(info))
     return rc, info.as_dict()

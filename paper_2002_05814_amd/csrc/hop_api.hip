@@ -947,10 +947,12 @@ static int auto_degree(int device, int k, size_t object_bytes, hipStream_t strea
     return pick_degree(k, object_bytes, L, B);
 }
 
-// Launches over more than this many bytes per object keep partial results while a participant
-// can still fail (smaller ones would not repay a second launch and the extra arrays; it is
-// also the size up to which a long program may be cut into sub-programs instead).
-static constexpr size_t kRetainAboveBytes = 1u << 20;
+// Launches over more than this many bytes per object (that is, of at least 8 MiB) keep partial results
+// while a participant can still fail. Below, keeping costs too much of every launch for what a repair
+// would save: the kernel that keeps partials works one step at a time, which is the fast shape only for
+// long ranges (12 fp32 inputs, per launch: 3-4 MiB +40 %, 6 MiB +25 %, 8-32 MiB +12-18 %, the extra bytes
+// being 15 %).
+static constexpr size_t kRetainAboveBytes = ((size_t)8 << 20) - 1;
 
 static void default_retention(Scheduler &s, const Shape &shape, int dtype)
 {

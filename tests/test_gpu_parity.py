@@ -975,13 +975,14 @@ def test_cfg4_full_size_failure_every_element():
 
 KEPT_CASES = [
     # dtype, op, n, k, d, object bytes, chunk bytes, {object (by arrival rank): chunks before it fails}
-    ("bf16", "sum", 32, 32, 8, (8 << 20) + 6, 256 << 10, {28: 10}),            # workload 4's shape: a childless child of the root
-    ("bf16", "sum", 32, 32, 8, (8 << 20) + 6, 256 << 10, {12: 7}),             # inside the second subtree
-    ("f32", "sum", 16, 12, 2, (4 << 20) + 12, 512 << 10, {3: 5}),              # binary tree, replaced by a waiting object
-    ("f32", "max", 40, 40, 4, (3 << 20) + 4, 256 << 10, {0: 6, 30: 9}),         # two failures at different times
-    ("i32", "sum", 64, 60, 16, 2 << 20, 128 << 10, {5: 15, 59: 15, 61: 3}),     # two at once, and a waiting object that dies too
-    ("bf16", "min", 24, 24, 3, (5 << 20) + 2, 1 << 20, {23: 4}),                # the last arrival; three levels of accumulators
-    ("f32", "sum", 12, 12, 4, 6 << 20, 2 << 20, {5: 2}),                        # the root itself
+    # (partial results are kept by launches over at least 8 MiB per object)
+    ("bf16", "sum", 32, 32, 8, (32 << 20) + 6, 1 << 20, {28: 10}),             # workload 4's shape: a childless child of the root
+    ("bf16", "sum", 32, 32, 8, (24 << 20) + 6, 1 << 20, {12: 9}),              # inside the second subtree
+    ("f32", "sum", 16, 12, 2, (24 << 20) + 12, 2 << 20, {3: 5}),               # binary tree, replaced by a waiting object
+    ("f32", "max", 40, 40, 4, (20 << 20) + 4, 1 << 20, {0: 9, 30: 17}),         # two failures at different times
+    ("i32", "sum", 64, 60, 16, 16 << 20, 512 << 10, {5: 24, 59: 24, 61: 3}),    # two at once, and a waiting object that dies too
+    ("bf16", "min", 24, 24, 3, (20 << 20) + 2, 4 << 20, {23: 2}),               # the last arrival; three levels of accumulators
+    ("f32", "sum", 12, 12, 4, 24 << 20, 8 << 20, {5: 1}),                       # the root itself
 ]
 
 
@@ -1027,11 +1028,11 @@ def test_failure_repaired_from_kept_partials_equals_oracle(dtype, op, n, k, d, n
 
 
 def test_allreduce_with_a_failure_keeps_partials_and_all_destinations_agree():
-    w = workloads.WORKLOADS[3].scaled(3 << 20, 256 << 10, n=20, k=20, tree_degree=4, n_dst=5, name="kept_allreduce")
+    w = workloads.WORKLOADS[3].scaled(16 << 20, 1 << 20, n=20, k=20, tree_degree=4, n_dst=5, name="kept_allreduce")
     objs = workloads.make_objects(w, device=dev())
     order = w.ready_order()
     fm = np.full(w.n, -1, np.int64)
-    fm[order[9]] = 6
+    fm[order[9]] = 9
     dsts = [torch.full_like(objs[0], -5) for _ in range(w.n_dst)]
     rc, info = hop.hop_allreduce(dsts, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, fm)
     torch.cuda.synchronize()
@@ -1047,7 +1048,7 @@ def test_late_arrival_into_a_hole_reuses_the_kept_partials():
     # 9 objects, binary tree on 8 positions; chunk by chunk; the 6th arrival fails after 3 chunks with nobody
     # waiting (a hole), later a 9th object arrives and takes the hole: the chunks produced in between are
     # repaired twice, each time from the partials of the subtree that did not change
-    w = workloads.WORKLOADS[2].scaled(16 << 20, 2 << 20, n=9, k=8, tree_degree=2, order_seed=None, name="kept_late")
+    w = workloads.WORKLOADS[2].scaled(64 << 20, 8 << 20, n=9, k=8, tree_degree=2, order_seed=None, name="kept_late")
     objs = workloads.make_objects(w, device=dev())
     dst = torch.zeros_like(objs[0])
     C = w.n_chunks

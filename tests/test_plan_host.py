@@ -140,11 +140,11 @@ def random_case(rng, max_n=14, with_fail=True):
     return n, k, d, chunk_elems, n_elems, order, fm
 
 
-# The schedule is in units of chunks, so the same plan can be made for objects 2^18 times as large
+# The schedule is in units of chunks, so the same plan can be made for objects 2^20 times as large
 # (chunks of megabytes instead of bytes) and still be interpreted on the small arrays: that is how the
 # tests here reach the policies that depend on the size of a launch (partial results are kept only by
-# launches over more than 1 MiB per object).
-BIG = 1 << 18
+# launches over at least 8 MiB per object).
+BIG = 1 << 20
 
 
 @pytest.mark.parametrize("op", ["sum", "max", "min"])
