@@ -335,6 +335,10 @@ def main():
                     help="also time the workload with tree degrees 1, 2, 4, 8 and k (the ablation of the paper's "
                          "appendix B, on one GPU: the degree fixes the association order and the accumulator depth, "
                          "not the traffic)")
+    ap.add_argument("--size-sweep", action="store_true",
+                    help="also time the workload's reduce (same n, k, degree, type) at object sizes from 1 to 64 MiB, "
+                         "inputs not cached, and fit time = fixed cost + bytes / rate: what part of a mid-size launch "
+                         "is the launch and what part the kernel")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run hop_broadcast of one 256 MiB object to one destination a few times: a copy of "
                          "known size against which hardware byte counters can be scaled")
@@ -522,6 +526,42 @@ def main():
         sweep["calibrated"] = {"status": rc_cal, "latency_us": round(lat * 1e6, 3), "GB/s": round(bw / 1e9, 1)}
         sweep["picked_by_eq1"] = hop.hop_pick_degree(w.k, w.object_bytes, 0.0, 0.0)
         out["degree_sweep"] = sweep
+    if args.size_sweep:
+        import statistics
+        rows = []
+        for mib in (1, 2, 3, 4, 6, 8, 10, 12, 16, 24, 32, 64):
+            ws = w.scaled(mib << 20, min(w.chunk_bytes, mib << 20), fail={}, name="%s_%dMiB" % (w.name, mib))
+            n_sets = max(2, -(-(768 << 20) // (w.n * (mib << 20))))          # three times the memory-side cache
+            base = workloads.make_objects(ws, device=dev)
+            sets = [hop.PtrTable(base)]
+            for _ in range(n_sets - 1):
+                block = torch.stack(base)
+                sets.append(hop.PtrTable([block[i] for i in range(ws.n)]))
+            dd = [torch.empty_like(base[0]) for _ in range(2)]
+            stt = {"i": 0}
+            strm = torch.cuda.current_stream().cuda_stream
+
+            def step_size():
+                stt["i"] += 1
+                hop.hop_reduce(dd[stt["i"] & 1], sets[stt["i"] % n_sets], ws.k, op, ws.dtype, ws.chunk_bytes, ws.tree_degree,
+                               order, None, stream=strm)
+            reps = 400 if mib <= 8 else 100
+            ms, _, med = time_calls_median(step_size, reps, 50, torch, batch=max(10, reps // 10))
+            nbytes = (ws.k + 1) * ws.object_bytes
+            rows.append({"MiB": mib, "us": round(med * 1e3, 2), "GB/s": round(nbytes / (med * 1e-3) / 1e9, 1),
+                         "frac": round(nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "bytes": nbytes})
+            del base, sets, dd
+            torch.cuda.empty_cache()
+        # least squares of time against bytes over the sizes
+        xs = [r["bytes"] for r in rows]
+        ys = [r["us"] for r in rows]
+        mx, my = statistics.mean(xs), statistics.mean(ys)
+        slope = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sum((x - mx) ** 2 for x in xs)
+        fixed = my - slope * mx
+        out["size_sweep"] = {"rows": rows, "fit": {"fixed_us": round(fixed, 2), "rate_GB/s": round(1e-3 / slope, 1),
+                                                  "model": "us = fixed_us + bytes / rate"}}
+        for r in rows:
+            r["model_us"] = round(fixed + slope * r["bytes"], 2)
     if args.streamed_interval_us is not None:
         out["streamed_chunks"] = streamed_chunks(hop, torch, w, objs, order, dsts[0][0], args.streamed_interval_us)
     if args.paced_interval_us is not None:

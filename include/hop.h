@@ -446,8 +446,10 @@ int hop_calibrate(double *latency_s, double *bytes_per_s);
  * this shape (arguments as hop_reduce; n_dst = destinations, 1 for a plain
  * reduce; tree_degree 0 = the degree the library would pick now). Counted:
  *   - the staged program (16 bytes per step when there are more than 128) and
- *     the table of the other n_dst - 1 destinations, in blocks of 256 KiB (the
- *     same number of bytes of pinned host memory goes with them);
+ *     the table of the other n_dst - 1 destinations when there are more than
+ *     64 of them (shorter programs and tables ride in the kernel arguments),
+ *     in blocks of 256 KiB (the same number of bytes of pinned host memory
+ *     goes with them);
  *   - for a call over 128 or more inputs of at most 1 MiB each (fp32, int32):
  *     the partial results and records of its sub-programs (at most 16 MiB; a
  *     cut that would need more is not made);

@@ -474,18 +474,12 @@ private:
         if (t0 > 0 || !final) return launch_segment(prog, c0, c1, t0, t1, final, live_before, live_after);
         for (const Entry &e : prog)
             if (e.obj < 0 || e.save >= 0) return launch_kept(prog, version, c0, c1);
-        if (dsts_.size() > 1 && !dev_extra_) {
-            dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
-            if (!dev_extra_) return ws_.error();
-        }
         const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
         if (wants_split(prog.size(), b1 - b0)) {
             int rc = launch_split(prog, b0, b1);
             if (rc != HOP_PARTIAL) {                // HOP_PARTIAL here = "not splittable, use the plain path"
                 if (rc < 0) return rc;
-                hipError_t ec = hipSuccess;
-                if (dsts_.size() > 1) ec = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
-                return ec == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+                return copy_to_other_destinations(b0, b1);
             }
         }
         if (version != dev_version_) {
@@ -503,18 +497,31 @@ private:
             }
             dev_version_ = version;
         }
-        // Reduce followed by broadcast, chunk run by chunk run: the finished chunks land in the
-        // first destination and the copy kernel carries them to the others while they are still
-        // cache-resident. Storing to all destinations from the reduce kernel itself was measured
-        // slower (reads and 64-way writes interleaved: 492 us against 391 us on 64 x 16 MiB).
+        // Storing to all destinations from the reduce kernel itself was measured slower than a reduce into
+        // the first one followed by the copy (reads and 64-way writes interleaved: 492 us against 391 us
+        // on 64 x 16 MiB).
         hipError_t e = launch_reduce(stream_, dtype_, op_, depth_, staging_.data(), dev_prog_, (int)prog.size(),
                                      dsts_[0], b0, b1);
-        if (e == hipSuccess && dsts_.size() > 1)
-            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
-        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+        if (e != hipSuccess) return HOP_ERR_DEVICE;
+        return copy_to_other_destinations(b0, b1);
     }
 
 private:
+    // Reduce followed by broadcast, chunk run by chunk run: the finished chunks have landed in the first
+    // destination and the copy kernel carries them to the others while they are still cache-resident. Up
+    // to kInlineDsts other destinations ride in the kernel arguments; more are staged once per call.
+    int copy_to_other_destinations(size_t b0, size_t b1)
+    {
+        if (dsts_.size() < 2) return HOP_OK;
+        const int n_other = (int)dsts_.size() - 1;
+        if (n_other > kInlineDsts && !dev_extra_) {
+            dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (size_t)n_other * sizeof(void *));
+            if (!dev_extra_) return ws_.error();
+        }
+        const hipError_t e = launch_copy(stream_, dsts_[0], dev_extra_, n_other, b0, b1, nullptr, extra_residue_, dsts_.data() + 1);
+        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+    }
+
     // Steps [t0, t1) only: accumulators come from and/or go to the spill area, one array of 4-byte
     // accumulators per level, each as long as the object has elements. It is taken from the
     // library's cache when the first partial segment is launched and returned with the session.
@@ -547,14 +554,8 @@ private:
         hipError_t e = launch_reduce_segment(stream_, dtype_, op_, depth, dev_steps, t1 - t0, dsts_[0], spill_,
                                              level_stride_, live_before, final ? 0 : live_after, b0, b1,
                                              steps.empty() ? 0 : lead_vectors(steps.data(), (int)steps.size(), b0));
-        if (e == hipSuccess && final && dsts_.size() > 1) {
-            if (!dev_extra_) {
-                dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
-                if (!dev_extra_) return ws_.error();
-            }
-            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
-        }
-        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+        if (e != hipSuccess) return HOP_ERR_DEVICE;
+        return final ? copy_to_other_destinations(b0, b1) : HOP_OK;
     }
 
     // A whole program some of whose steps read a kept partial result (obj = -(1 + q)) or store one
@@ -588,14 +589,8 @@ private:
         }
         hipError_t e = launch_reduce_kept(stream_, dtype_, op_, kept_depth_, kept_steps_.data(), kept_dev_, (int)prog.size(),
                                           dsts_[0], kept_, kept_stride_, b0, b1);
-        if (e == hipSuccess && dsts_.size() > 1) {
-            if (!dev_extra_) {
-                dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (dsts_.size() - 1) * sizeof(void *));
-                if (!dev_extra_) return ws_.error();
-            }
-            e = launch_copy(stream_, dsts_[0], dev_extra_, (int)dsts_.size() - 1, b0, b1, nullptr, extra_residue_);
-        }
-        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+        if (e != hipSuccess) return HOP_ERR_DEVICE;
+        return copy_to_other_destinations(b0, b1);
     }
 
     // Many inputs but few output tiles (the many-small-objects case): one wave per tile would walk
@@ -1250,11 +1245,15 @@ int hop_broadcast(void *const *dsts, int n_dst, const void *src, size_t object_b
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
     try {
+        // The whole source is present, so every chunk is ready at once: one launch covers them all. Up to
+        // kInlineDsts destinations ride in the kernel arguments, a longer table is staged in device memory.
         Workspace ws(device, (hipStream_t)stream);
-        void *const *table = (void *const *)ws.stage(dsts, (size_t)n_dst * sizeof(void *));
-        if (!table) return HOP_ERR_NOMEM;
-        // The whole source is present, so every chunk is ready at once: one launch covers them all.
-        hipError_t e = launch_copy((hipStream_t)stream, src, table, n_dst, 0, object_bytes, nullptr, common_residue(dsts, n_dst));
+        void *const *table = nullptr;
+        if (n_dst > kInlineDsts) {
+            table = (void *const *)ws.stage(dsts, (size_t)n_dst * sizeof(void *));
+            if (!table) return HOP_ERR_NOMEM;
+        }
+        hipError_t e = launch_copy((hipStream_t)stream, src, table, n_dst, 0, object_bytes, nullptr, common_residue(dsts, n_dst), dsts);
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     } catch (const std::bad_alloc &) {
         return HOP_ERR_NOMEM;
@@ -1596,7 +1595,7 @@ size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes
         // staged program (longer than the kernel arguments hold) and destination table
         size_t staged = 0;
         if (k > kInlineEntries) staged += round256((size_t)k * sizeof(DevEntry));
-        if (n_dst > 1) staged += round256((size_t)(n_dst - 1) * sizeof(void *));
+        if (n_dst - 1 > kInlineDsts) staged += round256((size_t)(n_dst - 1) * sizeof(void *));
         size_t total = blocks(staged);
         // the cut into sub-programs of a call over many small objects: their partial results and records
         if (dtype != HOP_BF16 && (size_t)k >= 128 && object_bytes > 0 && object_bytes <= ((size_t)1 << 20)) {

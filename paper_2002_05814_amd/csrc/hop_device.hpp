@@ -660,8 +660,8 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel_inline(ReduceArgsInline
 
 // One source, n_dst destinations: each 16-byte vector is read once (non-temporal) and
 // written n_dst times. VPT vectors per lane are in flight together.
-template <int VPT, int THREADS>
-__global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
+template <int VPT, int THREADS, class Table>
+__device__ __forceinline__ void copy_body(const CopyArgs &a, const Table dsts)
 {
     constexpr size_t kTile = (size_t)THREADS * VPT;
     // the vectors of a workgroup: contiguous, or VPT pieces 2^s pieces apart (as in reduce_body)
@@ -671,7 +671,6 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
     // costs a tenth of the bandwidth here and a third in the fan-out kernel)
     const size_t lead = (size_t)a.lead_vecs, n_all = a.n_vec + lead;
     const size_t n_tiles = sl < 0 ? (n_all + kTile - 1) / kTile : ((n_all + (kTile << sl) - 1) / (kTile << sl)) << sl;
-    const table_ptr dsts = (table_ptr)(uintptr_t)a.dsts;
     for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         uint4 x[VPT];
         size_t off[VPT];
@@ -691,7 +690,7 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
             x[j] = ld16(a.src, off[j]);
         }
         for (int d = 0; d < a.n_dst; ++d) {
-            void *dst = a.dsts ? dsts[d] : a.dst0;
+            void *dst = a.dst0 ? a.dst0 : dsts[d];
 #pragma unroll
             for (int j = 0; j < VPT; ++j)
                 if (live[j]) st16(dst, off[j], x[j]);
@@ -700,8 +699,14 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
     if (blockIdx.x == 0 && (int)threadIdx.x < a.n_tail_bytes) {
         const size_t off = a.byte_begin + a.n_vec * 16 + threadIdx.x;
         const unsigned char b = *((const unsigned char *)a.src + off);
-        for (int d = 0; d < a.n_dst; ++d) *((unsigned char *)(a.dsts ? dsts[d] : a.dst0) + off) = b;
+        for (int d = 0; d < a.n_dst; ++d) *((unsigned char *)(a.dst0 ? a.dst0 : dsts[d]) + off) = b;
     }
+}
+// destination table in device memory (or the single destination a.dst0)
+template <int VPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
+{
+    copy_body<VPT, THREADS>(a, (table_ptr)(uintptr_t)a.dsts);
 }
 
 // One source, several destinations, the source read through the caches: a workgroup copies
@@ -712,11 +717,10 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(CopyArgs a)
 // for every destination from the L2 of the XCD that read them first: workgroups are dealt to
 // the XCDs in turn and a span holds a multiple of 8 tiles, so a tile meets the same XCD for
 // every destination, and a span is sized to leave each XCD's share well inside its L2.
-template <int VPT, int THREADS>
-__global__ __launch_bounds__(THREADS) void fanout_kernel(CopyArgs a)
+template <int VPT, int THREADS, class Table>
+__device__ __forceinline__ void fanout_body(const CopyArgs &a, const Table dsts)
 {
     constexpr size_t kTile = (size_t)THREADS * VPT;
-    const table_ptr dsts = (table_ptr)(uintptr_t)a.dsts;
     const unsigned per_span = a.span_tiles * (unsigned)a.n_dst;
     const unsigned span = blockIdx.x / per_span, r = blockIdx.x - span * per_span;
     const unsigned first = span * a.span_tiles;
@@ -739,6 +743,18 @@ __global__ __launch_bounds__(THREADS) void fanout_kernel(CopyArgs a)
         const unsigned char b = *((const unsigned char *)a.src + off);
         for (int e = 0; e < a.n_dst; ++e) *((unsigned char *)dsts[e] + off) = b;
     }
+}
+// destination table in device memory
+template <int VPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void fanout_kernel(CopyArgs a)
+{
+    fanout_body<VPT, THREADS>(a, (table_ptr)(uintptr_t)a.dsts);
+}
+// destination table inside the kernel arguments
+template <int VPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void fanout_kernel_inline(CopyArgsInline a)
+{
+    fanout_body<VPT, THREADS>(a.base, &a.dsts[0]);
 }
 
 }  // namespace hop

@@ -73,6 +73,15 @@ struct CopyArgs {
     unsigned span_tiles;       // fan-out kernel only: tiles per span
 };
 
+// Destination tables of at most this many entries travel inside the kernel arguments
+// (no staging copy in front of the copy kernel); longer ones are staged in device memory.
+constexpr int kInlineDsts = 64;
+struct CopyArgsInline {
+    CopyArgs base;
+    void *dsts[kInlineDsts];
+};
+static_assert(sizeof(CopyArgsInline) <= 4096, "kernel arguments are limited to 4 KiB");
+
 int elem_bytes(int dtype);
 
 // Recording of kernel launches, for calls that will be repeated with the same arguments: while a
@@ -127,12 +136,14 @@ hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, 
 hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
                               int sub_entries, int n_subs, size_t byte_begin, size_t byte_end);
 
-// Copy [byte_begin, byte_end) of src into the same range of every destination
-// of the device table dsts; with dsts == nullptr and n_dst == 1 into dst0.
+// Copy [byte_begin, byte_end) of src into the same range of n_dst destinations: dst0 if n_dst == 1
+// and dst0 is given; else the table host_dsts (host memory) if it has at most kInlineDsts entries
+// (it then rides in the kernel arguments); else the device table dsts.
 // dst_residue: address modulo 128 of the table's destinations (of most of them, if they
 // differ; see common_residue), used to start the stores at whole lines; dst0's own otherwise.
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
-                       size_t byte_begin, size_t byte_end, void *dst0 = nullptr, unsigned dst_residue = 0);
+                       size_t byte_begin, size_t byte_end, void *dst0 = nullptr, unsigned dst_residue = 0,
+                       void *const *host_dsts = nullptr);
 
 // The address modulo 128 that most of n (16-byte aligned) host-visible pointers share.
 inline unsigned common_residue(void *const *p, int n)

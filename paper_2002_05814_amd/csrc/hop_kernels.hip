@@ -312,13 +312,17 @@ constexpr size_t kFanoutLongBytes = (size_t)128 << 20;
 static_assert(kFanoutSpanTiles % 8 == 0, "a tile must meet the same XCD for every destination");
 
 hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, int n_dst,
-                       size_t byte_begin, size_t byte_end, void *dst0, unsigned dst_residue)
+                       size_t byte_begin, size_t byte_end, void *dst0, unsigned dst_residue, void *const *host_dsts)
 {
     not_recordable();
+    if (n_dst != 1) dst0 = nullptr;
     if (dst0) dst_residue = (unsigned)((uintptr_t)dst0 & 127);
     if (byte_end <= byte_begin || n_dst <= 0) return hipSuccess;
-    if (!dsts && (n_dst != 1 || !dst0)) return hipErrorInvalidValue;
-    CopyArgs a;
+    const bool inl = !dst0 && host_dsts && n_dst <= kInlineDsts;
+    if (!dst0 && !inl && !dsts) return hipErrorInvalidValue;
+    if (n_dst == 1 && inl) { dst0 = host_dsts[0]; dst_residue = (unsigned)((uintptr_t)dst0 & 127); }
+    CopyArgsInline ai;
+    CopyArgs &a = ai.base;
     a.src = src;
     a.dst0 = dst0;
     a.dsts = dsts;
@@ -353,7 +357,15 @@ hipError_t launch_copy(hipStream_t stream, const void *src, void *const *dsts, i
             part.n_tiles = (unsigned)now;
             const size_t grid = (now < 1 ? 1 : now) * (size_t)n_dst;     // one workgroup at least, for the tail bytes
             if (now == 0) part.n_tiles = 1;                              // its only tile is empty: n_vec == 0
-            hipLaunchKernelGGL((fanout_kernel<kFanoutVpt, kThreads>), dim3((unsigned)grid), dim3(kThreads), lds, stream, part);
+            if (inl) {
+                CopyArgsInline pi;
+                pi.base = part;
+                pi.base.dsts = nullptr;
+                for (int i = 0; i < kInlineDsts; ++i) pi.dsts[i] = i < n_dst ? host_dsts[i] : nullptr;
+                hipLaunchKernelGGL((fanout_kernel_inline<kFanoutVpt, kThreads>), dim3((unsigned)grid), dim3(kThreads), lds, stream, pi);
+            } else {
+                hipLaunchKernelGGL((fanout_kernel<kFanoutVpt, kThreads>), dim3((unsigned)grid), dim3(kThreads), lds, stream, part);
+            }
             done += now;
         } while (done < tiles);
         return hipGetLastError();

@@ -37,8 +37,9 @@ def test_workspace_bytes_counts_every_kind_of_scratch():
     MiB = 1 << 20
     # workload 2: program in the kernel arguments, one destination: nothing from the workspace
     assert W(16, 12, 64 * MiB, 4 * MiB, 4, "f32") == 0
-    # workload 3: the table of the other 63 destinations: one 256 KiB block
-    assert W(64, 64, 16 * MiB, MiB, 2, "i32", n_dst=64) == 256 << 10
+    # workload 3: the table of the other 63 destinations rides in the kernel arguments; 99 others are staged
+    assert W(64, 64, 16 * MiB, MiB, 2, "i32", n_dst=64) == 0
+    assert W(64, 64, 16 * MiB, MiB, 2, "i32", n_dst=100) == 256 << 10
     # a program of 200 steps over large objects is staged
     assert W(200, 200, 2 * MiB, MiB, 4, "f32") == 256 << 10
     # workload 5: 56 sub-programs with one 4 KiB partial result each, and their records
