@@ -25,8 +25,27 @@ HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth, GB/s (1e9 B
 # shapes they were taken with: they are reported only while the library's hop_kernel_config() string is the
 # one recorded here (else null).
 PROFILED_TRAFFIC = {
-    "kernel_config": "",
-    "workloads": {},
+    "kernel_config": (
+                     "reduce: 64 lanes/workgroup, 4|2|1 vectors/lane by accumulator depth, unroll 1; below 768 4-KiB "
+                     "tiles: 1 KiB tiles, unroll 8; below 2048: 2 KiB per workgroup, unroll 2, in two pieces 16 KiB apart; "
+                     "from 2048: 1 KiB pieces 64 KiB apart, one per vector (the 2 KiB shape instead if the rounds of "
+                     "resident waves would be less than 80 % full); kernels with 4 vectors/lane: 8 waves per CU from 5120 "
+                     "tiles; bf16 at depth 5..8 from 768 tiles: 2 vectors/lane, unroll 2 (pieces 64 KiB apart from 2048 "
+                     "tiles); groups of 8 plain steps marked by the host; nontemporal loads+stores, programs <= 128 steps "
+                     "in kernel arguments; vector grids start at a 128-byte boundary of the sources (reduce) or "
+                     "destinations (copies); copy to one destination: 64 lanes/workgroup, 8 contiguous vectors/lane; from "
+                     "5120 8-KiB tiles 4 vectors/lane in 1 KiB pieces 64 KiB apart, 10 waves per CU; nontemporal; to "
+                     "several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 "
+                     "tiles, cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 "
+                     "destinations); launches that keep or read partial results: one step at a time, 4|2|1 vectors/lane, "
+                     "pieces 64 KiB apart from 2048 tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators "
+                     "indexed like the elements, nontemporal"),
+    "workloads": {
+        "cfg2_async_sgd": {"bytes_per_call": 872306923, "profile": "profiles/hbm_traffic_all_workloads.md"},
+        "cfg3_rl_allreduce": {"bytes_per_call": 2163397681, "profile": "profiles/hbm_traffic_all_workloads.md"},
+        "cfg4_large_fault": {"bytes_per_call": 10181981383, "profile": "profiles/hbm_traffic_all_workloads.md"},
+        "cfg4_large_fault_without_failure": {"bytes_per_call": 8856975592, "profile": "profiles/hbm_traffic_all_workloads.md"},
+    },
 }
 
 # The paper's own headline results (its sections 5.2-5.4 and 5 "setup"): context, not a target.
