@@ -74,12 +74,12 @@ def time_calls(fn, steps, warmup, torch):
     """Device time per call in ms over exactly `steps` calls enqueued back to back between two events on the
     current stream (the stream the kernels are launched on): (mean over all calls, host wall mean, median over
     batches). An event behind every call would cost 2-3 us per call (the next kernel no longer starts while
-    the previous one drains), so the calls are marked in batches of at least 5 (a tenth of the steps)."""
+    the previous one drains), so the calls are marked in batches of at least 10 (a tenth of the steps)."""
     import statistics
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    batch = max(5, steps // 10)
+    batch = max(10, steps // 10)
     edges = list(range(0, steps, batch)) + [steps]
     marks = [torch.cuda.Event(enable_timing=True) for _ in edges]
     t0 = time.perf_counter()
@@ -471,7 +471,7 @@ def main():
                     "status": rr["status"], "status_text": hop.hop_strerror(rr["status"]), "k_eff": rr["info"]["k_eff"],
                     "launches": rr["info"]["n_launches"], "host_ms_per_call": round(rr["wall_ms"], 5),
                     "c_caller": rr.get("c_loop"),
-                    "timing": "median of batches of 100 calls" if tiny else "median of batches of 5 calls"}
+                    "timing": "median of batches of 100 calls" if tiny else "median of batches of 10 calls"}
             del o2, d2
             torch.cuda.empty_cache()
     w, objs, order, dsts, res = run_workload(args.workload, args.steps, args.warmup)

@@ -53,8 +53,9 @@ typedef enum {
     HOP_ERR_NOMEM = -5,         /* host or device allocation failed                          */
     HOP_ERR_DEPTH = -6,         /* the tree needs more partial results in flight than the
                                    kernels hold in registers (see HOP_MAX_DEPTH)             */
-    HOP_ERR_TOO_LARGE = -7      /* hop_reduce_noalloc only: the call needs more device
-                                   scratch than the library's static array holds            */
+    HOP_ERR_TOO_LARGE = -7      /* the call needs more device scratch than it may take: than
+                                   the library's static array holds (hop_reduce_noalloc) or
+                                   than the caller's workspace (hop_session_set_workspace)   */
 } hop_status_t;
 
 /* Most partial results that can be live at once while one element's tree
@@ -318,6 +319,25 @@ int hop_session_set_adaptive(hop_session_t *s, int on);
  * or in hop_reduce_noalloc. on = 0: never keep; a repair reads every object
  * of the chunk again. Results are bit-identical either way. */
 int hop_session_set_retention(hop_session_t *s, int on);
+
+/* A workspace of the caller's for this session: from now on every byte of
+ * device scratch the session needs - staged programs and program segments,
+ * the saved accumulators of the eager policy, the kept partial results of
+ * failure repair - is taken from [device_memory, device_memory + bytes) and
+ * the session allocates nothing, neither on the device nor in pinned host
+ * memory (programs reach the workspace through kernel arguments), so its calls
+ * never block on an allocation and can be captured into a HIP graph.
+ * device_memory: device pointer, 256-byte aligned, owned by the caller, not to
+ * be touched until the stream has executed the session's work (and, for a
+ * captured graph, as long as the graph is replayed). Call it right after
+ * hop_session_begin: HOP_ERR_INVALID once the session has staged anything.
+ * hop_workspace_bytes gives the size of the object-sized arrays (saved
+ * accumulators, kept partials); on top of that every launch of the eager policy
+ * stages its program segment (16 bytes per step, rounded up to 256) and nothing
+ * is given back before the session ends, so add that for the launches expected.
+ * An event call that runs out of workspace returns HOP_ERR_TOO_LARGE (kept
+ * partial results that do not fit are simply not kept). */
+int hop_session_set_workspace(hop_session_t *s, void *device_memory, size_t bytes);
 
 /* Number of leading output chunks that are final in dst as far as the work
  * enqueued so far goes (a later failure can take chunks back). This is what a

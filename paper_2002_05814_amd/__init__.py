@@ -30,7 +30,7 @@ DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
 
 EXPORTS = ["hop_reduce", "hop_reduce_noalloc", "hop_noalloc_scratch_bytes", "hop_broadcast", "hop_allreduce", "hop_bcast_begin", "hop_bcast_source_ready",
            "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready", "hop_session_ready_after",
-           "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_set_adaptive", "hop_session_set_retention", "hop_session_chunks_final",
+           "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_set_adaptive", "hop_session_set_retention", "hop_session_set_workspace", "hop_session_chunks_final",
            "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
            "hop_pick_degree", "hop_calibrate", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
 
@@ -118,6 +118,7 @@ def lib() -> ctypes.CDLL:
         L.hop_session_set_eager.argtypes = [vp, ctypes.c_int]
         L.hop_session_set_adaptive.argtypes = [vp, ctypes.c_int]
         L.hop_session_set_retention.argtypes = [vp, ctypes.c_int]
+        L.hop_session_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
         L.hop_session_chunks_final.argtypes = [vp]
         L.hop_session_chunks_final.restype = ctypes.c_int64
         L.hop_plan_session_begin.argtypes = [ctypes.POINTER(vp), ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
@@ -366,6 +367,14 @@ def hop_session_fail(session, obj):
 
 def hop_session_set_adaptive(session, on):
     return lib().hop_session_set_adaptive(session, int(bool(on)))
+
+
+def hop_session_set_workspace(session, buf, nbytes=None):
+    """buf: a CUDA tensor (or raw address with nbytes) the session takes all its device scratch from."""
+    if isinstance(buf, torch.Tensor):
+        return lib().hop_session_set_workspace(session, ctypes.c_void_p(int(buf.data_ptr())),
+                                               buf.numel() * buf.element_size() if nbytes is None else int(nbytes))
+    return lib().hop_session_set_workspace(session, ctypes.c_void_p(int(buf)), int(nbytes))
 
 
 def hop_session_set_retention(session, on):

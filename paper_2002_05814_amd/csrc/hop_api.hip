@@ -279,6 +279,15 @@ public:
     ~Workspace() { for (Block *b : blocks_) release_block(b, stream_); }
 
     bool is_static() const { return static_base_ != nullptr; }
+    // Switches to static mode on the caller's memory; only while nothing has been taken yet.
+    bool make_static(char *base, size_t cap)
+    {
+        if (!blocks_.empty() || is_static() || !base) return false;
+        static_base_ = base;
+        static_cap_ = cap;
+        used_ = 0;
+        return true;
+    }
     // Hands the blocks over to the caller (who releases them later): what was staged stays valid.
     std::vector<Block *> detach()
     {
@@ -401,7 +410,7 @@ public:
                const Shape &shape, int op, int dtype, int k, int64_t degree, char *static_base = nullptr,
                size_t static_cap = 0)
         : ws_(device, stream, static_base, static_cap), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
-          op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device)
+          op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device), library_scratch_(static_base != nullptr)
     {
         if (dsts_.size() > 1) extra_residue_ = common_residue(dsts_.data() + 1, (int)dsts_.size() - 1);
     }
@@ -411,6 +420,14 @@ public:
         release_devbuf(spill_buf_, stream_);
         release_devbuf(kept_buf_, stream_);
         if (busy_ev_) (void)hipEventDestroy(busy_ev_);
+    }
+
+    // From now on every byte of device scratch (staged programs, saved accumulators, kept partial results)
+    // comes out of [base, base + bytes), memory of the caller's; possible only before anything was staged.
+    bool use_workspace(void *base, size_t bytes)
+    {
+        if (spill_ || kept_ || dev_prog_ || dev_extra_ || library_scratch_) return false;
+        return ws_.make_static((char *)base, bytes);
     }
 
     // the staged programs and scratch this back end's launches refer to, for a caller that will replay them
@@ -442,14 +459,21 @@ public:
     bool keep_partials(int n_partials) override
     {
         if (kept_) return true;
-        if (ws_.is_static() || n_partials < 1 || shape_.object_bytes == 0) return false;
+        if (n_partials < 1 || shape_.object_bytes == 0 || library_scratch_) return false;
         // 4 bytes per element, in blocks for 64 source vectors each (see kept_offset in the device code)
         const size_t n_blocks = ((shape_.object_bytes + 15) / 16 + 63) / 64;
         kept_stride_ = n_blocks * 1024 * (size_t)(4 / elem_bytes(dtype_));
         if (kept_stride_ > kMaxKeptBytes / (size_t)n_partials) return false;
-        kept_buf_ = acquire_devbuf(device_, kept_stride_ * (size_t)n_partials);
-        if (!kept_buf_) return false;
-        kept_ = kept_buf_->ptr;
+        if (ws_.is_static()) {
+            // a caller's workspace: the kept arrays come out of it if they fit (else nothing is kept)
+            if (kept_stride_ * (size_t)n_partials + 256 > ws_.static_left()) return false;
+            kept_ = (char *)ws_.scratch(kept_stride_ * (size_t)n_partials);
+            if (!kept_) return false;
+        } else {
+            kept_buf_ = acquire_devbuf(device_, kept_stride_ * (size_t)n_partials);
+            if (!kept_buf_) return false;
+            kept_ = kept_buf_->ptr;
+        }
         n_kept_ = n_partials;
         return true;
     }
@@ -530,13 +554,19 @@ private:
     {
         const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
         if (!spill_) {
-            if (ws_.is_static()) return HOP_ERR_TOO_LARGE;        // saved accumulators are object-sized: never from the static scratch
             const size_t n_elems = shape_.object_bytes / (size_t)elem_bytes(dtype_);
             level_stride_ = (n_elems * 4 + 255) & ~(size_t)255;
             spill_levels_ = std::min(HOP_MAX_DEPTH, full_tree_depth(k_, degree_));
-            spill_buf_ = acquire_devbuf(device_, level_stride_ * (size_t)spill_levels_);
-            if (!spill_buf_) return HOP_ERR_NOMEM;
-            spill_ = spill_buf_->ptr;
+            if (ws_.is_static()) {
+                // the library's own static scratch never holds object-sized arrays; a caller's workspace does
+                if (library_scratch_) return HOP_ERR_TOO_LARGE;
+                spill_ = (char *)ws_.scratch(level_stride_ * (size_t)spill_levels_);
+                if (!spill_) return ws_.error();
+            } else {
+                spill_buf_ = acquire_devbuf(device_, level_stride_ * (size_t)spill_levels_);
+                if (!spill_buf_) return HOP_ERR_NOMEM;
+                spill_ = spill_buf_->ptr;
+            }
         }
         int depth = 1;
         std::vector<DevEntry> steps((size_t)(t1 - t0));
@@ -707,6 +737,7 @@ private:
     int spill_levels_ = 0;
     hipEvent_t busy_ev_ = nullptr;
     bool busy_recorded_ = false, track_idle_ = false;
+    bool library_scratch_ = false;              // all scratch from the library's small static array (hop_reduce_noalloc)
     DevBuf *kept_buf_ = nullptr;                // partial results kept for failure repair
     char *kept_ = nullptr;
     size_t kept_stride_ = 0;
@@ -1438,6 +1469,14 @@ int hop_session_set_eager(hop_session_t *s, int min_steps)
     if (!s || min_steps < 0) return HOP_ERR_INVALID;
     s->sched->set_eager(min_steps);
     return HOP_OK;
+}
+
+int hop_session_set_workspace(hop_session_t *s, void *device_memory, size_t bytes)
+{
+    if (!s || !device_memory || bytes < 256) return HOP_ERR_INVALID;
+    if (((uintptr_t)device_memory & 255u) != 0) return HOP_ERR_ALIGN;
+    if (!s->be) return HOP_OK;                       // host-only sessions have no scratch
+    return s->be->use_workspace(device_memory, bytes) ? HOP_OK : HOP_ERR_INVALID;
 }
 
 int hop_session_set_retention(hop_session_t *s, int on)

@@ -416,11 +416,13 @@ def test_receiver_driven_broadcast_chains_and_survives_a_lost_copy():
 
 # ------------------------------------------------------------------ event-level sessions
 
-def session_replay(objs, dst, k, op, dtype, chunk, d, order, fm, C, fine, eager=0):
+def session_replay(objs, dst, k, op, dtype, chunk, d, order, fm, C, fine, eager=0, workspace=None, stream=None):
     """Drives the session API with the same timeline hop_reduce replays, either in bulk
     (per failure step) or chunk by chunk."""
-    rc, s = hop.hop_session_begin(dst, objs, k, op, dtype, chunk, d)
+    rc, s = hop.hop_session_begin(dst, objs, k, op, dtype, chunk, d, stream=stream)
     assert rc == hop.HOP_OK
+    if workspace is not None:
+        assert hop.hop_session_set_workspace(s, workspace) == hop.HOP_OK
     assert hop.hop_session_set_eager(s, eager) == hop.HOP_OK
     n = len(objs)
     limit = [C if (fm is None or fm[i] < 0 or fm[i] >= C) else int(fm[i]) for i in range(n)]
@@ -1079,6 +1081,80 @@ def test_late_arrival_into_a_hole_reuses_the_kept_partials():
     orc, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], 8, oracle.SUM, oracle.F32, w.chunk_bytes // 4, 2,
                                     order, fm)
     assert orc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+
+
+def test_session_with_a_workspace_of_the_callers():
+    # every byte of scratch (staged segments, saved accumulators, kept partials) from a buffer of the
+    # caller's: same bits as the oracle and as a session on the library's own caches
+    d = dev()
+    w = workloads.WORKLOADS[2].scaled((12 << 20) + 12, 1 << 20, n=14, k=12, tree_degree=3, order_seed=31, data_seed=32,
+                                      fail={}, name="own_workspace")
+    objs = workloads.make_objects(w, device=d)
+    order = w.ready_order()
+    fm = np.full(w.n, -1, np.int64)
+    fm[order[4]] = 9
+    C = w.n_chunks
+    need = hop.hop_workspace_bytes(w.n, w.k, w.object_bytes, w.chunk_bytes, w.tree_degree, w.dtype,
+                                   policy=hop.HOP_WS_EAGER | hop.HOP_WS_FAILURES)
+    assert need > 3 * w.n_elems * 4
+    host = [workloads.to_numpy(o) for o in objs]
+    orc, want, k_eff, _ = oracle.reduce(host, w.k, oracle.SUM, oracle.F32, w.chunk_bytes // 4, w.tree_degree, order, fm)
+    for eager in (0, 1):
+        ws = torch.empty(need + (1 << 20), dtype=torch.uint8, device=d)        # + room for the staged segments
+        dst = torch.zeros_like(objs[0])
+        rc, info = session_replay(objs, dst, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, fm, C, fine=False,
+                                  eager=eager, workspace=ws)
+        torch.cuda.synchronize()
+        assert rc == orc and info["k_eff"] == k_eff
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+        if eager == 0:
+            assert info["partial_stores"] > 0 and info["partial_loads"] > 0       # kept partials lived in the workspace
+    # a workspace that cannot hold the saved accumulators: the event that needs them says so
+    small = torch.empty(1 << 20, dtype=torch.uint8, device=d)
+    dst = torch.zeros_like(objs[0])
+    rc, s = hop.hop_session_begin(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree)
+    assert rc == hop.HOP_OK and hop.hop_session_set_workspace(s, small) == hop.HOP_OK
+    assert hop.hop_session_set_eager(s, 1) == hop.HOP_OK
+    assert hop.hop_session_ready(s, int(order[0]), C) == hop.HOP_ERR_TOO_LARGE
+    hop.hop_session_finish(s)
+    # too late once something has been staged; misaligned memory is refused
+    rc, s = hop.hop_session_begin(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree)
+    assert hop.hop_session_set_eager(s, 1) == hop.HOP_OK
+    assert hop.hop_session_ready(s, int(order[0]), C) == hop.HOP_OK
+    assert hop.hop_session_set_workspace(s, small) == hop.HOP_ERR_INVALID
+    assert hop.hop_session_set_workspace(s, int(small.data_ptr()) + 16, 1 << 19) == hop.HOP_ERR_ALIGN
+    hop.hop_session_finish(s)
+    torch.cuda.synchronize()
+
+
+def test_eager_session_with_a_workspace_can_be_captured_in_a_graph():
+    # with a workspace of the caller's an eager session is nothing but kernel launches: its event calls can
+    # be recorded into a graph, and every replay must see the current inputs
+    d = dev()
+    w = workloads.WORKLOADS[2].scaled((2 << 20) + 12, 512 << 10, n=6, k=6, tree_degree=2, order_seed=41, data_seed=42,
+                                      name="captured_session")
+    objs = workloads.make_objects(w, device=d)
+    order = w.ready_order()
+    dst = torch.zeros_like(objs[0])
+    need = hop.hop_workspace_bytes(w.n, w.k, w.object_bytes, w.chunk_bytes, w.tree_degree, w.dtype, policy=hop.HOP_WS_EAGER)
+    ws = torch.empty(need + (256 << 10), dtype=torch.uint8, device=d)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc, info = session_replay(objs, dst, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None, w.n_chunks,
+                                  fine=False, eager=1, workspace=ws)
+    assert rc == hop.HOP_OK and info["n_launches"] == w.k
+    rng = np.random.default_rng(6)
+    for rep in range(3):
+        for o in objs:                                # eager work between the replays
+            o.mul_(float(rng.uniform(0.5, 1.5)))
+        dst.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        _, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], w.k, oracle.SUM, oracle.F32,
+                                      w.chunk_bytes // 4, w.tree_degree, order, None)
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want)), rep
 
 
 def test_calibration_feeds_the_automatic_degree():
