@@ -1,7 +1,8 @@
-// C ABI of the reduce library (include/hop.h): argument checks, the GPU back
-// end that turns scheduler launches into kernel launches, the cached
-// workspace that carries accumulator programs and destination tables to the
-// device, and the recording back end behind hop_plan_reduce.
+// C ABI of the reduce library (include/hop.h): argument checks, the degree choice and its
+// calibration, the static scratch of the entry point that allocates nothing, the recordings of
+// repeated small calls, and the entry points themselves. The scheduler is in hop_plan.hpp, the
+// back ends that turn its launches into kernel launches in hop_gpu_backend.hpp, the cached
+// workspaces in hop_workspace.hpp.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -13,188 +14,12 @@
 #include <vector>
 
 #include "hop_bcast.hpp"
+#include "hop_gpu_backend.hpp"
 #include "hop_kernels.h"
 #include "hop_plan.hpp"
+#include "hop_workspace.hpp"
 
 namespace hop {
-
-// ----------------------------------------------------------------------------
-// workspace: pinned host staging + device memory, cached across calls
-// ----------------------------------------------------------------------------
-
-struct Block {
-    int device = -1;
-    char *host = nullptr;       // pinned
-    char *host_dev = nullptr;   // the pinned memory as the device addresses it
-    char *dev = nullptr;
-    size_t cap = 0;
-    hipEvent_t ev = nullptr;    // last use on a stream
-    bool pending = false;
-};
-
-static std::mutex g_mu;
-static std::vector<Block *> g_free;
-static constexpr size_t kMinBlock = 256 * 1024;
-
-// Once this many staging blocks exist, a caller that finds a large enough block still in use
-// by the GPU waits for the oldest such block instead of allocating another: a host that runs
-// ahead of the GPU is slowed down rather than growing the cache without bound. (Blocks held
-// by open sessions are not in the cache and are not waited for.)
-static constexpr int kMaxBlocks = 8;
-static int g_block_count = 0;
-
-static Block *acquire_block(int device, size_t bytes)
-{
-    Block *wait_for = nullptr, *too_small = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        for (size_t i = 0; i < g_free.size(); ++i) {
-            Block *b = g_free[i];
-            if (b->device != device || b->cap < bytes) continue;
-            if (b->pending) {
-                if (hipEventQuery(b->ev) != hipSuccess) {
-                    (void)hipGetLastError();
-                    if (!wait_for) wait_for = b;          // g_free is in release order: the oldest one
-                    continue;
-                }
-                b->pending = false;
-            }
-            g_free.erase(g_free.begin() + i);
-            return b;
-        }
-        if (g_block_count >= kMaxBlocks) {
-            // at the limit: an idle block that is too small makes room for one of the right size
-            // (otherwise callers of the larger size would queue for the few blocks that fit them)
-            for (size_t i = 0; i < g_free.size() && !too_small; ++i) {
-                Block *b = g_free[i];
-                if (b->device != device || b->cap >= bytes) continue;
-                if (b->pending && hipEventQuery(b->ev) != hipSuccess) { (void)hipGetLastError(); continue; }
-                too_small = b;
-                g_free.erase(g_free.begin() + i);
-            }
-        }
-        if (too_small) {
-            wait_for = nullptr;                           // its place in the count goes to the new block
-        } else if (wait_for && g_block_count >= kMaxBlocks) {
-            g_free.erase(std::find(g_free.begin(), g_free.end(), wait_for));
-        } else {
-            wait_for = nullptr;
-            g_block_count++;
-        }
-    }
-    if (too_small) {
-        (void)hipEventDestroy(too_small->ev);
-        (void)hipFree(too_small->dev);
-        (void)hipHostFree(too_small->host);
-        delete too_small;
-    }
-    if (wait_for) {
-        if (hipEventSynchronize(wait_for->ev) != hipSuccess) (void)hipGetLastError();
-        wait_for->pending = false;
-        return wait_for;
-    }
-    Block *b = new (std::nothrow) Block;
-    bool ok = b != nullptr;
-    if (ok) {
-        b->device = device;
-        b->cap = bytes < kMinBlock ? kMinBlock : ((bytes + kMinBlock - 1) / kMinBlock) * kMinBlock;
-        ok = hipHostMalloc((void **)&b->host, b->cap, hipHostMallocDefault) == hipSuccess;
-        if (ok && hipHostGetDevicePointer((void **)&b->host_dev, b->host, 0) != hipSuccess) { (void)hipHostFree(b->host); ok = false; }
-        if (ok && hipMalloc((void **)&b->dev, b->cap) != hipSuccess) { (void)hipHostFree(b->host); ok = false; }
-        if (ok && hipEventCreateWithFlags(&b->ev, hipEventDisableTiming) != hipSuccess) {
-            (void)hipFree(b->dev); (void)hipHostFree(b->host); ok = false;
-        }
-    }
-    if (!ok) {
-        delete b;
-        std::lock_guard<std::mutex> lk(g_mu);
-        g_block_count--;
-        return nullptr;
-    }
-    return b;
-}
-
-static void release_block(Block *b, hipStream_t stream)
-{
-    if (!b) return;
-    b->pending = (hipEventRecord(b->ev, stream) == hipSuccess);
-    std::lock_guard<std::mutex> lk(g_mu);
-    g_free.push_back(b);
-}
-
-// Large device-only scratch (saved accumulators of eager sessions), cached the same way: a
-// buffer goes back to the cache with an event and is handed out again once that event is done.
-struct DevBuf {
-    int device = -1;
-    char *ptr = nullptr;
-    size_t cap = 0;
-    hipEvent_t ev = nullptr;
-    bool pending = false;
-};
-static std::vector<DevBuf *> g_devbufs;
-static constexpr size_t kDevCacheLimit = (size_t)8 << 30;     // beyond this, idle buffers are freed
-
-static DevBuf *acquire_devbuf(int device, size_t bytes)
-{
-    DevBuf *wait_for = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        DevBuf *best = nullptr;
-        int n_busy = 0;
-        for (DevBuf *b : g_devbufs) {
-            if (b->device != device || b->cap < bytes) continue;
-            if (b->pending) {
-                if (hipEventQuery(b->ev) != hipSuccess) {
-                    (void)hipGetLastError();
-                    if (!wait_for) wait_for = b;          // release order: the oldest one
-                    ++n_busy;
-                    continue;
-                }
-                b->pending = false;
-            }
-            if (!best || b->cap < best->cap) best = b;
-        }
-        if (best) {
-            g_devbufs.erase(std::find(g_devbufs.begin(), g_devbufs.end(), best));
-            return best;
-        }
-        // two buffers in flight are enough to overlap one session's tail with the next one's
-        // start; beyond that, wait for the oldest instead of growing
-        if (wait_for && n_busy >= 2) g_devbufs.erase(std::find(g_devbufs.begin(), g_devbufs.end(), wait_for));
-        else wait_for = nullptr;
-    }
-    if (wait_for) {
-        if (hipEventSynchronize(wait_for->ev) != hipSuccess) (void)hipGetLastError();
-        wait_for->pending = false;
-        return wait_for;
-    }
-    DevBuf *b = new (std::nothrow) DevBuf;
-    if (!b) return nullptr;
-    b->device = device;
-    b->cap = bytes;
-    if (hipMalloc((void **)&b->ptr, bytes) != hipSuccess) { (void)hipGetLastError(); delete b; return nullptr; }
-    if (hipEventCreateWithFlags(&b->ev, hipEventDisableTiming) != hipSuccess) { (void)hipFree(b->ptr); delete b; return nullptr; }
-    return b;
-}
-
-static void release_devbuf(DevBuf *b, hipStream_t stream)
-{
-    if (!b) return;
-    b->pending = (hipEventRecord(b->ev, stream) == hipSuccess);
-    std::lock_guard<std::mutex> lk(g_mu);
-    g_devbufs.push_back(b);
-    size_t total = 0;
-    for (DevBuf *x : g_devbufs) total += x->cap;
-    for (size_t i = 0; i < g_devbufs.size() && total > kDevCacheLimit;) {
-        DevBuf *x = g_devbufs[i];
-        if (x->pending && hipEventQuery(x->ev) != hipSuccess) { (void)hipGetLastError(); ++i; continue; }
-        total -= x->cap;
-        (void)hipEventDestroy(x->ev);
-        (void)hipFree(x->ptr);
-        delete x;
-        g_devbufs.erase(g_devbufs.begin() + i);
-    }
-}
 
 // ----------------------------------------------------------------------------
 // scratch for callers that cannot allocate (hop_reduce_noalloc)
@@ -225,560 +50,6 @@ static int static_scratch(int device, char **ptr)
     *ptr = g_scratch_ptr[device];
     return HOP_OK;
 }
-
-// Carries up to kPokeVectors * 16 bytes from the kernel arguments to device memory: how programs
-// and tables reach the static scratch without a staging buffer.
-constexpr int kPokeVectors = 240;
-struct PokeArgs {
-    uint4 *dst;
-    int n;
-    int pad;
-    uint4 data[kPokeVectors];
-};
-static_assert(sizeof(PokeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
-
-__global__ __launch_bounds__(256) void poke_kernel(PokeArgs a)
-{
-    const int i = (int)threadIdx.x;
-    if (i < a.n) a.dst[i] = a.data[i];
-}
-
-static bool poke(hipStream_t stream, void *dst, const void *src, size_t bytes)
-{
-    const char *from = (const char *)src;
-    char *to = (char *)dst;
-    while (bytes > 0) {
-        PokeArgs a;
-        const size_t now = bytes < sizeof a.data ? bytes : sizeof a.data;
-        a.dst = (uint4 *)to;
-        a.n = (int)((now + 15) / 16);
-        a.pad = 0;
-        std::memset(&a.data[(size_t)a.n - 1], 0, sizeof(uint4));        // the last vector may be partly filled
-        std::memcpy(a.data, from, now);
-        hipLaunchKernelGGL(poke_kernel, dim3(1), dim3(256), 0, stream, a);
-        if (hipGetLastError() != hipSuccess) return false;
-        from += now;
-        to += now;
-        bytes -= now;
-    }
-    return true;
-}
-
-// Bump allocator over a list of blocks; everything staged is copied to the
-// device with one async copy per stage() call, ordered on the stream.
-//
-// Static mode (static_base given): every request is served from one caller-given stretch of
-// device memory, nothing is allocated, and staged data travels through kernel arguments. A
-// request that does not fit fails, and error() then says HOP_ERR_TOO_LARGE.
-class Workspace {
-public:
-    Workspace(int device, hipStream_t stream, char *static_base = nullptr, size_t static_cap = 0)
-        : device_(device), stream_(stream), static_base_(static_base), static_cap_(static_base ? static_cap : 0) {}
-    Workspace(const Workspace &) = delete;
-    Workspace &operator=(const Workspace &) = delete;
-    ~Workspace() { for (Block *b : blocks_) release_block(b, stream_); }
-
-    bool is_static() const { return static_base_ != nullptr; }
-    // Switches to static mode on the caller's memory; only while nothing has been taken yet.
-    bool make_static(char *base, size_t cap)
-    {
-        if (!blocks_.empty() || is_static() || !base) return false;
-        static_base_ = base;
-        static_cap_ = cap;
-        used_ = 0;
-        return true;
-    }
-    // Hands the blocks over to the caller (who releases them later): what was staged stays valid.
-    std::vector<Block *> detach()
-    {
-        std::vector<Block *> out;
-        out.swap(blocks_);
-        used_ = 0;
-        return out;
-    }
-    // why the last request failed
-    int error() const { return too_large_ ? HOP_ERR_TOO_LARGE : HOP_ERR_NOMEM; }
-    // bytes a request of any kind may still take in static mode
-    size_t static_left() const { return static_cap_ - used_; }
-
-    // Copies `bytes` from src to device memory (16-byte aligned); returns the device address or null.
-    void *stage(const void *src, size_t bytes)
-    {
-        size_t need = (bytes + 255) & ~(size_t)255;
-        if (is_static()) {
-            void *d = scratch(bytes);
-            if (d && !poke(stream_, d, src, bytes)) return nullptr;
-            return d;
-        }
-        if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
-            Block *b = acquire_block(device_, need);
-            if (!b) return nullptr;
-            blocks_.push_back(b);
-            used_ = 0;
-        }
-        Block *b = blocks_.back();
-        std::memcpy(b->host + used_, src, bytes);
-        if (hipMemcpyAsync(b->dev + used_, b->host + used_, bytes, hipMemcpyHostToDevice, stream_) != hipSuccess)
-            return nullptr;
-        void *d = b->dev + used_;
-        used_ += need;
-        return d;
-    }
-
-    // Copies `bytes` from src into pinned host memory and returns the address at which kernels
-    // read it in place (over the host link): for small tables read once by few workgroups this is
-    // cheaper than a copy engine transfer queued ahead of the kernel.
-    const void *stage_in_place(const void *src, size_t bytes)
-    {
-        size_t need = (bytes + 255) & ~(size_t)255;
-        if (is_static()) return stage(src, bytes);        // no pinned memory here: a copy on the device
-        if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
-            Block *b = acquire_block(device_, need);
-            if (!b) return nullptr;
-            blocks_.push_back(b);
-            used_ = 0;
-        }
-        Block *b = blocks_.back();
-        std::memcpy(b->host + used_, src, bytes);
-        const void *d = b->host_dev + used_;
-        used_ += need;
-        return d;
-    }
-
-    // Makes sure the next `bytes` of stage()/scratch() requests come from one block.
-    bool reserve(size_t bytes)
-    {
-        if (is_static()) {
-            too_large_ = used_ + bytes > static_cap_;
-            return !too_large_;
-        }
-        if (!blocks_.empty() && used_ + bytes <= blocks_.back()->cap) return true;
-        Block *b = acquire_block(device_, bytes);
-        if (!b) return false;
-        blocks_.push_back(b);
-        used_ = 0;
-        return true;
-    }
-
-    // Uninitialised device scratch (256-byte aligned), valid until the workspace is released.
-    void *scratch(size_t bytes)
-    {
-        size_t need = (bytes + 255) & ~(size_t)255;
-        if (is_static()) {
-            if (need > static_cap_ - used_) { too_large_ = true; return nullptr; }
-            void *d = static_base_ + used_;
-            used_ += need;
-            return d;
-        }
-        if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
-            Block *b = acquire_block(device_, need);
-            if (!b) return nullptr;
-            blocks_.push_back(b);
-            used_ = 0;
-        }
-        void *d = blocks_.back()->dev + used_;
-        used_ += need;
-        return d;
-    }
-
-private:
-    int device_;
-    hipStream_t stream_;
-    std::vector<Block *> blocks_;
-    size_t used_ = 0;
-    char *static_base_ = nullptr;
-    size_t static_cap_ = 0;
-    bool too_large_ = false;
-};
-
-// ----------------------------------------------------------------------------
-// back ends
-// ----------------------------------------------------------------------------
-
-struct Shape {
-    size_t object_bytes = 0, chunk_bytes = 0;
-    int64_t n_chunks = 1;
-    size_t begin(int64_t c) const { return (size_t)c * chunk_bytes; }
-    size_t end(int64_t c) const { size_t e = (size_t)c * chunk_bytes; return e < object_bytes ? e : object_bytes; }
-};
-
-class GpuBackend : public Backend {
-public:
-    // static_base != nullptr: all device scratch comes from [static_base, static_base + static_cap) and
-    // nothing is allocated (the back end of hop_reduce_noalloc)
-    GpuBackend(int device, hipStream_t stream, const void *const *objs, int n, std::vector<void *> dsts,
-               const Shape &shape, int op, int dtype, int k, int64_t degree, char *static_base = nullptr,
-               size_t static_cap = 0)
-        : ws_(device, stream, static_base, static_cap), stream_(stream), objs_(objs, objs + n), dsts_(std::move(dsts)), shape_(shape),
-          op_(op), dtype_(dtype), k_(k), degree_(degree), device_(device), library_scratch_(static_base != nullptr)
-    {
-        if (dsts_.size() > 1) extra_residue_ = common_residue(dsts_.data() + 1, (int)dsts_.size() - 1);
-    }
-
-    ~GpuBackend() override
-    {
-        release_devbuf(spill_buf_, stream_);
-        release_devbuf(kept_buf_, stream_);
-        if (busy_ev_) (void)hipEventDestroy(busy_ev_);
-    }
-
-    // From now on every byte of device scratch (staged programs, saved accumulators, kept partial results)
-    // comes out of [base, base + bytes), memory of the caller's; possible only before anything was staged.
-    bool use_workspace(void *base, size_t bytes)
-    {
-        if (spill_ || kept_ || dev_prog_ || dev_extra_ || library_scratch_) return false;
-        return ws_.make_static((char *)base, bytes);
-    }
-
-    // the staged programs and scratch this back end's launches refer to, for a caller that will replay them
-    std::vector<Block *> detach_blocks()
-    {
-        dev_prog_ = nullptr;
-        dev_extra_ = nullptr;
-        dev_version_ = 0;
-        return ws_.detach();
-    }
-
-    // Adaptive sessions ask whether the stream has worked off what this session launched: an event
-    // is recorded behind every launch from now on.
-    void track_idle() { track_idle_ = true; }
-    bool idle() override
-    {
-        if (!busy_recorded_) return true;
-        if (hipEventQuery(busy_ev_) == hipSuccess) return true;
-        (void)hipGetLastError();
-        return false;
-    }
-
-    // everything enqueued on the session's stream from now on runs after `ev` has completed
-    bool wait_for(hipEvent_t ev) { return hipStreamWaitEvent(stream_, ev, 0) == hipSuccess; }
-
-    // Memory for the partial results kept for failure repair: one array of 4-byte accumulators per
-    // partial, each as long as the object has elements, from the library's cache of device buffers.
-    // Refused without the right to allocate, and beyond kMaxKeptBytes.
-    bool keep_partials(int n_partials) override
-    {
-        if (kept_) return true;
-        if (n_partials < 1 || shape_.object_bytes == 0 || library_scratch_) return false;
-        // 4 bytes per element, in blocks for 64 source vectors each (see kept_offset in the device code)
-        const size_t n_blocks = ((shape_.object_bytes + 15) / 16 + 63) / 64;
-        kept_stride_ = n_blocks * 1024 * (size_t)(4 / elem_bytes(dtype_));
-        if (kept_stride_ > kMaxKeptBytes / (size_t)n_partials) return false;
-        if (ws_.is_static()) {
-            // a caller's workspace: the kept arrays come out of it if they fit (else nothing is kept)
-            if (kept_stride_ * (size_t)n_partials + 256 > ws_.static_left()) return false;
-            kept_ = (char *)ws_.scratch(kept_stride_ * (size_t)n_partials);
-            if (!kept_) return false;
-        } else {
-            kept_buf_ = acquire_devbuf(device_, kept_stride_ * (size_t)n_partials);
-            if (!kept_buf_) return false;
-            kept_ = kept_buf_->ptr;
-        }
-        n_kept_ = n_partials;
-        return true;
-    }
-
-    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
-               int live_before, int live_after) override
-    {
-        const int rc = launch_work(prog, version, c0, c1, t0, t1, final, live_before, live_after);
-        if (rc >= 0 && track_idle_) {
-            if (!busy_ev_ && hipEventCreateWithFlags(&busy_ev_, hipEventDisableTiming) != hipSuccess) return HOP_ERR_DEVICE;
-            if (hipEventRecord(busy_ev_, stream_) != hipSuccess) return HOP_ERR_DEVICE;
-            busy_recorded_ = true;
-        }
-        return rc;
-    }
-
-private:
-    int launch_work(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
-                    int live_before, int live_after)
-    {
-        if (shape_.object_bytes == 0) return HOP_OK;
-        if (t0 > 0 || !final) return launch_segment(prog, c0, c1, t0, t1, final, live_before, live_after);
-        for (const Entry &e : prog)
-            if (e.obj < 0 || e.save >= 0) return launch_kept(prog, version, c0, c1);
-        const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
-        if (wants_split(prog.size(), b1 - b0)) {
-            int rc = launch_split(prog, b0, b1);
-            if (rc != HOP_PARTIAL) {                // HOP_PARTIAL here = "not splittable, use the plain path"
-                if (rc < 0) return rc;
-                return copy_to_other_destinations(b0, b1);
-            }
-        }
-        if (version != dev_version_) {
-            staging_.resize(prog.size());
-            depth_ = 1;
-            for (size_t i = 0; i < prog.size(); ++i) {
-                staging_[i] = resolve(prog[i], nullptr, 0, 0);
-                depth_ = std::max(depth_, (int)prog[i].level + 1);
-            }
-            mark_runs(staging_.data(), staging_.size());
-            dev_prog_ = nullptr;
-            if ((int)staging_.size() > kInlineEntries) {      // short programs ride in the kernel arguments
-                dev_prog_ = (const DevEntry *)ws_.stage(staging_.data(), staging_.size() * sizeof(DevEntry));
-                if (!dev_prog_) return ws_.error();
-            }
-            dev_version_ = version;
-        }
-        // Storing to all destinations from the reduce kernel itself was measured slower than a reduce into
-        // the first one followed by the copy (reads and 64-way writes interleaved: 492 us against 391 us
-        // on 64 x 16 MiB).
-        hipError_t e = launch_reduce(stream_, dtype_, op_, depth_, staging_.data(), dev_prog_, (int)prog.size(),
-                                     dsts_[0], b0, b1);
-        if (e != hipSuccess) return HOP_ERR_DEVICE;
-        return copy_to_other_destinations(b0, b1);
-    }
-
-private:
-    // Reduce followed by broadcast, chunk run by chunk run: the finished chunks have landed in the first
-    // destination and the copy kernel carries them to the others while they are still cache-resident. Up
-    // to kInlineDsts other destinations ride in the kernel arguments; more are staged once per call.
-    int copy_to_other_destinations(size_t b0, size_t b1)
-    {
-        if (dsts_.size() < 2) return HOP_OK;
-        const int n_other = (int)dsts_.size() - 1;
-        if (n_other > kInlineDsts && !dev_extra_) {
-            dev_extra_ = (void *const *)ws_.stage(dsts_.data() + 1, (size_t)n_other * sizeof(void *));
-            if (!dev_extra_) return ws_.error();
-        }
-        const hipError_t e = launch_copy(stream_, dsts_[0], dev_extra_, n_other, b0, b1, nullptr, extra_residue_, dsts_.data() + 1);
-        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
-    }
-
-    // Steps [t0, t1) only: accumulators come from and/or go to the spill area, one array of 4-byte
-    // accumulators per level, each as long as the object has elements. It is taken from the
-    // library's cache when the first partial segment is launched and returned with the session.
-    int launch_segment(const std::vector<Entry> &prog, int64_t c0, int64_t c1, int t0, int t1, bool final,
-                       int live_before, int live_after)
-    {
-        const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
-        if (!spill_) {
-            const size_t n_elems = shape_.object_bytes / (size_t)elem_bytes(dtype_);
-            level_stride_ = (n_elems * 4 + 255) & ~(size_t)255;
-            spill_levels_ = std::min(HOP_MAX_DEPTH, full_tree_depth(k_, degree_));
-            if (ws_.is_static()) {
-                // the library's own static scratch never holds object-sized arrays; a caller's workspace does
-                if (library_scratch_) return HOP_ERR_TOO_LARGE;
-                spill_ = (char *)ws_.scratch(level_stride_ * (size_t)spill_levels_);
-                if (!spill_) return ws_.error();
-            } else {
-                spill_buf_ = acquire_devbuf(device_, level_stride_ * (size_t)spill_levels_);
-                if (!spill_buf_) return HOP_ERR_NOMEM;
-                spill_ = spill_buf_->ptr;
-            }
-        }
-        int depth = 1;
-        std::vector<DevEntry> steps((size_t)(t1 - t0));
-        for (int t = t0; t < t1; ++t) {
-            steps[(size_t)(t - t0)] = resolve(prog[(size_t)t], nullptr, 0, 0);
-            depth = std::max(depth, (int)prog[(size_t)t].level + 1);
-        }
-        depth = std::max(depth, std::max(live_before, live_after));
-        if (depth > spill_levels_) return HOP_ERR_DEPTH;
-        const DevEntry *dev_steps = nullptr;           // t0 == t1: only move saved accumulators to the result
-        if (!steps.empty()) {
-            dev_steps = (const DevEntry *)ws_.stage(steps.data(), steps.size() * sizeof(DevEntry));
-            if (!dev_steps) return ws_.error();
-        }
-        hipError_t e = launch_reduce_segment(stream_, dtype_, op_, depth, dev_steps, t1 - t0, dsts_[0], spill_,
-                                             level_stride_, live_before, final ? 0 : live_after, b0, b1,
-                                             steps.empty() ? 0 : lead_vectors(steps.data(), (int)steps.size(), b0));
-        if (e != hipSuccess) return HOP_ERR_DEVICE;
-        return final ? copy_to_other_destinations(b0, b1) : HOP_OK;
-    }
-
-    // A whole program some of whose steps read a kept partial result (obj = -(1 + q)) or store one
-    // (save = q): the repair of a failure and the launches that prepare for one.
-    static constexpr size_t kMaxKeptBytes = (size_t)16 << 30;
-
-    int launch_kept(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1)
-    {
-        if (!kept_) return HOP_ERR_NOMEM;               // keep_partials was not asked, or said no
-        const size_t b0 = shape_.begin(c0), b1 = shape_.end(c1);
-        if (version != kept_version_) {
-            kept_steps_.resize(prog.size());
-            kept_depth_ = 1;
-            for (size_t i = 0; i < prog.size(); ++i) {
-                const Entry &e = prog[i];
-                if (e.obj < 0 && -e.obj - 1 >= n_kept_) return HOP_ERR_INVALID;
-                if (e.save >= n_kept_ || e.save_level > e.level) return HOP_ERR_INVALID;
-                DevEntry d;
-                d.src = e.obj >= 0 ? objs_[e.obj] : (const void *)(kept_ + (size_t)(-e.obj - 1) * kept_stride_);
-                d.ctl = (uint32_t)e.level | ((uint32_t)e.set << 8) | ((uint32_t)e.n_fold << 16) | (e.obj < 0 ? kPartialBit : 0u);
-                d.aux = e.save >= 0 ? ((uint32_t)e.save + 1u) | ((uint32_t)e.save_level << 16) : 0u;
-                kept_steps_[i] = d;
-                kept_depth_ = std::max(kept_depth_, (int)e.level + 1);
-            }
-            kept_dev_ = nullptr;
-            if ((int)kept_steps_.size() > kInlineEntries) {       // short programs ride in the kernel arguments
-                kept_dev_ = (const DevEntry *)ws_.stage(kept_steps_.data(), kept_steps_.size() * sizeof(DevEntry));
-                if (!kept_dev_) return ws_.error();
-            }
-            kept_version_ = version;
-        }
-        hipError_t e = launch_reduce_kept(stream_, dtype_, op_, kept_depth_, kept_steps_.data(), kept_dev_, (int)prog.size(),
-                                          dsts_[0], kept_, kept_stride_, b0, b1);
-        if (e != hipSuccess) return HOP_ERR_DEVICE;
-        return copy_to_other_destinations(b0, b1);
-    }
-
-    // Many inputs but few output tiles (the many-small-objects case): one wave per tile would walk
-    // the whole program alone, so the independent subtrees are evaluated side by side first.
-    // Partials are stored in the accumulation type, which for bf16 is not the element type: bf16
-    // keeps the plain path.
-    static constexpr size_t kSplitWantSteps = 128;      // shorter programs are not worth extra launches
-    static constexpr int kSplitMaxRun = kMaxSubSteps;   // longest sub-program: a record fits the lanes of a wave
-    static constexpr size_t kSplitMaxBytes = 1u << 20;  // launches this large already fill the chip
-    static constexpr int kSplitMinRun = 4;
-    static constexpr size_t kSplitMaxScratch = 16u << 20;
-
-    bool wants_split(size_t n_steps, size_t range_bytes) const
-    {
-        return dtype_ != HOP_BF16 && n_steps >= kSplitWantSteps && range_bytes <= kSplitMaxBytes;
-    }
-
-    int launch_split(const std::vector<Entry> &prog, size_t b0, size_t b1)
-    {
-        MultiPlan mp;
-        if (!plan_passes(prog, kSplitWantSteps, kSplitMinRun, kSplitMaxRun, mp)) return HOP_PARTIAL;
-        const size_t range = b1 - b0;
-        const size_t part_bytes = (range + 255) & ~(size_t)255;
-        const size_t n_subs = mp.n_subs();
-        if (part_bytes * n_subs > kSplitMaxScratch || n_subs > 65535) return HOP_PARTIAL;
-        // partials, then every sub-program as a record of equal length per pass: from one block
-        struct PassInfo { size_t records_at; int sub_entries, n_subs, depth; };
-        std::vector<PassInfo> passes(mp.n_passes, PassInfo{0, 2, 0, 1});
-        for (size_t g = 0; g < n_subs; ++g) {
-            PassInfo &pi = passes[(size_t)mp.height[g]];
-            pi.sub_entries = std::max(pi.sub_entries, (int)(mp.begin[g + 1] - mp.begin[g]) + 1);
-            pi.depth = std::max(pi.depth, (int)mp.depth[g]);
-            pi.n_subs++;
-        }
-        size_t n_blob = mp.top.size();
-        for (const PassInfo &pi : passes) {
-            if (pi.sub_entries > kMaxSubSteps + 1) return HOP_PARTIAL;
-            n_blob += (size_t)pi.sub_entries * (size_t)pi.n_subs;
-        }
-        const size_t need = part_bytes * n_subs + n_blob * sizeof(DevEntry) + 512;
-        // without the right to allocate, a cut that does not fit beside the whole program (which the
-        // plain path then has to stage) is not made
-        if (ws_.is_static() && need + prog.size() * sizeof(DevEntry) + 256 > ws_.static_left()) return HOP_PARTIAL;
-        if (!ws_.reserve(need)) return ws_.error();
-        char *partials = (char *)ws_.scratch(part_bytes * n_subs);
-        if (!partials) return ws_.error();
-        // Kernels address sources and results by the object's byte offset, so a partial that holds
-        // only [b0, b1) is passed as base - b0. Passes run in stream order: pass h reads what
-        // passes < h wrote.
-        // All passes' records, then the top program, travel in one copy.
-        std::vector<DevEntry> blob;
-        blob.reserve(n_blob);
-        for (int pass = 0; pass < mp.n_passes; ++pass) {
-            PassInfo &pi = passes[(size_t)pass];
-            pi.records_at = blob.size();
-            for (size_t g = 0; g < n_subs; ++g) {
-                if (mp.height[g] != pass) continue;
-                const size_t rec_at = blob.size();
-                SubHeader h;
-                h.dst = (void *)((uintptr_t)partials + g * part_bytes - b0);
-                h.n_entries = (uint32_t)(mp.begin[g + 1] - mp.begin[g]);
-                h.reserved = 0;
-                DevEntry raw;
-                std::memcpy(&raw, &h, sizeof raw);
-                blob.push_back(raw);
-                for (int32_t t = mp.begin[g]; t < mp.begin[g + 1]; ++t)
-                    blob.push_back(resolve(mp.steps[(size_t)t], partials, part_bytes, b0));
-                mark_runs(blob.data() + rec_at + 1, blob.size() - rec_at - 1);
-                blob.resize(rec_at + (size_t)pi.sub_entries, DevEntry{nullptr, 0, 0});
-            }
-        }
-        const size_t top_at = blob.size();
-        for (const Entry &e : mp.top) blob.push_back(resolve(e, partials, part_bytes, b0));
-        mark_runs(blob.data() + top_at, blob.size() - top_at);
-        const DevEntry *dev = (const DevEntry *)ws_.stage_in_place(blob.data(), blob.size() * sizeof(DevEntry));
-        if (!dev) return ws_.error();
-        for (const PassInfo &pi : passes) {
-            if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.records_at, pi.sub_entries, pi.n_subs, b0,
-                                   b1) != hipSuccess)
-                return HOP_ERR_DEVICE;
-        }
-        hipError_t e = launch_reduce(stream_, dtype_, op_, mp.top_depth, blob.data() + top_at, dev + top_at,
-                                     (int)mp.top.size(), dsts_[0], b0, b1);
-        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
-    }
-
-    DevEntry resolve(const Entry &e, const char *partials, size_t part_bytes, size_t b0) const
-    {
-        DevEntry d;
-        d.src = e.obj >= 0 ? objs_[e.obj]
-                           : (const void *)((uintptr_t)partials + (size_t)(-e.obj - 1) * part_bytes - b0);
-        d.ctl = (uint32_t)e.level | ((uint32_t)e.set << 8) | ((uint32_t)e.n_fold << 16);
-        d.aux = 0;
-        return d;
-    }
-
-    Workspace ws_;
-    hipStream_t stream_;
-    std::vector<const void *> objs_;
-    std::vector<void *> dsts_;
-    Shape shape_;
-    int op_, dtype_, k_;
-    int64_t degree_;
-    std::vector<DevEntry> staging_;
-    const DevEntry *dev_prog_ = nullptr;
-    void *const *dev_extra_ = nullptr;
-    unsigned extra_residue_ = 0;                // address modulo 128 shared by (most of) the other destinations
-    uint64_t dev_version_ = 0;
-    int depth_ = 1;
-    int device_;
-    DevBuf *spill_buf_ = nullptr;
-    char *spill_ = nullptr;
-    size_t level_stride_ = 0;
-    int spill_levels_ = 0;
-    hipEvent_t busy_ev_ = nullptr;
-    bool busy_recorded_ = false, track_idle_ = false;
-    bool library_scratch_ = false;              // all scratch from the library's small static array (hop_reduce_noalloc)
-    DevBuf *kept_buf_ = nullptr;                // partial results kept for failure repair
-    char *kept_ = nullptr;
-    size_t kept_stride_ = 0;
-    int n_kept_ = 0;
-    std::vector<DevEntry> kept_steps_;
-    const DevEntry *kept_dev_ = nullptr;
-    uint64_t kept_version_ = 0;
-    int kept_depth_ = 1;
-};
-
-class RecordingBackend : public Backend {
-public:
-    int launch(const std::vector<Entry> &prog, uint64_t version, int64_t c0, int64_t c1, int t0, int t1, bool final,
-               int live_before, int live_after) override
-    {
-        if (version != version_) {
-            entry_begin_ = (int32_t)entries.size();
-            entries.insert(entries.end(), prog.begin(), prog.end());
-            version_ = version;
-        }
-        hop_plan_launch_t l;
-        l.chunk_begin = c0;
-        l.chunk_end = c1;
-        l.entry_begin = entry_begin_;
-        l.entry_end = (int32_t)(entry_begin_ + prog.size());
-        l.step_begin = t0;
-        l.step_end = t1;
-        l.final = final ? 1 : 0;
-        l.live_before = live_before;
-        l.live_after = live_after;
-        l.reserved = 0;
-        launches.push_back(l);
-        return HOP_OK;
-    }
-    std::vector<Entry> entries;
-    std::vector<hop_plan_launch_t> launches;
-
-private:
-    uint64_t version_ = 0;
-    int32_t entry_begin_ = 0;
-};
 
 // ----------------------------------------------------------------------------
 // argument checks shared by the entry points
