@@ -302,7 +302,7 @@ def streamed_chunks(hop, torch, w, objs, order, dst, interval_us, reps=5):
     first_k = [int(order[t]) for t in range(w.k)]
     res = {"interval_us": interval_us, "k": w.k, "chunks": C}
     # while the chunks stream in every participant can still fail, so by default each launch also keeps the
-    # partial results of the subtrees below the root (failure repair); "fused_no_keeping" switches that off
+    # partial results of subtrees (failure repair); "fused_no_keeping" switches that off
     for name in ("fused", "fused_no_keeping"):
         tails, totals, launches = [], [], 0
         for _ in range(reps + 1):

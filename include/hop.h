@@ -306,17 +306,20 @@ int hop_session_set_adaptive(hop_session_t *s, int on);
  * launch that produces output chunks while some participant in the tree is
  * still streaming - and so can still fail - also stores, in device scratch of
  * the library (4 bytes per element and subtree), the partial result of every
- * subtree below the root that has more than one node; after a failure (or a
- * late arrival into an empty position) the chunks already produced are
- * repaired by a launch that reads the kept partials of the untouched subtrees
- * and re-reads only the objects of the subtree that changed and those
- * directly below the root. Launches made when nobody can fail any more (every
- * launch of a call whose participants all complete) keep nothing and cost
- * nothing extra; launches that keep partials move 10-20 % more bytes and take
- * about as much longer. Nothing is kept either for launches over less than
- * 8 MiB per object, for chains and stars (no subtrees), for more than 16 subtrees, when
- * the kept arrays would exceed a quarter of what the launch reads or 16 GiB,
- * or in hop_reduce_noalloc. on = 0: never keep; a repair reads every object
+ * subtree with more than one node rooted at one level of the tree: one to
+ * four levels below the root, the level for which a repair reads least on
+ * average over who fails (level 1 for the wide trees, level 2 for a binary
+ * tree on 32). After a failure (or a late arrival into an empty position)
+ * the chunks already produced are repaired by a launch that reads the kept
+ * partials of the untouched subtrees and re-reads only the objects of the
+ * subtree that changed and those above the kept level. Launches made when
+ * nobody can fail any more (every launch of a call whose participants all
+ * complete) keep nothing and cost nothing extra; launches that keep partials
+ * move 10-20 % more bytes and take about as much longer. Nothing is kept
+ * either for launches over less than 8 MiB per object, for chains and stars
+ * (no subtrees), when every level has more than 16 subtrees or kept arrays
+ * beyond a quarter of what the launch reads or 16 GiB, or in
+ * hop_reduce_noalloc. on = 0: never keep; a repair reads every object
  * of the chunk again. Results are bit-identical either way. */
 int hop_session_set_retention(hop_session_t *s, int on);
 

@@ -929,7 +929,7 @@ size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes
             total += blocks(round256((size_t)k * sizeof(DevEntry)));
         }
         if ((policy & HOP_WS_FAILURES) && object_bytes > kRetainAboveBytes) {
-            const size_t runs = subtrees_below_root(k, d, kMaxKept).size();
+            const size_t runs = kept_subtrees(k, d, elem_bytes((int)dtype), kMaxKept).size();
             const size_t kept_stride = (((object_bytes + 15) / 16 + 63) / 64) * 1024 * (size_t)(4 / elem_bytes((int)dtype));
             if (runs > 0 && kept_stride <= ((size_t)16 << 30) / runs) total += kept_stride * runs;
         }

@@ -286,16 +286,17 @@ inline int full_tree_depth(int k, int64_t d)
     return compile_program(tr, occ, prog);
 }
 
-// The subtrees below the root that have more than one node, as ranges [slot_begin, slot_end) of
-// tree positions (in-order numbering makes a subtree a contiguous range of arrivals): the first
-// child's subtree, then the root, then the other children's subtrees, then the root's childless
-// children. These are the partial results kept for failure repair (section 3.5.2). More than
-// max_runs of them: none (too many arrays to keep).
+// The subtrees whose partial results are kept for failure repair (section 3.5.2: when a participant
+// fails only its ancestors clear their partial results): all subtrees of more than one node that are
+// rooted `depth` levels below the root, as ranges [slot_begin, slot_end) of tree positions (in-order
+// numbering makes a subtree a contiguous range of arrivals), in arrival order. What lies outside the
+// ranges - the nodes above that depth and the childless nodes at it - is re-read by every repair;
+// a failure inside a range re-reads that range. More than max_runs ranges: none.
 struct SlotRun { int slot_begin, slot_end; };
-inline std::vector<SlotRun> subtrees_below_root(int k, int64_t d, int max_runs)
+inline std::vector<SlotRun> subtrees_at_depth(int k, int64_t d, int depth, int max_runs)
 {
     std::vector<SlotRun> runs;
-    if (d < 2 || k < 3) return runs;
+    if (d < 2 || k < 3 || depth < 1) return runs;
     auto subtree_size = [&](int64_t j) {
         int64_t size = 0, first = j, last = j;
         while (first < k) {
@@ -306,17 +307,71 @@ inline std::vector<SlotRun> subtrees_below_root(int k, int64_t d, int max_runs)
         }
         return size;
     };
+    bool too_many = false;
     int64_t slot = 0;
-    for (int64_t c = 1; c <= d && c < k; ++c) {
-        const int64_t size = subtree_size(c);
-        if (size >= 2) {
-            if ((int)runs.size() == max_runs) { runs.clear(); return runs; }
-            runs.push_back({(int)slot, (int)(slot + size)});
+    // in-order walk of the levels above `depth`: first child's subtree, the node, the other children's
+    struct Walk {
+        const int k; const int64_t d; const int depth, max_runs;
+        std::vector<SlotRun> &runs; int64_t &slot; bool &too_many;
+        decltype(subtree_size) &size_of;
+        void visit(int64_t j, int level) {
+            if (too_many) return;
+            if (level == depth) {
+                const int64_t size = size_of(j);
+                if (size >= 2) {
+                    if ((int)runs.size() == max_runs) { too_many = true; return; }
+                    runs.push_back({(int)slot, (int)(slot + size)});
+                }
+                slot += size;
+                return;
+            }
+            const int64_t c1 = d * j + 1;
+            if (c1 < k) visit(c1, level + 1);
+            ++slot;                                      // the node itself
+            for (int64_t c = 2; c <= d && !too_many; ++c) {
+                const int64_t ch = d * j + c;
+                if (ch >= k) break;
+                visit(ch, level + 1);
+            }
         }
-        slot += size;
-        if (c == 1) ++slot;             // the root itself comes right after its first child's subtree
-    }
+    } w{k, d, depth, max_runs, runs, slot, too_many, subtree_size};
+    w.visit(0, 0);
+    if (too_many) runs.clear();
     return runs;
+}
+
+// The depth at which partial results are kept (1 to 4 levels below the root): the one for which a
+// repair reads least, averaged over which participant fails - a failure outside the kept subtrees
+// re-reads the other objects outside and every kept value (4 bytes), a failure inside one re-reads
+// the rest of that subtree, the objects outside and the other kept values - among the depths that
+// have subtrees, at most max_runs of them, and whose kept values stay below a quarter of what a launch
+// reads (k elements of elem_bytes). Level 1 - the subtrees below the root - if no depth qualifies.
+inline std::vector<SlotRun> kept_subtrees(int k, int64_t d, int elem_bytes, int max_runs)
+{
+    std::vector<SlotRun> best = subtrees_at_depth(k, d, 1, max_runs);
+    auto expected_repair_bytes = [&](const std::vector<SlotRun> &runs) {
+        int64_t covered = 0;
+        for (const SlotRun &r : runs) covered += r.slot_end - r.slot_begin;
+        const int64_t outside = k - covered, n_runs = (int64_t)runs.size();
+        double sum = (double)outside * (double)((outside - 1) * elem_bytes + n_runs * 4);
+        for (const SlotRun &r : runs) {
+            const int64_t size = r.slot_end - r.slot_begin;
+            sum += (double)size * (double)((outside + size - 1) * elem_bytes + (n_runs - 1) * 4);
+        }
+        return sum / k;
+    };
+    double best_cost = best.empty() ? 0.0 : expected_repair_bytes(best);
+    for (int depth = 2; depth <= 4; ++depth) {
+        std::vector<SlotRun> runs = subtrees_at_depth(k, d, depth, max_runs);
+        if (runs.empty()) break;
+        if ((int64_t)runs.size() * 16 > (int64_t)k * elem_bytes) continue;
+        const double cost = expected_repair_bytes(runs);
+        if (best.empty() || cost < best_cost) {
+            best.swap(runs);
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 // Where the scheduler sends work. launch() runs steps [t0, t1) of prog on output
@@ -359,10 +414,11 @@ public:
     // Retention of partial results across failures (section 3.5.2: when a participant fails, only
     // the partial results that contain its object are cleared). A launch that produces chunks
     // while some participant in the tree is still streaming - and so can still fail - also stores,
-    // per element, the partial result of every subtree below the root (in the accumulation type,
-    // exactly the value the root's fold consumes). If a participant then fails, the chunks already
-    // produced are repaired by a launch that reads the kept partials of the untouched subtrees and
-    // re-reads only the objects of the subtree that changed and those directly below the root.
+    // per element, the partial result of every subtree rooted at one level of the tree (the one
+    // kept_subtrees picks; in the accumulation type, exactly the value the parent's fold consumes).
+    // If a participant then fails, the chunks already produced are repaired by a launch that reads
+    // the kept partials of the untouched subtrees and re-reads only the objects of the subtree that
+    // changed and those above the kept level.
     // Launches made when nobody can fail any more (every bulk call) keep nothing and cost nothing.
     //   on          false: never keep anything (failures redo the produced chunks whole)
     //   min_chunks  launches over fewer chunks keep nothing (too small to be worth a second array)
@@ -683,7 +739,7 @@ private:
 
     void find_runs()
     {
-        runs_ = subtrees_below_root(k_, tree_.d, kMaxKept);
+        runs_ = kept_subtrees(k_, tree_.d, elem_bytes_, kMaxKept);
         if (runs_.empty()) return;
         run_of_slot_.assign((size_t)k_, -1);
         for (size_t r = 0; r < runs_.size(); ++r)
@@ -852,7 +908,7 @@ private:
     int eager_ = 0;
     bool adaptive_ = false;
     struct Kept { int64_t chunk_end; uint32_t gen; };
-    std::vector<SlotRun> runs_;                          // subtrees below the root, as ranges of positions
+    std::vector<SlotRun> runs_;                          // the subtrees whose partials are kept, as ranges of positions
     std::vector<int16_t> run_of_slot_;
     std::vector<uint32_t> run_ver_;                  // changes whenever an occupant inside the run changes
     std::vector<std::pair<int, int>> run_steps_;     // the run's steps in prog_: [first, second)

@@ -985,6 +985,8 @@ KEPT_CASES = [
     ("i32", "sum", 64, 60, 16, 16 << 20, 512 << 10, {5: 24, 59: 24, 61: 3}),    # two at once, and a waiting object that dies too
     ("bf16", "min", 24, 24, 3, (20 << 20) + 2, 4 << 20, {23: 2}),               # the last arrival; three levels of accumulators
     ("f32", "sum", 12, 12, 4, 24 << 20, 8 << 20, {5: 1}),                       # the root itself
+    ("f32", "sum", 32, 32, 2, (16 << 20) + 8, 4 << 20, {19: 2}),                # deep binary tree: subtrees two levels down are kept
+    ("i32", "max", 48, 48, 2, 24 << 20, 4 << 20, {2: 2, 40: 4}),                # the first repair keeps its subtree again, the second reads all four
 ]
 
 

@@ -339,6 +339,35 @@ def test_mid_stream_failure_repairs_from_kept_subtree_partials():
     assert info_s["chunks_redone"] == 10 * 31
 
 
+def test_deep_tree_keeps_partials_of_a_lower_level():
+    # binary tree over 32 fp32 objects of 64 MiB in 8 MiB chunks: the two subtrees below the root hold 16
+    # and 15 arrivals, so a repair from them would read half of the objects again. The four subtrees two
+    # levels down make the expected repair smaller.
+    n = k = 32
+    fm = np.full(n, -1, np.int64)
+    fm[19] = 3                               # the 20th arrival fails after 3 chunks
+    rc, info, launches, entries = hop.hop_plan_reduce(n, 64 << 20, k, "f32", 8 << 20, 2, None, fm)
+    assert rc == hop.HOP_PARTIAL and info["k_eff"] == 31 and info["stack_depth"] == 4
+    assert [(l[0], l[1]) for l in launches] == [(0, 3), (0, 3), (3, 8)]
+    first, repair, rest = (entries[l[2]:l[3]] for l in launches)
+    saves = [(first.index(e), e[4], e[5]) for e in first if len(e) > 4]
+    # four kept values, each stored from the accumulator level its subtree's result sits at
+    assert [s[1] for s in saves] == [0, 1, 2, 3] and len({s[0] for s in saves}) == 4
+    assert saves[-1][0] == 31 - 0 and saves[0][0] == 7          # in-order: the last subtree ends the program
+    # the repair reads three kept values and the surviving objects of the fourth subtree and outside
+    kept_read = [e[0] for e in repair if e[0] < 0]
+    assert len(kept_read) == 3 and 19 not in {e[0] for e in repair}
+    assert len(repair) < 16 and info["chunks_redone"] == 3 * (len(repair) - 3)
+    assert info["partial_stores"] == 3 * 4 and info["partial_loads"] == 3 * 3
+    # numerically: the launches applied in order (the repair reading what the first one kept) give the
+    # oracle's result over the 31 survivors, bit for bit; 4 elements stand for each 8 MiB chunk
+    rng = np.random.default_rng(5)
+    objs = [(rng.standard_normal(32) * 10.0 ** rng.integers(-3, 4)).astype(np.float32) for _ in range(n)]
+    got = interpret(objs, launches, entries, 32, 4, "sum")
+    orc, want, _, _ = oracle.reduce(objs, k, oracle.SUM, oracle.F32, 4, 2, None, fm)
+    assert orc == rc and np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
 def test_replacement_from_waiting_objects():
     # 6 of 10, second arrival fails after 3 chunks of 8: the 7th arrival takes its place
     n, k, C = 10, 6, 8
