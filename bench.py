@@ -39,7 +39,9 @@ PROFILED_TRAFFIC = {
                      "tiles, cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 "
                      "destinations); launches that keep or read partial results: one step at a time, 4|2|1 vectors/lane, "
                      "pieces 64 KiB apart from 2048 tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators "
-                     "indexed like the elements, nontemporal"),
+                     "indexed like the elements, nontemporal; programs of 48 steps or more over at most 64 KiB: one "
+                     "launch, 256 lanes per 64-byte column, chains of at most 23 items folded by teams of 4 lanes with all "
+                     "their loads in flight, values in LDS"),
     "workloads": {
         "cfg2_async_sgd": {"bytes_per_call": 872306923, "profile": "profiles/hbm_traffic_all_workloads.md"},
         "cfg3_rl_allreduce": {"bytes_per_call": 2163397681, "profile": "profiles/hbm_traffic_all_workloads.md"},

@@ -432,6 +432,29 @@ int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int want_step
                    hop_plan_entry_t *sub_entries, int sub_capacity, int *n_sub_entries,
                    int32_t *sub_begin, int32_t *sub_pass, int sub_table_capacity, int *n_subs, int *n_passes);
 
+/*
+ * Host-only view of the one-launch form of a long program over small objects:
+ * the program as chains. A chain is a left fold, item 0 (op) item 1 (op) ...
+ * in that order, of objects (item >= 0) and of the values of other chains
+ * (item = -(1 + g)); the last chain's value is the program's result. Every
+ * accumulator level of the program is one such fold (the steps that combine
+ * into it and the values folded down into it, in program order - the
+ * arithmetic of section 3.4.2's tree, unchanged). A chain is cut where it
+ * first needs a value that is ready later than all it holds so far, if it
+ * holds at least min_cut items by then: the front becomes a chain of its own.
+ * A chain that reaches max_items (>= 2) items is cut the same way.
+ * chain_pass[g] = 0 if chain g reads objects only, else 1 + the largest pass
+ * among the chains it reads; the chains of one pass are independent, and one
+ * workgroup evaluates them side by side, their values held in LDS.
+ * chain_begin receives n_chains + 1 offsets into items (table_capacity counts
+ * entries of chain_begin; chain_pass needs one less). Counts are always
+ * returned, arrays filled up to capacity. HOP_OK, or HOP_PARTIAL if the
+ * program has no such form (one object, or it reads kept partial results).
+ */
+int hop_plan_chains(const hop_plan_entry_t *entries, int n_entries, int min_cut, int max_items,
+                    int32_t *items, int item_capacity, int *n_items,
+                    int32_t *chain_begin, int32_t *chain_pass, int table_capacity, int *n_chains, int *n_passes);
+
 /* node_of_slot[t] (k entries) = level-order index of the tree node that the
  * t-th arrival takes in the complete d-ary tree on k nodes. */
 int hop_plan_slots(int k, int tree_degree, int32_t *node_of_slot);

@@ -31,7 +31,7 @@ DTYPES = {"f32": HOP_F32, "bf16": HOP_BF16, "i32": HOP_I32,
 EXPORTS = ["hop_reduce", "hop_reduce_noalloc", "hop_noalloc_scratch_bytes", "hop_broadcast", "hop_allreduce", "hop_bcast_begin", "hop_bcast_source_ready",
            "hop_bcast_join", "hop_bcast_fail", "hop_bcast_step", "hop_bcast_sender", "hop_bcast_finish", "hop_session_begin", "hop_session_ready", "hop_session_ready_after",
            "hop_session_fail", "hop_session_finish", "hop_session_set_eager", "hop_session_set_adaptive", "hop_session_set_retention", "hop_session_set_workspace", "hop_session_chunks_final",
-           "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_slots",
+           "hop_plan_session_begin", "hop_plan_session_finish", "hop_plan_reduce", "hop_plan_split", "hop_plan_chains", "hop_plan_slots",
            "hop_pick_degree", "hop_calibrate", "hop_workspace_bytes", "hop_shutdown", "hop_strerror", "hop_kernel_config"]
 
 
@@ -135,6 +135,9 @@ def lib() -> ctypes.CDLL:
                                      ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
                                      i32p, i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int),
                                      ctypes.POINTER(ctypes.c_int)]
+        L.hop_plan_chains.argtypes = [ctypes.POINTER(PlanEntry), ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p, ctypes.c_int,
+                                      ctypes.POINTER(ctypes.c_int), i32p, i32p, ctypes.c_int,
+                                      ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.hop_plan_slots.argtypes = [ctypes.c_int, ctypes.c_int, i32p]
         L.hop_pick_degree.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
         L.hop_calibrate.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -463,6 +466,25 @@ def hop_plan_split(entries, want_steps, min_run, max_run):
     tops = [as_t(top, i) for i in range(nt.value)]
     subs = [(int(passes[s]), [as_t(sub, i) for i in range(begins[s], begins[s + 1])]) for s in range(nsub.value)]
     return rc, tops, subs
+
+
+def hop_plan_chains(entries, min_cut=4, max_items=23):
+    """(status, [(pass, [item, ...]), ...]) for a program of (obj, level, set, n_fold[, save, save_level]) tuples:
+    item >= 0 is an object, item = -(1 + g) the value of chain g; the last chain's value is the result."""
+    n = len(entries)
+    E = (PlanEntry * max(n, 1))(*[PlanEntry(e[0], e[1], e[2], e[3], e[4] if len(e) > 4 else -1, e[5] if len(e) > 4 else 0)
+                                  for e in entries])
+    items = np.zeros(2 * n + 2, np.int32)
+    begins = np.zeros(n + 2, np.int32)
+    passes = np.zeros(n + 2, np.int32)
+    ni, nc, npass = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    i32 = ctypes.POINTER(ctypes.c_int32)
+    rc = lib().hop_plan_chains(E, n, int(min_cut), int(max_items), items.ctypes.data_as(i32), 2 * n + 2, ctypes.byref(ni),
+                               begins.ctypes.data_as(i32), passes.ctypes.data_as(i32), n + 2, ctypes.byref(nc),
+                               ctypes.byref(npass))
+    chains = [(int(passes[g]), [int(x) for x in items[begins[g]:begins[g + 1]]]) for g in range(nc.value)]
+    assert rc != HOP_OK or (ni.value <= 2 * n + 2 and npass.value == 1 + max(p for p, _ in chains))
+    return rc, chains
 
 
 def hop_plan_slots(k, tree_degree):

@@ -864,6 +864,31 @@ int hop_plan_split(const hop_plan_entry_t *entries, int n_entries, int want_step
     }
 }
 
+int hop_plan_chains(const hop_plan_entry_t *entries, int n_entries, int min_cut, int max_items,
+                    int32_t *items, int item_capacity, int *n_items,
+                    int32_t *chain_begin, int32_t *chain_pass, int table_capacity, int *n_chains, int *n_passes)
+{
+    if (!entries || n_entries < 0 || min_cut < 1 || max_items < 2) return HOP_ERR_INVALID;
+    try {
+        std::vector<Entry> prog(n_entries);
+        for (int i = 0; i < n_entries; ++i) {
+            prog[i] = {entries[i].obj, entries[i].level, entries[i].set, entries[i].n_fold};
+            prog[i].save = entries[i].save;
+        }
+        ChainPlan cp;
+        const bool ok = plan_chains(prog, min_cut, max_items, cp);
+        if (n_items) *n_items = (int)cp.items.size();
+        if (n_chains) *n_chains = (int)cp.n_chains();
+        if (n_passes) *n_passes = cp.n_passes;
+        for (int i = 0; items && i < item_capacity && i < (int)cp.items.size(); ++i) items[i] = cp.items[(size_t)i];
+        for (int i = 0; chain_begin && i < table_capacity && i < (int)cp.begin.size(); ++i) chain_begin[i] = cp.begin[(size_t)i];
+        for (int i = 0; chain_pass && i < table_capacity && i < (int)cp.n_chains(); ++i) chain_pass[i] = cp.pass[(size_t)i];
+        return ok ? HOP_OK : HOP_PARTIAL;
+    } catch (const std::bad_alloc &) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
 int hop_plan_slots(int k, int tree_degree, int32_t *node_of_slot)
 {
     if (k < 1 || tree_degree < 1 || !node_of_slot) return HOP_ERR_INVALID;

@@ -457,6 +457,155 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
     }
 }
 
+// ----------------------------------------------------------------------------
+// a long program over a narrow column of the objects, as chains (ChainArgs)
+// ----------------------------------------------------------------------------
+
+// The value x with x (op) identity == x for every x, bit for bit: -0.0 for a floating-point sum
+// (x + -0.0 is x also for x = +0.0), the infinities for min and max (combine keeps its left operand
+// unless the right one is strictly better, so a NaN on the left stays too), 0 and the extreme
+// integers for int32.
+template <int DT, int OP> __device__ __forceinline__ typename Traits<DT>::acc_t chain_identity()
+{
+    using A = typename Traits<DT>::acc_t;
+    if (DT == HOP_I32) return OP == HOP_SUM ? A(0) : OP == HOP_MIN ? A(INT32_MAX) : A(INT32_MIN);
+    return __builtin_bit_cast(A, OP == HOP_SUM ? 0x80000000u : OP == HOP_MIN ? 0x7f800000u : 0xff800000u);
+}
+
+// One team of kChainLanes lanes per chain, one 16-byte vector (TAIL: one element) per lane. A lane
+// loads its chain's whole record (one trip to the table), then everything the items name - vectors
+// of the objects from memory, values of other chains from LDS - all in flight together, then folds
+// in item order. The chains of the teams of one wave differ, so all of this is per-lane data, and
+// what counts is how few instructions an item takes (one wave per SIMD: nothing hides them): a
+// record is padded to its full length with the identity value, so neither the loads nor the folds
+// look at the item count. For 32-bit elements an object's vector and a chain's value are both 16
+// bytes per lane (TAIL: 4) and are fetched by the same flat load, whose address is the item plus
+// either the lane's byte offset into the object or the lane's place in the LDS window.
+// A value in LDS: W accumulators per lane, the value at byte offset b of the LDS array at
+// [b + lane * W * 4].
+template <int DT, int OP, bool TAIL>
+__device__ __forceinline__ void chains_body(const ChainArgs &a, typename Traits<DT>::acc_t *lds, const size_t off, const bool live)
+{
+    using T = Traits<DT>;
+    using A = typename T::acc_t;
+    constexpr int W = TAIL ? 1 : T::W;
+    constexpr int R = kChainMaxItems;
+    constexpr bool kAlike = T::ES == 4;
+    static_assert(kChainRecordWords % 8 == 0 && R + 1 == kChainRecordWords, "records are read as 16-byte pairs of words, held eight at a time");
+    const int lane = (int)threadIdx.x % kChainLanes, team = (int)threadIdx.x / kChainLanes;
+    char *const mine = (char *)lds + (size_t)lane * T::W * 4;           // this lane's part of the value at offset 0
+    const uint64_t mine_flat = (uint64_t)(uintptr_t)(const void *)mine;
+    // the identity value sits behind the chains' values; every team writes the same bytes
+    {
+        A *v = (A *)(mine + a.identity_at);
+#pragma unroll
+        for (int w = 0; w < T::W; ++w) v[w] = chain_identity<DT, OP>();
+    }
+    __syncthreads();
+    for (int p = 0; p < a.base.n_entries; ++p) {
+        for (uint32_t c = a.pass_begin[p] + (uint32_t)team; c < a.pass_begin[p + 1]; c += kChainTeams) {
+            const uint4 *const rec = (const uint4 *)a.base.prog + (size_t)c * (kChainRecordWords / 2);
+            uint64_t word[kChainRecordWords];
+#pragma unroll
+            for (int j = 0; j < kChainRecordWords / 2; ++j) {
+                const uint4 q = rec[j];
+                word[2 * j] = ((uint64_t)q.y << 32) | q.x;
+                word[2 * j + 1] = ((uint64_t)q.w << 32) | q.z;
+            }
+            // The whole record has arrived before the first item is fetched: an empty statement that formally
+            // rewrites every word. (Flat loads complete out of order with other loads, so with the record
+            // still on its way the compiler would wait for everything in flight before each use of a word.)
+#pragma unroll
+            for (int j = 0; j < kChainRecordWords; j += 8)
+                asm volatile("" : "+v"(word[j]), "+v"(word[j + 1]), "+v"(word[j + 2]), "+v"(word[j + 3]), "+v"(word[j + 4]),
+                             "+v"(word[j + 5]), "+v"(word[j + 6]), "+v"(word[j + 7]) : : "memory");
+            const uint32_t out = (uint32_t)word[0];
+            A acc[W];
+            if (kAlike) {
+                u32x4 raw[R + 1];
+#pragma unroll
+                for (int u = 0; u < R; ++u) {
+                    const uint64_t e = word[1 + u];
+                    const uint64_t at = e + ((uint32_t)(e >> 32) == 0 ? mine_flat : (uint64_t)off);
+                    if (TAIL) raw[u].x = *(const uint32_t *)(uintptr_t)at;
+                    else raw[u] = *(const u32x4 *)(uintptr_t)at;
+                }
+                raw[R] = raw[R - 1];
+                // Every load is issued before the first fold, and the folds start when all have arrived: an
+                // empty statement that formally rewrites every loaded value. (The compiler would otherwise
+                // interleave loads and folds to save registers, and the chain would wait for memory once
+                // per few items instead of once.)
+#pragma unroll
+                for (int u = 0; u < R + 1; u += 8)
+                    asm volatile("" : "+v"(raw[u]), "+v"(raw[u + 1]), "+v"(raw[u + 2]), "+v"(raw[u + 3]), "+v"(raw[u + 4]),
+                                 "+v"(raw[u + 5]), "+v"(raw[u + 6]), "+v"(raw[u + 7]) : : "memory");
+#pragma unroll
+                for (int u = 0; u < R; ++u) {
+                    const uint32_t r[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+#pragma unroll
+                    for (int w = 0; w < W; ++w) {
+                        const A x = __builtin_bit_cast(A, r[w]);
+                        acc[w] = u == 0 ? x : combine<OP>(acc[w], x);
+                    }
+                }
+            } else {
+                // bf16: an object's vector is 16 bytes of 8 elements, a value 32 bytes of 8 accumulators
+                A val[R][W];
+                uint4 raw[R];
+#pragma unroll
+                for (int u = 0; u < R; ++u) {
+                    const uint64_t e = word[1 + u];
+                    if ((uint32_t)(e >> 32) == 0) {
+                        const A *v = (const A *)(mine + (uint32_t)e);
+#pragma unroll
+                        for (int w = 0; w < W; ++w) val[u][w] = v[w];
+                    } else if (TAIL) {
+                        val[u][0] = load_elem<DT>((const void *)(uintptr_t)e, off);
+                    } else {
+                        raw[u] = ld16((const void *)(uintptr_t)e, off);
+                    }
+                }
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int u = 0; u < R; ++u) {
+                    if (!TAIL && (uint32_t)(word[1 + u] >> 32) != 0) decode<DT>(raw[u], val[u]);
+#pragma unroll
+                    for (int w = 0; w < W; ++w) acc[w] = u == 0 ? val[0][w] : combine<OP>(acc[w], val[u][w]);
+                }
+            }
+            if (out != kChainFinal) {
+                A *v = (A *)(mine + out);
+#pragma unroll
+                for (int w = 0; w < W; ++w) v[w] = acc[w];
+            } else if (live) {
+                if (TAIL) store_elem<DT>(a.base.dst, off, acc[0]);
+                else st16(a.base.dst, off, encode<DT>(acc));
+            }
+        }
+        __syncthreads();       // the next pass reads what this one wrote; every lane comes by here once per pass
+    }
+}
+
+template <int DT, int OP>
+__global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains(const ChainArgs a)
+{
+    using T = Traits<DT>;
+    extern __shared__ __align__(16) unsigned char chain_values[];
+    typename T::acc_t *const lds = (typename T::acc_t *)chain_values;
+    const size_t n_cols = (a.base.n_vec + kChainLanes - 1) / kChainLanes;
+    const size_t lane = threadIdx.x % kChainLanes;
+    if (blockIdx.x < n_cols) {
+        const size_t v = (size_t)blockIdx.x * kChainLanes + lane;
+        const bool live = v < a.base.n_vec;
+        chains_body<DT, OP, false>(a, lds, a.base.byte_begin + (live ? v : a.base.n_vec - 1) * 16, live);
+    } else {
+        // the workgroups after the last column: the elements behind the last full vector, one per lane
+        const size_t i = (blockIdx.x - n_cols) * kChainLanes + lane;
+        const bool live = i < (size_t)a.base.n_tail;
+        chains_body<DT, OP, true>(a, lds, a.base.byte_begin + a.base.n_vec * 16 + (live ? i : 0) * T::ES, live);
+    }
+}
+
 // Layout of a kept partial result: one accumulator-typed value (4 bytes) per element of the
 // object. The accumulators of 64 consecutive source vectors (the vectors the lanes of a wave hold)
 // form a block of Q * 1 KiB, Q = W / 4: first the accumulators 0..3 of all 64 vectors, then 4..7 of

@@ -58,6 +58,30 @@ struct ReduceArgsInline {
 };
 static_assert(sizeof(ReduceArgsInline) <= 4096, "kernel arguments are limited to 4 KiB");
 
+// A long program over a short byte range, evaluated by one launch as chains (see plan_chains in
+// hop_plan.hpp): a workgroup of kChainThreads lanes owns a column of kChainLanes 16-byte vectors
+// of the objects; its lanes form kChainTeams teams of kChainLanes, each team folds one chain at a
+// time, and the chains' values live in LDS between the passes (kChainLanes x W accumulators per
+// value that is still needed; W = accumulators per vector). The table in device memory holds one
+// record of kChainRecordWords 8-byte words per chain, in pass order: word 0 = where the value goes,
+// as a byte offset into the workgroup's LDS (bits 0..31; kChainFinal: it is the result and goes to
+// dst); words 1..kChainMaxItems = the items, each the address of an object (never below 2^32) or
+// the LDS byte offset of a chain's value, and behind the last item the offset of the identity value
+// (identity_at) up to the end of the record, so that loads and folds need not look at a count.
+constexpr int kChainLanes = 4;
+constexpr int kChainTeams = 64;
+constexpr int kChainThreads = kChainLanes * kChainTeams;
+constexpr int kChainMaxItems = 23;
+constexpr int kChainRecordWords = kChainMaxItems + 1;
+constexpr int kMaxChainPasses = 24;
+constexpr uint32_t kChainFinal = 0xffffffffu;
+constexpr size_t kChainLdsBytes = 64 * 1024;
+struct ChainArgs {
+    ReduceArgs base;           // prog = the table, n_entries = number of passes, dst / byte_begin / n_vec / n_tail as usual
+    uint32_t identity_at;      // LDS byte offset of the identity value (behind the chains' values)
+    uint32_t pass_begin[kMaxChainPasses + 1];      // pass p evaluates the chains [pass_begin[p], pass_begin[p + 1])
+};
+
 struct CopyArgs {
     const void *src;
     void *dst0;                // the only destination when dsts is null
@@ -86,12 +110,12 @@ int elem_bytes(int dtype);
 
 // Recording of kernel launches, for calls that will be repeated with the same arguments: while a
 // recorder is installed on the calling thread, every whole-program reduce launch (launch_reduce,
-// launch_reduce_subs) is also written down - kernel, grid, LDS, the argument block - and can be
+// launch_reduce_subs, launch_reduce_chains) is also written down - kernel, grid, workgroup size, LDS, the argument block - and can be
 // enqueued again later with replay_launch, with another result buffer if the launch wrote the
 // caller's result. Launches of any other kind mark the recording unusable.
 struct RecordedLaunch {
     const void *kernel;
-    unsigned grid_x, grid_y, lds;
+    unsigned grid_x, grid_y, lds, threads;
     bool writes_result;                 // the argument block's ReduceArgs::dst is the caller's destination
     std::vector<unsigned char> args;
 };
@@ -135,6 +159,17 @@ hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, 
 // sub-program covers the same byte range and needs at most `depth` accumulator levels.
 hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
                               int sub_entries, int n_subs, size_t byte_begin, size_t byte_end);
+
+// The program as chains in one launch: dev_table as described at ChainArgs (n_chains records, written for
+// values of chain_value_bytes(dtype) bytes each), n_slots = values alive at most at one time; the identity
+// value takes the place behind them. hipErrorInvalidValue if that is more LDS than a workgroup gets.
+hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uint64_t *dev_table, int n_chains,
+                                int n_slots, const uint32_t *pass_begin, int n_passes, void *dst,
+                                size_t byte_begin, size_t byte_end);
+// LDS bytes of one chain's value, and the number of values a launch_reduce_chains may keep alive at
+// one time, for this element type.
+size_t chain_value_bytes(int dtype);
+int chain_slots_max(int dtype);
 
 // Copy [byte_begin, byte_end) of src into the same range of n_dst destinations: dst0 if n_dst == 1
 // and dst0 is given; else the table host_dsts (host memory) if it has at most kInlineDsts entries

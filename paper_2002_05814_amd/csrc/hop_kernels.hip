@@ -50,7 +50,9 @@ const char *kernel_config()
            "to several: one 4 KiB tile and one destination per workgroup, destination-major within spans of 4096 tiles, "
            "cached loads, nontemporal stores, 12 waves per CU (no limit for >= 128 MiB to < 8 destinations); "
            "launches that keep or read partial results: one step at a time, 4|2|1 vectors/lane, pieces 64 KiB apart from 2048 "
-           "tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators indexed like the elements, nontemporal";
+           "tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators indexed like the elements, nontemporal; "
+           "programs of 48 steps or more over at most 64 KiB: one launch, 256 lanes per 64-byte column, chains of at most 23 items "
+           "folded by teams of 4 lanes with all their loads in flight, values in LDS";
 }
 
 static thread_local LaunchRecorder *tl_recorder = nullptr;
@@ -64,7 +66,8 @@ static void not_recordable()
 
 // Launch of a reduce kernel whose only parameter is its argument block (ReduceArgs first in it).
 template <class Args>
-static hipError_t enqueue(void (*kernel)(Args), dim3 grid, unsigned lds, hipStream_t stream, const Args &a, bool writes_result)
+static hipError_t enqueue(void (*kernel)(Args), dim3 grid, unsigned lds, hipStream_t stream, const Args &a, bool writes_result,
+                          unsigned threads = kThreads)
 {
     if (tl_recorder) {
         RecordedLaunch r;
@@ -72,11 +75,12 @@ static hipError_t enqueue(void (*kernel)(Args), dim3 grid, unsigned lds, hipStre
         r.grid_x = grid.x;
         r.grid_y = grid.y;
         r.lds = lds;
+        r.threads = threads;
         r.writes_result = writes_result;
         r.args.assign((const unsigned char *)&a, (const unsigned char *)&a + sizeof a);
         tl_recorder->launches.push_back(std::move(r));
     }
-    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, stream, a);
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, stream, a);
     return hipGetLastError();
 }
 
@@ -84,12 +88,13 @@ hipError_t replay_launch(const RecordedLaunch &l, hipStream_t stream, void *dst)
 {
     // the argument block is copied so that the result pointer can be replaced (and because another
     // thread may replay the same recording)
+    static_assert(sizeof(ChainArgs) <= sizeof(ReduceArgsInline), "the largest argument block");
     alignas(16) unsigned char block[sizeof(ReduceArgsInline)];
     if (l.args.size() > sizeof block) return hipErrorInvalidValue;
     std::memcpy(block, l.args.data(), l.args.size());
     if (l.writes_result) ((ReduceArgs *)block)->dst = dst;
     void *params[1] = {block};
-    return hipLaunchKernel(l.kernel, dim3(l.grid_x, l.grid_y), dim3(kThreads), params, l.lds, stream);
+    return hipLaunchKernel(l.kernel, dim3(l.grid_x, l.grid_y), dim3(l.threads), params, l.lds, stream);
 }
 
 static Launcher pick(int dtype, int op, int depth)
@@ -280,6 +285,34 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
     a.sub_entries = sub_entries;
     const unsigned grid = grid_for(a.n_vec, (size_t)kThreads);
     return enqueue(l.dev_small, dim3(grid, (unsigned)n_subs), 0, stream, a, false);
+}
+
+size_t chain_value_bytes(int dtype) { return (size_t)kChainLanes * (dtype == HOP_BF16 ? 8 : 4) * 4; }
+
+int chain_slots_max(int dtype) { return (int)(kChainLdsBytes / chain_value_bytes(dtype)) - 1; }     // one place is the identity's
+
+hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uint64_t *dev_table, int n_chains,
+                                int n_slots, const uint32_t *pass_begin, int n_passes, void *dst,
+                                size_t byte_begin, size_t byte_end)
+{
+    if (byte_end <= byte_begin) return hipSuccess;
+    if (!dev_table || !pass_begin || n_chains < 1 || n_passes < 1 || n_passes > kMaxChainPasses || n_slots < 0 ||
+        n_slots > chain_slots_max(dtype) || pass_begin[0] != 0 || pass_begin[n_passes] != (uint32_t)n_chains)
+        return hipErrorInvalidValue;
+    const Launcher l = pick(dtype, op, 1);
+    ChainArgs a;
+    a.base.prog = (const DevEntry *)dev_table;
+    a.base.n_entries = n_passes;
+    a.base.dst = dst;
+    a.base.sub_entries = 0;
+    fill_range(a.base, dtype, byte_begin, byte_end);
+    a.identity_at = (uint32_t)((size_t)n_slots * chain_value_bytes(dtype));
+    for (int p = 0; p <= kMaxChainPasses; ++p) a.pass_begin[p] = pass_begin[p < n_passes ? p : n_passes];
+    const size_t n_cols = (a.base.n_vec + kChainLanes - 1) / kChainLanes;
+    const size_t grid = n_cols + ((size_t)a.base.n_tail + kChainLanes - 1) / kChainLanes;
+    if (grid > kMaxGrid) return hipErrorInvalidValue;       // one column per workgroup: the kernel does not loop
+    const unsigned lds = (unsigned)(((size_t)n_slots + 1) * chain_value_bytes(dtype));
+    return enqueue(l.chains, dim3((unsigned)grid), lds, stream, a, true, kChainThreads);
 }
 
 // One destination: every vector is read once (non-temporal) and stored once; 8 contiguous

@@ -78,6 +78,7 @@ struct Launcher {
     void (*seg)(ReduceArgs);
     void (*kept)(ReduceArgs);
     void (*kept_inl)(ReduceArgsInline);
+    void (*chains)(ChainArgs);
     int vpt;
 };
 

@@ -276,6 +276,84 @@ inline bool plan_passes(const std::vector<Entry> &prog, size_t want_steps, int m
     return true;
 }
 
+// A program as chains: the form in which ONE workgroup can evaluate a long program over a narrow
+// column of the objects with many lanes side by side. A chain is a left fold, value = item 0 (op)
+// item 1 (op) ... in that order, of objects and of the values of other chains; the value of the
+// last chain is the program's result. Every accumulator level of the program is such a fold: the
+// steps that combine into it, and, where a fold of the level above lands in it, that level's value.
+// A chain is cut where it first needs a value that is ready later than everything it holds so far
+// (if it holds at least min_cut items by then): the front part becomes a chain of its own, evaluated
+// earlier, and the rest starts from its value - the same arithmetic, since a chain's value is kept
+// in the accumulation type. A chain that reaches max_items items is cut the same way (a long fold
+// has no independent parts: its pieces follow each other, one pass each). pass[g] = 0 if chain g reads only objects, else 1 + the largest pass of
+// the chains it reads: all chains of a pass are independent of each other.
+struct ChainPlan {
+    std::vector<int32_t> items;                  // obj >= 0: object; -(1 + g): value of chain g
+    std::vector<int32_t> begin;                  // chain g = items[begin[g], begin[g + 1])
+    std::vector<int32_t> pass;
+    int n_passes = 0;
+    int64_t critical_steps = 0;                  // items on the longest path: sum over passes of the longest chain
+    size_t n_chains() const { return pass.size(); }
+};
+
+// Returns false if the program is malformed, reads kept partial results, or is a single object.
+inline bool plan_chains(const std::vector<Entry> &prog, int min_cut, int max_items, ChainPlan &cp)
+{
+    cp = ChainPlan();
+    if (max_items < 2) return false;
+    cp.begin.push_back(0);
+    struct Open {
+        std::vector<int32_t> items;
+        int avail = 0;                           // pass before which nothing of `items` is missing
+    };
+    std::vector<Open> open(256);
+    auto avail_of = [&](int32_t item) { return item >= 0 ? 0 : cp.pass[(size_t)(-item - 1)] + 1; };
+    auto emit = [&](Open &o) {
+        const int32_t g = (int32_t)cp.pass.size();
+        cp.items.insert(cp.items.end(), o.items.begin(), o.items.end());
+        cp.begin.push_back((int32_t)cp.items.size());
+        cp.pass.push_back(o.avail);
+        return -(1 + g);
+    };
+    auto add = [&](Open &o, int32_t item) {
+        const int a = avail_of(item);
+        if ((a > o.avail && (int)o.items.size() >= std::max(min_cut, 2)) || (int)o.items.size() >= max_items) {
+            const int32_t front = emit(o);
+            o.items.assign(1, front);
+            o.avail = avail_of(front);
+        }
+        o.items.push_back(item);
+        o.avail = std::max(o.avail, a);
+    };
+    auto close = [&](Open &o) {                  // the level's value as one item
+        const int32_t item = o.items.size() == 1 ? o.items[0] : emit(o);
+        o.items.clear();
+        o.avail = 0;
+        return item;
+    };
+    for (const Entry &e : prog) {
+        if (e.obj < 0 || e.save >= 0 || e.n_fold > e.level) return false;
+        Open &o = open[e.level];
+        if (e.set != o.items.empty()) return false;      // a level starts with set and only then
+        add(o, e.obj);
+        for (int f = 0; f < (int)e.n_fold; ++f) {
+            const int l = (int)e.level - f;
+            if (open[(size_t)l].items.empty() || open[(size_t)l - 1].items.empty()) return false;
+            add(open[(size_t)l - 1], close(open[(size_t)l]));
+        }
+    }
+    for (size_t l = 1; l < open.size(); ++l)
+        if (!open[l].items.empty()) return false;
+    if (open[0].items.size() < 2) return false;
+    emit(open[0]);
+    cp.n_passes = cp.pass.back() + 1;
+    std::vector<int32_t> longest((size_t)cp.n_passes, 0);
+    for (size_t g = 0; g < cp.n_chains(); ++g)
+        longest[(size_t)cp.pass[g]] = std::max(longest[(size_t)cp.pass[g]], cp.begin[g + 1] - cp.begin[g]);
+    for (int32_t len : longest) cp.critical_steps += len;
+    return true;
+}
+
 // Accumulator levels a tree needs when every position is taken (holes only lower it).
 inline int full_tree_depth(int k, int64_t d)
 {

@@ -194,7 +194,7 @@ int main(int argc, char **argv)
     const int rounds = argc > 1 ? std::atoi(argv[1]) : 3000;
     std::mt19937_64 rng(12345);
     auto rnd = [&](int lo, int hi) { return lo + (int)(rng() % (uint64_t)(hi - lo + 1)); };
-    long total_launches = 0, total_kept_reads = 0, total_kept_writes = 0;
+    long total_launches = 0, total_kept_reads = 0, total_kept_writes = 0, total_chains = 0;
     for (int r = 0; r < rounds; ++r) {
         const int n = rnd(1, 40), k = rnd(1, n);
         const int degs[] = {1, 2, 3, 4, 8, 16, n + 1};
@@ -280,9 +280,34 @@ int main(int argc, char **argv)
         check_marks(prog);
         MultiPlan mp;
         { const int lo = rnd(1, 6); plan_passes(prog, (size_t)rnd(1, 40), lo, lo + rnd(0, 30), mp); }
+        // the same program as chains: the last chain's expression, with every chain's value written out, is
+        // the program's, parenthesis for parenthesis; chains read only values of earlier passes
+        {
+            ChainPlan cp;
+            const int max_items = 2 + (int)(prog.size() % 29);
+            const bool ok = plan_chains(prog, 1 + (int)(prog.size() % 8), max_items, cp);
+            if (ok != (prog.size() >= 2)) { std::printf("plan_chains: %d for %zu steps\n", (int)ok, prog.size()); std::abort(); }
+            if (ok) {
+                std::vector<std::string> value(cp.n_chains());
+                for (size_t g = 0; g < cp.n_chains(); ++g) {
+                    std::string acc;
+                    for (int32_t t = cp.begin[g]; t < cp.begin[g + 1]; ++t) {
+                        const int32_t item = cp.items[(size_t)t];
+                        if (item < 0 && ((size_t)(-item - 1) >= g || cp.pass[(size_t)(-item - 1)] >= cp.pass[g])) { std::printf("chain reads ahead\n"); std::abort(); }
+                        const std::string x = item >= 0 ? "o" + std::to_string(item) : value[(size_t)(-item - 1)];
+                        acc = t == cp.begin[g] ? x : "(" + acc + "+" + x + ")";
+                    }
+                    if (cp.begin[g + 1] - cp.begin[g] > max_items || cp.begin[g + 1] - cp.begin[g] < 2) { std::printf("chain length\n"); std::abort(); }
+                    value[g] = acc;
+                }
+                const std::string want = sym_eval(prog, 0, (int)prog.size(), {}, nullptr, nullptr, nullptr);
+                if (value.back() != want) { std::printf("chains give %s, the program %s\n", value.back().c_str(), want.c_str()); std::abort(); }
+                total_chains += (long)cp.n_chains();
+            }
+        }
         fuzz_bcast(rng);
     }
     if (rounds >= 1000 && (total_kept_reads < 50 || total_kept_writes < 200)) { std::printf("keeping was hardly exercised: %ld reads, %ld writes\n", total_kept_reads, total_kept_writes); return 1; }
-    std::printf("ok %d sessions, %ld launches, %ld partials kept, %ld reused\n", rounds, total_launches, total_kept_writes, total_kept_reads);
+    std::printf("ok %d sessions, %ld launches, %ld partials kept, %ld reused, %ld chains\n", rounds, total_launches, total_kept_writes, total_kept_reads, total_chains);
     return 0;
 }

@@ -162,6 +162,117 @@ def test_many_small_objects_take_the_multi_pass_path(dtype):
         run_both(w, "sum")
 
 
+def takes_the_one_launch_path(w, order=None, fm=None):
+    """Whether the library evaluates this call's final program as chains in one launch: at least 48 steps
+    over at most 64 KiB, the longest path through the chains at most half the program, at most 3072
+    workgroup rounds (64-byte columns x rounds of 64 chains), and the values that are alive at one time fit
+    the LDS beside the identity value."""
+    _, _, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
+                                                  w.ready_order() if order is None else order, fm)
+    final = entries[launches[-1][2]:launches[-1][3]]
+    if len(final) < 48 or w.object_bytes > (64 << 10):          # a call without failures is one launch over the object
+        return False
+    src, chains = hop.hop_plan_chains(final, 4)
+    if src != hop.HOP_OK:
+        return False
+    n_pass = 1 + max(p for p, _ in chains)
+    critical = sum(max(len(items) for p, items in chains if p == q) for q in range(n_pass))
+    # a chain's value occupies 16 B (bf16: 32 B) x 4 lanes of the workgroup's 64 KiB of LDS from its own pass to
+    # the pass that reads it
+    read_in = {-it - 1: p for p, items in chains for it in items if it < 0}
+    alive = max(sum(1 for g, (p, _) in enumerate(chains) if g in read_in and p <= q <= read_in[g]) for q in range(n_pass))
+    # a workgroup has 64 teams: a pass with more chains takes several rounds
+    rounds = sum(-(-sum(1 for p, _ in chains if p == q) // 64) for q in range(n_pass))
+    columns = -(-w.object_bytes // 64)
+    return (n_pass <= 24 and 2 * critical <= len(final) and alive <= (512 if w.dtype == "bf16" else 1024) - 1
+            and columns * rounds <= 3072)
+
+
+CHAIN_CASES = [
+    # dtype, n, k, d, object bytes, chunk bytes
+    ("f32", 1024, 1000, 16, 4096, 4096),             # workload 5
+    ("f32", 300, 300, 4, 4, 64),                     # one element: only the workgroup for the ragged end
+    ("f32", 200, 190, 8, 12, 64),
+    ("bf16", 500, 500, 16, 14, 64),                  # seven elements behind no vector at all: two workgroups of four lanes
+    ("bf16", 500, 400, 8, 16, 16),                   # exactly one vector
+    ("i32", 120, 120, 2, 252, 1024),                 # three columns, three vectors of a fourth and three elements; a binary tree
+    ("f32", 300, 280, 3, 256 + 4, 4096),             # four columns and one element
+    ("bf16", 900, 900, 32, 4096 + 2 * 5, 8192),
+    ("i32", 1000, 1000, 16, 65536 - 4, 16384),       # the largest range: 1024 columns less an element
+    ("f32", 2000, 2000, 16, 1000 * 4, 1024),         # four chunks, the last one ragged; more chains than teams
+    ("bf16", 1500, 1400, 40, 30 * 2, 4096),          # nodes with 40 children: folds longer than a record, cut in two
+    ("f32", 100, 100, 2, 8192, 2048),                # a binary tree: five passes
+    ("f32", 5000, 5000, 2, 512, 512),                # a binary tree on 5000: too many chains, the older path
+    ("f32", 1024, 1000, 16, 131072, 65536),          # workload 5 with larger objects: the older path
+    ("i32", 48, 48, 4, 640, 4096),                   # the shortest program that takes the path
+]
+
+
+@pytest.mark.parametrize("dtype,n,k,d,nbytes,chunk", CHAIN_CASES)
+def test_long_programs_over_small_objects_in_one_launch(dtype, n, k, d, nbytes, chunk):
+    base = workloads.WORKLOADS[{"f32": 5, "bf16": 4, "i32": 3}[dtype]]
+    dist = {"f32": "uniform_pm1", "bf16": "normal_std1", "i32": "randint_pm2p20"}[dtype]
+    w = base.scaled(nbytes, chunk, n=n, k=k, tree_degree=d, order_seed=n + d, data_seed=k + nbytes, fail={},
+                    name="chains_%s_%d" % (dtype, n), dist=dist, n_dst=0)
+    assert takes_the_one_launch_path(w) == (n != 5000 and nbytes != 131072)
+    objs = workloads.make_objects(w, device=dev())
+    for op in ("sum", "min", "max"):
+        rc, info = run_both(w, op, objs=objs)
+        assert rc == hop.HOP_OK and info["n_launches"] == 1
+    # with failures before and in the middle of the stream (holes, replacements, repairs of produced chunks)
+    rng = np.random.default_rng(n * 7 + d)
+    fm = np.full(n, -1, np.int64)
+    bad = rng.random(n) < 0.08
+    fm[bad] = rng.integers(0, w.n_chunks + 1, size=int(bad.sum()))
+    run_both(w, "sum", objs=objs, fm=fm)
+    # all-reduce: the copy to the other destinations follows the one launch
+    dsts = [torch.full_like(objs[0], 3) for _ in range(3)]
+    rc, info = hop.hop_allreduce(dsts, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
+    torch.cuda.synchronize()
+    orc, outs, _, _ = oracle.allreduce([workloads.to_numpy(o) for o in objs], 3, w.k, oracle.SUM, ORA_DT[dtype],
+                                       max(1, w.chunk_bytes // ES[dtype]), d, w.ready_order(), None)
+    assert rc == orc == hop.HOP_OK
+    for got, want in zip(dsts, outs):
+        assert np.array_equal(bits(workloads.to_numpy(got)), bits(want))
+
+
+def test_one_launch_path_with_specials_and_sources_at_odd_alignment():
+    # NaNs, infinities, signed zeros and denormals through the chains' folds and their values in LDS; the
+    # objects are views 16 bytes into their allocations
+    n, nbytes = 400, 1000 * 4
+    w = workloads.WORKLOADS[5].scaled(nbytes, 4096, n=n, k=n, tree_degree=8, order_seed=3, data_seed=4, fail={},
+                                      name="chains_specials", n_dst=0)
+    assert takes_the_one_launch_path(w)
+    rng = np.random.default_rng(12)
+    # every element position has one theme, so that two different NaNs never meet (which of them a sum
+    # returns is not defined): +inf among finite values, -inf, both (the sum generates a NaN), one quiet NaN
+    # pattern, zeros of both signs only, denormals only, large values that overflow, plain values
+    E = nbytes // 4
+    theme = rng.integers(0, 8, size=E)
+    qnan = np.array([0x7fc01234], np.uint32).view(np.float32)[0]
+    backing = [torch.zeros(E + 8, dtype=torch.float32, device=dev()) for _ in range(n)]
+    objs = []
+    for b in backing:
+        host = (rng.standard_normal(E) * 1e-3).astype(np.float32)
+        hit = rng.random(E) < 0.03
+        host[hit & (theme == 0)] = np.inf
+        host[hit & (theme == 1)] = -np.inf
+        both = hit & (theme == 2)
+        host[both] = np.where(rng.random(int(both.sum())) < 0.5, np.inf, -np.inf).astype(np.float32)
+        host[hit & (theme == 3)] = qnan
+        zeros = theme == 4
+        host[zeros] = np.where(rng.random(int(zeros.sum())) < 0.5, 0.0, -0.0).astype(np.float32)
+        den = theme == 5
+        host[den] = (rng.standard_normal(int(den.sum())) * 1e-42).astype(np.float32)
+        big = theme == 6
+        host[big] = (rng.standard_normal(int(big.sum())) * 3e37).astype(np.float32)
+        o = b[4:4 + E]
+        o.copy_(torch.from_numpy(host))
+        objs.append(o)
+    for op in ("sum", "min", "max"):
+        run_both(w, op, objs=objs)
+
+
 def test_infinities_and_nans_come_out_as_in_the_oracle():
     # at most one NaN meets any element position (which of two NaN payloads an addition keeps is not
     # fixed by the C the oracle is written in): inf - inf, inf + finite, a quiet NaN with a payload, a

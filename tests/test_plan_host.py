@@ -269,6 +269,90 @@ def test_split_program_keeps_the_bits(want_steps, min_run, max_run):
     assert len(tops) + sum(len(sp) for _, sp in subs) - len(subs) == 4000
 
 
+def run_chains(objs, chains, op):
+    """Chains pass by pass: each reads only objects and values of chains of earlier passes; the last one is the result."""
+    f = NP_OP[op]
+    values = [None] * len(chains)
+    for p in range(1 + max(ps for ps, _ in chains)):
+        for g, (ps, items) in enumerate(chains):
+            if ps != p:
+                continue
+            vals = []
+            for it in items:
+                if it < 0:
+                    assert chains[-it - 1][0] < p and values[-it - 1] is not None
+                vals.append(objs[it] if it >= 0 else values[-it - 1])
+            acc = vals[0].copy()
+            for x in vals[1:]:
+                acc = f(acc, x).astype(x.dtype)
+            values[g] = acc
+    return values[-1]
+
+
+@pytest.mark.parametrize("min_cut", [1, 2, 4, 9])
+def test_program_as_chains_keeps_the_bits(min_cut):
+    rng = np.random.default_rng(40 + min_cut)
+    n_cut = 0
+    for _ in range(150):
+        n = int(rng.integers(1, 200))
+        k = int(rng.integers(1, n + 1))
+        d = int(rng.choice([1, 2, 3, 4, 16, n + 1]))
+        order = rng.permutation(n).astype(np.int32)
+        fm = None
+        if rng.random() < 0.5:
+            fm = np.full(n, -1, np.int64)
+            bad = rng.random(n) < 0.2
+            fm[bad] = rng.integers(0, 3, size=int(bad.sum()))
+        objs = [(rng.standard_normal(16) * 10.0 ** rng.integers(-3, 4)).astype(np.float32) for _ in range(n)]
+        rc, info, launches, entries = hop.hop_plan_reduce(n, 64, k, "f32", 32, d, order, fm)
+        if rc < 0:
+            continue
+        final = entries[launches[-1][2]:launches[-1][3]]
+        max_items = int(rng.choice([2, 3, 8, 23, 1000]))
+        src, chains = hop.hop_plan_chains(final, min_cut, max_items)
+        if len(final) < 2:
+            assert src == hop.HOP_PARTIAL and chains == []
+            continue
+        assert src == hop.HOP_OK
+        # every object exactly once, every chain's value used exactly once except the last one's
+        seen = [it for _, items in chains for it in items if it >= 0]
+        assert sorted(seen) == sorted(e[0] for e in final)
+        refs = [-it - 1 for _, items in chains for it in items if it < 0]
+        assert sorted(refs) == list(range(len(chains) - 1))
+        # a chain's pass is one more than the latest pass it reads from, 0 if it reads objects only
+        for ps, items in chains:
+            assert ps == max([0] + [chains[-it - 1][0] + 1 for it in items if it < 0]) and 2 <= len(items) <= max_items
+        whole = run_entries(objs, final, "sum")
+        got = run_chains(objs, chains, "sum")
+        assert np.array_equal(got.view(np.uint32), whole.view(np.uint32))
+        n_cut += len(chains) > 1
+    assert n_cut > 30
+    # workload 5: 1000 steps become three passes whose longest chains have 18, 17 and 16 items, with at
+    # most 59 chains in a pass (a workgroup evaluates 64 side by side)
+    w = workloads.WORKLOADS[5]
+    _, _, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
+                                                  w.ready_order(), None)
+    src, chains = hop.hop_plan_chains(entries, 4)
+    assert src == hop.HOP_OK
+    per_pass = {}
+    for ps, items in chains:
+        per_pass.setdefault(ps, []).append(len(items))
+    assert sorted(per_pass) == [0, 1, 2] and [max(per_pass[p]) for p in range(3)] == [18, 17, 16]
+    assert [len(per_pass[p]) for p in range(3)] == [59, 3, 1]
+    # a chain or a star is one fold with nothing to do side by side: a single chain, or, with a limit on
+    # the items of a chain, pieces that follow each other one pass each
+    for d in (1, 5000):
+        _, _, _, e1 = hop.hop_plan_reduce(300, 64, 300, "f32", 64, d, None, None)
+        src, chains = hop.hop_plan_chains(e1, 4, 1000)
+        assert src == hop.HOP_OK and len(chains) == 1 and len(chains[0][1]) == 300
+        src, chains = hop.hop_plan_chains(e1, 4, 23)
+        assert src == hop.HOP_OK and [p for p, _ in chains] == list(range(14))
+        assert [len(items) for _, items in chains] == [23] * 13 + [1 + 300 - 23 - 12 * 22]
+    # programs that read kept partial results have no such form
+    assert hop.hop_plan_chains([(0, 0, 1, 0), (-1, 0, 0, 0)], 4)[0] == hop.HOP_PARTIAL
+    assert hop.hop_plan_chains([(0, 0, 1, 0, 0, 0), (1, 0, 0, 0)], 4)[0] == hop.HOP_PARTIAL
+
+
 def test_failure_free_call_is_one_launch_over_all_chunks():
     for cfg in (1, 2, 3, 5):
         w = workloads.WORKLOADS[cfg]
