@@ -285,7 +285,10 @@ struct CachedCall {
 static std::vector<CachedCall *> g_calls;
 static uint64_t g_call_stamp = 0;
 static constexpr size_t kMaxCachedCalls = 128;          // a serving loop may rotate through many sets of buffers
-static constexpr size_t kMaxCachedInputBytes = (size_t)64 << 20;      // larger calls are bound by the kernels
+static constexpr size_t kMaxCachedInputBytes = (size_t)64 << 20;      // larger calls are bound by the kernels ...
+static constexpr size_t kMaxCachedObjectBytes = (size_t)256 << 10;    // ... unless their objects are small: planning takes about
+                                                                      // 20 ns per input, the kernels object_bytes / 6.5 TB/s
+static constexpr size_t kMaxCachedScratch = (size_t)32 << 20;         // a recording keeps the scratch its launches use
 
 static void free_cached_call(CachedCall *c)
 {
@@ -325,7 +328,7 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
     const int64_t d = tree_degree > 0 ? tree_degree : auto_degree(device, k, object_bytes, (hipStream_t)stream);
-    bool cacheable = n_dst == 1 && !no_alloc && object_bytes > 0 && object_bytes <= kMaxCachedInputBytes / (size_t)k &&
+    bool cacheable = n_dst == 1 && !no_alloc && object_bytes > 0 && (object_bytes <= kMaxCachedInputBytes / (size_t)k || object_bytes <= kMaxCachedObjectBytes) &&
                      nobody_fails(fail_mask, n, shape.n_chunks);
     if (cacheable) {
         // a stream that is being captured into a graph takes the plain path: a recording's hand-over between
@@ -385,7 +388,7 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
         rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, &my_info);
         set_launch_recorder(nullptr);
         if (info) *info = my_info;
-        if (cacheable && rc >= 0 && !rec.unusable && !rec.launches.empty()) {
+        if (cacheable && rc >= 0 && !rec.unusable && !rec.launches.empty() && be.held_bytes() <= kMaxCachedScratch) {
             CachedCall *c = new CachedCall;
             c->device = device; c->n = n; c->k = k; c->op = op; c->dtype = dtype;
             c->object_bytes = object_bytes; c->chunk_bytes = chunk_bytes; c->degree = d;
@@ -933,16 +936,19 @@ size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes
         if (n_dst - 1 > kInlineDsts) staged += round256((size_t)(n_dst - 1) * sizeof(void *));
         size_t total = blocks(staged);
         // the cut into sub-programs of a call over many small objects: their partial results and records
-        if (dtype != HOP_BF16 && (size_t)k >= 128 && object_bytes > 0 && object_bytes <= ((size_t)1 << 20)) {
+        // the program as chains in one launch: a table of one record per chain (fewer chains than inputs)
+        if ((size_t)k >= kChainWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= kChainMaxBytes)
+            total += blocks(round256((size_t)k * kChainRecordWords * sizeof(uint64_t)));
+        if (dtype != HOP_BF16 && (size_t)k >= kSplitWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= kSplitMaxBytes) {
             Tree tr;
             tr.shape(k, d);
             std::vector<int32_t> occ((size_t)k, 0);
             std::vector<Entry> prog;
             compile_program(tr, occ, prog);
             MultiPlan mp;
-            if (plan_passes(prog, 128, 4, kMaxSubSteps, mp)) {
-                const size_t partials = round256(object_bytes) * mp.n_subs();
-                if (partials <= ((size_t)16 << 20))
+            if (plan_passes(prog, kSplitWantSteps, kSplitMinRun, kSplitMaxRun, mp)) {
+                const size_t partials = round256(std::min(object_bytes, kSplitMaxBytes)) * mp.n_subs();
+                if (partials <= kSplitMaxScratch)
                     total = std::max(total, blocks(partials + (mp.steps.size() + mp.n_subs() * 2 + mp.top.size()) * sizeof(DevEntry) + 512));
             }
         }

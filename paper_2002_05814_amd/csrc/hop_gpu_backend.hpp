@@ -28,6 +28,19 @@ struct Shape {
     size_t end(int64_t c) const { size_t e = (size_t)c * chunk_bytes; return e < object_bytes ? e : object_bytes; }
 };
 
+// When a long program over few output tiles is cut into sub-programs with partial results in memory
+// (GpuBackend::launch_split), and when it is evaluated as chains in one launch (launch_chains); the
+// measurements behind the numbers stand at those functions.
+constexpr size_t kSplitWantSteps = 128;             // shorter programs are not worth extra launches
+constexpr int kSplitMaxRun = kMaxSubSteps;          // longest sub-program: a record fits the lanes of a wave
+constexpr size_t kSplitMaxBytes = 768u << 10;       // above, a wave's walk through the whole program is hidden behind the streaming
+constexpr int kSplitMinRun = 4;
+constexpr size_t kSplitMaxScratch = 256u << 20;     // partial results of all sub-programs
+constexpr size_t kChainWantSteps = 48;              // shorter programs: one wave per tile walks them as fast
+constexpr size_t kChainMaxBytes = 64u << 10;        // at most 1024 columns
+constexpr int kChainMinCut = 4;
+constexpr size_t kChainMaxWork = 3072;              // columns x rounds
+
 class GpuBackend : public Backend {
 public:
     // static_base != nullptr: all device scratch comes from [static_base, static_base + static_cap) and
@@ -62,8 +75,11 @@ public:
         dev_prog_ = nullptr;
         dev_extra_ = nullptr;
         dev_version_ = 0;
+        chain_version_ = 0;
+        chain_table_ = nullptr;
         return ws_.detach();
     }
+    size_t held_bytes() const { return ws_.held_bytes(); }
 
     // Adaptive sessions ask whether the stream has worked off what this session launched: an event
     // is recorded behind every launch from now on.
@@ -259,12 +275,10 @@ private:
     // Many inputs but few output tiles (the many-small-objects case): one wave per tile would walk
     // the whole program alone, so the independent subtrees are evaluated side by side first.
     // Partials are stored in the accumulation type, which for bf16 is not the element type: bf16
-    // keeps the plain path.
-    static constexpr size_t kSplitWantSteps = 128;      // shorter programs are not worth extra launches
-    static constexpr int kSplitMaxRun = kMaxSubSteps;   // longest sub-program: a record fits the lanes of a wave
-    static constexpr size_t kSplitMaxBytes = 1u << 20;  // launches this large already fill the chip
-    static constexpr int kSplitMinRun = 4;
-    static constexpr size_t kSplitMaxScratch = 16u << 20;
+    // keeps the plain path. Measured (fp32 sums, 16-ary tree, inputs not in any cache): a wave that walks
+    // a program alone takes about 0.15 us per step whatever the range, so the cut pays while that is more
+    // than the time to stream the range - up to about 768 KiB: 4000 inputs of 256 KiB 212 us against 620
+    // for the plain path, 1000 inputs of 1 MiB 212 us against 186.
 
     bool wants_split(size_t n_steps, size_t range_bytes) const
     {
@@ -349,10 +363,6 @@ private:
     // against 19.6-33.6. It loses where the workgroups no longer run side by side (a workgroup is bound by
     // the latency of its few loads): 256 inputs of 256 KiB 28.8 against 19.3, 4000 of 64 KiB 109 against 67.
     // Hence the limit on columns x rounds, a round being 64 chains of one pass.
-    static constexpr size_t kChainWantSteps = 48;       // shorter programs: one wave per tile walks them as fast
-    static constexpr size_t kChainMaxBytes = 64u << 10; // at most 1024 columns
-    static constexpr int kChainMinCut = 4;
-    static constexpr size_t kChainMaxWork = 3072;       // columns x rounds
 
     bool wants_chains(size_t n_steps, size_t range_bytes) const
     {
@@ -361,18 +371,27 @@ private:
 
     int launch_chains(const std::vector<Entry> &prog, uint64_t version, size_t b0, size_t b1)
     {
+        const size_t columns = (b1 - b0 + 16 * kChainLanes - 1) / (16 * kChainLanes);
         if (version != chain_version_) {
+            // the plan is made once per program; the table only when a launch is short enough to use it
             chain_version_ = version;
             chain_table_ = nullptr;
-            ChainPlan cp;
+            chain_usable_ = false;
+            ChainPlan &cp = chain_plan_;
             if (!plan_chains(prog, kChainMinCut, kChainMaxItems, cp)) return HOP_PARTIAL;
             // worth it only if the longest path through the chains is much shorter than the program
             if (cp.n_passes > kMaxChainPasses || cp.critical_steps * 2 > (int64_t)prog.size()) return HOP_PARTIAL;
-            const size_t n_chains = cp.n_chains();
             std::vector<int> per_pass((size_t)cp.n_passes, 0);
             for (int32_t ps : cp.pass) per_pass[(size_t)ps]++;
             chain_rounds_ = 0;
             for (int cnt : per_pass) chain_rounds_ += (size_t)((cnt + kChainTeams - 1) / kChainTeams);
+            chain_usable_ = true;
+        }
+        if (!chain_usable_ || columns * chain_rounds_ > kChainMaxWork) return HOP_PARTIAL;
+        if (!chain_table_) {
+            chain_usable_ = false;               // until the table stands
+            const ChainPlan &cp = chain_plan_;
+            const size_t n_chains = cp.n_chains();
             // chains in pass order; a value's LDS slot is taken when its chain's pass starts and is free
             // again from the pass after the one that reads it
             std::vector<int32_t> order(n_chains);
@@ -427,10 +446,8 @@ private:
             if (!chain_table_) return ws_.error();
             chain_slots_ = (int)n_slots;
             chain_count_ = (int)n_chains;
+            chain_usable_ = true;
         }
-        if (!chain_table_) return HOP_PARTIAL;
-        const size_t columns = (b1 - b0 + 16 * kChainLanes - 1) / (16 * kChainLanes);
-        if (columns * chain_rounds_ > kChainMaxWork) return HOP_PARTIAL;
         const hipError_t e = launch_reduce_chains(stream_, dtype_, op_, chain_table_, chain_count_, chain_slots_,
                                                   chain_pass_begin_.data(), (int)chain_pass_begin_.size() - 1, dsts_[0], b0, b1);
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
@@ -463,6 +480,8 @@ private:
     std::vector<uint32_t> chain_pass_begin_;
     int chain_slots_ = 0, chain_count_ = 0;
     size_t chain_rounds_ = 0;
+    ChainPlan chain_plan_;
+    bool chain_usable_ = false;
     int depth_ = 1;
     int device_;
     DevBuf *spill_buf_ = nullptr;

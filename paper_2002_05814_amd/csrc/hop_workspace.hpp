@@ -264,6 +264,13 @@ public:
         used_ = 0;
         return out;
     }
+    // device bytes of the blocks held
+    size_t held_bytes() const
+    {
+        size_t total = 0;
+        for (const Block *b : blocks_) total += b->cap;
+        return total;
+    }
     // why the last request failed
     int error() const { return too_large_ ? HOP_ERR_TOO_LARGE : HOP_ERR_NOMEM; }
     // bytes a request of any kind may still take in static mode

@@ -160,6 +160,10 @@ def test_many_small_objects_take_the_multi_pass_path(dtype):
         w = base.scaled(256 * ES[dtype], 256 * ES[dtype], n=4000, k=3900, tree_degree=2, order_seed=77, data_seed=78,
                         fail={}, name="small_deep", dist=dist, n_dst=0)
         run_both(w, "sum")
+        # objects of a few hundred KiB: still cut (a wave alone would walk 1900 steps), with tens of MiB of partials
+        w = base.scaled(300 * 1024 + 4, 1 << 20, n=2000, k=1900, tree_degree=16, order_seed=79, data_seed=80,
+                        fail={}, name="small_wide", dist=dist, n_dst=0)
+        run_both(w, "sum")
 
 
 def takes_the_one_launch_path(w, order=None, fm=None):
