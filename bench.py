@@ -365,7 +365,7 @@ def main():
                          "known size against which hardware byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs one node's share of the reduce on ONE GPU; --gpus %d is not supported "
+        print("bench.py: this library runs one node's share of the reduce on ONE GPU; --gpus %d is not supported "
               "(no collectives between GPUs exist in it)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
@@ -397,10 +397,10 @@ def main():
         n_out = max(1, w.n_dst)
         # two destination sets, alternated, so that a call never finds its output lines in cache
         dsts = [[torch.empty_like(objs[0]) for _ in range(n_out)] for _ in range(2)]
-        # Workloads whose inputs would all sit in the 256 MB last-level cache get 64 copies of the input
-        # set at different addresses (>= 256 MiB in total), used in turn.
+        # Workloads whose inputs would all sit in the 256 MB last-level cache get at least 64 copies of the
+        # input set at different addresses (>= 512 MiB in total, twice that cache), used in turn.
         total = w.n * w.object_bytes
-        n_sets = 1 if total > (64 << 20) else max(64, -(-(256 << 20) // total))
+        n_sets = 1 if total > (64 << 20) else max(64, -(-(512 << 20) // total))
         obj_sets = [objs]
         for _ in range(n_sets - 1):
             block = torch.stack(objs)                      # one allocation, objects object_bytes apart
