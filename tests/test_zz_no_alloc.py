@@ -82,3 +82,32 @@ def test_no_alloc_rejects_what_does_not_fit():
     # and the next call works
     w = workloads.WORKLOADS[1]
     both_entry_points(w, "sum")
+
+
+def test_no_alloc_call_over_many_small_objects_in_a_graph():
+    # a call that allocates nothing and stages its tables through kernel arguments is nothing but kernel
+    # launches: workload 5 (the program as chains, one launch behind the launches that carry its table)
+    # recorded into a graph and replayed with other contents in the same buffers
+    dev = torch.device("cuda:0")
+    w = workloads.WORKLOADS[5]
+    objs = workloads.make_objects(w, device=dev)
+    order = w.ready_order()
+    dst = torch.zeros_like(objs[0])
+    rc, info = hop.hop_reduce_noalloc(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
+    torch.cuda.synchronize()
+    assert rc == hop.HOP_OK
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc, info = hop.hop_reduce_noalloc(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
+    assert rc == hop.HOP_OK and info["n_launches"] == 1
+    rng = np.random.default_rng(9)
+    for rep in range(3):
+        for o in objs[::37]:                          # eager work between the replays
+            o.mul_(float(rng.uniform(0.5, 1.5)))
+        dst.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        _, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], w.k, oracle.SUM, oracle.F32,
+                                      w.chunk_bytes // 4, w.tree_degree, order, None)
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want)), rep
