@@ -587,6 +587,41 @@ def test_session_events_match_oracle(fine):
                 assert info["n_launches"] == C          # one launch per chunk as each becomes complete
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_session_events_over_hundreds_of_small_objects(dtype):
+    # the event-level API over many small objects: every launch covers one or a few chunks of at most a few
+    # KiB with a program of hundreds of steps (the one-launch form), and every failure changes the program
+    rng = np.random.default_rng({"f32": 61, "bf16": 62}[dtype])
+    base = workloads.WORKLOADS[{"f32": 5, "bf16": 4}[dtype]]
+    es = ES[dtype]
+    for it in range(6):
+        n = int(rng.integers(100, 400))
+        k = int(rng.integers(60, n + 1))
+        d = int(rng.choice([3, 4, 8, 16]))
+        C = int(rng.integers(2, 6))
+        chunk = 16 * int(rng.integers(4, 130))
+        nbytes = (C - 1) * chunk + es * int(rng.integers(1, chunk // es + 1))
+        w = base.scaled(nbytes, chunk, n=n, k=k, tree_degree=d, order_seed=int(rng.integers(1 << 30)),
+                        data_seed=int(rng.integers(1 << 30)), fail={}, name="many%d" % it, n_dst=0,
+                        dist={"f32": "uniform_pm1", "bf16": "normal_std1"}[dtype])
+        objs = workloads.make_objects(w, device=dev())
+        order = w.ready_order()
+        fm = np.full(n, -1, np.int64)
+        bad = rng.random(n) < 0.05
+        fm[bad] = rng.integers(0, C + 1, size=int(bad.sum()))
+        dst = torch.full_like(objs[0], 9)
+        fine = bool(it % 2)
+        print("many-objects session", dtype, it, n, k, d, C, nbytes, fine, flush=True)
+        rc, info = session_replay(objs, dst, k, "sum", dtype, chunk, d, order, fm, C, fine)
+        torch.cuda.synchronize()
+        orc, want, k_eff, n_rep = oracle.reduce([workloads.to_numpy(o) for o in objs], k, oracle.SUM, ORA_DT[dtype],
+                                                chunk // es, d, order, fm)
+        assert rc == orc
+        if rc >= 0:
+            assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+            assert info["k_eff"] == k_eff and info["n_replaced"] == n_rep
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "i32"])
 def test_session_eager_segments_match_oracle(dtype):
     # objects arrive whole, one after the other (object-by-object timeline), some failing part-way:
