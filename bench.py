@@ -43,10 +43,10 @@ PROFILED_TRAFFIC = {
                      "launch, 256 lanes per 64-byte column, chains of at most 23 items folded by teams of 4 lanes with all "
                      "their loads in flight, values in LDS"),
     "workloads": {
-        "cfg2_async_sgd": {"bytes_per_call": 872306923, "profile": "profiles/hbm_traffic_all_workloads.md"},
-        "cfg3_rl_allreduce": {"bytes_per_call": 2163397681, "profile": "profiles/hbm_traffic_all_workloads.md"},
-        "cfg4_large_fault": {"bytes_per_call": 10181981383, "profile": "profiles/hbm_traffic_all_workloads.md"},
-        "cfg4_large_fault_without_failure": {"bytes_per_call": 8856975592, "profile": "profiles/hbm_traffic_all_workloads.md"},
+        "cfg2_async_sgd": {"bytes_per_call": 872327474, "profile": "profiles/hbm_traffic_all_workloads.md"},
+        "cfg3_rl_allreduce": {"bytes_per_call": 2163381761, "profile": "profiles/hbm_traffic_all_workloads.md"},
+        "cfg4_large_fault": {"bytes_per_call": 10181969677, "profile": "profiles/hbm_traffic_all_workloads.md"},
+        "cfg4_large_fault_without_failure": {"bytes_per_call": 8856980408, "profile": "profiles/hbm_traffic_all_workloads.md"},
     },
 }
 
