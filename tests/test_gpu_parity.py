@@ -1261,6 +1261,25 @@ def test_session_with_a_workspace_of_the_callers():
         assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
         if eager == 0:
             assert info["partial_stores"] > 0 and info["partial_loads"] > 0       # kept partials lived in the workspace
+    # many small objects: the table of the one-launch form of the program comes out of the workspace too, one
+    # per version of the program (each failure makes a new one); hop_workspace_bytes counts one
+    wm = workloads.WORKLOADS[5].scaled(3000 * 4, 4096, n=400, k=380, tree_degree=8, order_seed=33, data_seed=34,
+                                       fail={}, name="own_workspace_small", n_dst=0)
+    mobjs = workloads.make_objects(wm, device=d)
+    morder = wm.ready_order()
+    mfm = np.full(wm.n, -1, np.int64)
+    mfm[morder[7]], mfm[morder[200]] = 1, 2
+    per_version = hop.hop_workspace_bytes(wm.n, wm.k, wm.object_bytes, wm.chunk_bytes, wm.tree_degree, wm.dtype)
+    assert per_version >= 380 // 8 * 192
+    ws = torch.empty(4 * per_version, dtype=torch.uint8, device=d)
+    mdst = torch.zeros_like(mobjs[0])
+    rc, info = session_replay(mobjs, mdst, wm.k, "sum", wm.dtype, wm.chunk_bytes, wm.tree_degree, morder, mfm, wm.n_chunks,
+                              fine=True, workspace=ws)
+    torch.cuda.synchronize()
+    morc, mwant, mk_eff, _ = oracle.reduce([workloads.to_numpy(o) for o in mobjs], wm.k, oracle.SUM, oracle.F32,
+                                           wm.chunk_bytes // 4, wm.tree_degree, morder, mfm)
+    assert rc == morc and info["k_eff"] == mk_eff
+    assert np.array_equal(bits(workloads.to_numpy(mdst)), bits(mwant))
     # a workspace that cannot hold the saved accumulators: the event that needs them says so
     small = torch.empty(1 << 20, dtype=torch.uint8, device=d)
     dst = torch.zeros_like(objs[0])
