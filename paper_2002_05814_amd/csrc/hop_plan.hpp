@@ -306,7 +306,12 @@ inline bool plan_chains(const std::vector<Entry> &prog, int min_cut, int max_ite
         std::vector<int32_t> items;
         int avail = 0;                           // pass before which nothing of `items` is missing
     };
-    std::vector<Open> open(256);
+    int depth = 1;
+    for (const Entry &e : prog) depth = std::max(depth, (int)e.level + 1);
+    std::vector<Open> open((size_t)depth);
+    cp.items.reserve(prog.size() + prog.size() / 2);
+    cp.begin.reserve(prog.size() / 2 + 2);
+    cp.pass.reserve(prog.size() / 2 + 1);
     auto avail_of = [&](int32_t item) { return item >= 0 ? 0 : cp.pass[(size_t)(-item - 1)] + 1; };
     auto emit = [&](Open &o) {
         const int32_t g = (int32_t)cp.pass.size();
