@@ -358,7 +358,7 @@ private:
     // in which every column's workgroup evaluates the program as chains, up to 64 of them side by side,
     // their values in LDS (no second launch, no partials in memory; the values are accumulator-typed,
     // so bf16 takes this path too). Measured on fp32 sums in a 16-ary tree, inputs not in any cache,
-    // against the paths below, us per call: 128 inputs of 1-64 KiB 8.0-8.5 against 10.7-11.3; 1000 inputs of
+    // against the other paths, us per call: 128 inputs of 1-64 KiB 8.0-8.5 against 10.7-11.3; 1000 inputs of
     // 1-16 KiB 9.0-9.5 against 18.8-21.6, of 64 KiB 25.3 against 27.3; 4000 inputs of 1-16 KiB 15.5-23.5
     // against 19.6-33.6. It loses where the workgroups no longer run side by side (a workgroup is bound by
     // the latency of its few loads): 256 inputs of 256 KiB 28.8 against 19.3, 4000 of 64 KiB 109 against 67.
