@@ -53,9 +53,15 @@ typedef enum {
     HOP_ERR_NOMEM = -5,         /* host or device allocation failed                          */
     HOP_ERR_DEPTH = -6,         /* the tree needs more partial results in flight than the
                                    kernels hold in registers (see HOP_MAX_DEPTH)             */
-    HOP_ERR_TOO_LARGE = -7      /* the call needs more device scratch than it may take: than
+    HOP_ERR_TOO_LARGE = -7,     /* the call needs more device scratch than it may take: than
                                    the library's static array holds (hop_reduce_noalloc) or
                                    than the caller's workspace (hop_session_set_workspace)   */
+    HOP_ERR_CAPTURE = -8        /* the stream is being captured into a graph and the call
+                                   would need memory from the library's caches (a staged
+                                   program of more than 128 steps, a table, saved
+                                   accumulators), which a replay of the graph would find
+                                   rewritten: use hop_reduce_noalloc, or a session with
+                                   hop_session_set_workspace                                 */
 } hop_status_t;
 
 /* Most partial results that can be live at once while one element's tree

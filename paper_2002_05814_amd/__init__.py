@@ -21,7 +21,7 @@ HOP_SUM, HOP_MIN, HOP_MAX = 0, 1, 2
 HOP_F32, HOP_BF16, HOP_I32 = 0, 1, 2
 HOP_OK, HOP_PARTIAL = 0, 1
 HOP_ERR_INVALID, HOP_ERR_ALIGN, HOP_ERR_NO_SURVIVOR = -1, -2, -3
-HOP_ERR_DEVICE, HOP_ERR_NOMEM, HOP_ERR_DEPTH, HOP_ERR_TOO_LARGE = -4, -5, -6, -7
+HOP_ERR_DEVICE, HOP_ERR_NOMEM, HOP_ERR_DEPTH, HOP_ERR_TOO_LARGE, HOP_ERR_CAPTURE = -4, -5, -6, -7, -8
 HOP_MAX_DEPTH = 16
 
 OPS = {"sum": HOP_SUM, "min": HOP_MIN, "max": HOP_MAX}

@@ -1015,6 +1015,7 @@ const char *hop_strerror(int status)
     case HOP_ERR_DEVICE: return "HIP call failed";
     case HOP_ERR_NOMEM: return "out of memory";
     case HOP_ERR_DEPTH: return "reduce tree needs more live partial results than the kernels hold";
+    case HOP_ERR_CAPTURE: return "the stream is being captured into a graph and the call would need memory from the library's caches";
     case HOP_ERR_TOO_LARGE: return "the call needs more device scratch than the static array of the no-allocation entry point holds";
     default: return "unknown status";
     }

@@ -112,6 +112,7 @@ public:
             kept_ = (char *)ws_.scratch(kept_stride_ * (size_t)n_partials);
             if (!kept_) return false;
         } else {
+            if (ws_.capturing()) return false;          // a graph cannot own cached memory: nothing is kept
             kept_buf_ = acquire_devbuf(device_, kept_stride_ * (size_t)n_partials);
             if (!kept_buf_) return false;
             kept_ = kept_buf_->ptr;
@@ -212,6 +213,7 @@ private:
                 spill_ = (char *)ws_.scratch(level_stride_ * (size_t)spill_levels_);
                 if (!spill_) return ws_.error();
             } else {
+                if (ws_.capturing()) return ws_.error();
                 spill_buf_ = acquire_devbuf(device_, level_stride_ * (size_t)spill_levels_);
                 if (!spill_buf_) return HOP_ERR_NOMEM;
                 spill_ = spill_buf_->ptr;

@@ -272,7 +272,17 @@ public:
         return total;
     }
     // why the last request failed
-    int error() const { return too_large_ ? HOP_ERR_TOO_LARGE : HOP_ERR_NOMEM; }
+    int error() const { return capture_denied_ ? HOP_ERR_CAPTURE : too_large_ ? HOP_ERR_TOO_LARGE : HOP_ERR_NOMEM; }
+    // Whether the stream is being captured into a graph. Then nothing may come from the cached blocks: they
+    // go back to the cache when the call or session ends and are written again by later calls, while a
+    // replay of the graph would still copy from them and point its kernels at them.
+    bool capturing()
+    {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream_, &cap) != hipSuccess) { (void)hipGetLastError(); return false; }
+        capture_denied_ = cap != hipStreamCaptureStatusNone;
+        return capture_denied_;
+    }
     // bytes a request of any kind may still take in static mode
     size_t static_left() const { return static_cap_ - used_; }
 
@@ -285,6 +295,7 @@ public:
             if (d && !poke(stream_, d, src, bytes)) return nullptr;
             return d;
         }
+        if (capturing()) return nullptr;
         if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
             Block *b = acquire_block(device_, need);
             if (!b) return nullptr;
@@ -307,6 +318,7 @@ public:
     {
         size_t need = (bytes + 255) & ~(size_t)255;
         if (is_static()) return stage(src, bytes);        // no pinned memory here: a copy on the device
+        if (capturing()) return nullptr;
         if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
             Block *b = acquire_block(device_, need);
             if (!b) return nullptr;
@@ -327,6 +339,7 @@ public:
             too_large_ = used_ + bytes > static_cap_;
             return !too_large_;
         }
+        if (capturing()) return false;
         if (!blocks_.empty() && used_ + bytes <= blocks_.back()->cap) return true;
         Block *b = acquire_block(device_, bytes);
         if (!b) return false;
@@ -345,6 +358,7 @@ public:
             used_ += need;
             return d;
         }
+        if (capturing()) return nullptr;
         if (blocks_.empty() || used_ + need > blocks_.back()->cap) {
             Block *b = acquire_block(device_, need);
             if (!b) return nullptr;
@@ -363,6 +377,7 @@ private:
     size_t used_ = 0;
     char *static_base_ = nullptr;
     size_t static_cap_ = 0;
+    bool capture_denied_ = false;
     bool too_large_ = false;
 };
 

@@ -1444,6 +1444,27 @@ def test_objects_larger_than_4_gib_use_64_bit_offsets():
     assert torch.equal(dst, torch.maximum(a, c))
 
 
+def test_a_captured_call_that_would_need_cached_memory_is_refused():
+    # programs of more than 128 steps and chain tables are staged in blocks that go back to the library's cache
+    # when the call ends: a graph cannot own them, so under capture such a call fails loudly instead of leaving
+    # a graph whose replays read rewritten memory. hop_reduce_noalloc is the call for that (tested with its own).
+    d = dev()
+    for nbytes, n in ((4096, 300), (2 << 20, 200)):
+        w = workloads.WORKLOADS[5].scaled(nbytes, nbytes, n=n, k=n, tree_degree=8, order_seed=3, data_seed=4, fail={},
+                                          name="captured", n_dst=0)
+        objs = workloads.make_objects(w, device=d)
+        dst = torch.zeros_like(objs[0])
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            dst.zero_()
+            rc, _ = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, None, None)
+        assert rc == hop.HOP_ERR_CAPTURE and "captured" in hop.hop_strerror(rc)
+        # outside the capture the same call works
+        rc, _ = run_both(w, "sum", objs=objs)
+        assert rc == hop.HOP_OK
+
+
 @pytest.mark.parametrize("object_mib", [1, 49])
 def test_reduce_can_be_captured_in_a_graph_and_replayed(object_mib):
     # short programs ride in the kernel arguments: a call is nothing but kernel launches on the

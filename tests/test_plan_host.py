@@ -30,6 +30,7 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert getattr(L, name) is not None
     assert hop.hop_strerror(0) == "ok" and "align" in hop.hop_strerror(hop.HOP_ERR_ALIGN)
+    assert "captured" in hop.hop_strerror(hop.HOP_ERR_CAPTURE) and hop.HOP_ERR_CAPTURE == -8
 
 
 def test_workspace_bytes_counts_every_kind_of_scratch():
