@@ -41,7 +41,7 @@ PROFILED_TRAFFIC = {
                      "pieces 64 KiB apart from 2048 tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators "
                      "indexed like the elements, nontemporal; programs of 48 steps or more over at most 64 KiB: one "
                      "launch, 256 lanes per 64-byte column, chains of at most 23 items folded by teams of 4 lanes with all "
-                     "their loads in flight, values in LDS"),
+                     "their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments"),
     "workloads": {
         "cfg2_async_sgd": {"bytes_per_call": 872327474, "profile": "profiles/hbm_traffic_all_workloads.md"},
         "cfg3_rl_allreduce": {"bytes_per_call": 2163381761, "profile": "profiles/hbm_traffic_all_workloads.md"},
@@ -445,6 +445,15 @@ def main():
             if n_sets > 1 and not w.n_dst:
                 # launch-bound: what a caller written in C pays per call
                 results[op]["c_loop"] = c_loop_host_time(hop, torch, w, obj_tables, [d[0] for d in dsts], order, op)
+                # the same loop over more input sets than the library keeps recordings of (128): every call comes
+                # with addresses it has not seen, as from a caller that gets fresh buffers for every request
+                while len(obj_sets) < 160:
+                    block = torch.stack(objs)
+                    obj_sets.append([block[i] for i in range(w.n)])
+                    obj_tables.append(hop.PtrTable(obj_sets[-1]))
+                results[op]["c_loop_fresh"] = c_loop_host_time(hop, torch, w, obj_tables, [d[0] for d in dsts], order, op,
+                                                               repeats=1600)
+                del obj_sets[n_sets:], obj_tables[n_sets:]
         return w, objs, order, dsts, results
 
     # The headline workload runs first, on memory as a fresh process gets it: after the other workloads have
@@ -475,6 +484,7 @@ def main():
                     "status": rr["status"], "status_text": hop.hop_strerror(rr["status"]), "k_eff": rr["info"]["k_eff"],
                     "launches": rr["info"]["n_launches"], "host_ms_per_call": round(rr["wall_ms"], 5),
                     "c_caller": rr.get("c_loop"),
+                    "c_caller_fresh_buffers": rr.get("c_loop_fresh"),
                     "timing": "median of batches of 100 calls" if tiny else "median of batches of 10 calls"}
             del o2, d2
             torch.cuda.empty_cache()

@@ -290,8 +290,28 @@ static constexpr size_t kMaxCachedObjectBytes = (size_t)256 << 10;    // ... unl
                                                                       // 20 ns per input, the kernels object_bytes / 6.5 TB/s
 static constexpr size_t kMaxCachedScratch = (size_t)32 << 20;         // a recording keeps the scratch its launches use
 
+// A second level for the same kind of call over OTHER buffers (a serving loop that gets fresh output
+// buffers for every request): what the scheduler and the chain planner made of the shape - the one-launch
+// form of the program but for the objects' addresses - is kept under the key (device, order, k, degree,
+// op, type, sizes). A call that finds it fills in its addresses, stages the table and launches, without
+// planning anything. Only failure-free calls whose whole work was one launch of that form are kept.
+struct CallShape {
+    int device = 0, n = 0, k = 0, op = 0, dtype = 0;
+    size_t object_bytes = 0, chunk_bytes = 0;
+    int64_t degree = 0;
+    bool identity_order = true;
+    std::vector<int32_t> order;
+    ChainSkeleton skeleton;
+    hop_info_t info = {};
+    int status = HOP_OK;
+    uint64_t stamp = 0;
+};
+static std::vector<std::shared_ptr<CallShape>> g_shapes;
+static constexpr size_t kMaxCachedShapes = 32;
+
 static void free_cached_call(CachedCall *c)
 {
+    blocks_rejoin_pool(c->blocks.size());
     for (Block *b : c->blocks) release_block(b, c->last_stream);
     if (c->ev) (void)hipEventDestroy(c->ev);
     delete c;
@@ -373,20 +393,73 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
             return rc;
         }
     }
-    if ((rc = check_order(n, ready_order)) < 0) return rc;
+    std::shared_ptr<CallShape> known;
+    if (cacheable) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        for (const std::shared_ptr<CallShape> &c : g_shapes)
+            if (c->device == device && c->n == n && c->k == k && c->op == op && c->dtype == dtype && c->object_bytes == object_bytes &&
+                c->chunk_bytes == chunk_bytes && c->degree == d && c->identity_order == (ready_order == nullptr) &&
+                (!ready_order || std::memcmp(c->order.data(), ready_order, sizeof(int32_t) * (size_t)n) == 0)) {
+                known = c;
+                c->stamp = ++g_call_stamp;
+                break;
+            }
+    }
+    if (!known && (rc = check_order(n, ready_order)) < 0) return rc;      // a known shape's order was checked before
     if ((rc = check_buffers(objs, n, dsts, n_dst, object_bytes)) < 0) return rc;
     char *static_base = nullptr;
     if (no_alloc && (rc = static_scratch(device, &static_base)) < 0) return rc;
     try {
         GpuBackend be(device, (hipStream_t)stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype,
                       k, d, static_base, kStaticScratchBytes);
-        Scheduler s(n, k, shape.n_chunks, d, &be);
-        default_retention(s, shape, dtype);
         LaunchRecorder rec;
         hop_info_t my_info = {};
-        if (cacheable) set_launch_recorder(&rec);
-        rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, &my_info);
-        set_launch_recorder(nullptr);
+        bool planned = true;
+        if (known) {
+            // the shape's one launch with this call's addresses; anything in the way (an address that cannot be
+            // told from an offset, no room) sends the call down the whole path
+            set_launch_recorder(&rec);
+            rc = be.launch_skeleton(known->skeleton, 0, object_bytes);
+            set_launch_recorder(nullptr);
+            if (rc == HOP_OK) {
+                planned = false;
+                my_info = known->info;
+                rc = known->status;
+            } else if (rc < 0 && rc != HOP_ERR_INVALID) {
+                return rc;
+            } else {
+                rec = LaunchRecorder();
+            }
+        }
+        if (planned) {
+            Scheduler s(n, k, shape.n_chunks, d, &be);
+            default_retention(s, shape, dtype);
+            if (cacheable) set_launch_recorder(&rec);
+            rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, &my_info);
+            set_launch_recorder(nullptr);
+            if (cacheable && !known && rc >= 0) {
+                const ChainSkeleton *sk = be.sole_skeleton(my_info.n_launches);
+                if (sk) {
+                    auto c = std::make_shared<CallShape>();
+                    c->device = device; c->n = n; c->k = k; c->op = op; c->dtype = dtype;
+                    c->object_bytes = object_bytes; c->chunk_bytes = chunk_bytes; c->degree = d;
+                    c->identity_order = ready_order == nullptr;
+                    if (ready_order) c->order.assign(ready_order, ready_order + n);
+                    c->skeleton = *sk;
+                    c->info = my_info;
+                    c->status = rc;
+                    std::lock_guard<std::mutex> lk(g_mu);
+                    c->stamp = ++g_call_stamp;
+                    g_shapes.push_back(c);
+                    if (g_shapes.size() > kMaxCachedShapes) {
+                        size_t at = 0;
+                        for (size_t i = 1; i < g_shapes.size(); ++i)
+                            if (g_shapes[i]->stamp < g_shapes[at]->stamp) at = i;
+                        g_shapes.erase(g_shapes.begin() + (long)at);
+                    }
+                }
+            }
+        }
         if (info) *info = my_info;
         if (cacheable && rc >= 0 && !rec.unusable && !rec.launches.empty() && be.held_bytes() <= kMaxCachedScratch) {
             CachedCall *c = new CachedCall;
@@ -397,6 +470,7 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
             c->objs.assign(objs, objs + n);
             c->launches.swap(rec.launches);
             c->blocks = be.detach_blocks();
+            blocks_leave_pool(c->blocks.size());
             c->info = my_info;
             c->status = rc;
             c->last_stream = (hipStream_t)stream;
@@ -978,6 +1052,7 @@ int hop_shutdown(void)
         {
             std::lock_guard<std::mutex> lk(g_mu);
             calls.swap(g_calls);
+            g_shapes.clear();
         }
         for (CachedCall *c : calls) free_cached_call(c);
     }

@@ -484,7 +484,8 @@ template <int DT, int OP> __device__ __forceinline__ typename Traits<DT>::acc_t 
 // A value in LDS: W accumulators per lane, the value at byte offset b of the LDS array at
 // [b + lane * W * 4].
 template <int DT, int OP, bool TAIL>
-__device__ __forceinline__ void chains_body(const ChainArgs &a, typename Traits<DT>::acc_t *lds, const size_t off, const bool live)
+__device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *const table, typename Traits<DT>::acc_t *lds,
+                                            const size_t off, const bool live)
 {
     using T = Traits<DT>;
     using A = typename T::acc_t;
@@ -504,7 +505,7 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, typename Traits<
     __syncthreads();
     for (int p = 0; p < a.base.n_entries; ++p) {
         for (uint32_t c = a.pass_begin[p] + (uint32_t)team; c < a.pass_begin[p + 1]; c += kChainTeams) {
-            const uint4 *const rec = (const uint4 *)a.base.prog + (size_t)c * (kChainRecordWords / 2);
+            const uint4 *const rec = table + (size_t)c * (kChainRecordWords / 2);
             uint64_t word[kChainRecordWords];
 #pragma unroll
             for (int j = 0; j < kChainRecordWords / 2; ++j) {
@@ -586,8 +587,9 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, typename Traits<
     }
 }
 
+// The column (or, behind the last column, the elements after the last full vector) that this workgroup owns.
 template <int DT, int OP>
-__global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains(const ChainArgs a)
+__device__ __forceinline__ void chains_workgroup(const ChainArgs &a, const uint4 *const table)
 {
     using T = Traits<DT>;
     extern __shared__ __align__(16) unsigned char chain_values[];
@@ -597,13 +599,26 @@ __global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains(const Chai
     if (blockIdx.x < n_cols) {
         const size_t v = (size_t)blockIdx.x * kChainLanes + lane;
         const bool live = v < a.base.n_vec;
-        chains_body<DT, OP, false>(a, lds, a.base.byte_begin + (live ? v : a.base.n_vec - 1) * 16, live);
+        chains_body<DT, OP, false>(a, table, lds, a.base.byte_begin + (live ? v : a.base.n_vec - 1) * 16, live);
     } else {
         // the workgroups after the last column: the elements behind the last full vector, one per lane
         const size_t i = (blockIdx.x - n_cols) * kChainLanes + lane;
         const bool live = i < (size_t)a.base.n_tail;
-        chains_body<DT, OP, true>(a, lds, a.base.byte_begin + a.base.n_vec * 16 + (live ? i : 0) * T::ES, live);
+        chains_body<DT, OP, true>(a, table, lds, a.base.byte_begin + a.base.n_vec * 16 + (live ? i : 0) * T::ES, live);
     }
+}
+
+// The table in device memory (a.base.prog) ...
+template <int DT, int OP>
+__global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains(const ChainArgs a)
+{
+    chains_workgroup<DT, OP>(a, (const uint4 *)a.base.prog);
+}
+// ... or inside the kernel arguments: nothing is staged ahead of the launch.
+template <int DT, int OP, int WORDS>
+__global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains_inline(const ChainArgsInline<WORDS> a)
+{
+    chains_workgroup<DT, OP>(a.base, (const uint4 *)&a.table[0]);
 }
 
 // Layout of a kept partial result: one accumulator-typed value (4 bytes) per element of the

@@ -41,6 +41,18 @@ constexpr size_t kChainMaxBytes = 64u << 10;        // at most 1024 columns
 constexpr int kChainMinCut = 4;
 constexpr size_t kChainMaxWork = 3072;              // columns x rounds
 
+// The one-launch form of a program, complete but for the objects' addresses: the table of
+// launch_reduce_chains with kSkeletonObject | object index where an object's address belongs. A call
+// of the same shape over other buffers needs only these filled in (GpuBackend::launch_skeleton).
+constexpr uint64_t kSkeletonObject = 1ull << 63;
+struct ChainSkeleton {
+    std::vector<uint64_t> table;
+    std::vector<uint32_t> pass_begin;
+    int n_slots = 0, n_chains = 0;
+    size_t rounds = 0;                           // chains a team folds one after the other, summed over the passes
+    size_t n_steps = 0;                          // of the program it stands for
+};
+
 class GpuBackend : public Backend {
 public:
     // static_base != nullptr: all device scratch comes from [static_base, static_base + static_cap) and
@@ -77,6 +89,7 @@ public:
         dev_version_ = 0;
         chain_version_ = 0;
         chain_table_ = nullptr;
+        chain_host_table_.clear();
         return ws_.detach();
     }
     size_t held_bytes() const { return ws_.held_bytes(); }
@@ -373,88 +386,129 @@ private:
 
     int launch_chains(const std::vector<Entry> &prog, uint64_t version, size_t b0, size_t b1)
     {
-        const size_t columns = (b1 - b0 + 16 * kChainLanes - 1) / (16 * kChainLanes);
         if (version != chain_version_) {
             // the plan is made once per program; the table only when a launch is short enough to use it
             chain_version_ = version;
             chain_table_ = nullptr;
-            chain_usable_ = false;
-            ChainPlan &cp = chain_plan_;
-            if (!plan_chains(prog, kChainMinCut, kChainMaxItems, cp)) return HOP_PARTIAL;
-            // worth it only if the longest path through the chains is much shorter than the program
-            if (cp.n_passes > kMaxChainPasses || cp.critical_steps * 2 > (int64_t)prog.size()) return HOP_PARTIAL;
-            std::vector<int> per_pass((size_t)cp.n_passes, 0);
-            for (int32_t ps : cp.pass) per_pass[(size_t)ps]++;
-            chain_rounds_ = 0;
-            for (int cnt : per_pass) chain_rounds_ += (size_t)((cnt + kChainTeams - 1) / kChainTeams);
-            chain_usable_ = true;
+            chain_host_table_.clear();
+            chain_usable_ = build_skeleton(prog, skeleton_);
         }
-        if (!chain_usable_ || columns * chain_rounds_ > kChainMaxWork) return HOP_PARTIAL;
-        if (!chain_table_) {
-            chain_usable_ = false;               // until the table stands
-            const ChainPlan &cp = chain_plan_;
-            const size_t n_chains = cp.n_chains();
-            // chains in pass order; a value's LDS slot is taken when its chain's pass starts and is free
-            // again from the pass after the one that reads it
-            std::vector<int32_t> order(n_chains);
-            for (size_t g = 0; g < n_chains; ++g) order[g] = (int32_t)g;
-            std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cp.pass[(size_t)x] < cp.pass[(size_t)y]; });
-            std::vector<uint32_t> slot(n_chains, kChainFinal), free_slots, freed;
-            uint32_t n_slots = 0;
-            chain_pass_begin_.assign((size_t)cp.n_passes + 1, 0);
-            std::vector<uint64_t> table(n_chains * (size_t)kChainRecordWords);
-            const uint64_t value_bytes = chain_value_bytes(dtype_);
-            constexpr uint64_t kIdentityPending = 0xfffffffeu;       // no object's address and no value's offset
-            size_t at = 0;
-            for (int pass = 0; pass < cp.n_passes; ++pass) {
-                chain_pass_begin_[(size_t)pass] = (uint32_t)at;
-                free_slots.insert(free_slots.end(), freed.begin(), freed.end());
-                freed.clear();
-                for (size_t i = at; i < n_chains && cp.pass[(size_t)order[i]] == pass; ++i) {
-                    const size_t g = (size_t)order[i];
-                    if (g + 1 == n_chains) continue;                   // the result goes to memory
-                    if (free_slots.empty()) slot[g] = n_slots++;
-                    else { slot[g] = free_slots.back(); free_slots.pop_back(); }
-                }
-                for (; at < n_chains && cp.pass[(size_t)order[at]] == pass; ++at) {
-                    const size_t g = (size_t)order[at];
-                    const int32_t begin = cp.begin[g], n = cp.begin[g + 1] - begin;
-                    uint64_t *rec = table.data() + at * (size_t)kChainRecordWords;
-                    rec[0] = slot[g] == kChainFinal ? (uint64_t)kChainFinal : (uint64_t)slot[g] * value_bytes;
-                    for (int32_t t = 0; t < n; ++t) {
-                        const int32_t item = cp.items[(size_t)(begin + t)];
-                        if (item >= 0) {
-                            const uint64_t address = (uint64_t)(uintptr_t)objs_[(size_t)item];
-                            if ((address >> 32) == 0) return HOP_PARTIAL;      // would read as a value's offset
-                            rec[1 + t] = address;
-                        } else {
-                            rec[1 + t] = (uint64_t)slot[(size_t)(-item - 1)] * value_bytes;
-                            freed.push_back(slot[(size_t)(-item - 1)]);
-                        }
-                    }
-                    for (int32_t t = n; t < kChainMaxItems; ++t) rec[1 + t] = kIdentityPending;
-                }
-            }
-            chain_pass_begin_[(size_t)cp.n_passes] = (uint32_t)at;
-            if ((int)n_slots > chain_slots_max(dtype_)) return HOP_PARTIAL;
-            // the identity value takes the place behind the last value
-            for (uint64_t &word : table)
-                if (word == kIdentityPending) word = (uint64_t)n_slots * value_bytes;
-            // without the right to allocate, a table that does not fit beside the whole program (which the
-            // plain path then has to stage) is not made
-            const size_t bytes = table.size() * sizeof(uint64_t);
-            if (ws_.is_static() && bytes + prog.size() * sizeof(DevEntry) + 512 > ws_.static_left()) return HOP_PARTIAL;
-            chain_table_ = (const uint64_t *)ws_.stage(table.data(), bytes);
-            if (!chain_table_) return ws_.error();
-            chain_slots_ = (int)n_slots;
-            chain_count_ = (int)n_chains;
-            chain_usable_ = true;
-        }
-        const hipError_t e = launch_reduce_chains(stream_, dtype_, op_, chain_table_, chain_count_, chain_slots_,
-                                                  chain_pass_begin_.data(), (int)chain_pass_begin_.size() - 1, dsts_[0], b0, b1);
-        return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
+        if (!chain_usable_) return HOP_PARTIAL;
+        const int rc = launch_skeleton(skeleton_, b0, b1);
+        if (rc == HOP_OK) ++chain_launches_;
+        return rc;
     }
 
+    // The program as chains (plan_chains), in pass order, with LDS places for their values: a value's
+    // place is taken when its chain's pass starts and is free again from the pass after the one that
+    // reads it. False if the program has no such form or it would not pay.
+    bool build_skeleton(const std::vector<Entry> &prog, ChainSkeleton &sk) const
+    {
+        sk = ChainSkeleton();
+        ChainPlan cp;
+        if (!plan_chains(prog, kChainMinCut, kChainMaxItems, cp)) return false;
+        // worth it only if the longest path through the chains is much shorter than the program
+        if (cp.n_passes > kMaxChainPasses || cp.critical_steps * 2 > (int64_t)prog.size()) return false;
+        const size_t n_chains = cp.n_chains();
+        std::vector<int> per_pass((size_t)cp.n_passes, 0);
+        for (int32_t ps : cp.pass) per_pass[(size_t)ps]++;
+        for (int cnt : per_pass) sk.rounds += (size_t)((cnt + kChainTeams - 1) / kChainTeams);
+        std::vector<int32_t> order(n_chains);
+        for (size_t g = 0; g < n_chains; ++g) order[g] = (int32_t)g;
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cp.pass[(size_t)x] < cp.pass[(size_t)y]; });
+        std::vector<uint32_t> slot(n_chains, kChainFinal), free_slots, freed;
+        uint32_t n_slots = 0;
+        sk.pass_begin.assign((size_t)cp.n_passes + 1, 0);
+        sk.table.assign(n_chains * (size_t)kChainRecordWords, 0);
+        const uint64_t value_bytes = chain_value_bytes(dtype_);
+        constexpr uint64_t kIdentityPending = 0xfffffffeu;       // no object, no value's offset, no result mark
+        size_t at = 0;
+        for (int pass = 0; pass < cp.n_passes; ++pass) {
+            sk.pass_begin[(size_t)pass] = (uint32_t)at;
+            free_slots.insert(free_slots.end(), freed.begin(), freed.end());
+            freed.clear();
+            for (size_t i = at; i < n_chains && cp.pass[(size_t)order[i]] == pass; ++i) {
+                const size_t g = (size_t)order[i];
+                if (g + 1 == n_chains) continue;                   // the result goes to memory
+                if (free_slots.empty()) slot[g] = n_slots++;
+                else { slot[g] = free_slots.back(); free_slots.pop_back(); }
+            }
+            for (; at < n_chains && cp.pass[(size_t)order[at]] == pass; ++at) {
+                const size_t g = (size_t)order[at];
+                const int32_t begin = cp.begin[g], n = cp.begin[g + 1] - begin;
+                uint64_t *rec = sk.table.data() + at * (size_t)kChainRecordWords;
+                rec[0] = slot[g] == kChainFinal ? (uint64_t)kChainFinal : (uint64_t)slot[g] * value_bytes;
+                for (int32_t t = 0; t < n; ++t) {
+                    const int32_t item = cp.items[(size_t)(begin + t)];
+                    if (item >= 0) {
+                        rec[1 + t] = kSkeletonObject | (uint64_t)item;
+                    } else {
+                        rec[1 + t] = (uint64_t)slot[(size_t)(-item - 1)] * value_bytes;
+                        freed.push_back(slot[(size_t)(-item - 1)]);
+                    }
+                }
+                for (int32_t t = n; t < kChainMaxItems; ++t) rec[1 + t] = kIdentityPending;
+            }
+        }
+        sk.pass_begin[(size_t)cp.n_passes] = (uint32_t)at;
+        if ((int)n_slots > chain_slots_max(dtype_)) return false;
+        // the identity value takes the place behind the last value
+        for (uint64_t &word : sk.table)
+            if (word == kIdentityPending) word = (uint64_t)n_slots * value_bytes;
+        sk.n_slots = (int)n_slots;
+        sk.n_chains = (int)n_chains;
+        sk.n_steps = prog.size();
+        return true;
+    }
+
+public:
+    // One launch of a skeleton over [b0, b1) of this back end's objects: their addresses go into a copy of
+    // the table, which is staged once per back end. HOP_PARTIAL if the launch is too long for this form
+    // or an address cannot be told from a value's offset.
+    int launch_skeleton(const ChainSkeleton &sk, size_t b0, size_t b1)
+    {
+        const size_t columns = (b1 - b0 + 16 * kChainLanes - 1) / (16 * kChainLanes);
+        if (b1 - b0 > kChainMaxBytes || columns * sk.rounds > kChainMaxWork) return HOP_PARTIAL;
+        if (!chain_table_ && chain_host_table_.empty()) {
+            std::vector<uint64_t> table(sk.table);
+            for (uint64_t &word : table) {
+                if (!(word & kSkeletonObject)) continue;
+                const size_t index = (size_t)(word & ~kSkeletonObject);
+                if (index >= objs_.size()) return HOP_ERR_INVALID;
+                word = (uint64_t)(uintptr_t)objs_[index];
+                if ((word >> 32) == 0) return HOP_PARTIAL;         // would read as a value's offset
+            }
+            chain_host_table_.swap(table);
+        }
+        // a table of up to 256 chains rides in the kernel arguments; a longer one (or any, once the runtime has
+        // refused such arguments) is staged once per back end
+        for (int attempt = 0; attempt < 2; ++attempt) {
+            const bool inl = chain_table_inline(sk.n_chains);
+            if (!inl && !chain_table_) {
+                // without the right to allocate, a table that does not fit beside the whole program (which the
+                // plain path then has to stage) is not made
+                const size_t bytes = chain_host_table_.size() * sizeof(uint64_t);
+                if (ws_.is_static() && bytes + sk.n_steps * sizeof(DevEntry) + 512 > ws_.static_left()) return HOP_PARTIAL;
+                chain_table_ = (const uint64_t *)ws_.stage(chain_host_table_.data(), bytes);
+                if (!chain_table_) return ws_.error();
+            }
+            const hipError_t e = launch_reduce_chains(stream_, dtype_, op_, chain_table_, sk.n_chains, sk.n_slots,
+                                                      sk.pass_begin.data(), (int)sk.pass_begin.size() - 1, dsts_[0], b0, b1,
+                                                      inl ? chain_host_table_.data() : nullptr);
+            if (e == hipSuccess) return HOP_OK;
+            if (!inl || chain_table_inline(sk.n_chains)) return HOP_ERR_DEVICE;
+            (void)hipGetLastError();                               // refused as arguments: once more, staged
+        }
+        return HOP_ERR_DEVICE;
+    }
+    // The skeleton of the program in force if every launch so far was one launch of it (a failure-free call
+    // over many small objects), else null.
+    const ChainSkeleton *sole_skeleton(int n_launches) const
+    {
+        return chain_usable_ && chain_launches_ == n_launches && n_launches > 0 ? &skeleton_ : nullptr;
+    }
+
+private:
     DevEntry resolve(const Entry &e, const char *partials, size_t part_bytes, size_t b0) const
     {
         DevEntry d;
@@ -477,13 +531,12 @@ private:
     void *const *dev_extra_ = nullptr;
     unsigned extra_residue_ = 0;                // address modulo 128 shared by (most of) the other destinations
     uint64_t dev_version_ = 0;
-    uint64_t chain_version_ = 0;                // the program whose chain table chain_table_ is (null: it has none)
-    const uint64_t *chain_table_ = nullptr;
-    std::vector<uint32_t> chain_pass_begin_;
-    int chain_slots_ = 0, chain_count_ = 0;
-    size_t chain_rounds_ = 0;
-    ChainPlan chain_plan_;
+    uint64_t chain_version_ = 0;                // the program whose one-launch form skeleton_ is
+    const uint64_t *chain_table_ = nullptr;     // its table with this back end's objects, staged (null: not yet, or not needed)
+    std::vector<uint64_t> chain_host_table_;    // the same in host memory
+    ChainSkeleton skeleton_;
     bool chain_usable_ = false;
+    int chain_launches_ = 0;
     int depth_ = 1;
     int device_;
     DevBuf *spill_buf_ = nullptr;

@@ -81,6 +81,15 @@ struct ChainArgs {
     uint32_t identity_at;      // LDS byte offset of the identity value (behind the chains' values)
     uint32_t pass_begin[kMaxChainPasses + 1];      // pass p evaluates the chains [pass_begin[p], pass_begin[p + 1])
 };
+// The same with the table inside the kernel arguments. This runtime takes argument blocks far beyond
+// the 4 KiB of older ones (64 KiB were tried); a launch that is refused falls back to the staged table
+// for good (launch_reduce_chains). Two sizes, so that a small table does not cost a large copy.
+template <int WORDS> struct ChainArgsInline {
+    ChainArgs base;
+    alignas(16) uint64_t table[WORDS];
+};
+constexpr int kChainInlineWordsSmall = 2048;       // 85 chains, 16 KiB
+constexpr int kChainInlineWordsLarge = 6144;       // 256 chains, 48 KiB
 
 struct CopyArgs {
     const void *src;
@@ -161,11 +170,15 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
                               int sub_entries, int n_subs, size_t byte_begin, size_t byte_end);
 
 // The program as chains in one launch: dev_table as described at ChainArgs (n_chains records, written for
-// values of chain_value_bytes(dtype) bytes each), n_slots = values alive at most at one time; the identity
+// values of chain_value_bytes(dtype) bytes each) or, for tables that ride in the kernel arguments, host_table (the
+// same in host memory), n_slots = values alive at most at one time; the identity
 // value takes the place behind them. hipErrorInvalidValue if that is more LDS than a workgroup gets.
 hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uint64_t *dev_table, int n_chains,
                                 int n_slots, const uint32_t *pass_begin, int n_passes, void *dst,
-                                size_t byte_begin, size_t byte_end);
+                                size_t byte_begin, size_t byte_end, const uint64_t *host_table = nullptr);
+// Whether a table of n_chains records rides in the kernel arguments (then launch_reduce_chains needs
+// host_table only, else dev_table).
+bool chain_table_inline(int n_chains);
 // LDS bytes of one chain's value, and the number of values a launch_reduce_chains may keep alive at
 // one time, for this element type.
 size_t chain_value_bytes(int dtype);

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <utility>
@@ -52,7 +53,7 @@ const char *kernel_config()
            "launches that keep or read partial results: one step at a time, 4|2|1 vectors/lane, pieces 64 KiB apart from 2048 "
            "tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators indexed like the elements, nontemporal; "
            "programs of 48 steps or more over at most 64 KiB: one launch, 256 lanes per 64-byte column, chains of at most 23 items "
-           "folded by teams of 4 lanes with all their loads in flight, values in LDS";
+           "folded by teams of 4 lanes with all their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments";
 }
 
 static thread_local LaunchRecorder *tl_recorder = nullptr;
@@ -69,7 +70,9 @@ template <class Args>
 static hipError_t enqueue(void (*kernel)(Args), dim3 grid, unsigned lds, hipStream_t stream, const Args &a, bool writes_result,
                           unsigned threads = kThreads)
 {
-    if (tl_recorder) {
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, stream, a);
+    const hipError_t e = hipGetLastError();
+    if (tl_recorder && e == hipSuccess) {
         RecordedLaunch r;
         r.kernel = (const void *)kernel;
         r.grid_x = grid.x;
@@ -80,17 +83,17 @@ static hipError_t enqueue(void (*kernel)(Args), dim3 grid, unsigned lds, hipStre
         r.args.assign((const unsigned char *)&a, (const unsigned char *)&a + sizeof a);
         tl_recorder->launches.push_back(std::move(r));
     }
-    hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, stream, a);
-    return hipGetLastError();
+    return e;
 }
 
 hipError_t replay_launch(const RecordedLaunch &l, hipStream_t stream, void *dst)
 {
     // the argument block is copied so that the result pointer can be replaced (and because another
     // thread may replay the same recording)
-    static_assert(sizeof(ChainArgs) <= sizeof(ReduceArgsInline), "the largest argument block");
-    alignas(16) unsigned char block[sizeof(ReduceArgsInline)];
-    if (l.args.size() > sizeof block) return hipErrorInvalidValue;
+    static thread_local std::vector<uint64_t> copy;                    // 8-byte aligned, like every argument block here
+    if (l.args.size() < sizeof(ReduceArgs)) return hipErrorInvalidValue;
+    copy.resize((l.args.size() + 7) / 8);
+    unsigned char *block = (unsigned char *)copy.data();
     std::memcpy(block, l.args.data(), l.args.size());
     if (l.writes_result) ((ReduceArgs *)block)->dst = dst;
     void *params[1] = {block};
@@ -291,12 +294,31 @@ size_t chain_value_bytes(int dtype) { return (size_t)kChainLanes * (dtype == HOP
 
 int chain_slots_max(int dtype) { return (int)(kChainLdsBytes / chain_value_bytes(dtype)) - 1; }     // one place is the identity's
 
+// Tables ride in the kernel arguments until a launch with such an argument block is refused.
+static std::atomic<bool> g_inline_tables{true};
+
+bool chain_table_inline(int n_chains)
+{
+    return g_inline_tables.load(std::memory_order_relaxed) && n_chains >= 1 &&
+           (size_t)n_chains * kChainRecordWords <= (size_t)kChainInlineWordsLarge;
+}
+
+template <int WORDS>
+static hipError_t launch_chains_inline(void (*kernel)(ChainArgsInline<WORDS>), unsigned grid, unsigned lds, hipStream_t stream,
+                                       const ChainArgs &base, const uint64_t *host_table, size_t n_words)
+{
+    static thread_local ChainArgsInline<WORDS> a;          // tens of KiB: not on the stack of every caller
+    a.base = base;
+    std::memcpy(a.table, host_table, n_words * sizeof(uint64_t));
+    return enqueue(kernel, dim3(grid), lds, stream, a, true, kChainThreads);
+}
+
 hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uint64_t *dev_table, int n_chains,
                                 int n_slots, const uint32_t *pass_begin, int n_passes, void *dst,
-                                size_t byte_begin, size_t byte_end)
+                                size_t byte_begin, size_t byte_end, const uint64_t *host_table)
 {
     if (byte_end <= byte_begin) return hipSuccess;
-    if (!dev_table || !pass_begin || n_chains < 1 || n_passes < 1 || n_passes > kMaxChainPasses || n_slots < 0 ||
+    if ((!dev_table && !host_table) || !pass_begin || n_chains < 1 || n_passes < 1 || n_passes > kMaxChainPasses || n_slots < 0 ||
         n_slots > chain_slots_max(dtype) || pass_begin[0] != 0 || pass_begin[n_passes] != (uint32_t)n_chains)
         return hipErrorInvalidValue;
     const Launcher l = pick(dtype, op, 1);
@@ -312,6 +334,15 @@ hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uin
     const size_t grid = n_cols + ((size_t)a.base.n_tail + kChainLanes - 1) / kChainLanes;
     if (grid > kMaxGrid) return hipErrorInvalidValue;       // one column per workgroup: the kernel does not loop
     const unsigned lds = (unsigned)(((size_t)n_slots + 1) * chain_value_bytes(dtype));
+    if (host_table && chain_table_inline(n_chains)) {
+        const size_t n_words = (size_t)n_chains * kChainRecordWords;
+        const hipError_t e = n_words <= (size_t)kChainInlineWordsSmall
+                                 ? launch_chains_inline(l.chains_inl_small, (unsigned)grid, lds, stream, a, host_table, n_words)
+                                 : launch_chains_inline(l.chains_inl_large, (unsigned)grid, lds, stream, a, host_table, n_words);
+        if (e == hipSuccess) return e;
+        g_inline_tables.store(false, std::memory_order_relaxed);      // this runtime refuses the argument block
+    }
+    if (!dev_table) return hipErrorInvalidValue;            // the caller stages the table and calls again
     return enqueue(l.chains, dim3((unsigned)grid), lds, stream, a, true, kChainThreads);
 }
 

@@ -79,6 +79,8 @@ struct Launcher {
     void (*kept)(ReduceArgs);
     void (*kept_inl)(ReduceArgsInline);
     void (*chains)(ChainArgs);
+    void (*chains_inl_small)(ChainArgsInline<kChainInlineWordsSmall>);
+    void (*chains_inl_large)(ChainArgsInline<kChainInlineWordsLarge>);
     int vpt;
 };
 

@@ -112,6 +112,20 @@ static Block *acquire_block(int device, size_t bytes)
     return b;
 }
 
+// Blocks that a recording of a call takes with it (Workspace::detach) are no longer the pool's: they
+// do not count towards kMaxBlocks until they come back, or a process with many recordings would find
+// the pool "full" for good and wait for the GPU at every call that stages something.
+static void blocks_leave_pool(size_t n)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_block_count -= (int)n;
+}
+static void blocks_rejoin_pool(size_t n)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_block_count += (int)n;
+}
+
 static void release_block(Block *b, hipStream_t stream)
 {
     if (!b) return;
@@ -232,8 +246,18 @@ static bool poke(hipStream_t stream, void *dst, const void *src, size_t bytes)
     return true;
 }
 
+// Copies n_vec 16-byte vectors from pinned host memory (as the device addresses it) to device memory:
+// for a few KiB a kernel that reads over the host link starts sooner and costs the host less than a
+// copy-engine transfer queued ahead of the kernels that need the data (workload 5's 12 KiB table: the
+// call that has to stage it 24 -> 16 us).
+__global__ __launch_bounds__(256) void pull_kernel(uint4 *dst, const uint4 *src, size_t n_vec)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+constexpr size_t kPullMaxBytes = 64 * 1024;
+
 // Bump allocator over a list of blocks; everything staged is copied to the
-// device with one async copy per stage() call, ordered on the stream.
+// device with one copy per stage() call, ordered on the stream.
 //
 // Static mode (static_base given): every request is served from one caller-given stretch of
 // device memory, nothing is allocated, and staged data travels through kernel arguments. A
@@ -304,8 +328,14 @@ public:
         }
         Block *b = blocks_.back();
         std::memcpy(b->host + used_, src, bytes);
-        if (hipMemcpyAsync(b->dev + used_, b->host + used_, bytes, hipMemcpyHostToDevice, stream_) != hipSuccess)
+        if (bytes <= kPullMaxBytes) {
+            const size_t n_vec = (bytes + 15) / 16;           // requests are rounded up to 256 bytes: the tail is the block's
+            hipLaunchKernelGGL(pull_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, stream_, (uint4 *)(b->dev + used_),
+                               (const uint4 *)(b->host_dev + used_), n_vec);
+            if (hipGetLastError() != hipSuccess) return nullptr;
+        } else if (hipMemcpyAsync(b->dev + used_, b->host + used_, bytes, hipMemcpyHostToDevice, stream_) != hipSuccess) {
             return nullptr;
+        }
         void *d = b->dev + used_;
         used_ += need;
         return d;

@@ -1386,6 +1386,52 @@ def test_repeated_small_calls_replay_their_recorded_launches_correctly():
     check(objs, order, w.k, w.tree_degree)
 
 
+def test_a_known_shape_over_other_buffers_fills_in_the_addresses_only():
+    # a serving loop that gets fresh buffers for every request: the call's shape (order, k, degree, sizes) is
+    # known from an earlier call, only the addresses are new; the one-launch form is reused with them. Every
+    # call must read ITS objects (none of an earlier set), whatever mixture of known and new shapes comes by.
+    d = dev()
+    w = workloads.WORKLOADS[5]
+    order = w.ready_order()
+    rng = np.random.default_rng(77)
+
+    def fresh_set(n):
+        return [torch.from_numpy(rng.standard_normal(w.object_bytes // 4).astype(np.float32)).to(d) for _ in range(n)]
+
+    def check(objs_now, order_now, k, deg, op="sum"):
+        dst = torch.full_like(objs_now[0], -3)
+        rc, info = hop.hop_reduce(dst, objs_now, k, op, w.dtype, w.chunk_bytes, deg, order_now, None)
+        torch.cuda.synchronize()
+        orc, want, k_eff, _ = oracle.reduce([workloads.to_numpy(o) for o in objs_now], k, ORA_OP[op], oracle.F32,
+                                            w.chunk_bytes // 4, deg, order_now, None)
+        assert rc == orc == hop.HOP_OK and info["k_eff"] == k_eff and info["n_launches"] == 1
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want))
+        return info
+    sets = [fresh_set(w.n) for _ in range(4)]
+    first = check(sets[0], order, w.k, w.tree_degree)
+    for objs in sets[1:] + sets[:2]:                   # new addresses, then addresses seen before (recorded calls)
+        assert check(objs, order, w.k, w.tree_degree) == first
+    # what changes the schedule is another shape: other order, k, degree, op, number of objects
+    order2 = order.copy()
+    order2[[5, 9]] = order2[[9, 5]]
+    check(sets[2], order2, w.k, w.tree_degree)
+    check(sets[3], order2, w.k, w.tree_degree)
+    check(sets[1], order, w.k - 3, w.tree_degree)
+    check(sets[2], order, w.k, 5)
+    check(sets[3], order, w.k, w.tree_degree, op="max")
+    check(sets[0][:300], np.arange(300, dtype=np.int32), 280, 16)
+    check(sets[1][:300], None, 280, 16)                # the identity order given as no order: another key, same result
+    check(sets[2][:300], None, 280, 16)
+    # more shapes than are kept
+    for i in range(40):
+        check(sets[i % 4][:100 + i], None, 90 + i, 8)
+        check(sets[(i + 1) % 4][:100 + i], None, 90 + i, 8)
+    assert check(sets[3], order, w.k, w.tree_degree) == first
+    assert hop.hop_shutdown() == hop.HOP_OK
+    assert check(sets[2], order, w.k, w.tree_degree) == first
+    assert check(sets[1], order, w.k, w.tree_degree) == first
+
+
 def test_two_host_threads_on_their_own_streams_and_shutdown():
     import threading
     d = dev()
@@ -1445,12 +1491,13 @@ def test_objects_larger_than_4_gib_use_64_bit_offsets():
 
 
 def test_a_captured_call_that_would_need_cached_memory_is_refused():
-    # programs of more than 128 steps and chain tables are staged in blocks that go back to the library's cache
-    # when the call ends: a graph cannot own them, so under capture such a call fails loudly instead of leaving
-    # a graph whose replays read rewritten memory. hop_reduce_noalloc is the call for that (tested with its own).
+    # programs of more than 128 steps and long chain tables are staged in blocks that go back to the library's
+    # cache when the call ends: a graph cannot own them, so under capture such a call fails loudly instead of
+    # leaving a graph whose replays read rewritten memory. hop_reduce_noalloc is the call for that (tested with
+    # its own).
     d = dev()
-    for nbytes, n in ((4096, 300), (2 << 20, 200)):
-        w = workloads.WORKLOADS[5].scaled(nbytes, nbytes, n=n, k=n, tree_degree=8, order_seed=3, data_seed=4, fail={},
+    for nbytes, n in ((512, 6000), (2 << 20, 200)):         # more chains than ride in the kernel arguments; a staged program
+        w = workloads.WORKLOADS[5].scaled(nbytes, nbytes, n=n, k=n, tree_degree=16, order_seed=3, data_seed=4, fail={},
                                           name="captured", n_dst=0)
         objs = workloads.make_objects(w, device=d)
         dst = torch.zeros_like(objs[0])
@@ -1463,6 +1510,32 @@ def test_a_captured_call_that_would_need_cached_memory_is_refused():
         # outside the capture the same call works
         rc, _ = run_both(w, "sum", objs=objs)
         assert rc == hop.HOP_OK
+
+
+def test_a_call_over_many_small_objects_can_be_captured_when_its_table_rides_in_the_arguments():
+    # up to 256 chains travel inside the kernel arguments, which a graph node keeps: workload 5 through plain
+    # hop_reduce, recorded and replayed with other contents in the same buffers
+    d = dev()
+    w = workloads.WORKLOADS[5]
+    objs = workloads.make_objects(w, device=d)
+    order = w.ready_order()
+    dst = torch.zeros_like(objs[0])
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc, info = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
+    assert rc == hop.HOP_OK and info["n_launches"] == 1
+    rng = np.random.default_rng(19)
+    for rep in range(3):
+        for o in objs[::41]:
+            o.mul_(float(rng.uniform(0.5, 1.5)))
+        dst.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        _, want, _, _ = oracle.reduce([workloads.to_numpy(o) for o in objs], w.k, oracle.SUM, oracle.F32,
+                                      w.chunk_bytes // 4, w.tree_degree, order, None)
+        assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want)), rep
 
 
 @pytest.mark.parametrize("object_mib", [1, 49])
