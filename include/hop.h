@@ -58,8 +58,9 @@ typedef enum {
                                    than the caller's workspace (hop_session_set_workspace)   */
     HOP_ERR_CAPTURE = -8        /* the stream is being captured into a graph and the call
                                    would need memory from the library's caches (a staged
-                                   program of more than 128 steps, a table, saved
-                                   accumulators), which a replay of the graph would find
+                                   program of more than 128 steps, a table too long for the
+                                   kernel arguments, saved accumulators), which a replay of
+                                   the graph would find
                                    rewritten: use hop_reduce_noalloc, or a session with
                                    hop_session_set_workspace                                 */
 } hop_status_t;
