@@ -83,12 +83,14 @@ struct ChainArgs {
 };
 // The same with the table inside the kernel arguments. This runtime takes argument blocks far beyond
 // the 4 KiB of older ones (64 KiB were tried); a launch that is refused falls back to the staged table
-// for good (launch_reduce_chains). Two sizes, so that a small table does not cost a large copy.
+// for good (launch_reduce_chains). Three sizes, so that a small table does not cost a large copy (the
+// runtime copies the whole block at every launch: 4 KiB more cost the host about 0.5 us).
 template <int WORDS> struct ChainArgsInline {
     ChainArgs base;
     alignas(16) uint64_t table[WORDS];
 };
-constexpr int kChainInlineWordsSmall = 2048;       // 85 chains, 16 KiB
+constexpr int kChainInlineWordsSmall = 1536;       // 64 chains, 12 KiB
+constexpr int kChainInlineWordsMid = 3072;         // 128 chains, 24 KiB
 constexpr int kChainInlineWordsLarge = 6144;       // 256 chains, 48 KiB
 
 struct CopyArgs {
@@ -133,7 +135,7 @@ struct LaunchRecorder {
     bool unusable = false;
 };
 void set_launch_recorder(LaunchRecorder *r);          // per host thread; nullptr = none
-hipError_t replay_launch(const RecordedLaunch &l, hipStream_t stream, void *dst);
+hipError_t replay_launch(RecordedLaunch &l, hipStream_t stream, void *dst);       // one thread at a time per recording
 
 // Launch shape of the kernels, as text.
 const char *kernel_config();

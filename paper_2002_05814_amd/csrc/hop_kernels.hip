@@ -86,16 +86,13 @@ static hipError_t enqueue(void (*kernel)(Args), dim3 grid, unsigned lds, hipStre
     return e;
 }
 
-hipError_t replay_launch(const RecordedLaunch &l, hipStream_t stream, void *dst)
+hipError_t replay_launch(RecordedLaunch &l, hipStream_t stream, void *dst)
 {
-    // the argument block is copied so that the result pointer can be replaced (and because another
-    // thread may replay the same recording)
-    static thread_local std::vector<uint64_t> copy;                    // 8-byte aligned, like every argument block here
+    // the result pointer is replaced in the recorded block itself (the runtime copies the block at the launch;
+    // the caller lets one thread at a time use a recording)
     if (l.args.size() < sizeof(ReduceArgs)) return hipErrorInvalidValue;
-    copy.resize((l.args.size() + 7) / 8);
-    unsigned char *block = (unsigned char *)copy.data();
-    std::memcpy(block, l.args.data(), l.args.size());
-    if (l.writes_result) ((ReduceArgs *)block)->dst = dst;
+    unsigned char *block = l.args.data();
+    if (l.writes_result) std::memcpy(block + offsetof(ReduceArgs, dst), &dst, sizeof dst);
     void *params[1] = {block};
     return hipLaunchKernel(l.kernel, dim3(l.grid_x, l.grid_y), dim3(l.threads), params, l.lds, stream);
 }
@@ -338,6 +335,8 @@ hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uin
         const size_t n_words = (size_t)n_chains * kChainRecordWords;
         const hipError_t e = n_words <= (size_t)kChainInlineWordsSmall
                                  ? launch_chains_inline(l.chains_inl_small, (unsigned)grid, lds, stream, a, host_table, n_words)
+                             : n_words <= (size_t)kChainInlineWordsMid
+                                 ? launch_chains_inline(l.chains_inl_mid, (unsigned)grid, lds, stream, a, host_table, n_words)
                                  : launch_chains_inline(l.chains_inl_large, (unsigned)grid, lds, stream, a, host_table, n_words);
         if (e == hipSuccess) return e;
         g_inline_tables.store(false, std::memory_order_relaxed);      // this runtime refuses the argument block

@@ -80,6 +80,7 @@ struct Launcher {
     void (*kept_inl)(ReduceArgsInline);
     void (*chains)(ChainArgs);
     void (*chains_inl_small)(ChainArgsInline<kChainInlineWordsSmall>);
+    void (*chains_inl_mid)(ChainArgsInline<kChainInlineWordsMid>);
     void (*chains_inl_large)(ChainArgsInline<kChainInlineWordsLarge>);
     int vpt;
 };
