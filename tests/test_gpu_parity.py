@@ -1463,6 +1463,37 @@ def test_two_host_threads_on_their_own_streams_and_shutdown():
         t.join()
     assert not errors, errors
     torch.cuda.synchronize()
+    # the same with many small objects: every thread brings buffers of its own for one shape, so recordings and
+    # the shape's one-launch form are looked up, inserted and evicted from four threads at once
+    ws = workloads.WORKLOADS[5].scaled(2048, 2048, n=300, k=280, tree_degree=8, order_seed=9, data_seed=10, fail={},
+                                       name="threads_small", n_dst=0)
+    sorder = ws.ready_order()
+
+    def small_worker(seed):
+        try:
+            rng = np.random.default_rng(seed)
+            st = torch.cuda.Stream()
+            for rep in range(40):
+                vals = [rng.standard_normal(ws.object_bytes // 4).astype(np.float32) for _ in range(ws.n)]
+                sobjs = [torch.from_numpy(v).to(d) for v in vals]
+                sdst = torch.zeros_like(sobjs[0])
+                st.wait_stream(torch.cuda.current_stream())
+                rc, info = hop.hop_reduce(sdst, sobjs, ws.k, "sum", ws.dtype, ws.chunk_bytes, ws.tree_degree, sorder, None,
+                                          stream=st)
+                st.synchronize()
+                _, swant, _, _ = oracle.reduce(vals, ws.k, oracle.SUM, oracle.F32, ws.chunk_bytes // 4, ws.tree_degree,
+                                               sorder, None)
+                assert rc == hop.HOP_OK and np.array_equal(bits(workloads.to_numpy(sdst)), bits(swant)), rep
+        except Exception as e:            # noqa: BLE001 - reported to the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=small_worker, args=(100 + i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
     assert hop.hop_shutdown() == hop.HOP_OK          # cached workspaces freed; the library keeps working after
     dst = torch.zeros_like(objs[0])
     rc, _ = hop.hop_reduce(dst, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
