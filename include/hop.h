@@ -146,8 +146,8 @@ int hop_reduce(void *dst, const void *const *objs, int n, size_t object_bytes,
  * forbid hipMalloc. Same arguments, same result bits, same status codes as
  * hop_reduce, but the call allocates and frees nothing on the device and
  * calls no allocating library routine: whatever device scratch the kernels
- * need (programs of more than 128 steps; the partial results and
- * sub-programs of a reduce over many small objects) lives in one static
+ * need (programs of more than 128 steps; long chain tables, partial results
+ * and sub-programs of a reduce over many small objects) lives in one static
  * device array of hop_noalloc_scratch_bytes() bytes (8 MiB) that every GPU
  * the library runs on holds until the process ends, and programs and tables
  * reach it through kernel arguments instead of a staging buffer.
