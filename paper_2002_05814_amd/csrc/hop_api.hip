@@ -281,6 +281,7 @@ struct CachedCall {
     hipEvent_t ev = nullptr;
     bool in_use = false;
     uint64_t stamp = 0;
+    size_t held = 0;                    // device bytes of `blocks`
 };
 static std::vector<CachedCall *> g_calls;
 static uint64_t g_call_stamp = 0;
@@ -289,6 +290,8 @@ static constexpr size_t kMaxCachedInputBytes = (size_t)64 << 20;      // larger 
 static constexpr size_t kMaxCachedObjectBytes = (size_t)256 << 10;    // ... unless their objects are small: planning takes about
                                                                       // 20 ns per input, the kernels object_bytes / 6.5 TB/s
 static constexpr size_t kMaxCachedScratch = (size_t)32 << 20;         // a recording keeps the scratch its launches use
+static constexpr size_t kMaxCachedScratchTotal = (size_t)1 << 30;     // ... all recordings together (device bytes; as many pinned)
+static size_t g_calls_held = 0;                                       // device bytes of the blocks the recordings hold
 
 // A second level for the same kind of call over OTHER buffers (a serving loop that gets fresh output
 // buffers for every request): what the scheduler and the chain planner made of the shape - the one-launch
@@ -469,27 +472,30 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
             if (ready_order) c->order.assign(ready_order, ready_order + n);
             c->objs.assign(objs, objs + n);
             c->launches.swap(rec.launches);
+            c->held = be.held_bytes();
             c->blocks = be.detach_blocks();
             blocks_leave_pool(c->blocks.size());
             c->info = my_info;
             c->status = rc;
             c->last_stream = (hipStream_t)stream;
-            CachedCall *victim = nullptr;
+            // the least recently used recordings make room: for the new one, and for what it holds
+            std::vector<CachedCall *> victims;
             {
                 std::lock_guard<std::mutex> lk(g_mu);
                 c->stamp = ++g_call_stamp;
                 g_calls.push_back(c);
-                if (g_calls.size() > kMaxCachedCalls) {
+                g_calls_held += c->held;
+                while (g_calls.size() > kMaxCachedCalls || g_calls_held > kMaxCachedScratchTotal) {
                     size_t at = g_calls.size();
                     for (size_t i = 0; i < g_calls.size(); ++i)
                         if (!g_calls[i]->in_use && g_calls[i] != c && (at == g_calls.size() || g_calls[i]->stamp < g_calls[at]->stamp)) at = i;
-                    if (at < g_calls.size()) {
-                        victim = g_calls[at];
-                        g_calls.erase(g_calls.begin() + (long)at);
-                    }
+                    if (at == g_calls.size()) break;
+                    victims.push_back(g_calls[at]);
+                    g_calls_held -= g_calls[at]->held;
+                    g_calls.erase(g_calls.begin() + (long)at);
                 }
             }
-            if (victim) free_cached_call(victim);
+            for (CachedCall *victim : victims) free_cached_call(victim);
         }
         return rc;
     } catch (const std::bad_alloc &) {
@@ -1052,6 +1058,7 @@ int hop_shutdown(void)
         {
             std::lock_guard<std::mutex> lk(g_mu);
             calls.swap(g_calls);
+            g_calls_held = 0;
             g_shapes.clear();
         }
         for (CachedCall *c : calls) free_cached_call(c);

@@ -1386,6 +1386,35 @@ def test_repeated_small_calls_replay_their_recorded_launches_correctly():
     check(objs, order, w.k, w.tree_degree)
 
 
+def test_recordings_that_hold_much_scratch_make_room_for_each_other():
+    # calls over thousands of medium objects are recorded with the partial results of their sub-programs (tens
+    # of MiB each); together the recordings may hold 1 GiB, then the least recently used ones go. 90 distinct
+    # calls (k differs) of about 15 MiB each pass that limit; every result, recorded, replayed or planned again
+    # after its recording went, equals the oracle's
+    d = dev()
+    w = workloads.WORKLOADS[5].scaled(128 << 10, 128 << 10, n=2000, k=2000, tree_degree=16, order_seed=21, data_seed=22,
+                                      fail={}, name="big_recordings", n_dst=0)
+    objs = workloads.make_objects(w, device=d)
+    host = [workloads.to_numpy(o) for o in objs]
+    order = w.ready_order()
+
+    def check(k, with_oracle):
+        dst = torch.full_like(objs[0], -1)
+        rc, info = hop.hop_reduce(dst, objs, k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
+        torch.cuda.synchronize()
+        assert rc == hop.HOP_OK and info["k_eff"] == k
+        if with_oracle:
+            _, want, _, _ = oracle.reduce(host, k, oracle.SUM, oracle.F32, w.chunk_bytes // 4, w.tree_degree, order, None)
+            assert np.array_equal(bits(workloads.to_numpy(dst)), bits(want)), k
+        return workloads.to_numpy(dst)
+    first = {}
+    for k in range(1900, 1990):
+        first[k] = check(k, k % 15 == 0)
+    for k in (1900, 1945, 1989, 1901):                  # gone and planned again, or still recorded: the same bits
+        assert np.array_equal(bits(check(k, False)), bits(first[k]))
+    assert hop.hop_shutdown() == hop.HOP_OK
+
+
 def test_a_known_shape_over_other_buffers_fills_in_the_addresses_only():
     # a serving loop that gets fresh buffers for every request: the call's shape (order, k, degree, sizes) is
     # known from an earlier call, only the addresses are new; the one-launch form is reused with them. Every
