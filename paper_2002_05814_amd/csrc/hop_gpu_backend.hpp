@@ -41,18 +41,6 @@ constexpr size_t kChainMaxBytes = 64u << 10;        // at most 1024 columns
 constexpr int kChainMinCut = 4;
 constexpr size_t kChainMaxWork = 3072;              // columns x rounds
 
-// The one-launch form of a program, complete but for the objects' addresses: the table of
-// launch_reduce_chains with kSkeletonObject | object index where an object's address belongs. A call
-// of the same shape over other buffers needs only these filled in (GpuBackend::launch_skeleton).
-constexpr uint64_t kSkeletonObject = 1ull << 63;
-struct ChainSkeleton {
-    std::vector<uint64_t> table;
-    std::vector<uint32_t> pass_begin;
-    int n_slots = 0, n_chains = 0;
-    size_t rounds = 0;                           // chains a team folds one after the other, summed over the passes
-    size_t n_steps = 0;                          // of the program it stands for
-};
-
 class GpuBackend : public Backend {
 public:
     // static_base != nullptr: all device scratch comes from [static_base, static_base + static_cap) and
@@ -399,66 +387,18 @@ private:
         return rc;
     }
 
-    // The program as chains (plan_chains), in pass order, with LDS places for their values: a value's
-    // place is taken when its chain's pass starts and is free again from the pass after the one that
-    // reads it. False if the program has no such form or it would not pay.
     bool build_skeleton(const std::vector<Entry> &prog, ChainSkeleton &sk) const
     {
-        sk = ChainSkeleton();
-        ChainPlan cp;
-        if (!plan_chains(prog, kChainMinCut, kChainMaxItems, cp)) return false;
-        // worth it only if the longest path through the chains is much shorter than the program
-        if (cp.n_passes > kMaxChainPasses || cp.critical_steps * 2 > (int64_t)prog.size()) return false;
-        const size_t n_chains = cp.n_chains();
-        std::vector<int> per_pass((size_t)cp.n_passes, 0);
-        for (int32_t ps : cp.pass) per_pass[(size_t)ps]++;
-        for (int cnt : per_pass) sk.rounds += (size_t)((cnt + kChainTeams - 1) / kChainTeams);
-        std::vector<int32_t> order(n_chains);
-        for (size_t g = 0; g < n_chains; ++g) order[g] = (int32_t)g;
-        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cp.pass[(size_t)x] < cp.pass[(size_t)y]; });
-        std::vector<uint32_t> slot(n_chains, kChainFinal), free_slots, freed;
-        uint32_t n_slots = 0;
-        sk.pass_begin.assign((size_t)cp.n_passes + 1, 0);
-        sk.table.assign(n_chains * (size_t)kChainRecordWords, 0);
-        const uint64_t value_bytes = chain_value_bytes(dtype_);
-        constexpr uint64_t kIdentityPending = 0xfffffffeu;       // no object, no value's offset, no result mark
-        size_t at = 0;
-        for (int pass = 0; pass < cp.n_passes; ++pass) {
-            sk.pass_begin[(size_t)pass] = (uint32_t)at;
-            free_slots.insert(free_slots.end(), freed.begin(), freed.end());
-            freed.clear();
-            for (size_t i = at; i < n_chains && cp.pass[(size_t)order[i]] == pass; ++i) {
-                const size_t g = (size_t)order[i];
-                if (g + 1 == n_chains) continue;                   // the result goes to memory
-                if (free_slots.empty()) slot[g] = n_slots++;
-                else { slot[g] = free_slots.back(); free_slots.pop_back(); }
-            }
-            for (; at < n_chains && cp.pass[(size_t)order[at]] == pass; ++at) {
-                const size_t g = (size_t)order[at];
-                const int32_t begin = cp.begin[g], n = cp.begin[g + 1] - begin;
-                uint64_t *rec = sk.table.data() + at * (size_t)kChainRecordWords;
-                rec[0] = slot[g] == kChainFinal ? (uint64_t)kChainFinal : (uint64_t)slot[g] * value_bytes;
-                for (int32_t t = 0; t < n; ++t) {
-                    const int32_t item = cp.items[(size_t)(begin + t)];
-                    if (item >= 0) {
-                        rec[1 + t] = kSkeletonObject | (uint64_t)item;
-                    } else {
-                        rec[1 + t] = (uint64_t)slot[(size_t)(-item - 1)] * value_bytes;
-                        freed.push_back(slot[(size_t)(-item - 1)]);
-                    }
-                }
-                for (int32_t t = n; t < kChainMaxItems; ++t) rec[1 + t] = kIdentityPending;
-            }
-        }
-        sk.pass_begin[(size_t)cp.n_passes] = (uint32_t)at;
-        if ((int)n_slots > chain_slots_max(dtype_)) return false;
-        // the identity value takes the place behind the last value
-        for (uint64_t &word : sk.table)
-            if (word == kIdentityPending) word = (uint64_t)n_slots * value_bytes;
-        sk.n_slots = (int)n_slots;
-        sk.n_chains = (int)n_chains;
-        sk.n_steps = prog.size();
-        return true;
+        ChainFormat f;
+        f.min_cut = kChainMinCut;
+        f.max_items = kChainMaxItems;
+        f.record_words = kChainRecordWords;
+        f.teams = kChainTeams;
+        f.max_passes = kMaxChainPasses;
+        f.value_bytes = chain_value_bytes(dtype_);
+        f.max_values = chain_slots_max(dtype_);
+        f.result_mark = kChainFinal;
+        return build_chain_skeleton(prog, f, sk);
     }
 
 public:

@@ -359,6 +359,87 @@ inline bool plan_chains(const std::vector<Entry> &prog, int min_cut, int max_ite
     return true;
 }
 
+// The one-launch form of a program, complete but for the objects' addresses: a table of one record of
+// record_words 8-byte words per chain, in pass order. Word 0 of a record: where the chain's value goes,
+// as a byte offset into the workgroup's array of values, or result_mark for the chain whose value is the
+// result. Words 1..max_items: the items - kSkeletonObject | object index where an object's address
+// belongs, or the byte offset of another chain's value - and behind the last item the offset of the
+// identity value, which sits behind all values. A value's place is taken when its chain's pass starts and
+// is free again from the pass after the one that reads it (every value is read exactly once).
+constexpr uint64_t kSkeletonObject = 1ull << 63;
+struct ChainSkeleton {
+    std::vector<uint64_t> table;
+    std::vector<uint32_t> pass_begin;            // pass p is the records [pass_begin[p], pass_begin[p + 1])
+    int n_slots = 0, n_chains = 0;               // places for values (the identity takes place n_slots), records
+    size_t rounds = 0;                           // chains a team folds one after the other, summed over the passes
+    size_t n_steps = 0;                          // of the program it stands for
+};
+struct ChainFormat {
+    int min_cut = 4, max_items = 23, record_words = 24, teams = 64, max_passes = 24, max_values = 1023;
+    uint64_t value_bytes = 64;
+    uint32_t result_mark = 0xffffffffu;
+};
+
+// False if the program has no such form (plan_chains), needs more passes or places than the format has, or
+// would not pay: the longest path through the chains must be at most half the program.
+inline bool build_chain_skeleton(const std::vector<Entry> &prog, const ChainFormat &f, ChainSkeleton &sk)
+{
+    sk = ChainSkeleton();
+    if (f.record_words < f.max_items + 1 || f.teams < 1) return false;
+    ChainPlan cp;
+    if (!plan_chains(prog, f.min_cut, f.max_items, cp)) return false;
+    if (cp.n_passes > f.max_passes || cp.critical_steps * 2 > (int64_t)prog.size()) return false;
+    const size_t n_chains = cp.n_chains();
+    std::vector<int> per_pass((size_t)cp.n_passes, 0);
+    for (int32_t ps : cp.pass) per_pass[(size_t)ps]++;
+    for (int cnt : per_pass) sk.rounds += (size_t)((cnt + f.teams - 1) / f.teams);
+    std::vector<int32_t> order(n_chains);
+    for (size_t g = 0; g < n_chains; ++g) order[g] = (int32_t)g;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cp.pass[(size_t)x] < cp.pass[(size_t)y]; });
+    constexpr uint32_t kNoSlot = 0xffffffffu;
+    std::vector<uint32_t> slot(n_chains, kNoSlot), free_slots, freed;
+    uint32_t n_slots = 0;
+    sk.pass_begin.assign((size_t)cp.n_passes + 1, 0);
+    sk.table.assign(n_chains * (size_t)f.record_words, 0);
+    constexpr uint64_t kIdentityPending = ~0ull >> 1;        // no object, no value's offset, no result mark
+    size_t at = 0;
+    for (int pass = 0; pass < cp.n_passes; ++pass) {
+        sk.pass_begin[(size_t)pass] = (uint32_t)at;
+        free_slots.insert(free_slots.end(), freed.begin(), freed.end());
+        freed.clear();
+        for (size_t i = at; i < n_chains && cp.pass[(size_t)order[i]] == pass; ++i) {
+            const size_t g = (size_t)order[i];
+            if (g + 1 == n_chains) continue;                   // the result goes to memory
+            if (free_slots.empty()) slot[g] = n_slots++;
+            else { slot[g] = free_slots.back(); free_slots.pop_back(); }
+        }
+        for (; at < n_chains && cp.pass[(size_t)order[at]] == pass; ++at) {
+            const size_t g = (size_t)order[at];
+            const int32_t begin = cp.begin[g], n = cp.begin[g + 1] - begin;
+            uint64_t *rec = sk.table.data() + at * (size_t)f.record_words;
+            rec[0] = slot[g] == kNoSlot ? (uint64_t)f.result_mark : (uint64_t)slot[g] * f.value_bytes;
+            for (int32_t t = 0; t < n; ++t) {
+                const int32_t item = cp.items[(size_t)(begin + t)];
+                if (item >= 0) {
+                    rec[1 + t] = kSkeletonObject | (uint64_t)item;
+                } else {
+                    rec[1 + t] = (uint64_t)slot[(size_t)(-item - 1)] * f.value_bytes;
+                    freed.push_back(slot[(size_t)(-item - 1)]);
+                }
+            }
+            for (int32_t t = n; t < f.record_words - 1; ++t) rec[1 + t] = kIdentityPending;
+        }
+    }
+    sk.pass_begin[(size_t)cp.n_passes] = (uint32_t)at;
+    if ((int64_t)n_slots > (int64_t)f.max_values) return false;
+    for (uint64_t &word : sk.table)
+        if (word == kIdentityPending) word = (uint64_t)n_slots * f.value_bytes;
+    sk.n_slots = (int)n_slots;
+    sk.n_chains = (int)n_chains;
+    sk.n_steps = prog.size();
+    return true;
+}
+
 // Accumulator levels a tree needs when every position is taken (holes only lower it).
 inline int full_tree_depth(int k, int64_t d)
 {

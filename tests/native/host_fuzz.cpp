@@ -189,12 +189,74 @@ static void check_marks(const std::vector<Entry> &prog)
     if (walk(p, true) != plain) { std::printf("marked walk builds another expression\n"); std::abort(); }
 }
 
+// The one-launch table of a program, run as the kernel runs it: pass by pass, values in numbered places; no
+// place is written while its value is still unread or is read in the same pass, every read finds a value of
+// an earlier pass, the padding is the identity's place, and the result is the program's. Returns 1 if the
+// program has such a table.
+static long check_skeleton(const std::vector<Entry> &prog)
+{
+
+            ChainFormat f;
+            f.min_cut = 1 + (int)(prog.size() % 6);
+            f.max_items = 2 + (int)(prog.size() % 23);
+            f.record_words = f.max_items + 1 + (int)(prog.size() % 3);
+            f.teams = 1 + (int)(prog.size() % 7);
+            f.value_bytes = 16u << (prog.size() % 3);
+            f.max_values = 1 << 20;
+            f.max_passes = 1 << 20;
+            ChainSkeleton sk;
+            if (build_chain_skeleton(prog, f, sk)) {
+                const std::string want = sym_eval(prog, 0, (int)prog.size(), {}, nullptr, nullptr, nullptr);
+                std::vector<std::string> place((size_t)sk.n_slots);
+                std::vector<int> written_in((size_t)sk.n_slots, -1);
+                std::string result;
+                bool has_result = false;
+                if (sk.table.size() != (size_t)sk.n_chains * (size_t)f.record_words || sk.pass_begin.back() != (uint32_t)sk.n_chains) { std::printf("table size\n"); std::abort(); }
+                for (size_t pass = 0; pass + 1 < sk.pass_begin.size(); ++pass) {
+                    std::vector<std::pair<size_t, std::string>> writes;
+                    std::vector<size_t> reads;
+                    for (uint32_t c = sk.pass_begin[pass]; c < sk.pass_begin[pass + 1]; ++c) {
+                        const uint64_t *rec = sk.table.data() + (size_t)c * (size_t)f.record_words;
+                        std::string acc;
+                        bool padding = false;
+                        for (int t = 1; t < f.record_words; ++t) {
+                            const uint64_t w = rec[t];
+                            std::string x;
+                            if (w & kSkeletonObject) x = "o" + std::to_string(w & ~kSkeletonObject);
+                            else {
+                                if (w % f.value_bytes) { std::printf("offset\n"); std::abort(); }
+                                const size_t sl = (size_t)(w / f.value_bytes);
+                                if (sl == (size_t)sk.n_slots) { padding = true; continue; }       // the identity
+                                if (sl > (size_t)sk.n_slots || written_in[sl] < 0 || written_in[sl] >= (int)pass || place[sl].empty()) { std::printf("reads a place nothing was put in\n"); std::abort(); }
+                                x = place[sl];
+                                reads.push_back(sl);
+                            }
+                            if (padding) { std::printf("an item behind the padding\n"); std::abort(); }
+                            acc = t == 1 ? x : "(" + acc + "+" + x + ")";
+                        }
+                        if (rec[0] == f.result_mark) { result = acc; has_result = true; if (c + 1 != (uint32_t)sk.n_chains) { std::printf("result is not last\n"); std::abort(); } }
+                        else writes.emplace_back((size_t)(rec[0] / f.value_bytes), acc);
+                    }
+                    for (size_t sl : reads) place[sl].clear();                                // read exactly once
+                    for (auto &wv : writes) {
+                        if (wv.first >= (size_t)sk.n_slots || !place[wv.first].empty()) { std::printf("writes over a live value\n"); std::abort(); }
+                        for (size_t sl : reads) if (sl == wv.first) { std::printf("writes a place read in the same pass\n"); std::abort(); }
+                        place[wv.first] = wv.second;
+                        written_in[wv.first] = (int)pass;
+                    }
+                }
+                if (!has_result || result != want) { std::printf("the table gives %s, the program %s\n", result.c_str(), want.c_str()); std::abort(); }
+                return 1;
+            }
+            return 0;
+}
+
 int main(int argc, char **argv)
 {
     const int rounds = argc > 1 ? std::atoi(argv[1]) : 3000;
     std::mt19937_64 rng(12345);
     auto rnd = [&](int lo, int hi) { return lo + (int)(rng() % (uint64_t)(hi - lo + 1)); };
-    long total_launches = 0, total_kept_reads = 0, total_kept_writes = 0, total_chains = 0;
+    long total_launches = 0, total_kept_reads = 0, total_kept_writes = 0, total_chains = 0, total_tables = 0;
     for (int r = 0; r < rounds; ++r) {
         const int n = rnd(1, 40), k = rnd(1, n);
         const int degs[] = {1, 2, 3, 4, 8, 16, n + 1};
@@ -305,9 +367,22 @@ int main(int argc, char **argv)
                 total_chains += (long)cp.n_chains();
             }
         }
+        total_tables += check_skeleton(prog);
+        if (r % 8 == 0) {
+            // larger trees, where the form pays
+            std::mt19937_64 own((uint64_t)r * 7919 + 1);           // a generator of its own: the sessions' stream stays as it is
+            Tree big;
+            const int bk = 40 + (int)(own() % 660);
+            big.build(bk, 2 + (int64_t)(own() % 23));
+            std::vector<int32_t> bocc((size_t)bk);
+            for (int t = 0; t < bk; ++t) bocc[(size_t)t] = own() % 20 ? t : -1;
+            std::vector<Entry> bprog;
+            compile_program(big, bocc, bprog);
+            total_tables += check_skeleton(bprog);
+        }
         fuzz_bcast(rng);
     }
     if (rounds >= 1000 && (total_kept_reads < 50 || total_kept_writes < 200)) { std::printf("keeping was hardly exercised: %ld reads, %ld writes\n", total_kept_reads, total_kept_writes); return 1; }
-    std::printf("ok %d sessions, %ld launches, %ld partials kept, %ld reused, %ld chains\n", rounds, total_launches, total_kept_writes, total_kept_reads, total_chains);
+    std::printf("ok %d sessions, %ld launches, %ld partials kept, %ld reused, %ld chains, %ld tables\n", rounds, total_launches, total_kept_writes, total_kept_reads, total_chains, total_tables);
     return 0;
 }
