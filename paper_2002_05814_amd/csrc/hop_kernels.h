@@ -56,7 +56,7 @@ struct ReduceArgsInline {
     ReduceArgs base;
     DevEntry steps[kInlineEntries];
 };
-static_assert(sizeof(ReduceArgsInline) <= 4096, "kernel arguments are limited to 4 KiB");
+static_assert(sizeof(ReduceArgsInline) <= 4096, "these argument blocks stay within 4 KiB, which every runtime takes");
 
 // A long program over a short byte range, evaluated by one launch as chains (see plan_chains in
 // hop_plan.hpp): a workgroup of kChainThreads lanes owns a column of kChainLanes 16-byte vectors
@@ -115,7 +115,7 @@ struct CopyArgsInline {
     CopyArgs base;
     void *dsts[kInlineDsts];
 };
-static_assert(sizeof(CopyArgsInline) <= 4096, "kernel arguments are limited to 4 KiB");
+static_assert(sizeof(CopyArgsInline) <= 4096, "these argument blocks stay within 4 KiB, which every runtime takes");
 
 int elem_bytes(int dtype);
 

@@ -217,7 +217,7 @@ struct PokeArgs {
     int pad;
     uint4 data[kPokeVectors];
 };
-static_assert(sizeof(PokeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+static_assert(sizeof(PokeArgs) <= 4096, "these argument blocks stay within 4 KiB, which every runtime takes");
 
 __global__ __launch_bounds__(256) void poke_kernel(PokeArgs a)
 {
