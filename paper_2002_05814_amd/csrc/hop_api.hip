@@ -351,15 +351,17 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
     const int64_t d = tree_degree > 0 ? tree_degree : auto_degree(device, k, object_bytes, (hipStream_t)stream);
-    bool cacheable = n_dst == 1 && !no_alloc && object_bytes > 0 && (object_bytes <= kMaxCachedInputBytes / (size_t)k || object_bytes <= kMaxCachedObjectBytes) &&
+    // what may be remembered from call to call: failure-free calls that are bound by the host
+    bool shapeable = !no_alloc && object_bytes > 0 && (object_bytes <= kMaxCachedInputBytes / (size_t)k || object_bytes <= kMaxCachedObjectBytes) &&
                      nobody_fails(fail_mask, n, shape.n_chunks);
-    if (cacheable) {
+    if (shapeable) {
         // a stream that is being captured into a graph takes the plain path: a recording's hand-over between
         // streams uses an event from outside the capture
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing((hipStream_t)stream, &cap) != hipSuccess) { (void)hipGetLastError(); cacheable = false; }
-        else if (cap != hipStreamCaptureStatusNone) cacheable = false;
+        if (hipStreamIsCapturing((hipStream_t)stream, &cap) != hipSuccess) { (void)hipGetLastError(); shapeable = false; }
+        else if (cap != hipStreamCaptureStatusNone) shapeable = false;
     }
+    const bool cacheable = shapeable && n_dst == 1;       // recordings hold reduce launches only; shapes serve all-reduces too
     if (cacheable) {
         CachedCall *hit = nullptr;
         {
@@ -397,7 +399,7 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
         }
     }
     std::shared_ptr<CallShape> known;
-    if (cacheable) {
+    if (shapeable) {
         std::lock_guard<std::mutex> lk(g_mu);
         for (const std::shared_ptr<CallShape> &c : g_shapes)
             if (c->device == device && c->n == n && c->k == k && c->op == op && c->dtype == dtype && c->object_bytes == object_bytes &&
@@ -421,9 +423,10 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
         if (known) {
             // the shape's one launch with this call's addresses; anything in the way (an address that cannot be
             // told from an offset, no room) sends the call down the whole path
-            set_launch_recorder(&rec);
+            if (cacheable) set_launch_recorder(&rec);
             rc = be.launch_skeleton(known->skeleton, 0, object_bytes);
             set_launch_recorder(nullptr);
+            if (rc == HOP_OK && n_dst > 1 && (rc = be.copy_rest(0, object_bytes)) < 0) return rc;
             if (rc == HOP_OK) {
                 planned = false;
                 my_info = known->info;
@@ -440,7 +443,7 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
             if (cacheable) set_launch_recorder(&rec);
             rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, &my_info);
             set_launch_recorder(nullptr);
-            if (cacheable && !known && rc >= 0) {
+            if (shapeable && !known && rc >= 0) {
                 const ChainSkeleton *sk = be.sole_skeleton(my_info.n_launches);
                 if (sk) {
                     auto c = std::make_shared<CallShape>();

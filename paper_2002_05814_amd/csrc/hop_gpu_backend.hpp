@@ -441,6 +441,8 @@ public:
         }
         return HOP_ERR_DEVICE;
     }
+    // the copy of [b0, b1) of the first destination to the others, for a caller that launched the reduce itself
+    int copy_rest(size_t b0, size_t b1) { return copy_to_other_destinations(b0, b1); }
     // The skeleton of the program in force if every launch so far was one launch of it (a failure-free call
     // over many small objects), else null.
     const ChainSkeleton *sole_skeleton(int n_launches) const

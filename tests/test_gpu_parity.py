@@ -1456,6 +1456,16 @@ def test_a_known_shape_over_other_buffers_fills_in_the_addresses_only():
         check(sets[i % 4][:100 + i], None, 90 + i, 8)
         check(sets[(i + 1) % 4][:100 + i], None, 90 + i, 8)
     assert check(sets[3], order, w.k, w.tree_degree) == first
+    # all-reduces of one shape over fresh buffers: the reduce from the known form, then the copy
+    for objs in sets:
+        dsts = [torch.full_like(objs[0], 9) for _ in range(3)]
+        rc, info = hop.hop_allreduce(dsts, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, order, None)
+        torch.cuda.synchronize()
+        orc, outs, _, _ = oracle.allreduce([workloads.to_numpy(o) for o in objs], 3, w.k, oracle.SUM, oracle.F32,
+                                           w.chunk_bytes // 4, w.tree_degree, order, None)
+        assert rc == orc == hop.HOP_OK and info["n_launches"] == 1
+        for got, want in zip(dsts, outs):
+            assert np.array_equal(bits(workloads.to_numpy(got)), bits(want))
     assert hop.hop_shutdown() == hop.HOP_OK
     assert check(sets[2], order, w.k, w.tree_degree) == first
     assert check(sets[1], order, w.k, w.tree_degree) == first
