@@ -260,18 +260,59 @@ static void default_retention(Scheduler &s, const Shape &shape, int dtype)
 // repeated calls
 // ----------------------------------------------------------------------------
 
-// A failure-free hop_reduce over small inputs is bound by the host: checking, planning, cutting the
-// program and building its records take longer than the kernels run. A caller that repeats such a
-// call with the same objects, order and shape (a serving loop) gets the launches of the first call
-// again: they are recorded once, together with the staged programs and the scratch they refer to,
-// and enqueued again with the new destination. Bounded: at most kMaxCachedCalls recordings, the least
-// recently used one makes room; hop_shutdown frees them all.
-struct CachedCall {
+// What is remembered from call to call. A failure-free hop_reduce over small inputs is bound by the
+// host: checking, planning, cutting the program and building its records take longer than the kernels
+// run. Two levels:
+//  - Recordings (CachedCall). A caller that repeats a call with the same objects, order and shape (a
+//    serving loop) gets the launches of the first call again: they are recorded once, together with the
+//    staged programs and the scratch they refer to, and enqueued again with the new destination.
+//    Bounded: kMaxCachedCalls recordings holding kMaxCachedScratchTotal bytes of scratch, the least
+//    recently used ones make room.
+//  - Shapes (CallShape), for the same kind of call over OTHER buffers (a serving loop that gets fresh
+//    buffers for every request): what the scheduler and the chain planner made of the shape - the
+//    one-launch form of the program but for the objects' addresses - is kept under the key without the
+//    addresses. A call that finds it fills in its addresses and launches, planning nothing. Only calls
+//    whose whole work was one launch of that form are kept (all-reduces too: the copy follows).
+// hop_shutdown frees both.
+
+// The part of a call that decides its schedule: everything but the addresses.
+struct CallKey {
     int device = 0, n = 0, k = 0, op = 0, dtype = 0;
     size_t object_bytes = 0, chunk_bytes = 0;
     int64_t degree = 0;
-    bool identity_order = true;
+    bool identity_order = true;                  // ready_order was NULL
     std::vector<int32_t> order;
+};
+// The same of a call in progress (nothing copied).
+struct CallView {
+    int device, n, k, op, dtype;
+    size_t object_bytes, chunk_bytes;
+    int64_t degree;
+    const int32_t *ready_order;
+    const void *const *objs;
+
+    bool scalars_match(const CallKey &c) const
+    {
+        return c.device == device && c.n == n && c.k == k && c.op == op && c.dtype == dtype && c.object_bytes == object_bytes &&
+               c.chunk_bytes == chunk_bytes && c.degree == degree && c.identity_order == (ready_order == nullptr);
+    }
+    bool order_matches(const CallKey &c) const
+    {
+        return !ready_order || std::memcmp(c.order.data(), ready_order, sizeof(int32_t) * (size_t)n) == 0;
+    }
+    CallKey key() const
+    {
+        CallKey c;
+        c.device = device; c.n = n; c.k = k; c.op = op; c.dtype = dtype;
+        c.object_bytes = object_bytes; c.chunk_bytes = chunk_bytes; c.degree = degree;
+        c.identity_order = ready_order == nullptr;
+        if (ready_order) c.order.assign(ready_order, ready_order + n);
+        return c;
+    }
+};
+
+struct CachedCall {
+    CallKey key;
     std::vector<const void *> objs;
     std::vector<RecordedLaunch> launches;
     std::vector<Block *> blocks;
@@ -283,34 +324,24 @@ struct CachedCall {
     uint64_t stamp = 0;
     size_t held = 0;                    // device bytes of `blocks`
 };
-static std::vector<CachedCall *> g_calls;
-static uint64_t g_call_stamp = 0;
-static constexpr size_t kMaxCachedCalls = 128;          // a serving loop may rotate through many sets of buffers
-static constexpr size_t kMaxCachedInputBytes = (size_t)64 << 20;      // larger calls are bound by the kernels ...
-static constexpr size_t kMaxCachedObjectBytes = (size_t)256 << 10;    // ... unless their objects are small: planning takes about
-                                                                      // 20 ns per input, the kernels object_bytes / 6.5 TB/s
-static constexpr size_t kMaxCachedScratch = (size_t)32 << 20;         // a recording keeps the scratch its launches use
-static constexpr size_t kMaxCachedScratchTotal = (size_t)1 << 30;     // ... all recordings together (device bytes; as many pinned)
-static size_t g_calls_held = 0;                                       // device bytes of the blocks the recordings hold
-
-// A second level for the same kind of call over OTHER buffers (a serving loop that gets fresh output
-// buffers for every request): what the scheduler and the chain planner made of the shape - the one-launch
-// form of the program but for the objects' addresses - is kept under the key (device, order, k, degree,
-// op, type, sizes). A call that finds it fills in its addresses, stages the table and launches, without
-// planning anything. Only failure-free calls whose whole work was one launch of that form are kept.
 struct CallShape {
-    int device = 0, n = 0, k = 0, op = 0, dtype = 0;
-    size_t object_bytes = 0, chunk_bytes = 0;
-    int64_t degree = 0;
-    bool identity_order = true;
-    std::vector<int32_t> order;
+    CallKey key;
     ChainSkeleton skeleton;
     hop_info_t info = {};
     int status = HOP_OK;
     uint64_t stamp = 0;
 };
+static std::vector<CachedCall *> g_calls;
 static std::vector<std::shared_ptr<CallShape>> g_shapes;
+static uint64_t g_call_stamp = 0;
+static size_t g_calls_held = 0;                                       // device bytes of the blocks the recordings hold
+static constexpr size_t kMaxCachedCalls = 128;          // a serving loop may rotate through many sets of buffers
 static constexpr size_t kMaxCachedShapes = 32;
+static constexpr size_t kMaxCachedInputBytes = (size_t)64 << 20;      // larger calls are bound by the kernels ...
+static constexpr size_t kMaxCachedObjectBytes = (size_t)256 << 10;    // ... unless their objects are small: planning takes about
+                                                                      // 20 ns per input, the kernels object_bytes / 6.5 TB/s
+static constexpr size_t kMaxCachedScratch = (size_t)32 << 20;         // a recording keeps the scratch its launches use
+static constexpr size_t kMaxCachedScratchTotal = (size_t)1 << 30;     // ... all recordings together (device bytes; as many pinned)
 
 static void free_cached_call(CachedCall *c)
 {
@@ -318,17 +349,6 @@ static void free_cached_call(CachedCall *c)
     for (Block *b : c->blocks) release_block(b, c->last_stream);
     if (c->ev) (void)hipEventDestroy(c->ev);
     delete c;
-}
-
-static bool same_call(const CachedCall &c, int device, const void *const *objs, int n, size_t object_bytes,
-                      const int32_t *ready_order, int k, int op, int dtype, size_t chunk_bytes, int64_t degree)
-{
-    if (c.device != device || c.n != n || c.k != k || c.op != op || c.dtype != dtype || c.object_bytes != object_bytes ||
-        c.chunk_bytes != chunk_bytes || c.degree != degree || c.identity_order != (ready_order == nullptr))
-        return false;
-    // the objects first: recordings of the same shape over other buffers differ in the first pointer
-    if (std::memcmp(c.objs.data(), objs, sizeof(void *) * (size_t)n) != 0) return false;
-    return !ready_order || std::memcmp(c.order.data(), ready_order, sizeof(int32_t) * (size_t)n) == 0;
 }
 
 static bool nobody_fails(const int64_t *fail_mask, int n, int64_t n_chunks)
@@ -339,84 +359,149 @@ static bool nobody_fails(const int64_t *fail_mask, int n, int64_t n_chunks)
     return true;
 }
 
+// Whether this call may be remembered at all: failure-free, bound by the host, allowed to allocate, and
+// not under graph capture (a recording's hand-over between streams uses an event from outside the capture).
+static bool rememberable(int n, int k, size_t object_bytes, const int64_t *fail_mask, int64_t n_chunks, bool no_alloc,
+                         hipStream_t stream)
+{
+    if (no_alloc || object_bytes == 0) return false;
+    if (object_bytes > kMaxCachedInputBytes / (size_t)k && object_bytes > kMaxCachedObjectBytes) return false;
+    if (!nobody_fails(fail_mask, n, n_chunks)) return false;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return cap == hipStreamCaptureStatusNone;
+}
+
+// The recording of exactly this call, marked in use (one thread at a time replays a recording), or null.
+static CachedCall *take_recording(const CallView &v)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (CachedCall *c : g_calls) {
+        if (c->in_use || !v.scalars_match(c->key)) continue;
+        // the objects first: recordings of the same shape over other buffers differ in the first pointer
+        if (std::memcmp(c->objs.data(), v.objs, sizeof(void *) * (size_t)v.n) != 0 || !v.order_matches(c->key)) continue;
+        c->in_use = true;
+        c->stamp = ++g_call_stamp;
+        return c;
+    }
+    return nullptr;
+}
+
+// Enqueues a recording's launches again, with this call's destination.
+static int replay_recording(CachedCall *hit, const CallView &v, void *const *dsts, int n_dst, hipStream_t stream, hop_info_t *info)
+{
+    // the objects and the order were checked when the call was recorded; the destination is new
+    int rc = check_buffers(v.objs, v.n, dsts, n_dst, v.object_bytes);
+    if (rc >= 0 && hit->last_stream != stream) {
+        // the recording's scratch is shared by its uses: a use on another stream follows the last one
+        if (!hit->ev && hipEventCreateWithFlags(&hit->ev, hipEventDisableTiming) != hipSuccess) rc = HOP_ERR_DEVICE;
+        if (rc >= 0 && hipEventRecord(hit->ev, hit->last_stream) == hipSuccess) {
+            if (hipStreamWaitEvent(stream, hit->ev, 0) != hipSuccess) rc = HOP_ERR_DEVICE;
+        } else {
+            (void)hipGetLastError();        // the stream of the last use is gone: its work is done
+        }
+    }
+    for (size_t i = 0; rc >= 0 && i < hit->launches.size(); ++i)
+        if (replay_launch(hit->launches[i], stream, dsts[0]) != hipSuccess) rc = HOP_ERR_DEVICE;
+    if (rc >= 0) {
+        hit->last_stream = stream;
+        if (info) *info = hit->info;
+        rc = hit->status;
+    }
+    std::lock_guard<std::mutex> lk(g_mu);
+    hit->in_use = false;
+    return rc;
+}
+
+// Keeps what a call's launches need to be enqueued again; the least recently used recordings make room,
+// for the new one and for what it holds.
+static void remember_recording(const CallView &v, LaunchRecorder &rec, GpuBackend &be, const hop_info_t &info, int status,
+                               hipStream_t stream)
+{
+    CachedCall *c = new CachedCall;
+    c->key = v.key();
+    c->objs.assign(v.objs, v.objs + v.n);
+    c->launches.swap(rec.launches);
+    c->held = be.held_bytes();
+    c->blocks = be.detach_blocks();
+    blocks_leave_pool(c->blocks.size());
+    c->info = info;
+    c->status = status;
+    c->last_stream = stream;
+    std::vector<CachedCall *> victims;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        c->stamp = ++g_call_stamp;
+        g_calls.push_back(c);
+        g_calls_held += c->held;
+        while (g_calls.size() > kMaxCachedCalls || g_calls_held > kMaxCachedScratchTotal) {
+            size_t at = g_calls.size();
+            for (size_t i = 0; i < g_calls.size(); ++i)
+                if (!g_calls[i]->in_use && g_calls[i] != c && (at == g_calls.size() || g_calls[i]->stamp < g_calls[at]->stamp)) at = i;
+            if (at == g_calls.size()) break;
+            victims.push_back(g_calls[at]);
+            g_calls_held -= g_calls[at]->held;
+            g_calls.erase(g_calls.begin() + (long)at);
+        }
+    }
+    for (CachedCall *victim : victims) free_cached_call(victim);
+}
+
+static std::shared_ptr<CallShape> find_shape(const CallView &v)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (const std::shared_ptr<CallShape> &c : g_shapes)
+        if (v.scalars_match(c->key) && v.order_matches(c->key)) {
+            c->stamp = ++g_call_stamp;
+            return c;
+        }
+    return nullptr;
+}
+
+static void remember_shape(const CallView &v, const ChainSkeleton &sk, const hop_info_t &info, int status)
+{
+    auto c = std::make_shared<CallShape>();
+    c->key = v.key();
+    c->skeleton = sk;
+    c->info = info;
+    c->status = status;
+    std::lock_guard<std::mutex> lk(g_mu);
+    c->stamp = ++g_call_stamp;
+    g_shapes.push_back(c);
+    if (g_shapes.size() > kMaxCachedShapes) {
+        size_t at = 0;
+        for (size_t i = 1; i < g_shapes.size(); ++i)
+            if (g_shapes[i]->stamp < g_shapes[at]->stamp) at = i;
+        g_shapes.erase(g_shapes.begin() + (long)at);
+    }
+}
+
 static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, int n, size_t object_bytes,
                          const int32_t *ready_order, int k, int op, int dtype, size_t chunk_bytes,
-                         int tree_degree, const int64_t *fail_mask, void *stream, hop_info_t *info,
+                         int tree_degree, const int64_t *fail_mask, void *stream_, hop_info_t *info,
                          bool no_alloc = false)
 {
+    const hipStream_t stream = (hipStream_t)stream_;
     Shape shape;
     int rc = check_shape(n, object_bytes, k, op, dtype, chunk_bytes, tree_degree, &shape);
     if (rc < 0) return rc;
     if (!objs || !dsts) return HOP_ERR_INVALID;
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return HOP_ERR_DEVICE;
-    const int64_t d = tree_degree > 0 ? tree_degree : auto_degree(device, k, object_bytes, (hipStream_t)stream);
-    // what may be remembered from call to call: failure-free calls that are bound by the host
-    bool shapeable = !no_alloc && object_bytes > 0 && (object_bytes <= kMaxCachedInputBytes / (size_t)k || object_bytes <= kMaxCachedObjectBytes) &&
-                     nobody_fails(fail_mask, n, shape.n_chunks);
-    if (shapeable) {
-        // a stream that is being captured into a graph takes the plain path: a recording's hand-over between
-        // streams uses an event from outside the capture
-        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing((hipStream_t)stream, &cap) != hipSuccess) { (void)hipGetLastError(); shapeable = false; }
-        else if (cap != hipStreamCaptureStatusNone) shapeable = false;
-    }
+    const int64_t d = tree_degree > 0 ? tree_degree : auto_degree(device, k, object_bytes, stream);
+    const CallView view{device, n, k, op, dtype, object_bytes, chunk_bytes, d, ready_order, objs};
+    const bool shapeable = rememberable(n, k, object_bytes, fail_mask, shape.n_chunks, no_alloc, stream);
     const bool cacheable = shapeable && n_dst == 1;       // recordings hold reduce launches only; shapes serve all-reduces too
-    if (cacheable) {
-        CachedCall *hit = nullptr;
-        {
-            std::lock_guard<std::mutex> lk(g_mu);
-            for (CachedCall *c : g_calls)
-                if (!c->in_use && same_call(*c, device, objs, n, object_bytes, ready_order, k, op, dtype, chunk_bytes, d)) {
-                    hit = c;
-                    c->in_use = true;
-                    c->stamp = ++g_call_stamp;
-                    break;
-                }
-        }
-        if (hit) {
-            // the objects and the order were checked when the call was recorded; the destination is new
-            rc = check_buffers(objs, n, dsts, n_dst, object_bytes);
-            if (rc >= 0 && hit->last_stream != (hipStream_t)stream) {
-                // the recording's scratch is shared by its uses: a use on another stream follows the last one
-                if (!hit->ev && hipEventCreateWithFlags(&hit->ev, hipEventDisableTiming) != hipSuccess) rc = HOP_ERR_DEVICE;
-                if (rc >= 0 && hipEventRecord(hit->ev, hit->last_stream) == hipSuccess) {
-                    if (hipStreamWaitEvent((hipStream_t)stream, hit->ev, 0) != hipSuccess) rc = HOP_ERR_DEVICE;
-                } else {
-                    (void)hipGetLastError();        // the stream of the last use is gone: its work is done
-                }
-            }
-            for (size_t i = 0; rc >= 0 && i < hit->launches.size(); ++i)
-                if (replay_launch(hit->launches[i], (hipStream_t)stream, dsts[0]) != hipSuccess) rc = HOP_ERR_DEVICE;
-            if (rc >= 0) {
-                hit->last_stream = (hipStream_t)stream;
-                if (info) *info = hit->info;
-                rc = hit->status;
-            }
-            std::lock_guard<std::mutex> lk(g_mu);
-            hit->in_use = false;
-            return rc;
-        }
-    }
-    std::shared_ptr<CallShape> known;
-    if (shapeable) {
-        std::lock_guard<std::mutex> lk(g_mu);
-        for (const std::shared_ptr<CallShape> &c : g_shapes)
-            if (c->device == device && c->n == n && c->k == k && c->op == op && c->dtype == dtype && c->object_bytes == object_bytes &&
-                c->chunk_bytes == chunk_bytes && c->degree == d && c->identity_order == (ready_order == nullptr) &&
-                (!ready_order || std::memcmp(c->order.data(), ready_order, sizeof(int32_t) * (size_t)n) == 0)) {
-                known = c;
-                c->stamp = ++g_call_stamp;
-                break;
-            }
-    }
+    if (cacheable)
+        if (CachedCall *hit = take_recording(view)) return replay_recording(hit, view, dsts, n_dst, stream, info);
+    const std::shared_ptr<CallShape> known = shapeable ? find_shape(view) : nullptr;
     if (!known && (rc = check_order(n, ready_order)) < 0) return rc;      // a known shape's order was checked before
     if ((rc = check_buffers(objs, n, dsts, n_dst, object_bytes)) < 0) return rc;
     char *static_base = nullptr;
     if (no_alloc && (rc = static_scratch(device, &static_base)) < 0) return rc;
     try {
-        GpuBackend be(device, (hipStream_t)stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype,
-                      k, d, static_base, kStaticScratchBytes);
+        GpuBackend be(device, stream, objs, n, std::vector<void *>(dsts, dsts + n_dst), shape, op, dtype, k, d, static_base,
+                      kStaticScratchBytes);
         LaunchRecorder rec;
         hop_info_t my_info = {};
         bool planned = true;
@@ -443,63 +528,12 @@ static int reduce_common(void *const *dsts, int n_dst, const void *const *objs, 
             if (cacheable) set_launch_recorder(&rec);
             rc = replay_reduce(s, n, shape.n_chunks, ready_order, fail_mask, &my_info);
             set_launch_recorder(nullptr);
-            if (shapeable && !known && rc >= 0) {
-                const ChainSkeleton *sk = be.sole_skeleton(my_info.n_launches);
-                if (sk) {
-                    auto c = std::make_shared<CallShape>();
-                    c->device = device; c->n = n; c->k = k; c->op = op; c->dtype = dtype;
-                    c->object_bytes = object_bytes; c->chunk_bytes = chunk_bytes; c->degree = d;
-                    c->identity_order = ready_order == nullptr;
-                    if (ready_order) c->order.assign(ready_order, ready_order + n);
-                    c->skeleton = *sk;
-                    c->info = my_info;
-                    c->status = rc;
-                    std::lock_guard<std::mutex> lk(g_mu);
-                    c->stamp = ++g_call_stamp;
-                    g_shapes.push_back(c);
-                    if (g_shapes.size() > kMaxCachedShapes) {
-                        size_t at = 0;
-                        for (size_t i = 1; i < g_shapes.size(); ++i)
-                            if (g_shapes[i]->stamp < g_shapes[at]->stamp) at = i;
-                        g_shapes.erase(g_shapes.begin() + (long)at);
-                    }
-                }
-            }
+            if (shapeable && !known && rc >= 0)
+                if (const ChainSkeleton *sk = be.sole_skeleton(my_info.n_launches)) remember_shape(view, *sk, my_info, rc);
         }
         if (info) *info = my_info;
-        if (cacheable && rc >= 0 && !rec.unusable && !rec.launches.empty() && be.held_bytes() <= kMaxCachedScratch) {
-            CachedCall *c = new CachedCall;
-            c->device = device; c->n = n; c->k = k; c->op = op; c->dtype = dtype;
-            c->object_bytes = object_bytes; c->chunk_bytes = chunk_bytes; c->degree = d;
-            c->identity_order = ready_order == nullptr;
-            if (ready_order) c->order.assign(ready_order, ready_order + n);
-            c->objs.assign(objs, objs + n);
-            c->launches.swap(rec.launches);
-            c->held = be.held_bytes();
-            c->blocks = be.detach_blocks();
-            blocks_leave_pool(c->blocks.size());
-            c->info = my_info;
-            c->status = rc;
-            c->last_stream = (hipStream_t)stream;
-            // the least recently used recordings make room: for the new one, and for what it holds
-            std::vector<CachedCall *> victims;
-            {
-                std::lock_guard<std::mutex> lk(g_mu);
-                c->stamp = ++g_call_stamp;
-                g_calls.push_back(c);
-                g_calls_held += c->held;
-                while (g_calls.size() > kMaxCachedCalls || g_calls_held > kMaxCachedScratchTotal) {
-                    size_t at = g_calls.size();
-                    for (size_t i = 0; i < g_calls.size(); ++i)
-                        if (!g_calls[i]->in_use && g_calls[i] != c && (at == g_calls.size() || g_calls[i]->stamp < g_calls[at]->stamp)) at = i;
-                    if (at == g_calls.size()) break;
-                    victims.push_back(g_calls[at]);
-                    g_calls_held -= g_calls[at]->held;
-                    g_calls.erase(g_calls.begin() + (long)at);
-                }
-            }
-            for (CachedCall *victim : victims) free_cached_call(victim);
-        }
+        if (cacheable && rc >= 0 && !rec.unusable && !rec.launches.empty() && be.held_bytes() <= kMaxCachedScratch)
+            remember_recording(view, rec, be, my_info, rc, stream);
         return rc;
     } catch (const std::bad_alloc &) {
         set_launch_recorder(nullptr);
