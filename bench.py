@@ -360,6 +360,9 @@ def main():
                     help="also time the workload's reduce (same n, k, degree, type) at object sizes from 1 to 64 MiB, "
                          "inputs not cached, and fit time = fixed cost + bytes / rate: what part of a mid-size launch "
                          "is the launch and what part the kernel")
+    ap.add_argument("--many-objects-sweep", action="store_true",
+                    help="also time fp32 sums over 128..4000 inputs of 1 KiB..1 MiB in a 16-ary tree (launch- and "
+                         "latency-bound calls: us per call and GB/s per shape)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run hop_broadcast of one 256 MiB object to one destination a few times: a copy of "
                          "known size against which hardware byte counters can be scaled")
@@ -594,6 +597,41 @@ def main():
                                                   "model": "us = fixed_us + bytes / rate"}}
         for r in rows:
             r["model_us"] = round(fixed + slope * r["bytes"], 2)
+    if args.many_objects_sweep:
+        # many inputs of small to medium size (fp32 sum, 16-ary tree), inputs not in any cache: which of the
+        # library's forms of a long program takes the call depends on inputs x size (see path in each row)
+        base5 = workloads.WORKLOADS[5]
+        rows = []
+        for n_in in (128, 256, 1000, 4000):
+            for nbytes in (1 << 10, 4 << 10, 16 << 10, 64 << 10, 256 << 10, 1 << 20):
+                if n_in * nbytes > (1 << 30):
+                    continue
+                ws = base5.scaled(nbytes, nbytes, n=n_in, k=n_in, tree_degree=16, fail={}, name="many_%d_%d" % (n_in, nbytes),
+                                  n_dst=0)
+                n_sets = max(4, min(64, (256 << 20) // (n_in * nbytes)))
+                sets = []
+                for _ in range(n_sets):
+                    block = torch.rand((n_in, nbytes // 4), device=dev)
+                    t = hop.PtrTable([block[i] for i in range(n_in)])
+                    t.keep = block
+                    sets.append(t)
+                dd = [torch.zeros(nbytes // 4, device=dev) for _ in range(2)]
+                so = ws.ready_order()
+                stt = {"i": 0, "info": None}
+                strm = torch.cuda.current_stream().cuda_stream
+
+                def step_many():
+                    stt["i"] += 1
+                    _, stt["info"] = hop.hop_reduce(dd[stt["i"] & 1], sets[stt["i"] % n_sets], ws.k, "sum", ws.dtype, ws.chunk_bytes,
+                                                    ws.tree_degree, so, None, stream=strm)
+                reps = 400 if n_in * nbytes < (64 << 20) else 60
+                _, _, med = time_calls_median(step_many, reps, max(2 * n_sets, 50), torch, batch=max(10, reps // 10))
+                counted = (n_in + 1) * nbytes
+                rows.append({"inputs": n_in, "object_bytes": nbytes, "us": round(med * 1e3, 2),
+                             "GB/s": round(counted / (med * 1e-3) / 1e9, 1), "launches": stt["info"]["n_launches"]})
+                del sets, dd
+                torch.cuda.empty_cache()
+        out["many_objects_sweep"] = rows
     if args.streamed_interval_us is not None:
         out["streamed_chunks"] = streamed_chunks(hop, torch, w, objs, order, dsts[0][0], args.streamed_interval_us)
     if args.paced_interval_us is not None:
