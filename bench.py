@@ -41,7 +41,8 @@ PROFILED_TRAFFIC = {
                      "pieces 64 KiB apart from 2048 tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators "
                      "indexed like the elements, nontemporal; programs of 48 steps or more over at most 64 KiB: one "
                      "launch, 256 lanes per 64-byte column, chains of at most 23 items folded by teams of 4 lanes with all "
-                     "their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments"),
+                     "their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments, "
+                     "four columns in a row per die"),
     "workloads": {
         "cfg2_async_sgd": {"bytes_per_call": 872327474, "profile": "profiles/hbm_traffic_all_workloads.md"},
         "cfg3_rl_allreduce": {"bytes_per_call": 2163381761, "profile": "profiles/hbm_traffic_all_workloads.md"},

@@ -597,7 +597,14 @@ __device__ __forceinline__ void chains_workgroup(const ChainArgs &a, const uint4
     const size_t n_cols = (a.base.n_vec + kChainLanes - 1) / kChainLanes;
     const size_t lane = threadIdx.x % kChainLanes;
     if (blockIdx.x < n_cols) {
-        const size_t v = (size_t)blockIdx.x * kChainLanes + lane;
+        // Two columns share a 128-byte line. Workgroups go to the chip's 8 dies in turn, each die with an L2
+        // of its own: within every whole block of 8 * kChainColumnRun workgroups, the workgroups that land on
+        // one die take kChainColumnRun columns in a row, so a line is fetched from memory by one L2, once.
+        size_t col = blockIdx.x;
+        constexpr size_t kBlock = 8 * kChainColumnRun;
+        const size_t block0 = col / kBlock * kBlock;
+        if (block0 + kBlock <= n_cols) col = block0 + (col - block0) % 8 * kChainColumnRun + (col - block0) / 8;
+        const size_t v = col * kChainLanes + lane;
         const bool live = v < a.base.n_vec;
         chains_body<DT, OP, false>(a, table, lds, a.base.byte_begin + (live ? v : a.base.n_vec - 1) * 16, live);
     } else {

@@ -365,7 +365,10 @@ private:
     // 1-16 KiB 9.0-9.5 against 18.8-21.6, of 64 KiB 25.3 against 27.3; 4000 inputs of 1-16 KiB 15.5-23.5
     // against 19.6-33.6. It loses where the workgroups no longer run side by side (a workgroup is bound by
     // the latency of its few loads): 256 inputs of 256 KiB 28.8 against 19.3, 4000 of 64 KiB 109 against 67.
-    // Hence the limit on columns x rounds, a round being 64 chains of one pass.
+    // Hence the limit on columns x rounds, a round being 64 chains of one pass. (With each die's workgroups on
+    // columns in a row, see chains_workgroup: 1000 inputs of 64 KiB 17.6, 4000 of 16 KiB 17.1, 256 of 64 KiB 8.8;
+    // the same limits still came out best: 4000 of 64 KiB 72.8 as chains against 63.5, 4000 of 32 KiB 39.7
+    // as chains against 44.5.)
 
     bool wants_chains(size_t n_steps, size_t range_bytes) const
     {

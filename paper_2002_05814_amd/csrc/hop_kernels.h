@@ -69,6 +69,7 @@ static_assert(sizeof(ReduceArgsInline) <= 4096, "these argument blocks stay with
 // the LDS byte offset of a chain's value, and behind the last item the offset of the identity value
 // (identity_at) up to the end of the record, so that loads and folds need not look at a count.
 constexpr int kChainLanes = 4;
+constexpr int kChainColumnRun = 4;       // columns in a row that one die's workgroups take
 constexpr int kChainTeams = 64;
 constexpr int kChainThreads = kChainLanes * kChainTeams;
 constexpr int kChainMaxItems = 23;

@@ -53,7 +53,8 @@ const char *kernel_config()
            "launches that keep or read partial results: one step at a time, 4|2|1 vectors/lane, pieces 64 KiB apart from 2048 "
            "tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators indexed like the elements, nontemporal; "
            "programs of 48 steps or more over at most 64 KiB: one launch, 256 lanes per 64-byte column, chains of at most 23 items "
-           "folded by teams of 4 lanes with all their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments";
+           "folded by teams of 4 lanes with all their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments, "
+           "four columns in a row per die";
 }
 
 static thread_local LaunchRecorder *tl_recorder = nullptr;

@@ -209,6 +209,8 @@ CHAIN_CASES = [
     ("f32", 5000, 5000, 2, 512, 512),                # a binary tree on 5000: too many chains, the older path
     ("f32", 1024, 1000, 16, 131072, 65536),          # workload 5 with larger objects: the older path
     ("i32", 48, 48, 4, 640, 4096),                   # the shortest program that takes the path
+    ("f32", 150, 150, 4, 64 * 45 + 12, 4096),        # 45 columns: one whole block of 32 in die order, 13 in plain order
+    ("i32", 200, 180, 16, 6400, 2560),               # chunks of 40, 40 and 20 columns
 ]
 
 
