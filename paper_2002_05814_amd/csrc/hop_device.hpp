@@ -550,28 +550,58 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *con
                     }
                 }
             } else {
-                // bf16: an object's vector is 16 bytes of 8 elements, a value 32 bytes of 8 accumulators
-                A val[R][W];
-                uint4 raw[R];
+                // bf16: an object's vector is 16 bytes of 8 elements, a value 32 bytes of 8 accumulators. The
+                // objects' vectors are all fetched first (an item that is a value fetches the lane's part of the
+                // identity value instead, by the same flat load, and does not use it); the values are read from LDS
+                // as the fold comes to them (an item that is an object reads the identity value instead), so
+                // that the registers hold 16 bytes per item, not 48, and several workgroups fit a compute unit.
+                u32x4 raw[R];
+                uint32_t value_at[R], values = 0;       // where each item's value is in LDS; bit u: item u is a value
 #pragma unroll
                 for (int u = 0; u < R; ++u) {
                     const uint64_t e = word[1 + u];
-                    if ((uint32_t)(e >> 32) == 0) {
-                        const A *v = (const A *)(mine + (uint32_t)e);
-#pragma unroll
-                        for (int w = 0; w < W; ++w) val[u][w] = v[w];
-                    } else if (TAIL) {
-                        val[u][0] = load_elem<DT>((const void *)(uintptr_t)e, off);
-                    } else {
-                        raw[u] = ld16((const void *)(uintptr_t)e, off);
-                    }
+                    const bool is_value = (uint32_t)(e >> 32) == 0;
+                    value_at[u] = is_value ? (uint32_t)e : a.identity_at;
+                    values |= (uint32_t)is_value << u;
+                    const uint64_t at = is_value ? mine_flat + a.identity_at : e + (uint64_t)off;
+                    if constexpr (TAIL) raw[u].x = *(const uint16_t *)(uintptr_t)at;
+                    else raw[u] = *(const u32x4 *)(uintptr_t)at;
                 }
                 asm volatile("" ::: "memory");
+                // The value of item u + 1 is on its way from LDS while item u is folded. The empty statements
+                // formally use what was read, so the reads happen whether or not the item is a value (no
+                // branch around them), and being barriers for memory accesses they keep the next read ahead.
+                typedef const u32x4 __attribute__((address_space(3))) *lds_vec_ptr;
+                typedef const uint32_t __attribute__((address_space(3))) *lds_word_ptr;
+                constexpr int Q = TAIL ? 1 : T::W / 4;
+                u32x4 next[Q], cur[Q];
+                const auto fetch_value = [&](int u) {
+                    if constexpr (TAIL) next[0].x = *(lds_word_ptr)(mine + value_at[u]);
+                    else {
+#pragma unroll
+                        for (int q = 0; q < Q; ++q) next[q] = ((lds_vec_ptr)(mine + value_at[u]))[q];
+                    }
+                };
+                fetch_value(0);
 #pragma unroll
                 for (int u = 0; u < R; ++u) {
-                    if (!TAIL && (uint32_t)(word[1 + u] >> 32) != 0) decode<DT>(raw[u], val[u]);
+                    const bool is_value = (values >> u) & 1u;
 #pragma unroll
-                    for (int w = 0; w < W; ++w) acc[w] = u == 0 ? val[0][w] : combine<OP>(acc[w], val[u][w]);
+                    for (int q = 0; q < Q; ++q) cur[q] = next[q];
+                    if (u + 1 < R) fetch_value(u + 1);
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) {
+                        if constexpr (TAIL) asm volatile("" : "+v"(cur[q].x) : : "memory");
+                        else asm volatile("" : "+v"(cur[q]) : : "memory");
+                    }
+                    A x[W];
+                    if constexpr (TAIL) x[0] = bits_to_f32(raw[u].x << 16);
+                    else decode<DT>(make_uint4(raw[u].x, raw[u].y, raw[u].z, raw[u].w), x);
+#pragma unroll
+                    for (int w = 0; w < W; ++w) {
+                        const A y = is_value ? __builtin_bit_cast(A, (uint32_t)cur[w / 4][w % 4]) : x[w];
+                        acc[w] = u == 0 ? y : combine<OP>(acc[w], y);
+                    }
                 }
             }
             if (out != kChainFinal) {

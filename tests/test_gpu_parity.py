@@ -242,21 +242,24 @@ def test_long_programs_over_small_objects_in_one_launch(dtype, n, k, d, nbytes, 
         assert np.array_equal(bits(workloads.to_numpy(got)), bits(want))
 
 
-def test_one_launch_path_with_specials_and_sources_at_odd_alignment():
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_one_launch_path_with_specials_and_sources_at_odd_alignment(dtype):
     # NaNs, infinities, signed zeros and denormals through the chains' folds and their values in LDS; the
-    # objects are views 16 bytes into their allocations
-    n, nbytes = 400, 1000 * 4
-    w = workloads.WORKLOADS[5].scaled(nbytes, 4096, n=n, k=n, tree_degree=8, order_seed=3, data_seed=4, fail={},
-                                      name="chains_specials", n_dst=0)
+    # objects are views 16 bytes into their allocations (bf16: the upper halves of the same fp32 patterns)
+    es = ES[dtype]
+    n, nbytes = 400, 1000 * es
+    w = workloads.WORKLOADS[{"f32": 5, "bf16": 4}[dtype]].scaled(nbytes, 4096, n=n, k=n, tree_degree=8, order_seed=3,
+                                                                 data_seed=4, fail={}, name="chains_specials", n_dst=0)
     assert takes_the_one_launch_path(w)
     rng = np.random.default_rng(12)
     # every element position has one theme, so that two different NaNs never meet (which of them a sum
     # returns is not defined): +inf among finite values, -inf, both (the sum generates a NaN), one quiet NaN
     # pattern, zeros of both signs only, denormals only, large values that overflow, plain values
-    E = nbytes // 4
+    E = nbytes // es
     theme = rng.integers(0, 8, size=E)
     qnan = np.array([0x7fc01234], np.uint32).view(np.float32)[0]
-    backing = [torch.zeros(E + 8, dtype=torch.float32, device=dev()) for _ in range(n)]
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    backing = [torch.zeros(E + 16 // es * 2, dtype=tdt, device=dev()) for _ in range(n)]
     objs = []
     for b in backing:
         host = (rng.standard_normal(E) * 1e-3).astype(np.float32)
@@ -272,8 +275,10 @@ def test_one_launch_path_with_specials_and_sources_at_odd_alignment():
         host[den] = (rng.standard_normal(int(den.sum())) * 1e-42).astype(np.float32)
         big = theme == 6
         host[big] = (rng.standard_normal(int(big.sum())) * 3e37).astype(np.float32)
-        o = b[4:4 + E]
-        o.copy_(torch.from_numpy(host))
+        o = b[16 // es:16 // es + E]
+        if dtype == "bf16":
+            host = (host.view(np.uint32) >> 16).astype(np.uint16)       # truncated: themes and specials survive
+        o.copy_(workloads.from_numpy(host, dtype))
         objs.append(o)
     for op in ("sum", "min", "max"):
         run_both(w, op, objs=objs)
