@@ -506,9 +506,10 @@ int hop_calibrate(double *latency_s, double *bytes_per_s);
  *   - for a call over 48 or more inputs of at most 64 KiB each: the table of
  *     the one-launch form of its program (192 bytes per chain, fewer chains
  *     than inputs);
- *   - for a call over 128 or more inputs of at most 768 KiB each (fp32,
- *     int32): the partial results and records of its sub-programs (at most
- *     256 MiB; a cut that would need more is not made);
+ *   - for a call over 128 or more inputs of at most 768 KiB each (bf16:
+ *     512 KiB, and its partial results are 4-byte accumulators): the partial
+ *     results and records of its sub-programs (at most 256 MiB; a cut that
+ *     would need more is not made);
  *   - HOP_WS_EAGER (sessions with hop_session_set_eager(s, m >= 1)): the saved
  *     accumulators, 4 bytes per element and accumulator level of the tree;
  *   - HOP_WS_FAILURES (participants may fail mid-stream; objects of 8 MiB or more):

@@ -1056,7 +1056,7 @@ size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes
         // the program as chains in one launch: a table of one record per chain (fewer chains than inputs)
         if ((size_t)k >= kChainWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= kChainMaxBytes)
             total += blocks(round256((size_t)k * kChainRecordWords * sizeof(uint64_t)));
-        if (dtype != HOP_BF16 && (size_t)k >= kSplitWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= kSplitMaxBytes) {
+        if ((size_t)k >= kSplitWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= split_max_bytes((int)dtype)) {
             Tree tr;
             tr.shape(k, d);
             std::vector<int32_t> occ((size_t)k, 0);
@@ -1064,7 +1064,9 @@ size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes
             compile_program(tr, occ, prog);
             MultiPlan mp;
             if (plan_passes(prog, kSplitWantSteps, kSplitMinRun, kSplitMaxRun, mp)) {
-                const size_t partials = round256(std::min(object_bytes, kSplitMaxBytes)) * mp.n_subs();
+                // bf16: 4-byte accumulators in whole blocks of 1 KiB of the object, wherever the range starts
+                const size_t longest = std::min(object_bytes, split_max_bytes((int)dtype));
+                const size_t partials = (dtype == HOP_BF16 ? ((longest + 1023) / 1024 + 1) * 2048 : round256(longest)) * mp.n_subs();
                 if (partials <= kSplitMaxScratch)
                     total = std::max(total, blocks(partials + (mp.steps.size() + mp.n_subs() * 2 + mp.top.size()) * sizeof(DevEntry) + 512));
             }

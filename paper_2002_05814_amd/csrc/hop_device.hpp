@@ -239,6 +239,49 @@ template <int DT> __device__ __forceinline__ void store_acc(char *level_base, si
     }
 }
 
+// Layout of a kept partial result: one accumulator-typed value (4 bytes) per element of the
+// object. The accumulators of 64 consecutive source vectors (the vectors the lanes of a wave hold)
+// form a block of Q * 1 KiB, Q = W / 4: first the accumulators 0..3 of all 64 vectors, then 4..7 of
+// all 64 (bf16: Q = 2; for 32-bit elements the layout is simply that of the object). Every store
+// and load instruction of a wave then covers 1 KiB of consecutive addresses and a partial is one
+// sequential stream. With a vector's W accumulators side by side instead, each instruction would
+// touch every other 16 bytes of 2 KiB (measured: 10 % more bytes written to memory than stored);
+// with the two halves in two planes an object's length apart, twice as many write streams (10 %
+// slower).
+template <int DT> __device__ __forceinline__ size_t kept_offset(size_t off, int q)
+{
+    constexpr size_t Q = Traits<DT>::W / 4;
+    const size_t v = off >> 4;                   // index of the 16-byte source vector
+    return ((v >> 6) * Q + (size_t)q) * 1024 + (v & 63) * 16;
+}
+template <int DT> __device__ __forceinline__ void load_kept(const char *base, size_t off, typename Traits<DT>::acc_t *x)
+{
+    using A = typename Traits<DT>::acc_t;
+#pragma unroll
+    for (int q = 0; q < Traits<DT>::W / 4; ++q) {
+        const uint4 r = ld16(base, kept_offset<DT>(off, q));
+        x[4 * q + 0] = __builtin_bit_cast(A, r.x);
+        x[4 * q + 1] = __builtin_bit_cast(A, r.y);
+        x[4 * q + 2] = __builtin_bit_cast(A, r.z);
+        x[4 * q + 3] = __builtin_bit_cast(A, r.w);
+    }
+}
+template <int DT> __device__ __forceinline__ void store_kept(char *base, size_t off, const typename Traits<DT>::acc_t *x)
+{
+#pragma unroll
+    for (int q = 0; q < Traits<DT>::W / 4; ++q) {
+        const uint4 r = make_uint4(__builtin_bit_cast(uint32_t, x[4 * q + 0]), __builtin_bit_cast(uint32_t, x[4 * q + 1]),
+                                   __builtin_bit_cast(uint32_t, x[4 * q + 2]), __builtin_bit_cast(uint32_t, x[4 * q + 3]));
+        st16(base, kept_offset<DT>(off, q), r);
+    }
+}
+// where the accumulator of the single element at object byte offset off lives
+template <int DT> __device__ __forceinline__ size_t kept_elem_offset(size_t off)
+{
+    const size_t i = (off & 15) / Traits<DT>::ES;           // element within its vector
+    return kept_offset<DT>(off & ~(size_t)15, (int)(i >> 2)) + (i & 3) * 4;
+}
+
 // The program is read through the constant address space: it is never written
 // while a kernel runs, so its steps can be fetched with scalar loads and held
 // in SGPRs (a plain global pointer would make the compiler assume that the
@@ -264,6 +307,7 @@ struct LaneProg {
         return {(const void *)(uintptr_t)p, from(mine.z, t + 1)};
     }
     __device__ __forceinline__ int n_entries() const { return (int)from(mine.z, 0); }
+    __device__ __forceinline__ bool partial_out() const { return (from(mine.w, 0) & kSubStoresAccumulators) != 0; }
     __device__ __forceinline__ void *dst() const { return (void *)(uintptr_t)(((uint64_t)from(mine.y, 0) << 32) | from(mine.x, 0)); }
 };
 
@@ -295,44 +339,95 @@ template <int G> __device__ __forceinline__ void pin_here(const StepGroup<G> &g)
     for (int u = 0; u < G; ++u) asm volatile("" : : "s"(g.src[u]), "s"(g.ctl[u]));
 }
 
+// Whether a program's result is stored as accumulator-typed values laid out like a kept partial result
+// (see kept_offset) instead of as elements: a sub-program's header can say so.
+template <class Prog> __device__ __forceinline__ bool stores_accumulators(const Prog &) { return false; }
+__device__ __forceinline__ bool stores_accumulators(const LaneProg &p) { return p.partial_out(); }
+
+// What the loads of G steps bring in: one 16-byte vector per step and vector of the lane. MIXED (kernels
+// whose steps may read partial results of an element type with W = 8 accumulators per vector): a
+// step with kPartialBit reads W accumulator-typed values, the second half of which lands in more[].
+template <int G, int VPT, bool MIXED> struct Loaded {
+    uint4 raw[G][VPT];
+    uint4 more[MIXED ? G : 1][VPT];
+};
+
 // G consecutive program steps: all G*VPT loads are issued before the first value
 // is consumed, then the values are folded in program order.
-template <int DT, int G, int VPT, class M>
-__device__ __forceinline__ void issue_group(const StepGroup<G> &g, const size_t (&off)[VPT], uint4 (&raw)[G][VPT])
+template <int DT, int G, int VPT, bool MIXED>
+__device__ __forceinline__ void issue_group(const StepGroup<G> &g, const size_t (&off)[VPT], Loaded<G, VPT, MIXED> &in)
 {
 #pragma unroll
-    for (int u = 0; u < G; ++u)
+    for (int u = 0; u < G; ++u) {
+        if constexpr (MIXED) {
+            // one load that every step issues, at an offset picked by the step's kind, and a second one for
+            // partial results only: two loads into the same registers on either side of a branch would make
+            // the second wait for everything in flight
+            const bool partial = (g.ctl[u] & kPartialBit) != 0;
 #pragma unroll
-        for (int j = 0; j < VPT; ++j) raw[u][j] = ld16(g.src[u], off[j]);
+            for (int j = 0; j < VPT; ++j) {
+                size_t at = partial ? kept_offset<DT>(off[j], 0) : off[j];
+                asm volatile("" : "+v"(at));          // the offset is picked here, so that the load is not split in two again
+                in.raw[u][j] = ld16(g.src[u], at);
+            }
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) in.more[u][j] = ld16(g.src[u], kept_offset<DT>(off[j], 1));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) in.raw[u][j] = ld16(g.src[u], off[j]);
+        }
+    }
 }
-template <int DT, int G, int VPT, class M>
-__device__ __forceinline__ void fold_group(M &m, const StepGroup<G> &g, const uint4 (&raw)[G][VPT])
+template <int DT, int G, int VPT, bool MIXED, class M>
+__device__ __forceinline__ void fold_group(M &m, const StepGroup<G> &g, const Loaded<G, VPT, MIXED> &in)
 {
     using A = typename Traits<DT>::acc_t;
     constexpr int W = Traits<DT>::W;
     if (G == kRunSteps && (g.ctl[0] & kRunBit)) {
-        // a run of plain combines into one level: one dispatch for the whole group
+        // a run of plain combines of objects into one level: one dispatch for the whole group
         m.template run<G>(g.ctl[0] & 0xffu, [&](int u, A *x) {
 #pragma unroll
-            for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
+            for (int j = 0; j < VPT; ++j) decode<DT>(in.raw[u][j], &x[j * W]);
         });
         return;
     }
 #pragma unroll
     for (int u = 0; u < G; ++u) {
+        if constexpr (MIXED) {
+            static_assert(!MIXED || W == 8, "two vectors of four accumulators per source vector");
+            if (g.ctl[u] & kPartialBit) {
+                A y[VPT * W];
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) {
+                    const uint4 lo = in.raw[u][j], hi = in.more[u][j];
+                    y[j * W + 0] = __builtin_bit_cast(A, lo.x);
+                    y[j * W + 1] = __builtin_bit_cast(A, lo.y);
+                    y[j * W + 2] = __builtin_bit_cast(A, lo.z);
+                    y[j * W + 3] = __builtin_bit_cast(A, lo.w);
+                    y[j * W + 4] = __builtin_bit_cast(A, hi.x);
+                    y[j * W + 5] = __builtin_bit_cast(A, hi.y);
+                    y[j * W + 6] = __builtin_bit_cast(A, hi.z);
+                    y[j * W + 7] = __builtin_bit_cast(A, hi.w);
+                }
+                m.step(g.ctl[u], y);
+                continue;
+            }
+        }
         A x[VPT * W];
 #pragma unroll
-        for (int j = 0; j < VPT; ++j) decode<DT>(raw[u][j], &x[j * W]);
+        for (int j = 0; j < VPT; ++j) decode<DT>(in.raw[u][j], &x[j * W]);
         m.step(g.ctl[u], x);
     }
 }
-template <int DT, int G, int VPT, class M, class Prog>
+template <int DT, int G, int VPT, bool MIXED, class M, class Prog>
 __device__ __forceinline__ void run_group(M &m, const Prog prog, int t, int n, const size_t (&off)[VPT])
 {
     const StepGroup<G> g = fetch_steps<G>(prog, t, n);
-    uint4 raw[G][VPT];
-    issue_group<DT, G, VPT, M>(g, off, raw);
-    fold_group<DT, G, VPT, M>(m, g, raw);
+    Loaded<G, VPT, MIXED> in;
+    issue_group<DT, G, VPT, MIXED>(g, off, in);
+    fold_group<DT, G, VPT, MIXED>(m, g, in);
 }
 
 // One workgroup of THREADS lanes walks tiles of THREADS*VPT 16-byte vectors:
@@ -349,9 +444,15 @@ __device__ __forceinline__ void run_group(M &m, const Prog prog, int t, int n, c
 // written to the spill area (more steps will follow) or, when n_save is 0, the
 // result is stored like in a whole-program launch. The spill area holds one
 // object-sized array of accumulator-typed values per level.
-template <int DT, int OP, int D, int VPT, int U, int THREADS, bool SEG = false, class Prog>
+//
+// MIXED (bf16): steps with kPartialBit read a partial result, 4 bytes per element laid out as kept_offset
+// says, and a sub-program whose header says so stores its result that way: the pieces of a long program
+// that was cut into sub-programs (their partial results must be accumulator-typed, or the bits of the
+// result would depend on the cut).
+template <int DT, int OP, int D, int VPT, int U, int THREADS, bool SEG = false, bool MIXED = false, class Prog>
 __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog, const int n, void *const dst)
 {
+    static_assert(!(SEG && MIXED), "segments keep their accumulators in the spill area, not in partial results");
     using T = Traits<DT>;
     using A = typename T::acc_t;
     constexpr int W = T::W;
@@ -402,19 +503,19 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
             // flight, so that their latency does not add to the data's
             StepGroup<U> cur = fetch_steps<U>(prog, 0, n);
             for (; t + U <= n; t += U) {
-                uint4 raw[U][VPT];
-                issue_group<DT, U, VPT, decltype(m)>(cur, off, raw);
+                Loaded<U, VPT, MIXED> in;
+                issue_group<DT, U, VPT, MIXED>(cur, off, in);
                 const StepGroup<U> nxt = fetch_steps<U>(prog, t + U, n);
                 pin_here(nxt);
-                fold_group<DT, U, VPT>(m, cur, raw);
+                fold_group<DT, U, VPT, MIXED>(m, cur, in);
                 cur = nxt;
             }
         }
         // what is left is taken in halving groups so that it stays in flight together too
-        if (U > 8 && t + 8 <= n) { run_group<DT, 8, VPT>(m, prog, t, n, off); t += 8; }
-        if (U > 4 && t + 4 <= n) { run_group<DT, 4, VPT>(m, prog, t, n, off); t += 4; }
-        if (U > 2 && t + 2 <= n) { run_group<DT, 2, VPT>(m, prog, t, n, off); t += 2; }
-        if (U > 1 && t < n) { run_group<DT, 1, VPT>(m, prog, t, n, off); t += 1; }
+        if (U > 8 && t + 8 <= n) { run_group<DT, 8, VPT, MIXED>(m, prog, t, n, off); t += 8; }
+        if (U > 4 && t + 4 <= n) { run_group<DT, 4, VPT, MIXED>(m, prog, t, n, off); t += 4; }
+        if (U > 2 && t + 2 <= n) { run_group<DT, 2, VPT, MIXED>(m, prog, t, n, off); t += 2; }
+        if (U > 1 && t < n) { run_group<DT, 1, VPT, MIXED>(m, prog, t, n, off); t += 1; }
         if (SEG && a.n_save > 0) {
 #pragma unroll
             for (int L = 0; L < D; ++L) {
@@ -424,6 +525,10 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
                         if (live[j]) store_acc<DT>(a.spill + (size_t)L * a.level_stride, off[j], &m.acc[L][j * W]);
                 }
             }
+        } else if (MIXED && stores_accumulators(prog)) {
+#pragma unroll
+            for (int j = 0; j < VPT; ++j)
+                if (live[j]) store_kept<DT>((char *)dst, off[j], &m.acc[0][j * W]);
         } else {
 #pragma unroll
             for (int j = 0; j < VPT; ++j) {
@@ -444,13 +549,19 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
                 if (L < a.n_restore) m.acc[L][0] = *(const A *)(a.spill + (size_t)L * a.level_stride + acc_off);
         }
         for (int t = 0; t < n; ++t) {
-            A x[1] = {load_elem<DT>(prog[t].src, off)};
-            m.step(prog[t].ctl, x);
+            const void *const src = prog[t].src;
+            const uint32_t ctl = prog[t].ctl;
+            A x[1];
+            if (MIXED && (ctl & kPartialBit)) x[0] = *(const A *)((const char *)src + kept_elem_offset<DT>(off));
+            else x[0] = load_elem<DT>(src, off);
+            m.step(ctl, x);
         }
         if (SEG && a.n_save > 0) {
 #pragma unroll
             for (int L = 0; L < D; ++L)
                 if (L < a.n_save) *(A *)(a.spill + (size_t)L * a.level_stride + acc_off) = m.acc[L][0];
+        } else if (MIXED && stores_accumulators(prog)) {
+            *(A *)((char *)dst + kept_elem_offset<DT>(off)) = m.acc[0][0];
         } else {
             store_elem<DT>(dst, off, m.acc[0][0]);
         }
@@ -658,49 +769,6 @@ __global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains_inline(con
     chains_workgroup<DT, OP>(a.base, (const uint4 *)&a.table[0]);
 }
 
-// Layout of a kept partial result: one accumulator-typed value (4 bytes) per element of the
-// object. The accumulators of 64 consecutive source vectors (the vectors the lanes of a wave hold)
-// form a block of Q * 1 KiB, Q = W / 4: first the accumulators 0..3 of all 64 vectors, then 4..7 of
-// all 64 (bf16: Q = 2; for 32-bit elements the layout is simply that of the object). Every store
-// and load instruction of a wave then covers 1 KiB of consecutive addresses and a partial is one
-// sequential stream. With a vector's W accumulators side by side instead, each instruction would
-// touch every other 16 bytes of 2 KiB (measured: 10 % more bytes written to memory than stored);
-// with the two halves in two planes an object's length apart, twice as many write streams (10 %
-// slower).
-template <int DT> __device__ __forceinline__ size_t kept_offset(size_t off, int q)
-{
-    constexpr size_t Q = Traits<DT>::W / 4;
-    const size_t v = off >> 4;                   // index of the 16-byte source vector
-    return ((v >> 6) * Q + (size_t)q) * 1024 + (v & 63) * 16;
-}
-template <int DT> __device__ __forceinline__ void load_kept(const char *base, size_t off, typename Traits<DT>::acc_t *x)
-{
-    using A = typename Traits<DT>::acc_t;
-#pragma unroll
-    for (int q = 0; q < Traits<DT>::W / 4; ++q) {
-        const uint4 r = ld16(base, kept_offset<DT>(off, q));
-        x[4 * q + 0] = __builtin_bit_cast(A, r.x);
-        x[4 * q + 1] = __builtin_bit_cast(A, r.y);
-        x[4 * q + 2] = __builtin_bit_cast(A, r.z);
-        x[4 * q + 3] = __builtin_bit_cast(A, r.w);
-    }
-}
-template <int DT> __device__ __forceinline__ void store_kept(char *base, size_t off, const typename Traits<DT>::acc_t *x)
-{
-#pragma unroll
-    for (int q = 0; q < Traits<DT>::W / 4; ++q) {
-        const uint4 r = make_uint4(__builtin_bit_cast(uint32_t, x[4 * q + 0]), __builtin_bit_cast(uint32_t, x[4 * q + 1]),
-                                   __builtin_bit_cast(uint32_t, x[4 * q + 2]), __builtin_bit_cast(uint32_t, x[4 * q + 3]));
-        st16(base, kept_offset<DT>(off, q), r);
-    }
-}
-// where the accumulator of the single element at object byte offset off lives
-template <int DT> __device__ __forceinline__ size_t kept_elem_offset(size_t off)
-{
-    const size_t i = (off & 15) / Traits<DT>::ES;           // element within its vector
-    return kept_offset<DT>(off & ~(size_t)15, (int)(i >> 2)) + (i & 3) * 4;
-}
-
 // The reduce that keeps and reuses partial results (failure repair, section 3.5.2: the partial
 // results that do not contain the failed object survive). Same tiling as reduce_body, one step
 // at a time. A step whose control word carries kPartialBit reads a kept partial instead of an
@@ -829,7 +897,7 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel_kept_inline(ReduceArgsI
 }
 
 // Program in device memory.
-template <int DT, int OP, int D, int VPT, int U, int THREADS>
+template <int DT, int OP, int D, int VPT, int U, int THREADS, bool MIXED = false>
 __global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
 {
     if (a.sub_entries > 0) {
@@ -839,9 +907,9 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
         const int lane = (int)threadIdx.x < a.sub_entries ? (int)threadIdx.x : a.sub_entries - 1;
         const uint4 *rec = (const uint4 *)a.prog + (size_t)blockIdx.y * (size_t)a.sub_entries;
         const LaneProg lp{rec[lane]};
-        reduce_body<DT, OP, D, VPT, U, THREADS>(a, lp, lp.n_entries(), lp.dst());
+        reduce_body<DT, OP, D, VPT, U, THREADS, false, MIXED>(a, lp, lp.n_entries(), lp.dst());
     } else {
-        reduce_body<DT, OP, D, VPT, U, THREADS>(a, (prog_ptr)(uintptr_t)a.prog, a.n_entries, a.dst);
+        reduce_body<DT, OP, D, VPT, U, THREADS, false, MIXED>(a, (prog_ptr)(uintptr_t)a.prog, a.n_entries, a.dst);
     }
 }
 
@@ -853,10 +921,10 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel_seg(ReduceArgs a)
 }
 
 // Program inside the kernel arguments.
-template <int DT, int OP, int D, int VPT, int U, int THREADS>
+template <int DT, int OP, int D, int VPT, int U, int THREADS, bool MIXED = false>
 __global__ __launch_bounds__(THREADS) void reduce_kernel_inline(ReduceArgsInline a)
 {
-    reduce_body<DT, OP, D, VPT, U, THREADS>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
+    reduce_body<DT, OP, D, VPT, U, THREADS, false, MIXED>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
 }
 
 // One source, n_dst destinations: each 16-byte vector is read once (non-temporal) and

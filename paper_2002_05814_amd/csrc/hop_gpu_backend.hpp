@@ -34,6 +34,8 @@ struct Shape {
 constexpr size_t kSplitWantSteps = 128;             // shorter programs are not worth extra launches
 constexpr int kSplitMaxRun = kMaxSubSteps;          // longest sub-program: a record fits the lanes of a wave
 constexpr size_t kSplitMaxBytes = 768u << 10;       // above, a wave's walk through the whole program is hidden behind the streaming
+constexpr size_t kSplitMaxBytesBf16 = 512u << 10;   // bf16's partial results are twice the range: the cut stops paying earlier
+inline size_t split_max_bytes(int dtype) { return dtype == HOP_BF16 ? kSplitMaxBytesBf16 : kSplitMaxBytes; }
 constexpr int kSplitMinRun = 4;
 constexpr size_t kSplitMaxScratch = 256u << 20;     // partial results of all sub-programs
 constexpr size_t kChainWantSteps = 48;              // shorter programs: one wave per tile walks them as fast
@@ -277,23 +279,27 @@ private:
 
     // Many inputs but few output tiles (the many-small-objects case): one wave per tile would walk
     // the whole program alone, so the independent subtrees are evaluated side by side first.
-    // Partials are stored in the accumulation type, which for bf16 is not the element type: bf16
-    // keeps the plain path. Measured (fp32 sums, 16-ary tree, inputs not in any cache): a wave that walks
+    // Partials are stored in the accumulation type, which for bf16 is not the element type: its
+    // sub-programs store 4-byte accumulators in the layout of a kept partial result, and the steps that
+    // read them say so (kernels instantiated for that: launch_reduce_subs and launch_reduce with mixed).
+    // Measured (fp32 sums, 16-ary tree, inputs not in any cache): a wave that walks
     // a program alone takes about 0.15 us per step whatever the range, so the cut pays while that is more
     // than the time to stream the range - up to about 768 KiB: 4000 inputs of 256 KiB 212 us against 620
-    // for the plain path, 1000 inputs of 1 MiB 212 us against 186.
+    // for the plain path, 1000 inputs of 1 MiB 212 us against 186. bf16, cut against plain: 128 inputs of 72 KiB
+    // 15.1 against 21.9, of 512 KiB 22.8 against 24.2, of 768 KiB 32.3 against 25.5; 512 inputs of 128 KiB 27.0
+    // against 81.4, of 768 KiB 90.9 against 99.5; 1000 of 256 KiB 76.7 against 185; 4000 of 128 KiB 125 against 792.
 
     bool wants_split(size_t n_steps, size_t range_bytes) const
     {
-        return dtype_ != HOP_BF16 && n_steps >= kSplitWantSteps && range_bytes <= kSplitMaxBytes;
+        return n_steps >= kSplitWantSteps && range_bytes <= split_max_bytes(dtype_);
     }
 
     int launch_split(const std::vector<Entry> &prog, size_t b0, size_t b1)
     {
         MultiPlan mp;
         if (!plan_passes(prog, kSplitWantSteps, kSplitMinRun, kSplitMaxRun, mp)) return HOP_PARTIAL;
-        const size_t range = b1 - b0;
-        const size_t part_bytes = (range + 255) & ~(size_t)255;
+        const bool mixed = dtype_ == HOP_BF16;
+        const size_t part_bytes = split_partial_bytes(dtype_, b0, b1), part_off = split_partial_base_offset(dtype_, b0);
         const size_t n_subs = mp.n_subs();
         if (part_bytes * n_subs > kSplitMaxScratch || n_subs > 65535) return HOP_PARTIAL;
         // partials, then every sub-program as a record of equal length per pass: from one block
@@ -318,7 +324,7 @@ private:
         char *partials = (char *)ws_.scratch(part_bytes * n_subs);
         if (!partials) return ws_.error();
         // Kernels address sources and results by the object's byte offset, so a partial that holds
-        // only [b0, b1) is passed as base - b0. Passes run in stream order: pass h reads what
+        // only [b0, b1) is passed as base - b0 (bf16: less the offset of b0's block of accumulators). Passes run in stream order: pass h reads what
         // passes < h wrote.
         // All passes' records, then the top program, travel in one copy.
         std::vector<DevEntry> blob;
@@ -330,30 +336,30 @@ private:
                 if (mp.height[g] != pass) continue;
                 const size_t rec_at = blob.size();
                 SubHeader h;
-                h.dst = (void *)((uintptr_t)partials + g * part_bytes - b0);
+                h.dst = (void *)((uintptr_t)partials + g * part_bytes - part_off);
                 h.n_entries = (uint32_t)(mp.begin[g + 1] - mp.begin[g]);
-                h.reserved = 0;
+                h.flags = mixed ? kSubStoresAccumulators : 0u;
                 DevEntry raw;
                 std::memcpy(&raw, &h, sizeof raw);
                 blob.push_back(raw);
                 for (int32_t t = mp.begin[g]; t < mp.begin[g + 1]; ++t)
-                    blob.push_back(resolve(mp.steps[(size_t)t], partials, part_bytes, b0));
+                    blob.push_back(resolve(mp.steps[(size_t)t], partials, part_bytes, part_off, mixed));
                 mark_runs(blob.data() + rec_at + 1, blob.size() - rec_at - 1);
                 blob.resize(rec_at + (size_t)pi.sub_entries, DevEntry{nullptr, 0, 0});
             }
         }
         const size_t top_at = blob.size();
-        for (const Entry &e : mp.top) blob.push_back(resolve(e, partials, part_bytes, b0));
+        for (const Entry &e : mp.top) blob.push_back(resolve(e, partials, part_bytes, part_off, mixed));
         mark_runs(blob.data() + top_at, blob.size() - top_at);
         const DevEntry *dev = (const DevEntry *)ws_.stage_in_place(blob.data(), blob.size() * sizeof(DevEntry));
         if (!dev) return ws_.error();
         for (const PassInfo &pi : passes) {
             if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.records_at, pi.sub_entries, pi.n_subs, b0,
-                                   b1) != hipSuccess)
+                                   b1, mixed) != hipSuccess)
                 return HOP_ERR_DEVICE;
         }
         hipError_t e = launch_reduce(stream_, dtype_, op_, mp.top_depth, blob.data() + top_at, dev + top_at,
-                                     (int)mp.top.size(), dsts_[0], b0, b1);
+                                     (int)mp.top.size(), dsts_[0], b0, b1, mixed);
         return e == hipSuccess ? HOP_OK : HOP_ERR_DEVICE;
     }
 
@@ -454,12 +460,15 @@ public:
     }
 
 private:
-    DevEntry resolve(const Entry &e, const char *partials, size_t part_bytes, size_t b0) const
+    // partial q of a cut program lies at partials + q * part_bytes, and the kernels address it from part_off
+    // bytes in front of that; partial_bit: its values are accumulators, not elements (bf16)
+    DevEntry resolve(const Entry &e, const char *partials, size_t part_bytes, size_t part_off, bool partial_bit = false) const
     {
         DevEntry d;
         d.src = e.obj >= 0 ? objs_[e.obj]
-                           : (const void *)((uintptr_t)partials + (size_t)(-e.obj - 1) * part_bytes - b0);
-        d.ctl = (uint32_t)e.level | ((uint32_t)e.set << 8) | ((uint32_t)e.n_fold << 16);
+                           : (const void *)((uintptr_t)partials + (size_t)(-e.obj - 1) * part_bytes - part_off);
+        d.ctl = (uint32_t)e.level | ((uint32_t)e.set << 8) | ((uint32_t)e.n_fold << 16) |
+                (e.obj < 0 && partial_bit ? kPartialBit : 0u);
         d.aux = 0;
         return d;
     }

@@ -28,8 +28,11 @@ constexpr int kInlineEntries = 128;
 struct SubHeader {
     void *dst;                 // where the sub-program's result goes
     uint32_t n_entries;        // its number of steps
-    uint32_t reserved;
+    uint32_t flags;            // kSubStoresAccumulators or 0
 };
+// The sub-program's result is stored as accumulator-typed values, 4 bytes per element in the layout of a
+// kept partial result, not as elements (bf16: what later sub-programs and the top read with kPartialBit).
+constexpr uint32_t kSubStoresAccumulators = 1u;
 static_assert(sizeof(SubHeader) == sizeof(DevEntry), "a header takes one entry");
 constexpr int kMaxSubSteps = 63;   // header + steps fit the 64 lanes of a wave
 
@@ -148,7 +151,7 @@ const char *kernel_config();
 // steps in device memory. Every other pointer is a device pointer.
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
                          const DevEntry *dev_prog, int n_entries, void *dst, size_t byte_begin,
-                         size_t byte_end);
+                         size_t byte_end, bool mixed = false);
 
 // Steps [0, n_entries) of dev_prog as one segment of a longer program: n_restore accumulator
 // levels are read back from the spill area first; then n_save levels are written to it, or, if
@@ -169,8 +172,15 @@ hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, 
 // The same for n_subs independent sub-programs at once: dev_records holds n_subs records of
 // sub_entries entries (SubHeader, steps, padding; 2 <= sub_entries <= kMaxSubSteps + 1); every
 // sub-program covers the same byte range and needs at most `depth` accumulator levels.
+// mixed (bf16 only): steps may carry kPartialBit and headers kSubStoresAccumulators.
 hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
-                              int sub_entries, int n_subs, size_t byte_begin, size_t byte_end);
+                              int sub_entries, int n_subs, size_t byte_begin, size_t byte_end, bool mixed = false);
+// Bytes of one partial result of a cut program over [byte_begin, byte_end) of the objects, and how far in
+// front of its first byte the address lies that the kernels take as its base (they address sources by the
+// object's byte offset). 32-bit elements: the range itself. bf16: 4-byte accumulators in the layout of a
+// kept partial result, whose blocks of 64 vectors start at multiples of 1 KiB of the object.
+size_t split_partial_bytes(int dtype, size_t byte_begin, size_t byte_end);
+size_t split_partial_base_offset(int dtype, size_t byte_begin);
 
 // The program as chains in one launch: dev_table as described at ChainArgs (n_chains records, written for
 // values of chain_value_bytes(dtype) bytes each) or, for tables that ride in the kernel arguments, host_table (the

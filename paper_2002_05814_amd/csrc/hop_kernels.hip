@@ -143,10 +143,11 @@ static size_t chip_slots(const void *kernel)
 
 hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const DevEntry *host_steps,
                          const DevEntry *dev_prog, int n_entries, void *dst, size_t byte_begin,
-                         size_t byte_end)
+                         size_t byte_end, bool mixed)
 {
     if (byte_end <= byte_begin || n_entries <= 0) return hipSuccess;
     const Launcher l = pick(dtype, op, depth);
+    if (mixed && (!l.dev_small_mixed || !l.inl_small_mixed)) return hipErrorInvalidValue;
     ReduceArgsInline a;
     a.base.prog = dev_prog;
     a.base.n_entries = n_entries;
@@ -161,7 +162,7 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     // 32 MiB in a binary tree: 81 % of the HBM peak, against 59-63 % for one source at a time and
     // 70-79 %, depending on how the objects lie, for 1 KiB tiles with 8 sources in flight)
     const bool deep_bf16 = dtype == HOP_BF16 && depth > 4 && depth <= kDeepBf16MaxDepth;
-    int shape = tiles4k < kSmallLaunchTiles ? 0 : (tiles4k < kMidLaunchTiles || deep_bf16) ? 1 : 2;
+    int shape = (tiles4k < kSmallLaunchTiles || mixed) ? 0 : (tiles4k < kMidLaunchTiles || deep_bf16) ? 1 : 2;
     const bool inl = n_entries <= kInlineEntries;
     const size_t n_all = a.base.n_vec + (size_t)a.base.lead_vecs;
     // strided: whole groups of (vpt << stride) pieces, one workgroup per 2^stride-th of a group
@@ -191,10 +192,12 @@ hipError_t launch_reduce(hipStream_t stream, int dtype, int op, int depth, const
     if (inl) {
         for (int i = 0; i < n_entries; ++i) a.steps[i] = host_steps[i];
         for (int i = n_entries; i < kInlineEntries; ++i) a.steps[i] = DevEntry{nullptr, 0, 0};
-        return enqueue(shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), lds, stream, a, true);
+        return enqueue(mixed ? l.inl_small_mixed : shape == 0 ? l.inl_small : shape == 1 ? l.inl_mid : l.inl, dim3(grid), lds,
+                       stream, a, true);
     }
     if (!dev_prog) return hipErrorInvalidValue;
-    return enqueue(shape == 0 ? l.dev_small : shape == 1 ? l.dev_mid : l.dev, dim3(grid), lds, stream, a.base, true);
+    return enqueue(mixed ? l.dev_small_mixed : shape == 0 ? l.dev_small : shape == 1 ? l.dev_mid : l.dev, dim3(grid), lds, stream,
+                   a.base, true);
 }
 
 hipError_t launch_reduce_segment(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_prog,
@@ -272,12 +275,13 @@ hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, 
 }
 
 hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
-                              int sub_entries, int n_subs, size_t byte_begin, size_t byte_end)
+                              int sub_entries, int n_subs, size_t byte_begin, size_t byte_end, bool mixed)
 {
     if (byte_end <= byte_begin || n_subs <= 0) return hipSuccess;
     if (!dev_records || n_subs > 65535 || sub_entries < 2 || sub_entries > kMaxSubSteps + 1) return hipErrorInvalidValue;
     static_assert(kMaxSubSteps + 1 <= kThreads, "one lane per entry of a record");
     const Launcher l = pick(dtype, op, depth);
+    if (mixed && !l.dev_small_mixed) return hipErrorInvalidValue;
     ReduceArgs a;
     a.prog = dev_records;
     a.n_entries = 0;
@@ -285,7 +289,21 @@ hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, 
     fill_range(a, dtype, byte_begin, byte_end);
     a.sub_entries = sub_entries;
     const unsigned grid = grid_for(a.n_vec, (size_t)kThreads);
-    return enqueue(l.dev_small, dim3(grid, (unsigned)n_subs), 0, stream, a, false);
+    return enqueue(mixed ? l.dev_small_mixed : l.dev_small, dim3(grid, (unsigned)n_subs), 0, stream, a, false);
+}
+
+// bf16: whole blocks of 64 vectors (1 KiB of the object, 2 KiB of accumulators), so that the layout of a kept
+// partial result, which is defined on the object's byte offsets, holds inside the range's own array
+size_t split_partial_bytes(int dtype, size_t byte_begin, size_t byte_end)
+{
+    if (dtype != HOP_BF16) return (byte_end - byte_begin + 255) & ~(size_t)255;
+    const size_t first = byte_begin / 1024, last = (byte_end + 1023) / 1024;
+    return (last - first) * 2048;
+}
+
+size_t split_partial_base_offset(int dtype, size_t byte_begin)
+{
+    return dtype != HOP_BF16 ? byte_begin : byte_begin / 1024 * 2048;
 }
 
 size_t chain_value_bytes(int dtype) { return (size_t)kChainLanes * (dtype == HOP_BF16 ? 8 : 4) * 4; }

@@ -14,12 +14,24 @@
 
 namespace hop {
 
+// The small-shape kernels whose steps may read partial results: for bf16 only, whose partial results are
+// not of the element type.
+template <int DT, int OP, int D> struct mixed_small {
+    static void (*dev())(ReduceArgs) { return nullptr; }
+    static void (*inl())(ReduceArgsInline) { return nullptr; }
+};
+template <int OP, int D> struct mixed_small<HOP_BF16, OP, D> {
+    static void (*dev())(ReduceArgs) { return reduce_kernel<HOP_BF16, OP, D, 1, kSmallUnroll, kThreads, true>; }
+    static void (*inl())(ReduceArgsInline) { return reduce_kernel_inline<HOP_BF16, OP, D, 1, kSmallUnroll, kThreads, true>; }
+};
+
 template <int DT, int OP, int D> static Launcher make_launcher()
 {
     constexpr int V = VecPerLane<Traits<DT>::W, D>::value;
     return {reduce_kernel<DT, OP, D, V, kUnroll, kThreads>, reduce_kernel_inline<DT, OP, D, V, kUnroll, kThreads>,
             reduce_kernel<DT, OP, D, 1, kSmallUnroll, kThreads>,
             reduce_kernel_inline<DT, OP, D, 1, kSmallUnroll, kThreads>,
+            mixed_small<DT, OP, D>::dev(), mixed_small<DT, OP, D>::inl(),
             reduce_kernel<DT, OP, D, (V < kMidVecs ? V : kMidVecs), kMidUnroll, kThreads>,
             reduce_kernel_inline<DT, OP, D, (V < kMidVecs ? V : kMidVecs), kMidUnroll, kThreads>,
             reduce_kernel_seg<DT, OP, D, V, kUnroll, kThreads>, reduce_kernel_kept<DT, OP, D, V, kThreads>,

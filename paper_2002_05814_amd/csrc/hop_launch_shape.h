@@ -73,6 +73,8 @@ struct Launcher {
     void (*inl)(ReduceArgsInline);
     void (*dev_small)(ReduceArgs);
     void (*inl_small)(ReduceArgsInline);
+    void (*dev_small_mixed)(ReduceArgs);           // bf16 only (else null): steps may read partial results
+    void (*inl_small_mixed)(ReduceArgsInline);
     void (*dev_mid)(ReduceArgs);
     void (*inl_mid)(ReduceArgsInline);
     void (*seg)(ReduceArgs);

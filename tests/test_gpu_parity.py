@@ -155,15 +155,24 @@ def test_many_small_objects_take_the_multi_pass_path(dtype):
             fm[bad] = rng.integers(0, C + 1, size=int(bad.sum()))
         for op in ("sum", "max"):
             run_both(w, op, fm=fm)
-    if dtype != "bf16":
-        # thousands of inputs in a binary tree: the program is cut in two rounds (two passes and the top)
-        w = base.scaled(256 * ES[dtype], 256 * ES[dtype], n=4000, k=3900, tree_degree=2, order_seed=77, data_seed=78,
-                        fail={}, name="small_deep", dist=dist, n_dst=0)
-        run_both(w, "sum")
-        # objects of a few hundred KiB: still cut (a wave alone would walk 1900 steps), with tens of MiB of partials
-        w = base.scaled(300 * 1024 + 4, 1 << 20, n=2000, k=1900, tree_degree=16, order_seed=79, data_seed=80,
-                        fail={}, name="small_wide", dist=dist, n_dst=0)
-        run_both(w, "sum")
+    # thousands of inputs in a binary tree: the program is cut in two rounds (two passes and the top)
+    w = base.scaled(256 * ES[dtype], 256 * ES[dtype], n=4000, k=3900, tree_degree=2, order_seed=77, data_seed=78,
+                    fail={}, name="small_deep", dist=dist, n_dst=0)
+    run_both(w, "sum")
+    # objects of a few hundred KiB: still cut (a wave alone would walk 1900 steps), with tens of MiB of partials
+    # (bf16: the partial results are 4-byte accumulators, and the steps that read them say so)
+    w = base.scaled(300 * 1024 + 4, 1 << 20, n=2000, k=1900, tree_degree=16, order_seed=79, data_seed=80,
+                    fail={}, name="small_wide", dist=dist, n_dst=0)
+    run_both(w, "sum")
+    # the same over chunk runs that neither start nor end at a multiple of 1 KiB (the blocks in which bf16's
+    # partial results are laid out), beyond the one-launch form's 64 KiB, and with a ragged last chunk
+    w = base.scaled(70 * 1024 * 3 + 2 * ES[dtype], 16 * 4500, n=300, k=290, tree_degree=4, order_seed=81, data_seed=82,
+                    fail={}, name="small_chunks", dist=dist, n_dst=0)
+    for op in ("sum", "min"):
+        run_both(w, op)
+    fm = np.full(300, -1, np.int64)
+    fm[[5, 77, 200]] = [0, 1, 2]
+    run_both(w, "sum", fm=fm)
 
 
 def takes_the_one_launch_path(w, order=None, fm=None):
