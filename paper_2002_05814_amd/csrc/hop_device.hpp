@@ -896,9 +896,9 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel_kept_inline(ReduceArgsI
     reduce_body_kept<DT, OP, D, VPT, THREADS>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
 }
 
-// Program in device memory.
-template <int DT, int OP, int D, int VPT, int U, int THREADS, bool MIXED = false>
-__global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
+// Program in device memory (or, with sub_entries set, the records of several sub-programs).
+template <int DT, int OP, int D, int VPT, int U, int THREADS, bool MIXED>
+__device__ __forceinline__ void reduce_kernel_body(const ReduceArgs &a)
 {
     if (a.sub_entries > 0) {
         // several independent sub-programs in one launch: blockIdx.y picks a record, lane i fetches
@@ -913,6 +913,19 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
     }
 }
 
+template <int DT, int OP, int D, int VPT, int U, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
+{
+    reduce_kernel_body<DT, OP, D, VPT, U, THREADS, false>(a);
+}
+// The same for programs some of whose steps read partial results (kPartialBit) and sub-programs whose
+// headers may ask for accumulators as their result: see MIXED at reduce_body.
+template <int DT, int OP, int D, int VPT, int U, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel_mixed(ReduceArgs a)
+{
+    reduce_kernel_body<DT, OP, D, VPT, U, THREADS, true>(a);
+}
+
 // A segment of a program in device memory, with accumulators restored from and/or saved to the spill area.
 template <int DT, int OP, int D, int VPT, int U, int THREADS>
 __global__ __launch_bounds__(THREADS) void reduce_kernel_seg(ReduceArgs a)
@@ -921,10 +934,15 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel_seg(ReduceArgs a)
 }
 
 // Program inside the kernel arguments.
-template <int DT, int OP, int D, int VPT, int U, int THREADS, bool MIXED = false>
+template <int DT, int OP, int D, int VPT, int U, int THREADS>
 __global__ __launch_bounds__(THREADS) void reduce_kernel_inline(ReduceArgsInline a)
 {
-    reduce_body<DT, OP, D, VPT, U, THREADS, false, MIXED>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
+    reduce_body<DT, OP, D, VPT, U, THREADS>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
+}
+template <int DT, int OP, int D, int VPT, int U, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel_mixed_inline(ReduceArgsInline a)
+{
+    reduce_body<DT, OP, D, VPT, U, THREADS, false, true>(a.base, &a.steps[0], a.base.n_entries, a.base.dst);
 }
 
 // One source, n_dst destinations: each 16-byte vector is read once (non-temporal) and

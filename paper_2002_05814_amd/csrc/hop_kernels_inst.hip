@@ -21,8 +21,8 @@ template <int DT, int OP, int D> struct mixed_small {
     static void (*inl())(ReduceArgsInline) { return nullptr; }
 };
 template <int OP, int D> struct mixed_small<HOP_BF16, OP, D> {
-    static void (*dev())(ReduceArgs) { return reduce_kernel<HOP_BF16, OP, D, 1, kSmallUnroll, kThreads, true>; }
-    static void (*inl())(ReduceArgsInline) { return reduce_kernel_inline<HOP_BF16, OP, D, 1, kSmallUnroll, kThreads, true>; }
+    static void (*dev())(ReduceArgs) { return reduce_kernel_mixed<HOP_BF16, OP, D, 1, kSmallUnroll, kThreads>; }
+    static void (*inl())(ReduceArgsInline) { return reduce_kernel_mixed_inline<HOP_BF16, OP, D, 1, kSmallUnroll, kThreads>; }
 };
 
 template <int DT, int OP, int D> static Launcher make_launcher()
