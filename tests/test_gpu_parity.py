@@ -1296,6 +1296,26 @@ def test_session_with_a_workspace_of_the_callers():
                                            wm.chunk_bytes // 4, wm.tree_degree, morder, mfm)
     assert rc == morc and info["k_eff"] == mk_eff
     assert np.array_equal(bits(workloads.to_numpy(mdst)), bits(mwant))
+    # hundreds of bf16 objects of 100 KiB: the program is cut into sub-programs whose partial results (4-byte
+    # accumulators in whole blocks) and records come out of the workspace, which the library sized itself
+    wb = workloads.WORKLOADS[4].scaled(100 * 1024 + 6, 16 * 2100, n=260, k=250, tree_degree=16, order_seed=35, data_seed=36,
+                                       fail={}, name="own_workspace_cut", n_dst=0)
+    bobjs = workloads.make_objects(wb, device=d)
+    border = wb.ready_order()
+    need_cut = hop.hop_workspace_bytes(wb.n, wb.k, wb.object_bytes, wb.chunk_bytes, wb.tree_degree, wb.dtype)
+    assert need_cut >= 15 * 2 * 16 * 2100                 # 15 subtrees below the root, twice the bytes of a chunk each
+    ws = torch.zeros(need_cut, dtype=torch.uint8, device=d)
+    bdst = torch.zeros_like(bobjs[0])
+    rc, info = session_replay(bobjs, bdst, wb.k, "sum", wb.dtype, wb.chunk_bytes, wb.tree_degree, border, None, wb.n_chunks,
+                              fine=False, workspace=ws)
+    torch.cuda.synchronize()
+    borc, bwant, bk_eff, _ = oracle.reduce([workloads.to_numpy(o) for o in bobjs], wb.k, oracle.SUM, oracle.BF16,
+                                           wb.chunk_bytes // 2, wb.tree_degree, border, None)
+    assert rc == borc and info["k_eff"] == bk_eff
+    assert np.array_equal(bits(workloads.to_numpy(bdst)), bits(bwant))
+    # the cut was made (a workspace too small for it would have sent the call down the plain path, which leaves
+    # only the staged program behind): the partial results are still there
+    assert int((ws != 0).sum()) > 15 * wb.object_bytes
     # a workspace that cannot hold the saved accumulators: the event that needs them says so
     small = torch.empty(1 << 20, dtype=torch.uint8, device=d)
     dst = torch.zeros_like(objs[0])
