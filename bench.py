@@ -362,8 +362,9 @@ def main():
                          "inputs not cached, and fit time = fixed cost + bytes / rate: what part of a mid-size launch "
                          "is the launch and what part the kernel")
     ap.add_argument("--many-objects-sweep", action="store_true",
-                    help="also time fp32 sums over 128..4000 inputs of 1 KiB..1 MiB in a 16-ary tree (launch- and "
+                    help="also time sums over 128..4000 inputs of 1 KiB..1 MiB in a 16-ary tree (launch- and "
                          "latency-bound calls: us per call and GB/s per shape)")
+    ap.add_argument("--many-objects-dtype", choices=["f32", "bf16", "i32"], default="f32")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run hop_broadcast of one 256 MiB object to one destination a few times: a copy of "
                          "known size against which hardware byte counters can be scaled")
@@ -599,9 +600,12 @@ def main():
         for r in rows:
             r["model_us"] = round(fixed + slope * r["bytes"], 2)
     if args.many_objects_sweep:
-        # many inputs of small to medium size (fp32 sum, 16-ary tree), inputs not in any cache: which of the
-        # library's forms of a long program takes the call depends on inputs x size (see path in each row)
-        base5 = workloads.WORKLOADS[5]
+        # many inputs of small to medium size (sum, 16-ary tree), inputs not in any cache: which of the
+        # library's forms of a long program takes the call depends on inputs x size
+        sweep_dt = args.many_objects_dtype
+        base5 = workloads.WORKLOADS[{"f32": 5, "bf16": 4, "i32": 3}[sweep_dt]]
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}[sweep_dt]
+        es = workloads.ELEM_BYTES[sweep_dt]
         rows = []
         for n_in in (128, 256, 1000, 4000):
             for nbytes in (1 << 10, 4 << 10, 16 << 10, 64 << 10, 256 << 10, 1 << 20):
@@ -612,11 +616,11 @@ def main():
                 n_sets = max(4, min(64, (256 << 20) // (n_in * nbytes)))
                 sets = []
                 for _ in range(n_sets):
-                    block = torch.rand((n_in, nbytes // 4), device=dev)
+                    block = (torch.rand((n_in, nbytes // es), device=dev) * 64).to(tdt)
                     t = hop.PtrTable([block[i] for i in range(n_in)])
                     t.keep = block
                     sets.append(t)
-                dd = [torch.zeros(nbytes // 4, device=dev) for _ in range(2)]
+                dd = [torch.zeros(nbytes // es, device=dev, dtype=tdt) for _ in range(2)]
                 so = ws.ready_order()
                 stt = {"i": 0, "info": None}
                 strm = torch.cuda.current_stream().cuda_stream
@@ -632,7 +636,7 @@ def main():
                              "GB/s": round(counted / (med * 1e-3) / 1e9, 1), "launches": stt["info"]["n_launches"]})
                 del sets, dd
                 torch.cuda.empty_cache()
-        out["many_objects_sweep"] = rows
+        out["many_objects_sweep"] = {"dtype": sweep_dt, "rows": rows}
     if args.streamed_interval_us is not None:
         out["streamed_chunks"] = streamed_chunks(hop, torch, w, objs, order, dsts[0][0], args.streamed_interval_us)
     if args.paced_interval_us is not None:
