@@ -133,7 +133,7 @@ def test_every_input_count_up_to_forty(d):
 
 @pytest.mark.parametrize("dtype", ["f32", "i32", "bf16"])
 def test_many_small_objects_take_the_multi_pass_path(dtype):
-    # hundreds of inputs, few tiles: programs are cut into passes of independent subtrees (f32, i32);
+    # hundreds of inputs, few tiles: programs are cut into passes of independent subtrees (bf16: with fp32 partial results);
     # results must not change by a bit
     rng = np.random.default_rng({"f32": 71, "i32": 72, "bf16": 73}[dtype])
     base = workloads.WORKLOADS[{"f32": 5, "bf16": 4, "i32": 3}[dtype]]
