@@ -445,10 +445,10 @@ __device__ __forceinline__ void run_group(M &m, const Prog prog, int t, int n, c
 // result is stored like in a whole-program launch. The spill area holds one
 // object-sized array of accumulator-typed values per level.
 //
-// MIXED (bf16): steps with kPartialBit read a partial result, 4 bytes per element laid out as kept_offset
-// says, and a sub-program whose header says so stores its result that way: the pieces of a long program
-// that was cut into sub-programs (their partial results must be accumulator-typed, or the bits of the
-// result would depend on the cut).
+// The pieces of a long bf16 program that was cut into sub-programs: their partial results must be
+// accumulator-typed, or the bits of the result would depend on the cut. A sub-program whose header says so
+// stores its result as 4 bytes per element, laid out as kept_offset says (any bf16 kernel that runs
+// sub-programs can do that), and MIXED kernels take steps with kPartialBit, which read such a result.
 template <int DT, int OP, int D, int VPT, int U, int THREADS, bool SEG = false, bool MIXED = false, class Prog>
 __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog, const int n, void *const dst)
 {
@@ -525,7 +525,7 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
                         if (live[j]) store_acc<DT>(a.spill + (size_t)L * a.level_stride, off[j], &m.acc[L][j * W]);
                 }
             }
-        } else if (MIXED && stores_accumulators(prog)) {
+        } else if (DT == HOP_BF16 && stores_accumulators(prog)) {
 #pragma unroll
             for (int j = 0; j < VPT; ++j)
                 if (live[j]) store_kept<DT>((char *)dst, off[j], &m.acc[0][j * W]);
@@ -560,7 +560,7 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs &a, const Prog prog
 #pragma unroll
             for (int L = 0; L < D; ++L)
                 if (L < a.n_save) *(A *)(a.spill + (size_t)L * a.level_stride + acc_off) = m.acc[L][0];
-        } else if (MIXED && stores_accumulators(prog)) {
+        } else if (DT == HOP_BF16 && stores_accumulators(prog)) {
             *(A *)((char *)dst + kept_elem_offset<DT>(off)) = m.acc[0][0];
         } else {
             store_elem<DT>(dst, off, m.acc[0][0]);
@@ -918,8 +918,7 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(ReduceArgs a)
 {
     reduce_kernel_body<DT, OP, D, VPT, U, THREADS, false>(a);
 }
-// The same for programs some of whose steps read partial results (kPartialBit) and sub-programs whose
-// headers may ask for accumulators as their result: see MIXED at reduce_body.
+// The same for programs some of whose steps read partial results (kPartialBit): see MIXED at reduce_body.
 template <int DT, int OP, int D, int VPT, int U, int THREADS>
 __global__ __launch_bounds__(THREADS) void reduce_kernel_mixed(ReduceArgs a)
 {

@@ -354,8 +354,10 @@ private:
         const DevEntry *dev = (const DevEntry *)ws_.stage_in_place(blob.data(), blob.size() * sizeof(DevEntry));
         if (!dev) return ws_.error();
         for (const PassInfo &pi : passes) {
+            // the first pass reads objects only: the kernel without the registers for partial results does
+            const bool reads_partials = mixed && &pi != &passes[0];
             if (launch_reduce_subs(stream_, dtype_, op_, pi.depth, dev + pi.records_at, pi.sub_entries, pi.n_subs, b0,
-                                   b1, mixed) != hipSuccess)
+                                   b1, reads_partials) != hipSuccess)
                 return HOP_ERR_DEVICE;
         }
         hipError_t e = launch_reduce(stream_, dtype_, op_, mp.top_depth, blob.data() + top_at, dev + top_at,

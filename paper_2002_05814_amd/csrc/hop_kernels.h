@@ -172,7 +172,7 @@ hipError_t launch_reduce_kept(hipStream_t stream, int dtype, int op, int depth, 
 // The same for n_subs independent sub-programs at once: dev_records holds n_subs records of
 // sub_entries entries (SubHeader, steps, padding; 2 <= sub_entries <= kMaxSubSteps + 1); every
 // sub-program covers the same byte range and needs at most `depth` accumulator levels.
-// mixed (bf16 only): steps may carry kPartialBit and headers kSubStoresAccumulators.
+// mixed (bf16 only): steps may carry kPartialBit. Headers may carry kSubStoresAccumulators either way (bf16).
 hipError_t launch_reduce_subs(hipStream_t stream, int dtype, int op, int depth, const DevEntry *dev_records,
                               int sub_entries, int n_subs, size_t byte_begin, size_t byte_end, bool mixed = false);
 // Bytes of one partial result of a cut program over [byte_begin, byte_end) of the objects, and how far in
