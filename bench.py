@@ -42,7 +42,7 @@ PROFILED_TRAFFIC = {
                      "indexed like the elements, nontemporal; programs of 48 steps or more over at most 64 KiB: one "
                      "launch, 256 lanes per 64-byte column, chains of at most 23 items folded by teams of 4 lanes with all "
                      "their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments, "
-                     "four columns in a row per die"),
+                     "four columns in a row per die; above 64 KiB up to 768 KiB: 512 lanes per 1 KiB column, a wave per chain"),
     "workloads": {
         "cfg2_async_sgd": {"bytes_per_call": 872327474, "profile": "profiles/hbm_traffic_all_workloads.md"},
         "cfg3_rl_allreduce": {"bytes_per_call": 2163381761, "profile": "profiles/hbm_traffic_all_workloads.md"},

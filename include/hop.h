@@ -503,7 +503,7 @@ int hop_calibrate(double *latency_s, double *bytes_per_s);
  *     64 of them (shorter programs and tables ride in the kernel arguments),
  *     in blocks of 256 KiB (the same number of bytes of pinned host memory
  *     goes with them);
- *   - for a call over 48 or more inputs of at most 64 KiB each: the table of
+ *   - for a call over 48 or more inputs of at most 768 KiB each: the table of
  *     the one-launch form of its program (192 bytes per chain, fewer chains
  *     than inputs);
  *   - for a call over 128 or more inputs of at most 768 KiB each (bf16:

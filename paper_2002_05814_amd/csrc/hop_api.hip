@@ -1054,7 +1054,7 @@ size_t hop_workspace_bytes(int n, int k, size_t object_bytes, size_t chunk_bytes
         size_t total = blocks(staged);
         // the cut into sub-programs of a call over many small objects: their partial results and records
         // the program as chains in one launch: a table of one record per chain (fewer chains than inputs)
-        if ((size_t)k >= kChainWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= kChainMaxBytes)
+        if ((size_t)k >= kChainWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= kChainWideMaxBytes)
             total += blocks(round256((size_t)k * kChainRecordWords * sizeof(uint64_t)));
         if ((size_t)k >= kSplitWantSteps && object_bytes > 0 && std::min(object_bytes, shape.chunk_bytes) <= split_max_bytes((int)dtype)) {
             Tree tr;

@@ -594,7 +594,12 @@ template <int DT, int OP> __device__ __forceinline__ typename Traits<DT>::acc_t 
 // either the lane's byte offset into the object or the lane's place in the LDS window.
 // A value in LDS: W accumulators per lane, the value at byte offset b of the LDS array at
 // [b + lane * W * 4].
-template <int DT, int OP, bool TAIL>
+//
+// LANES, TEAMS: the narrow form is teams of kChainLanes lanes (64-byte columns, kChainTeams chains side by
+// side: ranges up to 64 KiB); the wide form is teams of kChainWideLanes = a whole wave each (1 KiB columns,
+// kChainWideTeams chains side by side: every load instruction covers 1 KiB of one object, for ranges of
+// hundreds of KiB, where the narrow form would need thousands of workgroups).
+template <int DT, int OP, bool TAIL, int LANES, int TEAMS>
 __device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *const table, typename Traits<DT>::acc_t *lds,
                                             const size_t off, const bool live)
 {
@@ -604,7 +609,7 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *con
     constexpr int R = kChainMaxItems;
     constexpr bool kAlike = T::ES == 4;
     static_assert(kChainRecordWords % 8 == 0 && R + 1 == kChainRecordWords, "records are read as 16-byte pairs of words, held eight at a time");
-    const int lane = (int)threadIdx.x % kChainLanes, team = (int)threadIdx.x / kChainLanes;
+    const int lane = (int)threadIdx.x % LANES, team = (int)threadIdx.x / LANES;
     char *const mine = (char *)lds + (size_t)lane * T::W * 4;           // this lane's part of the value at offset 0
     const uint64_t mine_flat = (uint64_t)(uintptr_t)(const void *)mine;
     // the identity value sits behind the chains' values; every team writes the same bytes
@@ -615,7 +620,7 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *con
     }
     __syncthreads();
     for (int p = 0; p < a.base.n_entries; ++p) {
-        for (uint32_t c = a.pass_begin[p] + (uint32_t)team; c < a.pass_begin[p + 1]; c += kChainTeams) {
+        for (uint32_t c = a.pass_begin[p] + (uint32_t)team; c < a.pass_begin[p + 1]; c += TEAMS) {
             const uint4 *const rec = table + (size_t)c * (kChainRecordWords / 2);
             uint64_t word[kChainRecordWords];
 #pragma unroll
@@ -729,30 +734,32 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *con
 }
 
 // The column (or, behind the last column, the elements after the last full vector) that this workgroup owns.
-template <int DT, int OP>
+template <int DT, int OP, int LANES, int TEAMS>
 __device__ __forceinline__ void chains_workgroup(const ChainArgs &a, const uint4 *const table)
 {
     using T = Traits<DT>;
     extern __shared__ __align__(16) unsigned char chain_values[];
     typename T::acc_t *const lds = (typename T::acc_t *)chain_values;
-    const size_t n_cols = (a.base.n_vec + kChainLanes - 1) / kChainLanes;
-    const size_t lane = threadIdx.x % kChainLanes;
+    const size_t n_cols = (a.base.n_vec + LANES - 1) / LANES;
+    const size_t lane = threadIdx.x % LANES;
     if (blockIdx.x < n_cols) {
-        // Two columns share a 128-byte line. Workgroups go to the chip's 8 dies in turn, each die with an L2
-        // of its own: within every whole block of 8 * kChainColumnRun workgroups, the workgroups that land on
-        // one die take kChainColumnRun columns in a row, so a line is fetched from memory by one L2, once.
         size_t col = blockIdx.x;
-        constexpr size_t kBlock = 8 * kChainColumnRun;
-        const size_t block0 = col / kBlock * kBlock;
-        if (block0 + kBlock <= n_cols) col = block0 + (col - block0) % 8 * kChainColumnRun + (col - block0) / 8;
-        const size_t v = col * kChainLanes + lane;
+        if constexpr (LANES * 16 < 128) {
+            // Two narrow columns share a 128-byte line. Workgroups go to the chip's 8 dies in turn, each die with
+            // an L2 of its own: within every whole block of 8 * kChainColumnRun workgroups, the workgroups that
+            // land on one die take kChainColumnRun columns in a row, so a line is fetched from memory by one L2, once.
+            constexpr size_t kBlock = 8 * kChainColumnRun;
+            const size_t block0 = col / kBlock * kBlock;
+            if (block0 + kBlock <= n_cols) col = block0 + (col - block0) % 8 * kChainColumnRun + (col - block0) / 8;
+        }
+        const size_t v = col * LANES + lane;
         const bool live = v < a.base.n_vec;
-        chains_body<DT, OP, false>(a, table, lds, a.base.byte_begin + (live ? v : a.base.n_vec - 1) * 16, live);
+        chains_body<DT, OP, false, LANES, TEAMS>(a, table, lds, a.base.byte_begin + (live ? v : a.base.n_vec - 1) * 16, live);
     } else {
         // the workgroups after the last column: the elements behind the last full vector, one per lane
-        const size_t i = (blockIdx.x - n_cols) * kChainLanes + lane;
+        const size_t i = (blockIdx.x - n_cols) * LANES + lane;
         const bool live = i < (size_t)a.base.n_tail;
-        chains_body<DT, OP, true>(a, table, lds, a.base.byte_begin + a.base.n_vec * 16 + (live ? i : 0) * T::ES, live);
+        chains_body<DT, OP, true, LANES, TEAMS>(a, table, lds, a.base.byte_begin + a.base.n_vec * 16 + (live ? i : 0) * T::ES, live);
     }
 }
 
@@ -760,13 +767,24 @@ __device__ __forceinline__ void chains_workgroup(const ChainArgs &a, const uint4
 template <int DT, int OP>
 __global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains(const ChainArgs a)
 {
-    chains_workgroup<DT, OP>(a, (const uint4 *)a.base.prog);
+    chains_workgroup<DT, OP, kChainLanes, kChainTeams>(a, (const uint4 *)a.base.prog);
 }
 // ... or inside the kernel arguments: nothing is staged ahead of the launch.
 template <int DT, int OP, int WORDS>
 __global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains_inline(const ChainArgsInline<WORDS> a)
 {
-    chains_workgroup<DT, OP>(a.base, (const uint4 *)&a.table[0]);
+    chains_workgroup<DT, OP, kChainLanes, kChainTeams>(a.base, (const uint4 *)&a.table[0]);
+}
+// The wide form of both.
+template <int DT, int OP>
+__global__ __launch_bounds__(kChainWideThreads) void reduce_kernel_chains_wide(const ChainArgs a)
+{
+    chains_workgroup<DT, OP, kChainWideLanes, kChainWideTeams>(a, (const uint4 *)a.base.prog);
+}
+template <int DT, int OP, int WORDS>
+__global__ __launch_bounds__(kChainWideThreads) void reduce_kernel_chains_wide_inline(const ChainArgsInline<WORDS> a)
+{
+    chains_workgroup<DT, OP, kChainWideLanes, kChainWideTeams>(a.base, (const uint4 *)&a.table[0]);
 }
 
 // The reduce that keeps and reuses partial results (failure repair, section 3.5.2: the partial

@@ -42,6 +42,7 @@ constexpr size_t kChainWantSteps = 48;              // shorter programs: one wav
 constexpr size_t kChainMaxBytes = 64u << 10;        // at most 1024 columns
 constexpr int kChainMinCut = 4;
 constexpr size_t kChainMaxWork = 3072;              // columns x rounds
+constexpr size_t kChainWideMaxBytes = 768u << 10;   // the wide form: ranges above kChainMaxBytes up to this
 
 class GpuBackend : public Backend {
 public:
@@ -378,19 +379,32 @@ private:
     // the same limits still came out best: 4000 of 64 KiB 72.8 as chains against 63.5, 4000 of 32 KiB 39.7
     // as chains against 44.5.)
 
+    //
+    // The wide form (a whole wave per chain, 1 KiB columns, 8 chains side by side) takes over above 64 KiB:
+    // every load instruction then covers 1 KiB of one object, as in the streaming kernels, and a range of
+    // 256 KiB is 256 workgroups instead of 4096. One launch where the cut into sub-programs needs two or
+    // three, and no partial results in memory. fp32 sums, 16-ary tree, cold inputs, us per call, wide form
+    // against the cut: 128 inputs of 128 KiB 8.4 / 12.8, of 256 KiB 8.4 / 14.1; 256 of 256 KiB 13.3 / 19.3;
+    // 1000 of 128 KiB 34.6 / 38.7, of 256 KiB 48.5 / 59.9; 512 of 512 KiB 52.5 / 59.5; 128 / 256 / 512 / 1000 of
+    // 768 KiB 25.8 / 42.1 / 76.9 / 139 against 29.5 / 46.4 / 84.1 / 156; at 1 MiB per object it loses against the
+    // plain path (128 inputs: 32.9 / 24.3) or draws (256, 1000 inputs). bf16: 128 of 128 KiB 9.6 / 15.1, 256 of
+    // 256 KiB 16.9 / 23.2, of 512 KiB 35.2 / 40.4. Programs with more values alive at one time than the LDS
+    // holds (63 of 1 KiB, bf16: 31 of 2 KiB; thousands of inputs) have no such form and are cut as before.
+
     bool wants_chains(size_t n_steps, size_t range_bytes) const
     {
-        return n_steps >= kChainWantSteps && range_bytes <= kChainMaxBytes;
+        return n_steps >= kChainWantSteps && range_bytes <= kChainWideMaxBytes;
     }
 
     int launch_chains(const std::vector<Entry> &prog, uint64_t version, size_t b0, size_t b1)
     {
-        if (version != chain_version_) {
-            // the plan is made once per program; the table only when a launch is short enough to use it
+        const bool wide = b1 - b0 > kChainMaxBytes;
+        if (version != chain_version_ || wide != skeleton_.wide) {
+            // the plan is made once per program and form; the table only when a launch is short enough to use it
             chain_version_ = version;
             chain_table_ = nullptr;
             chain_host_table_.clear();
-            chain_usable_ = build_skeleton(prog, skeleton_);
+            chain_usable_ = build_skeleton(prog, wide, skeleton_);
         }
         if (!chain_usable_) return HOP_PARTIAL;
         const int rc = launch_skeleton(skeleton_, b0, b1);
@@ -398,18 +412,20 @@ private:
         return rc;
     }
 
-    bool build_skeleton(const std::vector<Entry> &prog, ChainSkeleton &sk) const
+    bool build_skeleton(const std::vector<Entry> &prog, bool wide, ChainSkeleton &sk) const
     {
         ChainFormat f;
         f.min_cut = kChainMinCut;
         f.max_items = kChainMaxItems;
         f.record_words = kChainRecordWords;
-        f.teams = kChainTeams;
+        f.teams = wide ? kChainWideTeams : kChainTeams;
         f.max_passes = kMaxChainPasses;
-        f.value_bytes = chain_value_bytes(dtype_);
-        f.max_values = chain_slots_max(dtype_);
+        f.value_bytes = chain_value_bytes(dtype_, wide);
+        f.max_values = chain_slots_max(dtype_, wide);
         f.result_mark = kChainFinal;
-        return build_chain_skeleton(prog, f, sk);
+        const bool ok = build_chain_skeleton(prog, f, sk);
+        sk.wide = wide;
+        return ok;
     }
 
 public:
@@ -418,8 +434,12 @@ public:
     // or an address cannot be told from a value's offset.
     int launch_skeleton(const ChainSkeleton &sk, size_t b0, size_t b1)
     {
-        const size_t columns = (b1 - b0 + 16 * kChainLanes - 1) / (16 * kChainLanes);
-        if (b1 - b0 > kChainMaxBytes || columns * sk.rounds > kChainMaxWork) return HOP_PARTIAL;
+        if (sk.wide) {
+            if (b1 - b0 <= kChainMaxBytes || b1 - b0 > kChainWideMaxBytes) return HOP_PARTIAL;
+        } else {
+            const size_t columns = (b1 - b0 + 16 * kChainLanes - 1) / (16 * kChainLanes);
+            if (b1 - b0 > kChainMaxBytes || columns * sk.rounds > kChainMaxWork) return HOP_PARTIAL;
+        }
         if (!chain_table_ && chain_host_table_.empty()) {
             std::vector<uint64_t> table(sk.table);
             for (uint64_t &word : table) {
@@ -445,7 +465,7 @@ public:
             }
             const hipError_t e = launch_reduce_chains(stream_, dtype_, op_, chain_table_, sk.n_chains, sk.n_slots,
                                                       sk.pass_begin.data(), (int)sk.pass_begin.size() - 1, dsts_[0], b0, b1,
-                                                      inl ? chain_host_table_.data() : nullptr);
+                                                      inl ? chain_host_table_.data() : nullptr, sk.wide);
             if (e == hipSuccess) return HOP_OK;
             if (!inl || chain_table_inline(sk.n_chains)) return HOP_ERR_DEVICE;
             (void)hipGetLastError();                               // refused as arguments: once more, staged

@@ -75,6 +75,11 @@ constexpr int kChainLanes = 4;
 constexpr int kChainColumnRun = 4;       // columns in a row that one die's workgroups take
 constexpr int kChainTeams = 64;
 constexpr int kChainThreads = kChainLanes * kChainTeams;
+// The wide form of the same: a team is a whole wave (a column of 64 vectors = 1 KiB of the objects, a value
+// 1 KiB of LDS for 32-bit elements), 8 chains side by side. For ranges of hundreds of KiB.
+constexpr int kChainWideLanes = 64;
+constexpr int kChainWideTeams = 8;
+constexpr int kChainWideThreads = kChainWideLanes * kChainWideTeams;
 constexpr int kChainMaxItems = 23;
 constexpr int kChainRecordWords = kChainMaxItems + 1;
 constexpr int kMaxChainPasses = 24;
@@ -186,16 +191,17 @@ size_t split_partial_base_offset(int dtype, size_t byte_begin);
 // values of chain_value_bytes(dtype) bytes each) or, for tables that ride in the kernel arguments, host_table (the
 // same in host memory), n_slots = values alive at most at one time; the identity
 // value takes the place behind them. hipErrorInvalidValue if that is more LDS than a workgroup gets.
+// wide: the form with 1 KiB columns (the table written for its values and its kChainWideTeams teams).
 hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uint64_t *dev_table, int n_chains,
                                 int n_slots, const uint32_t *pass_begin, int n_passes, void *dst,
-                                size_t byte_begin, size_t byte_end, const uint64_t *host_table = nullptr);
+                                size_t byte_begin, size_t byte_end, const uint64_t *host_table = nullptr, bool wide = false);
 // Whether a table of n_chains records rides in the kernel arguments (then launch_reduce_chains needs
 // host_table only, else dev_table).
 bool chain_table_inline(int n_chains);
 // LDS bytes of one chain's value, and the number of values a launch_reduce_chains may keep alive at
 // one time, for this element type.
-size_t chain_value_bytes(int dtype);
-int chain_slots_max(int dtype);
+size_t chain_value_bytes(int dtype, bool wide = false);
+int chain_slots_max(int dtype, bool wide = false);
 
 // Copy [byte_begin, byte_end) of src into the same range of n_dst destinations: dst0 if n_dst == 1
 // and dst0 is given; else the table host_dsts (host memory) if it has at most kInlineDsts entries

@@ -54,7 +54,7 @@ const char *kernel_config()
            "tiles, 8 waves per CU from 5120 tiles, partials as 4-byte accumulators indexed like the elements, nontemporal; "
            "programs of 48 steps or more over at most 64 KiB: one launch, 256 lanes per 64-byte column, chains of at most 23 items "
            "folded by teams of 4 lanes with all their loads in flight, values in LDS, tables of up to 256 chains in the kernel arguments, "
-           "four columns in a row per die";
+           "four columns in a row per die; above 64 KiB up to 768 KiB: 512 lanes per 1 KiB column, a wave per chain";
 }
 
 static thread_local LaunchRecorder *tl_recorder = nullptr;
@@ -306,9 +306,12 @@ size_t split_partial_base_offset(int dtype, size_t byte_begin)
     return dtype != HOP_BF16 ? byte_begin : byte_begin / 1024 * 2048;
 }
 
-size_t chain_value_bytes(int dtype) { return (size_t)kChainLanes * (dtype == HOP_BF16 ? 8 : 4) * 4; }
+size_t chain_value_bytes(int dtype, bool wide)
+{
+    return (size_t)(wide ? kChainWideLanes : kChainLanes) * (dtype == HOP_BF16 ? 8 : 4) * 4;
+}
 
-int chain_slots_max(int dtype) { return (int)(kChainLdsBytes / chain_value_bytes(dtype)) - 1; }     // one place is the identity's
+int chain_slots_max(int dtype, bool wide) { return (int)(kChainLdsBytes / chain_value_bytes(dtype, wide)) - 1; }     // one place is the identity's
 
 // Tables ride in the kernel arguments until a launch with such an argument block is refused.
 static std::atomic<bool> g_inline_tables{true};
@@ -321,21 +324,21 @@ bool chain_table_inline(int n_chains)
 
 template <int WORDS>
 static hipError_t launch_chains_inline(void (*kernel)(ChainArgsInline<WORDS>), unsigned grid, unsigned lds, hipStream_t stream,
-                                       const ChainArgs &base, const uint64_t *host_table, size_t n_words)
+                                       const ChainArgs &base, const uint64_t *host_table, size_t n_words, int threads)
 {
     static thread_local ChainArgsInline<WORDS> a;          // tens of KiB: not on the stack of every caller
     a.base = base;
     std::memcpy(a.table, host_table, n_words * sizeof(uint64_t));
-    return enqueue(kernel, dim3(grid), lds, stream, a, true, kChainThreads);
+    return enqueue(kernel, dim3(grid), lds, stream, a, true, threads);
 }
 
 hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uint64_t *dev_table, int n_chains,
                                 int n_slots, const uint32_t *pass_begin, int n_passes, void *dst,
-                                size_t byte_begin, size_t byte_end, const uint64_t *host_table)
+                                size_t byte_begin, size_t byte_end, const uint64_t *host_table, bool wide)
 {
     if (byte_end <= byte_begin) return hipSuccess;
     if ((!dev_table && !host_table) || !pass_begin || n_chains < 1 || n_passes < 1 || n_passes > kMaxChainPasses || n_slots < 0 ||
-        n_slots > chain_slots_max(dtype) || pass_begin[0] != 0 || pass_begin[n_passes] != (uint32_t)n_chains)
+        n_slots > chain_slots_max(dtype, wide) || pass_begin[0] != 0 || pass_begin[n_passes] != (uint32_t)n_chains)
         return hipErrorInvalidValue;
     const Launcher l = pick(dtype, op, 1);
     ChainArgs a;
@@ -344,24 +347,26 @@ hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uin
     a.base.dst = dst;
     a.base.sub_entries = 0;
     fill_range(a.base, dtype, byte_begin, byte_end);
-    a.identity_at = (uint32_t)((size_t)n_slots * chain_value_bytes(dtype));
+    a.identity_at = (uint32_t)((size_t)n_slots * chain_value_bytes(dtype, wide));
     for (int p = 0; p <= kMaxChainPasses; ++p) a.pass_begin[p] = pass_begin[p < n_passes ? p : n_passes];
-    const size_t n_cols = (a.base.n_vec + kChainLanes - 1) / kChainLanes;
-    const size_t grid = n_cols + ((size_t)a.base.n_tail + kChainLanes - 1) / kChainLanes;
+    const size_t lanes = wide ? kChainWideLanes : kChainLanes;
+    const int threads = wide ? kChainWideThreads : kChainThreads;
+    const size_t n_cols = (a.base.n_vec + lanes - 1) / lanes;
+    const size_t grid = n_cols + ((size_t)a.base.n_tail + lanes - 1) / lanes;
     if (grid > kMaxGrid) return hipErrorInvalidValue;       // one column per workgroup: the kernel does not loop
-    const unsigned lds = (unsigned)(((size_t)n_slots + 1) * chain_value_bytes(dtype));
+    const unsigned lds = (unsigned)(((size_t)n_slots + 1) * chain_value_bytes(dtype, wide));
     if (host_table && chain_table_inline(n_chains)) {
         const size_t n_words = (size_t)n_chains * kChainRecordWords;
-        const hipError_t e = n_words <= (size_t)kChainInlineWordsSmall
-                                 ? launch_chains_inline(l.chains_inl_small, (unsigned)grid, lds, stream, a, host_table, n_words)
-                             : n_words <= (size_t)kChainInlineWordsMid
-                                 ? launch_chains_inline(l.chains_inl_mid, (unsigned)grid, lds, stream, a, host_table, n_words)
-                                 : launch_chains_inline(l.chains_inl_large, (unsigned)grid, lds, stream, a, host_table, n_words);
+        const int size = n_words <= (size_t)kChainInlineWordsSmall ? 0 : n_words <= (size_t)kChainInlineWordsMid ? 1 : 2;
+        const hipError_t e =
+            size == 0 ? launch_chains_inline(wide ? l.chains_wide_inl_small : l.chains_inl_small, (unsigned)grid, lds, stream, a, host_table, n_words, threads)
+            : size == 1 ? launch_chains_inline(wide ? l.chains_wide_inl_mid : l.chains_inl_mid, (unsigned)grid, lds, stream, a, host_table, n_words, threads)
+                        : launch_chains_inline(wide ? l.chains_wide_inl_large : l.chains_inl_large, (unsigned)grid, lds, stream, a, host_table, n_words, threads);
         if (e == hipSuccess) return e;
         g_inline_tables.store(false, std::memory_order_relaxed);      // this runtime refuses the argument block
     }
     if (!dev_table) return hipErrorInvalidValue;            // the caller stages the table and calls again
-    return enqueue(l.chains, dim3((unsigned)grid), lds, stream, a, true, kChainThreads);
+    return enqueue(wide ? l.chains_wide : l.chains, dim3((unsigned)grid), lds, stream, a, true, threads);
 }
 
 // One destination: every vector is read once (non-temporal) and stored once; 8 contiguous

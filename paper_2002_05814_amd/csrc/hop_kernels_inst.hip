@@ -37,7 +37,10 @@ template <int DT, int OP, int D> static Launcher make_launcher()
             reduce_kernel_seg<DT, OP, D, V, kUnroll, kThreads>, reduce_kernel_kept<DT, OP, D, V, kThreads>,
             reduce_kernel_kept_inline<DT, OP, D, V, kThreads>, reduce_kernel_chains<DT, OP>,
             reduce_kernel_chains_inline<DT, OP, kChainInlineWordsSmall>, reduce_kernel_chains_inline<DT, OP, kChainInlineWordsMid>,
-            reduce_kernel_chains_inline<DT, OP, kChainInlineWordsLarge>, V};
+            reduce_kernel_chains_inline<DT, OP, kChainInlineWordsLarge>, reduce_kernel_chains_wide<DT, OP>,
+            reduce_kernel_chains_wide_inline<DT, OP, kChainInlineWordsSmall>,
+            reduce_kernel_chains_wide_inline<DT, OP, kChainInlineWordsMid>,
+            reduce_kernel_chains_wide_inline<DT, OP, kChainInlineWordsLarge>, V};
 }
 
 #define HOP_CAT3(a, b, c) a##b##_##c

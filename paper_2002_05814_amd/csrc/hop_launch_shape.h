@@ -84,6 +84,10 @@ struct Launcher {
     void (*chains_inl_small)(ChainArgsInline<kChainInlineWordsSmall>);
     void (*chains_inl_mid)(ChainArgsInline<kChainInlineWordsMid>);
     void (*chains_inl_large)(ChainArgsInline<kChainInlineWordsLarge>);
+    void (*chains_wide)(ChainArgs);
+    void (*chains_wide_inl_small)(ChainArgsInline<kChainInlineWordsSmall>);
+    void (*chains_wide_inl_mid)(ChainArgsInline<kChainInlineWordsMid>);
+    void (*chains_wide_inl_large)(ChainArgsInline<kChainInlineWordsLarge>);
     int vpt;
 };
 

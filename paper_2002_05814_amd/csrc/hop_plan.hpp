@@ -373,6 +373,7 @@ struct ChainSkeleton {
     int n_slots = 0, n_chains = 0;               // places for values (the identity takes place n_slots), records
     size_t rounds = 0;                           // chains a team folds one after the other, summed over the passes
     size_t n_steps = 0;                          // of the program it stands for
+    bool wide = false;                           // written for the kernels' wide form (whole waves as teams, 1 KiB columns)
 };
 struct ChainFormat {
     int min_cut = 4, max_items = 23, record_words = 24, teams = 64, max_passes = 24, max_values = 1023;

@@ -175,14 +175,26 @@ def test_many_small_objects_take_the_multi_pass_path(dtype):
     run_both(w, "sum", fm=fm)
 
 
-def takes_the_one_launch_path(w, order=None, fm=None):
+def takes_the_one_launch_path(w, order=None, fm=None, wide=False):
     """Whether the library evaluates this call's final program as chains in one launch: at least 48 steps
     over at most 64 KiB, the longest path through the chains at most half the program, at most 3072
     workgroup rounds (64-byte columns x rounds of 64 chains), and the values that are alive at one time fit
-    the LDS beside the identity value."""
+    the LDS beside the identity value. wide: the same question for the form with 1 KiB columns, which takes
+    ranges above 64 KiB up to 768 KiB and whose values are sixteen times as large."""
     _, _, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
                                                   w.ready_order() if order is None else order, fm)
     final = entries[launches[-1][2]:launches[-1][3]]
+    if wide:
+        if len(final) < 48 or not (64 << 10) < w.object_bytes <= (768 << 10):
+            return False
+        src, chains = hop.hop_plan_chains(final, 4)
+        if src != hop.HOP_OK:
+            return False
+        n_pass = 1 + max(p for p, _ in chains)
+        critical = sum(max(len(items) for p, items in chains if p == q) for q in range(n_pass))
+        read_in = {-it - 1: p for p, items in chains for it in items if it < 0}
+        alive = max(sum(1 for g, (p, _) in enumerate(chains) if g in read_in and p <= q <= read_in[g]) for q in range(n_pass))
+        return n_pass <= 24 and 2 * critical <= len(final) and alive <= (32 if w.dtype == "bf16" else 64) - 1
     if len(final) < 48 or w.object_bytes > (64 << 10):          # a call without failures is one launch over the object
         return False
     src, chains = hop.hop_plan_chains(final, 4)
@@ -245,6 +257,48 @@ def test_long_programs_over_small_objects_in_one_launch(dtype, n, k, d, nbytes, 
     rc, info = hop.hop_allreduce(dsts, objs, w.k, "sum", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
     torch.cuda.synchronize()
     orc, outs, _, _ = oracle.allreduce([workloads.to_numpy(o) for o in objs], 3, w.k, oracle.SUM, ORA_DT[dtype],
+                                       max(1, w.chunk_bytes // ES[dtype]), d, w.ready_order(), None)
+    assert rc == orc == hop.HOP_OK
+    for got, want in zip(dsts, outs):
+        assert np.array_equal(bits(workloads.to_numpy(got)), bits(want))
+
+
+WIDE_CHAIN_CASES = [
+    # dtype, n, k, d, object bytes, chunk bytes, takes the wide form
+    ("f32", 200, 190, 16, 256 * 1024 + 12, 1 << 20, True),        # 257 columns of 1 KiB less most of the last, and three elements
+    ("i32", 1000, 990, 16, 100 * 1024, 1 << 20, True),
+    ("f32", 300, 280, 2, 72000 * 3 - 40, 72000, False),           # a binary tree: too long a path through the chains
+    ("f32", 300, 280, 8, 72000 * 3 - 40, 72000, True),            # with failures: chunk runs of 72000 bytes that start anywhere
+    ("bf16", 128, 128, 8, 200 * 1024 + 2, 1 << 20, True),         # values of 2 KiB: 31 at a time
+    ("bf16", 1000, 1000, 16, 128 * 1024, 1 << 20, False),         # more values alive than bf16 has room for: cut into sub-programs
+    ("f32", 60, 60, 4, 300 * 1024, 1 << 20, True),                # a short program
+    ("i32", 100, 100, 4, 768 * 1024, 1 << 20, True),              # the longest range
+    ("f32", 4000, 4000, 16, 80 * 1024, 1 << 20, False),           # more values alive than fit: cut into sub-programs
+]
+
+
+@pytest.mark.parametrize("dtype,n,k,d,nbytes,chunk,wide", WIDE_CHAIN_CASES)
+def test_long_programs_over_medium_objects_in_one_launch_of_wide_columns(dtype, n, k, d, nbytes, chunk, wide):
+    base = workloads.WORKLOADS[{"f32": 5, "bf16": 4, "i32": 3}[dtype]]
+    dist = {"f32": "uniform_pm1", "bf16": "normal_std1", "i32": "randint_pm2p20"}[dtype]
+    w = base.scaled(nbytes, chunk, n=n, k=k, tree_degree=d, order_seed=n + d + 1, data_seed=k + nbytes + 1, fail={},
+                    name="wide_%s_%d" % (dtype, n), dist=dist, n_dst=0)
+    assert takes_the_one_launch_path(w, wide=True) == wide
+    objs = workloads.make_objects(w, device=dev())
+    for op in ("sum", "min", "max"):
+        rc, info = run_both(w, op, objs=objs)
+        assert rc == hop.HOP_OK and info["n_launches"] == 1
+    # failures before and in the middle of the stream: launches over runs of chunks, holes, replacements, repairs
+    rng = np.random.default_rng(n * 5 + d)
+    fm = np.full(n, -1, np.int64)
+    bad = rng.random(n) < 0.05
+    fm[bad] = rng.integers(0, w.n_chunks + 1, size=int(bad.sum()))
+    run_both(w, "sum", objs=objs, fm=fm)
+    # all-reduce: the copy to the other destinations follows the one launch
+    dsts = [torch.full_like(objs[0], 3) for _ in range(2)]
+    rc, info = hop.hop_allreduce(dsts, objs, w.k, "max", w.dtype, w.chunk_bytes, w.tree_degree, w.ready_order(), None)
+    torch.cuda.synchronize()
+    orc, outs, _, _ = oracle.allreduce([workloads.to_numpy(o) for o in objs], 2, w.k, oracle.MAX, ORA_DT[dtype],
                                        max(1, w.chunk_bytes // ES[dtype]), d, w.ready_order(), None)
     assert rc == orc == hop.HOP_OK
     for got, want in zip(dsts, outs):
@@ -1296,14 +1350,16 @@ def test_session_with_a_workspace_of_the_callers():
                                            wm.chunk_bytes // 4, wm.tree_degree, morder, mfm)
     assert rc == morc and info["k_eff"] == mk_eff
     assert np.array_equal(bits(workloads.to_numpy(mdst)), bits(mwant))
-    # hundreds of bf16 objects of 100 KiB: the program is cut into sub-programs whose partial results (4-byte
-    # accumulators in whole blocks) and records come out of the workspace, which the library sized itself
-    wb = workloads.WORKLOADS[4].scaled(100 * 1024 + 6, 16 * 2100, n=260, k=250, tree_degree=16, order_seed=35, data_seed=36,
+    # a thousand bf16 objects of 100 KiB (more values alive at a time than the one-launch form has room for): the
+    # program is cut into sub-programs whose partial results (4-byte accumulators in whole blocks) and records
+    # come out of the workspace, which the library sized itself
+    wb = workloads.WORKLOADS[4].scaled(100 * 1024 + 6, 16 * 2100, n=1000, k=990, tree_degree=16, order_seed=35, data_seed=36,
                                        fail={}, name="own_workspace_cut", n_dst=0)
+    assert not takes_the_one_launch_path(wb, wide=True)
     bobjs = workloads.make_objects(wb, device=d)
     border = wb.ready_order()
     need_cut = hop.hop_workspace_bytes(wb.n, wb.k, wb.object_bytes, wb.chunk_bytes, wb.tree_degree, wb.dtype)
-    assert need_cut >= 15 * 2 * 16 * 2100                 # 15 subtrees below the root, twice the bytes of a chunk each
+    assert need_cut >= 50 * 2 * 16 * 2100                 # dozens of subtrees, twice the bytes of a chunk each
     ws = torch.zeros(need_cut, dtype=torch.uint8, device=d)
     bdst = torch.zeros_like(bobjs[0])
     rc, info = session_replay(bobjs, bdst, wb.k, "sum", wb.dtype, wb.chunk_bytes, wb.tree_degree, border, None, wb.n_chunks,
@@ -1315,7 +1371,7 @@ def test_session_with_a_workspace_of_the_callers():
     assert np.array_equal(bits(workloads.to_numpy(bdst)), bits(bwant))
     # the cut was made (a workspace too small for it would have sent the call down the plain path, which leaves
     # only the staged program behind): the partial results are still there
-    assert int((ws != 0).sum()) > 15 * wb.object_bytes
+    assert int((ws != 0).sum()) > 50 * wb.object_bytes
     # a workspace that cannot hold the saved accumulators: the event that needs them says so
     small = torch.empty(1 << 20, dtype=torch.uint8, device=d)
     dst = torch.zeros_like(objs[0])
