@@ -43,6 +43,8 @@ constexpr size_t kChainMaxBytes = 64u << 10;        // at most 1024 columns
 constexpr int kChainMinCut = 4;
 constexpr size_t kChainMaxWork = 3072;              // columns x rounds
 constexpr size_t kChainWideMaxBytes = 768u << 10;   // the wide form: ranges above kChainMaxBytes up to this
+constexpr size_t kChainWideEarlyBytes = 32u << 10;  // bf16 (two narrow workgroups per compute unit, not three): the wide form
+constexpr size_t kChainWideEarlySteps = 384;        // already from here on for programs up to this length
 
 class GpuBackend : public Backend {
 public:
@@ -396,9 +398,17 @@ private:
         return n_steps >= kChainWantSteps && range_bytes <= kChainWideMaxBytes;
     }
 
+    // bf16 from 32 KiB for programs of up to 384 steps: 128 / 256 inputs of 64 KiB 8.8 / 12.1 us wide against
+    // 14.9 / 15.5 narrow (1000 inputs: 42.1 against 26.6; at 32 KiB the narrow form wins or draws for every count)
+    bool takes_wide_form(size_t n_steps, size_t range_bytes) const
+    {
+        return range_bytes > kChainMaxBytes ||
+               (dtype_ == HOP_BF16 && range_bytes > kChainWideEarlyBytes && n_steps <= kChainWideEarlySteps);
+    }
+
     int launch_chains(const std::vector<Entry> &prog, uint64_t version, size_t b0, size_t b1)
     {
-        const bool wide = b1 - b0 > kChainMaxBytes;
+        const bool wide = takes_wide_form(prog.size(), b1 - b0);
         if (version != chain_version_ || wide != skeleton_.wide) {
             // the plan is made once per program and form; the table only when a launch is short enough to use it
             chain_version_ = version;
@@ -435,7 +445,7 @@ public:
     int launch_skeleton(const ChainSkeleton &sk, size_t b0, size_t b1)
     {
         if (sk.wide) {
-            if (b1 - b0 <= kChainMaxBytes || b1 - b0 > kChainWideMaxBytes) return HOP_PARTIAL;
+            if (!takes_wide_form(sk.n_steps, b1 - b0) || b1 - b0 > kChainWideMaxBytes) return HOP_PARTIAL;
         } else {
             const size_t columns = (b1 - b0 + 16 * kChainLanes - 1) / (16 * kChainLanes);
             if (b1 - b0 > kChainMaxBytes || columns * sk.rounds > kChainMaxWork) return HOP_PARTIAL;

@@ -184,8 +184,9 @@ def takes_the_one_launch_path(w, order=None, fm=None, wide=False):
     _, _, launches, entries = hop.hop_plan_reduce(w.n, w.object_bytes, w.k, w.dtype, w.chunk_bytes, w.tree_degree,
                                                   w.ready_order() if order is None else order, fm)
     final = entries[launches[-1][2]:launches[-1][3]]
+    early = w.dtype == "bf16" and w.object_bytes > (32 << 10) and len(final) <= 384      # bf16: wide from 32 KiB for short programs
     if wide:
-        if len(final) < 48 or not (64 << 10) < w.object_bytes <= (768 << 10):
+        if len(final) < 48 or not ((64 << 10) < w.object_bytes <= (768 << 10) or (early and w.object_bytes <= (64 << 10))):
             return False
         src, chains = hop.hop_plan_chains(final, 4)
         if src != hop.HOP_OK:
@@ -195,7 +196,7 @@ def takes_the_one_launch_path(w, order=None, fm=None, wide=False):
         read_in = {-it - 1: p for p, items in chains for it in items if it < 0}
         alive = max(sum(1 for g, (p, _) in enumerate(chains) if g in read_in and p <= q <= read_in[g]) for q in range(n_pass))
         return n_pass <= 24 and 2 * critical <= len(final) and alive <= (32 if w.dtype == "bf16" else 64) - 1
-    if len(final) < 48 or w.object_bytes > (64 << 10):          # a call without failures is one launch over the object
+    if len(final) < 48 or w.object_bytes > (64 << 10) or early:   # a call without failures is one launch over the object
         return False
     src, chains = hop.hop_plan_chains(final, 4)
     if src != hop.HOP_OK:
@@ -272,6 +273,7 @@ WIDE_CHAIN_CASES = [
     ("bf16", 128, 128, 8, 200 * 1024 + 2, 1 << 20, True),         # values of 2 KiB: 31 at a time
     ("bf16", 1000, 1000, 16, 128 * 1024, 1 << 20, False),         # more values alive than bf16 has room for: cut into sub-programs
     ("f32", 60, 60, 4, 300 * 1024, 1 << 20, True),                # a short program
+    ("bf16", 200, 200, 16, 48 * 1024 + 6, 1 << 20, True),         # bf16 takes the wide form from 32 KiB for short programs
     ("i32", 100, 100, 4, 768 * 1024, 1 << 20, True),              # the longest range
     ("f32", 4000, 4000, 16, 80 * 1024, 1 << 20, False),           # more values alive than fit: cut into sub-programs
 ]
