@@ -1563,6 +1563,15 @@ def test_a_known_shape_over_other_buffers_fills_in_the_addresses_only():
     assert hop.hop_shutdown() == hop.HOP_OK
     assert check(sets[2], order, w.k, w.tree_degree) == first
     assert check(sets[1], order, w.k, w.tree_degree) == first
+    # the same with objects of 96 KiB, whose shape is remembered in the wide one-launch form
+    w = workloads.WORKLOADS[5].scaled(96 * 1024, 96 * 1024, n=150, k=140, tree_degree=8, order_seed=7, data_seed=8, fail={},
+                                      name="known_wide", n_dst=0)
+    assert takes_the_one_launch_path(w, wide=True)
+    order = w.ready_order()
+    sets = [fresh_set(w.n) for _ in range(3)]
+    first = check(sets[0], order, w.k, w.tree_degree)
+    for objs in sets[1:] + sets[:2]:
+        assert check(objs, order, w.k, w.tree_degree) == first
 
 
 def test_two_host_threads_on_their_own_streams_and_shutdown():
