@@ -599,8 +599,8 @@ template <int DT, int OP> __device__ __forceinline__ typename Traits<DT>::acc_t 
 // side: ranges up to 64 KiB); the wide form is teams of kChainWideLanes = a whole wave each (1 KiB columns,
 // kChainWideTeams chains side by side: every load instruction covers 1 KiB of one object, for ranges of
 // hundreds of KiB, where the narrow form would need thousands of workgroups).
-template <int DT, int OP, bool TAIL, int LANES, int TEAMS>
-__device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *const table, typename Traits<DT>::acc_t *lds,
+template <int DT, int OP, bool TAIL, int LANES, int TEAMS, class Table>
+__device__ __forceinline__ void chains_body(const ChainArgs &a, const Table table, typename Traits<DT>::acc_t *lds,
                                             const size_t off, const bool live)
 {
     using T = Traits<DT>;
@@ -621,21 +621,38 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *con
     __syncthreads();
     for (int p = 0; p < a.base.n_entries; ++p) {
         for (uint32_t c = a.pass_begin[p] + (uint32_t)team; c < a.pass_begin[p + 1]; c += TEAMS) {
-            const uint4 *const rec = table + (size_t)c * (kChainRecordWords / 2);
             uint64_t word[kChainRecordWords];
+            if constexpr (LANES == 64) {
+                // a wave per chain: the record is the same for all its lanes and is fetched by scalar loads (the
+                // table is in the kernel arguments or comes as a pointer into the constant address space: see
+                // the kernels), so its 24 words sit in scalar registers
+                const size_t at = (size_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)c) * (kChainRecordWords / 2);
 #pragma unroll
-            for (int j = 0; j < kChainRecordWords / 2; ++j) {
-                const uint4 q = rec[j];
-                word[2 * j] = ((uint64_t)q.y << 32) | q.x;
-                word[2 * j + 1] = ((uint64_t)q.w << 32) | q.z;
+                for (int j = 0; j < kChainRecordWords / 2; ++j) {
+                    const u32x4 q = table[at + j];
+                    word[2 * j] = ((uint64_t)q.y << 32) | q.x;
+                    word[2 * j + 1] = ((uint64_t)q.w << 32) | q.z;
+                }
+#pragma unroll
+                for (int j = 0; j < kChainRecordWords; j += 8)
+                    asm volatile("" : "+s"(word[j]), "+s"(word[j + 1]), "+s"(word[j + 2]), "+s"(word[j + 3]), "+s"(word[j + 4]),
+                                 "+s"(word[j + 5]), "+s"(word[j + 6]), "+s"(word[j + 7]) : : "memory");
+            } else {
+                const auto rec = table + (size_t)c * (kChainRecordWords / 2);
+#pragma unroll
+                for (int j = 0; j < kChainRecordWords / 2; ++j) {
+                    const auto q = rec[j];
+                    word[2 * j] = ((uint64_t)q.y << 32) | q.x;
+                    word[2 * j + 1] = ((uint64_t)q.w << 32) | q.z;
+                }
+                // The whole record has arrived before the first item is fetched: an empty statement that formally
+                // rewrites every word. (Flat loads complete out of order with other loads, so with the record
+                // still on its way the compiler would wait for everything in flight before each use of a word.)
+#pragma unroll
+                for (int j = 0; j < kChainRecordWords; j += 8)
+                    asm volatile("" : "+v"(word[j]), "+v"(word[j + 1]), "+v"(word[j + 2]), "+v"(word[j + 3]), "+v"(word[j + 4]),
+                                 "+v"(word[j + 5]), "+v"(word[j + 6]), "+v"(word[j + 7]) : : "memory");
             }
-            // The whole record has arrived before the first item is fetched: an empty statement that formally
-            // rewrites every word. (Flat loads complete out of order with other loads, so with the record
-            // still on its way the compiler would wait for everything in flight before each use of a word.)
-#pragma unroll
-            for (int j = 0; j < kChainRecordWords; j += 8)
-                asm volatile("" : "+v"(word[j]), "+v"(word[j + 1]), "+v"(word[j + 2]), "+v"(word[j + 3]), "+v"(word[j + 4]),
-                             "+v"(word[j + 5]), "+v"(word[j + 6]), "+v"(word[j + 7]) : : "memory");
             const uint32_t out = (uint32_t)word[0];
             A acc[W];
             if (kAlike) {
@@ -734,8 +751,8 @@ __device__ __forceinline__ void chains_body(const ChainArgs &a, const uint4 *con
 }
 
 // The column (or, behind the last column, the elements after the last full vector) that this workgroup owns.
-template <int DT, int OP, int LANES, int TEAMS>
-__device__ __forceinline__ void chains_workgroup(const ChainArgs &a, const uint4 *const table)
+template <int DT, int OP, int LANES, int TEAMS, class Table>
+__device__ __forceinline__ void chains_workgroup(const ChainArgs &a, const Table table)
 {
     using T = Traits<DT>;
     extern __shared__ __align__(16) unsigned char chain_values[];
@@ -775,16 +792,19 @@ __global__ __launch_bounds__(kChainThreads) void reduce_kernel_chains_inline(con
 {
     chains_workgroup<DT, OP, kChainLanes, kChainTeams>(a.base, (const uint4 *)&a.table[0]);
 }
-// The wide form of both.
+// The wide form of both. Its records are read with a wave-uniform index: from the kernel arguments that is a
+// scalar load as it stands; a table in device memory is read through the constant address space for the
+// same effect (like the programs of the streaming kernels: nothing writes it while the kernel runs).
 template <int DT, int OP>
 __global__ __launch_bounds__(kChainWideThreads) void reduce_kernel_chains_wide(const ChainArgs a)
 {
-    chains_workgroup<DT, OP, kChainWideLanes, kChainWideTeams>(a, (const uint4 *)a.base.prog);
+    typedef const u32x4 __attribute__((address_space(4))) *uniform_table_ptr;
+    chains_workgroup<DT, OP, kChainWideLanes, kChainWideTeams>(a, (uniform_table_ptr)(uintptr_t)a.base.prog);
 }
 template <int DT, int OP, int WORDS>
 __global__ __launch_bounds__(kChainWideThreads) void reduce_kernel_chains_wide_inline(const ChainArgsInline<WORDS> a)
 {
-    chains_workgroup<DT, OP, kChainWideLanes, kChainWideTeams>(a.base, (const uint4 *)&a.table[0]);
+    chains_workgroup<DT, OP, kChainWideLanes, kChainWideTeams>(a.base, (const u32x4 *)&a.table[0]);
 }
 
 // The reduce that keeps and reuses partial results (failure repair, section 3.5.2: the partial
