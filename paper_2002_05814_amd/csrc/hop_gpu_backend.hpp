@@ -391,7 +391,8 @@ private:
     // 768 KiB 25.8 / 42.1 / 76.9 / 139 against 29.5 / 46.4 / 84.1 / 156; at 1 MiB per object it loses against the
     // plain path (128 inputs: 32.9 / 24.3) or draws (256, 1000 inputs). bf16: 128 of 128 KiB 9.6 / 15.1, 256 of
     // 256 KiB 16.9 / 23.2, of 512 KiB 35.2 / 40.4. Programs with more values alive at one time than the LDS
-    // holds (63 of 1 KiB, bf16: 31 of 2 KiB; thousands of inputs) have no such form and are cut as before.
+    // holds (128 KiB: 127 of 1 KiB, bf16: 63 of 2 KiB; thousands of inputs) have no such form and are cut as before
+    // (with 128 KiB instead of 64: fp32 2000 of 256 KiB 93 against 108, bf16 1000 of 256 KiB 54.2 against 79.5).
 
     bool wants_chains(size_t n_steps, size_t range_bytes) const
     {
@@ -477,6 +478,12 @@ public:
                                                       sk.pass_begin.data(), (int)sk.pass_begin.size() - 1, dsts_[0], b0, b1,
                                                       inl ? chain_host_table_.data() : nullptr, sk.wide);
             if (e == hipSuccess) return HOP_OK;
+            if (sk.wide && ((size_t)sk.n_slots + 1) * chain_value_bytes(dtype_, true) > kChainLdsBytes) {
+                // a workgroup was refused that much LDS (the launcher asks for less from now on): another path
+                (void)hipGetLastError();
+                chain_usable_ = false;
+                return HOP_PARTIAL;
+            }
             if (!inl || chain_table_inline(sk.n_chains)) return HOP_ERR_DEVICE;
             (void)hipGetLastError();                               // refused as arguments: once more, staged
         }

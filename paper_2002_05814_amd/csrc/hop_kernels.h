@@ -85,6 +85,7 @@ constexpr int kChainRecordWords = kChainMaxItems + 1;
 constexpr int kMaxChainPasses = 24;
 constexpr uint32_t kChainFinal = 0xffffffffu;
 constexpr size_t kChainLdsBytes = 64 * 1024;
+constexpr size_t kChainWideLdsBytes = 128 * 1024;  // the wide form, where the device gives a workgroup that much
 struct ChainArgs {
     ReduceArgs base;           // prog = the table, n_entries = number of passes, dst / byte_begin / n_vec / n_tail as usual
     uint32_t identity_at;      // LDS byte offset of the identity value (behind the chains' values)

@@ -311,7 +311,29 @@ size_t chain_value_bytes(int dtype, bool wide)
     return (size_t)(wide ? kChainWideLanes : kChainLanes) * (dtype == HOP_BF16 ? 8 : 4) * 4;
 }
 
-int chain_slots_max(int dtype, bool wide) { return (int)(kChainLdsBytes / chain_value_bytes(dtype, wide)) - 1; }     // one place is the identity's
+// LDS that one workgroup of the wide form may take: kChainWideLdsBytes where the device gives a workgroup
+// that much (asked once; a launch that is refused all the same takes it back), else what the narrow form has.
+static std::atomic<size_t> g_wide_lds{0};
+static size_t wide_lds_bytes()
+{
+    size_t v = g_wide_lds.load(std::memory_order_relaxed);
+    if (v) return v;
+    int dev = 0, per_block = 0;
+    v = kChainLdsBytes;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
+        (size_t)per_block >= kChainWideLdsBytes)
+        v = kChainWideLdsBytes;
+    else
+        (void)hipGetLastError();
+    g_wide_lds.store(v, std::memory_order_relaxed);
+    return v;
+}
+
+int chain_slots_max(int dtype, bool wide)
+{
+    return (int)((wide ? wide_lds_bytes() : kChainLdsBytes) / chain_value_bytes(dtype, wide)) - 1;     // one place is the identity's
+}
 
 // Tables ride in the kernel arguments until a launch with such an argument block is refused.
 static std::atomic<bool> g_inline_tables{true};
@@ -363,10 +385,17 @@ hipError_t launch_reduce_chains(hipStream_t stream, int dtype, int op, const uin
             : size == 1 ? launch_chains_inline(wide ? l.chains_wide_inl_mid : l.chains_inl_mid, (unsigned)grid, lds, stream, a, host_table, n_words, threads)
                         : launch_chains_inline(wide ? l.chains_wide_inl_large : l.chains_inl_large, (unsigned)grid, lds, stream, a, host_table, n_words, threads);
         if (e == hipSuccess) return e;
+        if (lds > kChainLdsBytes) {
+            // more LDS than the narrow form ever asks for: that, not the argument block, may be what was refused
+            g_wide_lds.store(kChainLdsBytes, std::memory_order_relaxed);
+            return e;
+        }
         g_inline_tables.store(false, std::memory_order_relaxed);      // this runtime refuses the argument block
     }
     if (!dev_table) return hipErrorInvalidValue;            // the caller stages the table and calls again
-    return enqueue(wide ? l.chains_wide : l.chains, dim3((unsigned)grid), lds, stream, a, true, threads);
+    const hipError_t e = enqueue(wide ? l.chains_wide : l.chains, dim3((unsigned)grid), lds, stream, a, true, threads);
+    if (e != hipSuccess && lds > kChainLdsBytes) g_wide_lds.store(kChainLdsBytes, std::memory_order_relaxed);
+    return e;
 }
 
 // One destination: every vector is read once (non-temporal) and stored once; 8 contiguous

@@ -195,7 +195,7 @@ def takes_the_one_launch_path(w, order=None, fm=None, wide=False):
         critical = sum(max(len(items) for p, items in chains if p == q) for q in range(n_pass))
         read_in = {-it - 1: p for p, items in chains for it in items if it < 0}
         alive = max(sum(1 for g, (p, _) in enumerate(chains) if g in read_in and p <= q <= read_in[g]) for q in range(n_pass))
-        return n_pass <= 24 and 2 * critical <= len(final) and alive <= (32 if w.dtype == "bf16" else 64) - 1
+        return n_pass <= 24 and 2 * critical <= len(final) and alive <= (64 if w.dtype == "bf16" else 128) - 1     # 128 KiB of LDS
     if len(final) < 48 or w.object_bytes > (64 << 10) or early:   # a call without failures is one launch over the object
         return False
     src, chains = hop.hop_plan_chains(final, 4)
@@ -268,10 +268,11 @@ WIDE_CHAIN_CASES = [
     # dtype, n, k, d, object bytes, chunk bytes, takes the wide form
     ("f32", 200, 190, 16, 256 * 1024 + 12, 1 << 20, True),        # 257 columns of 1 KiB less most of the last, and three elements
     ("i32", 1000, 990, 16, 100 * 1024, 1 << 20, True),
-    ("f32", 300, 280, 2, 72000 * 3 - 40, 72000, False),           # a binary tree: too long a path through the chains
+    ("f32", 300, 280, 2, 72000 * 3 - 40, 72000, True),            # a binary tree: 70 values alive at a time, more than 64 KiB of LDS
     ("f32", 300, 280, 8, 72000 * 3 - 40, 72000, True),            # with failures: chunk runs of 72000 bytes that start anywhere
     ("bf16", 128, 128, 8, 200 * 1024 + 2, 1 << 20, True),         # values of 2 KiB: 31 at a time
-    ("bf16", 1000, 1000, 16, 128 * 1024, 1 << 20, False),         # more values alive than bf16 has room for: cut into sub-programs
+    ("bf16", 1000, 1000, 16, 128 * 1024, 1 << 20, True),          # 59 values of 2 KiB alive at a time
+    ("bf16", 2000, 2000, 16, 96 * 1024, 1 << 20, False),          # more values alive than bf16 has room for: cut into sub-programs
     ("f32", 60, 60, 4, 300 * 1024, 1 << 20, True),                # a short program
     ("bf16", 200, 200, 16, 48 * 1024 + 6, 1 << 20, True),         # bf16 takes the wide form from 32 KiB for short programs
     ("i32", 100, 100, 4, 768 * 1024, 1 << 20, True),              # the longest range
@@ -1352,10 +1353,10 @@ def test_session_with_a_workspace_of_the_callers():
                                            wm.chunk_bytes // 4, wm.tree_degree, morder, mfm)
     assert rc == morc and info["k_eff"] == mk_eff
     assert np.array_equal(bits(workloads.to_numpy(mdst)), bits(mwant))
-    # a thousand bf16 objects of 100 KiB (more values alive at a time than the one-launch form has room for): the
+    # two thousand bf16 objects of 100 KiB (more values alive at a time than the one-launch form has room for): the
     # program is cut into sub-programs whose partial results (4-byte accumulators in whole blocks) and records
     # come out of the workspace, which the library sized itself
-    wb = workloads.WORKLOADS[4].scaled(100 * 1024 + 6, 16 * 2100, n=1000, k=990, tree_degree=16, order_seed=35, data_seed=36,
+    wb = workloads.WORKLOADS[4].scaled(100 * 1024 + 6, 16 * 2100, n=2000, k=1990, tree_degree=16, order_seed=35, data_seed=36,
                                        fail={}, name="own_workspace_cut", n_dst=0)
     assert not takes_the_one_launch_path(wb, wide=True)
     bobjs = workloads.make_objects(wb, device=d)
