@@ -44,11 +44,10 @@ def both_entry_points(w, op, fm=None):
 
 def test_no_alloc_entry_point_equals_hop_reduce_on_two_calls_in_a_row():
     assert hop.hop_noalloc_scratch_bytes() == 8 << 20
-    # many small objects: the program is cut into sub-programs whose partial results and records live in
-    # the static scratch (1000 inputs of 4 KiB, degree 16)
+    # many small objects (1000 inputs of 4 KiB, degree 16): the program as chains in one launch
     both_entry_points(workloads.WORKLOADS[5], "sum")
-    # right after it a smaller call (fewer and shorter objects, ragged, a binary tree): it finds the first
-    # call's partials and programs in the scratch and must not be disturbed by them
+    # right after it a smaller call (fewer and shorter objects, ragged, a binary tree): whatever the first
+    # call left in the scratch must not disturb it
     w = workloads.WORKLOADS[5].scaled(1024 + 12, 512, n=300, k=260, tree_degree=2, name="small_after_large")
     both_entry_points(w, "sum")
     both_entry_points(w, "max")
@@ -64,6 +63,14 @@ def test_no_alloc_long_program_large_objects_and_a_failure():
     w = workloads.WORKLOADS[4].scaled((1 << 20) + 6, 32 << 10)
     info_s, _ = both_entry_points(w, "sum", fm=w.fail_mask())
     assert info_s["k_eff"] == 31
+    # hundreds of objects of 200 KiB: the one-launch form with 1 KiB columns, its table in the kernel arguments
+    w = workloads.WORKLOADS[5].scaled(200 * 1024 + 8, 1 << 20, n=300, k=290, tree_degree=16, name="wide_columns", n_dst=0)
+    info_s, info_p = both_entry_points(w, "sum")
+    assert info_s["n_launches"] == info_p["n_launches"] == 1
+    # thousands of objects of 3 KiB in a binary tree: no one-launch form; cut into sub-programs whose partial
+    # results and records live in the static scratch
+    w = workloads.WORKLOADS[5].scaled(3 * 1024 + 4, 4096, n=5000, k=5000, tree_degree=2, name="cut_in_scratch", n_dst=0)
+    both_entry_points(w, "sum")
     # int32, short program (rides in the kernel arguments: no scratch at all)
     w = workloads.WORKLOADS[3].scaled(300 << 10, 16 << 10, n_dst=0)
     both_entry_points(w, "sum")
